@@ -1,0 +1,126 @@
+"""Build and call the C oracle (select_oracle.c) through ctypes.  Test infrastructure only.
+
+Argument marshalling only: every array is checked to be C-contiguous int32 and
+handed to the C functions as a plain pointer.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "select_oracle.c")
+_LIB = os.path.join(_HERE, "libselect_oracle.so")
+
+_I32P = ctypes.POINTER(ctypes.c_int32)
+
+
+def build_oracle(src: str = _SRC, out: str = _LIB, force: bool = True) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP for the outer query loop only)."""
+    if not force and os.path.exists(out) and os.path.getmtime(out) >= os.path.getmtime(src):
+        return out
+    tmp = out + f".tmp{os.getpid()}"
+    cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
+           "-o", tmp, src]
+    subprocess.run(cmd, check=True)
+    os.replace(tmp, out)
+    return out
+
+
+def _ptr(a: np.ndarray):
+    assert a.dtype == np.int32 and a.flags["C_CONTIGUOUS"], "int32 C-contiguous array expected"
+    return a.ctypes.data_as(_I32P)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+class Oracle:
+    """Thin wrapper around one compiled oracle library."""
+
+    def __init__(self, path: str):
+        self.path = path
+        lib = ctypes.CDLL(path)
+        sel_args = [ctypes.c_int64, ctypes.c_int32, _I32P, _I32P, _I32P, _I32P, _I32P,
+                    ctypes.c_int64, _I32P, _I32P, _I32P, _I32P, _I32P]
+        for name in ("oracle_select", "oracle_select_literal"):
+            fn = getattr(lib, name)
+            fn.argtypes = sel_args
+            fn.restype = ctypes.c_int
+        lib.oracle_count_feasible.argtypes = [ctypes.c_int64, ctypes.c_int32, _I32P, _I32P, _I32P,
+                                              _I32P, ctypes.c_int64, _I32P, _I32P, _I32P, _I32P,
+                                              _I32P]
+        lib.oracle_count_feasible.restype = ctypes.c_int
+        lib.oracle_update_load.argtypes = [ctypes.c_int64, _I32P, ctypes.c_int64, _I32P, _I32P]
+        lib.oracle_update_load.restype = None
+        lib.oracle_num_threads.argtypes = []
+        lib.oracle_num_threads.restype = ctypes.c_int
+        self._lib = lib
+
+    def num_threads(self) -> int:
+        return int(self._lib.oracle_num_threads())
+
+    def _select(self, fn, task_id, acc_bp, lat_us, cost, queue_us, q_task, q_slo, q_min_acc, q_bidx):
+        task_id, acc_bp, queue_us = _i32(task_id), _i32(acc_bp), _i32(queue_us)
+        lat_us, cost = _i32(lat_us), _i32(cost)
+        V = task_id.shape[0]
+        assert lat_us.ndim == 2 and lat_us.shape[0] == V and cost.shape == lat_us.shape
+        B = lat_us.shape[1]
+        assert acc_bp.shape == (V,) and queue_us.shape == (V,)
+        q_task, q_slo, q_min_acc, q_bidx = _i32(q_task), _i32(q_slo), _i32(q_min_acc), _i32(q_bidx)
+        N = q_task.shape[0]
+        assert q_slo.shape == (N,) and q_min_acc.shape == (N,) and q_bidx.shape == (N,)
+        out = np.empty(N, dtype=np.int32)
+        rc = fn(V, B, _ptr(task_id), _ptr(acc_bp), _ptr(lat_us), _ptr(cost), _ptr(queue_us),
+                N, _ptr(q_task), _ptr(q_slo), _ptr(q_min_acc), _ptr(q_bidx), _ptr(out))
+        if rc != 0:
+            raise ValueError("oracle rejected its arguments")
+        return out
+
+    def select(self, task_id, acc_bp, lat_us, cost, queue_us, q_task, q_slo, q_min_acc, q_bidx):
+        """Grouped brute force (multi-threaded over queries)."""
+        return self._select(self._lib.oracle_select, task_id, acc_bp, lat_us, cost, queue_us,
+                            q_task, q_slo, q_min_acc, q_bidx)
+
+    def select_literal(self, task_id, acc_bp, lat_us, cost, queue_us, q_task, q_slo, q_min_acc,
+                       q_bidx):
+        """Literal O(N*V) scan in the caller's row order."""
+        return self._select(self._lib.oracle_select_literal, task_id, acc_bp, lat_us, cost,
+                            queue_us, q_task, q_slo, q_min_acc, q_bidx)
+
+    def count_feasible(self, task_id, acc_bp, lat_us, queue_us, q_task, q_slo, q_min_acc, q_bidx):
+        task_id, acc_bp, queue_us, lat_us = _i32(task_id), _i32(acc_bp), _i32(queue_us), _i32(lat_us)
+        V, B = lat_us.shape
+        q_task, q_slo, q_min_acc, q_bidx = _i32(q_task), _i32(q_slo), _i32(q_min_acc), _i32(q_bidx)
+        N = q_task.shape[0]
+        out = np.empty(N, dtype=np.int32)
+        rc = self._lib.oracle_count_feasible(V, B, _ptr(task_id), _ptr(acc_bp), _ptr(lat_us),
+                                             _ptr(queue_us), N, _ptr(q_task), _ptr(q_slo),
+                                             _ptr(q_min_acc), _ptr(q_bidx), _ptr(out))
+        if rc != 0:
+            raise ValueError("oracle rejected its arguments")
+        return out
+
+    def update_load(self, queue_us: np.ndarray, variant_idx, new_queue_us) -> None:
+        """In place: queue_us[variant_idx[i]] = new_queue_us[i], array order."""
+        assert queue_us.dtype == np.int32 and queue_us.flags["C_CONTIGUOUS"]
+        variant_idx, new_queue_us = _i32(variant_idx), _i32(new_queue_us)
+        assert variant_idx.shape == new_queue_us.shape
+        self._lib.oracle_update_load(queue_us.shape[0], _ptr(queue_us), variant_idx.shape[0],
+                                     _ptr(variant_idx), _ptr(new_queue_us))
+
+
+_cached: Optional[Oracle] = None
+
+
+def load_oracle() -> Oracle:
+    """The oracle built from the committed source (compiled on first use)."""
+    global _cached
+    if _cached is None:
+        _cached = Oracle(build_oracle(force=False))
+    return _cached

@@ -1,0 +1,223 @@
+/*
+ * CPU oracle for per-query model-variant selection (INFaaS, arxiv 1905.13348).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the
+ * selection computes.  It exists so that tests, the smoke check and the
+ * benchmark's CPU-baseline leg have something to compare the GPU library with.
+ * The product library never links, loads or calls it, and it shares no code,
+ * header, table or helper with the GPU path.
+ *
+ * What is computed (Section 4.1, "Case I: on arrival of a query"; cheapest-choice
+ * objective as in the worked example of Section 2.2, Tables 2 and 3):
+ *
+ *   A query names a task (application), a latency objective slo_us, a minimum
+ *   accuracy min_acc_bp and a batch-size index b.  Among the registered variants
+ *   of that task, a variant v is FEASIBLE when
+ *       acc_bp[v] >= min_acc_bp                          (accuracy requirement)
+ *       lat_us[v][b] + queue_us[v] <= slo_us             (latency requirement;
+ *                                   "<=" as in the autoscaler's SLO constraint
+ *                                   T_inf <= S of Section 4.2; queue_us is the
+ *                                   dynamic state that Section 4 says must be
+ *                                   taken into account besides the static
+ *                                   profile)
+ *   and the answer is the feasible variant with the lexicographically smallest
+ *       (cost[v][b], lat_us[v][b], v)
+ *   i.e. the cheapest one, ties broken by profiled latency and then by the
+ *   caller's row index.  If no variant is feasible the answer is -1 (the
+ *   "no registered variant can meet the requirements" outcome of Section 4.1).
+ *
+ *   The brute-force search over all variants is the yardstick the paper itself
+ *   uses (Section 6.4), so the oracle IS that search: no sorting, no index, no
+ *   packing of keys.
+ *
+ * Readings taken where the paper is silent:
+ *   - the sum lat+queue is formed in 64 bits, so it cannot wrap;
+ *   - a task id or batch index outside the table, or a task with no variants,
+ *     has an empty feasible set, hence -1;
+ *   - load updates are applied in array order; an update whose row is outside
+ *     0..V-1 or whose value is negative is skipped.
+ *
+ * Pins (tests/, "not gpu"): the printed example of Tables 2/3, an independent
+ * numpy enumerator on tiny tables, invariants (chosen variant feasible, nothing
+ * feasible is smaller, -1 iff nothing feasible), special cases that reduce to a
+ * lexicographic sort, monotonicity and shift invariance, and seeded mutants of
+ * this file that each pin set must reject.  The only statement that stays
+ * "parity unpinned" is the count of valid options printed in Table 7, because
+ * the profiles behind it are not published.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* 1 when variant row v is feasible for the query (slo, min_acc, b). */
+static int feasible(const int32_t *acc_bp, const int32_t *lat_us, const int32_t *queue_us,
+                    int32_t B, int64_t v, int32_t slo_us, int32_t min_acc_bp, int32_t b)
+{
+    if (acc_bp[v] < min_acc_bp)
+        return 0;
+    int64_t total = (int64_t)lat_us[v * B + b] + (int64_t)queue_us[v];
+    if (total > (int64_t)slo_us)
+        return 0;
+    return 1;
+}
+
+/* 1 when (cost, lat, row) of v is lexicographically smaller than that of w. */
+static int cheaper(const int32_t *lat_us, const int32_t *cost, int32_t B, int32_t b,
+                   int64_t v, int64_t w)
+{
+    int32_t cv = cost[v * B + b], cw = cost[w * B + b];
+    if (cv != cw)
+        return cv < cw;
+    int32_t lv = lat_us[v * B + b], lw = lat_us[w * B + b];
+    if (lv != lw)
+        return lv < lw;
+    return v < w;
+}
+
+/*
+ * Literal form: every query looks at every row of the table, in the caller's
+ * order.  O(N*V); meant for small tables and as the cross-check of the grouped
+ * form below.  Returns 0, or -1 on bad arguments.
+ */
+int oracle_select_literal(int64_t V, int32_t B,
+                          const int32_t *task_id, const int32_t *acc_bp,
+                          const int32_t *lat_us, const int32_t *cost, const int32_t *queue_us,
+                          int64_t N,
+                          const int32_t *q_task, const int32_t *q_slo_us,
+                          const int32_t *q_min_acc_bp, const int32_t *q_batch_idx,
+                          int32_t *out_variant)
+{
+    if (V < 0 || B <= 0 || N < 0)
+        return -1;
+    for (int64_t q = 0; q < N; ++q) {
+        int64_t best = -1;
+        int32_t b = q_batch_idx[q];
+        if (b >= 0 && b < B) {
+            for (int64_t v = 0; v < V; ++v) {
+                if (task_id[v] != q_task[q])
+                    continue;
+                if (!feasible(acc_bp, lat_us, queue_us, B, v, q_slo_us[q], q_min_acc_bp[q], b))
+                    continue;
+                if (best < 0 || cheaper(lat_us, cost, B, b, v, best))
+                    best = v;
+            }
+        }
+        out_variant[q] = (int32_t)best;
+    }
+    return 0;
+}
+
+/*
+ * Grouped form: the rows of each task are listed once (in the caller's order),
+ * then every query runs the same brute-force search over its task's list only.
+ * Same result as the literal form; O(N * variants-per-task).  Queries are
+ * independent, so the outer loop may run on several host threads.
+ */
+int oracle_select(int64_t V, int32_t B,
+                  const int32_t *task_id, const int32_t *acc_bp,
+                  const int32_t *lat_us, const int32_t *cost, const int32_t *queue_us,
+                  int64_t N,
+                  const int32_t *q_task, const int32_t *q_slo_us,
+                  const int32_t *q_min_acc_bp, const int32_t *q_batch_idx,
+                  int32_t *out_variant)
+{
+    if (V < 0 || B <= 0 || N < 0)
+        return -1;
+    int64_t T = 0;
+    for (int64_t v = 0; v < V; ++v) {
+        if (task_id[v] < 0)
+            return -1;
+        if ((int64_t)task_id[v] + 1 > T)
+            T = (int64_t)task_id[v] + 1;
+    }
+    int64_t *first = (int64_t *)calloc((size_t)T + 1, sizeof(int64_t));
+    int64_t *rows = (int64_t *)malloc(sizeof(int64_t) * (size_t)(V > 0 ? V : 1));
+    int64_t *fill = (int64_t *)calloc((size_t)T + 1, sizeof(int64_t));
+    if (!first || !rows || !fill) {
+        free(first); free(rows); free(fill);
+        return -1;
+    }
+    for (int64_t v = 0; v < V; ++v)
+        first[task_id[v] + 1] += 1;
+    for (int64_t t = 0; t < T; ++t)
+        first[t + 1] += first[t];
+    for (int64_t v = 0; v < V; ++v) {
+        int64_t t = task_id[v];
+        rows[first[t] + fill[t]] = v;
+        fill[t] += 1;
+    }
+
+#pragma omp parallel for schedule(dynamic, 4096)
+    for (int64_t q = 0; q < N; ++q) {
+        int64_t best = -1;
+        int32_t b = q_batch_idx[q];
+        int64_t t = q_task[q];
+        if (b >= 0 && b < B && t >= 0 && t < T) {
+            for (int64_t i = first[t]; i < first[t + 1]; ++i) {
+                int64_t v = rows[i];
+                if (!feasible(acc_bp, lat_us, queue_us, B, v, q_slo_us[q], q_min_acc_bp[q], b))
+                    continue;
+                if (best < 0 || cheaper(lat_us, cost, B, b, v, best))
+                    best = v;
+            }
+        }
+        out_variant[q] = (int32_t)best;
+    }
+    free(first); free(rows); free(fill);
+    return 0;
+}
+
+/*
+ * Size of the feasible set of each query (the "valid options" column of the
+ * decision-overhead table in Section 6.4).  Diagnostic; literal scan.
+ */
+int oracle_count_feasible(int64_t V, int32_t B,
+                          const int32_t *task_id, const int32_t *acc_bp,
+                          const int32_t *lat_us, const int32_t *queue_us,
+                          int64_t N,
+                          const int32_t *q_task, const int32_t *q_slo_us,
+                          const int32_t *q_min_acc_bp, const int32_t *q_batch_idx,
+                          int32_t *out_count)
+{
+    if (V < 0 || B <= 0 || N < 0)
+        return -1;
+    for (int64_t q = 0; q < N; ++q) {
+        int32_t n = 0;
+        int32_t b = q_batch_idx[q];
+        if (b >= 0 && b < B)
+            for (int64_t v = 0; v < V; ++v)
+                if (task_id[v] == q_task[q] &&
+                    feasible(acc_bp, lat_us, queue_us, B, v, q_slo_us[q], q_min_acc_bp[q], b))
+                    n += 1;
+        out_count[q] = n;
+    }
+    return 0;
+}
+
+/*
+ * Load update (the monitoring daemons' periodic push of per-variant load,
+ * Section 5): queue_us[row[i]] = value[i], in array order.
+ */
+void oracle_update_load(int64_t V, int32_t *queue_us, int64_t n,
+                        const int32_t *variant_idx, const int32_t *new_queue_us)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t v = variant_idx[i];
+        if (v < 0 || v >= V || new_queue_us[i] < 0)
+            continue;
+        queue_us[v] = new_queue_us[i];
+    }
+}
+
+/* Host threads the grouped form uses. */
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,293 @@
+"""Pins of the CPU oracle: checks against what the paper prints and what the mathematics fixes.
+
+Every function takes an ``oracle.Oracle`` and raises AssertionError when that oracle is
+wrong.  They are run on the committed oracle (must pass) and on deliberately broken copies
+of its source (each copy must be rejected by at least one pin).
+"""
+import os
+
+import numpy as np
+
+import workloads
+from bruteforce_np import count_np, select_np
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+I32MAX = 2**31 - 1
+
+
+def _both(o, *args):
+    """Run the grouped and the literal form; they must agree; return the result."""
+    a = o.select(*args)
+    b = o.select_literal(*args)
+    assert np.array_equal(a, b), "grouped and literal oracle disagree"
+    return a
+
+
+def _read_worked_example():
+    names, lat_ms, cost, cases = [], [], [], []
+    with open(os.path.join(GOLDEN, "tables_2_3_worked_example.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            w = line.split()
+            if w[0] == "variant":
+                names.append(w[1]); lat_ms.append(int(w[2])); cost.append(int(w[3]))
+            elif w[0] == "case":
+                cases.append((int(w[1]), w[2]))
+    return names, lat_ms, cost, cases
+
+
+def pin_worked_example(o):
+    """Tables 2/3 of Section 2.2: SLO 300 ms -> variant A, SLO 50 ms -> variant B."""
+    names, lat_ms, cost, cases = _read_worked_example()
+    V = len(names)
+    task = np.zeros(V, np.int32)
+    acc = np.full(V, 7600, np.int32)             # same model, same accuracy
+    lat = (np.array(lat_ms, np.int32) * 1000).reshape(V, 1)
+    cst = np.array(cost, np.int32).reshape(V, 1)
+    queue = np.zeros(V, np.int32)
+    for slo_ms, want in cases:
+        got = _both(o, task, acc, lat, cst, queue, [0], [slo_ms * 1000], [7000], [0])
+        assert got[0] == names.index(want), (slo_ms, want, got)
+    # the printed rows stay true whatever order the three variants are registered in
+    for perm in ([2, 1, 0], [1, 2, 0], [2, 0, 1]):
+        p = np.array(perm)
+        for slo_ms, want in cases:
+            got = _both(o, task, acc, lat[p], cst[p], queue, [0], [slo_ms * 1000], [7000], [0])
+            assert p[got[0]] == names.index(want)
+
+
+def pin_worked_example_consequences(o):
+    """Consequences of the same rule on the same three variants (not printed values)."""
+    names, lat_ms, cost, _ = _read_worked_example()
+    V = len(names)
+    task = np.zeros(V, np.int32)
+    acc = np.full(V, 7600, np.int32)
+    lat = (np.array(lat_ms, np.int32) * 1000).reshape(V, 1)
+    cst = np.array(cost, np.int32).reshape(V, 1)
+    zero = np.zeros(V, np.int32)
+    assert _both(o, task, acc, lat, cst, zero, [0], [17000], [0], [0])[0] == 2     # only C fits
+    assert _both(o, task, acc, lat, cst, zero, [0], [10000], [0], [0])[0] == -1    # nothing fits
+    busy = np.array([150000, 0, 0], np.int32)   # A is queued behind 150 ms of work
+    assert _both(o, task, acc, lat, cst, busy, [0], [300000], [0], [0])[0] == 1    # 350 ms > SLO
+    busy = np.array([100000, 0, 0], np.int32)   # exactly 300 ms still fits
+    assert _both(o, task, acc, lat, cst, busy, [0], [300000], [0], [0])[0] == 0
+    assert _both(o, task, acc, lat, cst, zero, [0], [300000], [7601], [0])[0] == -1  # accuracy
+
+
+def _tiny_random(rng, V, T, B, N, span):
+    task = rng.integers(0, T, V).astype(np.int32)
+    acc = rng.integers(0, span, V).astype(np.int32)
+    lat = rng.integers(0, span, (V, B)).astype(np.int32)
+    cost = rng.integers(0, span, (V, B)).astype(np.int32)
+    queue = rng.integers(0, span, V).astype(np.int32)
+    qt = rng.integers(-1, T + 1, N).astype(np.int32)
+    qs = rng.integers(-1, 2 * span, N).astype(np.int32)
+    qa = rng.integers(-1, span + 1, N).astype(np.int32)
+    qb = rng.integers(-1, B + 1, N).astype(np.int32)
+    return (task, acc, lat, cost, queue), (qt, qs, qa, qb)
+
+
+def pin_numpy_enumerator(o):
+    """Tiny tables with small value ranges (many ties) against the numpy enumerator."""
+    rng = np.random.default_rng(7)
+    for trial in range(40):
+        V = int(rng.integers(1, 65)); T = int(rng.integers(1, 6)); B = int(rng.integers(1, 5))
+        span = int(rng.choice([2, 3, 5, 9, 50]))
+        tab, qry = _tiny_random(rng, V, T, B, 300, span)
+        want = select_np(*tab, *qry)
+        got = _both(o, *tab, *qry)
+        assert np.array_equal(got, want), f"trial {trial}"
+        cnt = o.count_feasible(tab[0], tab[1], tab[2], tab[4], *qry)
+        assert np.array_equal(cnt, count_np(tab[0], tab[1], tab[2], tab[4], *qry))
+        assert np.array_equal(cnt == 0, got == -1)
+
+
+def check_invariants(table, queries, out):
+    """Properties every correct answer has; usable at any size (vectorised)."""
+    task_id = table[0].astype(np.int64); acc = table[1].astype(np.int64)
+    lat = table[2].astype(np.int64); cost = table[3].astype(np.int64)
+    queue = table[4].astype(np.int64)
+    qt, qs, qa, qb = (np.asarray(x).astype(np.int64) for x in queries)
+    out = np.asarray(out).astype(np.int64)
+    V, B = lat.shape
+    hit = out >= 0
+    assert np.all(out[hit] < V)
+    v = out[hit]; b = qb[hit]
+    assert np.all((b >= 0) & (b < B))
+    assert np.all(task_id[v] == qt[hit]), "answer from another task"
+    assert np.all(acc[v] >= qa[hit]), "answer misses the accuracy minimum"
+    assert np.all(lat[v, b] + queue[v] <= qs[hit]), "answer misses the latency objective"
+
+
+def pin_invariants_tiny_config(o):
+    """Config 0: feasibility of every answer; optimality and -1 <=> empty set via counting."""
+    tb = workloads.make_table(0)
+    q = workloads.make_queries(0)
+    table = (tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us)
+    queries = (q.task, q.slo_us, q.min_acc_bp, q.batch_idx)
+    out = _both(o, *table, *queries)
+    check_invariants(table, queries, out)
+    # no feasible variant of the task has a smaller key: full check, row by row
+    lat = tb.lat_us.astype(np.int64); cost = tb.cost.astype(np.int64)
+    tot = lat + tb.queue_us.astype(np.int64)[:, None]
+    n_empty = 0
+    for i in range(q.N):
+        b = q.batch_idx[i]
+        ok = (tb.task_id == q.task[i]) & (tb.acc_bp >= q.min_acc_bp[i]) & (tot[:, b] <= q.slo_us[i])
+        if out[i] < 0:
+            assert not ok.any()
+            n_empty += 1
+            continue
+        assert ok[out[i]]
+        w = out[i]
+        rows = np.flatnonzero(ok)
+        smaller = (cost[rows, b] < cost[w, b]) | \
+                  ((cost[rows, b] == cost[w, b]) & (lat[rows, b] < lat[w, b])) | \
+                  ((cost[rows, b] == cost[w, b]) & (lat[rows, b] == lat[w, b]) & (rows < w))
+        assert not smaller.any()
+    assert 0 < n_empty < q.N, "config 0 should have both outcomes"
+
+
+def pin_all_feasible_is_lexsort(o):
+    """With SLO = INT32_MAX and no accuracy floor the answer is the first row of a
+    lexicographic sort of each (task, batch) slice: a library routine."""
+    tb = workloads.make_table(0)
+    T, B = tb.num_tasks, tb.B
+    qt, qb = np.meshgrid(np.arange(T), np.arange(B), indexing="ij")
+    qt = qt.ravel().astype(np.int32); qb = qb.ravel().astype(np.int32)
+    n = qt.size
+    queue = np.zeros(tb.V, np.int32)
+    out = _both(o, tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, queue, qt,
+                np.full(n, I32MAX, np.int32), np.full(n, -I32MAX, np.int32), qb)
+    for i in range(n):
+        rows = np.flatnonzero(tb.task_id == qt[i])
+        order = np.lexsort((rows, tb.lat_us[rows, qb[i]], tb.cost[rows, qb[i]]))
+        assert out[i] == rows[order[0]]
+
+
+def pin_boundaries_and_ties(o):
+    """Equality is feasible on both tests; tie order is cost, then profiled latency, then row."""
+    task = np.zeros(4, np.int32)
+    acc = np.array([7000, 7000, 7000, 7000], np.int32)
+    lat = np.array([[100], [100], [100], [100]], np.int32)
+    cost = np.array([[5], [5], [5], [5]], np.int32)
+    queue = np.array([50, 50, 50, 50], np.int32)
+    sel = lambda *a: _both(o, *a)
+    # accuracy exactly at the minimum, latency exactly at the objective
+    assert sel(task, acc, lat, cost, queue, [0], [150], [7000], [0])[0] == 0
+    assert sel(task, acc, lat, cost, queue, [0], [149], [7000], [0])[0] == -1
+    assert sel(task, acc, lat, cost, queue, [0], [150], [7001], [0])[0] == -1
+    # all keys equal -> lowest row; make row 2 cheaper -> row 2
+    c2 = cost.copy(); c2[2, 0] = 4
+    assert sel(task, acc, lat, c2, queue, [0], [1000], [0], [0])[0] == 2
+    # equal cost, row 3 has the lower PROFILED latency but the larger total (big queue):
+    # the tie goes by profiled latency, not by latency plus queue
+    l3 = lat.copy(); l3[3, 0] = 90
+    q3 = queue.copy(); q3[3] = 500
+    assert sel(task, acc, l3, cost, q3, [0], [1000], [0], [0])[0] == 3
+    # cost dominates latency: a cheaper, slower variant wins over a dearer, faster one
+    l4 = np.array([[900], [10], [10], [10]], np.int32)
+    c4 = np.array([[1], [2], [2], [2]], np.int32)
+    assert sel(task, acc, l4, c4, queue, [0], [1000], [0], [0])[0] == 0
+    assert sel(task, acc, l4, c4, queue, [0], [100], [0], [0])[0] == 1
+    # rows of a task need not be adjacent and the row tie-break is the caller's row number
+    task2 = np.array([1, 0, 1, 0], np.int32)
+    assert sel(task2, acc, lat, cost, queue, [0, 1], [1000, 1000], [0, 0], [0, 0]).tolist() == [1, 0]
+    # the answer is the highest-accuracy-agnostic cheapest: accuracy above the floor does not matter
+    acc5 = np.array([9000, 7000, 8000, 7500], np.int32)
+    c5 = np.array([[9], [1], [3], [2]], np.int32)
+    assert sel(task, acc5, lat, c5, queue, [0] * 4, [1000] * 4, [6000, 7001, 7501, 8001],
+               [0] * 4).tolist() == [1, 3, 2, 0]
+
+
+def pin_batch_column(o):
+    """The batch index picks the column of BOTH profiles; latency and cost are not interchangeable."""
+    task = np.zeros(2, np.int32)
+    acc = np.full(2, 8000, np.int32)
+    lat = np.array([[10, 500], [400, 20]], np.int32)
+    cost = np.array([[7, 1], [2, 9]], np.int32)
+    queue = np.zeros(2, np.int32)
+    out = _both(o, task, acc, lat, cost, queue, [0, 0, 0, 0], [1000, 1000, 100, 100], [0] * 4,
+                [0, 1, 0, 1])
+    assert out.tolist() == [1, 0, 0, 1]
+    out = _both(o, task, acc, lat, cost, queue, [0, 0, 0], [1000] * 3, [0] * 3, [-1, 2, 1])
+    assert out.tolist() == [-1, -1, 0]
+    # unknown task, negative task, task with no variants
+    task3 = np.array([0, 2], np.int32)
+    out = _both(o, task3, acc, lat, cost, queue, [1, 3, -1, 2], [1000] * 4, [0] * 4, [0] * 4)
+    assert out.tolist() == [-1, -1, -1, 1]
+
+
+def pin_no_wraparound(o):
+    """lat + queue is an exact sum: two large int32 values must not wrap into feasibility."""
+    task = np.zeros(2, np.int32)
+    acc = np.full(2, 8000, np.int32)
+    lat = np.array([[I32MAX], [I32MAX]], np.int32)
+    cost = np.array([[1], [2]], np.int32)
+    queue = np.array([I32MAX, 0], np.int32)
+    out = _both(o, task, acc, lat, cost, queue, [0, 0, 0], [I32MAX, I32MAX - 1, -5], [0] * 3, [0] * 3)
+    assert out.tolist() == [1, -1, -1]
+    queue2 = np.array([1, 1], np.int32)
+    assert _both(o, task, acc, lat, cost, queue2, [0], [I32MAX], [0], [0])[0] == -1
+
+
+def pin_monotone_and_shift(o):
+    """Relaxing a requirement never worsens the winning key; adding d to every queue and to
+    the SLO changes nothing."""
+    tb = workloads.make_table(0)
+    q = workloads.make_queries(0, n=3000)
+    table = (tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us)
+    base = _both(o, *table, q.task, q.slo_us, q.min_acc_bp, q.batch_idx)
+    relaxed_slo = _both(o, *table, q.task, q.slo_us + 5000, q.min_acc_bp, q.batch_idx)
+    relaxed_acc = _both(o, *table, q.task, q.slo_us, q.min_acc_bp - 300, q.batch_idx)
+
+    def key(out):
+        k = np.full((len(out), 3), np.iinfo(np.int64).max, dtype=np.int64)
+        hit = out >= 0
+        k[hit, 0] = tb.cost[out[hit], q.batch_idx[hit]]
+        k[hit, 1] = tb.lat_us[out[hit], q.batch_idx[hit]]
+        k[hit, 2] = out[hit]
+        return k
+
+    def leq(a, b):  # lexicographic a <= b, row-wise
+        lt = np.zeros(len(a), bool); eq = np.ones(len(a), bool)
+        for j in range(3):
+            lt |= eq & (a[:, j] < b[:, j]); eq &= a[:, j] == b[:, j]
+        return lt | eq
+
+    assert leq(key(relaxed_slo), key(base)).all()
+    assert leq(key(relaxed_acc), key(base)).all()
+    assert (relaxed_slo != base).any() and (relaxed_acc != base).any()
+    d = 12345
+    shifted = _both(o, tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us + d, q.task,
+                    q.slo_us + d, q.min_acc_bp, q.batch_idx)
+    assert np.array_equal(shifted, base)
+
+
+def pin_update_load(o):
+    """Updates land on the named rows, in array order, skipping bad rows and negative values."""
+    queue = np.array([10, 20, 30, 40], np.int32)
+    o.update_load(queue, [2, 0, 2, 7, -1, 1], [300, 100, 301, 9, 9, -5])
+    assert queue.tolist() == [100, 20, 301, 40]
+    task = np.zeros(4, np.int32); acc = np.full(4, 8000, np.int32)
+    lat = np.full((4, 1), 50, np.int32); cost = np.array([[1], [2], [3], [4]], np.int32)
+    assert _both(o, task, acc, lat, cost, queue, [0], [100], [0], [0])[0] == 1
+    o.update_load(queue, [1], [51])
+    assert _both(o, task, acc, lat, cost, queue, [0], [100], [0], [0])[0] == 3
+    assert _both(o, task, acc, lat, cost, queue, [0], [89], [0], [0])[0] == -1
+
+
+ALL_PINS = [
+    pin_worked_example,
+    pin_worked_example_consequences,
+    pin_numpy_enumerator,
+    pin_invariants_tiny_config,
+    pin_all_feasible_is_lexsort,
+    pin_boundaries_and_ties,
+    pin_batch_column,
+    pin_no_wraparound,
+    pin_monotone_and_shift,
+    pin_update_load,
+]

@@ -1,0 +1,71 @@
+"""Planted mistakes in copies of the oracle's source: every one must be caught by a pin.
+
+This shows the pins are tight enough that a dropped term, a flipped comparison, a wrong
+column or a wrong tie order in the oracle would not go unnoticed.  CPU only.
+"""
+import os
+
+import pytest
+
+import oracle
+import pins
+
+SRC = os.path.join(os.path.dirname(oracle.__file__), "select_oracle.c")
+
+# (name, text to find, replacement).  Each 'find' must occur in the source.
+MUTANTS = [
+    ("accuracy_strict", "if (acc_bp[v] < min_acc_bp)", "if (acc_bp[v] <= min_acc_bp)"),
+    ("accuracy_flipped", "if (acc_bp[v] < min_acc_bp)", "if (acc_bp[v] > min_acc_bp)"),
+    ("latency_strict", "if (total > (int64_t)slo_us)", "if (total >= (int64_t)slo_us)"),
+    ("queue_dropped", "(int64_t)lat_us[v * B + b] + (int64_t)queue_us[v];",
+     "(int64_t)lat_us[v * B + b];"),
+    ("latency_dropped", "(int64_t)lat_us[v * B + b] + (int64_t)queue_us[v];",
+     "(int64_t)queue_us[v];"),
+    ("sum_wraps_int32", "(int64_t)lat_us[v * B + b] + (int64_t)queue_us[v];",
+     "(int64_t)(int32_t)((uint32_t)lat_us[v * B + b] + (uint32_t)queue_us[v]);"),
+    ("cost_order_flipped", "return cv < cw;", "return cv > cw;"),
+    ("latency_tie_flipped", "return lv < lw;", "return lv > lw;"),
+    ("row_tie_flipped", "return v < w;", "return v > w;"),
+    ("latency_tie_skipped", "int32_t lv = lat_us[v * B + b], lw = lat_us[w * B + b];",
+     "int32_t lv = lat_us[v * B + b] + 0 * cw, lw = lat_us[w * B + b]; return v < w;"),
+    ("latency_before_cost", "int32_t cv = cost[v * B + b], cw = cost[w * B + b];",
+     "int32_t cv = lat_us[v * B + b], cw = lat_us[w * B + b];"),
+    ("cost_ignored", "if (cv != cw)", "if (0)"),
+    ("batch_column_ignored_in_key", "int32_t cv = cost[v * B + b], cw = cost[w * B + b];",
+     "int32_t cv = cost[v * B], cw = cost[w * B];"),
+    ("batch_column_ignored_in_filter", "int64_t total = (int64_t)lat_us[v * B + b]",
+     "int64_t total = (int64_t)lat_us[v * B]"),
+    ("bad_batch_index_reads_column_0", "int32_t b = q_batch_idx[q];",
+     "int32_t b = q_batch_idx[q]; if (b < 0 || b >= B) b = 0;"),
+    ("task_filter_dropped", "if (task_id[v] != q_task[q])\n                    continue;", ""),
+    ("first_feasible_wins", "if (best < 0 || cheaper(lat_us, cost, B, b, v, best))",
+     "if (best < 0)"),
+    ("last_feasible_wins", "if (best < 0 || cheaper(lat_us, cost, B, b, v, best))", "if (1)"),
+    ("update_keeps_negative", "if (v < 0 || v >= V || new_queue_us[i] < 0)",
+     "if (v < 0 || v >= V)"),
+    ("update_reversed", "for (int64_t i = 0; i < n; ++i) {\n        int64_t v = variant_idx[i];",
+     "for (int64_t i = n - 1; i >= 0; --i) {\n        int64_t v = variant_idx[i];"),
+    ("update_adds", "queue_us[v] = new_queue_us[i];", "queue_us[v] += new_queue_us[i];"),
+]
+
+
+@pytest.fixture(scope="module")
+def source_text():
+    with open(SRC) as f:
+        return f.read()
+
+
+@pytest.mark.parametrize("name,find,repl", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_mutant_is_caught(tmp_path, source_text, name, find, repl):
+    assert find in source_text, f"mutant {name}: pattern not in the oracle source any more"
+    src = tmp_path / f"{name}.c"
+    src.write_text(source_text.replace(find, repl))
+    lib = oracle.build_oracle(src=str(src), out=str(tmp_path / f"lib{name}.so"), force=True)
+    mutant = oracle.Oracle(lib)
+    caught = []
+    for pin in pins.ALL_PINS:
+        try:
+            pin(mutant)
+        except AssertionError:
+            caught.append(pin.__name__)
+    assert caught, f"no pin notices the planted mistake '{name}'"

@@ -1,0 +1,210 @@
+"""Synthetic workloads shaped like the paper's variant population and query mix.
+
+The paper's own populations (its profiled variants, Section 6 / Appendix table of
+model architectures; the production trace of Section 6.1) are not available, so
+every table and query stream here is drawn from a seeded generator.  What is
+taken from the paper is only the *shape*: accuracies spread over tens of
+percent, single-query latencies spread over three to four orders of magnitude,
+hardware prices spread over roughly one order of magnitude (Section 2.1),
+per-batch-size latency profiles at power-of-two batch sizes (Section 5), Zipf
+task popularity (Section 6.1) and "thousands of variants" per task (Section 1).
+
+All fields are int32.  Generator: numpy ``Generator(PCG64(seed))``.  The draw
+order inside each function is part of the recipe -- changing it changes every
+stored expectation -- and is spelled out in the comments.
+
+Five workload configurations:
+
+  0 tiny       8 tasks x 32 variants,        4 batch sizes {1,4,16,64},   10,000 queries
+  1 medium     100 tasks x 200 variants,     8 batch sizes {1..128},      1M queries
+  2 thousands  50 tasks x 2,000 variants,    8 batch sizes,               16M queries, Zipf(1.1) tasks
+  3 skewed     1,000 tasks, lognormal sizes, 8 batch sizes,               64M queries, bimodal SLO
+  4 streaming  config 2's table,             256M queries in 64 chunks of 4M, 10% load redraw per chunk
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+CONFIG_NAMES = ("tiny", "medium", "thousands", "skewed", "streaming")
+
+_SEED0 = 190513348  # one documented seed per configuration: _SEED0 + config id
+
+
+def base_seed(cfg: int) -> int:
+    """Seed of configuration ``cfg``'s variant table (config 4 shares config 2's)."""
+    return _SEED0 + (2 if cfg == 4 else cfg)
+
+
+@dataclass
+class VariantTable:
+    num_tasks: int
+    batch_sizes: np.ndarray  # [B] int32
+    task_id: np.ndarray      # [V] int32, caller order (NOT grouped by task)
+    acc_bp: np.ndarray       # [V] int32, accuracy in basis points
+    lat_us: np.ndarray       # [V, B] int32, profiled latency per batch size
+    cost: np.ndarray         # [V, B] int32, per-query cost per batch size
+    queue_us: np.ndarray     # [V] int32, current queueing delay
+
+    @property
+    def V(self) -> int:
+        return int(self.task_id.shape[0])
+
+    @property
+    def B(self) -> int:
+        return int(self.batch_sizes.shape[0])
+
+
+@dataclass
+class QueryBatch:
+    task: np.ndarray        # [N] int32
+    slo_us: np.ndarray      # [N] int32
+    min_acc_bp: np.ndarray  # [N] int32
+    batch_idx: np.ndarray   # [N] int32, index into VariantTable.batch_sizes
+
+    @property
+    def N(self) -> int:
+        return int(self.task.shape[0])
+
+
+@dataclass
+class LoadUpdate:
+    variant_idx: np.ndarray  # [n] int32, distinct caller-order variant rows
+    queue_us: np.ndarray     # [n] int32, new queueing delay
+
+
+def config_spec(cfg: int) -> dict:
+    """Static description of one configuration (no random draws)."""
+    if cfg == 0:
+        return dict(name="tiny", num_tasks=8, per_task=32, batch_sizes=[1, 4, 16, 64],
+                    num_queries=10_000, chunks=1, task_popularity="uniform", slo="unimodal")
+    if cfg == 1:
+        return dict(name="medium", num_tasks=100, per_task=200,
+                    batch_sizes=[1, 2, 4, 8, 16, 32, 64, 128],
+                    num_queries=1_000_000, chunks=1, task_popularity="uniform", slo="unimodal")
+    if cfg == 2:
+        return dict(name="thousands", num_tasks=50, per_task=2000,
+                    batch_sizes=[1, 2, 4, 8, 16, 32, 64, 128],
+                    num_queries=16_000_000, chunks=1, task_popularity="zipf1.1", slo="unimodal")
+    if cfg == 3:
+        return dict(name="skewed", num_tasks=1000, per_task=None,
+                    batch_sizes=[1, 2, 4, 8, 16, 32, 64, 128],
+                    num_queries=64_000_000, chunks=1, task_popularity="uniform", slo="bimodal")
+    if cfg == 4:
+        return dict(name="streaming", num_tasks=50, per_task=2000,
+                    batch_sizes=[1, 2, 4, 8, 16, 32, 64, 128],
+                    num_queries=256_000_000, chunks=64, task_popularity="zipf1.1", slo="unimodal",
+                    update_fraction=0.10)
+    raise ValueError(f"unknown configuration {cfg}")
+
+
+def _segment_sizes(cfg: int, rng: np.random.Generator) -> np.ndarray:
+    spec = config_spec(cfg)
+    T = spec["num_tasks"]
+    if spec["per_task"] is not None:
+        return np.full(T, spec["per_task"], dtype=np.int64)
+    # config 3: lognormal with ARITHMETIC mean 100 and sigma 1.5, clamped to 1..20000
+    sigma = 1.5
+    mu = np.log(100.0) - 0.5 * sigma * sigma
+    sizes = np.rint(rng.lognormal(mu, sigma, size=T)).astype(np.int64)
+    return np.clip(sizes, 1, 20000)
+
+
+def make_variant_fields(rng: np.random.Generator, V: int, batch_sizes: np.ndarray):
+    """Draw the per-variant fields.  Draw order: acc, hw class, base latency, alpha, queue."""
+    acc_bp = rng.integers(5000, 9501, size=V, dtype=np.int64)
+    hw = rng.integers(0, 3, size=V, dtype=np.int64)
+    price = np.array([1, 4, 9], dtype=np.int64)[hw]
+    base_us = np.clip(rng.lognormal(np.log(2000.0), 1.0, size=V), 100.0, 500000.0)
+    alpha = rng.uniform(0.3, 1.0, size=V)
+    queue_us = rng.integers(0, 50001, size=V, dtype=np.int64)
+    b = batch_sizes.astype(np.float64)[None, :]
+    lat = np.rint(base_us[:, None] * b ** alpha[:, None]).astype(np.int64)
+    lat = np.maximum(lat, 1)
+    bi = batch_sizes.astype(np.int64)[None, :]
+    cost = (lat * price[:, None] + bi - 1) // bi          # ceil(lat * price / b)
+    return (acc_bp.astype(np.int32), lat.astype(np.int32), cost.astype(np.int32),
+            queue_us.astype(np.int32))
+
+
+def make_table(cfg: int, seed: Optional[int] = None) -> VariantTable:
+    """Variant table of configuration ``cfg``.
+
+    Draw order: segment sizes (config 3 only), variant fields (see
+    ``make_variant_fields``), then one permutation that shuffles the rows so that
+    the caller's order is not grouped by task.
+    """
+    spec = config_spec(cfg)
+    rng = np.random.default_rng(np.random.PCG64(base_seed(cfg) if seed is None else seed))
+    sizes = _segment_sizes(cfg, rng)
+    T = spec["num_tasks"]
+    V = int(sizes.sum())
+    batch_sizes = np.asarray(spec["batch_sizes"], dtype=np.int32)
+    task_sorted = np.repeat(np.arange(T, dtype=np.int32), sizes)
+    acc, lat, cost, queue = make_variant_fields(rng, V, batch_sizes)
+    perm = rng.permutation(V)
+    return VariantTable(num_tasks=T, batch_sizes=batch_sizes, task_id=task_sorted[perm].copy(),
+                        acc_bp=acc, lat_us=lat, cost=cost, queue_us=queue)
+
+
+def _task_probabilities(spec: dict) -> Optional[np.ndarray]:
+    if spec["task_popularity"] == "uniform":
+        return None
+    T = spec["num_tasks"]
+    w = (np.arange(T, dtype=np.float64) + 1.0) ** -1.1   # bounded Zipf over task ids 0..T-1
+    return w / w.sum()
+
+
+def make_queries(cfg: int, n: Optional[int] = None, chunk: int = 0,
+                 seed: Optional[int] = None) -> QueryBatch:
+    """Query stream of configuration ``cfg`` (``n`` queries; default: the configured size,
+    or one chunk of it for the streaming configuration).
+
+    Seed: base_seed(cfg) + 1000 + chunk for config 4's chunks, base_seed(cfg) + 1000 otherwise
+    (config 4 uses its own stream: _SEED0 + 4 + 1000 + chunk).
+    Draw order: task, SLO (for the bimodal mix: component selector, then both components),
+    minimum accuracy, batch index.
+    """
+    spec = config_spec(cfg)
+    if n is None:
+        n = spec["num_queries"] // spec["chunks"]
+    if seed is None:
+        seed = _SEED0 + cfg + 1000 + chunk
+    rng = np.random.default_rng(np.random.PCG64(seed))
+    T = spec["num_tasks"]
+    B = len(spec["batch_sizes"])
+    p = _task_probabilities(spec)
+    if p is None:
+        task = rng.integers(0, T, size=n, dtype=np.int64)
+    else:
+        task = rng.choice(T, size=n, p=p)
+    if spec["slo"] == "unimodal":
+        slo = rng.lognormal(np.log(20000.0), 1.0, size=n)
+    else:
+        pick = rng.random(size=n) < 0.5
+        lo = rng.lognormal(np.log(5000.0), 1.0, size=n)
+        hi = rng.lognormal(np.log(200000.0), 1.0, size=n)
+        slo = np.where(pick, lo, hi)
+        del pick, lo, hi
+    slo = np.clip(np.rint(slo), 1000, 2_000_000)
+    min_acc = rng.integers(5000, 9501, size=n, dtype=np.int64)
+    bidx = rng.integers(0, B, size=n, dtype=np.int64)
+    return QueryBatch(task=task.astype(np.int32), slo_us=slo.astype(np.int32),
+                      min_acc_bp=min_acc.astype(np.int32), batch_idx=bidx.astype(np.int32))
+
+
+def make_load_update(cfg: int, V: int, chunk: int, fraction: float = 0.10,
+                     seed: Optional[int] = None) -> LoadUpdate:
+    """Load redraw applied before chunk ``chunk`` (>= 1) of the streaming configuration:
+    ``fraction`` of the variants, chosen without replacement, get a new queueing delay
+    uniform in 0..200000.  Seed: _SEED0 + cfg + 5000 + chunk.  Draw order: rows, values.
+    """
+    if seed is None:
+        seed = _SEED0 + cfg + 5000 + chunk
+    rng = np.random.default_rng(np.random.PCG64(seed))
+    n = int(round(V * fraction))
+    rows = rng.choice(V, size=n, replace=False)
+    vals = rng.integers(0, 200001, size=n, dtype=np.int64)
+    return LoadUpdate(variant_idx=rows.astype(np.int32), queue_us=vals.astype(np.int32))
