@@ -1,0 +1,186 @@
+/*
+ * infaas_sel -- batched per-query model-variant selection on one AMD Instinct MI355X.
+ *
+ * The operation is the variant choice that INFaaS (arxiv 1905.13348) makes on the
+ * critical path of every query (Section 4.1, "Case I: on arrival of a query"): given
+ * the query's requirements, pick the registered variant of the query's application
+ * that meets them at the lowest cost (the cheapest-choice objective of Section 2.2,
+ * Tables 2 and 3), taking the variants' current load into account (Section 4), or
+ * report that no variant can meet them.  Here millions of such decisions are made per
+ * call, on the GPU, with integer arithmetic only.
+ *
+ * Per query q = (task, slo_us, min_acc_bp, batch_idx) the result is the row v of the
+ * variant table that minimises the lexicographic key (cost[v][b], lat_us[v][b], v)
+ * among the rows with
+ *       task_id[v] == task,
+ *       acc_bp[v]  >= min_acc_bp,
+ *       lat_us[v][b] + queue_us[v] <= slo_us        (exact sum, never wraps),
+ * where b = batch_idx, or -1 when no row qualifies (also for a task or batch index
+ * outside the table and for a negative slo_us).
+ *
+ * Plain C ABI: opaque handle, plain pointers and sizes.  Each pointer below is marked
+ * HOST or DEVICE.  Nothing here allocates or frees memory the caller passed in.
+ *
+ * Threading / ordering: a handle is not thread-safe.  infaas_sel_update_load and
+ * infaas_sel_select only ENQUEUE work on the HIP stream they are given and return; the
+ * outputs are valid once the caller has synchronised that stream.  Work enqueued on
+ * one handle must be ordered by the caller (same stream, or events between streams),
+ * because all calls share the handle's table and scratch memory.
+ */
+#ifndef INFAAS_SEL_H
+#define INFAAS_SEL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct infaas_sel infaas_sel_t; /* opaque; owned by the library */
+
+/* Status codes: 0 on success, negative on failure.  No call aborts or throws. */
+enum {
+    INFAAS_SEL_OK = 0,
+    INFAAS_SEL_ERR_INVALID_ARG = -1,  /* null pointer, negative size, bad config */
+    INFAAS_SEL_ERR_NOT_LOADED = -2,   /* select / update_load before load_variants */
+    INFAAS_SEL_ERR_OUT_OF_RANGE = -3, /* a table value outside its documented range */
+    INFAAS_SEL_ERR_HIP = -4,          /* a HIP runtime call failed */
+    INFAAS_SEL_ERR_OOM = -5           /* host or device allocation failed */
+};
+
+/* infaas_sel_config.flags, bits 0-3: which search runs inside infaas_sel_select. */
+enum {
+    /* Default: the staircase index answers the queries it can decide; the few it cannot
+     * (slices whose index was truncated) are re-run by the scan. */
+    INFAAS_SEL_ENGINE_AUTO = 0,
+    /* Exhaustive scan only: queries bucketed by (task, batch) slice, slice staged in LDS,
+     * feasibility filter and wavefront min-reduction over every variant of the slice. */
+    INFAAS_SEL_ENGINE_SCAN = 1
+};
+#define INFAAS_SEL_ENGINE_MASK 0xFu
+
+typedef struct {
+    int32_t num_tasks;          /* T >= 1; task ids are 0..T-1 */
+    int32_t num_batch_sizes;    /* B, 1..64; queries carry an index 0..B-1 */
+    const int32_t *batch_sizes; /* HOST [B], copied, informational (may be NULL) */
+    int32_t device;             /* HIP device ordinal the handle lives on */
+    uint32_t flags;             /* INFAAS_SEL_ENGINE_* */
+    int32_t lds_segment_limit;  /* variants of one (task, batch) slice the scan stages in LDS
+                                   at once; larger slices are split across workgroups and the
+                                   partial minima merged device-wide.  0 = default (4096);
+                                   allowed 64..8192, rounded down to a multiple of 64. */
+} infaas_sel_config;
+
+/*
+ * Create a handle on cfg->device.  *out is set only on success.
+ * Errors: INVALID_ARG (null, T < 1, B outside 1..64, T*B > 2^24, bad flags/limit),
+ *         HIP, OOM.
+ */
+int infaas_sel_create(const infaas_sel_config *cfg, infaas_sel_t **out);
+
+/*
+ * Register the variant table (the static profiles and the initial load that the paper
+ * keeps in its Metadata Store, Sections 3.2 and 5).  All arrays are HOST memory and are
+ * copied; rows may come in any order and row numbers are the variant indices that
+ * infaas_sel_select returns and infaas_sel_update_load takes.
+ *   task_id  [V]    0..T-1
+ *   acc_bp   [V]    accuracy in basis points, any int32
+ *   lat_us   [V*B]  row-major [v][b], profiled latency at batch_sizes[b], >= 0
+ *   cost     [V*B]  row-major [v][b], cost of one query at that batch size, >= 0
+ *   queue_us [V]    current queueing delay, >= 0
+ * Synchronous: returns after the table is resident on the device.  Replaces any table
+ * loaded before.  V = 0 is allowed (every query then answers -1).
+ * Errors: INVALID_ARG, OUT_OF_RANGE (task id outside 0..T-1, negative lat/cost/queue;
+ *         the old table is kept), HIP, OOM.
+ */
+int infaas_sel_load_variants(infaas_sel_t *h, int32_t V,
+                             const int32_t *task_id, const int32_t *acc_bp,
+                             const int32_t *lat_us, const int32_t *cost,
+                             const int32_t *queue_us);
+
+/*
+ * Apply a load report (what the workers' monitoring daemons push every few seconds,
+ * Section 5): queue_us[d_variant_idx[i]] = d_queue_us[i] for i in 0..n-1.
+ *   d_variant_idx [n] DEVICE, rows of the loaded table; must not repeat within one call
+ *   d_queue_us    [n] DEVICE, new delay, >= 0
+ * An entry whose row is outside 0..V-1 or whose value is negative is skipped.
+ * Enqueues on hip_stream (a hipStream_t, NULL = the null stream) and returns.
+ * Errors: INVALID_ARG, NOT_LOADED, HIP.
+ */
+int infaas_sel_update_load(infaas_sel_t *h, int32_t n,
+                           const int32_t *d_variant_idx, const int32_t *d_queue_us,
+                           void *hip_stream);
+
+/*
+ * Decide N queries (Section 4.1).  All arrays are DEVICE memory, structure-of-arrays:
+ *   d_task, d_slo_us, d_min_acc_bp, d_batch_idx  [N]  inputs, read only
+ *   d_out_variant                                [N]  row of the chosen variant, or -1
+ * Results are in the caller's query order.  Enqueues on hip_stream and returns; the call
+ * never synchronises the device unless it has to grow its scratch memory (avoid that with
+ * infaas_sel_reserve).  N = 0 is a no-op.
+ * Errors: INVALID_ARG, NOT_LOADED, HIP, OOM.
+ */
+int infaas_sel_select(infaas_sel_t *h, int64_t N,
+                      const int32_t *d_task, const int32_t *d_slo_us,
+                      const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
+                      int32_t *d_out_variant, void *hip_stream);
+
+/* Free the handle and everything it owns.  NULL is a no-op. */
+void infaas_sel_destroy(infaas_sel_t *h);
+
+/* ---- helpers around the five calls above -------------------------------------- */
+
+/* Pre-grow the scratch memory for calls of up to max_queries queries, so that
+ * infaas_sel_select does not allocate.  Errors: INVALID_ARG, HIP, OOM. */
+int infaas_sel_reserve(infaas_sel_t *h, int64_t max_queries);
+
+/* Copy the current queue_us back to HOST memory [V], in the caller's row order, after
+ * synchronising hip_stream.  For tests of infaas_sel_update_load. */
+int infaas_sel_read_load(infaas_sel_t *h, int32_t *queue_us, void *hip_stream);
+
+/* Per-kernel timing.  When enabled, every kernel the library launches is bracketed by HIP
+ * events on the caller's stream; infaas_sel_get_timings synchronises those events and
+ * returns, per kernel, the number of launches and the summed duration since the last
+ * reset.  Kernel ids are INFAAS_SEL_K_*. */
+enum {
+    INFAAS_SEL_K_UPDATE = 0,     /* load-update scatter */
+    INFAAS_SEL_K_HISTOGRAM = 1,  /* scan engine: queries per slice */
+    INFAAS_SEL_K_PLAN = 2,       /* scan engine: prefix sums and tile plan */
+    INFAAS_SEL_K_SCATTER = 3,    /* scan engine: bucket the queries */
+    INFAAS_SEL_K_SCAN_LDS = 4,   /* scan engine: LDS-staged filter + argmin */
+    INFAAS_SEL_K_SCAN_WIDE = 5,  /* scan engine: device-wide path for large slices */
+    INFAAS_SEL_K_FINISH_WIDE = 6,/* scan engine: decode the device-wide minima */
+    INFAAS_SEL_K_INDEX_BUILD = 7,/* staircase index (re)build */
+    INFAAS_SEL_K_INDEX_SELECT = 8,/* staircase index lookup, one lane per query */
+    INFAAS_SEL_K_COUNT = 9
+};
+typedef struct {
+    int64_t launches[INFAAS_SEL_K_COUNT];
+    double total_ms[INFAAS_SEL_K_COUNT];
+} infaas_sel_timings;
+int infaas_sel_set_timing(infaas_sel_t *h, int32_t enabled); /* also resets the counters */
+int infaas_sel_get_timings(infaas_sel_t *h, infaas_sel_timings *out);
+
+/* Sizes the library derived from the loaded table. */
+typedef struct {
+    int32_t num_variants;       /* V */
+    int32_t num_slices;         /* T*B */
+    int32_t max_segment;        /* most variants in one task */
+    int32_t lds_segment_limit;  /* effective value */
+    int32_t wide_segments;      /* tasks handled by the device-wide scan path */
+    int32_t index_in_lds;       /* 1 when the whole staircase index fits in one CU's LDS */
+    int32_t index_truncated;    /* slices whose staircase was cut at its capacity */
+    int32_t index_max_steps;    /* longest staircase of any slice (as stored) */
+    int64_t index_bytes;        /* size of the staircase index */
+    int64_t table_bytes;        /* device bytes of the variant store */
+    int64_t scratch_bytes;      /* device bytes of scratch currently reserved */
+} infaas_sel_info;
+int infaas_sel_get_info(infaas_sel_t *h, infaas_sel_info *out);
+
+/* Static text for a status code. */
+const char *infaas_sel_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INFAAS_SEL_H */

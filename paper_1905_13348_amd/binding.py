@@ -1,0 +1,198 @@
+"""ctypes binding of libinfaas_sel.so.  Same call names as include/infaas_sel.h.
+
+Argument marshalling only.  Device arrays are passed as raw pointers (``tensor.data_ptr()``)
+and the HIP stream as ``torch.cuda.current_stream().cuda_stream``.  There is no CPU
+fallback: if the library has not been built the import of it fails with an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libinfaas_sel.so")
+
+ENGINE_AUTO = 0
+ENGINE_SCAN = 1
+
+KERNEL_NAMES = ("update_load", "histogram", "plan", "scatter", "scan_lds", "scan_wide",
+                "finish_wide", "index_build", "index_select")
+_K_COUNT = len(KERNEL_NAMES)
+
+_I32P = ctypes.POINTER(ctypes.c_int32)
+
+
+class InfaasSelError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"infaas_sel status {status}: {text}")
+        self.status = status
+
+
+class _Config(ctypes.Structure):
+    _fields_ = [("num_tasks", ctypes.c_int32), ("num_batch_sizes", ctypes.c_int32),
+                ("batch_sizes", _I32P), ("device", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("lds_segment_limit", ctypes.c_int32)]
+
+
+class _Timings(ctypes.Structure):
+    _fields_ = [("launches", ctypes.c_int64 * _K_COUNT), ("total_ms", ctypes.c_double * _K_COUNT)]
+
+
+class _Info(ctypes.Structure):
+    _fields_ = [("num_variants", ctypes.c_int32), ("num_slices", ctypes.c_int32),
+                ("max_segment", ctypes.c_int32), ("lds_segment_limit", ctypes.c_int32),
+                ("wide_segments", ctypes.c_int32), ("index_in_lds", ctypes.c_int32),
+                ("index_truncated", ctypes.c_int32), ("index_max_steps", ctypes.c_int32),
+                ("index_bytes", ctypes.c_int64), ("table_bytes", ctypes.c_int64),
+                ("scratch_bytes", ctypes.c_int64)]
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+# every symbol include/infaas_sel.h declares
+EXPORTED = ("infaas_sel_create", "infaas_sel_load_variants", "infaas_sel_update_load",
+            "infaas_sel_select", "infaas_sel_destroy", "infaas_sel_reserve",
+            "infaas_sel_read_load", "infaas_sel_set_timing", "infaas_sel_get_timings",
+            "infaas_sel_get_info", "infaas_sel_strerror")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the built library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it with "
+                          "`python -m paper_1905_13348_amd.build` (needs hipcc)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp = ctypes.c_void_p
+    lib.infaas_sel_create.argtypes = [ctypes.POINTER(_Config), ctypes.POINTER(vp)]
+    lib.infaas_sel_load_variants.argtypes = [vp, ctypes.c_int32, _I32P, _I32P, _I32P, _I32P, _I32P]
+    lib.infaas_sel_update_load.argtypes = [vp, ctypes.c_int32, vp, vp, vp]
+    lib.infaas_sel_select.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp]
+    lib.infaas_sel_destroy.argtypes = [vp]
+    lib.infaas_sel_destroy.restype = None
+    lib.infaas_sel_reserve.argtypes = [vp, ctypes.c_int64]
+    lib.infaas_sel_read_load.argtypes = [vp, _I32P, vp]
+    lib.infaas_sel_set_timing.argtypes = [vp, ctypes.c_int32]
+    lib.infaas_sel_get_timings.argtypes = [vp, ctypes.POINTER(_Timings)]
+    lib.infaas_sel_get_info.argtypes = [vp, ctypes.POINTER(_Info)]
+    lib.infaas_sel_strerror.argtypes = [ctypes.c_int]
+    lib.infaas_sel_strerror.restype = ctypes.c_char_p
+    for name in EXPORTED:
+        if name not in ("infaas_sel_destroy", "infaas_sel_strerror"):
+            getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise InfaasSelError(status, load_library().infaas_sel_strerror(status).decode())
+
+
+def _host_i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _dev_ptr(t, n: int, name: str) -> int:
+    """Raw device pointer of an int32 CUDA/HIP tensor with at least n elements."""
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != torch.int32 \
+            or not t.is_contiguous() or t.numel() < n:
+        raise TypeError(f"{name}: contiguous int32 device tensor with >= {n} elements expected")
+    return t.data_ptr()
+
+
+def _stream_ptr(stream) -> int:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+class Selector:
+    """One handle of the library (infaas_sel_create ... infaas_sel_destroy)."""
+
+    def __init__(self, num_tasks: int, batch_sizes: Sequence[int], device: int = 0,
+                 engine: int = ENGINE_AUTO, lds_segment_limit: int = 0):
+        lib = load_library()
+        bs = _host_i32(batch_sizes)
+        cfg = _Config(num_tasks=num_tasks, num_batch_sizes=bs.shape[0],
+                      batch_sizes=bs.ctypes.data_as(_I32P), device=device, flags=engine,
+                      lds_segment_limit=lds_segment_limit)
+        h = ctypes.c_void_p()
+        _check(lib.infaas_sel_create(ctypes.byref(cfg), ctypes.byref(h)))
+        self._h = h
+        self._lib = lib
+        self.num_tasks = num_tasks
+        self.num_batch_sizes = int(bs.shape[0])
+        self.device = device
+
+    # -- the five calls ------------------------------------------------------------
+    def load_variants(self, task_id, acc_bp, lat_us, cost, queue_us) -> None:
+        task_id, acc_bp, queue_us = _host_i32(task_id), _host_i32(acc_bp), _host_i32(queue_us)
+        lat_us, cost = _host_i32(lat_us), _host_i32(cost)
+        V = task_id.shape[0]
+        if lat_us.shape != (V, self.num_batch_sizes) or cost.shape != lat_us.shape \
+                or acc_bp.shape != (V,) or queue_us.shape != (V,):
+            raise ValueError("table arrays have inconsistent shapes")
+        p = lambda a: a.ctypes.data_as(_I32P)
+        _check(self._lib.infaas_sel_load_variants(self._h, V, p(task_id), p(acc_bp), p(lat_us),
+                                                  p(cost), p(queue_us)))
+
+    def update_load(self, d_variant_idx, d_queue_us, stream=None) -> None:
+        n = int(d_variant_idx.numel())
+        _check(self._lib.infaas_sel_update_load(
+            self._h, n, _dev_ptr(d_variant_idx, n, "d_variant_idx"),
+            _dev_ptr(d_queue_us, n, "d_queue_us"), _stream_ptr(stream)))
+
+    def select(self, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, stream=None,
+               n: Optional[int] = None) -> None:
+        n = int(d_task.numel()) if n is None else int(n)
+        _check(self._lib.infaas_sel_select(
+            self._h, n, _dev_ptr(d_task, n, "d_task"), _dev_ptr(d_slo_us, n, "d_slo_us"),
+            _dev_ptr(d_min_acc_bp, n, "d_min_acc_bp"), _dev_ptr(d_batch_idx, n, "d_batch_idx"),
+            _dev_ptr(d_out_variant, n, "d_out_variant"), _stream_ptr(stream)))
+
+    def destroy(self) -> None:
+        if self._h:
+            self._lib.infaas_sel_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    # -- helpers -------------------------------------------------------------------
+    def reserve(self, max_queries: int) -> None:
+        _check(self._lib.infaas_sel_reserve(self._h, int(max_queries)))
+
+    def read_load(self, num_variants: int, stream=None) -> np.ndarray:
+        out = np.empty(num_variants, dtype=np.int32)
+        _check(self._lib.infaas_sel_read_load(self._h, out.ctypes.data_as(_I32P),
+                                              _stream_ptr(stream)))
+        return out
+
+    def set_timing(self, enabled: bool) -> None:
+        _check(self._lib.infaas_sel_set_timing(self._h, 1 if enabled else 0))
+
+    def get_timings(self) -> dict:
+        t = _Timings()
+        _check(self._lib.infaas_sel_get_timings(self._h, ctypes.byref(t)))
+        return {name: dict(launches=int(t.launches[i]), total_ms=float(t.total_ms[i]))
+                for i, name in enumerate(KERNEL_NAMES)}
+
+    def info(self) -> dict:
+        i = _Info()
+        _check(self._lib.infaas_sel_get_info(self._h, ctypes.byref(i)))
+        return {name: int(getattr(i, name)) for name, _ in _Info._fields_}
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

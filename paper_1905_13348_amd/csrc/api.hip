@@ -1,0 +1,503 @@
+// Host runtime of libinfaas_sel: handle, variant-store build, scratch, launch sequencing.
+// The operation and its C ABI are specified in include/infaas_sel.h.
+#include "infaas_sel.h"
+#include "internal.h"
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <numeric>
+#include <vector>
+
+using namespace infaas;
+
+namespace {
+
+struct DeviceGuard {
+    int prev = -1;
+    bool ok = true;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) { ok = false; return; }
+        if (prev != dev && hipSetDevice(dev) != hipSuccess) ok = false;
+        target = dev;
+    }
+    ~DeviceGuard()
+    {
+        if (prev >= 0 && prev != target) (void)hipSetDevice(prev);
+    }
+    int target = -1;
+};
+
+struct TimedLaunch {
+    int kid;
+    hipEvent_t a, b;
+};
+
+template <typename T>
+hipError_t dev_alloc(T **p, size_t count)
+{
+    *p = nullptr;
+    return hipMalloc((void **)p, std::max<size_t>(count, 1) * sizeof(T));
+}
+
+}  // namespace
+
+struct infaas_sel {
+    int32_t T = 0, B = 0, device = 0;
+    uint32_t flags = 0;
+    int32_t lds_limit = 4096;
+    int num_cus = 256;
+    std::vector<int32_t> batch_sizes;
+
+    bool loaded = false;
+    // variant store (device)
+    int32_t V = 0, Vp = 0;
+    int32_t *d_acc = nullptr, *d_queue = nullptr, *d_orig = nullptr, *d_lat = nullptr;
+    uint32_t *d_rank = nullptr, *d_perm = nullptr;
+    int32_t *d_seg_off = nullptr, *d_seg_len = nullptr, *d_slot_of = nullptr;
+    int64_t table_bytes = 0;
+    int32_t max_segment = 0, max_lds_segment = 0, wide_segments = 0;
+    TableView tv{};
+
+    // scan scratch
+    ScanScratch sc{};
+    int64_t sc_capacity = 0;
+    int32_t sc_slices = 0;
+    int64_t scratch_bytes = 0;
+    bool cnt_dirty = false;
+
+    // timing
+    bool timing = false;
+    std::vector<TimedLaunch> pending;
+    std::vector<hipEvent_t> free_events;
+    infaas_sel_timings acc{};
+
+    void free_table()
+    {
+        (void)hipFree(d_acc); (void)hipFree(d_queue); (void)hipFree(d_orig); (void)hipFree(d_lat);
+        (void)hipFree(d_rank); (void)hipFree(d_perm); (void)hipFree(d_seg_off);
+        (void)hipFree(d_seg_len); (void)hipFree(d_slot_of);
+        d_acc = d_queue = d_orig = d_lat = d_seg_off = d_seg_len = d_slot_of = nullptr;
+        d_rank = d_perm = nullptr;
+        loaded = false;
+        table_bytes = 0;
+    }
+    void free_scratch()
+    {
+        (void)hipFree(sc.cnt); (void)hipFree(sc.bucket_off); (void)hipFree(sc.cursor);
+        (void)hipFree(sc.tile_off); (void)hipFree(sc.wide_off); (void)hipFree(sc.counters);
+        (void)hipFree(sc.recs); (void)hipFree(sc.best);
+        sc = ScanScratch{};
+        sc_capacity = 0;
+        sc_slices = 0;
+        scratch_bytes = 0;
+    }
+};
+
+namespace {
+
+bool get_event(infaas_sel *h, hipEvent_t *e)
+{
+    if (!h->free_events.empty()) {
+        *e = h->free_events.back();
+        h->free_events.pop_back();
+        return true;
+    }
+    return hipEventCreate(e) == hipSuccess;
+}
+
+// Brackets one kernel launch with events when timing is on.
+struct LaunchTimer {
+    infaas_sel *h;
+    hipStream_t st;
+    TimedLaunch tl{};
+    bool active = false;
+    LaunchTimer(infaas_sel *h_, int kid, hipStream_t st_) : h(h_), st(st_)
+    {
+        if (!h->timing) return;
+        tl.kid = kid;
+        if (!get_event(h, &tl.a)) return;
+        if (!get_event(h, &tl.b)) { h->free_events.push_back(tl.a); return; }
+        active = hipEventRecord(tl.a, st) == hipSuccess;
+        if (!active) { h->free_events.push_back(tl.a); h->free_events.push_back(tl.b); }
+    }
+    ~LaunchTimer()
+    {
+        if (!active) return;
+        if (hipEventRecord(tl.b, st) == hipSuccess) h->pending.push_back(tl);
+        else { h->free_events.push_back(tl.a); h->free_events.push_back(tl.b); }
+    }
+};
+
+int ensure_scratch(infaas_sel *h, int64_t capacity)
+{
+    const int32_t S = h->T * h->B;
+    if (h->sc.recs && h->sc_capacity >= capacity && h->sc_slices == S) return INFAAS_SEL_OK;
+    // growing: nothing enqueued earlier may still use the old buffers
+    if (hipDeviceSynchronize() != hipSuccess) return INFAAS_SEL_ERR_HIP;
+    int64_t cap = std::max<int64_t>(capacity, h->sc_capacity);
+    h->free_scratch();
+    ScanScratch sc{};
+    bool ok = dev_alloc(&sc.cnt, S) == hipSuccess && dev_alloc(&sc.bucket_off, S + 1) == hipSuccess &&
+              dev_alloc(&sc.cursor, S) == hipSuccess && dev_alloc(&sc.tile_off, S + 1) == hipSuccess &&
+              dev_alloc(&sc.wide_off, S + 1) == hipSuccess && dev_alloc(&sc.counters, 4) == hipSuccess &&
+              dev_alloc(&sc.recs, (size_t)cap) == hipSuccess && dev_alloc(&sc.best, (size_t)cap) == hipSuccess;
+    h->sc = sc;
+    if (!ok) {
+        h->free_scratch();
+        (void)hipGetLastError();
+        return INFAAS_SEL_ERR_OOM;
+    }
+    if (hipMemset(sc.cnt, 0, std::max<size_t>(S, 1) * 4) != hipSuccess ||
+        hipMemset(sc.counters, 0, 16) != hipSuccess) {
+        h->free_scratch();
+        return INFAAS_SEL_ERR_HIP;
+    }
+    h->cnt_dirty = false;
+    h->sc_capacity = cap;
+    h->sc_slices = S;
+    h->scratch_bytes = (int64_t)S * 4 * 5 + 8 + 16 + cap * (16 + 4);
+    return INFAAS_SEL_OK;
+}
+
+// One pass of the scan engine over n <= 2^28 queries.
+int scan_pass(infaas_sel *h, const QueryView &q, hipStream_t st)
+{
+    if (h->cnt_dirty) {  // an earlier call failed between histogram and plan
+        if (hipStreamSynchronize(st) != hipSuccess) return INFAAS_SEL_ERR_HIP;
+        if (hipMemset(h->sc.cnt, 0, (size_t)h->tv.S * 4) != hipSuccess) return INFAAS_SEL_ERR_HIP;
+        h->cnt_dirty = false;
+    }
+    h->cnt_dirty = true;
+    {
+        LaunchTimer t(h, INFAAS_SEL_K_HISTOGRAM, st);
+        if (launch_histogram(h->tv, q, h->sc, st) != hipSuccess) return INFAAS_SEL_ERR_HIP;
+    }
+    {
+        LaunchTimer t(h, INFAAS_SEL_K_PLAN, st);
+        if (launch_plan(h->tv, h->sc, st) != hipSuccess) return INFAAS_SEL_ERR_HIP;
+    }
+    h->cnt_dirty = false;
+    const bool wide = h->wide_segments > 0;
+    {
+        LaunchTimer t(h, INFAAS_SEL_K_SCATTER, st);
+        if (launch_scatter(h->tv, q, h->sc, wide, st) != hipSuccess) return INFAAS_SEL_ERR_HIP;
+    }
+    if (h->max_lds_segment > 0) {
+        LaunchTimer t(h, INFAAS_SEL_K_SCAN_LDS, st);
+        if (launch_scan_lds(h->tv, q, h->sc, h->max_lds_segment, h->num_cus, st) != hipSuccess)
+            return INFAAS_SEL_ERR_HIP;
+    }
+    if (wide) {
+        {
+            LaunchTimer t(h, INFAAS_SEL_K_SCAN_WIDE, st);
+            if (launch_scan_wide(h->tv, q, h->sc, h->num_cus, st) != hipSuccess)
+                return INFAAS_SEL_ERR_HIP;
+        }
+        LaunchTimer t(h, INFAAS_SEL_K_FINISH_WIDE, st);
+        if (launch_finish_wide(h->tv, q, h->sc, st) != hipSuccess) return INFAAS_SEL_ERR_HIP;
+    }
+    return INFAAS_SEL_OK;
+}
+
+constexpr int64_t kMaxPass = (int64_t)1 << 28;
+
+}  // namespace
+
+extern "C" {
+
+const char *infaas_sel_strerror(int status)
+{
+    switch (status) {
+    case INFAAS_SEL_OK: return "ok";
+    case INFAAS_SEL_ERR_INVALID_ARG: return "invalid argument";
+    case INFAAS_SEL_ERR_NOT_LOADED: return "no variant table loaded";
+    case INFAAS_SEL_ERR_OUT_OF_RANGE: return "table value out of range";
+    case INFAAS_SEL_ERR_HIP: return "HIP runtime error";
+    case INFAAS_SEL_ERR_OOM: return "out of memory";
+    default: return "unknown status";
+    }
+}
+
+int infaas_sel_create(const infaas_sel_config *cfg, infaas_sel_t **out)
+{
+    if (!cfg || !out) return INFAAS_SEL_ERR_INVALID_ARG;
+    if (cfg->num_tasks < 1 || cfg->num_batch_sizes < 1 || cfg->num_batch_sizes > 64)
+        return INFAAS_SEL_ERR_INVALID_ARG;
+    if ((int64_t)cfg->num_tasks * cfg->num_batch_sizes > ((int64_t)1 << 24))
+        return INFAAS_SEL_ERR_INVALID_ARG;
+    uint32_t engine = cfg->flags & INFAAS_SEL_ENGINE_MASK;
+    if ((cfg->flags & ~INFAAS_SEL_ENGINE_MASK) != 0 || engine > INFAAS_SEL_ENGINE_SCAN)
+        return INFAAS_SEL_ERR_INVALID_ARG;
+    int32_t lim = cfg->lds_segment_limit == 0 ? 4096 : cfg->lds_segment_limit;
+    if (lim < 64 || lim > 8192) return INFAAS_SEL_ERR_INVALID_ARG;
+    lim &= ~63;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess) return INFAAS_SEL_ERR_HIP;
+    if (cfg->device < 0 || cfg->device >= ndev) return INFAAS_SEL_ERR_INVALID_ARG;
+
+    infaas_sel *h = new (std::nothrow) infaas_sel();
+    if (!h) return INFAAS_SEL_ERR_OOM;
+    h->T = cfg->num_tasks;
+    h->B = cfg->num_batch_sizes;
+    h->device = cfg->device;
+    h->flags = cfg->flags;
+    h->lds_limit = lim;
+    if (cfg->batch_sizes) h->batch_sizes.assign(cfg->batch_sizes, cfg->batch_sizes + h->B);
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, h->device) != hipSuccess) {
+        delete h;
+        return INFAAS_SEL_ERR_HIP;
+    }
+    h->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    *out = h;
+    return INFAAS_SEL_OK;
+}
+
+int infaas_sel_load_variants(infaas_sel_t *h, int32_t V, const int32_t *task_id,
+                             const int32_t *acc_bp, const int32_t *lat_us, const int32_t *cost,
+                             const int32_t *queue_us)
+{
+    if (!h || V < 0) return INFAAS_SEL_ERR_INVALID_ARG;
+    if (V > 0 && (!task_id || !acc_bp || !lat_us || !cost || !queue_us))
+        return INFAAS_SEL_ERR_INVALID_ARG;
+    const int32_t T = h->T, B = h->B;
+
+    // ---- validate ranges before touching the old table
+    for (int64_t v = 0; v < V; ++v) {
+        if (task_id[v] < 0 || task_id[v] >= T || queue_us[v] < 0) return INFAAS_SEL_ERR_OUT_OF_RANGE;
+        for (int32_t b = 0; b < B; ++b)
+            if (lat_us[v * B + b] < 0 || cost[v * B + b] < 0) return INFAAS_SEL_ERR_OUT_OF_RANGE;
+    }
+
+    // ---- group rows by task (stable), pad every segment to a multiple of 4 slots
+    std::vector<int32_t> seg_len(T, 0), seg_off((size_t)T + 1, 0);
+    for (int64_t v = 0; v < V; ++v) seg_len[task_id[v]] += 1;
+    int64_t total = 0;
+    int32_t max_seg = 0, max_lds_seg = 0, wide = 0;
+    for (int32_t t = 0; t < T; ++t) {
+        seg_off[t] = (int32_t)total;
+        total += (seg_len[t] + 3) & ~3;
+        if (total > INT32_MAX - 64) return INFAAS_SEL_ERR_INVALID_ARG;
+        max_seg = std::max(max_seg, seg_len[t]);
+        if (seg_len[t] > h->lds_limit) wide += 1;
+        else max_lds_seg = std::max(max_lds_seg, seg_len[t]);
+    }
+    seg_off[T] = (int32_t)total;
+    const int32_t Vp = (int32_t)((total + 63) & ~(int64_t)63) + 64;
+
+    std::vector<int32_t> acc(Vp, INT32_MIN), queue(Vp, INT32_MAX), orig(Vp, -1), slot_of(std::max(V, 1), 0);
+    std::vector<int32_t> lat((size_t)B * Vp, INT32_MAX);
+    std::vector<uint32_t> rank((size_t)B * Vp, kNoRank), perm((size_t)B * Vp, 0u);
+    {
+        std::vector<int32_t> fill(T, 0);
+        for (int64_t v = 0; v < V; ++v) {
+            int32_t t = task_id[v];
+            int32_t slot = seg_off[t] + fill[t]++;
+            acc[slot] = acc_bp[v];
+            queue[slot] = queue_us[v];
+            orig[slot] = (int32_t)v;
+            slot_of[v] = slot;
+            for (int32_t b = 0; b < B; ++b) lat[(size_t)b * Vp + slot] = lat_us[v * B + b];
+        }
+    }
+    // ---- rank of every row inside its (task, batch) slice under (cost, latency, row)
+    {
+        std::vector<int32_t> ord;
+        for (int32_t t = 0; t < T; ++t) {
+            const int32_t L = seg_len[t], seg = seg_off[t];
+            if (L == 0) continue;
+            ord.resize(L);
+            for (int32_t b = 0; b < B; ++b) {
+                std::iota(ord.begin(), ord.end(), 0);
+                std::sort(ord.begin(), ord.end(), [&](int32_t x, int32_t y) {
+                    const int64_t vx = orig[seg + x], vy = orig[seg + y];
+                    const int32_t cx = cost[vx * B + b], cy = cost[vy * B + b];
+                    if (cx != cy) return cx < cy;
+                    const int32_t lx = lat_us[vx * B + b], ly = lat_us[vy * B + b];
+                    if (lx != ly) return lx < ly;
+                    return vx < vy;
+                });
+                for (int32_t r = 0; r < L; ++r) {
+                    perm[(size_t)b * Vp + seg + r] = (uint32_t)ord[r];
+                    rank[(size_t)b * Vp + seg + ord[r]] = (uint32_t)r;
+                }
+            }
+        }
+    }
+
+    // ---- upload
+    DeviceGuard g(h->device);
+    if (!g.ok) return INFAAS_SEL_ERR_HIP;
+    if (hipDeviceSynchronize() != hipSuccess) return INFAAS_SEL_ERR_HIP;
+    h->free_table();
+    bool ok = dev_alloc(&h->d_acc, Vp) == hipSuccess && dev_alloc(&h->d_queue, Vp) == hipSuccess &&
+              dev_alloc(&h->d_orig, Vp) == hipSuccess && dev_alloc(&h->d_lat, (size_t)B * Vp) == hipSuccess &&
+              dev_alloc(&h->d_rank, (size_t)B * Vp) == hipSuccess &&
+              dev_alloc(&h->d_perm, (size_t)B * Vp) == hipSuccess &&
+              dev_alloc(&h->d_seg_off, (size_t)T + 1) == hipSuccess && dev_alloc(&h->d_seg_len, T) == hipSuccess &&
+              dev_alloc(&h->d_slot_of, std::max(V, 1)) == hipSuccess;
+    if (!ok) {
+        h->free_table();
+        (void)hipGetLastError();
+        return INFAAS_SEL_ERR_OOM;
+    }
+    auto up = [](void *d, const void *s, size_t bytes) {
+        return bytes == 0 || hipMemcpy(d, s, bytes, hipMemcpyHostToDevice) == hipSuccess;
+    };
+    ok = up(h->d_acc, acc.data(), (size_t)Vp * 4) && up(h->d_queue, queue.data(), (size_t)Vp * 4) &&
+         up(h->d_orig, orig.data(), (size_t)Vp * 4) && up(h->d_lat, lat.data(), (size_t)B * Vp * 4) &&
+         up(h->d_rank, rank.data(), (size_t)B * Vp * 4) && up(h->d_perm, perm.data(), (size_t)B * Vp * 4) &&
+         up(h->d_seg_off, seg_off.data(), ((size_t)T + 1) * 4) && up(h->d_seg_len, seg_len.data(), (size_t)T * 4) &&
+         up(h->d_slot_of, slot_of.data(), (size_t)std::max(V, 1) * 4);
+    if (!ok) {
+        h->free_table();
+        return INFAAS_SEL_ERR_HIP;
+    }
+    h->V = V;
+    h->Vp = Vp;
+    h->max_segment = max_seg;
+    h->max_lds_segment = max_lds_seg;
+    h->wide_segments = wide;
+    h->table_bytes = (int64_t)Vp * 4 * (3 + 3 * (int64_t)B) + ((int64_t)2 * T + 1 + std::max(V, 1)) * 4;
+    TableView tv{};
+    tv.T = T; tv.B = B; tv.S = T * B; tv.V = V; tv.Vp = Vp; tv.lds_limit = h->lds_limit;
+    tv.acc = h->d_acc; tv.queue = h->d_queue; tv.orig = h->d_orig; tv.lat = h->d_lat;
+    tv.rank = h->d_rank; tv.perm = h->d_perm; tv.seg_off = h->d_seg_off; tv.seg_len = h->d_seg_len;
+    tv.slot_of = h->d_slot_of;
+    h->tv = tv;
+    h->loaded = true;
+    return INFAAS_SEL_OK;
+}
+
+int infaas_sel_update_load(infaas_sel_t *h, int32_t n, const int32_t *d_variant_idx,
+                           const int32_t *d_queue_us, void *hip_stream)
+{
+    if (!h || n < 0) return INFAAS_SEL_ERR_INVALID_ARG;
+    if (!h->loaded) return INFAAS_SEL_ERR_NOT_LOADED;
+    if (n == 0) return INFAAS_SEL_OK;
+    if (!d_variant_idx || !d_queue_us) return INFAAS_SEL_ERR_INVALID_ARG;
+    DeviceGuard g(h->device);
+    if (!g.ok) return INFAAS_SEL_ERR_HIP;
+    hipStream_t st = (hipStream_t)hip_stream;
+    LaunchTimer t(h, INFAAS_SEL_K_UPDATE, st);
+    if (launch_update_load(h->tv, n, d_variant_idx, d_queue_us, nullptr, st) != hipSuccess)
+        return INFAAS_SEL_ERR_HIP;
+    return INFAAS_SEL_OK;
+}
+
+int infaas_sel_select(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,
+                      const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
+                      int32_t *d_out_variant, void *hip_stream)
+{
+    if (!h || N < 0) return INFAAS_SEL_ERR_INVALID_ARG;
+    if (!h->loaded) return INFAAS_SEL_ERR_NOT_LOADED;
+    if (N == 0) return INFAAS_SEL_OK;
+    if (!d_task || !d_slo_us || !d_min_acc_bp || !d_batch_idx || !d_out_variant)
+        return INFAAS_SEL_ERR_INVALID_ARG;
+    DeviceGuard g(h->device);
+    if (!g.ok) return INFAAS_SEL_ERR_HIP;
+    hipStream_t st = (hipStream_t)hip_stream;
+    int rc = ensure_scratch(h, std::min(N, kMaxPass));
+    if (rc != INFAAS_SEL_OK) return rc;
+    for (int64_t done = 0; done < N; done += kMaxPass) {
+        QueryView q{};
+        q.n = (int32_t)std::min(kMaxPass, N - done);
+        q.task = d_task + done; q.slo = d_slo_us + done; q.min_acc = d_min_acc_bp + done;
+        q.bidx = d_batch_idx + done; q.out = d_out_variant + done;
+        rc = scan_pass(h, q, st);
+        if (rc != INFAAS_SEL_OK) return rc;
+    }
+    return INFAAS_SEL_OK;
+}
+
+void infaas_sel_destroy(infaas_sel_t *h)
+{
+    if (!h) return;
+    {
+        DeviceGuard g(h->device);
+        (void)hipDeviceSynchronize();
+        h->free_table();
+        h->free_scratch();
+        for (auto &p : h->pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+        for (auto &e : h->free_events) (void)hipEventDestroy(e);
+    }
+    delete h;
+}
+
+int infaas_sel_reserve(infaas_sel_t *h, int64_t max_queries)
+{
+    if (!h || max_queries < 0) return INFAAS_SEL_ERR_INVALID_ARG;
+    DeviceGuard g(h->device);
+    if (!g.ok) return INFAAS_SEL_ERR_HIP;
+    return ensure_scratch(h, std::max<int64_t>(1, std::min(max_queries, kMaxPass)));
+}
+
+int infaas_sel_read_load(infaas_sel_t *h, int32_t *queue_us, void *hip_stream)
+{
+    if (!h || !queue_us) return INFAAS_SEL_ERR_INVALID_ARG;
+    if (!h->loaded) return INFAAS_SEL_ERR_NOT_LOADED;
+    DeviceGuard g(h->device);
+    if (!g.ok) return INFAAS_SEL_ERR_HIP;
+    if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return INFAAS_SEL_ERR_HIP;
+    std::vector<int32_t> q(h->Vp), slot(std::max(h->V, 1));
+    if (hipMemcpy(q.data(), h->d_queue, (size_t)h->Vp * 4, hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemcpy(slot.data(), h->d_slot_of, (size_t)std::max(h->V, 1) * 4, hipMemcpyDeviceToHost) != hipSuccess)
+        return INFAAS_SEL_ERR_HIP;
+    for (int32_t v = 0; v < h->V; ++v) queue_us[v] = q[slot[v]];
+    return INFAAS_SEL_OK;
+}
+
+int infaas_sel_set_timing(infaas_sel_t *h, int32_t enabled)
+{
+    if (!h) return INFAAS_SEL_ERR_INVALID_ARG;
+    DeviceGuard g(h->device);
+    for (auto &p : h->pending) {
+        (void)hipEventSynchronize(p.b);
+        h->free_events.push_back(p.a);
+        h->free_events.push_back(p.b);
+    }
+    h->pending.clear();
+    h->acc = infaas_sel_timings{};
+    h->timing = enabled != 0;
+    return INFAAS_SEL_OK;
+}
+
+int infaas_sel_get_timings(infaas_sel_t *h, infaas_sel_timings *out)
+{
+    if (!h || !out) return INFAAS_SEL_ERR_INVALID_ARG;
+    DeviceGuard g(h->device);
+    if (!g.ok) return INFAAS_SEL_ERR_HIP;
+    int rc = INFAAS_SEL_OK;
+    for (auto &p : h->pending) {
+        float ms = 0.f;
+        if (hipEventSynchronize(p.b) == hipSuccess && hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) {
+            h->acc.launches[p.kid] += 1;
+            h->acc.total_ms[p.kid] += ms;
+        } else {
+            rc = INFAAS_SEL_ERR_HIP;
+        }
+        h->free_events.push_back(p.a);
+        h->free_events.push_back(p.b);
+    }
+    h->pending.clear();
+    *out = h->acc;
+    return rc;
+}
+
+int infaas_sel_get_info(infaas_sel_t *h, infaas_sel_info *out)
+{
+    if (!h || !out) return INFAAS_SEL_ERR_INVALID_ARG;
+    std::memset(out, 0, sizeof(*out));
+    out->num_variants = h->V;
+    out->num_slices = h->T * h->B;
+    out->max_segment = h->max_segment;
+    out->lds_segment_limit = h->lds_limit;
+    out->wide_segments = h->wide_segments;
+    out->table_bytes = h->table_bytes;
+    out->scratch_bytes = h->scratch_bytes;
+    return INFAAS_SEL_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,294 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle.
+
+All fields are integers, so the bar is bit-exact equality on every query.  Small cases are
+compared element by element; the full-size configurations are compared on a random sample
+of queries that the oracle computes one by one, plus feasibility of every answer.
+"""
+import numpy as np
+import pytest
+
+import workloads
+from gpu_util import gpu_select, make_selector, query_args, table_args, to_dev
+from pins import check_invariants
+
+pytestmark = pytest.mark.gpu
+
+ENGINES = [0, 1]  # auto (index + scan fall-back), scan only
+ENGINE_IDS = ["auto", "scan"]
+I32MAX = 2**31 - 1
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _table(num_tasks, batch_sizes, task_id, acc, lat, cost, queue):
+    return workloads.VariantTable(num_tasks=num_tasks, batch_sizes=np.asarray(batch_sizes, np.int32),
+                                  task_id=np.asarray(task_id, np.int32), acc_bp=np.asarray(acc, np.int32),
+                                  lat_us=np.asarray(lat, np.int32), cost=np.asarray(cost, np.int32),
+                                  queue_us=np.asarray(queue, np.int32))
+
+
+def _random_table(rng, T, sizes, B, span=None):
+    """Table with given segment sizes; small `span` forces ties everywhere."""
+    V = int(np.sum(sizes))
+    task = np.repeat(np.arange(T, dtype=np.int32), sizes)
+    if span is None:
+        acc, lat, cost, queue = workloads.configs.make_variant_fields(
+            rng, V, np.asarray([1, 2, 4, 8, 16, 32, 64, 128][:B], np.int32))
+    else:
+        acc = rng.integers(0, span, V); lat = rng.integers(0, span, (V, B))
+        cost = rng.integers(0, span, (V, B)); queue = rng.integers(0, span, V)
+    perm = rng.permutation(V)
+    return _table(T, list(range(1, B + 1)), task[perm], acc, lat, cost, queue)
+
+
+def _random_queries(rng, T, B, n, span=None, with_invalid=True):
+    lo = -1 if with_invalid else 0
+    task = rng.integers(lo, T + (1 if with_invalid else 0), n)
+    bidx = rng.integers(lo, B + (1 if with_invalid else 0), n)
+    if span is None:
+        slo = np.clip(np.rint(rng.lognormal(np.log(20000.0), 1.0, n)), 1000, 2_000_000)
+        acc = rng.integers(5000, 9501, n)
+        if with_invalid:
+            slo[rng.random(n) < 0.01] = -7
+    else:
+        slo = rng.integers(lo, 2 * span, n); acc = rng.integers(lo, span + 1, n)
+    return tuple(np.asarray(x, np.int32) for x in (task, slo, acc, bidx))
+
+
+def _compare(oracle_lib, tb, queries, engine, lds_limit=0, label=""):
+    _say(f"case {label}: V={tb.V} T={tb.num_tasks} B={tb.B} N={len(queries[0])} engine={engine} "
+         f"lds_limit={lds_limit}")
+    sel = make_selector(tb, engine=engine, lds_segment_limit=lds_limit)
+    got = gpu_select(sel, *queries)
+    want = oracle_lib.select(*table_args(tb), *queries)
+    bad = np.flatnonzero(got != want)
+    assert bad.size == 0, f"{label}: {bad.size} mismatches, first at {bad[:5]}: got {got[bad[:5]]} want {want[bad[:5]]}"
+    sel.destroy()
+    return got
+
+
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
+def test_config0_tiny_exact(oracle_lib, engine):
+    tb = workloads.make_table(0)
+    q = workloads.make_queries(0)
+    _compare(oracle_lib, tb, query_args(q), engine, label="config0")
+
+
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
+def test_config1_medium_exact(oracle_lib, engine):
+    """Config 1 at its full 1M queries: 200-variant segments, several tiles and a ragged tail."""
+    tb = workloads.make_table(1)
+    q = workloads.make_queries(1, n=1_000_003 if engine == 0 else 300_007)
+    _compare(oracle_lib, tb, query_args(q), engine, label="config1")
+
+
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
+def test_ties_and_invalid_queries(oracle_lib, engine):
+    """Small value ranges: many equal costs and latencies, so the row tie-break decides;
+    queries include unknown tasks, bad batch indices and negative objectives."""
+    rng = np.random.default_rng(11)
+    for trial in range(6):
+        T = int(rng.integers(1, 9)); B = int(rng.integers(1, 6))
+        sizes = rng.integers(0, 70, T)
+        span = int(rng.choice([2, 3, 7, 40]))
+        tb = _random_table(rng, T, sizes, B, span=span)
+        qs = _random_queries(rng, T, B, 5000, span=span)
+        _compare(oracle_lib, tb, qs, engine, label=f"ties{trial}")
+
+
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
+@pytest.mark.parametrize("lds_limit", [64, 128])
+def test_wide_path_small_limit(oracle_lib, engine, lds_limit):
+    """A low LDS limit sends config 1's 200-variant segments through the device-wide path
+    (chunks of 64: three full chunks and a ragged one)."""
+    tb = workloads.make_table(1)
+    q = workloads.make_queries(1, n=100_000)
+    _compare(oracle_lib, tb, query_args(q), engine, lds_limit=lds_limit, label="wide-small")
+
+
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
+def test_segment_sizes_around_the_limit_and_maximum(oracle_lib, engine):
+    """Segments of 1, limit-1, limit, limit+1 variants and one of 20,000 (the largest a task
+    may have in the skewed configuration), with an empty task in between."""
+    rng = np.random.default_rng(5)
+    sizes = np.array([1, 4095, 4096, 4097, 0, 20000, 3, 257], dtype=np.int64)
+    tb = _random_table(rng, len(sizes), sizes, 8)
+    qs = _random_queries(rng, len(sizes), 8, 60_000)
+    got = _compare(oracle_lib, tb, qs, engine, label="limits")
+    assert (got[qs[0] == 4] == -1).all()
+
+
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
+def test_degenerate_inputs(oracle_lib, engine):
+    import torch
+    import paper_1905_13348_amd as lib
+    rng = np.random.default_rng(3)
+    # all infeasible / all feasible / all ties
+    tb = _random_table(rng, 3, np.array([50, 50, 50]), 2, span=5)
+    n = 3000
+    task = rng.integers(0, 3, n).astype(np.int32); bidx = rng.integers(0, 2, n).astype(np.int32)
+    for slo, acc in ((np.full(n, 0), np.full(n, 100)), (np.full(n, I32MAX), np.full(n, -I32MAX - 1)),
+                     (np.full(n, 4), np.full(n, 2))):
+        _compare(oracle_lib, tb, (task, slo.astype(np.int32), acc.astype(np.int32), bidx), engine,
+                 label="degenerate")
+    # empty table and empty query batch
+    sel = lib.Selector(4, [1, 2], engine=engine)
+    e = np.zeros(0, np.int32)
+    sel.load_variants(e, e, np.zeros((0, 2), np.int32), np.zeros((0, 2), np.int32), e)
+    got = gpu_select(sel, task[:100] % 4, np.full(100, 5, np.int32), np.zeros(100, np.int32), bidx[:100])
+    assert (got == -1).all()
+    out = torch.zeros(1, dtype=torch.int32, device="cuda")
+    sel.select(out, out, out, out, out, n=0)
+    sel.destroy()
+    # extreme values: the sum lat + queue must not wrap
+    tb = _table(1, [1], [0, 0], [8000, 8000], [[I32MAX], [I32MAX]], [[1], [2]], [I32MAX, 0])
+    qs = tuple(np.asarray(x, np.int32) for x in ([0, 0, 0], [I32MAX, I32MAX - 1, -5], [0, 0, 0], [0, 0, 0]))
+    _compare(oracle_lib, tb, qs, engine, label="extremes")
+
+
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
+def test_update_load_then_select(oracle_lib, engine):
+    """Load reports between batches: values land on the right rows, bad entries are skipped,
+    and the next batch sees the new load (same stream ordering)."""
+    import torch
+    tb = workloads.make_table(1)
+    sel = make_selector(tb, engine=engine)
+    queue = tb.queue_us.copy()
+    rng = np.random.default_rng(17)
+    for step in range(4):
+        q = workloads.make_queries(1, n=50_000, seed=900 + step)
+        up = workloads.make_load_update(1, tb.V, chunk=step + 1, fraction=0.1)
+        idx = up.variant_idx.copy(); val = up.queue_us.copy()
+        if step == 2:  # bad entries: skipped by both sides
+            idx[:3] = [-1, tb.V, tb.V + 5]; val[3:6] = -1
+        _say(f"update step {step}: n={idx.size}")
+        sel.update_load(to_dev(idx), to_dev(val))
+        oracle_lib.update_load(queue, idx, val)
+        got = gpu_select(sel, *query_args(q))
+        want = oracle_lib.select(*table_args(tb, queue), *query_args(q))
+        assert np.array_equal(got, want), f"step {step}"
+        assert np.array_equal(sel.read_load(tb.V), queue)
+    sel.destroy()
+
+
+def test_error_codes():
+    import torch
+    import paper_1905_13348_amd as lib
+    with pytest.raises(lib.InfaasSelError) as e:
+        lib.Selector(0, [1])
+    assert e.value.status == -1
+    with pytest.raises(lib.InfaasSelError):
+        lib.Selector(2, [1], lds_segment_limit=9)
+    sel = lib.Selector(2, [1, 2])
+    x = torch.zeros(4, dtype=torch.int32, device="cuda")
+    with pytest.raises(lib.InfaasSelError) as e:
+        sel.select(x, x, x, x, x)
+    assert e.value.status == -2
+    one = np.ones(2, np.int32); two = np.ones((2, 2), np.int32)
+    for bad in ("task_hi", "task_lo", "lat", "cost", "queue"):
+        t, l, c, qu = np.array([0, 1], np.int32), two.copy(), two.copy(), one.copy()
+        if bad == "task_hi": t[1] = 2
+        if bad == "task_lo": t[0] = -1
+        if bad == "lat": l[1, 1] = -1
+        if bad == "cost": c[0, 0] = -3
+        if bad == "queue": qu[1] = -1
+        with pytest.raises(lib.InfaasSelError) as e:
+            sel.load_variants(t, one, l, c, qu)
+        assert e.value.status == -3, bad
+    sel.load_variants(np.array([0, 1], np.int32), one, two, two, one)
+    sel.select(x, x, x, x, x)
+    torch.cuda.synchronize()
+    sel.destroy()
+    sel.destroy()
+
+
+# ------------------------------------------------------------------ full-size configurations
+
+def _sampled_parity(oracle_lib, tb, queue, q, got, sample, rng, label):
+    table = table_args(tb, queue)
+    check_invariants(table, query_args(q), got)
+    pick = rng.choice(q.N, size=min(sample, q.N), replace=False)
+    sub = tuple(np.ascontiguousarray(x[pick]) for x in query_args(q))
+    want = oracle_lib.select(*table, *sub)
+    bad = np.flatnonzero(got[pick] != want)
+    assert bad.size == 0, f"{label}: {bad.size} of {pick.size} sampled queries differ"
+
+
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
+def test_config2_full_size_sampled(oracle_lib, engine):
+    """16M queries, 50 tasks x 2,000 variants, Zipf task popularity -- the benchmark's launch
+    configuration.  Every answer is checked for feasibility; 150k sampled queries are
+    compared with the oracle."""
+    tb = workloads.make_table(2)
+    q = workloads.make_queries(2)
+    _say(f"config2 engine={engine}: N={q.N}")
+    sel = make_selector(tb, engine=engine)
+    got = gpu_select(sel, *query_args(q))
+    _sampled_parity(oracle_lib, tb, None, q, got, 150_000, np.random.default_rng(2), "config2")
+    sel.destroy()
+
+
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
+def test_config3_full_size_sampled(oracle_lib, engine):
+    """64M queries over 1,000 tasks with lognormal segment sizes and a bimodal objective."""
+    tb = workloads.make_table(3)
+    q = workloads.make_queries(3)
+    _say(f"config3 engine={engine}: N={q.N} V={tb.V}")
+    sel = make_selector(tb, engine=engine)
+    got = gpu_select(sel, *query_args(q))
+    _sampled_parity(oracle_lib, tb, None, q, got, 400_000, np.random.default_rng(3), "config3")
+    sel.destroy()
+
+
+def test_config3_low_limit_forces_wide_path(oracle_lib):
+    """Config 3's table with a 256-variant LDS limit: its large segments take the wide path."""
+    tb = workloads.make_table(3)
+    q = workloads.make_queries(3, n=2_000_000)
+    for engine in ENGINES:
+        sel = make_selector(tb, engine=engine, lds_segment_limit=256)
+        assert sel.info()["wide_segments"] > 10
+        got = gpu_select(sel, *query_args(q))
+        _sampled_parity(oracle_lib, tb, None, q, got, 300_000, np.random.default_rng(33), "config3-wide")
+        sel.destroy()
+
+
+def test_config4_streaming_sampled(oracle_lib):
+    """256M queries in 64 chunks of 4M; before every chunk after the first, 10% of the variants
+    get a new load.  Per chunk: feasibility of every answer and 20k sampled queries against the
+    oracle, whose copy of the load follows the same updates."""
+    import torch
+    tb = workloads.make_table(4)
+    spec = workloads.config_spec(4)
+    sel = make_selector(tb, engine=0)
+    queue = tb.queue_us.copy()
+    rng = np.random.default_rng(4)
+    per_chunk = spec["num_queries"] // spec["chunks"]
+    sel.reserve(per_chunk)
+    for chunk in range(spec["chunks"]):
+        if chunk > 0:
+            up = workloads.make_load_update(4, tb.V, chunk)
+            sel.update_load(to_dev(up.variant_idx), to_dev(up.queue_us))
+            oracle_lib.update_load(queue, up.variant_idx, up.queue_us)
+        q = workloads.make_queries(4, chunk=chunk)
+        assert q.N == per_chunk
+        if chunk % 8 == 0:
+            _say(f"config4 chunk {chunk}")
+        got = gpu_select(sel, *query_args(q))
+        _sampled_parity(oracle_lib, tb, queue, q, got, 20_000, rng, f"config4 chunk {chunk}")
+    assert np.array_equal(sel.read_load(tb.V), queue)
+    sel.destroy()
+
+
+def test_results_do_not_depend_on_run(oracle_lib):
+    """Two runs over the same input give the same bytes (bucket order is not deterministic,
+    the answers are)."""
+    tb = workloads.make_table(1)
+    q = workloads.make_queries(1, n=400_000)
+    for engine in ENGINES:
+        sel = make_selector(tb, engine=engine)
+        a = gpu_select(sel, *query_args(q))
+        b = gpu_select(sel, *query_args(q))
+        assert np.array_equal(a, b)
+        sel.destroy()

@@ -1,0 +1,57 @@
+"""The built C-ABI library loads and exports every function the header declares (CPU only;
+no compute call is made)."""
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "infaas_sel.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(infaas_sel_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_five_calls():
+    names = _declared()
+    for n in ("infaas_sel_create", "infaas_sel_load_variants", "infaas_sel_update_load",
+              "infaas_sel_select", "infaas_sel_destroy"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_1905_13348_amd as pkg
+    from paper_1905_13348_amd.binding import EXPORTED
+    if not os.path.exists(pkg.library_path()):
+        pytest.skip("library not built here (run __graft_entry__.build())")
+    lib = pkg.load_library()
+    declared = _declared()
+    assert sorted(EXPORTED) == declared
+    for n in declared:
+        assert hasattr(lib, n), n
+
+
+def test_status_text():
+    import paper_1905_13348_amd as pkg
+    if not os.path.exists(pkg.library_path()):
+        pytest.skip("library not built here")
+    lib = pkg.load_library()
+    assert lib.infaas_sel_strerror(0) == b"ok"
+    assert lib.infaas_sel_strerror(-2) == b"no variant table loaded"
+    # null handles are rejected without touching a device
+    assert lib.infaas_sel_select(None, 1, None, None, None, None, None, None) == -1
+    assert lib.infaas_sel_update_load(None, 1, None, None, None) == -1
+    lib.infaas_sel_destroy(None)
+
+
+def test_product_does_not_touch_the_oracle():
+    """The package and the C/HIP sources never import, include or name the oracle."""
+    pkg_dir = os.path.join(ROOT, "paper_1905_13348_amd")
+    for dirpath, _, files in os.walk(pkg_dir):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), os.path.join(dirpath, f)
+    assert "oracle" not in open(os.path.join(ROOT, "include", "infaas_sel.h")).read().lower()
