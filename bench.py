@@ -1,0 +1,164 @@
+"""Benchmark of the batched variant-selection path on one MI355X.
+
+One "step" is one call of infaas_sel_select over the whole query batch of the chosen
+configuration (default: configuration 2 -- 50 tasks x 2,000 variants, 16M queries with Zipf
+task popularity), inputs already resident in HBM.  For the streaming configuration (4) a step
+is one 4M-query chunk preceded by its load update (10% of the variants).
+
+Prints ONE JSON line: decisions/s, the roofline of the dominant kernel (algorithmic bytes:
+20 B per decision + the variant table once, against 8 TB/s of HBM) timed with HIP events on
+the launch stream, and the CPU oracle timed on a bounded sample of the same queries.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+BYTES_PER_DECISION = 20          # 4 int32 query fields read + 1 int32 result written
+UPDATE_BYTES = 8                 # one (row, value) pair of a load report
+
+
+def table_bytes(tb) -> int:
+    """Variant store read once per call: acc, queue, orig-free static columns (12 + 8B bytes/row)."""
+    return tb.V * (12 + 8 * tb.B)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, choices=[0, 1, 2, 3, 4])
+    ap.add_argument("--engine", default="auto", choices=["auto", "scan"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; queries would shard across GPUs with no "
+              "exchange step, but no multi-GPU path exists here. Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_1905_13348_amd as pkg
+    import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg = args.config
+    spec = workloads.config_spec(cfg)
+    tb = workloads.make_table(cfg)
+    chunks = spec["chunks"]
+    per_step = spec["num_queries"] // chunks
+    engine = pkg.ENGINE_AUTO if args.engine == "auto" else pkg.ENGINE_SCAN
+
+    sel = pkg.Selector(tb.num_tasks, tb.batch_sizes, device=0, engine=engine)
+    sel.load_variants(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us)
+    sel.reserve(per_step)
+
+    # inputs resident in HBM before the timed region.  The streaming configuration cycles over a
+    # few distinct chunks and load reports; the others reuse one batch.
+    n_sets = min(4, chunks)
+    host_q = [workloads.make_queries(cfg, chunk=c) for c in range(n_sets)]
+    dev_q = [[torch.from_numpy(x).cuda() for x in (q.task, q.slo_us, q.min_acc_bp, q.batch_idx)]
+             for q in host_q]
+    out = torch.empty(per_step, dtype=torch.int32, device="cuda")
+    updates = []
+    if chunks > 1:
+        for c in range(1, n_sets + 1):
+            up = workloads.make_load_update(cfg, tb.V, c)
+            updates.append((torch.from_numpy(up.variant_idx).cuda(), torch.from_numpy(up.queue_us).cuda(), up))
+
+    def step(i: int) -> None:
+        if updates:
+            u = updates[i % len(updates)]
+            sel.update_load(u[0], u[1])
+        sel.select(*dev_q[i % n_sets], out)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    sel.set_timing(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    timings = sel.get_timings()
+    sel.set_timing(False)
+    elapsed = t1 - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = per_step * args.steps / elapsed
+
+    # ---- roofline of the dominant kernel
+    active = {k: v for k, v in timings.items() if v["launches"] > 0}
+    dom = max(active, key=lambda k: active[k]["total_ms"])
+    dom_avg_ms = active[dom]["total_ms"] / active[dom]["launches"]
+    launches_per_step = active[dom]["launches"] / args.steps
+    algo_bytes = (BYTES_PER_DECISION * per_step + table_bytes(tb)) / launches_per_step
+    achieved = algo_bytes / (dom_avg_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                "avg_kernel_ms": round(dom_avg_ms, 5),
+                "algorithmic_bytes_per_launch": int(algo_bytes)}
+    whole_bytes = BYTES_PER_DECISION * per_step + table_bytes(tb) + \
+        (UPDATE_BYTES * updates[0][2].variant_idx.size if updates else 0)
+    whole_frac = whole_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
+
+    # ---- the last step's result, checked on a sample, and the oracle timed beside it
+    cpu = None
+    mismatches = None
+    if not args.no_cpu_baseline:
+        import oracle
+        ref = oracle.load_oracle()
+        last = (args.warmup + args.steps - 1)
+        q = host_q[last % n_sets]
+        queue = tb.queue_us.copy()
+        if updates:  # replay the load reports in the order the steps applied them
+            for i in range(args.warmup + args.steps):
+                up = updates[i % len(updates)][2]
+                ref.update_load(queue, up.variant_idx, up.queue_us)
+        fields = (q.task, q.slo_us, q.min_acc_bp, q.batch_idx)
+        n0 = min(per_step, 100_000)
+        s0 = time.perf_counter()
+        ref.select(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, queue, *(f[:n0] for f in fields))
+        rate0 = n0 / (time.perf_counter() - s0)
+        n = int(min(per_step, max(n0, rate0 * args.cpu_seconds)))
+        s0 = time.perf_counter()
+        want = ref.select(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, queue, *(f[:n] for f in fields))
+        dt = time.perf_counter() - s0
+        got = out[:n].cpu().numpy()
+        mismatches = int((got != want).sum())
+        cpu = {"value": round(n / dt, 1), "unit": "decisions/s", "cores": ref.num_threads(),
+               "kind": "oracle", "sample": f"first {n} queries of the last timed batch, {dt:.1f} s"}
+
+    line = {
+        "metric": "variant-selection decisions/sec on 1 MI355X; % of HBM roofline",
+        "value": round(value, 1), "unit": "decisions/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": f"config {cfg} ({spec['name']}): {tb.num_tasks} tasks, {tb.V} variants, "
+                               f"{tb.B} batch sizes, {per_step} queries per step"
+                               + (f", load report of {updates[0][2].variant_idx.size} rows before every step" if updates else ""),
+                   "engine": args.engine},
+        "roofline": roofline,
+        "whole_step_frac_of_hbm_roofline": round(whole_frac, 5),
+        "kernels_ms_per_step": {k: round(v["total_ms"] / args.steps, 5) for k, v in active.items()},
+        "cpu_baseline": cpu,
+        "parity_sample_mismatches": mismatches,
+        "index": {k: v for k, v in sel.info().items() if k.startswith("index")},
+    }
+    print(json.dumps(line))
+    sel.destroy()
+    return 0 if not mismatches else 1
+
+
+if __name__ == "__main__":
+    sys.exit(main())

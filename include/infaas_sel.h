@@ -180,6 +180,10 @@ int infaas_sel_get_info(infaas_sel_t *h, infaas_sel_info *out);
 /* Static text for a status code. */
 const char *infaas_sel_strerror(int status);
 
+/* Text of the HIP call that failed most recently on the calling thread (which call, HIP's
+ * message); empty if none has.  Valid until the next failure on that thread. */
+const char *infaas_sel_last_error(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -56,7 +56,7 @@ _lib: Optional[ctypes.CDLL] = None
 EXPORTED = ("infaas_sel_create", "infaas_sel_load_variants", "infaas_sel_update_load",
             "infaas_sel_select", "infaas_sel_destroy", "infaas_sel_reserve",
             "infaas_sel_read_load", "infaas_sel_set_timing", "infaas_sel_get_timings",
-            "infaas_sel_get_info", "infaas_sel_strerror")
+            "infaas_sel_get_info", "infaas_sel_strerror", "infaas_sel_last_error")
 
 
 def library_path() -> str:
@@ -71,6 +71,13 @@ def load_library() -> ctypes.CDLL:
     if not os.path.exists(_LIB_PATH):
         raise ImportError(f"{_LIB_PATH} is missing: build it with "
                           "`python -m paper_1905_13348_amd.build` (needs hipcc)")
+    # The process must hold ONE HIP runtime.  PyTorch ships its own copy (same soname as the
+    # system one); importing torch first makes the loader resolve this library's dependency to
+    # the copy torch already mapped, instead of mapping a second runtime beside it.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(_LIB_PATH)
     vp = ctypes.c_void_p
     lib.infaas_sel_create.argtypes = [ctypes.POINTER(_Config), ctypes.POINTER(vp)]
@@ -86,8 +93,10 @@ def load_library() -> ctypes.CDLL:
     lib.infaas_sel_get_info.argtypes = [vp, ctypes.POINTER(_Info)]
     lib.infaas_sel_strerror.argtypes = [ctypes.c_int]
     lib.infaas_sel_strerror.restype = ctypes.c_char_p
+    lib.infaas_sel_last_error.argtypes = []
+    lib.infaas_sel_last_error.restype = ctypes.c_char_p
     for name in EXPORTED:
-        if name not in ("infaas_sel_destroy", "infaas_sel_strerror"):
+        if name not in ("infaas_sel_destroy", "infaas_sel_strerror", "infaas_sel_last_error"):
             getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -95,7 +104,11 @@ def load_library() -> ctypes.CDLL:
 
 def _check(status: int) -> None:
     if status != 0:
-        raise InfaasSelError(status, load_library().infaas_sel_strerror(status).decode())
+        lib = load_library()
+        text = lib.infaas_sel_strerror(status).decode()
+        if status == -4:
+            text += " [" + lib.infaas_sel_last_error().decode() + "]"
+        raise InfaasSelError(status, text)
 
 
 def _host_i32(a) -> np.ndarray:

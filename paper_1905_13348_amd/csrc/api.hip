@@ -4,6 +4,7 @@
 #include "internal.h"
 
 #include <algorithm>
+#include <cstdio>
 #include <cstring>
 #include <new>
 #include <numeric>
@@ -13,13 +14,25 @@ using namespace infaas;
 
 namespace {
 
+thread_local char g_last_error[320] = "";
+
+// Records which HIP call failed and why; returns true when the call succeeded.
+bool hip_ok(hipError_t e, const char *what)
+{
+    if (e == hipSuccess) return true;
+    snprintf(g_last_error, sizeof(g_last_error), "%s: %s (%d)", what, hipGetErrorString(e), (int)e);
+    (void)hipGetLastError();
+    return false;
+}
+#define HIP_OK(call) hip_ok((call), #call)
+
 struct DeviceGuard {
     int prev = -1;
     bool ok = true;
     explicit DeviceGuard(int dev)
     {
-        if (hipGetDevice(&prev) != hipSuccess) { ok = false; return; }
-        if (prev != dev && hipSetDevice(dev) != hipSuccess) ok = false;
+        if (!HIP_OK(hipGetDevice(&prev))) { ok = false; return; }
+        if (prev != dev && !HIP_OK(hipSetDevice(dev))) ok = false;
         target = dev;
     }
     ~DeviceGuard()
@@ -135,7 +148,7 @@ int ensure_scratch(infaas_sel *h, int64_t capacity)
     const int32_t S = h->T * h->B;
     if (h->sc.recs && h->sc_capacity >= capacity && h->sc_slices == S) return INFAAS_SEL_OK;
     // growing: nothing enqueued earlier may still use the old buffers
-    if (hipDeviceSynchronize() != hipSuccess) return INFAAS_SEL_ERR_HIP;
+    if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
     int64_t cap = std::max<int64_t>(capacity, h->sc_capacity);
     h->free_scratch();
     ScanScratch sc{};
@@ -149,8 +162,8 @@ int ensure_scratch(infaas_sel *h, int64_t capacity)
         (void)hipGetLastError();
         return INFAAS_SEL_ERR_OOM;
     }
-    if (hipMemset(sc.cnt, 0, std::max<size_t>(S, 1) * 4) != hipSuccess ||
-        hipMemset(sc.counters, 0, 16) != hipSuccess) {
+    if (!HIP_OK(hipMemset(sc.cnt, 0, std::max<size_t>(S, 1) * 4)) ||
+        !HIP_OK(hipMemset(sc.counters, 0, 16))) {
         h->free_scratch();
         return INFAAS_SEL_ERR_HIP;
     }
@@ -165,38 +178,38 @@ int ensure_scratch(infaas_sel *h, int64_t capacity)
 int scan_pass(infaas_sel *h, const QueryView &q, hipStream_t st)
 {
     if (h->cnt_dirty) {  // an earlier call failed between histogram and plan
-        if (hipStreamSynchronize(st) != hipSuccess) return INFAAS_SEL_ERR_HIP;
-        if (hipMemset(h->sc.cnt, 0, (size_t)h->tv.S * 4) != hipSuccess) return INFAAS_SEL_ERR_HIP;
+        if (!HIP_OK(hipStreamSynchronize(st))) return INFAAS_SEL_ERR_HIP;
+        if (!HIP_OK(hipMemset(h->sc.cnt, 0, (size_t)h->tv.S * 4))) return INFAAS_SEL_ERR_HIP;
         h->cnt_dirty = false;
     }
     h->cnt_dirty = true;
     {
         LaunchTimer t(h, INFAAS_SEL_K_HISTOGRAM, st);
-        if (launch_histogram(h->tv, q, h->sc, st) != hipSuccess) return INFAAS_SEL_ERR_HIP;
+        if (!HIP_OK(launch_histogram(h->tv, q, h->sc, st))) return INFAAS_SEL_ERR_HIP;
     }
     {
         LaunchTimer t(h, INFAAS_SEL_K_PLAN, st);
-        if (launch_plan(h->tv, h->sc, st) != hipSuccess) return INFAAS_SEL_ERR_HIP;
+        if (!HIP_OK(launch_plan(h->tv, h->sc, st))) return INFAAS_SEL_ERR_HIP;
     }
     h->cnt_dirty = false;
     const bool wide = h->wide_segments > 0;
     {
         LaunchTimer t(h, INFAAS_SEL_K_SCATTER, st);
-        if (launch_scatter(h->tv, q, h->sc, wide, st) != hipSuccess) return INFAAS_SEL_ERR_HIP;
+        if (!HIP_OK(launch_scatter(h->tv, q, h->sc, wide, st))) return INFAAS_SEL_ERR_HIP;
     }
     if (h->max_lds_segment > 0) {
         LaunchTimer t(h, INFAAS_SEL_K_SCAN_LDS, st);
-        if (launch_scan_lds(h->tv, q, h->sc, h->max_lds_segment, h->num_cus, st) != hipSuccess)
+        if (!HIP_OK(launch_scan_lds(h->tv, q, h->sc, h->max_lds_segment, h->num_cus, st)))
             return INFAAS_SEL_ERR_HIP;
     }
     if (wide) {
         {
             LaunchTimer t(h, INFAAS_SEL_K_SCAN_WIDE, st);
-            if (launch_scan_wide(h->tv, q, h->sc, h->num_cus, st) != hipSuccess)
+            if (!HIP_OK(launch_scan_wide(h->tv, q, h->sc, h->num_cus, st)))
                 return INFAAS_SEL_ERR_HIP;
         }
         LaunchTimer t(h, INFAAS_SEL_K_FINISH_WIDE, st);
-        if (launch_finish_wide(h->tv, q, h->sc, st) != hipSuccess) return INFAAS_SEL_ERR_HIP;
+        if (!HIP_OK(launch_finish_wide(h->tv, q, h->sc, st))) return INFAAS_SEL_ERR_HIP;
     }
     return INFAAS_SEL_OK;
 }
@@ -206,6 +219,8 @@ constexpr int64_t kMaxPass = (int64_t)1 << 28;
 }  // namespace
 
 extern "C" {
+
+const char *infaas_sel_last_error(void) { return g_last_error; }
 
 const char *infaas_sel_strerror(int status)
 {
@@ -234,7 +249,7 @@ int infaas_sel_create(const infaas_sel_config *cfg, infaas_sel_t **out)
     if (lim < 64 || lim > 8192) return INFAAS_SEL_ERR_INVALID_ARG;
     lim &= ~63;
     int ndev = 0;
-    if (hipGetDeviceCount(&ndev) != hipSuccess) return INFAAS_SEL_ERR_HIP;
+    if (!HIP_OK(hipGetDeviceCount(&ndev))) return INFAAS_SEL_ERR_HIP;
     if (cfg->device < 0 || cfg->device >= ndev) return INFAAS_SEL_ERR_INVALID_ARG;
 
     infaas_sel *h = new (std::nothrow) infaas_sel();
@@ -246,7 +261,7 @@ int infaas_sel_create(const infaas_sel_config *cfg, infaas_sel_t **out)
     h->lds_limit = lim;
     if (cfg->batch_sizes) h->batch_sizes.assign(cfg->batch_sizes, cfg->batch_sizes + h->B);
     hipDeviceProp_t prop;
-    if (hipGetDeviceProperties(&prop, h->device) != hipSuccess) {
+    if (!HIP_OK(hipGetDeviceProperties(&prop, h->device))) {
         delete h;
         return INFAAS_SEL_ERR_HIP;
     }
@@ -330,7 +345,7 @@ int infaas_sel_load_variants(infaas_sel_t *h, int32_t V, const int32_t *task_id,
     // ---- upload
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
-    if (hipDeviceSynchronize() != hipSuccess) return INFAAS_SEL_ERR_HIP;
+    if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
     h->free_table();
     bool ok = dev_alloc(&h->d_acc, Vp) == hipSuccess && dev_alloc(&h->d_queue, Vp) == hipSuccess &&
               dev_alloc(&h->d_orig, Vp) == hipSuccess && dev_alloc(&h->d_lat, (size_t)B * Vp) == hipSuccess &&
@@ -344,7 +359,7 @@ int infaas_sel_load_variants(infaas_sel_t *h, int32_t V, const int32_t *task_id,
         return INFAAS_SEL_ERR_OOM;
     }
     auto up = [](void *d, const void *s, size_t bytes) {
-        return bytes == 0 || hipMemcpy(d, s, bytes, hipMemcpyHostToDevice) == hipSuccess;
+        return bytes == 0 || HIP_OK(hipMemcpy(d, s, bytes, hipMemcpyHostToDevice));
     };
     ok = up(h->d_acc, acc.data(), (size_t)Vp * 4) && up(h->d_queue, queue.data(), (size_t)Vp * 4) &&
          up(h->d_orig, orig.data(), (size_t)Vp * 4) && up(h->d_lat, lat.data(), (size_t)B * Vp * 4) &&
@@ -382,7 +397,7 @@ int infaas_sel_update_load(infaas_sel_t *h, int32_t n, const int32_t *d_variant_
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     hipStream_t st = (hipStream_t)hip_stream;
     LaunchTimer t(h, INFAAS_SEL_K_UPDATE, st);
-    if (launch_update_load(h->tv, n, d_variant_idx, d_queue_us, nullptr, st) != hipSuccess)
+    if (!HIP_OK(launch_update_load(h->tv, n, d_variant_idx, d_queue_us, nullptr, st)))
         return INFAAS_SEL_ERR_HIP;
     return INFAAS_SEL_OK;
 }
@@ -440,10 +455,10 @@ int infaas_sel_read_load(infaas_sel_t *h, int32_t *queue_us, void *hip_stream)
     if (!h->loaded) return INFAAS_SEL_ERR_NOT_LOADED;
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
-    if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return INFAAS_SEL_ERR_HIP;
+    if (!HIP_OK(hipStreamSynchronize((hipStream_t)hip_stream))) return INFAAS_SEL_ERR_HIP;
     std::vector<int32_t> q(h->Vp), slot(std::max(h->V, 1));
-    if (hipMemcpy(q.data(), h->d_queue, (size_t)h->Vp * 4, hipMemcpyDeviceToHost) != hipSuccess ||
-        hipMemcpy(slot.data(), h->d_slot_of, (size_t)std::max(h->V, 1) * 4, hipMemcpyDeviceToHost) != hipSuccess)
+    if (!HIP_OK(hipMemcpy(q.data(), h->d_queue, (size_t)h->Vp * 4, hipMemcpyDeviceToHost)) ||
+        !HIP_OK(hipMemcpy(slot.data(), h->d_slot_of, (size_t)std::max(h->V, 1) * 4, hipMemcpyDeviceToHost)))
         return INFAAS_SEL_ERR_HIP;
     for (int32_t v = 0; v < h->V; ++v) queue_us[v] = q[slot[v]];
     return INFAAS_SEL_OK;
