@@ -50,12 +50,17 @@ enum {
 
 /* infaas_sel_config.flags, bits 0-3: which search runs inside infaas_sel_select. */
 enum {
-    /* Default: the staircase index answers the queries it can decide; the few it cannot
-     * (slices whose index was truncated) are re-run by the scan. */
+    /* Default: the staircase index (per slice, the variants no cheaper variant dominates; a
+     * query is two binary searches and a bit-set intersection) when it fits in one compute
+     * unit's LDS, the exhaustive scan otherwise.  Queries the index cannot decide (its
+     * per-slice capacity was exceeded) are finished by a rank-ordered scan inside the same
+     * kernel, so results never depend on the engine. */
     INFAAS_SEL_ENGINE_AUTO = 0,
     /* Exhaustive scan only: queries bucketed by (task, batch) slice, slice staged in LDS,
      * feasibility filter and wavefront min-reduction over every variant of the slice. */
-    INFAAS_SEL_ENGINE_SCAN = 1
+    INFAAS_SEL_ENGINE_SCAN = 1,
+    /* Staircase index always, read from global memory when it does not fit in LDS. */
+    INFAAS_SEL_ENGINE_INDEX = 2
 };
 #define INFAAS_SEL_ENGINE_MASK 0xFu
 
@@ -169,9 +174,10 @@ typedef struct {
     int32_t lds_segment_limit;  /* effective value */
     int32_t wide_segments;      /* tasks handled by the device-wide scan path */
     int32_t index_in_lds;       /* 1 when the whole staircase index fits in one CU's LDS */
-    int32_t index_truncated;    /* slices whose staircase was cut at its capacity */
+    int32_t index_truncated;    /* slices whose staircase was cut at its capacity or not stored */
     int32_t index_max_steps;    /* longest staircase of any slice (as stored) */
     int64_t index_bytes;        /* size of the staircase index */
+    int64_t index_steps;        /* steps over all slices */
     int64_t table_bytes;        /* device bytes of the variant store */
     int64_t scratch_bytes;      /* device bytes of scratch currently reserved */
 } infaas_sel_info;

@@ -7,6 +7,7 @@ arguments.  PyTorch is used by callers for device memory and streams.
 from .binding import (  # noqa: F401
     ENGINE_AUTO,
     ENGINE_SCAN,
+    ENGINE_INDEX,
     KERNEL_NAMES,
     InfaasSelError,
     Selector,

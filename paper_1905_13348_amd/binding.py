@@ -17,6 +17,7 @@ _LIB_PATH = os.path.join(_PKG, "libinfaas_sel.so")
 
 ENGINE_AUTO = 0
 ENGINE_SCAN = 1
+ENGINE_INDEX = 2
 
 KERNEL_NAMES = ("update_load", "histogram", "plan", "scatter", "scan_lds", "scan_wide",
                 "finish_wide", "index_build", "index_select")
@@ -46,7 +47,8 @@ class _Info(ctypes.Structure):
                 ("max_segment", ctypes.c_int32), ("lds_segment_limit", ctypes.c_int32),
                 ("wide_segments", ctypes.c_int32), ("index_in_lds", ctypes.c_int32),
                 ("index_truncated", ctypes.c_int32), ("index_max_steps", ctypes.c_int32),
-                ("index_bytes", ctypes.c_int64), ("table_bytes", ctypes.c_int64),
+                ("index_bytes", ctypes.c_int64), ("index_steps", ctypes.c_int64),
+                ("table_bytes", ctypes.c_int64),
                 ("scratch_bytes", ctypes.c_int64)]
 
 

@@ -69,9 +69,19 @@ struct infaas_sel {
     int32_t *d_acc = nullptr, *d_queue = nullptr, *d_orig = nullptr, *d_lat = nullptr;
     uint32_t *d_rank = nullptr, *d_perm = nullptr;
     int32_t *d_seg_off = nullptr, *d_seg_len = nullptr, *d_slot_of = nullptr;
+    int32_t *d_acc_r = nullptr, *d_lat_r = nullptr, *d_orig_r = nullptr, *d_gpos = nullptr;
+    uint32_t *d_tot_r = nullptr;
     int64_t table_bytes = 0;
     int32_t max_segment = 0, max_lds_segment = 0, wide_segments = 0;
     TableView tv{};
+
+    // staircase index
+    IndexView ix{};
+    bool have_index = false;
+    uint32_t index_lds_bytes = 0;     // dynamic LDS of the lookup kernel; 0 = read the index from global memory
+    uint32_t ix_stats[8] = {0};       // copy of ix.ctrl taken after the build at load time
+    int32_t *d_defer = nullptr;
+    int64_t defer_capacity = 0;
 
     // scan scratch
     ScanScratch sc{};
@@ -91,16 +101,31 @@ struct infaas_sel {
         (void)hipFree(d_acc); (void)hipFree(d_queue); (void)hipFree(d_orig); (void)hipFree(d_lat);
         (void)hipFree(d_rank); (void)hipFree(d_perm); (void)hipFree(d_seg_off);
         (void)hipFree(d_seg_len); (void)hipFree(d_slot_of);
+        (void)hipFree(d_acc_r); (void)hipFree(d_lat_r); (void)hipFree(d_orig_r); (void)hipFree(d_gpos);
+        (void)hipFree(d_tot_r);
         d_acc = d_queue = d_orig = d_lat = d_seg_off = d_seg_len = d_slot_of = nullptr;
+        d_acc_r = d_lat_r = d_orig_r = d_gpos = nullptr;
+        d_tot_r = nullptr;
         d_rank = d_perm = nullptr;
         loaded = false;
         table_bytes = 0;
+        free_index();
+    }
+    void free_index()
+    {
+        (void)hipFree(ix.hdr); (void)hipFree(ix.pool); (void)hipFree(ix.step_row); (void)hipFree(ix.ctrl);
+        ix = IndexView{};
+        have_index = false;
+        index_lds_bytes = 0;
     }
     void free_scratch()
     {
         (void)hipFree(sc.cnt); (void)hipFree(sc.bucket_off); (void)hipFree(sc.cursor);
         (void)hipFree(sc.tile_off); (void)hipFree(sc.wide_off); (void)hipFree(sc.counters);
         (void)hipFree(sc.recs); (void)hipFree(sc.best);
+        (void)hipFree(d_defer);
+        d_defer = nullptr;
+        defer_capacity = 0;
         sc = ScanScratch{};
         sc_capacity = 0;
         sc_slices = 0;
@@ -174,6 +199,72 @@ int ensure_scratch(infaas_sel *h, int64_t capacity)
     return INFAAS_SEL_OK;
 }
 
+constexpr uint32_t kLdsMax = 160 * 1024 - 256;  // dynamic LDS the lookup kernel may ask for
+
+// Allocate the staircase index for the loaded table, build it and read its sizes back.
+int create_index(infaas_sel *h)
+{
+    const int64_t S = (int64_t)h->T * h->B;
+    const uint32_t worst = BodyLayout(kIndexCap, true).size;
+    IndexView ix{};
+    ix.pool_bytes = (uint32_t)std::min<int64_t>(kDummyBodyBytes + S * worst, (int64_t)1 << 30);
+    ix.step_cap = (uint32_t)std::min<int64_t>(1 + S * kIndexCap, (int64_t)1 << 28);
+    bool ok = dev_alloc(&ix.hdr, (size_t)S) == hipSuccess && dev_alloc(&ix.pool, ix.pool_bytes) == hipSuccess &&
+              dev_alloc(&ix.step_row, ix.step_cap) == hipSuccess && dev_alloc(&ix.ctrl, 8) == hipSuccess;
+    h->ix = ix;
+    if (!ok) {
+        h->free_index();
+        (void)hipGetLastError();
+        return INFAAS_SEL_ERR_OOM;
+    }
+    // dummy body of a slice without steps (sentinels only) at offset 0; step_row[0] is never an answer
+    uint8_t dummy[kDummyBodyBytes] = {0};
+    dummy[4] = dummy[5] = dummy[6] = dummy[7] = 0xFF;
+    const int32_t none = -1;
+    const uint32_t ctrl0[8] = {kDummyBodyBytes, 1u, 1u, 0u, 0u, 0u, 0u, 0u};
+    if (!HIP_OK(hipMemcpy(ix.pool, dummy, sizeof(dummy), hipMemcpyHostToDevice)) ||
+        !HIP_OK(hipMemcpy(ix.step_row, &none, 4, hipMemcpyHostToDevice)) ||
+        !HIP_OK(hipMemcpy(ix.ctrl, ctrl0, sizeof(ctrl0), hipMemcpyHostToDevice)) ||
+        !HIP_OK(launch_index_build(h->tv, ix, nullptr)) || !HIP_OK(hipDeviceSynchronize()) ||
+        !HIP_OK(hipMemcpy(h->ix_stats, ix.ctrl, sizeof(ctrl0), hipMemcpyDeviceToHost))) {
+        h->free_index();
+        return INFAAS_SEL_ERR_HIP;
+    }
+    h->have_index = true;
+    const int64_t need = S * 16 + h->ix_stats[0];
+    h->index_lds_bytes = need <= kLdsMax ? kLdsMax : 0u;
+    return INFAAS_SEL_OK;
+}
+
+// One pass of the index engine over n <= 2^28 queries.
+int index_pass(infaas_sel *h, const QueryView &q, hipStream_t st)
+{
+    const int64_t need = (int64_t)q.n + (int64_t)(index_select_blocks(h->num_cus) + 2) * kIndexTile;
+    if (h->defer_capacity < need) {
+        if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
+        (void)hipFree(h->d_defer);
+        h->d_defer = nullptr;
+        h->defer_capacity = 0;
+        if (dev_alloc(&h->d_defer, (size_t)need) != hipSuccess) {
+            (void)hipGetLastError();
+            return INFAAS_SEL_ERR_OOM;
+        }
+        h->defer_capacity = need;
+    }
+    LaunchTimer t(h, INFAAS_SEL_K_INDEX_SELECT, st);
+    if (!HIP_OK(launch_index_select(h->tv, h->ix, q, h->d_defer, h->index_lds_bytes, h->num_cus, st)))
+        return INFAAS_SEL_ERR_HIP;
+    return INFAAS_SEL_OK;
+}
+
+bool use_index(const infaas_sel *h)
+{
+    const uint32_t engine = h->flags & INFAAS_SEL_ENGINE_MASK;
+    if (!h->have_index || engine == INFAAS_SEL_ENGINE_SCAN) return false;
+    if (engine == INFAAS_SEL_ENGINE_INDEX) return true;
+    return h->index_lds_bytes > 0;  // auto: the index when it fits in LDS, the scan otherwise
+}
+
 // One pass of the scan engine over n <= 2^28 queries.
 int scan_pass(infaas_sel *h, const QueryView &q, hipStream_t st)
 {
@@ -243,7 +334,7 @@ int infaas_sel_create(const infaas_sel_config *cfg, infaas_sel_t **out)
     if ((int64_t)cfg->num_tasks * cfg->num_batch_sizes > ((int64_t)1 << 24))
         return INFAAS_SEL_ERR_INVALID_ARG;
     uint32_t engine = cfg->flags & INFAAS_SEL_ENGINE_MASK;
-    if ((cfg->flags & ~INFAAS_SEL_ENGINE_MASK) != 0 || engine > INFAAS_SEL_ENGINE_SCAN)
+    if ((cfg->flags & ~INFAAS_SEL_ENGINE_MASK) != 0 || engine > INFAAS_SEL_ENGINE_INDEX)
         return INFAAS_SEL_ERR_INVALID_ARG;
     int32_t lim = cfg->lds_segment_limit == 0 ? 4096 : cfg->lds_segment_limit;
     if (lim < 64 || lim > 8192) return INFAAS_SEL_ERR_INVALID_ARG;
@@ -305,6 +396,9 @@ int infaas_sel_load_variants(infaas_sel_t *h, int32_t V, const int32_t *task_id,
     std::vector<int32_t> acc(Vp, INT32_MIN), queue(Vp, INT32_MAX), orig(Vp, -1), slot_of(std::max(V, 1), 0);
     std::vector<int32_t> lat((size_t)B * Vp, INT32_MAX);
     std::vector<uint32_t> rank((size_t)B * Vp, kNoRank), perm((size_t)B * Vp, 0u);
+    std::vector<int32_t> acc_r((size_t)B * Vp, INT32_MIN), lat_r((size_t)B * Vp, 0), orig_r((size_t)B * Vp, -1);
+    std::vector<int32_t> gpos((size_t)B * Vp, 0);
+    std::vector<uint32_t> tot_r((size_t)B * Vp, 0xFFFFFFFFu);
     {
         std::vector<int32_t> fill(T, 0);
         for (int64_t v = 0; v < V; ++v) {
@@ -335,8 +429,14 @@ int infaas_sel_load_variants(infaas_sel_t *h, int32_t V, const int32_t *task_id,
                     return vx < vy;
                 });
                 for (int32_t r = 0; r < L; ++r) {
-                    perm[(size_t)b * Vp + seg + r] = (uint32_t)ord[r];
-                    rank[(size_t)b * Vp + seg + ord[r]] = (uint32_t)r;
+                    const size_t g = (size_t)b * Vp + seg + r, sl = (size_t)b * Vp + seg + ord[r];
+                    perm[g] = (uint32_t)ord[r];
+                    rank[sl] = (uint32_t)r;
+                    acc_r[g] = acc[seg + ord[r]];
+                    lat_r[g] = lat[sl];
+                    tot_r[g] = (uint32_t)lat[sl] + (uint32_t)queue[seg + ord[r]];
+                    orig_r[g] = orig[seg + ord[r]];
+                    gpos[sl] = seg + r;
                 }
             }
         }
@@ -352,7 +452,10 @@ int infaas_sel_load_variants(infaas_sel_t *h, int32_t V, const int32_t *task_id,
               dev_alloc(&h->d_rank, (size_t)B * Vp) == hipSuccess &&
               dev_alloc(&h->d_perm, (size_t)B * Vp) == hipSuccess &&
               dev_alloc(&h->d_seg_off, (size_t)T + 1) == hipSuccess && dev_alloc(&h->d_seg_len, T) == hipSuccess &&
-              dev_alloc(&h->d_slot_of, std::max(V, 1)) == hipSuccess;
+              dev_alloc(&h->d_slot_of, std::max(V, 1)) == hipSuccess &&
+              dev_alloc(&h->d_acc_r, (size_t)B * Vp) == hipSuccess && dev_alloc(&h->d_lat_r, (size_t)B * Vp) == hipSuccess &&
+              dev_alloc(&h->d_orig_r, (size_t)B * Vp) == hipSuccess && dev_alloc(&h->d_gpos, (size_t)B * Vp) == hipSuccess &&
+              dev_alloc(&h->d_tot_r, (size_t)B * Vp) == hipSuccess;
     if (!ok) {
         h->free_table();
         (void)hipGetLastError();
@@ -365,7 +468,10 @@ int infaas_sel_load_variants(infaas_sel_t *h, int32_t V, const int32_t *task_id,
          up(h->d_orig, orig.data(), (size_t)Vp * 4) && up(h->d_lat, lat.data(), (size_t)B * Vp * 4) &&
          up(h->d_rank, rank.data(), (size_t)B * Vp * 4) && up(h->d_perm, perm.data(), (size_t)B * Vp * 4) &&
          up(h->d_seg_off, seg_off.data(), ((size_t)T + 1) * 4) && up(h->d_seg_len, seg_len.data(), (size_t)T * 4) &&
-         up(h->d_slot_of, slot_of.data(), (size_t)std::max(V, 1) * 4);
+         up(h->d_slot_of, slot_of.data(), (size_t)std::max(V, 1) * 4) &&
+         up(h->d_acc_r, acc_r.data(), (size_t)B * Vp * 4) && up(h->d_lat_r, lat_r.data(), (size_t)B * Vp * 4) &&
+         up(h->d_orig_r, orig_r.data(), (size_t)B * Vp * 4) && up(h->d_gpos, gpos.data(), (size_t)B * Vp * 4) &&
+         up(h->d_tot_r, tot_r.data(), (size_t)B * Vp * 4);
     if (!ok) {
         h->free_table();
         return INFAAS_SEL_ERR_HIP;
@@ -375,14 +481,23 @@ int infaas_sel_load_variants(infaas_sel_t *h, int32_t V, const int32_t *task_id,
     h->max_segment = max_seg;
     h->max_lds_segment = max_lds_seg;
     h->wide_segments = wide;
-    h->table_bytes = (int64_t)Vp * 4 * (3 + 3 * (int64_t)B) + ((int64_t)2 * T + 1 + std::max(V, 1)) * 4;
+    h->table_bytes = (int64_t)Vp * 4 * (3 + 8 * (int64_t)B) + ((int64_t)2 * T + 1 + std::max(V, 1)) * 4;
     TableView tv{};
     tv.T = T; tv.B = B; tv.S = T * B; tv.V = V; tv.Vp = Vp; tv.lds_limit = h->lds_limit;
     tv.acc = h->d_acc; tv.queue = h->d_queue; tv.orig = h->d_orig; tv.lat = h->d_lat;
     tv.rank = h->d_rank; tv.perm = h->d_perm; tv.seg_off = h->d_seg_off; tv.seg_len = h->d_seg_len;
     tv.slot_of = h->d_slot_of;
+    tv.acc_r = h->d_acc_r; tv.tot_r = h->d_tot_r; tv.lat_r = h->d_lat_r; tv.orig_r = h->d_orig_r;
+    tv.gpos = h->d_gpos;
     h->tv = tv;
     h->loaded = true;
+    if ((h->flags & INFAAS_SEL_ENGINE_MASK) != INFAAS_SEL_ENGINE_SCAN) {
+        int rc = create_index(h);
+        if (rc != INFAAS_SEL_OK) {
+            h->free_table();
+            return rc;
+        }
+    }
     return INFAAS_SEL_OK;
 }
 
@@ -396,9 +511,16 @@ int infaas_sel_update_load(infaas_sel_t *h, int32_t n, const int32_t *d_variant_
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     hipStream_t st = (hipStream_t)hip_stream;
-    LaunchTimer t(h, INFAAS_SEL_K_UPDATE, st);
-    if (!HIP_OK(launch_update_load(h->tv, n, d_variant_idx, d_queue_us, nullptr, st)))
-        return INFAAS_SEL_ERR_HIP;
+    {
+        LaunchTimer t(h, INFAAS_SEL_K_UPDATE, st);
+        if (!HIP_OK(launch_update_load(h->tv, n, d_variant_idx, d_queue_us,
+                                       h->have_index ? h->ix.ctrl : nullptr, st)))
+            return INFAAS_SEL_ERR_HIP;
+    }
+    if (h->have_index) {  // the steps depend on the load: rebuild them behind the update
+        LaunchTimer t(h, INFAAS_SEL_K_INDEX_BUILD, st);
+        if (!HIP_OK(launch_index_build(h->tv, h->ix, st))) return INFAAS_SEL_ERR_HIP;
+    }
     return INFAAS_SEL_OK;
 }
 
@@ -414,14 +536,15 @@ int infaas_sel_select(infaas_sel_t *h, int64_t N, const int32_t *d_task, const i
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     hipStream_t st = (hipStream_t)hip_stream;
-    int rc = ensure_scratch(h, std::min(N, kMaxPass));
+    const bool idx = use_index(h);
+    int rc = idx ? INFAAS_SEL_OK : ensure_scratch(h, std::min(N, kMaxPass));
     if (rc != INFAAS_SEL_OK) return rc;
     for (int64_t done = 0; done < N; done += kMaxPass) {
         QueryView q{};
         q.n = (int32_t)std::min(kMaxPass, N - done);
         q.task = d_task + done; q.slo = d_slo_us + done; q.min_acc = d_min_acc_bp + done;
         q.bidx = d_batch_idx + done; q.out = d_out_variant + done;
-        rc = scan_pass(h, q, st);
+        rc = idx ? index_pass(h, q, st) : scan_pass(h, q, st);
         if (rc != INFAAS_SEL_OK) return rc;
     }
     return INFAAS_SEL_OK;
@@ -446,7 +569,22 @@ int infaas_sel_reserve(infaas_sel_t *h, int64_t max_queries)
     if (!h || max_queries < 0) return INFAAS_SEL_ERR_INVALID_ARG;
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
-    return ensure_scratch(h, std::max<int64_t>(1, std::min(max_queries, kMaxPass)));
+    const int64_t cap = std::max<int64_t>(1, std::min(max_queries, kMaxPass));
+    if (h->loaded && use_index(h)) {
+        const int64_t need = cap + (int64_t)(index_select_blocks(h->num_cus) + 2) * kIndexTile;
+        if (h->defer_capacity >= need) return INFAAS_SEL_OK;
+        if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
+        (void)hipFree(h->d_defer);
+        h->d_defer = nullptr;
+        h->defer_capacity = 0;
+        if (dev_alloc(&h->d_defer, (size_t)need) != hipSuccess) {
+            (void)hipGetLastError();
+            return INFAAS_SEL_ERR_OOM;
+        }
+        h->defer_capacity = need;
+        return INFAAS_SEL_OK;
+    }
+    return ensure_scratch(h, cap);
 }
 
 int infaas_sel_read_load(infaas_sel_t *h, int32_t *queue_us, void *hip_stream)
@@ -511,7 +649,14 @@ int infaas_sel_get_info(infaas_sel_t *h, infaas_sel_info *out)
     out->lds_segment_limit = h->lds_limit;
     out->wide_segments = h->wide_segments;
     out->table_bytes = h->table_bytes;
-    out->scratch_bytes = h->scratch_bytes;
+    out->scratch_bytes = h->scratch_bytes + h->defer_capacity * 4;
+    if (h->have_index) {
+        out->index_in_lds = h->index_lds_bytes > 0 ? 1 : 0;
+        out->index_truncated = (int32_t)(h->ix_stats[3] + h->ix_stats[4]);
+        out->index_max_steps = (int32_t)h->ix_stats[2];
+        out->index_bytes = (int64_t)h->ix_stats[0] + (int64_t)h->T * h->B * 16 + (int64_t)h->ix_stats[1] * 4;
+        out->index_steps = (int64_t)h->ix_stats[5];
+    }
     return INFAAS_SEL_OK;
 }
 

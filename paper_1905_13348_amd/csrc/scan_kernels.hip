@@ -71,29 +71,34 @@ __device__ __forceinline__ int32_t wave_incl_scan(int32_t v)
 
 // ---------------------------------------------------------------- load update
 
+// One thread per (update, batch size): the queue itself, and latency-plus-queue of the variant's
+// entry in each rank-ordered column.  Thread 0 also rewinds the index allocator, because the
+// index is rebuilt after every load report.
 __global__ __launch_bounds__(256) void k_update_load(TableView tv, int32_t n,
                                                      const int32_t *__restrict__ idx,
                                                      const int32_t *__restrict__ val,
-                                                     uint32_t *__restrict__ dirty_tasks)
+                                                     uint32_t *__restrict__ index_ctrl)
 {
-    int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n)
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (tid == 0 && index_ctrl) {
+        index_ctrl[0] = kDummyBodyBytes;
+        index_ctrl[1] = 1;
+        index_ctrl[2] = 1;
+        index_ctrl[3] = 0;
+        index_ctrl[4] = 0;
+        index_ctrl[5] = 0;
+    }
+    if (tid >= (int64_t)n * tv.B)
         return;
-    int32_t v = idx[i];
-    int32_t x = val[i];
+    const int32_t i = (int32_t)(tid / tv.B), b = (int32_t)(tid - (int64_t)i * tv.B);
+    const int32_t v = idx[i];
+    const int32_t x = val[i];
     if ((uint32_t)v >= (uint32_t)tv.V || x < 0)
         return;
-    int32_t slot = tv.slot_of[v];
-    tv.queue[slot] = x;
-    if (dirty_tasks) {
-        // find the task of the slot: seg_off is sorted, T+1 entries
-        int32_t lo = 0, hi = tv.T;
-        while (hi - lo > 1) {
-            int32_t mid = (lo + hi) >> 1;
-            if (tv.seg_off[mid] <= slot) lo = mid; else hi = mid;
-        }
-        dirty_tasks[lo] = 1u;
-    }
+    const int32_t slot = tv.slot_of[v];
+    if (b == 0) tv.queue[slot] = x;
+    const int64_t g = (int64_t)b * tv.Vp + tv.gpos[(int64_t)b * tv.Vp + slot];
+    tv.tot_r[g] = (uint32_t)tv.lat_r[g] + (uint32_t)x;
 }
 
 // ---------------------------------------------------------------- bucketing
@@ -382,10 +387,11 @@ __global__ __launch_bounds__(256) void k_finish_wide(TableView tv, QueryView q, 
 // ---------------------------------------------------------------- launchers
 
 hipError_t launch_update_load(const TableView &tv, int32_t n, const int32_t *idx,
-                              const int32_t *val, uint32_t *dirty_tasks, hipStream_t st)
+                              const int32_t *val, uint32_t *index_ctrl, hipStream_t st)
 {
     if (n <= 0) return hipSuccess;
-    k_update_load<<<(n + 255) / 256, 256, 0, st>>>(tv, n, idx, val, dirty_tasks);
+    const int64_t threads = (int64_t)n * tv.B;
+    k_update_load<<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(tv, n, idx, val, index_ctrl);
     return hipGetLastError();
 }
 

@@ -13,8 +13,8 @@ from pins import check_invariants
 
 pytestmark = pytest.mark.gpu
 
-ENGINES = [0, 1]  # auto (index + scan fall-back), scan only
-ENGINE_IDS = ["auto", "scan"]
+ENGINES = [0, 1, 2]  # auto (index if it fits in LDS, else scan), scan only, index always
+ENGINE_IDS = ["auto", "scan", "index"]
 I32MAX = 2**31 - 1
 
 
@@ -80,7 +80,7 @@ def test_config0_tiny_exact(oracle_lib, engine):
 def test_config1_medium_exact(oracle_lib, engine):
     """Config 1 at its full 1M queries: 200-variant segments, several tiles and a ragged tail."""
     tb = workloads.make_table(1)
-    q = workloads.make_queries(1, n=1_000_003 if engine == 0 else 300_007)
+    q = workloads.make_queries(1, n=1_000_003 if engine != 1 else 300_007)
     _compare(oracle_lib, tb, query_args(q), engine, label="config1")
 
 
