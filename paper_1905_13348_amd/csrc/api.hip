@@ -209,7 +209,7 @@ int create_index(infaas_sel *h)
     IndexView ix{};
     ix.pool_bytes = (uint32_t)std::min<int64_t>(kDummyBodyBytes + S * worst, (int64_t)1 << 30);
     ix.step_cap = (uint32_t)std::min<int64_t>(1 + S * kIndexCap, (int64_t)1 << 28);
-    bool ok = dev_alloc(&ix.hdr, (size_t)S) == hipSuccess && dev_alloc(&ix.pool, ix.pool_bytes) == hipSuccess &&
+    bool ok = dev_alloc(&ix.hdr, (size_t)S * 2) == hipSuccess && dev_alloc(&ix.pool, ix.pool_bytes) == hipSuccess &&
               dev_alloc(&ix.step_row, ix.step_cap) == hipSuccess && dev_alloc(&ix.ctrl, 8) == hipSuccess;
     h->ix = ix;
     if (!ok) {
@@ -231,7 +231,7 @@ int create_index(infaas_sel *h)
         return INFAAS_SEL_ERR_HIP;
     }
     h->have_index = true;
-    const int64_t need = S * 16 + h->ix_stats[0];
+    const int64_t need = kLdsCtrlBytes + S * kHdrBytes + h->ix_stats[0];
     h->index_lds_bytes = need <= kLdsMax ? kLdsMax : 0u;
     return INFAAS_SEL_OK;
 }
@@ -654,7 +654,7 @@ int infaas_sel_get_info(infaas_sel_t *h, infaas_sel_info *out)
         out->index_in_lds = h->index_lds_bytes > 0 ? 1 : 0;
         out->index_truncated = (int32_t)(h->ix_stats[3] + h->ix_stats[4]);
         out->index_max_steps = (int32_t)h->ix_stats[2];
-        out->index_bytes = (int64_t)h->ix_stats[0] + (int64_t)h->T * h->B * 16 + (int64_t)h->ix_stats[1] * 4;
+        out->index_bytes = (int64_t)h->ix_stats[0] + (int64_t)h->T * h->B * kHdrBytes + (int64_t)h->ix_stats[1] * 4;
         out->index_steps = (int64_t)h->ix_stats[5];
     }
     return INFAAS_SEL_OK;

@@ -20,6 +20,7 @@ namespace infaas {
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
 constexpr int kSelThreads = 1024;
 constexpr int kPerThread = 4;
@@ -40,8 +41,12 @@ __global__ __launch_bounds__(64) void k_index_build(TableView tv, IndexView ix)
     const int lane = threadIdx.x;
     const int32_t t = s / tv.B, b = s - t * tv.B;
     const int32_t seg = tv.seg_off[t], L = tv.seg_len[t];
-    if (L == 0) {  // no variants: the K = 0 dummy body answers "nothing feasible"
-        if (lane == 0) ix.hdr[s] = make_uint4(0u, kHdrIndexed, 0u, 0u);
+    const BodyLayout empty(0, false);
+    if (L == 0) {  // no variants: the K = 0 dummy body at offset 0 answers "nothing feasible"
+        if (lane == 0) {
+            ix.hdr[2 * s] = make_uint4(0u - 2u, empty.o_tot - 4u, empty.o_ea - 4u, empty.o_es - 4u);
+            ix.hdr[2 * s + 1] = make_uint4(1u | kHdrIndexed, 0u, 0u, empty.size);
+        }
         return;
     }
     const int32_t *__restrict__ accc = tv.acc_r + (int64_t)b * tv.Vp + seg;
@@ -100,7 +105,8 @@ __global__ __launch_bounds__(64) void k_index_build(TableView tv, IndexView ix)
                       (int64_t)hi - (int64_t)lo <= 65533;
     if (!fits) {  // no body: every query of this slice goes to the rank-ordered scan
         if (lane == 0) {
-            ix.hdr[s] = make_uint4(0u, kHdrTrunc, 0u, 0u);
+            ix.hdr[2 * s] = make_uint4(0u - 2u, empty.o_tot - 4u, empty.o_ea - 4u, empty.o_es - 4u);
+            ix.hdr[2 * s + 1] = make_uint4(1u | kHdrPark | kHdrTrunc, 0u, 0u, 0u);
             atomicAdd(&ix.ctrl[4], 1u);
         }
         return;
@@ -140,8 +146,10 @@ __global__ __launch_bounds__(64) void k_index_build(TableView tv, IndexView ix)
         }
     }
     if (lane == 0) {
-        ix.hdr[s] = make_uint4(off, (uint32_t)K | (wide ? kHdrWide : 0u) | (trunc ? kHdrTrunc : 0u) | kHdrIndexed,
-                               (uint32_t)lo, rec);
+        const uint32_t esz = wide ? 8u : 4u;
+        ix.hdr[2 * s] = make_uint4(off - 2u, off + lay.o_tot - 4u, off + lay.o_ea - esz, off + lay.o_es - esz);
+        ix.hdr[2 * s + 1] = make_uint4((uint32_t)(K + 1) | (wide ? kHdrWide : 0u) | (trunc ? kHdrTrunc : 0u) | kHdrIndexed,
+                                       (uint32_t)lo, rec, off + lay.size);
         atomicMax(&ix.ctrl[2], (uint32_t)K);
         if (trunc) atomicAdd(&ix.ctrl[3], 1u);
         atomicAdd(&ix.ctrl[5], (uint32_t)K);
@@ -150,92 +158,101 @@ __global__ __launch_bounds__(64) void k_index_build(TableView tv, IndexView ix)
 
 // ---------------------------------------------------------------- lookup
 
+#define INFAAS_LDS __attribute__((address_space(3)))
+
+// Readers of index memory by 32-bit byte address: an LDS address, or an offset from a global base.
 struct LdsMem {
-    const uint32_t *w;
-    __device__ __forceinline__ uint32_t ld32(uint32_t off) const { return w[off >> 2]; }
-    __device__ __forceinline__ uint32_t ld16(uint32_t off) const { return ((const uint16_t *)w)[off >> 1]; }
-    __device__ __forceinline__ uint32_t ld8(uint32_t off) const { return ((const uint8_t *)w)[off]; }
+    __device__ __forceinline__ uint32_t ld32(uint32_t a) const { return *(const INFAAS_LDS uint32_t *)a; }
+    __device__ __forceinline__ uint32_t ld16(uint32_t a) const { return *(const INFAAS_LDS uint16_t *)a; }
+    __device__ __forceinline__ uint32_t ld8(uint32_t a) const { return *(const INFAAS_LDS uint8_t *)a; }
+    __device__ __forceinline__ v4u ld128(uint32_t a) const { return *(const INFAAS_LDS v4u *)a; }
 };
 struct GlobalMem {
     const uint8_t *p;
-    __device__ __forceinline__ uint32_t ld32(uint32_t off) const { return *(const uint32_t *)(p + off); }
-    __device__ __forceinline__ uint32_t ld16(uint32_t off) const { return *(const uint16_t *)(p + off); }
-    __device__ __forceinline__ uint32_t ld8(uint32_t off) const { return p[off]; }
+    __device__ __forceinline__ uint32_t ld32(uint32_t a) const { return *(const uint32_t *)(p + a); }
+    __device__ __forceinline__ uint32_t ld16(uint32_t a) const { return *(const uint16_t *)(p + a); }
+    __device__ __forceinline__ uint32_t ld8(uint32_t a) const { return p[a]; }
+    __device__ __forceinline__ v4u ld128(uint32_t a) const { return *(const v4u *)(p + a); }
 };
 
-// Bit set of the steps that satisfy (min_acc, slo) in the body at byte offset `body`.
-// Branch-free; every read stays inside the body plus its slack.  `nit` = search iterations,
-// enough for the largest K of the whole index.
-template <class Mem>
-__device__ __forceinline__ uint64_t lookup_mask(const Mem &mem, uint32_t body, uint32_t K,
-                                                bool wide, int32_t base, int32_t min_acc,
-                                                uint32_t slo, int nit)
+// kN queries of one lane against the index, interleaved so that their dependent reads overlap.
+// Branch-free apart from wave-uniform conditions; every read stays inside a body plus its slack
+// (slices that cannot be used point at the empty dummy body).
+//   bodies : memory that the header's addresses refer to
+//   hdrs   : memory holding the slice headers, hdr0 = address of header 0
+//   nit    : binary-search iterations that cover the largest K of the whole index
+// Header of a slice: h0 = {acc keys - 2, tot keys - 4, ea - one entry, es - one entry},
+//                    h1 = {K + 1 | flags, acc base, first entry in step_row, body end}.
+// Outputs ans (row or -1) and park (query must be finished by the slow path).
+template <int kN, class Mem, class HMem>
+__device__ __forceinline__ void decide_n(const TableView &tv, const int32_t *__restrict__ step_row,
+                                         const Mem &bodies, const HMem &hdrs, uint32_t hdr0, int nit,
+                                         const int32_t (&task)[kN], const int32_t (&slo)[kN],
+                                         const int32_t (&min_acc)[kN], const int32_t (&bidx)[kN],
+                                         int32_t (&ans)[kN], bool (&park)[kN])
 {
-    const BodyLayout lay(K, wide);
-    const uint32_t k1 = K + 1;
-    // accuracy: keys are acc - base + 1 (>= 1), descending; count those >= dd
-    uint32_t dd = (uint32_t)min_acc - (uint32_t)base;
-    dd = dd < 65535u ? dd : 65535u;
-    dd = min_acc > base ? dd + 1u : 1u;
-    uint32_t p = 0, ps = 0;
-    for (int it = nit - 1; it >= 0; --it) {
-        const uint32_t st = 1u << it;
-        uint32_t pr = p + st, qr = ps + st;
-        uint32_t ia = pr < k1 ? pr : k1, is = qr < k1 ? qr : k1;
-        const uint32_t ka = mem.ld16(body + 2 * ia - 2);
-        const uint32_t ks = mem.ld32(body + lay.o_tot + 4 * is - 4);
-        p = ka >= dd ? pr : p;
-        ps = ks <= slo ? qr : ps;
+    bool valid[kN];
+    v4u h0[kN], h1[kN];
+#pragma unroll
+    for (int k = 0; k < kN; ++k) {
+        valid[k] = (uint32_t)task[k] < (uint32_t)tv.T && (uint32_t)bidx[k] < (uint32_t)tv.B && slo[k] >= 0;
+        const uint32_t s = valid[k] ? (uint32_t)(task[k] * tv.B + bidx[k]) : 0u;
+        h0[k] = hdrs.ld128(hdr0 + s * kHdrBytes);
+        h1[k] = hdrs.ld128(hdr0 + s * kHdrBytes + 16);
     }
-    // bit sets: even counts are stored, odd counts add the bit of the next step
-    const uint32_t ja = p >> 1, js = ps >> 1;
-    const uint32_t ea_i = ja ? ja - 1 : 0, es_i = js ? js - 1 : 0;
-    uint64_t A, Sm;
-    if (wide) {
-        A = (uint64_t)mem.ld32(body + lay.o_ea + 8 * ea_i) | ((uint64_t)mem.ld32(body + lay.o_ea + 8 * ea_i + 4) << 32);
-        Sm = (uint64_t)mem.ld32(body + lay.o_es + 8 * es_i) | ((uint64_t)mem.ld32(body + lay.o_es + 8 * es_i + 4) << 32);
-    } else {
-        A = mem.ld32(body + lay.o_ea + 4 * ea_i);
-        Sm = mem.ld32(body + lay.o_es + 4 * es_i);
+    // binary searches on byte addresses: key number j (1-based) of a slice sits at keys + j * size
+    uint32_t dd[kN], pa[kN], la[kN], pt[kN], lt[kN];
+#pragma unroll
+    for (int k = 0; k < kN; ++k) {
+        const uint32_t k1 = h1[k].x & 0xFFu;
+        const int32_t base = (int32_t)h1[k].y;
+        uint32_t d = (uint32_t)min_acc[k] - (uint32_t)base;
+        d = d < 65535u ? d : 65535u;
+        dd[k] = min_acc[k] > base ? d + 1u : 1u;
+        pa[k] = h0[k].x;
+        la[k] = h0[k].x + 2u * k1;
+        pt[k] = h0[k].y;
+        lt[k] = h0[k].y + 4u * k1;
     }
-    A = ja ? A : 0ull;
-    Sm = js ? Sm : 0ull;
-    const uint32_t ra = mem.ld8(body + lay.o_ra + (p ? p - 1 : 0));
-    const uint32_t rs = mem.ld8(body + lay.o_rs + (ps ? ps - 1 : 0));
-    A |= (p & 1u) ? (1ull << ra) : 0ull;
-    Sm |= (ps & 1u) ? (1ull << rs) : 0ull;
-    return A & Sm;
-}
-
-struct Decision {
-    int32_t ans;
-    bool defer;
-};
-
-// One query against the index held in `mem` (header array `hdr`).  kLds: bodies beyond
-// lds_cap bytes are not resident and the query is parked.
-template <bool kLds, class Mem, class HdrPtr>
-__device__ __forceinline__ Decision decide(const TableView &tv, const IndexView &ix, const Mem &mem,
-                                           HdrPtr hdr, uint32_t lds_cap, int nit, int32_t task,
-                                           int32_t slo, int32_t min_acc, int32_t bidx)
-{
-    const bool valid = (uint32_t)task < (uint32_t)tv.T && (uint32_t)bidx < (uint32_t)tv.B && slo >= 0;
-    const uint32_t s = valid ? (uint32_t)(task * tv.B + bidx) : 0u;
-    const uint4 h = hdr[s];
-    uint32_t K = h.y & 0xFFu;
-    const bool wide = (h.y & kHdrWide) != 0;
-    bool usable = valid && (h.y & kHdrIndexed);
-    if (kLds) usable = usable && (h.x + BodyLayout(K, wide).size <= lds_cap);
-    K = usable ? K : 0u;
-    const uint32_t body = usable ? h.x : 0u;
-    const uint64_t m = lookup_mask(mem, body, K, usable && wide, (int32_t)h.z, min_acc, (uint32_t)slo, nit);
-    const bool hit = m != 0ull;
-    const uint32_t step = hit ? (usable ? h.w : 0u) + (uint32_t)__builtin_ctzll(m | (1ull << 63)) : 0u;
-    const int32_t row = ix.step_row[step];
-    Decision d;
-    d.ans = hit ? row : -1;
-    d.defer = valid && (!usable || (!hit && (h.y & kHdrTrunc)));
-    return d;
+#pragma unroll
+    for (int it = 5; it >= 0; --it) {
+        if (it < nit) {
+#pragma unroll
+            for (int k = 0; k < kN; ++k) {
+                const uint32_t ca = pa[k] + (2u << it), ct = pt[k] + (4u << it);
+                const uint32_t ka = bodies.ld16(ca < la[k] ? ca : la[k]);
+                const uint32_t kt = bodies.ld32(ct < lt[k] ? ct : lt[k]);
+                pa[k] = ka >= dd[k] ? ca : pa[k];
+                pt[k] = kt <= (uint32_t)slo[k] ? ct : pt[k];
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kN; ++k) {
+        const bool wide = (h1[k].x & kHdrWide) != 0;
+        const uint32_t sh = wide ? 3u : 2u;
+        const uint32_t p = (pa[k] - h0[k].x) >> 1, ps = (pt[k] - h0[k].y) >> 2;
+        const uint32_t a_ra = lt[k] + 3u;                       // ra[-1]
+        const uint32_t a_rs = a_ra + (((h1[k].x & 0xFFu) + 2u) & ~3u);
+        const uint32_t ja = p >> 1, js = ps >> 1;
+        const uint32_t ea = h0[k].z + (ja << sh), es = h0[k].w + (js << sh);
+        uint32_t a_lo = bodies.ld32(ea), a_hi = bodies.ld32(ea + 4);
+        uint32_t s_lo = bodies.ld32(es), s_hi = bodies.ld32(es + 4);
+        const uint32_t ra = bodies.ld8(a_ra + p);
+        const uint32_t rs = bodies.ld8(a_rs + ps);
+        a_lo = ja ? a_lo : 0u;
+        a_hi = (ja && wide) ? a_hi : 0u;
+        s_lo = js ? s_lo : 0u;
+        s_hi = (js && wide) ? s_hi : 0u;
+        const uint64_t A = ((uint64_t)a_hi << 32 | a_lo) | ((uint64_t)(p & 1u) << ra);
+        const uint64_t Sm = ((uint64_t)s_hi << 32 | s_lo) | ((uint64_t)(ps & 1u) << rs);
+        const uint64_t m = A & Sm;
+        const bool hit = valid[k] && m != 0ull;
+        const uint32_t step = hit ? h1[k].z + (uint32_t)__builtin_ctzll(m | (1ull << 63)) : 0u;
+        const int32_t row = step_row[step];
+        ans[k] = hit ? row : -1;
+        park[k] = valid[k] && ((h1[k].x & kHdrPark) || (!hit && (h1[k].x & kHdrTrunc)));
+    }
 }
 
 template <bool kLds>
@@ -243,26 +260,40 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                                                               int32_t *__restrict__ defer_q,
                                                               uint32_t lds_cap, int32_t per_block_cap)
 {
-    extern __shared__ __align__(16) uint32_t lds_w[];  // [S * 4 header words][lds_cap bytes of bodies]
-    __shared__ uint32_t s_defer;
+    extern __shared__ __align__(16) uint32_t lds_w[];  // [16 B control][S headers][lds_cap bytes of bodies]
+    uint32_t &s_defer = lds_w[0];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t hdr_words = kLds ? (uint32_t)tv.S * 4u : 0u;
+    const uint32_t hdr_bytes = kLds ? (uint32_t)tv.S * kHdrBytes : 0u;
+    const uint32_t lds_hdr0 = (uint32_t)(uintptr_t)(INFAAS_LDS uint32_t *)lds_w + kLdsCtrlBytes;  // LDS address of header 0
     if (kLds) {
-        const uint32_t *gh = (const uint32_t *)ix.hdr;
-        for (uint32_t i = tid; i < hdr_words; i += kSelThreads) lds_w[i] = gh[i];
+        // headers: rebased onto the LDS copy; slices whose body is not resident are parked
+        for (uint32_t s = tid; s < (uint32_t)tv.S; s += kSelThreads) {
+            uint4 g0 = ix.hdr[2 * s], g1 = ix.hdr[2 * s + 1];
+            const bool resident = !(g1.x & kHdrPark) && g1.w <= lds_cap;
+            if (!resident) {
+                const BodyLayout e(0, false);
+                g0 = make_uint4(0u - 2u, e.o_tot - 4u, e.o_ea - 4u, e.o_es - 4u);
+                g1 = make_uint4(1u | kHdrPark, 0u, 0u, 0u);
+            }
+            const uint32_t rebase = lds_hdr0 + hdr_bytes;   // LDS address of pool offset 0
+            g0.x += rebase; g0.y += rebase; g0.z += rebase; g0.w += rebase;
+            *(uint4 *)(lds_w + (kLdsCtrlBytes / 4) + s * (kHdrBytes / 4)) = g0;
+            *(uint4 *)(lds_w + (kLdsCtrlBytes / 4) + s * (kHdrBytes / 4) + 4) = g1;
+        }
         uint32_t used = ix.ctrl[0];
         used = used < lds_cap ? used : lds_cap;
         const uint32_t *gp = (const uint32_t *)ix.pool;
-        for (uint32_t i = tid; i < (used >> 2); i += kSelThreads) lds_w[hdr_words + i] = gp[i];
+        for (uint32_t i = tid; i < (used >> 2); i += kSelThreads)
+            lds_w[((kLdsCtrlBytes + hdr_bytes) >> 2) + i] = gp[i];
     }
     if (tid == 0) s_defer = 0;
     __syncthreads();
 
     const uint32_t max_k = ix.ctrl[2];
     const int nit = 32 - __builtin_clz(max_k | 1u);
-    const LdsMem lmem{lds_w + hdr_words};
-    const GlobalMem gmem{ix.pool};
-    const uint4 *lhdr = (const uint4 *)lds_w;
+    const LdsMem lmem{};
+    const GlobalMem gbody{ix.pool};
+    const GlobalMem ghdr{(const uint8_t *)ix.hdr};
     int32_t *region = defer_q + (int64_t)blockIdx.x * per_block_cap;
 
     const bool aligned = ((((uintptr_t)q.task) | ((uintptr_t)q.slo) | ((uintptr_t)q.min_acc) |
@@ -293,13 +324,8 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         }
         int32_t ans[kPerThread];
         bool df[kPerThread];
-#pragma unroll
-        for (int k = 0; k < kPerThread; ++k) {
-            Decision d = kLds ? decide<true>(tv, ix, lmem, lhdr, lds_cap, nit, tk[k], sl[k], am[k], bi[k])
-                              : decide<false>(tv, ix, gmem, (const uint4 *)ix.hdr, 0u, nit, tk[k], sl[k], am[k], bi[k]);
-            ans[k] = d.ans;
-            df[k] = d.defer;
-        }
+        if (kLds) decide_n<kPerThread>(tv, ix.step_row, lmem, lmem, lds_hdr0, nit, tk, sl, am, bi, ans, df);
+        else decide_n<kPerThread>(tv, ix.step_row, gbody, ghdr, 0u, nit, tk, sl, am, bi, ans, df);
         if (vec) {
             const v4i r = {ans[0], ans[1], ans[2], ans[3]};
             __builtin_nontemporal_store(r, (v4i *)(q.out + i0));
@@ -312,9 +338,10 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         for (int k = 0; k < kPerThread; ++k) {
             const uint64_t mask = __ballot(df[k]);
             if (mask) {
+                const int leader = (int)__builtin_ctzll(mask);
                 uint32_t base = 0;
-                if (lane == (int)__builtin_ctzll(mask)) base = atomicAdd(&s_defer, (uint32_t)__builtin_popcountll(mask));
-                base = (uint32_t)__builtin_amdgcn_readlane((int)base, (int)__builtin_ctzll(mask));
+                if (lane == leader) base = atomicAdd(&s_defer, (uint32_t)__builtin_popcountll(mask));
+                base = (uint32_t)__builtin_amdgcn_readlane((int)base, leader);
                 if (df[k]) region[base + lanes_below(mask)] = i0 + k;
             }
         }
@@ -327,17 +354,18 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         const uint32_t j = j0 + lane;
         const bool have = j < nd;
         const int32_t qi = have ? __hip_atomic_load(&region[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
-        const int32_t task = have ? q.task[qi] : -1;
-        const int32_t slo = q.slo[qi], min_acc = q.min_acc[qi], bidx = q.bidx[qi];
-        Decision d = decide<false>(tv, ix, gmem, (const uint4 *)ix.hdr, 0u, nit, task, slo, min_acc, bidx);
-        int32_t ans = d.ans;
-        uint64_t todo = __ballot(have && d.defer);
+        const int32_t task[1] = {have ? q.task[qi] : -1};
+        const int32_t slo[1] = {q.slo[qi]}, min_acc[1] = {q.min_acc[qi]}, bidx[1] = {q.bidx[qi]};
+        int32_t ans[1];
+        bool pk[1];
+        decide_n<1>(tv, ix.step_row, gbody, ghdr, 0u, nit, task, slo, min_acc, bidx, ans, pk);
+        uint64_t todo = __ballot(have && pk[0]);
         while (todo) {
             const int l = __builtin_ctzll(todo);
             todo &= todo - 1;
-            const int32_t t = __builtin_amdgcn_readlane(task, l), b = __builtin_amdgcn_readlane(bidx, l);
-            const int32_t am = __builtin_amdgcn_readlane(min_acc, l);
-            const uint32_t lim = (uint32_t)__builtin_amdgcn_readlane(slo, l);
+            const int32_t t = __builtin_amdgcn_readlane(task[0], l), b = __builtin_amdgcn_readlane(bidx[0], l);
+            const int32_t am = __builtin_amdgcn_readlane(min_acc[0], l);
+            const uint32_t lim = (uint32_t)__builtin_amdgcn_readlane(slo[0], l);
             const int32_t seg = tv.seg_off[t], L = tv.seg_len[t];
             const int64_t col = (int64_t)b * tv.Vp + seg;
             int32_t found = -1;
@@ -347,9 +375,9 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                 const uint64_t bm = __ballot(ok);
                 if (bm) { found = blk + (int32_t)__builtin_ctzll(bm); break; }
             }
-            if (lane == l) ans = found >= 0 ? tv.orig_r[col + found] : -1;
+            if (lane == l) ans[0] = found >= 0 ? tv.orig_r[col + found] : -1;
         }
-        if (have) q.out[qi] = ans;
+        if (have) q.out[qi] = ans[0];
     }
 }
 
@@ -373,14 +401,14 @@ hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const Q
     const int32_t ntiles = (q.n + kIndexTile - 1) / kIndexTile;
     const int32_t per_block_cap = ((ntiles + blocks - 1) / blocks) * kIndexTile;
     if (lds_bytes > 0) {
-        const uint32_t hdr_bytes = (uint32_t)tv.S * 16u;
+        const uint32_t hdr_bytes = (uint32_t)tv.S * kHdrBytes;
         hipError_t e = hipFuncSetAttribute((const void *)k_index_select<true>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
         k_index_select<true><<<blocks, kSelThreads, lds_bytes, st>>>(tv, ix, q, defer_q,
-                                                                    lds_bytes - hdr_bytes, per_block_cap);
+                                                                    lds_bytes - hdr_bytes - kLdsCtrlBytes, per_block_cap);
     } else {
-        k_index_select<false><<<blocks, kSelThreads, 0, st>>>(tv, ix, q, defer_q, 0u, per_block_cap);
+        k_index_select<false><<<blocks, kSelThreads, kLdsCtrlBytes, st>>>(tv, ix, q, defer_q, 0u, per_block_cap);
     }
     return hipGetLastError();
 }

@@ -55,6 +55,9 @@ constexpr int kIndexCap = 63;            // steps kept per slice; more => slice 
 constexpr uint32_t kHdrWide = 1u << 8;   // 64-bit masks
 constexpr uint32_t kHdrTrunc = 1u << 9;  // steps beyond the capacity exist: an empty mask proves nothing
 constexpr uint32_t kHdrIndexed = 1u << 10;  // body and step table are valid
+constexpr uint32_t kHdrPark = 1u << 11;  // no usable body: every query of the slice takes the slow path
+constexpr uint32_t kHdrBytes = 32;       // two uint4 per slice, see IndexView::hdr
+constexpr uint32_t kLdsCtrlBytes = 16;   // control words at the start of the lookup kernel's LDS
 constexpr uint32_t kBodySlack = 8;       // bytes after every body that unconditional reads may touch
 constexpr int kIndexTile = 4096;         // queries per workgroup step of the index lookup kernel
 
@@ -73,7 +76,8 @@ struct BodyLayout {
 };
 
 struct IndexView {
-    uint4 *hdr;          // [S] {body offset, K | flags, acc base, first entry in step_row}
+    uint4 *hdr;          // [2S] per slice: {acc keys - 2, tot keys - 4, ea - 1 entry, es - 1 entry} (byte offsets in pool),
+                         //               {K + 1 | flags, acc base, first entry in step_row, body end}
     uint8_t *pool;       // bodies; a dummy K=1 body sits at offset 0
     uint32_t pool_bytes;
     int32_t *step_row;   // caller row of every step
