@@ -13,7 +13,7 @@ LIB = os.path.join(PKG, "libinfaas_sel.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-    "-Wall", "-Wextra", "-Wno-unused-parameter",
+    "-Wall", "-Wextra", "-Wno-unused-parameter", "-Wno-int-to-pointer-cast",
     # keep the compiler from forming packed-fp32 instructions (no float code here, but the
     # flag is part of how every HIP file of this library is built)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

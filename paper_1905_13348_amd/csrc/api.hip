@@ -113,7 +113,7 @@ struct infaas_sel {
     }
     void free_index()
     {
-        (void)hipFree(ix.hdr); (void)hipFree(ix.pool); (void)hipFree(ix.step_row); (void)hipFree(ix.ctrl);
+        (void)hipFree(ix.pool); (void)hipFree(ix.step_row); (void)hipFree(ix.ctrl);  // hdr lives in pool's allocation
         ix = IndexView{};
         have_index = false;
         index_lds_bytes = 0;
@@ -205,12 +205,15 @@ constexpr uint32_t kLdsMax = 160 * 1024 - 256;  // dynamic LDS the lookup kernel
 int create_index(infaas_sel *h)
 {
     const int64_t S = (int64_t)h->T * h->B;
-    const uint32_t worst = BodyLayout(kIndexCap, true).size;
+    const uint32_t worst = 2 * body_bytes(kBodySteps + 1);
     IndexView ix{};
-    ix.pool_bytes = (uint32_t)std::min<int64_t>(kDummyBodyBytes + S * worst, (int64_t)1 << 30);
+    ix.pool_bytes = (uint32_t)std::min<int64_t>(kDummyBodyBytes + S * worst + 64, (int64_t)1 << 30);
     ix.step_cap = (uint32_t)std::min<int64_t>(1 + S * kIndexCap, (int64_t)1 << 28);
-    bool ok = dev_alloc(&ix.hdr, (size_t)S * 2) == hipSuccess && dev_alloc(&ix.pool, ix.pool_bytes) == hipSuccess &&
+    // one allocation: the pool, then the headers, so that one 32-bit offset reaches both
+    ix.pool_bytes &= ~15u;
+    bool ok = dev_alloc(&ix.pool, (size_t)ix.pool_bytes + (size_t)(S + 1) * 16) == hipSuccess &&
               dev_alloc(&ix.step_row, ix.step_cap) == hipSuccess && dev_alloc(&ix.ctrl, 8) == hipSuccess;
+    ix.hdr = ok ? (uint4 *)(ix.pool + ix.pool_bytes) : nullptr;
     h->ix = ix;
     if (!ok) {
         h->free_index();
@@ -219,19 +222,21 @@ int create_index(infaas_sel *h)
     }
     // dummy body of a slice without steps (sentinels only) at offset 0; step_row[0] is never an answer
     uint8_t dummy[kDummyBodyBytes] = {0};
-    dummy[4] = dummy[5] = dummy[6] = dummy[7] = 0xFF;
+    for (uint32_t i = 8; i < 16; ++i) dummy[i] = 0xFF;  // latency sentinels of the empty body (Re = 2)
     const int32_t none = -1;
     const uint32_t ctrl0[8] = {kDummyBodyBytes, 1u, 1u, 0u, 0u, 0u, 0u, 0u};
+    const uint32_t empty_hdr[4] = {0u, kEmptyHdrY, 0u, body_bytes(1)};
     if (!HIP_OK(hipMemcpy(ix.pool, dummy, sizeof(dummy), hipMemcpyHostToDevice)) ||
         !HIP_OK(hipMemcpy(ix.step_row, &none, 4, hipMemcpyHostToDevice)) ||
         !HIP_OK(hipMemcpy(ix.ctrl, ctrl0, sizeof(ctrl0), hipMemcpyHostToDevice)) ||
+        !HIP_OK(hipMemcpy(&ix.hdr[S], empty_hdr, sizeof(empty_hdr), hipMemcpyHostToDevice)) ||
         !HIP_OK(launch_index_build(h->tv, ix, nullptr)) || !HIP_OK(hipDeviceSynchronize()) ||
         !HIP_OK(hipMemcpy(h->ix_stats, ix.ctrl, sizeof(ctrl0), hipMemcpyDeviceToHost))) {
         h->free_index();
         return INFAAS_SEL_ERR_HIP;
     }
     h->have_index = true;
-    const int64_t need = kLdsCtrlBytes + S * kHdrBytes + h->ix_stats[0];
+    const int64_t need = kLdsCtrlBytes + lds_header_bytes((int32_t)S) + h->ix_stats[0] + 16;
     h->index_lds_bytes = need <= kLdsMax ? kLdsMax : 0u;
     return INFAAS_SEL_OK;
 }
@@ -489,6 +494,8 @@ int infaas_sel_load_variants(infaas_sel_t *h, int32_t V, const int32_t *task_id,
     tv.slot_of = h->d_slot_of;
     tv.acc_r = h->d_acc_r; tv.tot_r = h->d_tot_r; tv.lat_r = h->d_lat_r; tv.orig_r = h->d_orig_r;
     tv.gpos = h->d_gpos;
+    tv.acc_base = 0;
+    for (int64_t v = 0; v < V; ++v) tv.acc_base = (v == 0 || acc_bp[v] < tv.acc_base) ? acc_bp[v] : tv.acc_base;
     h->tv = tv;
     h->loaded = true;
     if ((h->flags & INFAAS_SEL_ENGINE_MASK) != INFAAS_SEL_ENGINE_SCAN) {
@@ -653,8 +660,8 @@ int infaas_sel_get_info(infaas_sel_t *h, infaas_sel_info *out)
     if (h->have_index) {
         out->index_in_lds = h->index_lds_bytes > 0 ? 1 : 0;
         out->index_truncated = (int32_t)(h->ix_stats[3] + h->ix_stats[4]);
-        out->index_max_steps = (int32_t)h->ix_stats[2];
-        out->index_bytes = (int64_t)h->ix_stats[0] + (int64_t)h->T * h->B * kHdrBytes + (int64_t)h->ix_stats[1] * 4;
+        out->index_max_steps = (int32_t)h->ix_stats[6];
+        out->index_bytes = (int64_t)h->ix_stats[0] + (int64_t)h->T * h->B * 16 + (int64_t)h->ix_stats[1] * 4;
         out->index_steps = (int64_t)h->ix_stats[5];
     }
     return INFAAS_SEL_OK;

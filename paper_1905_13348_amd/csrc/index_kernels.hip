@@ -6,13 +6,14 @@
 //
 //   k_index_build  : one wavefront per (task, batch) slice walks the slice in rank order and
 //                    keeps the "steps" (variants not dominated by a cheaper one), then writes
-//                    sorted keys and bit sets for them (layout: see BodyLayout)
+//                    sorted keys and bit sets for them (layout: internal.h)
 //   k_index_select : one lane per query.  The whole index is mirrored in LDS; a query costs two
-//                    binary searches in LDS, two bit-set reads, one AND and one count-trailing-
-//                    zeros.  Queries it cannot decide from LDS (slice not resident, or staircase
-//                    truncated and no step fits) are parked and finished by the same workgroup:
-//                    first from the index copy in global memory, then by a wavefront-wide scan of
-//                    the rank-ordered slice that stops at the first feasible variant.
+//                    5-probe binary searches in LDS, two bit-set reads, one AND and one count-
+//                    trailing-zeros.  Queries the first body of their slice cannot decide (no
+//                    fitting step among its first 31, slice not resident, staircase truncated)
+//                    are parked and finished by the same workgroup: second body, index copy in
+//                    global memory, and last a wavefront-wide scan of the rank-ordered slice that
+//                    stops at the first feasible variant.
 #include "internal.h"
 
 namespace infaas {
@@ -20,11 +21,14 @@ namespace infaas {
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
-typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+typedef uint32_t v2u __attribute__((ext_vector_type(2)));
 
 constexpr int kSelThreads = 1024;
-constexpr int kPerThread = 4;
-static_assert(kSelThreads * kPerThread == kIndexTile, "tile = threads x queries per thread");
+#ifndef INFAAS_PER_THREAD
+#define INFAAS_PER_THREAD 4
+#endif
+constexpr int kPerThread = INFAAS_PER_THREAD;   // queries per lane and tile (4 or 8)
+constexpr int kTile = kSelThreads * kPerThread;  // queries per workgroup step
 
 __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
 {
@@ -34,6 +38,39 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
 
 // ---------------------------------------------------------------- build
 
+// Writes the body of steps [g0, g0 + kb) (held one per lane, lanes g0..g0+kb-1) at `body`.
+__device__ __forceinline__ void write_body(uint8_t *body, int g0, int kb, int lane, int32_t st_acc,
+                                           uint32_t st_tot, int32_t acc_base)
+{
+    const bool mine = lane >= g0 && lane < g0 + kb;
+    int32_t pa = 0, ps = 0;
+    for (int j = g0; j < g0 + kb; ++j) {
+        const int32_t aj = __builtin_amdgcn_readlane(st_acc, j);
+        const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)st_tot, j);
+        pa += (aj > st_acc || (aj == st_acc && j < lane)) ? 1 : 0;
+        ps += (tj < st_tot || (tj == st_tot && j < lane)) ? 1 : 0;
+    }
+    const uint32_t re = ((uint32_t)kb + 2u) & ~1u;   // keys = kb + 1, rounded up to even
+    uint16_t *k_acc = (uint16_t *)(body + 4);
+    uint32_t *k_tot = (uint32_t *)(body + 4 + 2 * re);
+    uint32_t *m_a = (uint32_t *)(body + 4 + 6 * re);
+    uint32_t *m_s = (uint32_t *)(body + 4 + 10 * re);
+    if (mine) {
+        k_acc[pa] = (uint16_t)(st_acc - acc_base + 1);
+        k_tot[ps] = st_tot;
+    }
+    if (lane >= kb && lane < (int)re) {  // sentinels behind the keys (any lane will do)
+        k_acc[lane] = 0;
+        k_tot[lane] = 0xFFFFFFFFu;
+    }
+    if (lane == 0) { m_a[0] = 0; m_s[0] = 0; }
+    for (int p = 1; p <= kb; ++p) {
+        const uint32_t ma = (uint32_t)(__ballot(mine && pa < p) >> g0);
+        const uint32_t ms = (uint32_t)(__ballot(mine && ps < p) >> g0);
+        if (lane == 0) { m_a[p] = ma; m_s[p] = ms; }
+    }
+}
+
 __global__ __launch_bounds__(64) void k_index_build(TableView tv, IndexView ix)
 {
     const int32_t s = blockIdx.x;
@@ -41,12 +78,8 @@ __global__ __launch_bounds__(64) void k_index_build(TableView tv, IndexView ix)
     const int lane = threadIdx.x;
     const int32_t t = s / tv.B, b = s - t * tv.B;
     const int32_t seg = tv.seg_off[t], L = tv.seg_len[t];
-    const BodyLayout empty(0, false);
-    if (L == 0) {  // no variants: the K = 0 dummy body at offset 0 answers "nothing feasible"
-        if (lane == 0) {
-            ix.hdr[2 * s] = make_uint4(0u - 2u, empty.o_tot - 4u, empty.o_ea - 4u, empty.o_es - 4u);
-            ix.hdr[2 * s + 1] = make_uint4(1u | kHdrIndexed, 0u, 0u, empty.size);
-        }
+    if (L == 0) {  // no variants: the empty dummy body at offset 0 answers "nothing feasible"
+        if (lane == 0) ix.hdr[s] = make_uint4(0u, kEmptyHdrY, 0u, body_bytes(1));
         return;
     }
     const int32_t *__restrict__ accc = tv.acc_r + (int64_t)b * tv.Vp + seg;
@@ -85,74 +118,41 @@ __global__ __launch_bounds__(64) void k_index_build(TableView tv, IndexView ix)
         }
     }
 
-    // ---- phase B: sorted keys and bit sets
-    int32_t lo = __builtin_amdgcn_readlane(st_acc, 0), hi = lo;
+    // ---- phase B: one or two bodies of sorted keys and bit sets
+    int32_t hi = __builtin_amdgcn_readlane(st_acc, 0);
     for (int32_t j = 1; j < K; ++j) {
         const int32_t aj = __builtin_amdgcn_readlane(st_acc, j);
-        lo = aj < lo ? aj : lo;
         hi = aj > hi ? aj : hi;
     }
-    const bool wide = K > 32;
-    const BodyLayout lay((uint32_t)K, wide);
+    const int k0 = K < kBodySteps ? K : kBodySteps, k1 = K - k0;
+    const uint32_t size0 = body_bytes(k0 + 1), size = size0 + (k1 ? body_bytes(k1 + 1) : 0u);
     uint32_t off = 0, rec = 0;
     if (lane == 0) {
-        off = atomicAdd(&ix.ctrl[0], lay.size);
+        off = atomicAdd(&ix.ctrl[0], size);
         rec = atomicAdd(&ix.ctrl[1], (uint32_t)K);
     }
     off = (uint32_t)__builtin_amdgcn_readfirstlane((int)off);
     rec = (uint32_t)__builtin_amdgcn_readfirstlane((int)rec);
-    const bool fits = (uint64_t)off + lay.size <= ix.pool_bytes && (uint64_t)rec + K <= ix.step_cap &&
-                      (int64_t)hi - (int64_t)lo <= 65533;
+    const bool fits = (uint64_t)off + size <= ix.pool_bytes && (uint64_t)rec + K <= ix.step_cap &&
+                      (int64_t)hi - (int64_t)tv.acc_base <= 65533;
     if (!fits) {  // no body: every query of this slice goes to the rank-ordered scan
         if (lane == 0) {
-            ix.hdr[2 * s] = make_uint4(0u - 2u, empty.o_tot - 4u, empty.o_ea - 4u, empty.o_es - 4u);
-            ix.hdr[2 * s + 1] = make_uint4(1u | kHdrPark | kHdrTrunc, 0u, 0u, 0u);
+            ix.hdr[s] = make_uint4(0u, kEmptyHdrY | kHdrPark | kHdrTrunc, 0u, 0u);
             atomicAdd(&ix.ctrl[4], 1u);
         }
         return;
     }
-    const bool active = lane < K;
-    int32_t pa = 0, ps = 0;
-    for (int32_t j = 0; j < K; ++j) {
-        const int32_t aj = __builtin_amdgcn_readlane(st_acc, j);
-        const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)st_tot, j);
-        pa += (aj > st_acc || (aj == st_acc && j < lane)) ? 1 : 0;
-        ps += (tj < st_tot || (tj == st_tot && j < lane)) ? 1 : 0;
-    }
-    uint8_t *body = ix.pool + off;
-    if (active) {
-        ((uint16_t *)body)[pa] = (uint16_t)(st_acc - lo + 1);
-        ((uint32_t *)(body + lay.o_tot))[ps] = st_tot;
-        body[lay.o_ra + pa] = (uint8_t)lane;
-        body[lay.o_rs + ps] = (uint8_t)lane;
-        ix.step_row[rec + lane] = tv.orig_r[(int64_t)b * tv.Vp + seg + st_pos];
-    }
+    write_body(ix.pool + off, 0, k0, lane, st_acc, st_tot, tv.acc_base);
+    if (k1) write_body(ix.pool + off + size0, k0, k1, lane, st_acc, st_tot, tv.acc_base);
+    if (lane < K) ix.step_row[rec + lane] = tv.orig_r[(int64_t)b * tv.Vp + seg + st_pos];
     if (lane == 0) {
-        ((uint16_t *)body)[K] = 0;
-        ((uint32_t *)(body + lay.o_tot))[K] = 0xFFFFFFFFu;
-    }
-    uint32_t *ea = (uint32_t *)(body + lay.o_ea), *es = (uint32_t *)(body + lay.o_es);
-    for (int32_t j = 1; j <= (K >> 1); ++j) {
-        const uint64_t ma = __ballot(active && pa < 2 * j);
-        const uint64_t ms = __ballot(active && ps < 2 * j);
-        if (lane == 0) {
-            if (wide) {
-                ea[2 * (j - 1)] = (uint32_t)ma; ea[2 * (j - 1) + 1] = (uint32_t)(ma >> 32);
-                es[2 * (j - 1)] = (uint32_t)ms; es[2 * (j - 1) + 1] = (uint32_t)(ms >> 32);
-            } else {
-                ea[j - 1] = (uint32_t)ma;
-                es[j - 1] = (uint32_t)ms;
-            }
-        }
-    }
-    if (lane == 0) {
-        const uint32_t esz = wide ? 8u : 4u;
-        ix.hdr[2 * s] = make_uint4(off - 2u, off + lay.o_tot - 4u, off + lay.o_ea - esz, off + lay.o_es - esz);
-        ix.hdr[2 * s + 1] = make_uint4((uint32_t)(K + 1) | (wide ? kHdrWide : 0u) | (trunc ? kHdrTrunc : 0u) | kHdrIndexed,
-                                       (uint32_t)lo, rec, off + lay.size);
-        atomicMax(&ix.ctrl[2], (uint32_t)K);
+        const uint32_t y = ((uint32_t)(k0 + 1) << kHdrK0Shift) | (k1 ? (uint32_t)(k1 + 1) << kHdrK1Shift : 0u) |
+                           (trunc ? kHdrTrunc : 0u);
+        ix.hdr[s] = make_uint4(off, y, rec, off + size);
+        atomicMax(&ix.ctrl[2], (uint32_t)k0);
         if (trunc) atomicAdd(&ix.ctrl[3], 1u);
         atomicAdd(&ix.ctrl[5], (uint32_t)K);
+        atomicMax(&ix.ctrl[6], (uint32_t)K);
     }
 }
 
@@ -162,97 +162,62 @@ __global__ __launch_bounds__(64) void k_index_build(TableView tv, IndexView ix)
 
 // Readers of index memory by 32-bit byte address: an LDS address, or an offset from a global base.
 struct LdsMem {
-    __device__ __forceinline__ uint32_t ld32(uint32_t a) const { return *(const INFAAS_LDS uint32_t *)a; }
-    __device__ __forceinline__ uint32_t ld16(uint32_t a) const { return *(const INFAAS_LDS uint16_t *)a; }
-    __device__ __forceinline__ uint32_t ld8(uint32_t a) const { return *(const INFAAS_LDS uint8_t *)a; }
-    __device__ __forceinline__ v4u ld128(uint32_t a) const { return *(const INFAAS_LDS v4u *)a; }
+    __device__ __forceinline__ uint32_t ld32(uint32_t a, uint32_t imm) const { return *(const INFAAS_LDS uint32_t *)(a + imm); }
+    __device__ __forceinline__ uint32_t ld16(uint32_t a, uint32_t imm) const { return *(const INFAAS_LDS uint16_t *)(a + imm); }
+    __device__ __forceinline__ v2u ld64(uint32_t a) const { return *(const INFAAS_LDS v2u *)a; }
 };
 struct GlobalMem {
     const uint8_t *p;
-    __device__ __forceinline__ uint32_t ld32(uint32_t a) const { return *(const uint32_t *)(p + a); }
-    __device__ __forceinline__ uint32_t ld16(uint32_t a) const { return *(const uint16_t *)(p + a); }
-    __device__ __forceinline__ uint32_t ld8(uint32_t a) const { return p[a]; }
-    __device__ __forceinline__ v4u ld128(uint32_t a) const { return *(const v4u *)(p + a); }
+    __device__ __forceinline__ uint32_t ld32(uint32_t a, uint32_t imm) const { return *(const uint32_t *)(p + a + imm); }
+    __device__ __forceinline__ uint32_t ld16(uint32_t a, uint32_t imm) const { return *(const uint16_t *)(p + a + imm); }
 };
 
-// kN queries of one lane against the index, interleaved so that their dependent reads overlap.
-// Branch-free apart from wave-uniform conditions; every read stays inside a body plus its slack
-// (slices that cannot be used point at the empty dummy body).
-//   bodies : memory that the header's addresses refer to
-//   hdrs   : memory holding the slice headers, hdr0 = address of header 0
-//   nit    : binary-search iterations that cover the largest K of the whole index
-// Header of a slice: h0 = {acc keys - 2, tot keys - 4, ea - one entry, es - one entry},
-//                    h1 = {K + 1 | flags, acc base, first entry in step_row, body end}.
-// Outputs ans (row or -1) and park (query must be finished by the slow path).
-template <int kN, class Mem, class HMem>
-__device__ __forceinline__ void decide_n(const TableView &tv, const int32_t *__restrict__ step_row,
-                                         const Mem &bodies, const HMem &hdrs, uint32_t hdr0, int nit,
-                                         const int32_t (&task)[kN], const int32_t (&slo)[kN],
-                                         const int32_t (&min_acc)[kN], const int32_t (&bidx)[kN],
-                                         int32_t (&ans)[kN], bool (&park)[kN])
+// First fitting step of kN bodies (one per query of this lane), as bit sets; the kN searches are
+// interleaved so that their dependent reads overlap.  Branch-free apart from the wave-uniform
+// probe count.  body[k] / keys[k]: address and key count (sentinel included) of the body;
+// dd[k]: accuracy threshold in key space; lim[k]: latency bound.
+template <int kN, class Mem>
+__device__ __forceinline__ void search_bodies(const Mem &mem, int nit, const uint32_t (&body)[kN],
+                                              const uint32_t (&keys)[kN], const uint32_t (&dd)[kN],
+                                              const uint32_t (&lim)[kN], uint32_t (&m)[kN])
 {
-    bool valid[kN];
-    v4u h0[kN], h1[kN];
+    uint32_t pa[kN], la[kN], pt[kN], lt[kN], re[kN];
 #pragma unroll
     for (int k = 0; k < kN; ++k) {
-        valid[k] = (uint32_t)task[k] < (uint32_t)tv.T && (uint32_t)bidx[k] < (uint32_t)tv.B && slo[k] >= 0;
-        const uint32_t s = valid[k] ? (uint32_t)(task[k] * tv.B + bidx[k]) : 0u;
-        h0[k] = hdrs.ld128(hdr0 + s * kHdrBytes);
-        h1[k] = hdrs.ld128(hdr0 + s * kHdrBytes + 16);
-    }
-    // binary searches on byte addresses: key number j (1-based) of a slice sits at keys + j * size
-    uint32_t dd[kN], pa[kN], la[kN], pt[kN], lt[kN];
-#pragma unroll
-    for (int k = 0; k < kN; ++k) {
-        const uint32_t k1 = h1[k].x & 0xFFu;
-        const int32_t base = (int32_t)h1[k].y;
-        uint32_t d = (uint32_t)min_acc[k] - (uint32_t)base;
-        d = d < 65535u ? d : 65535u;
-        dd[k] = min_acc[k] > base ? d + 1u : 1u;
-        pa[k] = h0[k].x;
-        la[k] = h0[k].x + 2u * k1;
-        pt[k] = h0[k].y;
-        lt[k] = h0[k].y + 4u * k1;
+        re[k] = (keys[k] + 1u) & ~1u;
+        pa[k] = body[k];                       // accuracy key j (1-based) at body + 2 + 2j
+        la[k] = body[k] + 2u * keys[k];        // probes beyond the keys land on the sentinel
+        pt[k] = body[k] + 2u * re[k];          // latency key j at body + 2 Re + 4j
+        lt[k] = pt[k] + 4u * keys[k];
     }
 #pragma unroll
-    for (int it = 5; it >= 0; --it) {
+    for (int it = 4; it >= 0; --it) {
         if (it < nit) {
 #pragma unroll
             for (int k = 0; k < kN; ++k) {
                 const uint32_t ca = pa[k] + (2u << it), ct = pt[k] + (4u << it);
-                const uint32_t ka = bodies.ld16(ca < la[k] ? ca : la[k]);
-                const uint32_t kt = bodies.ld32(ct < lt[k] ? ct : lt[k]);
+                const uint32_t ka = mem.ld16(ca < la[k] ? ca : la[k], 2u);
+                const uint32_t kt = mem.ld32(ct < lt[k] ? ct : lt[k], 0u);
                 pa[k] = ka >= dd[k] ? ca : pa[k];
-                pt[k] = kt <= (uint32_t)slo[k] ? ct : pt[k];
+                pt[k] = kt <= lim[k] ? ct : pt[k];
             }
         }
     }
 #pragma unroll
     for (int k = 0; k < kN; ++k) {
-        const bool wide = (h1[k].x & kHdrWide) != 0;
-        const uint32_t sh = wide ? 3u : 2u;
-        const uint32_t p = (pa[k] - h0[k].x) >> 1, ps = (pt[k] - h0[k].y) >> 2;
-        const uint32_t a_ra = lt[k] + 3u;                       // ra[-1]
-        const uint32_t a_rs = a_ra + (((h1[k].x & 0xFFu) + 2u) & ~3u);
-        const uint32_t ja = p >> 1, js = ps >> 1;
-        const uint32_t ea = h0[k].z + (ja << sh), es = h0[k].w + (js << sh);
-        uint32_t a_lo = bodies.ld32(ea), a_hi = bodies.ld32(ea + 4);
-        uint32_t s_lo = bodies.ld32(es), s_hi = bodies.ld32(es + 4);
-        const uint32_t ra = bodies.ld8(a_ra + p);
-        const uint32_t rs = bodies.ld8(a_rs + ps);
-        a_lo = ja ? a_lo : 0u;
-        a_hi = (ja && wide) ? a_hi : 0u;
-        s_lo = js ? s_lo : 0u;
-        s_hi = (js && wide) ? s_hi : 0u;
-        const uint64_t A = ((uint64_t)a_hi << 32 | a_lo) | ((uint64_t)(p & 1u) << ra);
-        const uint64_t Sm = ((uint64_t)s_hi << 32 | s_lo) | ((uint64_t)(ps & 1u) << rs);
-        const uint64_t m = A & Sm;
-        const bool hit = valid[k] && m != 0ull;
-        const uint32_t step = hit ? h1[k].z + (uint32_t)__builtin_ctzll(m | (1ull << 63)) : 0u;
-        const int32_t row = step_row[step];
-        ans[k] = hit ? row : -1;
-        park[k] = valid[k] && ((h1[k].x & kHdrPark) || (!hit && (h1[k].x & kHdrTrunc)));
+        // A[p] at body + 4 + 6 Re + 4p with pa = body + 2p;  S[ps] at body + 4 + 10 Re + 4 ps with
+        // pt = body + 2 Re + 4 ps
+        const uint32_t a_at = 2u * pa[k] + (6u * re[k] - body[k]);
+        const uint32_t s_at = pt[k] + 8u * re[k];
+        m[k] = mem.ld32(a_at, 4u) & mem.ld32(s_at, 4u);
     }
+}
+
+__device__ __forceinline__ uint32_t acc_threshold(int32_t min_acc, int32_t acc_base)
+{
+    uint32_t d = (uint32_t)min_acc - (uint32_t)acc_base;
+    d = d < 65535u ? d : 65535u;
+    return min_acc > acc_base ? d + 1u : 1u;   // keys are acc - acc_base + 1 >= 1
 }
 
 template <bool kLds>
@@ -260,80 +225,172 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                                                               int32_t *__restrict__ defer_q,
                                                               uint32_t lds_cap, int32_t per_block_cap)
 {
-    extern __shared__ __align__(16) uint32_t lds_w[];  // [16 B control][S headers][lds_cap bytes of bodies]
+    extern __shared__ __align__(16) uint32_t lds_w[];  // [16 B control][S + 1 headers][lds_cap bytes of bodies]
     uint32_t &s_defer = lds_w[0];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint32_t hdr_bytes = kLds ? (uint32_t)tv.S * kHdrBytes : 0u;
-    const uint32_t lds_hdr0 = (uint32_t)(uintptr_t)(INFAAS_LDS uint32_t *)lds_w + kLdsCtrlBytes;  // LDS address of header 0
+    const uint32_t nhdr = (uint32_t)tv.S + 1u;
+    const uint32_t hdr_bytes = kLds ? lds_header_bytes(tv.S) : 0u;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(INFAAS_LDS uint32_t *)lds_w;
+    const uint32_t lds_hdr0 = lds_base + kLdsCtrlBytes;
+    const uint32_t rebase = lds_hdr0 + hdr_bytes;      // LDS address of pool offset 0
     if (kLds) {
-        // headers: rebased onto the LDS copy; slices whose body is not resident are parked
-        for (uint32_t s = tid; s < (uint32_t)tv.S; s += kSelThreads) {
-            uint4 g0 = ix.hdr[2 * s], g1 = ix.hdr[2 * s + 1];
-            const bool resident = !(g1.x & kHdrPark) && g1.w <= lds_cap;
-            if (!resident) {
-                const BodyLayout e(0, false);
-                g0 = make_uint4(0u - 2u, e.o_tot - 4u, e.o_ea - 4u, e.o_es - 4u);
-                g1 = make_uint4(1u | kHdrPark, 0u, 0u, 0u);
-            }
-            const uint32_t rebase = lds_hdr0 + hdr_bytes;   // LDS address of pool offset 0
-            g0.x += rebase; g0.y += rebase; g0.z += rebase; g0.w += rebase;
-            *(uint4 *)(lds_w + (kLdsCtrlBytes / 4) + s * (kHdrBytes / 4)) = g0;
-            *(uint4 *)(lds_w + (kLdsCtrlBytes / 4) + s * (kHdrBytes / 4) + 4) = g1;
+        // Mirror the index: all global loads of a lane (its headers and up to kFillDepth x 16 bytes
+        // of bodies) are issued before the first LDS write, so the fill costs about one memory
+        // round trip.  The whole LDS capacity is copied, used or not, which keeps the copy
+        // independent of any value that would have to be read from memory first.
+        // Every workgroup copies the same bytes at the same time; the copy goes in 1 KB chunks, one
+        // per wavefront and load, and every wavefront of the device starts at a different chunk, so
+        // that the requests spread over all L2 channels.
+        constexpr int kFillDepth = 10;
+        const uint4 *gp = (const uint4 *)ix.pool;
+        uint4 *lp = (uint4 *)(lds_w + ((kLdsCtrlBytes + hdr_bytes) >> 2));
+        const uint32_t nvec = (lds_cap < ix.pool_bytes ? lds_cap : ix.pool_bytes) >> 4;
+        const uint32_t nchunks = (nvec + 63u) >> 6;
+        const uint32_t per_wave = (nchunks + (kSelThreads / 64) - 1) / (kSelThreads / 64);
+        const uint32_t start = nchunks ? (blockIdx.x * 11u + (uint32_t)wave * per_wave) % nchunks : 0u;
+        uint4 v[kFillDepth];
+        uint32_t at[kFillDepth];
+        bool ok[kFillDepth];
+#pragma unroll
+        for (int u = 0; u < kFillDepth; ++u) {
+            uint32_t c = start + u;
+            c = c >= nchunks ? c - nchunks : c;
+            ok[u] = (uint32_t)u < per_wave && (uint32_t)wave * per_wave + u < nchunks && c * 64u + lane < nvec;
+            at[u] = ok[u] ? c * 64u + lane : 0u;   // lanes with nothing to copy read vector 0 and drop it
+            v[u] = gp[at[u]];                      // unconditional: keeps all loads in flight together
         }
-        uint32_t used = ix.ctrl[0];
-        used = used < lds_cap ? used : lds_cap;
-        const uint32_t *gp = (const uint32_t *)ix.pool;
-        for (uint32_t i = tid; i < (used >> 2); i += kSelThreads)
-            lds_w[((kLdsCtrlBytes + hdr_bytes) >> 2) + i] = gp[i];
+        // headers: rebased onto the LDS copy; slices whose bodies are not resident are parked
+        for (uint32_t s = tid; s < nhdr; s += kSelThreads) {
+            const uint4 g = ix.hdr[s];
+            const bool resident = !(g.y & kHdrPark) && g.w <= lds_cap && g.z < 65536u;
+            v2u l;
+            l.x = (resident ? g.x : 0u) + rebase;
+            l.y = resident ? (g.y | g.z) : (kEmptyHdrY | kHdrPark);
+            *(v2u *)(lds_w + (kLdsCtrlBytes / 4) + s * (kLdsHdrBytes / 4)) = l;
+        }
+#pragma unroll
+        for (int u = 0; u < kFillDepth; ++u)
+            if (ok[u]) lp[at[u]] = v[u];
+        for (uint32_t c0 = kFillDepth; c0 < per_wave; ++c0) {   // only if LDS ever exceeds 160 KB
+            uint32_t c = start + c0;
+            c = c >= nchunks ? c - nchunks : c;
+            const uint32_t i = c * 64u + lane;
+            if ((uint32_t)wave * per_wave + c0 < nchunks && i < nvec) lp[i] = gp[i];
+        }
     }
-    if (tid == 0) s_defer = 0;
+    if (tid < 4) lds_w[tid] = 0;
     __syncthreads();
 
     const uint32_t max_k = ix.ctrl[2];
-    const int nit = 32 - __builtin_clz(max_k | 1u);
+    const int nit = 32 - __builtin_clz(max_k | 1u);    // <= 5
     const LdsMem lmem{};
-    const GlobalMem gbody{ix.pool};
-    const GlobalMem ghdr{(const uint8_t *)ix.hdr};
+    const GlobalMem gmem{ix.pool};
     int32_t *region = defer_q + (int64_t)blockIdx.x * per_block_cap;
 
     const bool aligned = ((((uintptr_t)q.task) | ((uintptr_t)q.slo) | ((uintptr_t)q.min_acc) |
                            ((uintptr_t)q.bidx) | ((uintptr_t)q.out)) & 15u) == 0;
-    const int32_t ntiles = (q.n + kIndexTile - 1) / kIndexTile;
-    for (int32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int32_t i0 = tile * kIndexTile + tid * kPerThread;
-        int32_t tk[kPerThread], sl[kPerThread], am[kPerThread], bi[kPerThread];
-        const bool vec = aligned && i0 + kPerThread <= q.n;
-        if (vec) {
-            const v4i a = __builtin_nontemporal_load((const v4i *)(q.task + i0));
-            const v4i b = __builtin_nontemporal_load((const v4i *)(q.slo + i0));
-            const v4i c = __builtin_nontemporal_load((const v4i *)(q.min_acc + i0));
-            const v4i d = __builtin_nontemporal_load((const v4i *)(q.bidx + i0));
-            tk[0] = a.x; tk[1] = a.y; tk[2] = a.z; tk[3] = a.w;
-            sl[0] = b.x; sl[1] = b.y; sl[2] = b.z; sl[3] = b.w;
-            am[0] = c.x; am[1] = c.y; am[2] = c.z; am[3] = c.w;
-            bi[0] = d.x; bi[1] = d.y; bi[2] = d.z; bi[3] = d.w;
+    const int32_t ntiles = (q.n + kTile - 1) / kTile;
+    // Query fields of one tile for this lane.  The next tile's loads are issued before the
+    // current tile is searched, so that their latency overlaps with the LDS work.
+    auto load_tile = [&](int32_t tile, int32_t (&tk)[kPerThread], int32_t (&sl)[kPerThread],
+                         int32_t (&am)[kPerThread], int32_t (&bi)[kPerThread]) {
+        const int32_t i0 = tile * kTile + tid * kPerThread;
+        if (tile >= ntiles) {
+#pragma unroll
+            for (int k = 0; k < kPerThread; ++k) { tk[k] = -1; sl[k] = 0; am[k] = 0; bi[k] = 0; }
+        } else if (aligned && i0 + kPerThread <= q.n) {
+#pragma unroll
+            for (int h = 0; h < kPerThread / 4; ++h) {
+                const v4i a = __builtin_nontemporal_load((const v4i *)(q.task + i0) + h);
+                const v4i b = __builtin_nontemporal_load((const v4i *)(q.slo + i0) + h);
+                const v4i c = __builtin_nontemporal_load((const v4i *)(q.min_acc + i0) + h);
+                const v4i d = __builtin_nontemporal_load((const v4i *)(q.bidx + i0) + h);
+                tk[4 * h] = a.x; tk[4 * h + 1] = a.y; tk[4 * h + 2] = a.z; tk[4 * h + 3] = a.w;
+                sl[4 * h] = b.x; sl[4 * h + 1] = b.y; sl[4 * h + 2] = b.z; sl[4 * h + 3] = b.w;
+                am[4 * h] = c.x; am[4 * h + 1] = c.y; am[4 * h + 2] = c.z; am[4 * h + 3] = c.w;
+                bi[4 * h] = d.x; bi[4 * h + 1] = d.y; bi[4 * h + 2] = d.z; bi[4 * h + 3] = d.w;
+            }
         } else {
 #pragma unroll
             for (int k = 0; k < kPerThread; ++k) {
                 const bool in = i0 + k < q.n;
-                tk[k] = in ? q.task[i0 + k] : -1;   // -1: invalid task, decided as "nothing feasible"
+                tk[k] = in ? q.task[i0 + k] : -1;   // -1: outside the table, answered "nothing feasible"
                 sl[k] = in ? q.slo[i0 + k] : 0;
                 am[k] = in ? q.min_acc[i0 + k] : 0;
                 bi[k] = in ? q.bidx[i0 + k] : 0;
             }
         }
-        int32_t ans[kPerThread];
-        bool df[kPerThread];
-        if (kLds) decide_n<kPerThread>(tv, ix.step_row, lmem, lmem, lds_hdr0, nit, tk, sl, am, bi, ans, df);
-        else decide_n<kPerThread>(tv, ix.step_row, gbody, ghdr, 0u, nit, tk, sl, am, bi, ans, df);
-        if (vec) {
-            const v4i r = {ans[0], ans[1], ans[2], ans[3]};
-            __builtin_nontemporal_store(r, (v4i *)(q.out + i0));
+    };
+    // two tiles ahead: the data of tile t + 2 is requested while tile t is searched
+    int32_t ntk[kPerThread], nsl[kPerThread], nam[kPerThread], nbi[kPerThread];
+    int32_t ftk[kPerThread], fsl[kPerThread], fam[kPerThread], fbi[kPerThread];
+    load_tile(blockIdx.x, ntk, nsl, nam, nbi);
+    load_tile(blockIdx.x + gridDim.x, ftk, fsl, fam, fbi);
+    // Software pipeline.  A wavefront waits for memory once per tile, at the top, where it needs the
+    // tile's query fields; that wait also covers everything requested before it.  The rows gathered
+    // for a tile are therefore consumed, and its results stored, only after the NEXT tile's wait --
+    // one full tile of LDS work after they were requested -- so neither the gather nor the store
+    // latency is exposed.
+    int32_t p_row[kPerThread], p_i0 = 0;
+    bool p_hit[kPerThread], p_vec = false, p_have = false;
+    auto store_tile = [&]() {
+        if (!p_have) return;
+        if (p_vec) {
+#pragma unroll
+            for (int h = 0; h < kPerThread / 4; ++h) {
+                const v4i r = {p_hit[4 * h] ? p_row[4 * h] : -1, p_hit[4 * h + 1] ? p_row[4 * h + 1] : -1,
+                               p_hit[4 * h + 2] ? p_row[4 * h + 2] : -1, p_hit[4 * h + 3] ? p_row[4 * h + 3] : -1};
+                __builtin_nontemporal_store(r, (v4i *)(q.out + p_i0) + h);
+            }
         } else {
 #pragma unroll
             for (int k = 0; k < kPerThread; ++k)
-                if (i0 + k < q.n) q.out[i0 + k] = ans[k];
+                if (p_i0 + k < q.n) q.out[p_i0 + k] = p_hit[k] ? p_row[k] : -1;
         }
+    };
+    for (int32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int32_t i0 = tile * kTile + tid * kPerThread;
+        const bool vec = aligned && i0 + kPerThread <= q.n;
+        int32_t tk[kPerThread], sl[kPerThread], am[kPerThread], bi[kPerThread];
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            tk[k] = ntk[k]; sl[k] = nsl[k]; am[k] = nam[k]; bi[k] = nbi[k];
+            ntk[k] = ftk[k]; nsl[k] = fsl[k]; nam[k] = fam[k]; nbi[k] = fbi[k];
+        }
+        store_tile();                                   // results of the previous tile
+        load_tile(tile + 2 * gridDim.x, ftk, fsl, fam, fbi);
+        // slice header; queries outside the table use the header of the empty slice (entry S)
+        uint32_t body[kPerThread], y[kPerThread], rec[kPerThread], keys[kPerThread], dd[kPerThread],
+            lim[kPerThread], m[kPerThread];
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            const uint32_t ok = ((uint32_t)tk[k] < (uint32_t)tv.T) & ((uint32_t)bi[k] < (uint32_t)tv.B) &
+                                (uint32_t)(sl[k] >= 0);
+            const uint32_t s = ok ? __umul24((uint32_t)tk[k], (uint32_t)tv.B) + (uint32_t)bi[k] : (uint32_t)tv.S;
+            if (kLds) {
+                const v2u h = lmem.ld64(lds_hdr0 + s * kLdsHdrBytes);
+                body[k] = h.x; y[k] = h.y; rec[k] = h.y & 0xFFFFu;
+            } else {
+                const uint4 h = ix.hdr[s];
+                body[k] = h.x; y[k] = h.y; rec[k] = h.z;
+            }
+            keys[k] = (y[k] >> kHdrK0Shift) & 0x3Fu;
+            dd[k] = acc_threshold(am[k], tv.acc_base);
+            lim[k] = (uint32_t)sl[k];
+        }
+        if (kLds) search_bodies<kPerThread>(lmem, nit, body, keys, dd, lim, m);
+        else search_bodies<kPerThread>(gmem, nit, body, keys, dd, lim, m);
+        bool df[kPerThread];
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            const bool hit = m[k] != 0u;
+            const uint32_t step = hit ? rec[k] + (uint32_t)__builtin_ctz(m[k] | 0x80000000u) : 0u;
+            p_row[k] = ix.step_row[step];               // requested now, used after the next wait
+            p_hit[k] = hit;
+            // parked: unusable slice, or a miss that the second body / the scan may still turn into a hit
+            df[k] = (y[k] & kHdrPark) || (!hit && (y[k] & ((0x3Fu << kHdrK1Shift) | kHdrTrunc)));
+        }
+        p_i0 = i0; p_vec = vec; p_have = true;
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) {
             const uint64_t mask = __ballot(df[k]);
@@ -346,38 +403,74 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             }
         }
     }
+    store_tile();   // a parked query gets -1 here and its real answer below, after the barrier
 
-    // ---- parked queries: index copy in global memory, then the rank-ordered scan
+    // ---- parked queries (all of them are inside the table)
     __syncthreads();
     const uint32_t nd = s_defer;
     for (uint32_t j0 = wave * 64; j0 < nd; j0 += kSelThreads) {
         const uint32_t j = j0 + lane;
         const bool have = j < nd;
         const int32_t qi = have ? __hip_atomic_load(&region[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
-        const int32_t task[1] = {have ? q.task[qi] : -1};
-        const int32_t slo[1] = {q.slo[qi]}, min_acc[1] = {q.min_acc[qi]}, bidx[1] = {q.bidx[qi]};
-        int32_t ans[1];
-        bool pk[1];
-        decide_n<1>(tv, ix.step_row, gbody, ghdr, 0u, nit, task, slo, min_acc, bidx, ans, pk);
-        uint64_t todo = __ballot(have && pk[0]);
+        const int32_t task = q.task[qi], slo = q.slo[qi], min_acc = q.min_acc[qi], bidx = q.bidx[qi];
+        const uint32_t s = have ? __umul24((uint32_t)task, (uint32_t)tv.B) + (uint32_t)bidx : (uint32_t)tv.S;
+        const uint4 g = ix.hdr[s];
+        const bool indexed = !(g.y & kHdrPark);
+        bool resident = false;
+        uint32_t lbody = rebase;
+        if (kLds) {
+            const v2u h = lmem.ld64(lds_hdr0 + s * kLdsHdrBytes);
+            resident = !(h.y & kHdrPark);
+            lbody = h.x;
+        }
+        const uint32_t keys0 = (g.y >> kHdrK0Shift) & 0x3Fu, keys1 = (g.y >> kHdrK1Shift) & 0x3Fu;
+        const uint32_t size0 = body_bytes(keys0);
+        const uint32_t dd[1] = {acc_threshold(min_acc, tv.acc_base)}, lim[1] = {(uint32_t)slo};
+        int32_t ans = -1;
+        bool done = false;
+        // first body from global memory: only if the main loop could not use the LDS copy
+        const bool need_g0 = have && indexed && kLds && !resident;
+        if (__ballot(need_g0)) {
+            const uint32_t bd[1] = {need_g0 ? g.x : 0u}, ks[1] = {need_g0 ? keys0 : 1u};
+            uint32_t m[1];
+            search_bodies<1>(gmem, nit, bd, ks, dd, lim, m);
+            if (need_g0 && m[0]) { ans = ix.step_row[g.z + __builtin_ctz(m[0])]; done = true; }
+        }
+        // second body: LDS copy when resident, global memory otherwise
+        const bool need1 = have && indexed && keys1 != 0u && !done;
+        const bool need_l1 = need1 && resident, need_g1 = need1 && !resident;
+        if (kLds && __ballot(need_l1)) {
+            const uint32_t bd[1] = {need_l1 ? lbody + size0 : rebase}, ks[1] = {need_l1 ? keys1 : 1u};
+            uint32_t m[1];
+            search_bodies<1>(lmem, nit, bd, ks, dd, lim, m);
+            if (need_l1 && m[0]) { ans = ix.step_row[g.z + kBodySteps + __builtin_ctz(m[0])]; done = true; }
+        }
+        if (__ballot(need_g1)) {
+            const uint32_t bd[1] = {need_g1 ? g.x + size0 : 0u}, ks[1] = {need_g1 ? keys1 : 1u};
+            uint32_t m[1];
+            search_bodies<1>(gmem, nit, bd, ks, dd, lim, m);
+            if (need_g1 && m[0]) { ans = ix.step_row[g.z + kBodySteps + __builtin_ctz(m[0])]; done = true; }
+        }
+        // no body, or both bodies missed and more steps exist: scan the slice in rank order
+        uint64_t todo = __ballot(have && !done && (!indexed || (g.y & kHdrTrunc)));
         while (todo) {
             const int l = __builtin_ctzll(todo);
             todo &= todo - 1;
-            const int32_t t = __builtin_amdgcn_readlane(task[0], l), b = __builtin_amdgcn_readlane(bidx[0], l);
-            const int32_t am = __builtin_amdgcn_readlane(min_acc[0], l);
-            const uint32_t lim = (uint32_t)__builtin_amdgcn_readlane(slo[0], l);
+            const int32_t t = __builtin_amdgcn_readlane(task, l), b = __builtin_amdgcn_readlane(bidx, l);
+            const int32_t am = __builtin_amdgcn_readlane(min_acc, l);
+            const uint32_t bound = (uint32_t)__builtin_amdgcn_readlane(slo, l);
             const int32_t seg = tv.seg_off[t], L = tv.seg_len[t];
             const int64_t col = (int64_t)b * tv.Vp + seg;
             int32_t found = -1;
             for (int32_t blk = 0; blk < L; blk += 64) {
                 const int32_t pos = blk + lane;
-                const bool ok = pos < L && tv.acc_r[col + pos] >= am && tv.tot_r[col + pos] <= lim;
+                const bool ok = pos < L && tv.acc_r[col + pos] >= am && tv.tot_r[col + pos] <= bound;
                 const uint64_t bm = __ballot(ok);
                 if (bm) { found = blk + (int32_t)__builtin_ctzll(bm); break; }
             }
-            if (lane == l) ans[0] = found >= 0 ? tv.orig_r[col + found] : -1;
+            if (lane == l) ans = found >= 0 ? tv.orig_r[col + found] : -1;
         }
-        if (have) q.out[qi] = ans[0];
+        if (have) q.out[qi] = ans;
     }
 }
 
@@ -398,15 +491,16 @@ hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const Q
                                int32_t *defer_q, uint32_t lds_bytes, int num_cus, hipStream_t st)
 {
     const int blocks = index_select_blocks(num_cus);
-    const int32_t ntiles = (q.n + kIndexTile - 1) / kIndexTile;
-    const int32_t per_block_cap = ((ntiles + blocks - 1) / blocks) * kIndexTile;
+    const int32_t ntiles = (q.n + kTile - 1) / kTile;
+    const int32_t per_block_cap = ((ntiles + blocks - 1) / blocks) * kTile;
     if (lds_bytes > 0) {
-        const uint32_t hdr_bytes = (uint32_t)tv.S * kHdrBytes;
+        const uint32_t fixed = kLdsCtrlBytes + lds_header_bytes(tv.S);
+        lds_bytes = fixed + ((lds_bytes - fixed) & ~15u);
         hipError_t e = hipFuncSetAttribute((const void *)k_index_select<true>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
-        k_index_select<true><<<blocks, kSelThreads, lds_bytes, st>>>(tv, ix, q, defer_q,
-                                                                    lds_bytes - hdr_bytes - kLdsCtrlBytes, per_block_cap);
+        k_index_select<true><<<blocks, kSelThreads, lds_bytes, st>>>(tv, ix, q, defer_q, lds_bytes - fixed,
+                                                                    per_block_cap);
     } else {
         k_index_select<false><<<blocks, kSelThreads, kLdsCtrlBytes, st>>>(tv, ix, q, defer_q, 0u, per_block_cap);
     }

@@ -31,6 +31,7 @@ struct TableView {
     const int32_t *lat_r;       // [B][Vp]
     const int32_t *orig_r;      // [B][Vp] caller row
     const int32_t *gpos;        // [B][Vp] slot -> its entry in the rank-ordered column b
+    int32_t acc_base;           // smallest accuracy in the table; index keys are acc - acc_base + 1
 };
 
 // ---------------------------------------------------------------- staircase index
@@ -39,53 +40,49 @@ struct TableView {
 // earlier (cheaper) one has at least its accuracy and at most its latency-plus-queue: a query
 // that the later one satisfies is also satisfied by the earlier one, which wins.  The kept
 // variants ("steps") are the only possible answers, and the answer to (min_acc, slo) is the
-// first step with acc >= min_acc and tot <= slo.  With K <= 63 steps that is
-//     ctz( A[#steps with acc >= min_acc] & S[#steps with tot <= slo] )
-// where A[p] / S[p] are bit sets (over step numbers) of the p most accurate / p fastest steps.
-// Both counts come from a binary search over a sorted copy of the keys.
+// first step with acc >= min_acc and tot <= slo.
 //
-// Body of one slice (byte offsets from the body start; every section 4-byte aligned):
-//   acc16 : u16[K+1]  acc - base + 1, descending, then a 0 sentinel
-//   totk  : u32[K+1]  tot, ascending, then a 0xFFFFFFFF sentinel
-//   ra    : u8[K]     step number of the j-th most accurate step
-//   rs    : u8[K]     step number of the j-th fastest step
-//   ea    : (u32 x W)[K/2]  A[2], A[4], ...   (W = 2 when K > 32; odd counts add one bit via ra)
-//   es    : (u32 x W)[K/2]  S[2], S[4], ...
-constexpr int kIndexCap = 63;            // steps kept per slice; more => slice marked truncated
-constexpr uint32_t kHdrWide = 1u << 8;   // 64-bit masks
-constexpr uint32_t kHdrTrunc = 1u << 9;  // steps beyond the capacity exist: an empty mask proves nothing
-constexpr uint32_t kHdrIndexed = 1u << 10;  // body and step table are valid
-constexpr uint32_t kHdrPark = 1u << 11;  // no usable body: every query of the slice takes the slow path
-constexpr uint32_t kHdrBytes = 32;       // two uint4 per slice, see IndexView::hdr
-constexpr uint32_t kLdsCtrlBytes = 16;   // control words at the start of the lookup kernel's LDS
-constexpr uint32_t kBodySlack = 8;       // bytes after every body that unconditional reads may touch
-constexpr int kIndexTile = 4096;         // queries per workgroup step of the index lookup kernel
+// Steps are stored in groups of at most 31 ("bodies"; a slice has up to two).  Within a body
+// the first fitting step is
+//     ctz( A[#steps with acc >= min_acc] & S[#steps with tot <= slo] )
+// where A[p] / S[p] are 32-bit sets (over the body's step numbers) of its p most accurate /
+// p fastest steps.  Both counts come from a 5-probe binary search over a sorted copy of the
+// keys.  Only when the first body has no fitting step is the second one consulted.
+//
+// Body with K steps (K + 1 = k1 keys including the sentinel; Re = k1 rounded up to even).
+// Byte offsets from the body start, which is 4-byte aligned:
+//   0            4 bytes unused
+//   4            acc16 : u16[Re]  acc - acc_base + 1, descending; then 0 (sentinel)
+//   4 + 2 Re     totk  : u32[Re]  tot, ascending; then 0xFFFFFFFF (sentinel)
+//   4 + 6 Re     A     : u32[Re]  A[0] = 0, A[p] for p = 1..K
+//   4 + 10 Re    S     : u32[Re]  S[0] = 0, S[p] for p = 1..K
+// so accuracy key j (1-based) is at body + 2 + 2j and latency key j at body + 2 Re + 4j.
+constexpr int kBodySteps = 31;               // steps per body
+constexpr int kIndexCap = 2 * kBodySteps;    // steps kept per slice; more => slice marked truncated
+constexpr uint32_t kHdrK0Shift = 16;         // header word y: bits 0-15 first step_row entry (LDS copy),
+constexpr uint32_t kHdrK1Shift = 22;         //   bits 16-21 keys of body 0, bits 22-27 keys of body 1 (0 = none)
+constexpr uint32_t kHdrTrunc = 1u << 28;     // steps beyond the capacity exist: a miss in both bodies proves nothing
+constexpr uint32_t kHdrPark = 1u << 29;      // no usable body: every query of the slice takes the slow path
+constexpr uint32_t kLdsHdrBytes = 8;         // per slice in the lookup kernel's LDS: {body address, y | first step}
+constexpr uint32_t kLdsCtrlBytes = 16;       // control words at the start of the lookup kernel's LDS
+constexpr int kIndexTile = 8192;             // most queries per workgroup step of the index lookup kernel
 
-struct BodyLayout {
-    uint32_t o_tot, o_ra, o_rs, o_ea, o_es, size;
-    __host__ __device__ BodyLayout(uint32_t K, uint32_t wide)
-    {
-        const uint32_t k1 = K + 1, rk = (K + 3) & ~3u, e = (K >> 1) << (wide ? 3 : 2);
-        o_tot = (2 * k1 + 3) & ~3u;
-        o_ra = o_tot + 4 * k1;
-        o_rs = o_ra + rk;
-        o_ea = o_rs + rk;
-        o_es = o_ea + e;
-        size = o_es + e + kBodySlack;
-    }
-};
+// LDS bytes of the S + 1 slice headers, padded so that the bodies behind them are 16-byte aligned
+__host__ __device__ inline uint32_t lds_header_bytes(int32_t S) { return (((uint32_t)S + 1u) * kLdsHdrBytes + 15u) & ~15u; }
+__host__ __device__ inline uint32_t body_bytes(uint32_t keys) { return 4u + 14u * ((keys + 1u) & ~1u); }
 
 struct IndexView {
-    uint4 *hdr;          // [2S] per slice: {acc keys - 2, tot keys - 4, ea - 1 entry, es - 1 entry} (byte offsets in pool),
-                         //               {K + 1 | flags, acc base, first entry in step_row, body end}
-    uint8_t *pool;       // bodies; a dummy K=1 body sits at offset 0
+    uint4 *hdr;          // [S + 1] {body offset in pool, y (see kHdr*), first entry in step_row, end of bodies};
+                         //         entry S is the header of an empty slice, used for queries outside the table
+    uint8_t *pool;       // bodies; an empty dummy body sits at offset 0
     uint32_t pool_bytes;
-    int32_t *step_row;   // caller row of every step
+    int32_t *step_row;   // caller row of every step; entry 0 is unused
     uint32_t step_cap;
-    uint32_t *ctrl;      // [0] pool bump, [1] step bump, [2] max K, [3] truncated slices,
+    uint32_t *ctrl;      // [0] pool bump, [1] step bump, [2] most keys in one body, [3] truncated slices,
                          // [4] slices without body, [5] total steps
 };
-constexpr uint32_t kDummyBodyBytes = 64;
+constexpr uint32_t kDummyBodyBytes = 64;     // empty body (32 bytes) and padding
+constexpr uint32_t kEmptyHdrY = 1u << kHdrK0Shift;  // one key (the sentinel), no second body
 
 // Scratch of the scan engine for one pass over up to `capacity` queries.
 struct ScanScratch {

@@ -87,6 +87,7 @@ __global__ __launch_bounds__(256) void k_update_load(TableView tv, int32_t n,
         index_ctrl[3] = 0;
         index_ctrl[4] = 0;
         index_ctrl[5] = 0;
+        index_ctrl[6] = 0;
     }
     if (tid >= (int64_t)n * tv.B)
         return;
