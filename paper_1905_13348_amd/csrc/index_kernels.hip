@@ -71,52 +71,164 @@ __device__ __forceinline__ void write_body(uint8_t *body, int g0, int kb, int la
     }
 }
 
-__global__ __launch_bounds__(64) void k_index_build(TableView tv, IndexView ix)
+constexpr int kBuildThreads = 512;
+constexpr int kBuildChunk = 4096;   // entries of a slice staged in LDS at a time
+
+// Sequential part of the staircase walk, run by the first wavefront: the candidates `alive`
+// of one block of 64 entries (a, tt per lane, rank position pos0 + lane) are tested against the
+// steps from number j0 on and appended, in rank order, when nothing earlier dominates them.
+// Lane j keeps step j.  Returns false when the capacity is exceeded.
+__device__ __forceinline__ bool absorb_block(bool alive, int32_t a, uint32_t tt, int32_t pos0, int lane,
+                                             int32_t j0, int32_t &K, int32_t &st_acc, uint32_t &st_tot,
+                                             int32_t &st_pos)
 {
+    for (int32_t j = j0; j < K; ++j) {
+        const int32_t aj = __builtin_amdgcn_readlane(st_acc, j);
+        const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)st_tot, j);
+        alive = alive && !(aj >= a && tj <= tt);
+        if (((j - j0) & 3) == 3 && __ballot(alive) == 0) return true;
+    }
+    uint64_t mask = __ballot(alive);
+    while (mask) {
+        if (K == kIndexCap) return false;
+        const int l = __builtin_ctzll(mask);
+        const int32_t al = __builtin_amdgcn_readlane(a, l);
+        const uint32_t tl = (uint32_t)__builtin_amdgcn_readlane((int)tt, l);
+        if (lane == K) { st_acc = al; st_tot = tl; st_pos = pos0 + l; }
+        K += 1;
+        alive = alive && !(al >= a && tl <= tt);   // also retires lane l itself
+        mask = __ballot(alive);
+    }
+    return true;
+}
+
+// One workgroup per slice.  All of its lanes copy the slice (rank-ordered accuracy and
+// latency-plus-queue columns) into LDS with every load in flight at once.  Per staged chunk:
+//   1. (first chunk only) the first wavefront finds the steps among the first 64 entries;
+//   2. all wavefronts test the remaining entries against the steps known so far -- in parallel,
+//      because that set is fixed -- which removes nearly all of them;
+//   3. the first wavefront walks the few survivors in rank order against the steps found since.
+__global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, IndexView ix)
+{
+    __shared__ int32_t s_acc[kBuildChunk];
+    __shared__ uint32_t s_tot[kBuildChunk];
+    __shared__ uint64_t s_live[kBuildChunk / 64];   // per block of 64 entries: lanes that survived step 2
+    __shared__ int32_t p_acc[64];                   // steps published for step 2
+    __shared__ uint32_t p_tot[64];
+    __shared__ int32_t s_kpub, s_stop;
     const int32_t s = blockIdx.x;
     if (s >= tv.S) return;
-    const int lane = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool scanner = wave == 0;
     const int32_t t = s / tv.B, b = s - t * tv.B;
     const int32_t seg = tv.seg_off[t], L = tv.seg_len[t];
     if (L == 0) {  // no variants: the empty dummy body at offset 0 answers "nothing feasible"
-        if (lane == 0) ix.hdr[s] = make_uint4(0u, kEmptyHdrY, 0u, body_bytes(1));
+        if (tid == 0) ix.hdr[s] = make_uint4(0u, kEmptyHdrY, 0u, body_bytes(1));
         return;
     }
     const int32_t *__restrict__ accc = tv.acc_r + (int64_t)b * tv.Vp + seg;
     const uint32_t *__restrict__ totc = tv.tot_r + (int64_t)b * tv.Vp + seg;
 
-    // ---- phase A: the steps, in rank order; lane j keeps step j
+    // ---- phase A: the steps, in rank order; lane j of the first wavefront keeps step j
     int32_t K = 0;
     bool trunc = false;
     int32_t st_acc = 0, st_pos = 0;
     uint32_t st_tot = 0;
-    int32_t a_nx = lane < L ? accc[lane] : INT32_MIN;
-    uint32_t t_nx = lane < L ? totc[lane] : 0xFFFFFFFFu;
-    for (int32_t blk = 0; blk < L && !trunc; blk += 64) {
-        const int32_t a = a_nx;
-        const uint32_t tt = t_nx;
-        bool alive = blk + lane < L;
-        const int32_t nx = blk + 64 + lane;
-        a_nx = nx < L ? accc[nx] : INT32_MIN;
-        t_nx = nx < L ? totc[nx] : 0xFFFFFFFFu;
-        for (int32_t j = 0; j < K; ++j) {
-            const int32_t aj = __builtin_amdgcn_readlane(st_acc, j);
-            const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)st_tot, j);
-            alive = alive && !(aj >= a && tj <= tt);
-            if ((j & 3) == 3 && __ballot(alive) == 0) break;
+    if (tid == 0) s_stop = 0;
+    for (int32_t c0 = 0; c0 < L; c0 += kBuildChunk) {
+        const int32_t n = L - c0 < kBuildChunk ? L - c0 : kBuildChunk;
+        const int32_t nblk = (n + 63) >> 6;
+        {
+            constexpr int kPer = kBuildChunk / kBuildThreads;
+            int32_t va[kPer];
+            uint32_t vt[kPer];
+#pragma unroll
+            for (int u = 0; u < kPer; ++u) {   // unconditional loads (clamped), so that they overlap
+                const int32_t i = u * kBuildThreads + tid;
+                const int32_t j = c0 + (i < n ? i : n - 1);
+                va[u] = accc[j];
+                vt[u] = totc[j];
+            }
+#pragma unroll
+            for (int u = 0; u < kPer; ++u) {
+                const int32_t i = u * kBuildThreads + tid;
+                s_acc[i] = va[u];
+                s_tot[i] = vt[u];
+            }
         }
-        uint64_t mask = __ballot(alive);
-        while (mask) {
-            if (K == kIndexCap) { trunc = true; break; }
-            const int l = __builtin_ctzll(mask);
-            const int32_t al = __builtin_amdgcn_readlane(a, l);
-            const uint32_t tl = (uint32_t)__builtin_amdgcn_readlane((int)tt, l);
-            if (lane == K) { st_acc = al; st_tot = tl; st_pos = blk + l; }
-            K += 1;
-            alive = alive && !(al >= a && tl <= tt);   // also retires lane l itself
-            mask = __ballot(alive);
+        __syncthreads();
+        // Rounds over growing groups of blocks: {0}, {1..3}, {4..12}, {13..39}, then 32 at a time.  The first block of
+        // a slice is absorbed directly; every later group is first filtered, by all wavefronts in
+        // parallel, against the steps known when its round starts, and then its few survivors are
+        // absorbed in rank order by the first wavefront.
+        int32_t g0 = 0;
+        if (c0 == 0) {
+            if (scanner)
+                trunc = !absorb_block(lane < n, s_acc[lane], s_tot[lane], 0, lane, 0, K, st_acc, st_tot, st_pos);
+            g0 = 1;
         }
+        for (int32_t gsz = 3; g0 < nblk; g0 += gsz, gsz = gsz * 3 < 32 ? gsz * 3 : 32) {
+            const int32_t g1 = g0 + gsz < nblk ? g0 + gsz : nblk;
+            if (scanner) {
+                if (lane < K) { p_acc[lane] = st_acc; p_tot[lane] = st_tot; }
+                if (lane == 0) { s_kpub = K; if (trunc) s_stop = 1; }
+            }
+            __syncthreads();
+            if (s_stop) break;
+            const int32_t kpub = s_kpub;
+            {   // every wavefront: its share of the group's blocks against the published steps
+                const int32_t pa_ = lane < kpub ? p_acc[lane] : 0;
+                const uint32_t pt_ = lane < kpub ? p_tot[lane] : 0u;
+                for (int32_t blk = g0 + wave; blk < g1; blk += kBuildThreads / 64) {
+                    const int32_t i = blk * 64 + lane;
+                    const int32_t a = s_acc[i];
+                    const uint32_t tt = s_tot[i];
+                    bool alive = i < n;
+                    for (int32_t j = 0; j < kpub; j += 4) {   // four steps per pass; lanes >= kpub hold (0, 0)
+                        bool d0, d1, d2, d3;
+                        {
+                            const int32_t aj = __builtin_amdgcn_readlane(pa_, j);
+                            const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)pt_, j);
+                            d0 = aj >= a && tj <= tt;
+                        }
+                        {
+                            const int32_t aj = __builtin_amdgcn_readlane(pa_, j + 1);
+                            const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)pt_, j + 1);
+                            d1 = j + 1 < kpub && aj >= a && tj <= tt;
+                        }
+                        {
+                            const int32_t aj = __builtin_amdgcn_readlane(pa_, j + 2);
+                            const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)pt_, j + 2);
+                            d2 = j + 2 < kpub && aj >= a && tj <= tt;
+                        }
+                        {
+                            const int32_t aj = __builtin_amdgcn_readlane(pa_, j + 3);
+                            const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)pt_, j + 3);
+                            d3 = j + 3 < kpub && aj >= a && tj <= tt;
+                        }
+                        alive = alive && !(d0 || d1 || d2 || d3);
+                        if (__ballot(alive) == 0) break;
+                    }
+                    const uint64_t live = __ballot(alive);
+                    if (lane == 0) s_live[blk] = live;
+                }
+            }
+            __syncthreads();
+            if (scanner) {   // survivors, in rank order, against the steps found since publishing
+                for (int32_t blk = g0; blk < g1 && !trunc; ++blk) {
+                    const uint64_t live = s_live[blk];
+                    if (live == 0) continue;
+                    const int32_t i = blk * 64 + lane;
+                    trunc = !absorb_block((live >> lane) & 1ull, s_acc[i], s_tot[i], c0 + blk * 64, lane, kpub,
+                                          K, st_acc, st_tot, st_pos);
+                }
+            }
+        }
+        if (scanner && trunc && lane == 0) s_stop = 1;
+        __syncthreads();
+        if (s_stop) break;
     }
+    if (!scanner) return;
 
     // ---- phase B: one or two bodies of sorted keys and bit sets
     int32_t hi = __builtin_amdgcn_readlane(st_acc, 0);
@@ -481,7 +593,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
 hipError_t launch_index_build(const TableView &tv, const IndexView &ix, hipStream_t st)
 {
     if (tv.S <= 0) return hipSuccess;
-    k_index_build<<<tv.S, 64, 0, st>>>(tv, ix);
+    k_index_build<<<tv.S, kBuildThreads, 0, st>>>(tv, ix);
     return hipGetLastError();
 }
 
