@@ -47,6 +47,7 @@ class _Info(ctypes.Structure):
                 ("max_segment", ctypes.c_int32), ("lds_segment_limit", ctypes.c_int32),
                 ("wide_segments", ctypes.c_int32), ("index_in_lds", ctypes.c_int32),
                 ("index_truncated", ctypes.c_int32), ("index_max_steps", ctypes.c_int32),
+                ("index_hot_rows", ctypes.c_int32),
                 ("index_bytes", ctypes.c_int64), ("index_steps", ctypes.c_int64),
                 ("table_bytes", ctypes.c_int64),
                 ("scratch_bytes", ctypes.c_int64)]

@@ -199,13 +199,13 @@ int ensure_scratch(infaas_sel *h, int64_t capacity)
     return INFAAS_SEL_OK;
 }
 
-constexpr uint32_t kLdsMax = 160 * 1024 - 256;  // dynamic LDS the lookup kernel may ask for
+constexpr uint32_t kLdsMax = 160 * 1024;  // dynamic LDS the lookup kernel may ask for
 
 // Allocate the staircase index for the loaded table, build it and read its sizes back.
 int create_index(infaas_sel *h)
 {
     const int64_t S = (int64_t)h->T * h->B;
-    const uint32_t worst = 2 * body_bytes(kBodySteps + 1);
+    const uint32_t worst = 2 * body_bytes(kBodySteps + 1, kBodySteps);
     IndexView ix{};
     ix.pool_bytes = (uint32_t)std::min<int64_t>(kDummyBodyBytes + S * worst + 64, (int64_t)1 << 30);
     ix.step_cap = (uint32_t)std::min<int64_t>(1 + S * kIndexCap, (int64_t)1 << 28);
@@ -236,8 +236,23 @@ int create_index(infaas_sel *h)
         return INFAAS_SEL_ERR_HIP;
     }
     h->have_index = true;
-    const int64_t need = kLdsCtrlBytes + lds_header_bytes((int32_t)S) + h->ix_stats[0] + 16;
+    const int64_t fixed = kLdsCtrlBytes + lds_header_bytes((int32_t)S) + 16;
+    const int64_t need = fixed + h->ix_stats[0];
     h->index_lds_bytes = need <= kLdsMax ? kLdsMax : 0u;
+    // LDS left over holds the caller rows of the first steps of every slice (the steps most answers
+    // come from), which saves those answers a gather from global memory.  Rebuild with that many.
+    const int64_t spare = (int64_t)kLdsMax - need - 1536;   // keep room for staircases that grow with load
+    const uint32_t hot = spare > 0 ? (uint32_t)std::min<int64_t>(spare / (4 * S), kBodySteps) : 0u;
+    if (h->index_lds_bytes && hot > 0) {
+        h->ix.hot_rows = hot;
+        if (!HIP_OK(hipMemcpy(h->ix.ctrl, ctrl0, sizeof(ctrl0), hipMemcpyHostToDevice)) ||
+            !HIP_OK(launch_index_build(h->tv, h->ix, nullptr)) || !HIP_OK(hipDeviceSynchronize()) ||
+            !HIP_OK(hipMemcpy(h->ix_stats, h->ix.ctrl, sizeof(ctrl0), hipMemcpyDeviceToHost))) {
+            h->free_index();
+            return INFAAS_SEL_ERR_HIP;
+        }
+        if (fixed + h->ix_stats[0] > kLdsMax) h->index_lds_bytes = 0u;   // cannot happen: hot rows fit by construction
+    }
     return INFAAS_SEL_OK;
 }
 
@@ -661,6 +676,7 @@ int infaas_sel_get_info(infaas_sel_t *h, infaas_sel_info *out)
         out->index_in_lds = h->index_lds_bytes > 0 ? 1 : 0;
         out->index_truncated = (int32_t)(h->ix_stats[3] + h->ix_stats[4]);
         out->index_max_steps = (int32_t)h->ix_stats[6];
+        out->index_hot_rows = (int32_t)h->ix.hot_rows;
         out->index_bytes = (int64_t)h->ix_stats[0] + (int64_t)h->T * h->B * 16 + (int64_t)h->ix_stats[1] * 4;
         out->index_steps = (int64_t)h->ix_stats[5];
     }

@@ -28,7 +28,6 @@ constexpr int kSelThreads = 1024;
 #define INFAAS_PER_THREAD 4
 #endif
 constexpr int kPerThread = INFAAS_PER_THREAD;   // queries per lane and tile (4 or 8)
-constexpr int kTile = kSelThreads * kPerThread;  // queries per workgroup step
 
 __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
 {
@@ -51,10 +50,10 @@ __device__ __forceinline__ void write_body(uint8_t *body, int g0, int kb, int la
         ps += (tj < st_tot || (tj == st_tot && j < lane)) ? 1 : 0;
     }
     const uint32_t re = ((uint32_t)kb + 2u) & ~1u;   // keys = kb + 1, rounded up to even
-    uint16_t *k_acc = (uint16_t *)(body + 4);
-    uint32_t *k_tot = (uint32_t *)(body + 4 + 2 * re);
-    uint32_t *m_a = (uint32_t *)(body + 4 + 6 * re);
-    uint32_t *m_s = (uint32_t *)(body + 4 + 10 * re);
+    uint16_t *k_acc = (uint16_t *)body;
+    uint32_t *k_tot = (uint32_t *)(body + 2 * re);
+    uint32_t *m_a = (uint32_t *)(body + 6 * re);
+    uint32_t *m_s = (uint32_t *)(body + 10 * re);
     if (mine) {
         k_acc[pa] = (uint16_t)(st_acc - acc_base + 1);
         k_tot[ps] = st_tot;
@@ -237,7 +236,8 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
         hi = aj > hi ? aj : hi;
     }
     const int k0 = K < kBodySteps ? K : kBodySteps, k1 = K - k0;
-    const uint32_t size0 = body_bytes(k0 + 1), size = size0 + (k1 ? body_bytes(k1 + 1) : 0u);
+    const uint32_t r0 = (uint32_t)k0 < ix.hot_rows ? (uint32_t)k0 : ix.hot_rows;
+    const uint32_t size0 = body_bytes(k0 + 1, r0), size = size0 + (k1 ? body_bytes(k1 + 1) : 0u);
     uint32_t off = 0, rec = 0;
     if (lane == 0) {
         off = atomicAdd(&ix.ctrl[0], size);
@@ -256,11 +256,15 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
     }
     write_body(ix.pool + off, 0, k0, lane, st_acc, st_tot, tv.acc_base);
     if (k1) write_body(ix.pool + off + size0, k0, k1, lane, st_acc, st_tot, tv.acc_base);
-    if (lane < K) ix.step_row[rec + lane] = tv.orig_r[(int64_t)b * tv.Vp + seg + st_pos];
+    if (lane < K) {
+        const int32_t row = tv.orig_r[(int64_t)b * tv.Vp + seg + st_pos];
+        ix.step_row[rec + lane] = row;
+        if ((uint32_t)lane < r0) ((int32_t *)(ix.pool + off + body_bytes(k0 + 1)))[lane] = row;   // rows section
+    }
     if (lane == 0) {
         const uint32_t y = ((uint32_t)(k0 + 1) << kHdrK0Shift) | (k1 ? (uint32_t)(k1 + 1) << kHdrK1Shift : 0u) |
                            (trunc ? kHdrTrunc : 0u);
-        ix.hdr[s] = make_uint4(off, y, rec, off + size);
+        ix.hdr[s] = make_uint4(off - 4u, y, rec, off + size);
         atomicMax(&ix.ctrl[2], (uint32_t)k0);
         if (trunc) atomicAdd(&ix.ctrl[3], 1u);
         atomicAdd(&ix.ctrl[5], (uint32_t)K);
@@ -382,7 +386,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         }
 #pragma unroll
         for (int u = 0; u < kFillDepth; ++u)
-            if (ok[u]) lp[at[u]] = v[u];
+            lp[at[u]] = v[u];   // unconditional as well (lanes without work rewrite vector 0 with itself)
         for (uint32_t c0 = kFillDepth; c0 < per_wave; ++c0) {   // only if LDS ever exceeds 160 KB
             uint32_t c = start + c0;
             c = c >= nchunks ? c - nchunks : c;
@@ -397,19 +401,36 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     const int nit = 32 - __builtin_clz(max_k | 1u);    // <= 5
     const LdsMem lmem{};
     const GlobalMem gmem{ix.pool};
-    int32_t *region = defer_q + (int64_t)blockIdx.x * per_block_cap;
+    int32_t *region = defer_q + (int64_t)blockIdx.x * per_block_cap;   // parked queries of this workgroup
 
     const bool aligned = ((((uintptr_t)q.task) | ((uintptr_t)q.slo) | ((uintptr_t)q.min_acc) |
                            ((uintptr_t)q.bidx) | ((uintptr_t)q.out)) & 15u) == 0;
-    const int32_t ntiles = (q.n + kTile - 1) / kTile;
-    // Query fields of one tile for this lane.  The next tile's loads are issued before the
-    // current tile is searched, so that their latency overlaps with the LDS work.
-    auto load_tile = [&](int32_t tile, int32_t (&tk)[kPerThread], int32_t (&sl)[kPerThread],
-                         int32_t (&am)[kPerThread], int32_t (&bi)[kPerThread]) {
-        const int32_t i0 = tile * kTile + tid * kPerThread;
-        if (tile >= ntiles) {
+    // Work units of one wavefront: 64 lanes x kPerThread consecutive queries.  The units are split
+    // evenly and contiguously over the workgroups; inside a workgroup the wavefronts draw them from
+    // a counter in LDS, because the wavefronts of a SIMD do not advance at the same speed.
+    constexpr int kUnit = 64 * kPerThread;
+    const int32_t nunits = (q.n + kUnit - 1) / kUnit;
+    const int32_t u_begin = (int32_t)(((int64_t)nunits * blockIdx.x) / gridDim.x);
+    const int32_t u_end = (int32_t)(((int64_t)nunits * (blockIdx.x + 1)) / gridDim.x);
+    uint32_t &s_next = lds_w[2];
+    auto next_unit = [&]() -> int32_t {
+        uint32_t u = 0;
+        if (lane == 0) u = atomicAdd(&s_next, 1u);
+        u = (uint32_t)__builtin_amdgcn_readfirstlane((int)u);
+        const int64_t unit = (int64_t)u_begin + u;
+        return unit < u_end ? (int32_t)unit : -1;
+    };
+    // Query fields of one unit for this lane (unit < 0: nothing left; the fields then describe a
+    // query outside the table).
+    struct Fields {
+        int32_t tk[kPerThread], sl[kPerThread], am[kPerThread], bi[kPerThread], unit;
+    };
+    auto load_unit = [&](Fields &f, int32_t unit) {
+        f.unit = unit;
+        const int32_t i0 = unit * kUnit + lane * kPerThread;
+        if (unit < 0) {
 #pragma unroll
-            for (int k = 0; k < kPerThread; ++k) { tk[k] = -1; sl[k] = 0; am[k] = 0; bi[k] = 0; }
+            for (int k = 0; k < kPerThread; ++k) { f.tk[k] = -1; f.sl[k] = 0; f.am[k] = 0; f.bi[k] = 0; }
         } else if (aligned && i0 + kPerThread <= q.n) {
 #pragma unroll
             for (int h = 0; h < kPerThread / 4; ++h) {
@@ -417,68 +438,59 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                 const v4i b = __builtin_nontemporal_load((const v4i *)(q.slo + i0) + h);
                 const v4i c = __builtin_nontemporal_load((const v4i *)(q.min_acc + i0) + h);
                 const v4i d = __builtin_nontemporal_load((const v4i *)(q.bidx + i0) + h);
-                tk[4 * h] = a.x; tk[4 * h + 1] = a.y; tk[4 * h + 2] = a.z; tk[4 * h + 3] = a.w;
-                sl[4 * h] = b.x; sl[4 * h + 1] = b.y; sl[4 * h + 2] = b.z; sl[4 * h + 3] = b.w;
-                am[4 * h] = c.x; am[4 * h + 1] = c.y; am[4 * h + 2] = c.z; am[4 * h + 3] = c.w;
-                bi[4 * h] = d.x; bi[4 * h + 1] = d.y; bi[4 * h + 2] = d.z; bi[4 * h + 3] = d.w;
+                f.tk[4 * h] = a.x; f.tk[4 * h + 1] = a.y; f.tk[4 * h + 2] = a.z; f.tk[4 * h + 3] = a.w;
+                f.sl[4 * h] = b.x; f.sl[4 * h + 1] = b.y; f.sl[4 * h + 2] = b.z; f.sl[4 * h + 3] = b.w;
+                f.am[4 * h] = c.x; f.am[4 * h + 1] = c.y; f.am[4 * h + 2] = c.z; f.am[4 * h + 3] = c.w;
+                f.bi[4 * h] = d.x; f.bi[4 * h + 1] = d.y; f.bi[4 * h + 2] = d.z; f.bi[4 * h + 3] = d.w;
             }
         } else {
 #pragma unroll
             for (int k = 0; k < kPerThread; ++k) {
                 const bool in = i0 + k < q.n;
-                tk[k] = in ? q.task[i0 + k] : -1;   // -1: outside the table, answered "nothing feasible"
-                sl[k] = in ? q.slo[i0 + k] : 0;
-                am[k] = in ? q.min_acc[i0 + k] : 0;
-                bi[k] = in ? q.bidx[i0 + k] : 0;
+                f.tk[k] = in ? q.task[i0 + k] : -1;   // -1: outside the table, answered "nothing feasible"
+                f.sl[k] = in ? q.slo[i0 + k] : 0;
+                f.am[k] = in ? q.min_acc[i0 + k] : 0;
+                f.bi[k] = in ? q.bidx[i0 + k] : 0;
             }
         }
     };
-    // two tiles ahead: the data of tile t + 2 is requested while tile t is searched
-    int32_t ntk[kPerThread], nsl[kPerThread], nam[kPerThread], nbi[kPerThread];
-    int32_t ftk[kPerThread], fsl[kPerThread], fam[kPerThread], fbi[kPerThread];
-    load_tile(blockIdx.x, ntk, nsl, nam, nbi);
-    load_tile(blockIdx.x + gridDim.x, ftk, fsl, fam, fbi);
-    // Software pipeline.  A wavefront waits for memory once per tile, at the top, where it needs the
-    // tile's query fields; that wait also covers everything requested before it.  The rows gathered
-    // for a tile are therefore consumed, and its results stored, only after the NEXT tile's wait --
-    // one full tile of LDS work after they were requested -- so neither the gather nor the store
-    // latency is exposed.
-    int32_t p_row[kPerThread], p_i0 = 0;
-    bool p_hit[kPerThread], p_vec = false, p_have = false;
-    auto store_tile = [&]() {
-        if (!p_have) return;
-        if (p_vec) {
+
+    // Software pipeline.  A wavefront waits for memory once per unit, at the top, where it needs the
+    // unit's query fields; that wait also covers everything requested before it.  The rows gathered
+    // for a unit are therefore consumed, and its results stored, only after the NEXT unit's wait --
+    // one full unit of LDS work after they were requested -- so neither the gather nor the store
+    // latency is exposed.  The fields of the unit after the next are requested meanwhile.
+    int32_t p_lrow[kPerThread], p_grow[kPerThread], p_i0 = -1;
+    bool p_hit[kPerThread], p_inl[kPerThread];
+    auto p_val = [&](int k) -> int32_t { return p_hit[k] ? (p_inl[k] ? p_lrow[k] : p_grow[k]) : -1; };
+    auto store_unit = [&]() {
+        if (p_i0 < 0) return;
+        if (aligned && p_i0 + kPerThread <= q.n) {
 #pragma unroll
             for (int h = 0; h < kPerThread / 4; ++h) {
-                const v4i r = {p_hit[4 * h] ? p_row[4 * h] : -1, p_hit[4 * h + 1] ? p_row[4 * h + 1] : -1,
-                               p_hit[4 * h + 2] ? p_row[4 * h + 2] : -1, p_hit[4 * h + 3] ? p_row[4 * h + 3] : -1};
+                const v4i r = {p_val(4 * h), p_val(4 * h + 1), p_val(4 * h + 2), p_val(4 * h + 3)};
                 __builtin_nontemporal_store(r, (v4i *)(q.out + p_i0) + h);
             }
         } else {
 #pragma unroll
             for (int k = 0; k < kPerThread; ++k)
-                if (p_i0 + k < q.n) q.out[p_i0 + k] = p_hit[k] ? p_row[k] : -1;
+                if (p_i0 + k < q.n) q.out[p_i0 + k] = p_val(k);
         }
     };
-    for (int32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int32_t i0 = tile * kTile + tid * kPerThread;
-        const bool vec = aligned && i0 + kPerThread <= q.n;
-        int32_t tk[kPerThread], sl[kPerThread], am[kPerThread], bi[kPerThread];
-#pragma unroll
-        for (int k = 0; k < kPerThread; ++k) {
-            tk[k] = ntk[k]; sl[k] = nsl[k]; am[k] = nam[k]; bi[k] = nbi[k];
-            ntk[k] = ftk[k]; nsl[k] = fsl[k]; nam[k] = fam[k]; nbi[k] = fbi[k];
-        }
-        store_tile();                                   // results of the previous tile
-        load_tile(tile + 2 * gridDim.x, ftk, fsl, fam, fbi);
+    // One pipeline stage: search the unit in `cur`, request the unit after the next into `far`.
+    auto stage = [&](Fields &cur, Fields &far) {
+        const int32_t i0 = cur.unit * kUnit + lane * kPerThread;
+        store_unit();                                   // results of the previous unit
+        load_unit(far, next_unit());
         // slice header; queries outside the table use the header of the empty slice (entry S)
         uint32_t body[kPerThread], y[kPerThread], rec[kPerThread], keys[kPerThread], dd[kPerThread],
             lim[kPerThread], m[kPerThread];
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) {
-            const uint32_t ok = ((uint32_t)tk[k] < (uint32_t)tv.T) & ((uint32_t)bi[k] < (uint32_t)tv.B) &
-                                (uint32_t)(sl[k] >= 0);
-            const uint32_t s = ok ? __umul24((uint32_t)tk[k], (uint32_t)tv.B) + (uint32_t)bi[k] : (uint32_t)tv.S;
+            const uint32_t ok = ((uint32_t)cur.tk[k] < (uint32_t)tv.T) & ((uint32_t)cur.bi[k] < (uint32_t)tv.B) &
+                                (uint32_t)(cur.sl[k] >= 0);
+            const uint32_t s = ok ? __umul24((uint32_t)cur.tk[k], (uint32_t)tv.B) + (uint32_t)cur.bi[k]
+                                  : (uint32_t)tv.S;
             if (kLds) {
                 const v2u h = lmem.ld64(lds_hdr0 + s * kLdsHdrBytes);
                 body[k] = h.x; y[k] = h.y; rec[k] = h.y & 0xFFFFu;
@@ -487,8 +499,8 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                 body[k] = h.x; y[k] = h.y; rec[k] = h.z;
             }
             keys[k] = (y[k] >> kHdrK0Shift) & 0x3Fu;
-            dd[k] = acc_threshold(am[k], tv.acc_base);
-            lim[k] = (uint32_t)sl[k];
+            dd[k] = acc_threshold(cur.am[k], tv.acc_base);
+            lim[k] = (uint32_t)cur.sl[k];
         }
         if (kLds) search_bodies<kPerThread>(lmem, nit, body, keys, dd, lim, m);
         else search_bodies<kPerThread>(gmem, nit, body, keys, dd, lim, m);
@@ -496,13 +508,22 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) {
             const bool hit = m[k] != 0u;
-            const uint32_t step = hit ? rec[k] + (uint32_t)__builtin_ctz(m[k] | 0x80000000u) : 0u;
-            p_row[k] = ix.step_row[step];               // requested now, used after the next wait
+            const uint32_t step = (uint32_t)__builtin_ctz(m[k] | 0x80000000u);
+            // row of the step: from the body when it is one of its first hot_rows steps, else from
+            // step_row in global memory.  Both reads are issued for every lane (lanes that do not need
+            // one read a fixed address) and used after the next wait.
+            const uint32_t re = (keys[k] + 1u) & ~1u;
+            const uint32_t r0 = keys[k] - 1u < ix.hot_rows ? keys[k] - 1u : ix.hot_rows;
+            const bool inl = hit && step < r0;
+            const uint32_t at = inl ? body[k] + 14u * re + 4u * step : body[k];
+            p_lrow[k] = kLds ? (int32_t)lmem.ld32(at, 4u) : (int32_t)gmem.ld32(at, 4u);
+            p_grow[k] = ix.step_row[(hit && !inl) ? rec[k] + step : 0u];
             p_hit[k] = hit;
+            p_inl[k] = inl;
             // parked: unusable slice, or a miss that the second body / the scan may still turn into a hit
             df[k] = (y[k] & kHdrPark) || (!hit && (y[k] & ((0x3Fu << kHdrK1Shift) | kHdrTrunc)));
         }
-        p_i0 = i0; p_vec = vec; p_have = true;
+        p_i0 = i0;
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) {
             const uint64_t mask = __ballot(df[k]);
@@ -514,8 +535,21 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                 if (df[k]) region[base + lanes_below(mask)] = i0 + k;
             }
         }
+    };
+    {
+        Fields fa, fb, fc;   // three buffers in rotation: searched now, next, the one after
+        load_unit(fa, next_unit());
+        load_unit(fb, next_unit());
+        for (;;) {
+            if (fa.unit < 0) break;
+            stage(fa, fc);
+            if (fb.unit < 0) break;
+            stage(fb, fa);
+            if (fc.unit < 0) break;
+            stage(fc, fb);
+        }
+        store_unit();   // a parked query gets -1 here and its real answer below, after the barrier
     }
-    store_tile();   // a parked query gets -1 here and its real answer below, after the barrier
 
     // ---- parked queries (all of them are inside the table)
     __syncthreads();
@@ -536,7 +570,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             lbody = h.x;
         }
         const uint32_t keys0 = (g.y >> kHdrK0Shift) & 0x3Fu, keys1 = (g.y >> kHdrK1Shift) & 0x3Fu;
-        const uint32_t size0 = body_bytes(keys0);
+        const uint32_t size0 = body_bytes(keys0, keys0 - 1u < ix.hot_rows ? keys0 - 1u : ix.hot_rows);
         const uint32_t dd[1] = {acc_threshold(min_acc, tv.acc_base)}, lim[1] = {(uint32_t)slo};
         int32_t ans = -1;
         bool done = false;
@@ -603,8 +637,8 @@ hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const Q
                                int32_t *defer_q, uint32_t lds_bytes, int num_cus, hipStream_t st)
 {
     const int blocks = index_select_blocks(num_cus);
-    const int32_t ntiles = (q.n + kTile - 1) / kTile;
-    const int32_t per_block_cap = ((ntiles + blocks - 1) / blocks) * kTile;
+    const int32_t nunits = (q.n + 64 * kPerThread - 1) / (64 * kPerThread);
+    const int32_t per_block_cap = ((nunits + blocks - 1) / blocks + 1) * 64 * kPerThread;
     if (lds_bytes > 0) {
         const uint32_t fixed = kLdsCtrlBytes + lds_header_bytes(tv.S);
         lds_bytes = fixed + ((lds_bytes - fixed) & ~15u);

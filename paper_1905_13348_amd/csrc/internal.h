@@ -51,12 +51,15 @@ struct TableView {
 //
 // Body with K steps (K + 1 = k1 keys including the sentinel; Re = k1 rounded up to even).
 // Byte offsets from the body start, which is 4-byte aligned:
-//   0            4 bytes unused
-//   4            acc16 : u16[Re]  acc - acc_base + 1, descending; then 0 (sentinel)
-//   4 + 2 Re     totk  : u32[Re]  tot, ascending; then 0xFFFFFFFF (sentinel)
-//   4 + 6 Re     A     : u32[Re]  A[0] = 0, A[p] for p = 1..K
-//   4 + 10 Re    S     : u32[Re]  S[0] = 0, S[p] for p = 1..K
-// so accuracy key j (1-based) is at body + 2 + 2j and latency key j at body + 2 Re + 4j.
+//   0            acc16 : u16[Re]  acc - acc_base + 1, descending; then 0 (sentinel)
+//   2 Re         totk  : u32[Re]  tot, ascending; then 0xFFFFFFFF (sentinel)
+//   6 Re         A     : u32[Re]  A[0] = 0, A[p] for p = 1..K
+//   10 Re        S     : u32[Re]  S[0] = 0, S[p] for p = 1..K
+//   14 Re        rows  : i32[r]   caller row of step i, for the first r = min(K, hot_rows) steps of
+//                                 a slice's FIRST body (none in the second); deeper steps are
+//                                 translated through step_row in global memory
+// Headers hold "body start - 4" (called the body address below), so that accuracy key j (1-based)
+// is at address + 2 + 2j and latency key j at address + 2 Re + 4j.
 constexpr int kBodySteps = 31;               // steps per body
 constexpr int kIndexCap = 2 * kBodySteps;    // steps kept per slice; more => slice marked truncated
 constexpr uint32_t kHdrK0Shift = 16;         // header word y: bits 0-15 first step_row entry (LDS copy),
@@ -69,19 +72,23 @@ constexpr int kIndexTile = 8192;             // most queries per workgroup step 
 
 // LDS bytes of the S + 1 slice headers, padded so that the bodies behind them are 16-byte aligned
 __host__ __device__ inline uint32_t lds_header_bytes(int32_t S) { return (((uint32_t)S + 1u) * kLdsHdrBytes + 15u) & ~15u; }
-__host__ __device__ inline uint32_t body_bytes(uint32_t keys) { return 4u + 14u * ((keys + 1u) & ~1u); }
+__host__ __device__ inline uint32_t body_bytes(uint32_t keys, uint32_t rows = 0u)
+{
+    return 14u * ((keys + 1u) & ~1u) + 4u * rows;
+}
 
 struct IndexView {
-    uint4 *hdr;          // [S + 1] {body offset in pool, y (see kHdr*), first entry in step_row, end of bodies};
+    uint4 *hdr;          // [S + 1] {body address (pool offset - 4), y (see kHdr*), first entry in step_row, end of bodies};
                          //         entry S is the header of an empty slice, used for queries outside the table
-    uint8_t *pool;       // bodies; an empty dummy body sits at offset 0
+    uint8_t *pool;       // bodies; an empty dummy body sits at offset 4 (its address is 0)
     uint32_t pool_bytes;
     int32_t *step_row;   // caller row of every step; entry 0 is unused
     uint32_t step_cap;
+    uint32_t hot_rows;   // rows kept inside the first body of every slice (fills the LDS left over)
     uint32_t *ctrl;      // [0] pool bump, [1] step bump, [2] most keys in one body, [3] truncated slices,
                          // [4] slices without body, [5] total steps
 };
-constexpr uint32_t kDummyBodyBytes = 64;     // empty body (32 bytes) and padding
+constexpr uint32_t kDummyBodyBytes = 64;     // 4 unused bytes, the empty body (28 bytes), padding
 constexpr uint32_t kEmptyHdrY = 1u << kHdrK0Shift;  // one key (the sentinel), no second body
 
 // Scratch of the scan engine for one pass over up to `capacity` queries.

@@ -173,6 +173,105 @@ def test_update_load_then_select(oracle_lib, engine):
     sel.destroy()
 
 
+def _staircase_table(T, n, B=2, acc0=1000, acc_step=1):
+    """Every variant of a task is a step: cost, accuracy rise and latency falls with the row, so no
+    cheaper variant dominates a dearer one.  The staircase of a slice has n entries."""
+    task = np.repeat(np.arange(T, dtype=np.int32), n)
+    i = np.tile(np.arange(n, dtype=np.int64), T)
+    acc = acc0 + acc_step * i
+    lat = np.stack([100_000 - 100 * i + 7 * b for b in range(B)], axis=1)
+    cost = np.stack([10 + i + b for b in range(B)], axis=1)
+    queue = np.zeros(T * n, np.int64)
+    return _table(T, list(range(1, B + 1)), task, acc, lat, cost, queue)
+
+
+def _staircase_queries(rng, tb, n_queries, n):
+    T, B = tb.num_tasks, tb.B
+    task = rng.integers(0, T, n_queries)
+    bidx = rng.integers(0, B, n_queries)
+    want_row = rng.integers(-3, n + 3, n_queries)           # aim at a given depth of the staircase
+    acc = tb.acc_bp.min() + (tb.acc_bp[1] - tb.acc_bp[0]) * want_row
+    slo = rng.choice([100_000 + 50, 60_000, 20_000, 99_000], n_queries) + rng.integers(-300, 300, n_queries)
+    return tuple(np.asarray(x, np.int32) for x in (task, slo, acc, bidx))
+
+
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
+@pytest.mark.parametrize("steps", [31, 32, 50, 62, 63, 300])
+def test_long_staircases(oracle_lib, engine, steps):
+    """Slices whose staircase fills one index body exactly (31), needs the second one (32..62), or
+    exceeds the index capacity (63, 300: the in-kernel rank-ordered scan must finish the query)."""
+    rng = np.random.default_rng(steps)
+    tb = _staircase_table(5, steps)
+    qs = _staircase_queries(rng, tb, 40_000, steps)
+    _compare(oracle_lib, tb, qs, engine, label=f"staircase{steps}")
+    if engine != 1:
+        sel = make_selector(tb, engine=engine)
+        info = sel.info()
+        assert info["index_max_steps"] == min(steps, 62)
+        assert (info["index_truncated"] > 0) == (steps > 62)
+        sel.destroy()
+
+
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
+def test_accuracy_range_too_wide_for_the_index(oracle_lib, engine):
+    """Accuracies that span more than 16 bits inside a slice: those slices get no index body and
+    every query of theirs is answered by the scan; the other task keeps its index."""
+    rng = np.random.default_rng(8)
+    wide = _staircase_table(1, 40, acc0=-50_000, acc_step=5_000)       # -50,000 .. 145,000
+    narrow = _staircase_table(1, 40)
+    tb = _table(2, [1, 2], np.concatenate([wide.task_id, narrow.task_id + 1]),
+                np.concatenate([wide.acc_bp, narrow.acc_bp]), np.concatenate([wide.lat_us, narrow.lat_us]),
+                np.concatenate([wide.cost, narrow.cost]), np.concatenate([wide.queue_us, narrow.queue_us]))
+    n = 30_000
+    task = rng.integers(0, 2, n)
+    acc = np.where(task == 0, rng.integers(-60_000, 150_000, n), rng.integers(990, 1050, n))
+    qs = tuple(np.asarray(x, np.int32) for x in (task, rng.integers(90_000, 101_000, n), acc, rng.integers(0, 2, n)))
+    _compare(oracle_lib, tb, qs, engine, label="wide-acc")
+
+
+def test_index_outgrows_lds_after_load_update(oracle_lib):
+    """At load every slice has a one-step staircase (row 0 of each task dominates the rest), so the
+    index fits in LDS.  A load report then pushes those rows out of reach: all staircases grow to
+    62 steps, the index no longer fits, and the queries of the slices left outside LDS are
+    finished from the index copy in global memory."""
+    T, n = 700, 62
+    tb = _staircase_table(T, n, B=1)
+    first = np.arange(T) * n
+    tb.acc_bp[first] = 5000          # most accurate ...
+    tb.lat_us[first, 0] = 10         # ... and fastest, and it is the cheapest row of its task
+    rng = np.random.default_rng(21)
+    sel = make_selector(tb, engine=0)
+    assert sel.info()["index_in_lds"] == 1 and sel.info()["index_max_steps"] == 1
+    qs = _staircase_queries(rng, tb, 200_000, n)
+    got = gpu_select(sel, *qs)
+    assert np.array_equal(got, oracle_lib.select(*table_args(tb), *qs))
+    queue = tb.queue_us.copy()
+    idx = first.astype(np.int32); val = np.full(T, 2_000_000_000, np.int32)
+    sel.update_load(to_dev(idx), to_dev(val))
+    oracle_lib.update_load(queue, idx, val)
+    got = gpu_select(sel, *qs)
+    want = oracle_lib.select(*table_args(tb, queue), *qs)
+    assert np.array_equal(got, want)
+    assert (want >= 0).mean() > 0.3 and len(np.unique(want)) > 1000
+    sel.destroy()
+
+
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
+def test_unaligned_query_arrays(oracle_lib, engine):
+    """Query and result arrays that start 4 bytes into an allocation (not 16-byte aligned)."""
+    import torch
+    tb = workloads.make_table(1)
+    q = workloads.make_queries(1, n=70_001)
+    sel = make_selector(tb, engine=engine)
+    dev = [torch.cat([torch.zeros(1, dtype=torch.int32), torch.from_numpy(x)]).cuda()[1:] for x in query_args(q)]
+    out = torch.full((q.N + 1,), -7, dtype=torch.int32, device="cuda")[1:]
+    assert dev[0].data_ptr() % 16 == 4
+    sel.select(*dev, out, n=q.N)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), oracle_lib.select(*table_args(tb), *query_args(q)))
+    sel.destroy()
+
+
 def test_error_codes():
     import torch
     import paper_1905_13348_amd as lib
