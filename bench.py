@@ -25,8 +25,34 @@ UPDATE_BYTES = 8                 # one (row, value) pair of a load report
 
 
 def table_bytes(tb) -> int:
-    """Variant store read once per call: acc, queue, orig-free static columns (12 + 8B bytes/row)."""
+    """Variant store, counted once per call: accuracy, queue and row of every variant plus its
+    latency and cost at every batch size (12 + 8 B bytes per variant)."""
     return tb.V * (12 + 8 * tb.B)
+
+
+def kernel_source_digest() -> str:
+    """Digest of the HIP sources; counter readings are only valid for the code they were taken on."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_1905_13348_amd", "csrc", "*"))):
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(kernel: str, cfg: int, engine: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc readings
+    (profiles/traffic.json), or None when there are none for this workload or the kernels have
+    changed since they were taken."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        rec = json.load(f)
+    if rec.get("source_digest") != kernel_source_digest():
+        return None
+    return rec.get("bytes_per_launch", {}).get(f"config{cfg}/{engine}/{kernel}")
 
 
 def main() -> int:
@@ -38,6 +64,9 @@ def main() -> int:
     ap.add_argument("--engine", default="auto", choices=["auto", "scan"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device-to-device copy of 256 MiB a few times (reference for "
+                         "scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; queries would shard across GPUs with no "
@@ -51,6 +80,14 @@ def main() -> int:
     import workloads
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.calibrate_copy:
+        src = torch.arange(64 * 1024 * 1024, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4}))
+        return 0
     cfg = args.config
     spec = workloads.config_spec(cfg)
     tb = workloads.make_table(cfg)
@@ -102,10 +139,16 @@ def main() -> int:
     dom = max(active, key=lambda k: active[k]["total_ms"])
     dom_avg_ms = active[dom]["total_ms"] / active[dom]["launches"]
     launches_per_step = active[dom]["launches"] / args.steps
-    algo_bytes = (BYTES_PER_DECISION * per_step + table_bytes(tb)) / launches_per_step
+    if dom == "index_build":     # reads the rank-ordered accuracy and latency+queue columns once
+        algo_bytes = 8 * tb.B * tb.V
+    elif dom == "update_load":
+        algo_bytes = UPDATE_BYTES * updates[0][2].variant_idx.size
+    else:                        # a select kernel: every query in, every result out, the table once
+        algo_bytes = (BYTES_PER_DECISION * per_step + table_bytes(tb)) / launches_per_step
     achieved = algo_bytes / (dom_avg_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
+                "traffic": measured_traffic(dom, cfg, args.engine),
                 "avg_kernel_ms": round(dom_avg_ms, 5),
                 "algorithmic_bytes_per_launch": int(algo_bytes)}
     whole_bytes = BYTES_PER_DECISION * per_step + table_bytes(tb) + \

@@ -51,15 +51,16 @@ enum {
 /* infaas_sel_config.flags, bits 0-3: which search runs inside infaas_sel_select. */
 enum {
     /* Default: the staircase index (per slice, the variants no cheaper variant dominates; a
-     * query is two binary searches and a bit-set intersection) when it fits in one compute
-     * unit's LDS, the exhaustive scan otherwise.  Queries the index cannot decide (its
-     * per-slice capacity was exceeded) are finished by a rank-ordered scan inside the same
-     * kernel, so results never depend on the engine. */
+     * query is two binary searches and a bit-set intersection), mirrored in one compute unit's
+     * LDS when it fits and read from global memory otherwise.  Queries the index cannot decide
+     * (its per-slice capacity was exceeded) are finished by a rank-ordered scan inside the same
+     * kernel, so results never depend on the engine.  If more than half of the slices exceed the
+     * capacity when the table is loaded, the exhaustive scan is used instead. */
     INFAAS_SEL_ENGINE_AUTO = 0,
     /* Exhaustive scan only: queries bucketed by (task, batch) slice, slice staged in LDS,
      * feasibility filter and wavefront min-reduction over every variant of the slice. */
     INFAAS_SEL_ENGINE_SCAN = 1,
-    /* Staircase index always, read from global memory when it does not fit in LDS. */
+    /* Staircase index always. */
     INFAAS_SEL_ENGINE_INDEX = 2
 };
 #define INFAAS_SEL_ENGINE_MASK 0xFu

@@ -282,7 +282,11 @@ bool use_index(const infaas_sel *h)
     const uint32_t engine = h->flags & INFAAS_SEL_ENGINE_MASK;
     if (!h->have_index || engine == INFAAS_SEL_ENGINE_SCAN) return false;
     if (engine == INFAAS_SEL_ENGINE_INDEX) return true;
-    return h->index_lds_bytes > 0;  // auto: the index when it fits in LDS, the scan otherwise
+    // auto: the index (mirrored in LDS when it fits, read from global memory otherwise), unless
+    // at load time more than half of the slices could not be indexed completely -- their queries
+    // would mostly end in the in-kernel scan, which the bucketed scan engine does faster
+    const int64_t S = (int64_t)h->T * h->B;
+    return 2 * ((int64_t)h->ix_stats[3] + h->ix_stats[4]) <= S;
 }
 
 // One pass of the scan engine over n <= 2^28 queries.
