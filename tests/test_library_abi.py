@@ -46,6 +46,29 @@ def test_status_text():
     lib.infaas_sel_destroy(None)
 
 
+def test_create_rejects_bad_configs_before_touching_a_device():
+    """Argument checks of infaas_sel_create come before any HIP call, so they work without a GPU."""
+    import ctypes
+    import paper_1905_13348_amd as pkg
+    from paper_1905_13348_amd.binding import _Config
+    if not os.path.exists(pkg.library_path()):
+        pytest.skip("library not built here")
+    lib = pkg.load_library()
+    h = ctypes.c_void_p()
+    assert lib.infaas_sel_create(None, ctypes.byref(h)) == -1
+    for kw in (dict(num_tasks=0, num_batch_sizes=1), dict(num_tasks=1, num_batch_sizes=0),
+               dict(num_tasks=1, num_batch_sizes=65), dict(num_tasks=1 << 22, num_batch_sizes=8),
+               dict(num_tasks=1, num_batch_sizes=1, flags=7), dict(num_tasks=1, num_batch_sizes=1, flags=16),
+               dict(num_tasks=1, num_batch_sizes=1, lds_segment_limit=63),
+               dict(num_tasks=1, num_batch_sizes=1, lds_segment_limit=9000)):
+        cfg = _Config(batch_sizes=None, device=0, **kw)
+        assert lib.infaas_sel_create(ctypes.byref(cfg), ctypes.byref(h)) == -1, kw
+        assert not h.value
+    assert lib.infaas_sel_load_variants(None, 0, None, None, None, None, None) == -1
+    assert lib.infaas_sel_reserve(None, 10) == -1
+    assert lib.infaas_sel_get_info(None, None) == -1
+
+
 def test_product_does_not_touch_the_oracle():
     """The package and the C/HIP sources never import, include or name the oracle."""
     pkg_dir = os.path.join(ROOT, "paper_1905_13348_amd")
