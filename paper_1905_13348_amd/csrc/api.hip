@@ -80,8 +80,8 @@ struct infaas_sel {
     bool have_index = false;
     uint32_t index_lds_bytes = 0;     // dynamic LDS of the lookup kernel; 0 = read the index from global memory
     uint32_t ix_stats[8] = {0};       // copy of ix.ctrl taken after the build at load time
-    int32_t *d_defer = nullptr;
-    int64_t defer_capacity = 0;
+    int32_t *d_park = nullptr;        // queues of parked queries of the lookup kernel (fixed size)
+    int64_t park_bytes = 0;
 
     // scan scratch
     ScanScratch sc{};
@@ -114,6 +114,9 @@ struct infaas_sel {
     void free_index()
     {
         (void)hipFree(ix.pool); (void)hipFree(ix.step_row); (void)hipFree(ix.ctrl);  // hdr lives in pool's allocation
+        (void)hipFree(d_park);
+        d_park = nullptr;
+        park_bytes = 0;
         ix = IndexView{};
         have_index = false;
         index_lds_bytes = 0;
@@ -123,9 +126,6 @@ struct infaas_sel {
         (void)hipFree(sc.cnt); (void)hipFree(sc.bucket_off); (void)hipFree(sc.cursor);
         (void)hipFree(sc.tile_off); (void)hipFree(sc.wide_off); (void)hipFree(sc.counters);
         (void)hipFree(sc.recs); (void)hipFree(sc.best);
-        (void)hipFree(d_defer);
-        d_defer = nullptr;
-        defer_capacity = 0;
         sc = ScanScratch{};
         sc_capacity = 0;
         sc_slices = 0;
@@ -215,6 +215,9 @@ int create_index(infaas_sel *h)
               dev_alloc(&ix.step_row, ix.step_cap) == hipSuccess && dev_alloc(&ix.ctrl, 8) == hipSuccess;
     ix.hdr = ok ? (uint4 *)(ix.pool + ix.pool_bytes) : nullptr;
     h->ix = ix;
+    const size_t park = index_park_bytes(h->num_cus);
+    ok = ok && dev_alloc(&h->d_park, park / 4) == hipSuccess;
+    h->park_bytes = ok ? (int64_t)park : 0;
     if (!ok) {
         h->free_index();
         (void)hipGetLastError();
@@ -259,20 +262,8 @@ int create_index(infaas_sel *h)
 // One pass of the index engine over n <= 2^28 queries.
 int index_pass(infaas_sel *h, const QueryView &q, hipStream_t st)
 {
-    const int64_t need = (int64_t)q.n + (int64_t)(index_select_blocks(h->num_cus) + 2) * kIndexTile;
-    if (h->defer_capacity < need) {
-        if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
-        (void)hipFree(h->d_defer);
-        h->d_defer = nullptr;
-        h->defer_capacity = 0;
-        if (dev_alloc(&h->d_defer, (size_t)need) != hipSuccess) {
-            (void)hipGetLastError();
-            return INFAAS_SEL_ERR_OOM;
-        }
-        h->defer_capacity = need;
-    }
     LaunchTimer t(h, INFAAS_SEL_K_INDEX_SELECT, st);
-    if (!HIP_OK(launch_index_select(h->tv, h->ix, q, h->d_defer, h->index_lds_bytes, h->num_cus, st)))
+    if (!HIP_OK(launch_index_select(h->tv, h->ix, q, h->d_park, h->index_lds_bytes, h->num_cus, st)))
         return INFAAS_SEL_ERR_HIP;
     return INFAAS_SEL_OK;
 }
@@ -596,20 +587,7 @@ int infaas_sel_reserve(infaas_sel_t *h, int64_t max_queries)
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     const int64_t cap = std::max<int64_t>(1, std::min(max_queries, kMaxPass));
-    if (h->loaded && use_index(h)) {
-        const int64_t need = cap + (int64_t)(index_select_blocks(h->num_cus) + 2) * kIndexTile;
-        if (h->defer_capacity >= need) return INFAAS_SEL_OK;
-        if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
-        (void)hipFree(h->d_defer);
-        h->d_defer = nullptr;
-        h->defer_capacity = 0;
-        if (dev_alloc(&h->d_defer, (size_t)need) != hipSuccess) {
-            (void)hipGetLastError();
-            return INFAAS_SEL_ERR_OOM;
-        }
-        h->defer_capacity = need;
-        return INFAAS_SEL_OK;
-    }
+    if (h->loaded && use_index(h)) return INFAAS_SEL_OK;   // the index engine needs no per-query scratch
     return ensure_scratch(h, cap);
 }
 
@@ -675,7 +653,7 @@ int infaas_sel_get_info(infaas_sel_t *h, infaas_sel_info *out)
     out->lds_segment_limit = h->lds_limit;
     out->wide_segments = h->wide_segments;
     out->table_bytes = h->table_bytes;
-    out->scratch_bytes = h->scratch_bytes + h->defer_capacity * 4;
+    out->scratch_bytes = h->scratch_bytes + h->park_bytes;
     if (h->have_index) {
         out->index_in_lds = h->index_lds_bytes > 0 ? 1 : 0;
         out->index_truncated = (int32_t)(h->ix_stats[3] + h->ix_stats[4]);

@@ -11,9 +11,10 @@
 //                    5-probe binary searches in LDS, two bit-set reads, one AND and one count-
 //                    trailing-zeros.  Queries the first body of their slice cannot decide (no
 //                    fitting step among its first 31, slice not resident, staircase truncated)
-//                    are parked and finished by the same workgroup: second body, index copy in
-//                    global memory, and last a wavefront-wide scan of the rank-ordered slice that
-//                    stops at the first feasible variant.
+//                    are parked in a queue of the wavefront and finished by it, 64 at a time or
+//                    when it runs out of work: second body, index copy in global memory, and last
+//                    a wavefront-wide scan of the rank-ordered slice that stops at the first
+//                    feasible variant.
 #include "internal.h"
 
 namespace infaas {
@@ -28,6 +29,7 @@ constexpr int kSelThreads = 1024;
 #define INFAAS_PER_THREAD 4
 #endif
 constexpr int kPerThread = INFAAS_PER_THREAD;   // queries per lane and tile (4 or 8)
+constexpr int kWaveQueue = 64 + 64 * kPerThread;   // parked queries a wavefront can hold: a full pass plus one unit
 
 __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
 {
@@ -338,11 +340,9 @@ __device__ __forceinline__ uint32_t acc_threshold(int32_t min_acc, int32_t acc_b
 
 template <bool kLds>
 __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, IndexView ix, QueryView q,
-                                                              int32_t *__restrict__ defer_q,
-                                                              uint32_t lds_cap, int32_t per_block_cap)
+                                                              int32_t *__restrict__ park_mem, uint32_t lds_cap)
 {
     extern __shared__ __align__(16) uint32_t lds_w[];  // [16 B control][S + 1 headers][lds_cap bytes of bodies]
-    uint32_t &s_defer = lds_w[0];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t nhdr = (uint32_t)tv.S + 1u;
     const uint32_t hdr_bytes = kLds ? lds_header_bytes(tv.S) : 0u;
@@ -401,7 +401,10 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     const int nit = 32 - __builtin_clz(max_k | 1u);    // <= 5
     const LdsMem lmem{};
     const GlobalMem gmem{ix.pool};
-    int32_t *region = defer_q + (int64_t)blockIdx.x * per_block_cap;   // parked queries of this workgroup
+    // Parked queries of this wavefront: (query, latency bound, accuracy bound, slice) records in a
+    // queue of its own in global memory, written and read by this wavefront only.
+    v4i *wq = (v4i *)park_mem + ((int64_t)blockIdx.x * (kSelThreads / 64) + wave) * kWaveQueue;
+    uint32_t cnt = 0;   // records in the queue (wave-uniform)
 
     const bool aligned = ((((uintptr_t)q.task) | ((uintptr_t)q.slo) | ((uintptr_t)q.min_acc) |
                            ((uintptr_t)q.bidx) | ((uintptr_t)q.out)) & 15u) == 0;
@@ -484,13 +487,14 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         load_unit(far, next_unit());
         // slice header; queries outside the table use the header of the empty slice (entry S)
         uint32_t body[kPerThread], y[kPerThread], rec[kPerThread], keys[kPerThread], dd[kPerThread],
-            lim[kPerThread], m[kPerThread];
+            lim[kPerThread], m[kPerThread], sl_of[kPerThread];
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) {
             const uint32_t ok = ((uint32_t)cur.tk[k] < (uint32_t)tv.T) & ((uint32_t)cur.bi[k] < (uint32_t)tv.B) &
                                 (uint32_t)(cur.sl[k] >= 0);
             const uint32_t s = ok ? __umul24((uint32_t)cur.tk[k], (uint32_t)tv.B) + (uint32_t)cur.bi[k]
                                   : (uint32_t)tv.S;
+            sl_of[k] = s;
             if (kLds) {
                 const v2u h = lmem.ld64(lds_hdr0 + s * kLdsHdrBytes);
                 body[k] = h.x; y[k] = h.y; rec[k] = h.y & 0xFFFFu;
@@ -527,60 +531,49 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) {
             const uint64_t mask = __ballot(df[k]);
-            if (mask) {
-                const int leader = (int)__builtin_ctzll(mask);
-                uint32_t base = 0;
-                if (lane == leader) base = atomicAdd(&s_defer, (uint32_t)__builtin_popcountll(mask));
-                base = (uint32_t)__builtin_amdgcn_readlane((int)base, leader);
-                if (df[k]) region[base + lanes_below(mask)] = i0 + k;
+            if (mask) {   // parked queries are always inside the table
+                if (df[k]) wq[cnt + lanes_below(mask)] = v4i{i0 + k, cur.sl[k], cur.am[k], (int32_t)sl_of[k]};
+                cnt += (uint32_t)__builtin_popcountll(mask);
             }
         }
     };
-    {
-        Fields fa, fb, fc;   // three buffers in rotation: searched now, next, the one after
-        load_unit(fa, next_unit());
-        load_unit(fb, next_unit());
-        for (;;) {
-            if (fa.unit < 0) break;
-            stage(fa, fc);
-            if (fb.unit < 0) break;
-            stage(fb, fa);
-            if (fc.unit < 0) break;
-            stage(fc, fb);
-        }
-        store_unit();   // a parked query gets -1 here and its real answer below, after the barrier
-    }
-
-    // ---- parked queries (all of them are inside the table)
-    __syncthreads();
-    const uint32_t nd = s_defer;
-    for (uint32_t j0 = wave * 64; j0 < nd; j0 += kSelThreads) {
-        const uint32_t j = j0 + lane;
-        const bool have = j < nd;
-        const int32_t qi = have ? __hip_atomic_load(&region[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
-        const int32_t task = q.task[qi], slo = q.slo[qi], min_acc = q.min_acc[qi], bidx = q.bidx[qi];
-        const uint32_t s = have ? __umul24((uint32_t)task, (uint32_t)tv.B) + (uint32_t)bidx : (uint32_t)tv.S;
-        const uint4 g = ix.hdr[s];
-        const bool indexed = !(g.y & kHdrPark);
+    // Finishes `count` <= 64 parked queries, records [first, first + count) of the queue.
+    auto drain = [&](uint32_t first, uint32_t count) {
+        // The records, and the "nothing feasible" stored for these queries by the main loop, must
+        // have left this wavefront before they are read back and overwritten.  Writer and reader are
+        // the same wavefront, so workgroup scope is enough (a wider release would write back L2).
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        const bool have = (uint32_t)lane < count;
+        const int32_t *e = (const int32_t *)(wq + first + (have ? lane : 0));
+        const int32_t qi = __hip_atomic_load(e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const int32_t slo = __hip_atomic_load(e + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const int32_t min_acc = __hip_atomic_load(e + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const int32_t s_ld = __hip_atomic_load(e + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const uint32_t s = have ? (uint32_t)s_ld : (uint32_t)tv.S;   // idle lanes: the empty slice
+        uint32_t y = 0, rec = 0, lbody = rebase, gbody = 0;
         bool resident = false;
-        uint32_t lbody = rebase;
         if (kLds) {
             const v2u h = lmem.ld64(lds_hdr0 + s * kLdsHdrBytes);
             resident = !(h.y & kHdrPark);
-            lbody = h.x;
+            lbody = h.x; y = h.y; rec = h.y & 0xFFFFu;
         }
-        const uint32_t keys0 = (g.y >> kHdrK0Shift) & 0x3Fu, keys1 = (g.y >> kHdrK1Shift) & 0x3Fu;
+        if (__ballot(!resident)) {   // slices without a body in LDS: header from global memory
+            const uint4 g = ix.hdr[resident ? (uint32_t)tv.S : s];
+            if (!resident) { y = g.y; rec = g.z; gbody = g.x; }
+        }
+        const bool indexed = !(y & kHdrPark);
+        const uint32_t keys0 = (y >> kHdrK0Shift) & 0x3Fu, keys1 = (y >> kHdrK1Shift) & 0x3Fu;
         const uint32_t size0 = body_bytes(keys0, keys0 - 1u < ix.hot_rows ? keys0 - 1u : ix.hot_rows);
         const uint32_t dd[1] = {acc_threshold(min_acc, tv.acc_base)}, lim[1] = {(uint32_t)slo};
         int32_t ans = -1;
         bool done = false;
-        // first body from global memory: only if the main loop could not use the LDS copy
+        // first body from global memory: only if the main loop could not use an LDS copy
         const bool need_g0 = have && indexed && kLds && !resident;
         if (__ballot(need_g0)) {
-            const uint32_t bd[1] = {need_g0 ? g.x : 0u}, ks[1] = {need_g0 ? keys0 : 1u};
+            const uint32_t bd[1] = {need_g0 ? gbody : 0u}, ks[1] = {need_g0 ? keys0 : 1u};
             uint32_t m[1];
             search_bodies<1>(gmem, nit, bd, ks, dd, lim, m);
-            if (need_g0 && m[0]) { ans = ix.step_row[g.z + __builtin_ctz(m[0])]; done = true; }
+            if (need_g0 && m[0]) { ans = ix.step_row[rec + __builtin_ctz(m[0])]; done = true; }
         }
         // second body: LDS copy when resident, global memory otherwise
         const bool need1 = have && indexed && keys1 != 0u && !done;
@@ -589,34 +582,74 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             const uint32_t bd[1] = {need_l1 ? lbody + size0 : rebase}, ks[1] = {need_l1 ? keys1 : 1u};
             uint32_t m[1];
             search_bodies<1>(lmem, nit, bd, ks, dd, lim, m);
-            if (need_l1 && m[0]) { ans = ix.step_row[g.z + kBodySteps + __builtin_ctz(m[0])]; done = true; }
+            if (need_l1 && m[0]) { ans = ix.step_row[rec + kBodySteps + __builtin_ctz(m[0])]; done = true; }
         }
         if (__ballot(need_g1)) {
-            const uint32_t bd[1] = {need_g1 ? g.x + size0 : 0u}, ks[1] = {need_g1 ? keys1 : 1u};
+            const uint32_t bd[1] = {need_g1 ? gbody + size0 : 0u}, ks[1] = {need_g1 ? keys1 : 1u};
             uint32_t m[1];
             search_bodies<1>(gmem, nit, bd, ks, dd, lim, m);
-            if (need_g1 && m[0]) { ans = ix.step_row[g.z + kBodySteps + __builtin_ctz(m[0])]; done = true; }
+            if (need_g1 && m[0]) { ans = ix.step_row[rec + kBodySteps + __builtin_ctz(m[0])]; done = true; }
         }
         // no body, or both bodies missed and more steps exist: scan the slice in rank order
-        uint64_t todo = __ballot(have && !done && (!indexed || (g.y & kHdrTrunc)));
-        while (todo) {
-            const int l = __builtin_ctzll(todo);
-            todo &= todo - 1;
-            const int32_t t = __builtin_amdgcn_readlane(task, l), b = __builtin_amdgcn_readlane(bidx, l);
-            const int32_t am = __builtin_amdgcn_readlane(min_acc, l);
-            const uint32_t bound = (uint32_t)__builtin_amdgcn_readlane(slo, l);
-            const int32_t seg = tv.seg_off[t], L = tv.seg_len[t];
-            const int64_t col = (int64_t)b * tv.Vp + seg;
-            int32_t found = -1;
-            for (int32_t blk = 0; blk < L; blk += 64) {
-                const int32_t pos = blk + lane;
-                const bool ok = pos < L && tv.acc_r[col + pos] >= am && tv.tot_r[col + pos] <= bound;
-                const uint64_t bm = __ballot(ok);
-                if (bm) { found = blk + (int32_t)__builtin_ctzll(bm); break; }
+        uint64_t todo = __ballot(have && !done && (!indexed || (y & kHdrTrunc)));
+        if (todo) {
+            const int32_t task = (int32_t)(s / (uint32_t)tv.B), bidx = (int32_t)(s - (uint32_t)task * (uint32_t)tv.B);
+            while (todo) {
+                const int l = __builtin_ctzll(todo);
+                todo &= todo - 1;
+                const int32_t t = __builtin_amdgcn_readlane(task, l), b = __builtin_amdgcn_readlane(bidx, l);
+                const int32_t am = __builtin_amdgcn_readlane(min_acc, l);
+                const uint32_t bound = (uint32_t)__builtin_amdgcn_readlane(slo, l);
+                const int32_t seg = tv.seg_off[t], L = tv.seg_len[t];
+                const int64_t col = (int64_t)b * tv.Vp + seg;
+                int32_t found = -1;
+                for (int32_t blk = 0; blk < L; blk += 64) {
+                    const int32_t pos = blk + lane;
+                    const bool ok = pos < L && tv.acc_r[col + pos] >= am && tv.tot_r[col + pos] <= bound;
+                    const uint64_t bm = __ballot(ok);
+                    if (bm) { found = blk + (int32_t)__builtin_ctzll(bm); break; }
+                }
+                if (lane == l) ans = found >= 0 ? tv.orig_r[col + found] : -1;
             }
-            if (lane == l) ans = found >= 0 ? tv.orig_r[col + found] : -1;
         }
         if (have) q.out[qi] = ans;
+    };
+
+    {
+        Fields fa, fb, fc;   // three buffers in rotation: searched now, next, the one after
+        load_unit(fa, next_unit());
+        load_unit(fb, next_unit());
+        // The rotation is interrupted only when 64 parked queries have collected (one full pass of
+        // the wavefront) and resumed where it stopped.
+        int phase = 0;
+        bool more = true;
+        while (more) {
+            for (;;) {
+                if (phase == 0) {
+                    if (fa.unit < 0) { more = false; break; }
+                    stage(fa, fc);
+                    phase = 1;
+                    if (cnt >= 64u) break;
+                }
+                if (phase == 1) {
+                    if (fb.unit < 0) { more = false; break; }
+                    stage(fb, fa);
+                    phase = 2;
+                    if (cnt >= 64u) break;
+                }
+                if (fc.unit < 0) { more = false; break; }
+                stage(fc, fb);
+                phase = 0;
+                if (cnt >= 64u) break;
+            }
+            store_unit();   // a parked query gets -1 here and its real answer in drain()
+            p_i0 = -1;
+            while (cnt >= 64u || (!more && cnt > 0u)) {
+                const uint32_t c = cnt < 64u ? cnt : 64u;
+                drain(cnt - c, c);
+                cnt -= c;
+            }
+        }
     }
 }
 
@@ -633,22 +666,24 @@ hipError_t launch_index_build(const TableView &tv, const IndexView &ix, hipStrea
 
 int index_select_blocks(int num_cus) { return num_cus; }
 
+size_t index_park_bytes(int num_cus)
+{
+    return (size_t)index_select_blocks(num_cus) * (kSelThreads / 64) * kWaveQueue * sizeof(v4i);
+}
+
 hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const QueryView &q,
-                               int32_t *defer_q, uint32_t lds_bytes, int num_cus, hipStream_t st)
+                               int32_t *park_mem, uint32_t lds_bytes, int num_cus, hipStream_t st)
 {
     const int blocks = index_select_blocks(num_cus);
-    const int32_t nunits = (q.n + 64 * kPerThread - 1) / (64 * kPerThread);
-    const int32_t per_block_cap = ((nunits + blocks - 1) / blocks + 1) * 64 * kPerThread;
     if (lds_bytes > 0) {
         const uint32_t fixed = kLdsCtrlBytes + lds_header_bytes(tv.S);
         lds_bytes = fixed + ((lds_bytes - fixed) & ~15u);
         hipError_t e = hipFuncSetAttribute((const void *)k_index_select<true>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
-        k_index_select<true><<<blocks, kSelThreads, lds_bytes, st>>>(tv, ix, q, defer_q, lds_bytes - fixed,
-                                                                    per_block_cap);
+        k_index_select<true><<<blocks, kSelThreads, lds_bytes, st>>>(tv, ix, q, park_mem, lds_bytes - fixed);
     } else {
-        k_index_select<false><<<blocks, kSelThreads, kLdsCtrlBytes, st>>>(tv, ix, q, defer_q, 0u, per_block_cap);
+        k_index_select<false><<<blocks, kSelThreads, kLdsCtrlBytes, st>>>(tv, ix, q, park_mem, 0u);
     }
     return hipGetLastError();
 }

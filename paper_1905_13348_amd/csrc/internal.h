@@ -127,9 +127,11 @@ hipError_t launch_finish_wide(const TableView &tv, const QueryView &q, const Sca
 // Kernel launchers (staircase index).
 hipError_t launch_index_build(const TableView &tv, const IndexView &ix, hipStream_t st);
 // lds_bytes: dynamic LDS of the lookup kernel when the index is mirrored in LDS, 0 to read it
-// from global memory.  defer_q holds at least n + blocks * kIndexTile entries.
+// from global memory.  park_mem: index_park_bytes() of device memory (16-byte aligned) for the
+// queues of parked queries; its size does not depend on the number of queries.
 hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const QueryView &q,
-                               int32_t *defer_q, uint32_t lds_bytes, int num_cus, hipStream_t st);
+                               int32_t *park_mem, uint32_t lds_bytes, int num_cus, hipStream_t st);
 int index_select_blocks(int num_cus);
+size_t index_park_bytes(int num_cus);
 
 }  // namespace infaas
