@@ -506,6 +506,8 @@ int infaas_sel_load_variants(infaas_sel_t *h, int32_t V, const int32_t *task_id,
     tv.gpos = h->d_gpos;
     tv.acc_base = 0;
     for (int64_t v = 0; v < V; ++v) tv.acc_base = (v == 0 || acc_bp[v] < tv.acc_base) ? acc_bp[v] : tv.acc_base;
+    // the lookup forms acc_base - 1; a slice that holds the one accuracy below this base is not indexed
+    if (tv.acc_base == INT32_MIN) tv.acc_base = INT32_MIN + 1;
     h->tv = tv;
     h->loaded = true;
     if ((h->flags & INFAAS_SEL_ENGINE_MASK) != INFAAS_SEL_ENGINE_SCAN) {

@@ -232,10 +232,11 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
     if (!scanner) return;
 
     // ---- phase B: one or two bodies of sorted keys and bit sets
-    int32_t hi = __builtin_amdgcn_readlane(st_acc, 0);
+    int32_t hi = __builtin_amdgcn_readlane(st_acc, 0), lo = hi;
     for (int32_t j = 1; j < K; ++j) {
         const int32_t aj = __builtin_amdgcn_readlane(st_acc, j);
         hi = aj > hi ? aj : hi;
+        lo = aj < lo ? aj : lo;
     }
     const int k0 = K < kBodySteps ? K : kBodySteps, k1 = K - k0;
     const uint32_t r0 = (uint32_t)k0 < ix.hot_rows ? (uint32_t)k0 : ix.hot_rows;
@@ -248,7 +249,7 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
     off = (uint32_t)__builtin_amdgcn_readfirstlane((int)off);
     rec = (uint32_t)__builtin_amdgcn_readfirstlane((int)rec);
     const bool fits = (uint64_t)off + size <= ix.pool_bytes && (uint64_t)rec + K <= ix.step_cap &&
-                      (int64_t)hi - (int64_t)tv.acc_base <= 65533;
+                      (int64_t)hi - (int64_t)tv.acc_base <= 65533 && lo >= tv.acc_base;   // 16-bit accuracy keys
     if (!fits) {  // no body: every query of this slice goes to the rank-ordered scan
         if (lane == 0) {
             ix.hdr[s] = make_uint4(0u, kEmptyHdrY | kHdrPark | kHdrTrunc, 0u, 0u);
@@ -311,13 +312,18 @@ __device__ __forceinline__ void search_bodies(const Mem &mem, int nit, const uin
 #pragma unroll
     for (int it = 4; it >= 0; --it) {
         if (it < nit) {
+            uint32_t ca[kN], ct[kN], ka[kN], kt[kN];
+#pragma unroll
+            for (int k = 0; k < kN; ++k) {   // all reads of a level first, so that they overlap
+                ca[k] = pa[k] + (2u << it);
+                ct[k] = pt[k] + (4u << it);
+                ka[k] = mem.ld16(ca[k] < la[k] ? ca[k] : la[k], 2u);
+                kt[k] = mem.ld32(ct[k] < lt[k] ? ct[k] : lt[k], 0u);
+            }
 #pragma unroll
             for (int k = 0; k < kN; ++k) {
-                const uint32_t ca = pa[k] + (2u << it), ct = pt[k] + (4u << it);
-                const uint32_t ka = mem.ld16(ca < la[k] ? ca : la[k], 2u);
-                const uint32_t kt = mem.ld32(ct < lt[k] ? ct : lt[k], 0u);
-                pa[k] = ka >= dd[k] ? ca : pa[k];
-                pt[k] = kt <= lim[k] ? ct : pt[k];
+                pa[k] = ka[k] >= dd[k] ? ca[k] : pa[k];
+                pt[k] = kt[k] <= lim[k] ? ct[k] : pt[k];
             }
         }
     }
@@ -331,11 +337,12 @@ __device__ __forceinline__ void search_bodies(const Mem &mem, int nit, const uin
     }
 }
 
-__device__ __forceinline__ uint32_t acc_threshold(int32_t min_acc, int32_t acc_base)
+// Accuracy bound in key space: keys are acc - acc_base + 1 >= 1, so the bound is
+// min_acc - acc_base + 1 limited to [1, 65536] (65536 is above every key).
+__device__ __forceinline__ uint32_t acc_threshold(int32_t min_acc, int32_t acc_base_m1)
 {
-    uint32_t d = (uint32_t)min_acc - (uint32_t)acc_base;
-    d = d < 65535u ? d : 65535u;
-    return min_acc > acc_base ? d + 1u : 1u;   // keys are acc - acc_base + 1 >= 1
+    const int32_t d = __builtin_elementwise_sub_sat(min_acc, acc_base_m1);   // acc_base_m1 = acc_base - 1
+    return (uint32_t)(d < 1 ? 1 : (d > 65536 ? 65536 : d));
 }
 
 template <bool kLds>
@@ -349,6 +356,52 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     const uint32_t lds_base = (uint32_t)(uintptr_t)(INFAAS_LDS uint32_t *)lds_w;
     const uint32_t lds_hdr0 = lds_base + kLdsCtrlBytes;
     const uint32_t rebase = lds_hdr0 + hdr_bytes;      // LDS address of pool offset 0
+    const bool aligned = ((((uintptr_t)q.task) | ((uintptr_t)q.slo) | ((uintptr_t)q.min_acc) |
+                           ((uintptr_t)q.bidx) | ((uintptr_t)q.out)) & 15u) == 0;
+    // Work units of one wavefront: 64 lanes x kPerThread consecutive queries.  The units are split
+    // evenly and contiguously over the workgroups; inside a workgroup the wavefronts draw them from
+    // a counter in LDS, because the wavefronts of a SIMD do not advance at the same speed.
+    constexpr int kUnit = 64 * kPerThread;
+    const int32_t nunits = (q.n + kUnit - 1) / kUnit;
+    const int32_t u_begin = (int32_t)(((int64_t)nunits * blockIdx.x) / gridDim.x);
+    const int32_t u_end = (int32_t)(((int64_t)nunits * (blockIdx.x + 1)) / gridDim.x);
+    // Query fields of one unit for this lane (unit < 0: nothing left; the fields then describe a
+    // query outside the table).
+    struct Fields {
+        int32_t tk[kPerThread], sl[kPerThread], am[kPerThread], bi[kPerThread], unit;
+    };
+    auto load_unit = [&](Fields &f, int32_t unit) {
+        f.unit = unit;
+        const int32_t i0 = unit * kUnit + lane * kPerThread;
+        if (unit < 0) {
+#pragma unroll
+            for (int k = 0; k < kPerThread; ++k) { f.tk[k] = -1; f.sl[k] = 0; f.am[k] = 0; f.bi[k] = 0; }
+        } else if (aligned && i0 + kPerThread <= q.n) {
+            const uint32_t off = (uint32_t)i0 * 4u;   // one 32-bit byte offset for all four arrays (n <= 2^28)
+#pragma unroll
+            for (int h = 0; h < kPerThread / 4; ++h) {
+                const v4i a = __builtin_nontemporal_load((const v4i *)((const char *)q.task + off) + h);
+                const v4i b = __builtin_nontemporal_load((const v4i *)((const char *)q.slo + off) + h);
+                const v4i c = __builtin_nontemporal_load((const v4i *)((const char *)q.min_acc + off) + h);
+                const v4i d = __builtin_nontemporal_load((const v4i *)((const char *)q.bidx + off) + h);
+                f.tk[4 * h] = a.x; f.tk[4 * h + 1] = a.y; f.tk[4 * h + 2] = a.z; f.tk[4 * h + 3] = a.w;
+                f.sl[4 * h] = b.x; f.sl[4 * h + 1] = b.y; f.sl[4 * h + 2] = b.z; f.sl[4 * h + 3] = b.w;
+                f.am[4 * h] = c.x; f.am[4 * h + 1] = c.y; f.am[4 * h + 2] = c.z; f.am[4 * h + 3] = c.w;
+                f.bi[4 * h] = d.x; f.bi[4 * h + 1] = d.y; f.bi[4 * h + 2] = d.z; f.bi[4 * h + 3] = d.w;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < kPerThread; ++k) {
+                const bool in = i0 + k < q.n;
+                f.tk[k] = in ? q.task[i0 + k] : -1;   // -1: outside the table, answered "nothing feasible"
+                f.sl[k] = in ? q.slo[i0 + k] : 0;
+                f.am[k] = in ? q.min_acc[i0 + k] : 0;
+                f.bi[k] = in ? q.bidx[i0 + k] : 0;
+            }
+        }
+    };
+
+    Fields fa, fb, fc;   // three buffers in rotation: searched now, next, the one after
     if (kLds) {
         // Mirror the index: all global loads of a lane (its headers and up to kFillDepth x 16 bytes
         // of bodies) are issued before the first LDS write, so the fill costs about one memory
@@ -394,9 +447,10 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             if ((uint32_t)wave * per_wave + c0 < nchunks && i < nvec) lp[i] = gp[i];
         }
     }
-    if (tid < 4) lds_w[tid] = 0;
+    if (tid < 4) lds_w[tid] = 0u;
     __syncthreads();
 
+    const int32_t acc_base_m1 = tv.acc_base - 1;   // acc_base is above INT32_MIN
     const uint32_t max_k = ix.ctrl[2];
     const int nit = 32 - __builtin_clz(max_k | 1u);    // <= 5
     const LdsMem lmem{};
@@ -406,15 +460,6 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     v4i *wq = (v4i *)park_mem + ((int64_t)blockIdx.x * (kSelThreads / 64) + wave) * kWaveQueue;
     uint32_t cnt = 0;   // records in the queue (wave-uniform)
 
-    const bool aligned = ((((uintptr_t)q.task) | ((uintptr_t)q.slo) | ((uintptr_t)q.min_acc) |
-                           ((uintptr_t)q.bidx) | ((uintptr_t)q.out)) & 15u) == 0;
-    // Work units of one wavefront: 64 lanes x kPerThread consecutive queries.  The units are split
-    // evenly and contiguously over the workgroups; inside a workgroup the wavefronts draw them from
-    // a counter in LDS, because the wavefronts of a SIMD do not advance at the same speed.
-    constexpr int kUnit = 64 * kPerThread;
-    const int32_t nunits = (q.n + kUnit - 1) / kUnit;
-    const int32_t u_begin = (int32_t)(((int64_t)nunits * blockIdx.x) / gridDim.x);
-    const int32_t u_end = (int32_t)(((int64_t)nunits * (blockIdx.x + 1)) / gridDim.x);
     uint32_t &s_next = lds_w[2];
     auto next_unit = [&]() -> int32_t {
         uint32_t u = 0;
@@ -423,41 +468,8 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         const int64_t unit = (int64_t)u_begin + u;
         return unit < u_end ? (int32_t)unit : -1;
     };
-    // Query fields of one unit for this lane (unit < 0: nothing left; the fields then describe a
-    // query outside the table).
-    struct Fields {
-        int32_t tk[kPerThread], sl[kPerThread], am[kPerThread], bi[kPerThread], unit;
-    };
-    auto load_unit = [&](Fields &f, int32_t unit) {
-        f.unit = unit;
-        const int32_t i0 = unit * kUnit + lane * kPerThread;
-        if (unit < 0) {
-#pragma unroll
-            for (int k = 0; k < kPerThread; ++k) { f.tk[k] = -1; f.sl[k] = 0; f.am[k] = 0; f.bi[k] = 0; }
-        } else if (aligned && i0 + kPerThread <= q.n) {
-#pragma unroll
-            for (int h = 0; h < kPerThread / 4; ++h) {
-                const v4i a = __builtin_nontemporal_load((const v4i *)(q.task + i0) + h);
-                const v4i b = __builtin_nontemporal_load((const v4i *)(q.slo + i0) + h);
-                const v4i c = __builtin_nontemporal_load((const v4i *)(q.min_acc + i0) + h);
-                const v4i d = __builtin_nontemporal_load((const v4i *)(q.bidx + i0) + h);
-                f.tk[4 * h] = a.x; f.tk[4 * h + 1] = a.y; f.tk[4 * h + 2] = a.z; f.tk[4 * h + 3] = a.w;
-                f.sl[4 * h] = b.x; f.sl[4 * h + 1] = b.y; f.sl[4 * h + 2] = b.z; f.sl[4 * h + 3] = b.w;
-                f.am[4 * h] = c.x; f.am[4 * h + 1] = c.y; f.am[4 * h + 2] = c.z; f.am[4 * h + 3] = c.w;
-                f.bi[4 * h] = d.x; f.bi[4 * h + 1] = d.y; f.bi[4 * h + 2] = d.z; f.bi[4 * h + 3] = d.w;
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < kPerThread; ++k) {
-                const bool in = i0 + k < q.n;
-                f.tk[k] = in ? q.task[i0 + k] : -1;   // -1: outside the table, answered "nothing feasible"
-                f.sl[k] = in ? q.slo[i0 + k] : 0;
-                f.am[k] = in ? q.min_acc[i0 + k] : 0;
-                f.bi[k] = in ? q.bidx[i0 + k] : 0;
-            }
-        }
-    };
-
+    load_unit(fa, next_unit());
+    load_unit(fb, next_unit());
     // Software pipeline.  A wavefront waits for memory once per unit, at the top, where it needs the
     // unit's query fields; that wait also covers everything requested before it.  The rows gathered
     // for a unit are therefore consumed, and its results stored, only after the NEXT unit's wait --
@@ -472,7 +484,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
 #pragma unroll
             for (int h = 0; h < kPerThread / 4; ++h) {
                 const v4i r = {p_val(4 * h), p_val(4 * h + 1), p_val(4 * h + 2), p_val(4 * h + 3)};
-                __builtin_nontemporal_store(r, (v4i *)(q.out + p_i0) + h);
+                __builtin_nontemporal_store(r, (v4i *)((char *)q.out + (uint32_t)p_i0 * 4u) + h);
             }
         } else {
 #pragma unroll
@@ -503,7 +515,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                 body[k] = h.x; y[k] = h.y; rec[k] = h.z;
             }
             keys[k] = (y[k] >> kHdrK0Shift) & 0x3Fu;
-            dd[k] = acc_threshold(cur.am[k], tv.acc_base);
+            dd[k] = acc_threshold(cur.am[k], acc_base_m1);
             lim[k] = (uint32_t)cur.sl[k];
         }
         if (kLds) search_bodies<kPerThread>(lmem, nit, body, keys, dd, lim, m);
@@ -521,7 +533,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             const bool inl = hit && step < r0;
             const uint32_t at = inl ? body[k] + 14u * re + 4u * step : body[k];
             p_lrow[k] = kLds ? (int32_t)lmem.ld32(at, 4u) : (int32_t)gmem.ld32(at, 4u);
-            p_grow[k] = ix.step_row[(hit && !inl) ? rec[k] + step : 0u];
+            p_grow[k] = *(const int32_t *)((const char *)ix.step_row + ((hit && !inl) ? (rec[k] + step) * 4u : 0u));
             p_hit[k] = hit;
             p_inl[k] = inl;
             // parked: unusable slice, or a miss that the second body / the scan may still turn into a hit
@@ -564,7 +576,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         const bool indexed = !(y & kHdrPark);
         const uint32_t keys0 = (y >> kHdrK0Shift) & 0x3Fu, keys1 = (y >> kHdrK1Shift) & 0x3Fu;
         const uint32_t size0 = body_bytes(keys0, keys0 - 1u < ix.hot_rows ? keys0 - 1u : ix.hot_rows);
-        const uint32_t dd[1] = {acc_threshold(min_acc, tv.acc_base)}, lim[1] = {(uint32_t)slo};
+        const uint32_t dd[1] = {acc_threshold(min_acc, acc_base_m1)}, lim[1] = {(uint32_t)slo};
         int32_t ans = -1;
         bool done = false;
         // first body from global memory: only if the main loop could not use an LDS copy
@@ -616,9 +628,6 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     };
 
     {
-        Fields fa, fb, fc;   // three buffers in rotation: searched now, next, the one after
-        load_unit(fa, next_unit());
-        load_unit(fb, next_unit());
         // The rotation is interrupted only when 64 parked queries have collected (one full pass of
         // the wavefront) and resumed where it stopped.
         int phase = 0;

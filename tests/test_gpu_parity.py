@@ -229,6 +229,30 @@ def test_accuracy_range_too_wide_for_the_index(oracle_lib, engine):
     _compare(oracle_lib, tb, qs, engine, label="wide-acc")
 
 
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
+def test_extreme_accuracies(oracle_lib, engine):
+    """The smallest and largest int32 as accuracies, in the table and in the queries: task 0 holds
+    a variant at INT32_MIN (the index keeps no key for it, the scan answers its slices), task 1
+    spans a narrow range just below INT32_MAX, task 2 a narrow range just above INT32_MIN + 1."""
+    rng = np.random.default_rng(77)
+    lo, hi = np.iinfo(np.int32).min, np.iinfo(np.int32).max
+    a = _staircase_table(1, 20)
+    acc0 = a.acc_bp.astype(np.int64).copy(); acc0[:] = lo + 1 + np.arange(20) * 3; acc0[0] = lo
+    acc1 = hi - 3 * np.arange(20)[::-1].astype(np.int64)
+    acc2 = lo + 1 + 5 * np.arange(20).astype(np.int64)
+    tb = _table(3, [1, 2], np.concatenate([a.task_id, a.task_id + 1, a.task_id + 2]),
+                np.concatenate([acc0, acc1, acc2]), np.concatenate([a.lat_us] * 3),
+                np.concatenate([a.cost] * 3), np.concatenate([a.queue_us] * 3))
+    n = 30_000
+    task = rng.integers(0, 3, n)
+    near_lo = lo + rng.integers(0, 120, n)
+    near_hi = hi - rng.integers(0, 80, n)
+    acc = np.where(task == 1, np.where(rng.random(n) < 0.8, near_hi, near_lo),
+                   np.where(rng.random(n) < 0.8, near_lo, near_hi))
+    qs = tuple(np.asarray(x, np.int32) for x in (task, rng.integers(90_000, 101_000, n), acc, rng.integers(0, 2, n)))
+    _compare(oracle_lib, tb, qs, engine, label="extreme-acc")
+
+
 def test_index_outgrows_lds_after_load_update(oracle_lib):
     """At load every slice has a one-step staircase (row 0 of each task dominates the rest), so the
     index fits in LDS.  A load report then pushes those rows out of reach: all staircases grow to
