@@ -205,7 +205,7 @@ constexpr uint32_t kLdsMax = 160 * 1024;  // dynamic LDS the lookup kernel may a
 int create_index(infaas_sel *h)
 {
     const int64_t S = (int64_t)h->T * h->B;
-    const uint32_t worst = 2 * body_bytes(kBodySteps + 1, kBodySteps);
+    const uint32_t worst = 2 * body_bytes(body_re(kBodySteps)) + 4 * kBodySteps;
     IndexView ix{};
     ix.pool_bytes = (uint32_t)std::min<int64_t>(kDummyBodyBytes + S * worst + 64, (int64_t)1 << 30);
     ix.step_cap = (uint32_t)std::min<int64_t>(1 + S * kIndexCap, (int64_t)1 << 28);
@@ -228,7 +228,7 @@ int create_index(infaas_sel *h)
     for (uint32_t i = 8; i < 16; ++i) dummy[i] = 0xFF;  // latency sentinels of the empty body (Re = 2)
     const int32_t none = -1;
     const uint32_t ctrl0[8] = {kDummyBodyBytes, 1u, 1u, 0u, 0u, 0u, 0u, 0u};
-    const uint32_t empty_hdr[4] = {0u, kEmptyHdrY, 0u, body_bytes(1)};
+    const uint32_t empty_hdr[4] = {0u, kEmptyHdrY, 0u, 4u + body_bytes(2)};
     if (!HIP_OK(hipMemcpy(ix.pool, dummy, sizeof(dummy), hipMemcpyHostToDevice)) ||
         !HIP_OK(hipMemcpy(ix.step_row, &none, 4, hipMemcpyHostToDevice)) ||
         !HIP_OK(hipMemcpy(ix.ctrl, ctrl0, sizeof(ctrl0), hipMemcpyHostToDevice)) ||

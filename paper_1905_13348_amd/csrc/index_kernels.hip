@@ -124,7 +124,7 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
     const int32_t t = s / tv.B, b = s - t * tv.B;
     const int32_t seg = tv.seg_off[t], L = tv.seg_len[t];
     if (L == 0) {  // no variants: the empty dummy body at offset 0 answers "nothing feasible"
-        if (tid == 0) ix.hdr[s] = make_uint4(0u, kEmptyHdrY, 0u, body_bytes(1));
+        if (tid == 0) ix.hdr[s] = make_uint4(0u, kEmptyHdrY, 0u, 4u + body_bytes(2));
         return;
     }
     const int32_t *__restrict__ accc = tv.acc_r + (int64_t)b * tv.Vp + seg;
@@ -240,7 +240,8 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
     }
     const int k0 = K < kBodySteps ? K : kBodySteps, k1 = K - k0;
     const uint32_t r0 = (uint32_t)k0 < ix.hot_rows ? (uint32_t)k0 : ix.hot_rows;
-    const uint32_t size0 = body_bytes(k0 + 1, r0), size = size0 + (k1 ? body_bytes(k1 + 1) : 0u);
+    const uint32_t re0 = body_re(k0), re1 = k1 ? body_re(k1) : 0u;
+    const uint32_t rows = 4u * r0, size0 = body_bytes(re0), size = rows + size0 + body_bytes(re1);
     uint32_t off = 0, rec = 0;
     if (lane == 0) {
         off = atomicAdd(&ix.ctrl[0], size);
@@ -252,22 +253,23 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
                       (int64_t)hi - (int64_t)tv.acc_base <= 65533 && lo >= tv.acc_base;   // 16-bit accuracy keys
     if (!fits) {  // no body: every query of this slice goes to the rank-ordered scan
         if (lane == 0) {
-            ix.hdr[s] = make_uint4(0u, kEmptyHdrY | kHdrPark | kHdrTrunc, 0u, 0u);
+            ix.hdr[s] = make_uint4(0u, kEmptyHdrY | kHdrPark | kHdrTrunc | kHdrDeep, 0u, 0u);
             atomicAdd(&ix.ctrl[4], 1u);
         }
         return;
     }
-    write_body(ix.pool + off, 0, k0, lane, st_acc, st_tot, tv.acc_base);
-    if (k1) write_body(ix.pool + off + size0, k0, k1, lane, st_acc, st_tot, tv.acc_base);
+    uint8_t *body0 = ix.pool + off + rows;
+    write_body(body0, 0, k0, lane, st_acc, st_tot, tv.acc_base);
+    if (k1) write_body(body0 + size0, k0, k1, lane, st_acc, st_tot, tv.acc_base);
     if (lane < K) {
         const int32_t row = tv.orig_r[(int64_t)b * tv.Vp + seg + st_pos];
         ix.step_row[rec + lane] = row;
-        if ((uint32_t)lane < r0) ((int32_t *)(ix.pool + off + body_bytes(k0 + 1)))[lane] = row;   // rows section
+        if ((uint32_t)lane < r0) *(int32_t *)(body0 - 4 - 4 * lane) = row;   // rows, in reverse in front of the body
     }
     if (lane == 0) {
-        const uint32_t y = ((uint32_t)(k0 + 1) << kHdrK0Shift) | (k1 ? (uint32_t)(k1 + 1) << kHdrK1Shift : 0u) |
-                           (trunc ? kHdrTrunc : 0u);
-        ix.hdr[s] = make_uint4(off - 4u, y, rec, off + size);
+        const uint32_t y = (re0 << kHdrK0Shift) | (re1 << kHdrK1Shift) | (trunc ? kHdrTrunc : 0u) |
+                           ((k1 || trunc) ? kHdrDeep : 0u);
+        ix.hdr[s] = make_uint4(off + rows - 4u, y, rec, off + size);
         atomicMax(&ix.ctrl[2], (uint32_t)k0);
         if (trunc) atomicAdd(&ix.ctrl[3], 1u);
         atomicAdd(&ix.ctrl[5], (uint32_t)K);
@@ -293,21 +295,20 @@ struct GlobalMem {
 
 // First fitting step of kN bodies (one per query of this lane), as bit sets; the kN searches are
 // interleaved so that their dependent reads overlap.  Branch-free apart from the wave-uniform
-// probe count.  body[k] / keys[k]: address and key count (sentinel included) of the body;
-// dd[k]: accuracy threshold in key space; lim[k]: latency bound.
+// probe count.  body[k] / re[k]: address and keys per array (Re) of the body; dd[k]: accuracy
+// threshold in key space; lim[k]: latency bound.
 template <int kN, class Mem>
 __device__ __forceinline__ void search_bodies(const Mem &mem, int nit, const uint32_t (&body)[kN],
-                                              const uint32_t (&keys)[kN], const uint32_t (&dd)[kN],
+                                              const uint32_t (&re)[kN], const uint32_t (&dd)[kN],
                                               const uint32_t (&lim)[kN], uint32_t (&m)[kN])
 {
-    uint32_t pa[kN], la[kN], pt[kN], lt[kN], re[kN];
+    uint32_t pa[kN], la[kN], pt[kN], lt[kN];
 #pragma unroll
     for (int k = 0; k < kN; ++k) {
-        re[k] = (keys[k] + 1u) & ~1u;
         pa[k] = body[k];                       // accuracy key j (1-based) at body + 2 + 2j
-        la[k] = body[k] + 2u * keys[k];        // probes beyond the keys land on the sentinel
-        pt[k] = body[k] + 2u * re[k];          // latency key j at body + 2 Re + 4j
-        lt[k] = pt[k] + 4u * keys[k];
+        la[k] = body[k] + 2u * re[k];          // probes beyond the keys land on the last sentinel
+        pt[k] = la[k];                         // latency key j at body + 2 Re + 4j
+        lt[k] = pt[k] + 4u * re[k];
     }
 #pragma unroll
     for (int it = 4; it >= 0; --it) {
@@ -434,7 +435,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             const bool resident = !(g.y & kHdrPark) && g.w <= lds_cap && g.z < 65536u;
             v2u l;
             l.x = (resident ? g.x : 0u) + rebase;
-            l.y = resident ? (g.y | g.z) : (kEmptyHdrY | kHdrPark);
+            l.y = resident ? (g.y | g.z) : (kEmptyHdrY | kHdrPark | kHdrDeep);
             *(v2u *)(lds_w + (kLdsCtrlBytes / 4) + s * (kLdsHdrBytes / 4)) = l;
         }
 #pragma unroll
@@ -476,8 +477,8 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     // one full unit of LDS work after they were requested -- so neither the gather nor the store
     // latency is exposed.  The fields of the unit after the next are requested meanwhile.
     int32_t p_lrow[kPerThread], p_grow[kPerThread], p_i0 = -1;
-    bool p_hit[kPerThread], p_inl[kPerThread];
-    auto p_val = [&](int k) -> int32_t { return p_hit[k] ? (p_inl[k] ? p_lrow[k] : p_grow[k]) : -1; };
+    bool p_inl[kPerThread];
+    auto p_val = [&](int k) -> int32_t { return p_inl[k] ? p_lrow[k] : p_grow[k]; };
     auto store_unit = [&]() {
         if (p_i0 < 0) return;
         if (aligned && p_i0 + kPerThread <= q.n) {
@@ -514,7 +515,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                 const uint4 h = ix.hdr[s];
                 body[k] = h.x; y[k] = h.y; rec[k] = h.z;
             }
-            keys[k] = (y[k] >> kHdrK0Shift) & 0x3Fu;
+            keys[k] = (y[k] >> kHdrK0Shift) & 0x3Fu;   // Re of the first body
             dd[k] = acc_threshold(cur.am[k], acc_base_m1);
             lim[k] = (uint32_t)cur.sl[k];
         }
@@ -524,20 +525,18 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) {
             const bool hit = m[k] != 0u;
-            const uint32_t step = (uint32_t)__builtin_ctz(m[k] | 0x80000000u);
-            // row of the step: from the body when it is one of its first hot_rows steps, else from
-            // step_row in global memory.  Both reads are issued for every lane (lanes that do not need
-            // one read a fixed address) and used after the next wait.
-            const uint32_t re = (keys[k] + 1u) & ~1u;
-            const uint32_t r0 = keys[k] - 1u < ix.hot_rows ? keys[k] - 1u : ix.hot_rows;
-            const bool inl = hit && step < r0;
-            const uint32_t at = inl ? body[k] + 14u * re + 4u * step : body[k];
-            p_lrow[k] = kLds ? (int32_t)lmem.ld32(at, 4u) : (int32_t)gmem.ld32(at, 4u);
+            const uint32_t step = (uint32_t)__builtin_ctzg(m[k], -1);   // no fitting step: above every count
+            // row of the step: from in front of the body when it is one of its first hot_rows steps,
+            // else from step_row in global memory.  Both reads are issued for every lane (lanes that
+            // do not need one read a fixed address) and used after the next wait.  step_row[0] is -1,
+            // which is what a lane without a fitting step reads and reports.
+            const bool inl = step < ix.hot_rows;
+            const uint32_t at = inl ? body[k] - 4u * step : body[k];
+            p_lrow[k] = kLds ? (int32_t)lmem.ld32(at, 0u) : (int32_t)gmem.ld32(at, 0u);
             p_grow[k] = *(const int32_t *)((const char *)ix.step_row + ((hit && !inl) ? (rec[k] + step) * 4u : 0u));
-            p_hit[k] = hit;
             p_inl[k] = inl;
-            // parked: unusable slice, or a miss that the second body / the scan may still turn into a hit
-            df[k] = (y[k] & kHdrPark) || (!hit && (y[k] & ((0x3Fu << kHdrK1Shift) | kHdrTrunc)));
+            // parked: a miss that the second body / the scan may still turn into a hit
+            df[k] = !hit && (int32_t)y[k] < 0;
         }
         p_i0 = i0;
 #pragma unroll
@@ -574,15 +573,15 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             if (!resident) { y = g.y; rec = g.z; gbody = g.x; }
         }
         const bool indexed = !(y & kHdrPark);
-        const uint32_t keys0 = (y >> kHdrK0Shift) & 0x3Fu, keys1 = (y >> kHdrK1Shift) & 0x3Fu;
-        const uint32_t size0 = body_bytes(keys0, keys0 - 1u < ix.hot_rows ? keys0 - 1u : ix.hot_rows);
+        const uint32_t keys0 = (y >> kHdrK0Shift) & 0x3Fu, keys1 = (y >> kHdrK1Shift) & 0x3Fu;   // Re of the bodies
+        const uint32_t size0 = body_bytes(keys0);
         const uint32_t dd[1] = {acc_threshold(min_acc, acc_base_m1)}, lim[1] = {(uint32_t)slo};
         int32_t ans = -1;
         bool done = false;
         // first body from global memory: only if the main loop could not use an LDS copy
         const bool need_g0 = have && indexed && kLds && !resident;
         if (__ballot(need_g0)) {
-            const uint32_t bd[1] = {need_g0 ? gbody : 0u}, ks[1] = {need_g0 ? keys0 : 1u};
+            const uint32_t bd[1] = {need_g0 ? gbody : 0u}, ks[1] = {need_g0 ? keys0 : 2u};
             uint32_t m[1];
             search_bodies<1>(gmem, nit, bd, ks, dd, lim, m);
             if (need_g0 && m[0]) { ans = ix.step_row[rec + __builtin_ctz(m[0])]; done = true; }
@@ -591,13 +590,13 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         const bool need1 = have && indexed && keys1 != 0u && !done;
         const bool need_l1 = need1 && resident, need_g1 = need1 && !resident;
         if (kLds && __ballot(need_l1)) {
-            const uint32_t bd[1] = {need_l1 ? lbody + size0 : rebase}, ks[1] = {need_l1 ? keys1 : 1u};
+            const uint32_t bd[1] = {need_l1 ? lbody + size0 : rebase}, ks[1] = {need_l1 ? keys1 : 2u};
             uint32_t m[1];
             search_bodies<1>(lmem, nit, bd, ks, dd, lim, m);
             if (need_l1 && m[0]) { ans = ix.step_row[rec + kBodySteps + __builtin_ctz(m[0])]; done = true; }
         }
         if (__ballot(need_g1)) {
-            const uint32_t bd[1] = {need_g1 ? gbody + size0 : 0u}, ks[1] = {need_g1 ? keys1 : 1u};
+            const uint32_t bd[1] = {need_g1 ? gbody + size0 : 0u}, ks[1] = {need_g1 ? keys1 : 2u};
             uint32_t m[1];
             search_bodies<1>(gmem, nit, bd, ks, dd, lim, m);
             if (need_g1 && m[0]) { ans = ix.step_row[rec + kBodySteps + __builtin_ctz(m[0])]; done = true; }

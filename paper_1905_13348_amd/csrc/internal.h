@@ -49,33 +49,35 @@ struct TableView {
 // p fastest steps.  Both counts come from a 5-probe binary search over a sorted copy of the
 // keys.  Only when the first body has no fitting step is the second one consulted.
 //
-// Body with K steps (K + 1 = k1 keys including the sentinel; Re = k1 rounded up to even).
-// Byte offsets from the body start, which is 4-byte aligned:
-//   0            acc16 : u16[Re]  acc - acc_base + 1, descending; then 0 (sentinel)
-//   2 Re         totk  : u32[Re]  tot, ascending; then 0xFFFFFFFF (sentinel)
+// Body with K steps: Re keys per sorted array, Re = K + 1 rounded up to even (the keys of the
+// steps, then one or two sentinels).  Byte offsets from the body start, which is 4-byte aligned:
+//   0            acc16 : u16[Re]  acc - acc_base + 1, descending; then 0 (sentinels)
+//   2 Re         totk  : u32[Re]  tot, ascending; then 0xFFFFFFFF (sentinels)
 //   6 Re         A     : u32[Re]  A[0] = 0, A[p] for p = 1..K
 //   10 Re        S     : u32[Re]  S[0] = 0, S[p] for p = 1..K
-//   14 Re        rows  : i32[r]   caller row of step i, for the first r = min(K, hot_rows) steps of
-//                                 a slice's FIRST body (none in the second); deeper steps are
-//                                 translated through step_row in global memory
+// A slice's block in the pool is  [rows][first body][second body]:  rows holds the caller rows
+// of the first r = min(K, hot_rows) steps of the first body in REVERSE order, so that the row of
+// step i is at (first body start) - 4 - 4 i; deeper steps are translated through step_row in
+// global memory.
 // Headers hold "body start - 4" (called the body address below), so that accuracy key j (1-based)
-// is at address + 2 + 2j and latency key j at address + 2 Re + 4j.
+// is at address + 2 + 2j, latency key j at address + 2 Re + 4j and the row of step i at
+// address - 4i.
 constexpr int kBodySteps = 31;               // steps per body
 constexpr int kIndexCap = 2 * kBodySteps;    // steps kept per slice; more => slice marked truncated
 constexpr uint32_t kHdrK0Shift = 16;         // header word y: bits 0-15 first step_row entry (LDS copy),
-constexpr uint32_t kHdrK1Shift = 22;         //   bits 16-21 keys of body 0, bits 22-27 keys of body 1 (0 = none)
+constexpr uint32_t kHdrK1Shift = 22;         //   bits 16-21 Re of body 0, bits 22-27 Re of body 1 (0 = none)
 constexpr uint32_t kHdrTrunc = 1u << 28;     // steps beyond the capacity exist: a miss in both bodies proves nothing
 constexpr uint32_t kHdrPark = 1u << 29;      // no usable body: every query of the slice takes the slow path
+constexpr uint32_t kHdrDeep = 1u << 31;      // a miss in the first body is not final (second body, truncation or
+                                             // no usable body); the sign bit, so that one compare tests it
 constexpr uint32_t kLdsHdrBytes = 8;         // per slice in the lookup kernel's LDS: {body address, y | first step}
 constexpr uint32_t kLdsCtrlBytes = 16;       // control words at the start of the lookup kernel's LDS
 constexpr int kIndexTile = 8192;             // most queries per workgroup step of the index lookup kernel
 
 // LDS bytes of the S + 1 slice headers, padded so that the bodies behind them are 16-byte aligned
 __host__ __device__ inline uint32_t lds_header_bytes(int32_t S) { return (((uint32_t)S + 1u) * kLdsHdrBytes + 15u) & ~15u; }
-__host__ __device__ inline uint32_t body_bytes(uint32_t keys, uint32_t rows = 0u)
-{
-    return 14u * ((keys + 1u) & ~1u) + 4u * rows;
-}
+__host__ __device__ inline uint32_t body_re(uint32_t steps) { return (steps + 2u) & ~1u; }   // Re of a body with `steps` steps
+__host__ __device__ inline uint32_t body_bytes(uint32_t re) { return 14u * re; }
 
 struct IndexView {
     uint4 *hdr;          // [S + 1] {body address (pool offset - 4), y (see kHdr*), first entry in step_row, end of bodies};
@@ -89,7 +91,7 @@ struct IndexView {
                          // [4] slices without body, [5] total steps
 };
 constexpr uint32_t kDummyBodyBytes = 64;     // 4 unused bytes, the empty body (28 bytes), padding
-constexpr uint32_t kEmptyHdrY = 1u << kHdrK0Shift;  // one key (the sentinel), no second body
+constexpr uint32_t kEmptyHdrY = 2u << kHdrK0Shift;  // Re = 2 (sentinels only), no second body
 
 // Scratch of the scan engine for one pass over up to `capacity` queries.
 struct ScanScratch {
