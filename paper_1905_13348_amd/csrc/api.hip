@@ -205,7 +205,7 @@ constexpr uint32_t kLdsMax = 160 * 1024;  // dynamic LDS the lookup kernel may a
 int create_index(infaas_sel *h)
 {
     const int64_t S = (int64_t)h->T * h->B;
-    const uint32_t worst = 2 * body_bytes(body_re(kBodySteps)) + 4 * kBodySteps;
+    const uint32_t worst = 2 * body_bytes(body_re(kBodySteps)) + 2 * (kBodySteps + 1);
     IndexView ix{};
     ix.pool_bytes = (uint32_t)std::min<int64_t>(kDummyBodyBytes + S * worst + 64, (int64_t)1 << 30);
     ix.step_cap = (uint32_t)std::min<int64_t>(1 + S * kIndexCap, (int64_t)1 << 28);
@@ -245,7 +245,11 @@ int create_index(infaas_sel *h)
     // LDS left over holds the caller rows of the first steps of every slice (the steps most answers
     // come from), which saves those answers a gather from global memory.  Rebuild with that many.
     const int64_t spare = (int64_t)kLdsMax - need - 1536;   // keep room for staircases that grow with load
-    const uint32_t hot = spare > 0 ? (uint32_t)std::min<int64_t>(spare / (4 * S), kBodySteps) : 0u;
+    // 2 bytes each, in pairs; the bits of a row number above 16 go into a 14-bit header field
+    const uint32_t row_bits = h->V > 1 ? 64u - (uint32_t)__builtin_clzll((unsigned long long)(h->V - 1)) : 1u;
+    h->ix.row_hi_bits = row_bits > 16 ? row_bits - 16 : 0u;
+    const uint32_t hot_max = h->ix.row_hi_bits ? kRowHiField / h->ix.row_hi_bits : (uint32_t)kBodySteps;
+    const uint32_t hot = spare > 0 ? (uint32_t)std::min<int64_t>((spare / (4 * S)) * 2, std::min<uint32_t>(hot_max, kBodySteps)) : 0u;
     if (h->index_lds_bytes && hot > 0) {
         h->ix.hot_rows = hot;
         if (!HIP_OK(hipMemcpy(h->ix.ctrl, ctrl0, sizeof(ctrl0), hipMemcpyHostToDevice)) ||

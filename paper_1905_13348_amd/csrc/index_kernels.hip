@@ -239,9 +239,14 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
         lo = aj < lo ? aj : lo;
     }
     const int k0 = K < kBodySteps ? K : kBodySteps, k1 = K - k0;
+    // caller rows of the first steps: low 16 bits in front of the body, the bits above in the header
+    const int32_t row = lane < K ? tv.orig_r[(int64_t)b * tv.Vp + seg + st_pos] : 0;
     const uint32_t r0 = (uint32_t)k0 < ix.hot_rows ? (uint32_t)k0 : ix.hot_rows;
+    uint32_t row_hi = 0;
+    for (uint32_t j = 0; j < r0; ++j)
+        row_hi |= ((uint32_t)__builtin_amdgcn_readlane(row, (int)j) >> 16) << (j * ix.row_hi_bits);
     const uint32_t re0 = body_re(k0), re1 = k1 ? body_re(k1) : 0u;
-    const uint32_t rows = 4u * r0, size0 = body_bytes(re0), size = rows + size0 + body_bytes(re1);
+    const uint32_t rows = (2u * r0 + 3u) & ~3u, size0 = body_bytes(re0), size = rows + size0 + body_bytes(re1);
     uint32_t off = 0, rec = 0;
     if (lane == 0) {
         off = atomicAdd(&ix.ctrl[0], size);
@@ -262,13 +267,13 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
     write_body(body0, 0, k0, lane, st_acc, st_tot, tv.acc_base);
     if (k1) write_body(body0 + size0, k0, k1, lane, st_acc, st_tot, tv.acc_base);
     if (lane < K) {
-        const int32_t row = tv.orig_r[(int64_t)b * tv.Vp + seg + st_pos];
         ix.step_row[rec + lane] = row;
-        if ((uint32_t)lane < r0) *(int32_t *)(body0 - 4 - 4 * lane) = row;   // rows, in reverse in front of the body
+        if ((uint32_t)lane < r0)   // in reverse in front of the body
+            *(uint16_t *)(body0 - 2 - 2 * lane) = (uint16_t)row;
     }
     if (lane == 0) {
         const uint32_t y = (re0 << kHdrK0Shift) | (re1 << kHdrK1Shift) | (trunc ? kHdrTrunc : 0u) |
-                           ((k1 || trunc) ? kHdrDeep : 0u);
+                           ((k1 || trunc) ? kHdrDeep : 0u) | row_hi;
         ix.hdr[s] = make_uint4(off + rows - 4u, y, rec, off + size);
         atomicMax(&ix.ctrl[2], (uint32_t)k0);
         if (trunc) atomicAdd(&ix.ctrl[3], 1u);
@@ -362,7 +367,11 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     // Work units of one wavefront: 64 lanes x kPerThread consecutive queries.  The units are split
     // evenly and contiguously over the workgroups; inside a workgroup the wavefronts draw them from
     // a counter in LDS, because the wavefronts of a SIMD do not advance at the same speed.
+    // A lane's queries in a unit: four consecutive ones in every block of 256, so that each 16-byte
+    // access of the wavefront covers one contiguous kilobyte.
     constexpr int kUnit = 64 * kPerThread;
+    constexpr int kSpan = (kPerThread / 4 - 1) * 256 + 4;           // from a lane's first query to behind its last
+    auto qoff = [](int k) -> int32_t { return (k >> 2) * 256 + (k & 3); };   // offset of query k of a lane
     const int32_t nunits = (q.n + kUnit - 1) / kUnit;
     const int32_t u_begin = (int32_t)(((int64_t)nunits * blockIdx.x) / gridDim.x);
     const int32_t u_end = (int32_t)(((int64_t)nunits * (blockIdx.x + 1)) / gridDim.x);
@@ -373,18 +382,18 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     };
     auto load_unit = [&](Fields &f, int32_t unit) {
         f.unit = unit;
-        const int32_t i0 = unit * kUnit + lane * kPerThread;
+        const int32_t i0 = unit * kUnit + lane * 4;
         if (unit < 0) {
 #pragma unroll
             for (int k = 0; k < kPerThread; ++k) { f.tk[k] = -1; f.sl[k] = 0; f.am[k] = 0; f.bi[k] = 0; }
-        } else if (aligned && i0 + kPerThread <= q.n) {
+        } else if (aligned && i0 + kSpan <= q.n) {
             const uint32_t off = (uint32_t)i0 * 4u;   // one 32-bit byte offset for all four arrays (n <= 2^28)
 #pragma unroll
             for (int h = 0; h < kPerThread / 4; ++h) {
-                const v4i a = __builtin_nontemporal_load((const v4i *)((const char *)q.task + off) + h);
-                const v4i b = __builtin_nontemporal_load((const v4i *)((const char *)q.slo + off) + h);
-                const v4i c = __builtin_nontemporal_load((const v4i *)((const char *)q.min_acc + off) + h);
-                const v4i d = __builtin_nontemporal_load((const v4i *)((const char *)q.bidx + off) + h);
+                const v4i a = __builtin_nontemporal_load((const v4i *)((const char *)q.task + off) + 64 * h);
+                const v4i b = __builtin_nontemporal_load((const v4i *)((const char *)q.slo + off) + 64 * h);
+                const v4i c = __builtin_nontemporal_load((const v4i *)((const char *)q.min_acc + off) + 64 * h);
+                const v4i d = __builtin_nontemporal_load((const v4i *)((const char *)q.bidx + off) + 64 * h);
                 f.tk[4 * h] = a.x; f.tk[4 * h + 1] = a.y; f.tk[4 * h + 2] = a.z; f.tk[4 * h + 3] = a.w;
                 f.sl[4 * h] = b.x; f.sl[4 * h + 1] = b.y; f.sl[4 * h + 2] = b.z; f.sl[4 * h + 3] = b.w;
                 f.am[4 * h] = c.x; f.am[4 * h + 1] = c.y; f.am[4 * h + 2] = c.z; f.am[4 * h + 3] = c.w;
@@ -393,11 +402,12 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         } else {
 #pragma unroll
             for (int k = 0; k < kPerThread; ++k) {
-                const bool in = i0 + k < q.n;
-                f.tk[k] = in ? q.task[i0 + k] : -1;   // -1: outside the table, answered "nothing feasible"
-                f.sl[k] = in ? q.slo[i0 + k] : 0;
-                f.am[k] = in ? q.min_acc[i0 + k] : 0;
-                f.bi[k] = in ? q.bidx[i0 + k] : 0;
+                const int32_t i = i0 + qoff(k);
+                const bool in = i < q.n;
+                f.tk[k] = in ? q.task[i] : -1;   // -1: outside the table, answered "nothing feasible"
+                f.sl[k] = in ? q.slo[i] : 0;
+                f.am[k] = in ? q.min_acc[i] : 0;
+                f.bi[k] = in ? q.bidx[i] : 0;
             }
         }
     };
@@ -434,8 +444,8 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             const uint4 g = ix.hdr[s];
             const bool resident = !(g.y & kHdrPark) && g.w <= lds_cap && g.z < 65536u;
             v2u l;
-            l.x = (resident ? g.x : 0u) + rebase;
-            l.y = resident ? (g.y | g.z) : (kEmptyHdrY | kHdrPark | kHdrDeep);
+            l.x = ((resident ? g.x : 0u) + rebase) | (g.y << kLdsAddrBits);   // high row bits above the address
+            l.y = resident ? ((g.y & 0xFFFF0000u) | g.z) : (kEmptyHdrY | kHdrPark | kHdrDeep);
             *(v2u *)(lds_w + (kLdsCtrlBytes / 4) + s * (kLdsHdrBytes / 4)) = l;
         }
 #pragma unroll
@@ -451,6 +461,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     if (tid < 4) lds_w[tid] = 0u;
     __syncthreads();
 
+    const uint32_t row_hi_mask = (1u << ix.row_hi_bits) - 1u;
     const int32_t acc_base_m1 = tv.acc_base - 1;   // acc_base is above INT32_MIN
     const uint32_t max_k = ix.ctrl[2];
     const int nit = 32 - __builtin_clz(max_k | 1u);    // <= 5
@@ -477,30 +488,31 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     // one full unit of LDS work after they were requested -- so neither the gather nor the store
     // latency is exposed.  The fields of the unit after the next are requested meanwhile.
     int32_t p_lrow[kPerThread], p_grow[kPerThread], p_i0 = -1;
+    uint32_t p_base[kPerThread];
     bool p_inl[kPerThread];
-    auto p_val = [&](int k) -> int32_t { return p_inl[k] ? p_lrow[k] : p_grow[k]; };
+    auto p_val = [&](int k) -> int32_t { return p_inl[k] ? (int32_t)((p_base[k] << 16) | (uint32_t)p_lrow[k]) : p_grow[k]; };
     auto store_unit = [&]() {
         if (p_i0 < 0) return;
-        if (aligned && p_i0 + kPerThread <= q.n) {
+        if (aligned && p_i0 + kSpan <= q.n) {
 #pragma unroll
             for (int h = 0; h < kPerThread / 4; ++h) {
                 const v4i r = {p_val(4 * h), p_val(4 * h + 1), p_val(4 * h + 2), p_val(4 * h + 3)};
-                __builtin_nontemporal_store(r, (v4i *)((char *)q.out + (uint32_t)p_i0 * 4u) + h);
+                __builtin_nontemporal_store(r, (v4i *)((char *)q.out + (uint32_t)p_i0 * 4u) + 64 * h);
             }
         } else {
 #pragma unroll
             for (int k = 0; k < kPerThread; ++k)
-                if (p_i0 + k < q.n) q.out[p_i0 + k] = p_val(k);
+                if (p_i0 + qoff(k) < q.n) q.out[p_i0 + qoff(k)] = p_val(k);
         }
     };
     // One pipeline stage: search the unit in `cur`, request the unit after the next into `far`.
     auto stage = [&](Fields &cur, Fields &far) {
-        const int32_t i0 = cur.unit * kUnit + lane * kPerThread;
+        const int32_t i0 = cur.unit * kUnit + lane * 4;
         store_unit();                                   // results of the previous unit
         load_unit(far, next_unit());
         // slice header; queries outside the table use the header of the empty slice (entry S)
         uint32_t body[kPerThread], y[kPerThread], rec[kPerThread], keys[kPerThread], dd[kPerThread],
-            lim[kPerThread], m[kPerThread], sl_of[kPerThread];
+            lim[kPerThread], m[kPerThread], sl_of[kPerThread], rbase[kPerThread];
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) {
             const uint32_t ok = ((uint32_t)cur.tk[k] < (uint32_t)tv.T) & ((uint32_t)cur.bi[k] < (uint32_t)tv.B) &
@@ -510,10 +522,12 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             sl_of[k] = s;
             if (kLds) {
                 const v2u h = lmem.ld64(lds_hdr0 + s * kLdsHdrBytes);
-                body[k] = h.x; y[k] = h.y; rec[k] = h.y & 0xFFFFu;
+                body[k] = h.x & ((1u << kLdsAddrBits) - 1u); y[k] = h.y; rec[k] = h.y & 0xFFFFu;
+                rbase[k] = h.x >> kLdsAddrBits;
             } else {
                 const uint4 h = ix.hdr[s];
                 body[k] = h.x; y[k] = h.y; rec[k] = h.z;
+                rbase[k] = h.y & ((1u << kRowHiField) - 1u);
             }
             keys[k] = (y[k] >> kHdrK0Shift) & 0x3Fu;   // Re of the first body
             dd[k] = acc_threshold(cur.am[k], acc_base_m1);
@@ -526,13 +540,15 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         for (int k = 0; k < kPerThread; ++k) {
             const bool hit = m[k] != 0u;
             const uint32_t step = (uint32_t)__builtin_ctzg(m[k], -1);   // no fitting step: above every count
-            // row of the step: from in front of the body when it is one of its first hot_rows steps,
-            // else from step_row in global memory.  Both reads are issued for every lane (lanes that
-            // do not need one read a fixed address) and used after the next wait.  step_row[0] is -1,
-            // which is what a lane without a fitting step reads and reports.
+            // row of the step: from in front of the body (low 16 bits) and the header (the bits above)
+            // when it is one of its first hot_rows steps, else from step_row in global memory.  Both
+            // reads are issued for every lane (lanes that do not need one read a fixed address) and
+            // used after the next wait.  step_row[0] is -1, which is what a lane without a fitting
+            // step reads and reports.
             const bool inl = step < ix.hot_rows;
-            const uint32_t at = inl ? body[k] - 4u * step : body[k];
-            p_lrow[k] = kLds ? (int32_t)lmem.ld32(at, 0u) : (int32_t)gmem.ld32(at, 0u);
+            const uint32_t at = inl ? body[k] - 2u * step : body[k];
+            p_lrow[k] = kLds ? (int32_t)lmem.ld16(at, 2u) : (int32_t)gmem.ld16(at, 2u);
+            p_base[k] = (rbase[k] >> ((step * ix.row_hi_bits) & 31u)) & row_hi_mask;
             p_grow[k] = *(const int32_t *)((const char *)ix.step_row + ((hit && !inl) ? (rec[k] + step) * 4u : 0u));
             p_inl[k] = inl;
             // parked: a miss that the second body / the scan may still turn into a hit
@@ -543,7 +559,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         for (int k = 0; k < kPerThread; ++k) {
             const uint64_t mask = __ballot(df[k]);
             if (mask) {   // parked queries are always inside the table
-                if (df[k]) wq[cnt + lanes_below(mask)] = v4i{i0 + k, cur.sl[k], cur.am[k], (int32_t)sl_of[k]};
+                if (df[k]) wq[cnt + lanes_below(mask)] = v4i{i0 + qoff(k), cur.sl[k], cur.am[k], (int32_t)sl_of[k]};
                 cnt += (uint32_t)__builtin_popcountll(mask);
             }
         }
@@ -566,7 +582,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         if (kLds) {
             const v2u h = lmem.ld64(lds_hdr0 + s * kLdsHdrBytes);
             resident = !(h.y & kHdrPark);
-            lbody = h.x; y = h.y; rec = h.y & 0xFFFFu;
+            lbody = h.x & ((1u << kLdsAddrBits) - 1u); y = h.y; rec = h.y & 0xFFFFu;
         }
         if (__ballot(!resident)) {   // slices without a body in LDS: header from global memory
             const uint4 g = ix.hdr[resident ? (uint32_t)tv.S : s];

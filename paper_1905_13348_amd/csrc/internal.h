@@ -55,19 +55,23 @@ struct TableView {
 //   2 Re         totk  : u32[Re]  tot, ascending; then 0xFFFFFFFF (sentinels)
 //   6 Re         A     : u32[Re]  A[0] = 0, A[p] for p = 1..K
 //   10 Re        S     : u32[Re]  S[0] = 0, S[p] for p = 1..K
-// A slice's block in the pool is  [rows][first body][second body]:  rows holds the caller rows
-// of the first r = min(K, hot_rows) steps of the first body in REVERSE order, so that the row of
-// step i is at (first body start) - 4 - 4 i; deeper steps are translated through step_row in
-// global memory.
+// A slice's block in the pool is  [rows][first body][second body]:  rows holds the low 16 bits
+// of the caller rows of the first r = min(K, hot_rows) steps of the first body, in REVERSE order
+// and padded in front to 4 bytes, so that those of step i are at (first body start) - 2 - 2 i.
+// The bits above (row_hi_bits per step, as many as the table's row numbers need) sit in the
+// header, step i at bit i * row_hi_bits of a 14-bit field, which limits hot_rows to
+// 14 / row_hi_bits.  Deeper steps are translated through step_row in global memory.
 // Headers hold "body start - 4" (called the body address below), so that accuracy key j (1-based)
 // is at address + 2 + 2j, latency key j at address + 2 Re + 4j and the row of step i at
-// address - 4i.
+// address + 2 - 2i.
 constexpr int kBodySteps = 31;               // steps per body
 constexpr int kIndexCap = 2 * kBodySteps;    // steps kept per slice; more => slice marked truncated
-constexpr uint32_t kHdrK0Shift = 16;         // header word y: bits 0-15 first step_row entry (LDS copy),
+constexpr uint32_t kHdrK0Shift = 16;         // header word y: bits 0-13 high row bits (global) / bits 0-15 first step_row entry (LDS copy),
 constexpr uint32_t kHdrK1Shift = 22;         //   bits 16-21 Re of body 0, bits 22-27 Re of body 1 (0 = none)
 constexpr uint32_t kHdrTrunc = 1u << 28;     // steps beyond the capacity exist: a miss in both bodies proves nothing
 constexpr uint32_t kHdrPark = 1u << 29;      // no usable body: every query of the slice takes the slow path
+constexpr uint32_t kLdsAddrBits = 18;        // LDS copy of a header: x = body address | high row bits << 18
+constexpr uint32_t kRowHiField = 32 - kLdsAddrBits;   // bits for the high row bits of the first steps
 constexpr uint32_t kHdrDeep = 1u << 31;      // a miss in the first body is not final (second body, truncation or
                                              // no usable body); the sign bit, so that one compare tests it
 constexpr uint32_t kLdsHdrBytes = 8;         // per slice in the lookup kernel's LDS: {body address, y | first step}
@@ -86,7 +90,8 @@ struct IndexView {
     uint32_t pool_bytes;
     int32_t *step_row;   // caller row of every step; entry 0 is unused
     uint32_t step_cap;
-    uint32_t hot_rows;   // rows kept inside the first body of every slice (fills the LDS left over)
+    uint32_t hot_rows;   // rows kept in front of the first body of every slice (fills the LDS left over)
+    uint32_t row_hi_bits;// bits of a row number above its low 16
     uint32_t *ctrl;      // [0] pool bump, [1] step bump, [2] most keys in one body, [3] truncated slices,
                          // [4] slices without body, [5] total steps
 };

@@ -253,6 +253,23 @@ def test_extreme_accuracies(oracle_lib, engine):
     _compare(oracle_lib, tb, qs, engine, label="extreme-acc")
 
 
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
+def test_rows_scattered_over_a_large_table(oracle_lib, engine):
+    """300,000 variants.  Tasks 0-3 own rows spread over the first 200,000 (the first steps of a
+    slice lie more than 65,536 rows apart, so the index cannot keep them as 16-bit offsets), tasks
+    4-7 own contiguous blocks behind them, two of which start above row 2^18."""
+    rng = np.random.default_rng(300)
+    V, B = 300_000, 2
+    acc, lat, cost, queue = workloads.configs.make_variant_fields(rng, V, np.asarray([1, 8], np.int32))
+    task = np.empty(V, np.int32)
+    task[:200_000] = rng.integers(0, 4, 200_000)
+    task[200_000:] = 4 + np.arange(100_000) // 25_000
+    tb = _table(8, [1, 8], task, acc, lat, cost, queue)
+    qs = _random_queries(rng, 8, B, 6_000)
+    got = _compare(oracle_lib, tb, qs, engine, label="scattered-rows")
+    assert (got >= 262_144).any() and ((got >= 0) & (got < 200_000)).any()
+
+
 def test_index_outgrows_lds_after_load_update(oracle_lib):
     """At load every slice has a one-step staircase (row 0 of each task dominates the rest), so the
     index fits in LDS.  A load report then pushes those rows out of reach: all staircases grow to
