@@ -206,6 +206,9 @@ int create_index(infaas_sel *h)
 {
     const int64_t S = (int64_t)h->T * h->B;
     const uint32_t worst = 2 * body_bytes(body_re(kBodySteps)) + 2 * (kBodySteps + 1);
+    // The build takes room with one add on a pair of 32-bit counters; their sums must not carry.
+    // A table with that many slices (millions) gets no index and is answered by the scan engine.
+    if (kDummyBodyBytes + S * worst > 0xFFFF0000ll || 1 + S * kIndexCap > 0xFFFF0000ll) return INFAAS_SEL_OK;
     IndexView ix{};
     ix.pool_bytes = (uint32_t)std::min<int64_t>(kDummyBodyBytes + S * worst + 64, (int64_t)1 << 30);
     ix.step_cap = (uint32_t)std::min<int64_t>(1 + S * kIndexCap, (int64_t)1 << 28);

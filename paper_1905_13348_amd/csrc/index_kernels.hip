@@ -4,8 +4,8 @@
 // its brute-force search needs ~100 ms because its metadata store keeps sorted sets
 // (Sections 5 and 6.4); this is the exact, batched GPU counterpart of that idea.
 //
-//   k_index_build  : one wavefront per (task, batch) slice walks the slice in rank order and
-//                    keeps the "steps" (variants not dominated by a cheaper one), then writes
+//   k_index_build  : one workgroup per (task, batch) slice finds the "steps" (variants that no
+//                    cheaper one dominates) with block-wise and all-pairs tests, then writes
 //                    sorted keys and bit sets for them (layout: internal.h)
 //   k_index_select : one lane per query.  The whole index is mirrored in LDS; a query costs two
 //                    5-probe binary searches in LDS, two bit-set reads, one AND and one count-
@@ -44,14 +44,14 @@ __device__ __forceinline__ void write_body(uint8_t *body, int g0, int kb, int la
                                            uint32_t st_tot, int32_t acc_base)
 {
     const bool mine = lane >= g0 && lane < g0 + kb;
-    int32_t pa = 0, ps = 0;
+    int32_t pa = 0, ps = 0;   // position of this lane's step in the sorted key arrays
     for (int j = g0; j < g0 + kb; ++j) {
         const int32_t aj = __builtin_amdgcn_readlane(st_acc, j);
         const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)st_tot, j);
         pa += (aj > st_acc || (aj == st_acc && j < lane)) ? 1 : 0;
         ps += (tj < st_tot || (tj == st_tot && j < lane)) ? 1 : 0;
     }
-    const uint32_t re = ((uint32_t)kb + 2u) & ~1u;   // keys = kb + 1, rounded up to even
+    const uint32_t re = body_re((uint32_t)kb);
     uint16_t *k_acc = (uint16_t *)body;
     uint32_t *k_tot = (uint32_t *)(body + 2 * re);
     uint32_t *m_a = (uint32_t *)(body + 6 * re);
@@ -64,63 +64,48 @@ __device__ __forceinline__ void write_body(uint8_t *body, int g0, int kb, int la
         k_acc[lane] = 0;
         k_tot[lane] = 0xFFFFFFFFu;
     }
-    if (lane == 0) { m_a[0] = 0; m_s[0] = 0; }
-    for (int p = 1; p <= kb; ++p) {
-        const uint32_t ma = (uint32_t)(__ballot(mine && pa < p) >> g0);
-        const uint32_t ms = (uint32_t)(__ballot(mine && ps < p) >> g0);
-        if (lane == 0) { m_a[p] = ma; m_s[p] = ms; }
+    // lane p builds A[p] and S[p]: the steps among the p most accurate / p fastest
+    uint32_t ma = 0, ms = 0;
+    for (int j = g0; j < g0 + kb; ++j) {
+        const int32_t paj = __builtin_amdgcn_readlane(pa, j), psj = __builtin_amdgcn_readlane(ps, j);
+        const uint32_t bit = 1u << (j - g0);
+        ma |= paj < lane ? bit : 0u;
+        ms |= psj < lane ? bit : 0u;
     }
+    if (lane <= kb) { m_a[lane] = ma; m_s[lane] = ms; }
 }
 
 constexpr int kBuildThreads = 512;
-constexpr int kBuildChunk = 4096;   // entries of a slice staged in LDS at a time
+constexpr int kBuildWaves = kBuildThreads / 64;
+constexpr int kBuildChunk = 2048;                          // entries of a slice staged in LDS at a time
+constexpr int kBuildBlocks = kBuildChunk / 64;             // blocks of 64 entries in a chunk
+constexpr int kBlocksPerWave = kBuildBlocks / kBuildWaves;
 
-// Sequential part of the staircase walk, run by the first wavefront: the candidates `alive`
-// of one block of 64 entries (a, tt per lane, rank position pos0 + lane) are tested against the
-// steps from number j0 on and appended, in rank order, when nothing earlier dominates them.
-// Lane j keeps step j.  Returns false when the capacity is exceeded.
-__device__ __forceinline__ bool absorb_block(bool alive, int32_t a, uint32_t tt, int32_t pos0, int lane,
-                                             int32_t j0, int32_t &K, int32_t &st_acc, uint32_t &st_tot,
-                                             int32_t &st_pos)
-{
-    for (int32_t j = j0; j < K; ++j) {
-        const int32_t aj = __builtin_amdgcn_readlane(st_acc, j);
-        const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)st_tot, j);
-        alive = alive && !(aj >= a && tj <= tt);
-        if (((j - j0) & 3) == 3 && __ballot(alive) == 0) return true;
-    }
-    uint64_t mask = __ballot(alive);
-    while (mask) {
-        if (K == kIndexCap) return false;
-        const int l = __builtin_ctzll(mask);
-        const int32_t al = __builtin_amdgcn_readlane(a, l);
-        const uint32_t tl = (uint32_t)__builtin_amdgcn_readlane((int)tt, l);
-        if (lane == K) { st_acc = al; st_tot = tl; st_pos = pos0 + l; }
-        K += 1;
-        alive = alive && !(al >= a && tl <= tt);   // also retires lane l itself
-        mask = __ballot(alive);
-    }
-    return true;
-}
-
-// One workgroup per slice.  All of its lanes copy the slice (rank-ordered accuracy and
-// latency-plus-queue columns) into LDS with every load in flight at once.  Per staged chunk:
-//   1. (first chunk only) the first wavefront finds the steps among the first 64 entries;
-//   2. all wavefronts test the remaining entries against the steps known so far -- in parallel,
-//      because that set is fixed -- which removes nearly all of them;
-//   3. the first wavefront walks the few survivors in rank order against the steps found since.
+// One workgroup per slice.  An entry of the slice is a step exactly when no entry ranked before it
+// has at least its accuracy and at most its latency-plus-queue; because that relation is
+// transitive it is enough to test against earlier STEPS, or against any set of earlier entries
+// that contains them.  Per staged chunk of the rank-ordered columns:
+//   0. (first chunk) the first wavefront finds the steps among the first 64 entries;
+//   1. every wavefront, for its blocks of 64 entries: drop what a step known so far dominates,
+//      then what an earlier entry of the same block dominates;
+//   2. the survivors ("candidates", a few per block) are compacted in rank order;
+//   3. 512 candidates at a time, each is tested against the steps accepted since the chunk began
+//      and against the candidates in front of it in its batch; what is left are steps.
+// Nothing in it is sequential in the number of steps.  The first wavefront then writes the bodies.
 __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, IndexView ix)
 {
     __shared__ int32_t s_acc[kBuildChunk];
     __shared__ uint32_t s_tot[kBuildChunk];
-    __shared__ uint64_t s_live[kBuildChunk / 64];   // per block of 64 entries: lanes that survived step 2
-    __shared__ int32_t p_acc[64];                   // steps published for step 2
-    __shared__ uint32_t p_tot[64];
-    __shared__ int32_t s_kpub, s_stop;
+    __shared__ v2u c_at[kBuildChunk];            // candidates: {accuracy, latency + queue}
+    __shared__ int32_t c_pos[kBuildChunk];       //             rank position in the slice
+    __shared__ int32_t p_acc[kIndexCap];         // steps, in rank order
+    __shared__ uint32_t p_tot[kIndexCap];
+    __shared__ int32_t p_pos[kIndexCap];
+    __shared__ int32_t s_cnt[kBuildBlocks];      // survivors per block; then accepted candidates per wavefront
+    __shared__ int32_t s_K, s_trunc;
     const int32_t s = blockIdx.x;
     if (s >= tv.S) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const bool scanner = wave == 0;
     const int32_t t = s / tv.B, b = s - t * tv.B;
     const int32_t seg = tv.seg_off[t], L = tv.seg_len[t];
     if (L == 0) {  // no variants: the empty dummy body at offset 0 answers "nothing feasible"
@@ -130,12 +115,8 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
     const int32_t *__restrict__ accc = tv.acc_r + (int64_t)b * tv.Vp + seg;
     const uint32_t *__restrict__ totc = tv.tot_r + (int64_t)b * tv.Vp + seg;
 
-    // ---- phase A: the steps, in rank order; lane j of the first wavefront keeps step j
-    int32_t K = 0;
-    bool trunc = false;
-    int32_t st_acc = 0, st_pos = 0;
-    uint32_t st_tot = 0;
-    if (tid == 0) s_stop = 0;
+    // ---- phase A: the steps, in rank order
+    if (tid == 0) { s_K = 0; s_trunc = 0; }
     for (int32_t c0 = 0; c0 < L; c0 += kBuildChunk) {
         const int32_t n = L - c0 < kBuildChunk ? L - c0 : kBuildChunk;
         const int32_t nblk = (n + 63) >> 6;
@@ -158,78 +139,116 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
             }
         }
         __syncthreads();
-        // Rounds over growing groups of blocks: {0}, {1..3}, {4..12}, {13..39}, then 32 at a time.  The first block of
-        // a slice is absorbed directly; every later group is first filtered, by all wavefronts in
-        // parallel, against the steps known when its round starts, and then its few survivors are
-        // absorbed in rank order by the first wavefront.
-        int32_t g0 = 0;
+        // 0. (first chunk) the steps among the first 64 entries, found by the first wavefront alone:
+        //    nothing precedes them, and they already dominate most of what follows
         if (c0 == 0) {
-            if (scanner)
-                trunc = !absorb_block(lane < n, s_acc[lane], s_tot[lane], 0, lane, 0, K, st_acc, st_tot, st_pos);
-            g0 = 1;
-        }
-        for (int32_t gsz = 3; g0 < nblk; g0 += gsz, gsz = gsz * 3 < 32 ? gsz * 3 : 32) {
-            const int32_t g1 = g0 + gsz < nblk ? g0 + gsz : nblk;
-            if (scanner) {
-                if (lane < K) { p_acc[lane] = st_acc; p_tot[lane] = st_tot; }
-                if (lane == 0) { s_kpub = K; if (trunc) s_stop = 1; }
+            if (wave == 0) {
+                const int32_t a = s_acc[lane];
+                const uint32_t tt = s_tot[lane];
+                bool alive = lane < n;
+                uint64_t rest = __ballot(alive);
+                while (rest) {   // entry l is a step (nothing alive precedes it): retire what it dominates
+                    const int l = __builtin_ctzll(rest);
+                    const int32_t al = __builtin_amdgcn_readlane(a, l);
+                    const uint32_t tl = (uint32_t)__builtin_amdgcn_readlane((int)tt, l);
+                    alive = alive && !(l < lane && al >= a && tl <= tt);
+                    rest = __ballot(alive) & ~((2ull << l) - 1ull);
+                }
+                const uint64_t ok = __ballot(alive);
+                const int32_t at = (int32_t)lanes_below(ok), k = (int32_t)__builtin_popcountll(ok);
+                if (alive && at < kIndexCap) { p_acc[at] = a; p_tot[at] = tt; p_pos[at] = lane; }
+                if (lane == 0) { s_K = k < kIndexCap ? k : kIndexCap; s_trunc = k > kIndexCap; }
             }
             __syncthreads();
-            if (s_stop) break;
-            const int32_t kpub = s_kpub;
-            {   // every wavefront: its share of the group's blocks against the published steps
-                const int32_t pa_ = lane < kpub ? p_acc[lane] : 0;
-                const uint32_t pt_ = lane < kpub ? p_tot[lane] : 0u;
-                for (int32_t blk = g0 + wave; blk < g1; blk += kBuildThreads / 64) {
-                    const int32_t i = blk * 64 + lane;
-                    const int32_t a = s_acc[i];
-                    const uint32_t tt = s_tot[i];
-                    bool alive = i < n;
-                    for (int32_t j = 0; j < kpub; j += 4) {   // four steps per pass; lanes >= kpub hold (0, 0)
-                        bool d0, d1, d2, d3;
-                        {
-                            const int32_t aj = __builtin_amdgcn_readlane(pa_, j);
-                            const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)pt_, j);
-                            d0 = aj >= a && tj <= tt;
-                        }
-                        {
-                            const int32_t aj = __builtin_amdgcn_readlane(pa_, j + 1);
-                            const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)pt_, j + 1);
-                            d1 = j + 1 < kpub && aj >= a && tj <= tt;
-                        }
-                        {
-                            const int32_t aj = __builtin_amdgcn_readlane(pa_, j + 2);
-                            const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)pt_, j + 2);
-                            d2 = j + 2 < kpub && aj >= a && tj <= tt;
-                        }
-                        {
-                            const int32_t aj = __builtin_amdgcn_readlane(pa_, j + 3);
-                            const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)pt_, j + 3);
-                            d3 = j + 3 < kpub && aj >= a && tj <= tt;
-                        }
-                        alive = alive && !(d0 || d1 || d2 || d3);
-                        if (__ballot(alive) == 0) break;
-                    }
-                    const uint64_t live = __ballot(alive);
-                    if (lane == 0) s_live[blk] = live;
-                }
-            }
-            __syncthreads();
-            if (scanner) {   // survivors, in rank order, against the steps found since publishing
-                for (int32_t blk = g0; blk < g1 && !trunc; ++blk) {
-                    const uint64_t live = s_live[blk];
-                    if (live == 0) continue;
-                    const int32_t i = blk * 64 + lane;
-                    trunc = !absorb_block((live >> lane) & 1ull, s_acc[i], s_tot[i], c0 + blk * 64, lane, kpub,
-                                          K, st_acc, st_tot, st_pos);
-                }
-            }
+            if (s_trunc) break;
         }
-        if (scanner && trunc && lane == 0) s_stop = 1;
+        const int32_t K0 = s_K;   // steps known when the rest of the chunk starts
+
+        // 1. survivors of every block
+        uint64_t live[kBlocksPerWave];
+#pragma unroll
+        for (int u = 0; u < kBlocksPerWave; ++u) {
+            const int32_t blk = wave * kBlocksPerWave + u;
+            live[u] = 0;
+            if (blk < nblk && (c0 != 0 || blk != 0)) {
+                const int32_t i = blk * 64 + lane;
+                const int32_t a = s_acc[i];
+                const uint32_t tt = s_tot[i];
+                bool alive = i < n;
+                for (int32_t j = 0; j < K0; ++j) alive = alive && !(p_acc[j] >= a && p_tot[j] <= tt);
+                uint64_t rest = __ballot(alive);
+                while (rest) {   // what is left, against the entries of the block in front of it
+                    const int l = __builtin_ctzll(rest);
+                    rest &= rest - 1;
+                    const int32_t al = __builtin_amdgcn_readlane(a, l);
+                    const uint32_t tl = (uint32_t)__builtin_amdgcn_readlane((int)tt, l);
+                    alive = alive && !(l < lane && al >= a && tl <= tt);
+                }
+                live[u] = __ballot(alive);
+            }
+            if (lane == 0) s_cnt[blk] = (int32_t)__builtin_popcountll(live[u]);
+        }
         __syncthreads();
-        if (s_stop) break;
+
+        // 2. candidates, compacted in rank order
+        int32_t before = 0, total = 0;
+        for (int32_t k = 0; k < nblk; ++k) {
+            const int32_t c = s_cnt[k];
+            total += c;
+            before += k < wave * kBlocksPerWave ? c : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < kBlocksPerWave; ++u) {
+            const int32_t i = (wave * kBlocksPerWave + u) * 64 + lane;
+            if ((live[u] >> lane) & 1ull) {
+                const int32_t at = before + (int32_t)lanes_below(live[u]);
+                c_at[at] = v2u{(uint32_t)s_acc[i], s_tot[i]};
+                c_pos[at] = c0 + i;
+            }
+            before += (int32_t)__builtin_popcountll(live[u]);
+        }
+        __syncthreads();
+
+        // 3. steps among the candidates, one batch of kBuildThreads at a time
+        bool stop = false;
+        for (int32_t b0 = 0; b0 < total && !stop; b0 += kBuildThreads) {
+            const int32_t K1 = s_K;   // steps accepted so far
+            const int32_t c = b0 + tid;
+            const bool have = c < total;
+            const v2u me = c_at[have ? c : 0];
+            const int32_t a = (int32_t)me.x;
+            const uint32_t tt = me.y;
+            bool alive = have;
+            for (int32_t j = K0; j < K1; ++j) alive = alive && !(p_acc[j] >= a && p_tot[j] <= tt);
+            const int32_t w0 = b0 + wave * 64;   // first and last candidate of this wavefront
+            const int32_t last = w0 >= total ? b0 : (w0 + 63 < total ? w0 + 63 : total - 1);
+            for (int32_t e = b0; e < last; ++e) {
+                const v2u o = c_at[e];
+                alive = alive && !(e < c && (int32_t)o.x >= a && o.y <= tt);
+            }
+            const uint64_t ok = __ballot(alive);
+            if (lane == 0) s_cnt[wave] = (int32_t)__builtin_popcountll(ok);
+            __syncthreads();
+            int32_t at = K1, accepted = 0;
+            for (int w = 0; w < kBuildWaves; ++w) {
+                const int32_t cw = s_cnt[w];
+                accepted += cw;
+                at += w < wave ? cw : 0;
+            }
+            at += (int32_t)lanes_below(ok);
+            if (alive && at < kIndexCap) { p_acc[at] = a; p_tot[at] = tt; p_pos[at] = c_pos[c]; }
+            stop = K1 + accepted > kIndexCap;   // more steps than the index keeps: truncated
+            __syncthreads();
+            if (tid == 0) { s_K = stop ? kIndexCap : K1 + accepted; if (stop) s_trunc = 1; }
+            __syncthreads();
+        }
+        if (stop) break;
     }
-    if (!scanner) return;
+    if (wave != 0) return;
+    const int32_t K = s_K;
+    const bool trunc = s_trunc != 0;
+    const int32_t st_acc = lane < K ? p_acc[lane] : 0, st_pos = lane < K ? p_pos[lane] : 0;
+    const uint32_t st_tot = lane < K ? p_tot[lane] : 0u;
 
     // ---- phase B: one or two bodies of sorted keys and bit sets
     int32_t hi = __builtin_amdgcn_readlane(st_acc, 0), lo = hi;
@@ -247,10 +266,12 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
         row_hi |= ((uint32_t)__builtin_amdgcn_readlane(row, (int)j) >> 16) << (j * ix.row_hi_bits);
     const uint32_t re0 = body_re(k0), re1 = k1 ? body_re(k1) : 0u;
     const uint32_t rows = (2u * r0 + 3u) & ~3u, size0 = body_bytes(re0), size = rows + size0 + body_bytes(re1);
+    // room in the pool and in step_row: one 64-bit add on the pair of counters (pool in the low word)
     uint32_t off = 0, rec = 0;
     if (lane == 0) {
-        off = atomicAdd(&ix.ctrl[0], size);
-        rec = atomicAdd(&ix.ctrl[1], (uint32_t)K);
+        const unsigned long long old = atomicAdd((unsigned long long *)ix.ctrl, ((unsigned long long)K << 32) | size);
+        off = (uint32_t)old;
+        rec = (uint32_t)(old >> 32);
     }
     off = (uint32_t)__builtin_amdgcn_readfirstlane((int)off);
     rec = (uint32_t)__builtin_amdgcn_readfirstlane((int)rec);
