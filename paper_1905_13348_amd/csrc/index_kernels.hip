@@ -39,40 +39,46 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
 
 // ---------------------------------------------------------------- build
 
-// Writes the body of steps [g0, g0 + kb) (held one per lane, lanes g0..g0+kb-1) at `body`.
-__device__ __forceinline__ void write_body(uint8_t *body, int g0, int kb, int lane, int32_t st_acc,
-                                           uint32_t st_tot, int32_t acc_base)
+// Body of steps [g0, g0 + kb), held one per lane (lanes g0..g0+kb-1), in two parts: what can be
+// computed before the body's place in the pool is known, and the stores.
+struct BodyRegs {
+    int32_t pa, ps;     // position of this lane's step in the sorted accuracy / latency keys
+    uint32_t ma, ms;    // lane p: A[p] and S[p], the steps among the p most accurate / p fastest
+};
+__device__ __forceinline__ BodyRegs body_compute(int g0, int kb, int lane, int32_t st_acc, uint32_t st_tot)
 {
-    const bool mine = lane >= g0 && lane < g0 + kb;
-    int32_t pa = 0, ps = 0;   // position of this lane's step in the sorted key arrays
+    BodyRegs r{0, 0, 0u, 0u};
     for (int j = g0; j < g0 + kb; ++j) {
         const int32_t aj = __builtin_amdgcn_readlane(st_acc, j);
         const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)st_tot, j);
-        pa += (aj > st_acc || (aj == st_acc && j < lane)) ? 1 : 0;
-        ps += (tj < st_tot || (tj == st_tot && j < lane)) ? 1 : 0;
+        r.pa += (aj > st_acc || (aj == st_acc && j < lane)) ? 1 : 0;
+        r.ps += (tj < st_tot || (tj == st_tot && j < lane)) ? 1 : 0;
     }
+    for (int j = g0; j < g0 + kb; ++j) {
+        const int32_t paj = __builtin_amdgcn_readlane(r.pa, j), psj = __builtin_amdgcn_readlane(r.ps, j);
+        const uint32_t bit = 1u << (j - g0);
+        r.ma |= paj < lane ? bit : 0u;
+        r.ms |= psj < lane ? bit : 0u;
+    }
+    return r;
+}
+__device__ __forceinline__ void body_store(uint8_t *body, int g0, int kb, int lane, int32_t st_acc,
+                                           uint32_t st_tot, int32_t acc_base, const BodyRegs &r)
+{
     const uint32_t re = body_re((uint32_t)kb);
     uint16_t *k_acc = (uint16_t *)body;
     uint32_t *k_tot = (uint32_t *)(body + 2 * re);
     uint32_t *m_a = (uint32_t *)(body + 6 * re);
     uint32_t *m_s = (uint32_t *)(body + 10 * re);
-    if (mine) {
-        k_acc[pa] = (uint16_t)(st_acc - acc_base + 1);
-        k_tot[ps] = st_tot;
+    if (lane >= g0 && lane < g0 + kb) {
+        k_acc[r.pa] = (uint16_t)(st_acc - acc_base + 1);
+        k_tot[r.ps] = st_tot;
     }
     if (lane >= kb && lane < (int)re) {  // sentinels behind the keys (any lane will do)
         k_acc[lane] = 0;
         k_tot[lane] = 0xFFFFFFFFu;
     }
-    // lane p builds A[p] and S[p]: the steps among the p most accurate / p fastest
-    uint32_t ma = 0, ms = 0;
-    for (int j = g0; j < g0 + kb; ++j) {
-        const int32_t paj = __builtin_amdgcn_readlane(pa, j), psj = __builtin_amdgcn_readlane(ps, j);
-        const uint32_t bit = 1u << (j - g0);
-        ma |= paj < lane ? bit : 0u;
-        ms |= psj < lane ? bit : 0u;
-    }
-    if (lane <= kb) { m_a[lane] = ma; m_s[lane] = ms; }
+    if (lane <= kb) { m_a[lane] = r.ma; m_s[lane] = r.ms; }
 }
 
 constexpr int kBuildThreads = 512;
@@ -80,6 +86,20 @@ constexpr int kBuildWaves = kBuildThreads / 64;
 constexpr int kBuildChunk = 2048;                          // entries of a slice staged in LDS at a time
 constexpr int kBuildBlocks = kBuildChunk / 64;             // blocks of 64 entries in a chunk
 constexpr int kBlocksPerWave = kBuildBlocks / kBuildWaves;
+
+// alive &= none of the entries held by lanes [j0, j1) of (ra, rt) -- entry j of them being number
+// first + j of some rank-ordered list -- precedes entry number `me` and dominates (a, tt).
+// The loop reads lanes, not memory, so that nothing in it waits.
+__device__ __forceinline__ bool not_dominated(bool alive, int32_t a, uint32_t tt, int32_t ra, uint32_t rt,
+                                              int j0, int j1, int32_t first, int32_t me)
+{
+    for (int j = j0; j < j1; ++j) {
+        const int32_t aj = __builtin_amdgcn_readlane(ra, j);
+        const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)rt, j);
+        alive = alive && !(first + j < me && aj >= a && tj <= tt);
+    }
+    return alive;
+}
 
 // One workgroup per slice.  An entry of the slice is a step exactly when no entry ranked before it
 // has at least its accuracy and at most its latency-plus-queue; because that relation is
@@ -162,144 +182,162 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
             __syncthreads();
             if (s_trunc) break;
         }
-        const int32_t K0 = s_K;   // steps known when the rest of the chunk starts
-
-        // 1. survivors of every block
-        uint64_t live[kBlocksPerWave];
-#pragma unroll
-        for (int u = 0; u < kBlocksPerWave; ++u) {
-            const int32_t blk = wave * kBlocksPerWave + u;
-            live[u] = 0;
-            if (blk < nblk && (c0 != 0 || blk != 0)) {
-                const int32_t i = blk * 64 + lane;
-                const int32_t a = s_acc[i];
-                const uint32_t tt = s_tot[i];
-                bool alive = i < n;
-                for (int32_t j = 0; j < K0; ++j) alive = alive && !(p_acc[j] >= a && p_tot[j] <= tt);
-                uint64_t rest = __ballot(alive);
-                while (rest) {   // what is left, against the entries of the block in front of it
-                    const int l = __builtin_ctzll(rest);
-                    rest &= rest - 1;
-                    const int32_t al = __builtin_amdgcn_readlane(a, l);
-                    const uint32_t tl = (uint32_t)__builtin_amdgcn_readlane((int)tt, l);
-                    alive = alive && !(l < lane && al >= a && tl <= tt);
-                }
-                live[u] = __ballot(alive);
-            }
-            if (lane == 0) s_cnt[blk] = (int32_t)__builtin_popcountll(live[u]);
-        }
-        __syncthreads();
-
-        // 2. candidates, compacted in rank order
-        int32_t before = 0, total = 0;
-        for (int32_t k = 0; k < nblk; ++k) {
-            const int32_t c = s_cnt[k];
-            total += c;
-            before += k < wave * kBlocksPerWave ? c : 0;
-        }
-#pragma unroll
-        for (int u = 0; u < kBlocksPerWave; ++u) {
-            const int32_t i = (wave * kBlocksPerWave + u) * 64 + lane;
-            if ((live[u] >> lane) & 1ull) {
-                const int32_t at = before + (int32_t)lanes_below(live[u]);
-                c_at[at] = v2u{(uint32_t)s_acc[i], s_tot[i]};
-                c_pos[at] = c0 + i;
-            }
-            before += (int32_t)__builtin_popcountll(live[u]);
-        }
-        __syncthreads();
-
-        // 3. steps among the candidates, one batch of kBuildThreads at a time
+        // The first chunk goes in two groups of blocks, 1..7 and the rest: the steps of the first 512
+        // entries leave very little of the rest alive.
         bool stop = false;
-        for (int32_t b0 = 0; b0 < total && !stop; b0 += kBuildThreads) {
-            const int32_t K1 = s_K;   // steps accepted so far
-            const int32_t c = b0 + tid;
-            const bool have = c < total;
-            const v2u me = c_at[have ? c : 0];
-            const int32_t a = (int32_t)me.x;
-            const uint32_t tt = me.y;
-            bool alive = have;
-            for (int32_t j = K0; j < K1; ++j) alive = alive && !(p_acc[j] >= a && p_tot[j] <= tt);
-            const int32_t w0 = b0 + wave * 64;   // first and last candidate of this wavefront
-            const int32_t last = w0 >= total ? b0 : (w0 + 63 < total ? w0 + 63 : total - 1);
-            for (int32_t e = b0; e < last; ++e) {
-                const v2u o = c_at[e];
-                alive = alive && !(e < c && (int32_t)o.x >= a && o.y <= tt);
+        for (int32_t gb = c0 == 0 ? 1 : 0; gb < nblk && !stop;) {
+            const int32_t ge = (c0 == 0 && gb == 1 && nblk > 8) ? 8 : nblk;
+            const int32_t K0 = s_K;   // steps known when the group starts
+
+            // 1. survivors of every block of the group (blocks dealt round-robin to the wavefronts)
+            const int32_t ka = lane < K0 ? p_acc[lane] : 0;   // lane j holds step j
+            const uint32_t kt = lane < K0 ? p_tot[lane] : 0u;
+            uint64_t live[kBlocksPerWave];
+#pragma unroll
+            for (int u = 0; u < kBlocksPerWave; ++u) {
+                const int32_t blk = gb + wave + kBuildWaves * u;
+                live[u] = 0;
+                if (blk < ge) {
+                    const int32_t i = blk * 64 + lane;
+                    const int32_t a = s_acc[i];
+                    const uint32_t tt = s_tot[i];
+                    bool alive = not_dominated(i < n, a, tt, ka, kt, 0, K0, 0, 0x7FFFFFFF);
+                    uint64_t rest = __ballot(alive);
+                    while (rest) {   // what is left, against the entries of the block in front of it
+                        const int l = __builtin_ctzll(rest);
+                        rest &= rest - 1;
+                        const int32_t al = __builtin_amdgcn_readlane(a, l);
+                        const uint32_t tl = (uint32_t)__builtin_amdgcn_readlane((int)tt, l);
+                        alive = alive && !(l < lane && al >= a && tl <= tt);
+                    }
+                    live[u] = __ballot(alive);
+                    if (lane == 0) s_cnt[blk] = (int32_t)__builtin_popcountll(live[u]);
+                }
             }
-            const uint64_t ok = __ballot(alive);
-            if (lane == 0) s_cnt[wave] = (int32_t)__builtin_popcountll(ok);
             __syncthreads();
-            int32_t at = K1, accepted = 0;
-            for (int w = 0; w < kBuildWaves; ++w) {
-                const int32_t cw = s_cnt[w];
-                accepted += cw;
-                at += w < wave ? cw : 0;
+
+            // 2. candidates, compacted in rank order
+            int32_t pre[kBlocksPerWave], total = 0;
+            for (int32_t k = gb; k < ge; ++k) {
+#pragma unroll
+                for (int u = 0; u < kBlocksPerWave; ++u)
+                    if (k == gb + wave + kBuildWaves * u) pre[u] = total;
+                total += s_cnt[k];
             }
-            at += (int32_t)lanes_below(ok);
-            if (alive && at < kIndexCap) { p_acc[at] = a; p_tot[at] = tt; p_pos[at] = c_pos[c]; }
-            stop = K1 + accepted > kIndexCap;   // more steps than the index keeps: truncated
+#pragma unroll
+            for (int u = 0; u < kBlocksPerWave; ++u) {
+                const int32_t i = (gb + wave + kBuildWaves * u) * 64 + lane;
+                if ((live[u] >> lane) & 1ull) {   // only set for blocks of the group
+                    const int32_t at = pre[u] + (int32_t)lanes_below(live[u]);
+                    c_at[at] = v2u{(uint32_t)s_acc[i], s_tot[i]};
+                    c_pos[at] = c0 + i;
+                }
+            }
             __syncthreads();
-            if (tid == 0) { s_K = stop ? kIndexCap : K1 + accepted; if (stop) s_trunc = 1; }
-            __syncthreads();
+
+            // 3. steps among the candidates, one batch of kBuildThreads at a time
+            for (int32_t b0 = 0; b0 < total && !stop; b0 += kBuildThreads) {
+                const int32_t K1 = s_K;   // steps accepted so far
+                const int32_t c = b0 + tid;
+                const bool have = c < total;
+                const v2u me = c_at[have ? c : 0];
+                const int32_t a = (int32_t)me.x;
+                const uint32_t tt = me.y;
+                const int32_t na = lane < K1 ? p_acc[lane] : 0;   // steps accepted in this group before the batch
+                const uint32_t nt = lane < K1 ? p_tot[lane] : 0u;
+                bool alive = not_dominated(have, a, tt, na, nt, K0, K1, 0, 0x7FFFFFFF);
+                const int32_t w0 = b0 + wave * 64;   // first and last candidate of this wavefront
+                const int32_t last = w0 >= total ? b0 : (w0 + 63 < total ? w0 + 63 : total - 1);
+                for (int32_t e0 = b0; e0 < last; e0 += 64) {   // the candidates in front, 64 at a time
+                    const v2u o = c_at[e0 + lane < total ? e0 + lane : 0];
+                    alive = not_dominated(alive, a, tt, (int32_t)o.x, o.y, 0, last - e0 < 64 ? last - e0 : 64, e0, c);
+                }
+                const uint64_t ok = __ballot(alive);
+                if (lane == 0) s_cnt[wave] = (int32_t)__builtin_popcountll(ok);
+                __syncthreads();
+                int32_t at = K1, accepted = 0;
+                for (int w = 0; w < kBuildWaves; ++w) {
+                    const int32_t cw = s_cnt[w];
+                    accepted += cw;
+                    at += w < wave ? cw : 0;
+                }
+                at += (int32_t)lanes_below(ok);
+                if (alive && at < kIndexCap) { p_acc[at] = a; p_tot[at] = tt; p_pos[at] = c_pos[c]; }
+                stop = K1 + accepted > kIndexCap;   // more steps than the index keeps: truncated
+                __syncthreads();
+                if (tid == 0) { s_K = stop ? kIndexCap : K1 + accepted; if (stop) s_trunc = 1; }
+                __syncthreads();
+            }
+            gb = ge;
         }
         if (stop) break;
     }
-    if (wave != 0) return;
+    // ---- phase B: one or two bodies of sorted keys and bit sets.  The first wavefront takes the
+    // first body, the rows and the header, the second wavefront the second body; both compute
+    // their part while the request for room in the pool is under way.
+    if (wave > 1) return;
     const int32_t K = s_K;
     const bool trunc = s_trunc != 0;
     const int32_t st_acc = lane < K ? p_acc[lane] : 0, st_pos = lane < K ? p_pos[lane] : 0;
     const uint32_t st_tot = lane < K ? p_tot[lane] : 0u;
-
-    // ---- phase B: one or two bodies of sorted keys and bit sets
-    int32_t hi = __builtin_amdgcn_readlane(st_acc, 0), lo = hi;
-    for (int32_t j = 1; j < K; ++j) {
-        const int32_t aj = __builtin_amdgcn_readlane(st_acc, j);
-        hi = aj > hi ? aj : hi;
-        lo = aj < lo ? aj : lo;
-    }
     const int k0 = K < kBodySteps ? K : kBodySteps, k1 = K - k0;
-    // caller rows of the first steps: low 16 bits in front of the body, the bits above in the header
-    const int32_t row = lane < K ? tv.orig_r[(int64_t)b * tv.Vp + seg + st_pos] : 0;
+    if (wave == 1 && k1 == 0) return;
     const uint32_t r0 = (uint32_t)k0 < ix.hot_rows ? (uint32_t)k0 : ix.hot_rows;
-    uint32_t row_hi = 0;
-    for (uint32_t j = 0; j < r0; ++j)
-        row_hi |= ((uint32_t)__builtin_amdgcn_readlane(row, (int)j) >> 16) << (j * ix.row_hi_bits);
     const uint32_t re0 = body_re(k0), re1 = k1 ? body_re(k1) : 0u;
     const uint32_t rows = (2u * r0 + 3u) & ~3u, size0 = body_bytes(re0), size = rows + size0 + body_bytes(re1);
-    // room in the pool and in step_row: one 64-bit add on the pair of counters (pool in the low word)
-    uint32_t off = 0, rec = 0;
-    if (lane == 0) {
-        const unsigned long long old = atomicAdd((unsigned long long *)ix.ctrl, ((unsigned long long)K << 32) | size);
-        off = (uint32_t)old;
-        rec = (uint32_t)(old >> 32);
-    }
-    off = (uint32_t)__builtin_amdgcn_readfirstlane((int)off);
-    rec = (uint32_t)__builtin_amdgcn_readfirstlane((int)rec);
-    const bool fits = (uint64_t)off + size <= ix.pool_bytes && (uint64_t)rec + K <= ix.step_cap &&
-                      (int64_t)hi - (int64_t)tv.acc_base <= 65533 && lo >= tv.acc_base;   // 16-bit accuracy keys
-    if (!fits) {  // no body: every query of this slice goes to the rank-ordered scan
-        if (lane == 0) {
-            ix.hdr[s] = make_uint4(0u, kEmptyHdrY | kHdrPark | kHdrTrunc | kHdrDeep, 0u, 0u);
-            atomicAdd(&ix.ctrl[4], 1u);
+    __shared__ uint32_t s_off, s_fits;
+    int32_t row = 0;
+    uint32_t row_hi = 0;
+    if (wave == 0) {
+        // room in the pool and in step_row: one 64-bit add on the pair of counters (pool in the low word)
+        unsigned long long old = 0;
+        if (lane == 0) old = atomicAdd((unsigned long long *)ix.ctrl, ((unsigned long long)K << 32) | size);
+        // caller rows of the steps; of the first ones the low 16 bits go in front of the body, the
+        // bits above into the header
+        row = lane < K ? tv.orig_r[(int64_t)b * tv.Vp + seg + st_pos] : 0;
+        int32_t hi = __builtin_amdgcn_readlane(st_acc, 0), lo = hi;
+        for (int32_t j = 1; j < K; ++j) {
+            const int32_t aj = __builtin_amdgcn_readlane(st_acc, j);
+            hi = aj > hi ? aj : hi;
+            lo = aj < lo ? aj : lo;
         }
-        return;
-    }
-    uint8_t *body0 = ix.pool + off + rows;
-    write_body(body0, 0, k0, lane, st_acc, st_tot, tv.acc_base);
-    if (k1) write_body(body0 + size0, k0, k1, lane, st_acc, st_tot, tv.acc_base);
-    if (lane < K) {
-        ix.step_row[rec + lane] = row;
-        if ((uint32_t)lane < r0)   // in reverse in front of the body
-            *(uint16_t *)(body0 - 2 - 2 * lane) = (uint16_t)row;
-    }
-    if (lane == 0) {
-        const uint32_t y = (re0 << kHdrK0Shift) | (re1 << kHdrK1Shift) | (trunc ? kHdrTrunc : 0u) |
-                           ((k1 || trunc) ? kHdrDeep : 0u) | row_hi;
-        ix.hdr[s] = make_uint4(off + rows - 4u, y, rec, off + size);
-        atomicMax(&ix.ctrl[2], (uint32_t)k0);
-        if (trunc) atomicAdd(&ix.ctrl[3], 1u);
-        atomicAdd(&ix.ctrl[5], (uint32_t)K);
-        atomicMax(&ix.ctrl[6], (uint32_t)K);
+        const BodyRegs r = body_compute(0, k0, lane, st_acc, st_tot);
+        for (uint32_t j = 0; j < r0; ++j)
+            row_hi |= ((uint32_t)__builtin_amdgcn_readlane(row, (int)j) >> 16) << (j * ix.row_hi_bits);
+        const uint32_t off = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)old);
+        const uint32_t rec = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(old >> 32));
+        const bool fits = (uint64_t)off + size <= ix.pool_bytes && (uint64_t)rec + K <= ix.step_cap &&
+                          (int64_t)hi - (int64_t)tv.acc_base <= 65533 && lo >= tv.acc_base;   // 16-bit accuracy keys
+        if (lane == 0) { s_off = off; s_fits = fits; }
+        __syncthreads();
+        if (!fits) {  // no body: every query of this slice goes to the rank-ordered scan
+            if (lane == 0) {
+                ix.hdr[s] = make_uint4(0u, kEmptyHdrY | kHdrPark | kHdrTrunc | kHdrDeep, 0u, 0u);
+                atomicAdd(&ix.ctrl[4], 1u);
+            }
+            return;
+        }
+        uint8_t *body0 = ix.pool + off + rows;
+        body_store(body0, 0, k0, lane, st_acc, st_tot, tv.acc_base, r);
+        if (lane < K) {
+            ix.step_row[rec + lane] = row;
+            if ((uint32_t)lane < r0)   // in reverse in front of the body
+                *(uint16_t *)(body0 - 2 - 2 * lane) = (uint16_t)row;
+        }
+        if (lane == 0) {
+            const uint32_t y = (re0 << kHdrK0Shift) | (re1 << kHdrK1Shift) | (trunc ? kHdrTrunc : 0u) |
+                               ((k1 || trunc) ? kHdrDeep : 0u) | row_hi;
+            ix.hdr[s] = make_uint4(off + rows - 4u, y, rec, off + size);
+            atomicMax(&ix.ctrl[2], (uint32_t)k0);
+            if (trunc) atomicAdd(&ix.ctrl[3], 1u);
+            atomicAdd(&ix.ctrl[5], (uint32_t)K);
+            atomicMax(&ix.ctrl[6], (uint32_t)K);
+        }
+    } else {
+        const BodyRegs r = body_compute(k0, k1, lane, st_acc, st_tot);
+        __syncthreads();
+        if (!s_fits) return;
+        body_store(ix.pool + s_off + rows + size0, k0, k1, lane, st_acc, st_tot, tv.acc_base, r);
     }
 }
 
