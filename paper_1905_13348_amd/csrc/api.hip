@@ -79,7 +79,7 @@ struct infaas_sel {
     IndexView ix{};
     bool have_index = false;
     uint32_t index_lds_bytes = 0;     // dynamic LDS of the lookup kernel; 0 = read the index from global memory
-    uint32_t ix_stats[8] = {0};       // copy of ix.ctrl taken after the build at load time
+    uint32_t ix_stats[kCtlWords] = {0};      // copy of ix.ctrl taken after the build at load time
     int32_t *d_park = nullptr;        // queues of parked queries of the lookup kernel (fixed size)
     int64_t park_bytes = 0;
 
@@ -215,7 +215,7 @@ int create_index(infaas_sel *h)
     // one allocation: the pool, then the headers, so that one 32-bit offset reaches both
     ix.pool_bytes &= ~15u;
     bool ok = dev_alloc(&ix.pool, (size_t)ix.pool_bytes + (size_t)(S + 1) * 16) == hipSuccess &&
-              dev_alloc(&ix.step_row, ix.step_cap) == hipSuccess && dev_alloc(&ix.ctrl, 8) == hipSuccess;
+              dev_alloc(&ix.step_row, ix.step_cap) == hipSuccess && dev_alloc(&ix.ctrl, kCtlWords) == hipSuccess;
     ix.hdr = ok ? (uint4 *)(ix.pool + ix.pool_bytes) : nullptr;
     h->ix = ix;
     const size_t park = index_park_bytes(h->num_cus);
@@ -230,7 +230,8 @@ int create_index(infaas_sel *h)
     uint8_t dummy[kDummyBodyBytes] = {0};
     for (uint32_t i = 8; i < 16; ++i) dummy[i] = 0xFF;  // latency sentinels of the empty body (Re = 2)
     const int32_t none = -1;
-    const uint32_t ctrl0[8] = {kDummyBodyBytes, 1u, 1u, 0u, 0u, 0u, 0u, 0u};
+    uint32_t ctrl0[kCtlWords] = {0};
+    ctrl0[kCtlPool] = kDummyBodyBytes; ctrl0[kCtlSteps] = 1u; ctrl0[kCtlMaxK0] = 1u;
     const uint32_t empty_hdr[4] = {0u, kEmptyHdrY, 0u, 4u + body_bytes(2)};
     if (!HIP_OK(hipMemcpy(ix.pool, dummy, sizeof(dummy), hipMemcpyHostToDevice)) ||
         !HIP_OK(hipMemcpy(ix.step_row, &none, 4, hipMemcpyHostToDevice)) ||
@@ -243,7 +244,7 @@ int create_index(infaas_sel *h)
     }
     h->have_index = true;
     const int64_t fixed = kLdsCtrlBytes + lds_header_bytes((int32_t)S) + 16;
-    const int64_t need = fixed + h->ix_stats[0];
+    const int64_t need = fixed + h->ix_stats[kCtlPool];
     h->index_lds_bytes = need <= kLdsMax ? kLdsMax : 0u;
     // LDS left over holds the caller rows of the first steps of every slice (the steps most answers
     // come from), which saves those answers a gather from global memory.  Rebuild with that many.
@@ -261,7 +262,7 @@ int create_index(infaas_sel *h)
             h->free_index();
             return INFAAS_SEL_ERR_HIP;
         }
-        if (fixed + h->ix_stats[0] > kLdsMax) h->index_lds_bytes = 0u;   // cannot happen: hot rows fit by construction
+        if (fixed + h->ix_stats[kCtlPool] > kLdsMax) h->index_lds_bytes = 0u;   // cannot happen: hot rows fit by construction
     }
     return INFAAS_SEL_OK;
 }
@@ -284,7 +285,7 @@ bool use_index(const infaas_sel *h)
     // at load time more than half of the slices could not be indexed completely -- their queries
     // would mostly end in the in-kernel scan, which the bucketed scan engine does faster
     const int64_t S = (int64_t)h->T * h->B;
-    return 2 * ((int64_t)h->ix_stats[3] + h->ix_stats[4]) <= S;
+    return 2 * ((int64_t)h->ix_stats[kCtlTrunc] + h->ix_stats[kCtlNoBody]) <= S;
 }
 
 // One pass of the scan engine over n <= 2^28 queries.
@@ -665,11 +666,11 @@ int infaas_sel_get_info(infaas_sel_t *h, infaas_sel_info *out)
     out->scratch_bytes = h->scratch_bytes + h->park_bytes;
     if (h->have_index) {
         out->index_in_lds = h->index_lds_bytes > 0 ? 1 : 0;
-        out->index_truncated = (int32_t)(h->ix_stats[3] + h->ix_stats[4]);
-        out->index_max_steps = (int32_t)h->ix_stats[6];
+        out->index_truncated = (int32_t)(h->ix_stats[kCtlTrunc] + h->ix_stats[kCtlNoBody]);
+        out->index_max_steps = (int32_t)h->ix_stats[kCtlMaxK];
         out->index_hot_rows = (int32_t)h->ix.hot_rows;
-        out->index_bytes = (int64_t)h->ix_stats[0] + (int64_t)h->T * h->B * 16 + (int64_t)h->ix_stats[1] * 4;
-        out->index_steps = (int64_t)h->ix_stats[5];
+        out->index_bytes = (int64_t)h->ix_stats[kCtlPool] + (int64_t)h->T * h->B * 16 + (int64_t)h->ix_stats[kCtlSteps] * 4;
+        out->index_steps = (int64_t)h->ix_stats[kCtlSteps] - 1;   // step_row entries handed out (entry 0 is unused)
     }
     return INFAAS_SEL_OK;
 }

@@ -218,11 +218,12 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
 
             // 2. candidates, compacted in rank order
             int32_t pre[kBlocksPerWave], total = 0;
-            for (int32_t k = gb; k < ge; ++k) {
+            const int32_t cnt_l = gb + lane < ge ? s_cnt[gb + lane] : 0;   // lane k: block gb + k
+            for (int32_t k = 0; k < ge - gb; ++k) {
 #pragma unroll
                 for (int u = 0; u < kBlocksPerWave; ++u)
-                    if (k == gb + wave + kBuildWaves * u) pre[u] = total;
-                total += s_cnt[k];
+                    if (k == wave + kBuildWaves * u) pre[u] = total;
+                total += __builtin_amdgcn_readlane(cnt_l, k);
             }
 #pragma unroll
             for (int u = 0; u < kBlocksPerWave; ++u) {
@@ -256,8 +257,10 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
                 if (lane == 0) s_cnt[wave] = (int32_t)__builtin_popcountll(ok);
                 __syncthreads();
                 int32_t at = K1, accepted = 0;
+                const int32_t cnt_w = lane < kBuildWaves ? s_cnt[lane] : 0;
+#pragma unroll
                 for (int w = 0; w < kBuildWaves; ++w) {
-                    const int32_t cw = s_cnt[w];
+                    const int32_t cw = __builtin_amdgcn_readlane(cnt_w, w);
                     accepted += cw;
                     at += w < wave ? cw : 0;
                 }
@@ -291,7 +294,7 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
     if (wave == 0) {
         // room in the pool and in step_row: one 64-bit add on the pair of counters (pool in the low word)
         unsigned long long old = 0;
-        if (lane == 0) old = atomicAdd((unsigned long long *)ix.ctrl, ((unsigned long long)K << 32) | size);
+        if (lane == 0) old = atomicAdd((unsigned long long *)(ix.ctrl + kCtlPool), ((unsigned long long)K << 32) | size);
         // caller rows of the steps; of the first ones the low 16 bits go in front of the body, the
         // bits above into the header
         row = lane < K ? tv.orig_r[(int64_t)b * tv.Vp + seg + st_pos] : 0;
@@ -313,7 +316,7 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
         if (!fits) {  // no body: every query of this slice goes to the rank-ordered scan
             if (lane == 0) {
                 ix.hdr[s] = make_uint4(0u, kEmptyHdrY | kHdrPark | kHdrTrunc | kHdrDeep, 0u, 0u);
-                atomicAdd(&ix.ctrl[4], 1u);
+                atomicAdd(&ix.ctrl[kCtlNoBody], 1u);
             }
             return;
         }
@@ -328,10 +331,9 @@ __global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, Ind
             const uint32_t y = (re0 << kHdrK0Shift) | (re1 << kHdrK1Shift) | (trunc ? kHdrTrunc : 0u) |
                                ((k1 || trunc) ? kHdrDeep : 0u) | row_hi;
             ix.hdr[s] = make_uint4(off + rows - 4u, y, rec, off + size);
-            atomicMax(&ix.ctrl[2], (uint32_t)k0);
-            if (trunc) atomicAdd(&ix.ctrl[3], 1u);
-            atomicAdd(&ix.ctrl[5], (uint32_t)K);
-            atomicMax(&ix.ctrl[6], (uint32_t)K);
+            atomicMax(&ix.ctrl[kCtlMaxK0], (uint32_t)k0);   // statistics: nobody waits for these
+            atomicMax(&ix.ctrl[kCtlMaxK], (uint32_t)K);
+            if (trunc) atomicAdd(&ix.ctrl[kCtlTrunc], 1u);
         }
     } else {
         const BodyRegs r = body_compute(k0, k1, lane, st_acc, st_tot);
@@ -522,7 +524,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
 
     const uint32_t row_hi_mask = (1u << ix.row_hi_bits) - 1u;
     const int32_t acc_base_m1 = tv.acc_base - 1;   // acc_base is above INT32_MIN
-    const uint32_t max_k = ix.ctrl[2];
+    const uint32_t max_k = ix.ctrl[kCtlMaxK0];
     const int nit = 32 - __builtin_clz(max_k | 1u);    // <= 5
     const LdsMem lmem{};
     const GlobalMem gmem{ix.pool};

@@ -92,9 +92,18 @@ struct IndexView {
     uint32_t step_cap;
     uint32_t hot_rows;   // rows kept in front of the first body of every slice (fills the LDS left over)
     uint32_t row_hi_bits;// bits of a row number above its low 16
-    uint32_t *ctrl;      // [0] pool bump, [1] step bump, [2] most keys in one body, [3] truncated slices,
-                         // [4] slices without body, [5] total steps
+    uint32_t *ctrl;      // [kCtlWords] counters of the build, see kCtl*
 };
+// Counters of the index build.  Every slice takes its room with one 64-bit add on the pair
+// (kCtlPool, kCtlSteps) and waits for the answer; the statistics live on a cache line of their
+// own so that their updates, which nobody waits for, do not queue in front of those requests.
+constexpr int kCtlPool = 0;       // bytes of the pool handed out
+constexpr int kCtlSteps = 1;      // entries of step_row handed out (entry 0 is unused)
+constexpr int kCtlMaxK0 = 32;     // most steps in a first body (sets the probe count of the lookup)
+constexpr int kCtlTrunc = 33;     // slices with more steps than the index keeps
+constexpr int kCtlNoBody = 34;    // slices without a body
+constexpr int kCtlMaxK = 35;      // most steps in a slice
+constexpr int kCtlWords = 64;
 constexpr uint32_t kDummyBodyBytes = 64;     // 4 unused bytes, the empty body (28 bytes), padding
 constexpr uint32_t kEmptyHdrY = 2u << kHdrK0Shift;  // Re = 2 (sentinels only), no second body
 

@@ -81,13 +81,12 @@ __global__ __launch_bounds__(256) void k_update_load(TableView tv, int32_t n,
 {
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (tid == 0 && index_ctrl) {
-        index_ctrl[0] = kDummyBodyBytes;
-        index_ctrl[1] = 1;
-        index_ctrl[2] = 1;
-        index_ctrl[3] = 0;
-        index_ctrl[4] = 0;
-        index_ctrl[5] = 0;
-        index_ctrl[6] = 0;
+        index_ctrl[kCtlPool] = kDummyBodyBytes;
+        index_ctrl[kCtlSteps] = 1;
+        index_ctrl[kCtlMaxK0] = 1;
+        index_ctrl[kCtlTrunc] = 0;
+        index_ctrl[kCtlNoBody] = 0;
+        index_ctrl[kCtlMaxK] = 0;
     }
     if (tid >= (int64_t)n * tv.B)
         return;
