@@ -174,7 +174,8 @@ typedef struct {
     int32_t max_segment;        /* most variants in one task */
     int32_t lds_segment_limit;  /* effective value */
     int32_t wide_segments;      /* tasks handled by the device-wide scan path */
-    int32_t index_in_lds;       /* 1 when the whole staircase index fits in one CU's LDS */
+    int32_t index_in_lds;       /* 1 when the lookup kernel mirrors the index in LDS (all of it, or
+                                   as many slices as fit; the others are read from global memory) */
     int32_t index_truncated;    /* slices whose staircase was cut at its capacity or not stored */
     int32_t index_max_steps;    /* longest staircase of any slice (as stored) */
     int32_t index_hot_rows;     /* steps per slice whose caller row is kept beside the index in LDS */

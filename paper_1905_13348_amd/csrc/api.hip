@@ -245,7 +245,11 @@ int create_index(infaas_sel *h)
     h->have_index = true;
     const int64_t fixed = kLdsCtrlBytes + lds_header_bytes((int32_t)S) + 16;
     const int64_t need = fixed + h->ix_stats[kCtlPool];
-    h->index_lds_bytes = need <= kLdsMax ? kLdsMax : 0u;
+    // The lookup kernel mirrors the index in LDS when the slice headers leave at least half of it to
+    // the bodies; bodies that do not fit stay in global memory and their queries take the slower
+    // path inside the same kernel.  With more headers than that the kernel reads everything from
+    // global memory.
+    h->index_lds_bytes = fixed <= (int64_t)kLdsMax / 2 ? kLdsMax : 0u;
     // LDS left over holds the caller rows of the first steps of every slice (the steps most answers
     // come from), which saves those answers a gather from global memory.  Rebuild with that many.
     const int64_t spare = (int64_t)kLdsMax - need - 1536;   // keep room for staircases that grow with load
@@ -262,7 +266,6 @@ int create_index(infaas_sel *h)
             h->free_index();
             return INFAAS_SEL_ERR_HIP;
         }
-        if (fixed + h->ix_stats[kCtlPool] > kLdsMax) h->index_lds_bytes = 0u;   // cannot happen: hot rows fit by construction
     }
     return INFAAS_SEL_OK;
 }
