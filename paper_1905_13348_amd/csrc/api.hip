@@ -145,26 +145,30 @@ bool get_event(infaas_sel *h, hipEvent_t *e)
     return hipEventCreate(e) == hipSuccess;
 }
 
-// Brackets one kernel launch with events when timing is on.
+// Hands a launcher the pair of events to attach to its kernel when timing is on.
 struct LaunchTimer {
     infaas_sel *h;
-    hipStream_t st;
     TimedLaunch tl{};
+    LaunchEvents pair{};
     bool active = false;
-    LaunchTimer(infaas_sel *h_, int kid, hipStream_t st_) : h(h_), st(st_)
+    LaunchTimer(infaas_sel *h_, int kid, hipStream_t) : h(h_)
     {
         if (!h->timing) return;
         tl.kid = kid;
         if (!get_event(h, &tl.a)) return;
         if (!get_event(h, &tl.b)) { h->free_events.push_back(tl.a); return; }
-        active = hipEventRecord(tl.a, st) == hipSuccess;
-        if (!active) { h->free_events.push_back(tl.a); h->free_events.push_back(tl.b); }
+        pair = LaunchEvents{tl.a, tl.b};
+        active = true;
+    }
+    const LaunchEvents *ev() const { return active ? &pair : nullptr; }
+    void failed()   // the launch did not happen: the events were never recorded
+    {
+        if (active) { h->free_events.push_back(tl.a); h->free_events.push_back(tl.b); }
+        active = false;
     }
     ~LaunchTimer()
     {
-        if (!active) return;
-        if (hipEventRecord(tl.b, st) == hipSuccess) h->pending.push_back(tl);
-        else { h->free_events.push_back(tl.a); h->free_events.push_back(tl.b); }
+        if (active) h->pending.push_back(tl);
     }
 };
 
@@ -274,7 +278,7 @@ int create_index(infaas_sel *h)
 int index_pass(infaas_sel *h, const QueryView &q, hipStream_t st)
 {
     LaunchTimer t(h, INFAAS_SEL_K_INDEX_SELECT, st);
-    if (!HIP_OK(launch_index_select(h->tv, h->ix, q, h->d_park, h->index_lds_bytes, h->num_cus, st)))
+    if (!HIP_OK(launch_index_select(h->tv, h->ix, q, h->d_park, h->index_lds_bytes, h->num_cus, st, t.ev())))
         return INFAAS_SEL_ERR_HIP;
     return INFAAS_SEL_OK;
 }
@@ -302,31 +306,31 @@ int scan_pass(infaas_sel *h, const QueryView &q, hipStream_t st)
     h->cnt_dirty = true;
     {
         LaunchTimer t(h, INFAAS_SEL_K_HISTOGRAM, st);
-        if (!HIP_OK(launch_histogram(h->tv, q, h->sc, st))) return INFAAS_SEL_ERR_HIP;
+        if (!HIP_OK(launch_histogram(h->tv, q, h->sc, st, t.ev()))) return INFAAS_SEL_ERR_HIP;
     }
     {
         LaunchTimer t(h, INFAAS_SEL_K_PLAN, st);
-        if (!HIP_OK(launch_plan(h->tv, h->sc, st))) return INFAAS_SEL_ERR_HIP;
+        if (!HIP_OK(launch_plan(h->tv, h->sc, st, t.ev()))) return INFAAS_SEL_ERR_HIP;
     }
     h->cnt_dirty = false;
     const bool wide = h->wide_segments > 0;
     {
         LaunchTimer t(h, INFAAS_SEL_K_SCATTER, st);
-        if (!HIP_OK(launch_scatter(h->tv, q, h->sc, wide, st))) return INFAAS_SEL_ERR_HIP;
+        if (!HIP_OK(launch_scatter(h->tv, q, h->sc, wide, st, t.ev()))) return INFAAS_SEL_ERR_HIP;
     }
     if (h->max_lds_segment > 0) {
         LaunchTimer t(h, INFAAS_SEL_K_SCAN_LDS, st);
-        if (!HIP_OK(launch_scan_lds(h->tv, q, h->sc, h->max_lds_segment, h->num_cus, st)))
+        if (!HIP_OK(launch_scan_lds(h->tv, q, h->sc, h->max_lds_segment, h->num_cus, st, t.ev())))
             return INFAAS_SEL_ERR_HIP;
     }
     if (wide) {
         {
             LaunchTimer t(h, INFAAS_SEL_K_SCAN_WIDE, st);
-            if (!HIP_OK(launch_scan_wide(h->tv, q, h->sc, h->num_cus, st)))
+            if (!HIP_OK(launch_scan_wide(h->tv, q, h->sc, h->num_cus, st, t.ev())))
                 return INFAAS_SEL_ERR_HIP;
         }
         LaunchTimer t(h, INFAAS_SEL_K_FINISH_WIDE, st);
-        if (!HIP_OK(launch_finish_wide(h->tv, q, h->sc, st))) return INFAAS_SEL_ERR_HIP;
+        if (!HIP_OK(launch_finish_wide(h->tv, q, h->sc, st, t.ev()))) return INFAAS_SEL_ERR_HIP;
     }
     return INFAAS_SEL_OK;
 }
@@ -544,12 +548,12 @@ int infaas_sel_update_load(infaas_sel_t *h, int32_t n, const int32_t *d_variant_
     {
         LaunchTimer t(h, INFAAS_SEL_K_UPDATE, st);
         if (!HIP_OK(launch_update_load(h->tv, n, d_variant_idx, d_queue_us,
-                                       h->have_index ? h->ix.ctrl : nullptr, st)))
+                                       h->have_index ? h->ix.ctrl : nullptr, st, t.ev())))
             return INFAAS_SEL_ERR_HIP;
     }
     if (h->have_index) {  // the steps depend on the load: rebuild them behind the update
         LaunchTimer t(h, INFAAS_SEL_K_INDEX_BUILD, st);
-        if (!HIP_OK(launch_index_build(h->tv, h->ix, st))) return INFAAS_SEL_ERR_HIP;
+        if (!HIP_OK(launch_index_build(h->tv, h->ix, st, t.ev()))) return INFAAS_SEL_ERR_HIP;
     }
     return INFAAS_SEL_OK;
 }
@@ -645,7 +649,8 @@ int infaas_sel_get_timings(infaas_sel_t *h, infaas_sel_timings *out)
         if (hipEventSynchronize(p.b) == hipSuccess && hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) {
             h->acc.launches[p.kid] += 1;
             h->acc.total_ms[p.kid] += ms;
-        } else {
+        } else {   // e.g. the launch itself failed and the events were never attached
+            (void)hipGetLastError();
             rc = INFAAS_SEL_ERR_HIP;
         }
         h->free_events.push_back(p.a);

@@ -742,11 +742,10 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
 
 // ---------------------------------------------------------------- launchers
 
-hipError_t launch_index_build(const TableView &tv, const IndexView &ix, hipStream_t st)
+hipError_t launch_index_build(const TableView &tv, const IndexView &ix, hipStream_t st, const LaunchEvents *ev)
 {
     if (tv.S <= 0) return hipSuccess;
-    k_index_build<<<tv.S, kBuildThreads, 0, st>>>(tv, ix);
-    return hipGetLastError();
+    return launch_kernel(ev, k_index_build, dim3((unsigned)(tv.S)), dim3((unsigned)kBuildThreads), 0, st, tv, ix);
 }
 
 int index_select_blocks(int num_cus) { return num_cus; }
@@ -757,7 +756,7 @@ size_t index_park_bytes(int num_cus)
 }
 
 hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const QueryView &q,
-                               int32_t *park_mem, uint32_t lds_bytes, int num_cus, hipStream_t st)
+                               int32_t *park_mem, uint32_t lds_bytes, int num_cus, hipStream_t st, const LaunchEvents *ev)
 {
     const int blocks = index_select_blocks(num_cus);
     if (lds_bytes > 0) {
@@ -766,11 +765,10 @@ hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const Q
         hipError_t e = hipFuncSetAttribute((const void *)k_index_select<true>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
-        k_index_select<true><<<blocks, kSelThreads, lds_bytes, st>>>(tv, ix, q, park_mem, lds_bytes - fixed);
+        return launch_kernel(ev, k_index_select<true>, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), lds_bytes, st, tv, ix, q, park_mem, lds_bytes - fixed);
     } else {
-        k_index_select<false><<<blocks, kSelThreads, kLdsCtrlBytes, st>>>(tv, ix, q, park_mem, 0u);
+        return launch_kernel(ev, k_index_select<false>, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), kLdsCtrlBytes, st, tv, ix, q, park_mem, 0u);
     }
-    return hipGetLastError();
 }
 
 }  // namespace infaas

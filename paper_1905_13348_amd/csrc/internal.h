@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace infaas {
@@ -125,28 +126,44 @@ struct QueryView {
     int32_t *out;
 };
 
+// A pair of events that a launcher attaches to its kernel's dispatch (the events then carry the
+// kernel's own start and end time, without the gaps that separately recorded events include).
+struct LaunchEvents {
+    hipEvent_t start, stop;
+};
+
+// Launches `kernel`, with the events attached when ev is not null.
+template <class... P, class... A>
+inline hipError_t launch_kernel(const LaunchEvents *ev, void (*kernel)(P...), dim3 grid, dim3 block, size_t lds,
+                                hipStream_t st, A... args)
+{
+    if (ev) hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, st, ev->start, ev->stop, 0u, static_cast<P>(args)...);
+    else hipLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, st, static_cast<P>(args)...);
+    return hipGetLastError();
+}
+
 // Kernel launchers (scan engine).  Each returns the hipError_t of its launch.
 hipError_t launch_update_load(const TableView &tv, int32_t n, const int32_t *idx,
-                              const int32_t *val, uint32_t *index_ctrl, hipStream_t st);
+                              const int32_t *val, uint32_t *index_ctrl, hipStream_t st, const LaunchEvents *ev = nullptr);
 hipError_t launch_histogram(const TableView &tv, const QueryView &q, const ScanScratch &sc,
-                            hipStream_t st);
-hipError_t launch_plan(const TableView &tv, const ScanScratch &sc, hipStream_t st);
+                            hipStream_t st, const LaunchEvents *ev = nullptr);
+hipError_t launch_plan(const TableView &tv, const ScanScratch &sc, hipStream_t st, const LaunchEvents *ev = nullptr);
 hipError_t launch_scatter(const TableView &tv, const QueryView &q, const ScanScratch &sc,
-                          bool init_best, hipStream_t st);
+                          bool init_best, hipStream_t st, const LaunchEvents *ev = nullptr);
 hipError_t launch_scan_lds(const TableView &tv, const QueryView &q, const ScanScratch &sc,
-                           int32_t max_lds_segment, int num_cus, hipStream_t st);
+                           int32_t max_lds_segment, int num_cus, hipStream_t st, const LaunchEvents *ev = nullptr);
 hipError_t launch_scan_wide(const TableView &tv, const QueryView &q, const ScanScratch &sc,
-                            int num_cus, hipStream_t st);
+                            int num_cus, hipStream_t st, const LaunchEvents *ev = nullptr);
 hipError_t launch_finish_wide(const TableView &tv, const QueryView &q, const ScanScratch &sc,
-                              hipStream_t st);
+                              hipStream_t st, const LaunchEvents *ev = nullptr);
 
 // Kernel launchers (staircase index).
-hipError_t launch_index_build(const TableView &tv, const IndexView &ix, hipStream_t st);
+hipError_t launch_index_build(const TableView &tv, const IndexView &ix, hipStream_t st, const LaunchEvents *ev = nullptr);
 // lds_bytes: dynamic LDS of the lookup kernel when the index is mirrored in LDS, 0 to read it
 // from global memory.  park_mem: index_park_bytes() of device memory (16-byte aligned) for the
 // queues of parked queries; its size does not depend on the number of queries.
 hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const QueryView &q,
-                               int32_t *park_mem, uint32_t lds_bytes, int num_cus, hipStream_t st);
+                               int32_t *park_mem, uint32_t lds_bytes, int num_cus, hipStream_t st, const LaunchEvents *ev = nullptr);
 int index_select_blocks(int num_cus);
 size_t index_park_bytes(int num_cus);
 

@@ -387,44 +387,40 @@ __global__ __launch_bounds__(256) void k_finish_wide(TableView tv, QueryView q, 
 // ---------------------------------------------------------------- launchers
 
 hipError_t launch_update_load(const TableView &tv, int32_t n, const int32_t *idx,
-                              const int32_t *val, uint32_t *index_ctrl, hipStream_t st)
+                              const int32_t *val, uint32_t *index_ctrl, hipStream_t st, const LaunchEvents *ev)
 {
     if (n <= 0) return hipSuccess;
     const int64_t threads = (int64_t)n * tv.B;
-    k_update_load<<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(tv, n, idx, val, index_ctrl);
-    return hipGetLastError();
+    return launch_kernel(ev, k_update_load, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tv, n, idx, val, index_ctrl);
 }
 
 hipError_t launch_histogram(const TableView &tv, const QueryView &q, const ScanScratch &sc,
-                            hipStream_t st)
+                            hipStream_t st, const LaunchEvents *ev)
 {
     int blocks = (int)((q.n + 16383) / 16384);
     if (blocks > 2048) blocks = 2048;
     if (blocks < 1) blocks = 1;
     if (tv.S <= kLdsHistMaxSlices)
-        k_histogram<true><<<blocks, 256, (size_t)tv.S * 4, st>>>(tv, q, sc.cnt);
+        return launch_kernel(ev, k_histogram<true>, dim3((unsigned)blocks), dim3(256), (size_t)tv.S * 4, st, tv, q, sc.cnt);
     else
-        k_histogram<false><<<blocks, 256, 0, st>>>(tv, q, sc.cnt);
-    return hipGetLastError();
+        return launch_kernel(ev, k_histogram<false>, dim3((unsigned)blocks), dim3(256), 0, st, tv, q, sc.cnt);
 }
 
-hipError_t launch_plan(const TableView &tv, const ScanScratch &sc, hipStream_t st)
+hipError_t launch_plan(const TableView &tv, const ScanScratch &sc, hipStream_t st, const LaunchEvents *ev)
 {
-    k_plan<<<1, 1024, 0, st>>>(tv, sc);
-    return hipGetLastError();
+    return launch_kernel(ev, k_plan, dim3(1), dim3(1024), 0, st, tv, sc);
 }
 
 hipError_t launch_scatter(const TableView &tv, const QueryView &q, const ScanScratch &sc,
-                          bool init_best, hipStream_t st)
+                          bool init_best, hipStream_t st, const LaunchEvents *ev)
 {
     const int per_block = kScatterThreads * kScatterPerThread;
     int blocks = (q.n + per_block - 1) / per_block;
     if (blocks < 1) blocks = 1;
     if (tv.S <= kLdsHistMaxSlices)
-        k_scatter<true><<<blocks, kScatterThreads, (size_t)tv.S * 4, st>>>(tv, q, sc, init_best);
+        return launch_kernel(ev, k_scatter<true>, dim3((unsigned)blocks), dim3((unsigned)kScatterThreads), (size_t)tv.S * 4, st, tv, q, sc, init_best);
     else
-        k_scatter<false><<<blocks, kScatterThreads, 0, st>>>(tv, q, sc, init_best);
-    return hipGetLastError();
+        return launch_kernel(ev, k_scatter<false>, dim3((unsigned)blocks), dim3((unsigned)kScatterThreads), 0, st, tv, q, sc, init_best);
 }
 
 static int scan_blocks(int num_cus, size_t lds_bytes)
@@ -436,7 +432,7 @@ static int scan_blocks(int num_cus, size_t lds_bytes)
 }
 
 hipError_t launch_scan_lds(const TableView &tv, const QueryView &q, const ScanScratch &sc,
-                           int32_t max_lds_segment, int num_cus, hipStream_t st)
+                           int32_t max_lds_segment, int num_cus, hipStream_t st, const LaunchEvents *ev)
 {
     int32_t entries = (max_lds_segment + 255) & ~255;
     if (entries < 256) entries = 256;
@@ -446,12 +442,11 @@ hipError_t launch_scan_lds(const TableView &tv, const QueryView &q, const ScanSc
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    k_scan<false><<<scan_blocks(num_cus, lds), kScanThreads, lds, st>>>(tv, q, sc, entries);
-    return hipGetLastError();
+    return launch_kernel(ev, k_scan<false>, dim3((unsigned)(scan_blocks(num_cus, lds))), dim3((unsigned)kScanThreads), lds, st, tv, q, sc, entries);
 }
 
 hipError_t launch_scan_wide(const TableView &tv, const QueryView &q, const ScanScratch &sc,
-                            int num_cus, hipStream_t st)
+                            int num_cus, hipStream_t st, const LaunchEvents *ev)
 {
     int32_t entries = (tv.lds_limit + 255) & ~255;
     size_t lds = (size_t)entries * 12;
@@ -460,18 +455,16 @@ hipError_t launch_scan_wide(const TableView &tv, const QueryView &q, const ScanS
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    k_scan<true><<<scan_blocks(num_cus, lds), kScanThreads, lds, st>>>(tv, q, sc, entries);
-    return hipGetLastError();
+    return launch_kernel(ev, k_scan<true>, dim3((unsigned)(scan_blocks(num_cus, lds))), dim3((unsigned)kScanThreads), lds, st, tv, q, sc, entries);
 }
 
 hipError_t launch_finish_wide(const TableView &tv, const QueryView &q, const ScanScratch &sc,
-                              hipStream_t st)
+                              hipStream_t st, const LaunchEvents *ev)
 {
     int blocks = (q.n + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     if (blocks < 1) blocks = 1;
-    k_finish_wide<<<blocks, 256, 0, st>>>(tv, q, sc);
-    return hipGetLastError();
+    return launch_kernel(ev, k_finish_wide, dim3((unsigned)blocks), dim3(256), 0, st, tv, q, sc);
 }
 
 }  // namespace infaas
