@@ -256,7 +256,7 @@ int create_index(infaas_sel *h)
     h->index_lds_bytes = fixed <= (int64_t)kLdsMax / 2 ? kLdsMax : 0u;
     // LDS left over holds the caller rows of the first steps of every slice (the steps most answers
     // come from), which saves those answers a gather from global memory.  Rebuild with that many.
-    const int64_t spare = (int64_t)kLdsMax - need - 1536;   // keep room for staircases that grow with load
+    const int64_t spare = (int64_t)kLdsMax - need - 1024;   // keep room for staircases that grow with load
     // 2 bytes each, in pairs; the bits of a row number above 16 go into a 14-bit header field
     const uint32_t row_bits = h->V > 1 ? 64u - (uint32_t)__builtin_clzll((unsigned long long)(h->V - 1)) : 1u;
     h->ix.row_hi_bits = row_bits > 16 ? row_bits - 16 : 0u;
