@@ -52,6 +52,10 @@ class Oracle:
             fn = getattr(lib, name)
             fn.argtypes = sel_args
             fn.restype = ctypes.c_int
+        for name in ("oracle_select_closest", "oracle_select_closest_literal"):
+            fn = getattr(lib, name)
+            fn.argtypes = sel_args + [_I32P]
+            fn.restype = ctypes.c_int
         lib.oracle_count_feasible.argtypes = [ctypes.c_int64, ctypes.c_int32, _I32P, _I32P, _I32P,
                                               _I32P, ctypes.c_int64, _I32P, _I32P, _I32P, _I32P,
                                               _I32P]
@@ -92,6 +96,33 @@ class Oracle:
         """Literal O(N*V) scan in the caller's row order."""
         return self._select(self._lib.oracle_select_literal, task_id, acc_bp, lat_us, cost,
                             queue_us, q_task, q_slo, q_min_acc, q_bidx)
+
+    def _closest(self, fn, task_id, acc_bp, lat_us, cost, queue_us, q_task, q_slo, q_min_acc, q_bidx):
+        task_id, acc_bp, queue_us = _i32(task_id), _i32(acc_bp), _i32(queue_us)
+        lat_us, cost = _i32(lat_us), _i32(cost)
+        V, B = lat_us.shape
+        assert cost.shape == lat_us.shape and acc_bp.shape == (V,) and queue_us.shape == (V,)
+        q_task, q_slo, q_min_acc, q_bidx = _i32(q_task), _i32(q_slo), _i32(q_min_acc), _i32(q_bidx)
+        N = q_task.shape[0]
+        assert q_slo.shape == (N,) and q_min_acc.shape == (N,) and q_bidx.shape == (N,)
+        out = np.empty(N, dtype=np.int32)
+        closest = np.empty(N, dtype=np.int32)
+        rc = fn(V, B, _ptr(task_id), _ptr(acc_bp), _ptr(lat_us), _ptr(cost), _ptr(queue_us),
+                N, _ptr(q_task), _ptr(q_slo), _ptr(q_min_acc), _ptr(q_bidx), _ptr(out), _ptr(closest))
+        if rc != 0:
+            raise ValueError("oracle rejected its arguments")
+        return out, closest
+
+    def select_closest(self, task_id, acc_bp, lat_us, cost, queue_us, q_task, q_slo, q_min_acc, q_bidx):
+        """(selected variant or -1, closest variant) per query; grouped, multi-threaded."""
+        return self._closest(self._lib.oracle_select_closest, task_id, acc_bp, lat_us, cost, queue_us,
+                             q_task, q_slo, q_min_acc, q_bidx)
+
+    def select_closest_literal(self, task_id, acc_bp, lat_us, cost, queue_us, q_task, q_slo, q_min_acc,
+                               q_bidx):
+        """The same by the literal O(N*V) scan."""
+        return self._closest(self._lib.oracle_select_closest_literal, task_id, acc_bp, lat_us, cost,
+                             queue_us, q_task, q_slo, q_min_acc, q_bidx)
 
     def count_feasible(self, task_id, acc_bp, lat_us, queue_us, q_task, q_slo, q_min_acc, q_bidx):
         task_id, acc_bp, queue_us, lat_us = _i32(task_id), _i32(acc_bp), _i32(queue_us), _i32(lat_us)

@@ -41,7 +41,11 @@
  * numpy enumerator on tiny tables, invariants (chosen variant feasible, nothing
  * feasible is smaller, -1 iff nothing feasible), special cases that reduce to a
  * lexicographic sort, monotonicity and shift invariance, and seeded mutants of
- * this file that each pin set must reject.  The only statement that stays
+ * this file that each pin set must reject.  The closest-variant search further
+ * down follows a reading of this file's own (the paper names no distance); it is
+ * pinned by two independently written numpy enumerators (one by cases, one by a
+ * sorted key), structural properties, extreme values and its own mutants.
+ * The only statement that stays
  * "parity unpinned" is the count of valid options printed in Table 7, because
  * the profiles behind it are not published.
  */
@@ -210,6 +214,141 @@ void oracle_update_load(int64_t V, int32_t *queue_us, int64_t n,
             continue;
         queue_us[v] = new_queue_us[i];
     }
+}
+
+/*
+ * Closest variant (Section 4.1, last step of Case I): when no registered variant
+ * meets the requirements, a variant that comes closest to the accuracy and/or
+ * latency target is suggested.  The paper names no distance.  The reading taken
+ * here orders the variants of the task by, in this order,
+ *     1. how many of the two requirements they miss (0, 1 or 2),
+ *     2. by how much lat_us[v][b] + queue_us[v] exceeds slo_us (0 when it fits),
+ *     3. by how much acc_bp[v] falls short of min_acc_bp (0 when it meets it),
+ *     4. the selection key (cost[v][b], lat_us[v][b], v),
+ * all differences formed in 64 bits, and suggests the first one.  A variant that
+ * meets both requirements has (0, 0, 0) in front of its key, so for a query with
+ * a non-empty feasible set the suggestion IS the selected variant.  The result is
+ * -1 only when the task has no variants at that batch index (task or batch index
+ * outside the table included).
+ */
+typedef struct {
+    int missed;          /* requirements not met */
+    int64_t over_us;     /* latency beyond the objective */
+    int64_t short_bp;    /* accuracy below the minimum */
+} distance_t;
+
+static distance_t distance_of(const int32_t *acc_bp, const int32_t *lat_us, const int32_t *queue_us,
+                              int32_t B, int64_t v, int32_t slo_us, int32_t min_acc_bp, int32_t b)
+{
+    distance_t d;
+    int64_t total = (int64_t)lat_us[v * B + b] + (int64_t)queue_us[v];
+    d.over_us = total > (int64_t)slo_us ? total - (int64_t)slo_us : 0;
+    d.short_bp = acc_bp[v] < min_acc_bp ? (int64_t)min_acc_bp - (int64_t)acc_bp[v] : 0;
+    d.missed = (d.over_us > 0) + (d.short_bp > 0);
+    return d;
+}
+
+/* 1 when v comes before w in the order above. */
+static int closer(const int32_t *acc_bp, const int32_t *lat_us, const int32_t *cost,
+                  const int32_t *queue_us, int32_t B, int32_t slo_us, int32_t min_acc_bp, int32_t b,
+                  int64_t v, int64_t w)
+{
+    distance_t dv = distance_of(acc_bp, lat_us, queue_us, B, v, slo_us, min_acc_bp, b);
+    distance_t dw = distance_of(acc_bp, lat_us, queue_us, B, w, slo_us, min_acc_bp, b);
+    if (dv.missed != dw.missed)
+        return dv.missed < dw.missed;
+    if (dv.over_us != dw.over_us)
+        return dv.over_us < dw.over_us;
+    if (dv.short_bp != dw.short_bp)
+        return dv.short_bp < dw.short_bp;
+    return cheaper(lat_us, cost, B, b, v, w);
+}
+
+/*
+ * Literal form: every query looks at every row of the table.  out_variant gets
+ * the selection (as oracle_select_literal), out_closest the suggestion.
+ */
+int oracle_select_closest_literal(int64_t V, int32_t B,
+                                  const int32_t *task_id, const int32_t *acc_bp,
+                                  const int32_t *lat_us, const int32_t *cost, const int32_t *queue_us,
+                                  int64_t N,
+                                  const int32_t *q_task, const int32_t *q_slo_us,
+                                  const int32_t *q_min_acc_bp, const int32_t *q_batch_idx,
+                                  int32_t *out_variant, int32_t *out_closest)
+{
+    if (V < 0 || B <= 0 || N < 0)
+        return -1;
+    for (int64_t q = 0; q < N; ++q) {
+        int64_t best = -1;
+        int32_t b = q_batch_idx[q];
+        if (b >= 0 && b < B) {
+            for (int64_t v = 0; v < V; ++v) {
+                if (task_id[v] != q_task[q])
+                    continue;
+                if (best < 0 || closer(acc_bp, lat_us, cost, queue_us, B, q_slo_us[q], q_min_acc_bp[q], b, v, best))
+                    best = v;
+            }
+        }
+        out_closest[q] = (int32_t)best;
+        out_variant[q] = (best >= 0 && feasible(acc_bp, lat_us, queue_us, B, best, q_slo_us[q], q_min_acc_bp[q], b))
+                             ? (int32_t)best : -1;
+    }
+    return 0;
+}
+
+/* Grouped form of the same search (rows listed per task once, queries on several host threads). */
+int oracle_select_closest(int64_t V, int32_t B,
+                          const int32_t *task_id, const int32_t *acc_bp,
+                          const int32_t *lat_us, const int32_t *cost, const int32_t *queue_us,
+                          int64_t N,
+                          const int32_t *q_task, const int32_t *q_slo_us,
+                          const int32_t *q_min_acc_bp, const int32_t *q_batch_idx,
+                          int32_t *out_variant, int32_t *out_closest)
+{
+    if (V < 0 || B <= 0 || N < 0)
+        return -1;
+    int64_t T = 0;
+    for (int64_t v = 0; v < V; ++v) {
+        if (task_id[v] < 0)
+            return -1;
+        if ((int64_t)task_id[v] + 1 > T)
+            T = (int64_t)task_id[v] + 1;
+    }
+    int64_t *first = (int64_t *)calloc((size_t)T + 1, sizeof(int64_t));
+    int64_t *rows = (int64_t *)malloc(sizeof(int64_t) * (size_t)(V > 0 ? V : 1));
+    int64_t *fill = (int64_t *)calloc((size_t)T + 1, sizeof(int64_t));
+    if (!first || !rows || !fill) {
+        free(first); free(rows); free(fill);
+        return -1;
+    }
+    for (int64_t v = 0; v < V; ++v)
+        first[task_id[v] + 1] += 1;
+    for (int64_t t = 0; t < T; ++t)
+        first[t + 1] += first[t];
+    for (int64_t v = 0; v < V; ++v) {
+        int64_t t = task_id[v];
+        rows[first[t] + fill[t]] = v;
+        fill[t] += 1;
+    }
+
+#pragma omp parallel for schedule(dynamic, 4096)
+    for (int64_t q = 0; q < N; ++q) {
+        int64_t best = -1;
+        int32_t b = q_batch_idx[q];
+        int64_t t = q_task[q];
+        if (b >= 0 && b < B && t >= 0 && t < T) {
+            for (int64_t i = first[t]; i < first[t + 1]; ++i) {
+                int64_t v = rows[i];
+                if (best < 0 || closer(acc_bp, lat_us, cost, queue_us, B, q_slo_us[q], q_min_acc_bp[q], b, v, best))
+                    best = v;
+            }
+        }
+        out_closest[q] = (int32_t)best;
+        out_variant[q] = (best >= 0 && feasible(acc_bp, lat_us, queue_us, B, best, q_slo_us[q], q_min_acc_bp[q], b))
+                             ? (int32_t)best : -1;
+    }
+    free(first); free(rows); free(fill);
+    return 0;
 }
 
 /* Host threads the grouped form uses. */

@@ -43,3 +43,67 @@ def count_np(task_id, acc_bp, lat_us, queue_us, q_task, q_slo, q_min_acc, q_bidx
         ok &= (lat_us[:, b] + np.asarray(queue_us, dtype=np.int64)) <= int(q_slo[q])
         out[q] = int(ok.sum())
     return out
+
+
+def closest_np(task_id, acc_bp, lat_us, cost, queue_us, q_task, q_slo, q_min_acc, q_bidx):
+    """Closest variant by CASES instead of one lexicographic key: if some variant of the task
+    meets the latency objective, the most accurate of those; else if some variant meets the
+    accuracy minimum, the fastest (latency + queue) of those; else the fastest of all, the most
+    accurate among equally fast ones.  Remaining ties by (cost, lat, row).  A query with a
+    feasible variant gets the selected variant.  -1 when the task has no row at that batch index."""
+    task_id = np.asarray(task_id, dtype=np.int64)
+    acc_bp = np.asarray(acc_bp, dtype=np.int64)
+    lat_us = np.asarray(lat_us, dtype=np.int64)
+    cost = np.asarray(cost, dtype=np.int64)
+    queue_us = np.asarray(queue_us, dtype=np.int64)
+    V, B = lat_us.shape
+    out = np.full(len(q_task), -1, dtype=np.int32)
+
+    def first_by_key(cand, b):
+        return cand[np.lexsort((cand, lat_us[cand, b], cost[cand, b]))[0]]
+
+    for q in range(len(q_task)):
+        b = int(q_bidx[q])
+        if not 0 <= b < B:
+            continue
+        rows = np.flatnonzero(task_id == int(q_task[q]))
+        if rows.size == 0:
+            continue
+        tot = lat_us[rows, b] + queue_us[rows]
+        fits = tot <= int(q_slo[q])
+        accurate = acc_bp[rows] >= int(q_min_acc[q])
+        if (fits & accurate).any():
+            out[q] = first_by_key(rows[fits & accurate], b)
+        elif fits.any():
+            r = rows[fits]
+            out[q] = first_by_key(r[acc_bp[r] == acc_bp[r].max()], b)
+        elif accurate.any():
+            r = rows[accurate]; t = tot[accurate]
+            out[q] = first_by_key(r[t == t.min()], b)
+        else:
+            r = rows[tot == tot.min()]
+            out[q] = first_by_key(r[acc_bp[r] == acc_bp[r].max()], b)
+    return out
+
+
+def closest_key_np(task_id, acc_bp, lat_us, cost, queue_us, q_task, q_slo, q_min_acc, q_bidx):
+    """The same by sorting the task's rows on (missed, overshoot, shortfall, cost, lat, row)."""
+    task_id = np.asarray(task_id, dtype=np.int64)
+    acc_bp = np.asarray(acc_bp, dtype=np.int64)
+    lat_us = np.asarray(lat_us, dtype=np.int64)
+    cost = np.asarray(cost, dtype=np.int64)
+    queue_us = np.asarray(queue_us, dtype=np.int64)
+    V, B = lat_us.shape
+    out = np.full(len(q_task), -1, dtype=np.int32)
+    for q in range(len(q_task)):
+        b = int(q_bidx[q])
+        if not 0 <= b < B:
+            continue
+        rows = np.flatnonzero(task_id == int(q_task[q]))
+        if rows.size == 0:
+            continue
+        over = np.maximum(lat_us[rows, b] + queue_us[rows] - int(q_slo[q]), 0)
+        short = np.maximum(int(q_min_acc[q]) - acc_bp[rows], 0)
+        missed = (over > 0).astype(np.int64) + (short > 0)
+        out[q] = rows[np.lexsort((rows, lat_us[rows, b], cost[rows, b], short, over, missed))[0]]
+    return out

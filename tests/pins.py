@@ -9,7 +9,7 @@ import os
 import numpy as np
 
 import workloads
-from bruteforce_np import count_np, select_np
+from bruteforce_np import closest_key_np, closest_np, count_np, select_np
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 I32MAX = 2**31 - 1
@@ -290,4 +290,114 @@ ALL_PINS = [
     pin_no_wraparound,
     pin_monotone_and_shift,
     pin_update_load,
+]
+
+
+# ---------------------------------------------------------------- closest variant (Section 4.1, last step)
+
+def _both_closest(o, *args):
+    a = o.select_closest(*args)
+    b = o.select_closest_literal(*args)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]), "grouped and literal oracle disagree"
+    assert np.array_equal(a[0], o.select(*args)), "selection differs between the two entry points"
+    return a
+
+
+def pin_closest_worked_example(o):
+    """The three variants of Tables 2/3 (A 200 ms, B 20 ms, C 15 ms; costs 1, 3, 16): consequences
+    of the reading, not printed values.  SLO 10 ms: nothing fits, C overshoots least.  Accuracy
+    floor above all three with a generous SLO: all miss only the accuracy, by the same amount, so
+    the cheapest (A) is suggested.  Both missed by all: least overshoot first (C)."""
+    names, lat_ms, cost, _ = _read_worked_example()
+    V = len(names)
+    task = np.zeros(V, np.int32)
+    acc = np.full(V, 7600, np.int32)
+    lat = (np.array(lat_ms, np.int32) * 1000).reshape(V, 1)
+    cst = np.array(cost, np.int32).reshape(V, 1)
+    zero = np.zeros(V, np.int32)
+    sel, clo = _both_closest(o, task, acc, lat, cst, zero, [0, 0, 0, 0], [10000, 300000, 10000, 50000],
+                             [0, 7700, 7700, 0], [0] * 4)
+    assert sel.tolist() == [-1, -1, -1, 1]
+    assert clo.tolist() == [2, 0, 2, 1]
+    # a slightly more accurate B wins the accuracy-only case over the cheaper A
+    acc2 = np.array([7600, 7650, 7600], np.int32)
+    assert _both_closest(o, task, acc2, lat, cst, zero, [0], [300000], [7700], [0])[1][0] == 1
+    # fitting the latency counts before accuracy shortfall: with SLO 17 ms only C fits, and it is
+    # suggested although A and B are equally accurate and cheaper
+    assert _both_closest(o, task, acc, lat, cst, zero, [0], [17000], [7700], [0])[1][0] == 2
+
+
+def pin_closest_numpy(o):
+    """Tiny tables with many ties against two numpy formulations (by cases, by sorted key)."""
+    rng = np.random.default_rng(11)
+    for trial in range(40):
+        V = int(rng.integers(1, 65)); T = int(rng.integers(1, 6)); B = int(rng.integers(1, 5))
+        span = int(rng.choice([2, 3, 5, 9, 50]))
+        tab, qry = _tiny_random(rng, V, T, B, 300, span)
+        sel, clo = _both_closest(o, *tab, *qry)
+        assert np.array_equal(clo, closest_np(*tab, *qry)), f"trial {trial} (cases)"
+        assert np.array_equal(clo, closest_key_np(*tab, *qry)), f"trial {trial} (key)"
+        assert np.array_equal(sel, select_np(*tab, *qry))
+
+
+def pin_closest_structure(o):
+    """Config 0: the suggestion equals the selection wherever one exists; it is -1 exactly for
+    queries outside the table; it belongs to the query's task; and when nothing is feasible it
+    misses no more requirements than any other variant of the task."""
+    tb = workloads.make_table(0)
+    q = workloads.make_queries(0)
+    table = (tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us)
+    qt = q.task.copy(); qb = q.batch_idx.copy()
+    qt[:50] = tb.num_tasks + 3; qb[50:100] = -1           # some queries outside the table
+    sel, clo = _both_closest(o, *table, qt, q.slo_us, q.min_acc_bp, qb)
+    hit = sel >= 0
+    assert np.array_equal(clo[hit], sel[hit])
+    outside = (qt < 0) | (qt >= tb.num_tasks) | (qb < 0) | (qb >= tb.B)
+    assert np.array_equal(clo < 0, outside)
+    inside = ~outside
+    assert np.all(tb.task_id[clo[inside]] == qt[inside])
+    tot = tb.lat_us.astype(np.int64) + tb.queue_us.astype(np.int64)[:, None]
+    n_none = 0
+    for i in np.flatnonzero(inside & ~hit)[:400]:
+        rows = np.flatnonzero(tb.task_id == qt[i])
+        missed = (tot[rows, qb[i]] > q.slo_us[i]).astype(int) + (tb.acc_bp[rows] < q.min_acc_bp[i])
+        w = clo[i]
+        mw = int(tot[w, qb[i]] > q.slo_us[i]) + int(tb.acc_bp[w] < q.min_acc_bp[i])
+        assert mw == missed.min() and mw >= 1
+        n_none += 1
+    assert n_none > 50
+
+
+def pin_closest_no_wraparound(o):
+    """Overshoot and shortfall are exact differences: extreme int32 values must not wrap."""
+    lo = -2**31
+    task = np.zeros(3, np.int32)
+    acc = np.array([lo, 0, I32MAX], np.int32)
+    lat = np.array([[I32MAX], [I32MAX], [10]], np.int32)
+    cost = np.array([[1], [1], [1]], np.int32)
+    queue = np.array([I32MAX, 0, I32MAX], np.int32)
+    # slo = INT32_MIN: overshoots are 2^32+2^31-2, 2^32-1 and 2^31+2^31+9: row 1 is closest
+    sel, clo = _both_closest(o, task, acc, lat, cost, queue, [0], [lo], [lo], [0])
+    assert sel[0] == -1 and clo[0] == 1
+    # all fit (slo max is below two of the totals, so only row 1 fits): accuracy shortfall from INT32_MAX
+    sel, clo = _both_closest(o, task, acc, lat, cost, queue, [0], [I32MAX], [I32MAX], [0])
+    assert sel[0] == -1 and clo[0] == 1          # only row 1 fits the latency; it misses accuracy by 2^31-1
+    # an overshoot of 2^32 + 4 must not look like 4: row 1 (overshoot 110) is closer
+    lat3 = np.array([[I32MAX], [100], [I32MAX]], np.int32)
+    queue3 = np.array([I32MAX - 4, 0, I32MAX], np.int32)
+    sel, clo = _both_closest(o, task, np.zeros(3, np.int32), lat3, cost, queue3, [0], [-10], [0], [0])
+    assert sel[0] == -1 and clo[0] == 1
+    lat2 = np.array([[5], [6], [2000000000]], np.int32)
+    zero = np.zeros(3, np.int32)
+    sel, clo = _both_closest(o, task, acc, lat2, cost, zero, [0], [100], [I32MAX - 1], [0])
+    assert sel[0] == -1 and clo[0] == 1          # rows 0, 1 fit; shortfalls 2^32-2 and 2^31-2
+    sel, clo = _both_closest(o, task, acc, lat2, cost, zero, [0], [2], [I32MAX], [0])
+    assert sel[0] == -1 and clo[0] == 2          # nothing fits, row 2 is accurate: it wins despite its overshoot
+
+
+CLOSEST_PINS = [
+    pin_closest_worked_example,
+    pin_closest_numpy,
+    pin_closest_structure,
+    pin_closest_no_wraparound,
 ]

@@ -49,6 +49,42 @@ MUTANTS = [
 ]
 
 
+# planted mistakes in the closest-variant search
+CLOSEST_MUTANTS = [
+    ("closest_missed_count_ignored", "if (dv.missed != dw.missed)", "if (0)"),
+    ("closest_shortfall_before_overshoot", "if (dv.over_us != dw.over_us)\n        return dv.over_us < dw.over_us;",
+     "if (dv.short_bp != dw.short_bp)\n        return dv.short_bp < dw.short_bp;\n    if (dv.over_us != dw.over_us)\n        return dv.over_us < dw.over_us;"),
+    ("closest_overshoot_flipped", "return dv.over_us < dw.over_us;", "return dv.over_us > dw.over_us;"),
+    ("closest_shortfall_flipped", "return dv.short_bp < dw.short_bp;", "return dv.short_bp > dw.short_bp;"),
+    ("closest_shortfall_ignored", "if (dv.short_bp != dw.short_bp)", "if (0)"),
+    ("closest_overshoot_wraps", "d.over_us = total > (int64_t)slo_us ? total - (int64_t)slo_us : 0;",
+     "d.over_us = total > (int64_t)slo_us ? (int64_t)(int32_t)(uint32_t)(total - (int64_t)slo_us) : 0;"),
+    ("closest_shortfall_wraps", "(int64_t)min_acc_bp - (int64_t)acc_bp[v] : 0;",
+     "(int64_t)(int32_t)((uint32_t)min_acc_bp - (uint32_t)acc_bp[v]) : 0;"),
+    ("closest_queue_dropped", "int64_t total = (int64_t)lat_us[v * B + b] + (int64_t)queue_us[v];\n    d.over_us",
+     "int64_t total = (int64_t)lat_us[v * B + b];\n    d.over_us"),
+    ("closest_key_tie_dropped", "return cheaper(lat_us, cost, B, b, v, w);\n}\n\n/*\n * Literal form: every query looks at every row of the table.  out_variant",
+     "return v < w;\n}\n\n/*\n * Literal form: every query looks at every row of the table.  out_variant"),
+    ("closest_reports_infeasible_as_selected", "out_variant[q] = (best >= 0 && feasible(", "out_variant[q] = (best >= 0 || feasible("),
+]
+
+
+@pytest.mark.parametrize("name,find,repl", CLOSEST_MUTANTS, ids=[m[0] for m in CLOSEST_MUTANTS])
+def test_closest_mutant_is_caught(tmp_path, source_text, name, find, repl):
+    assert find in source_text, f"mutant {name}: pattern not in the oracle source any more"
+    src = tmp_path / f"{name}.c"
+    src.write_text(source_text.replace(find, repl))
+    lib = oracle.build_oracle(src=str(src), out=str(tmp_path / f"lib{name}.so"), force=True)
+    mutant = oracle.Oracle(lib)
+    caught = []
+    for pin in pins.CLOSEST_PINS:
+        try:
+            pin(mutant)
+        except AssertionError:
+            caught.append(pin.__name__)
+    assert caught, f"no pin notices the planted mistake '{name}'"
+
+
 @pytest.fixture(scope="module")
 def source_text():
     with open(SRC) as f:
