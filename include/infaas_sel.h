@@ -131,6 +131,30 @@ int infaas_sel_select(infaas_sel_t *h, int64_t N,
                       const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
                       int32_t *d_out_variant, void *hip_stream);
 
+/*
+ * infaas_sel_select plus a suggestion for the queries that nothing satisfies: the last step
+ * of Section 4.1's Case I, where a variant that comes closest to the accuracy and/or latency
+ * target is proposed when no registered variant meets the requirements.  The paper names no
+ * distance; this library orders the variants of the query's task (at its batch index) by
+ *     1. the number of the two requirements they miss,
+ *     2. lat_us[v][b] + queue_us[v] - slo_us where positive, else 0,
+ *     3. min_acc_bp - acc_bp[v] where positive, else 0,
+ *     4. (cost[v][b], lat_us[v][b], v),
+ * exact differences, and takes the first.  Hence, if some variant is within the latency bound,
+ * the most accurate of those; else if some variant is accurate enough, the fastest of those;
+ * else the fastest of all (the most accurate among equally fast ones).
+ *   d_out_variant  [N]  as infaas_sel_select
+ *   d_out_closest  [N]  d_out_variant where that is not -1, else the suggestion; -1 only when
+ *                       the task has no variants (task or batch index outside the table included)
+ * Both DEVICE memory.  Needs the staircase index: a handle created with
+ * INFAAS_SEL_ENGINE_SCAN, or whose table is too large for the index, gets INVALID_ARG.
+ * Otherwise as infaas_sel_select.
+ */
+int infaas_sel_select_closest(infaas_sel_t *h, int64_t N,
+                              const int32_t *d_task, const int32_t *d_slo_us,
+                              const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
+                              int32_t *d_out_variant, int32_t *d_out_closest, void *hip_stream);
+
 /* Free the handle and everything it owns.  NULL is a no-op. */
 void infaas_sel_destroy(infaas_sel_t *h);
 

@@ -57,7 +57,7 @@ _lib: Optional[ctypes.CDLL] = None
 
 # every symbol include/infaas_sel.h declares
 EXPORTED = ("infaas_sel_create", "infaas_sel_load_variants", "infaas_sel_update_load",
-            "infaas_sel_select", "infaas_sel_destroy", "infaas_sel_reserve",
+            "infaas_sel_select", "infaas_sel_select_closest", "infaas_sel_destroy", "infaas_sel_reserve",
             "infaas_sel_read_load", "infaas_sel_set_timing", "infaas_sel_get_timings",
             "infaas_sel_get_info", "infaas_sel_strerror", "infaas_sel_last_error")
 
@@ -87,6 +87,7 @@ def load_library() -> ctypes.CDLL:
     lib.infaas_sel_load_variants.argtypes = [vp, ctypes.c_int32, _I32P, _I32P, _I32P, _I32P, _I32P]
     lib.infaas_sel_update_load.argtypes = [vp, ctypes.c_int32, vp, vp, vp]
     lib.infaas_sel_select.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp]
+    lib.infaas_sel_select_closest.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp]
     lib.infaas_sel_destroy.argtypes = [vp]
     lib.infaas_sel_destroy.restype = None
     lib.infaas_sel_reserve.argtypes = [vp, ctypes.c_int64]
@@ -177,6 +178,15 @@ class Selector:
             self._h, n, _dev_ptr(d_task, n, "d_task"), _dev_ptr(d_slo_us, n, "d_slo_us"),
             _dev_ptr(d_min_acc_bp, n, "d_min_acc_bp"), _dev_ptr(d_batch_idx, n, "d_batch_idx"),
             _dev_ptr(d_out_variant, n, "d_out_variant"), _stream_ptr(stream)))
+
+    def select_closest(self, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, d_out_closest,
+                       stream=None, n: Optional[int] = None) -> None:
+        n = int(d_task.numel()) if n is None else int(n)
+        _check(self._lib.infaas_sel_select_closest(
+            self._h, n, _dev_ptr(d_task, n, "d_task"), _dev_ptr(d_slo_us, n, "d_slo_us"),
+            _dev_ptr(d_min_acc_bp, n, "d_min_acc_bp"), _dev_ptr(d_batch_idx, n, "d_batch_idx"),
+            _dev_ptr(d_out_variant, n, "d_out_variant"), _dev_ptr(d_out_closest, n, "d_out_closest"),
+            _stream_ptr(stream)))
 
     def destroy(self) -> None:
         if self._h:

@@ -558,19 +558,27 @@ int infaas_sel_update_load(infaas_sel_t *h, int32_t n, const int32_t *d_variant_
     return INFAAS_SEL_OK;
 }
 
-int infaas_sel_select(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,
-                      const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
-                      int32_t *d_out_variant, void *hip_stream)
+namespace {
+
+// Common part of the two select calls; d_out_closest is null for the plain one.
+int select_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,
+                const int32_t *d_min_acc_bp, const int32_t *d_batch_idx, int32_t *d_out_variant,
+                int32_t *d_out_closest, bool closest, void *hip_stream)
 {
     if (!h || N < 0) return INFAAS_SEL_ERR_INVALID_ARG;
     if (!h->loaded) return INFAAS_SEL_ERR_NOT_LOADED;
+    if (closest && !h->have_index) {
+        snprintf(g_last_error, sizeof(g_last_error),
+                 "infaas_sel_select_closest needs the staircase index, which this handle does not have");
+        return INFAAS_SEL_ERR_INVALID_ARG;
+    }
     if (N == 0) return INFAAS_SEL_OK;
-    if (!d_task || !d_slo_us || !d_min_acc_bp || !d_batch_idx || !d_out_variant)
+    if (!d_task || !d_slo_us || !d_min_acc_bp || !d_batch_idx || !d_out_variant || (closest && !d_out_closest))
         return INFAAS_SEL_ERR_INVALID_ARG;
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     hipStream_t st = (hipStream_t)hip_stream;
-    const bool idx = use_index(h);
+    const bool idx = closest || use_index(h);
     int rc = idx ? INFAAS_SEL_OK : ensure_scratch(h, std::min(N, kMaxPass));
     if (rc != INFAAS_SEL_OK) return rc;
     for (int64_t done = 0; done < N; done += kMaxPass) {
@@ -578,10 +586,28 @@ int infaas_sel_select(infaas_sel_t *h, int64_t N, const int32_t *d_task, const i
         q.n = (int32_t)std::min(kMaxPass, N - done);
         q.task = d_task + done; q.slo = d_slo_us + done; q.min_acc = d_min_acc_bp + done;
         q.bidx = d_batch_idx + done; q.out = d_out_variant + done;
+        q.closest = closest ? d_out_closest + done : nullptr;
         rc = idx ? index_pass(h, q, st) : scan_pass(h, q, st);
         if (rc != INFAAS_SEL_OK) return rc;
     }
     return INFAAS_SEL_OK;
+}
+
+}  // namespace
+
+int infaas_sel_select(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,
+                      const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
+                      int32_t *d_out_variant, void *hip_stream)
+{
+    return select_impl(h, N, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, nullptr, false, hip_stream);
+}
+
+int infaas_sel_select_closest(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,
+                              const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
+                              int32_t *d_out_variant, int32_t *d_out_closest, void *hip_stream)
+{
+    return select_impl(h, N, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, d_out_closest, true,
+                       hip_stream);
 }
 
 void infaas_sel_destroy(infaas_sel_t *h)

@@ -29,6 +29,7 @@ constexpr int kSelThreads = 1024;
 #define INFAAS_PER_THREAD 4
 #endif
 constexpr int kPerThread = INFAAS_PER_THREAD;   // queries per lane and tile (4 or 8)
+constexpr uint32_t kParkFinal = 1u << 31;          // in a parked record's slice word: the selection is known to be -1
 constexpr int kWaveQueue = 64 + 64 * kPerThread;   // parked queries a wavefront can hold: a full pass plus one unit
 
 __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
@@ -78,7 +79,7 @@ __device__ __forceinline__ void body_store(uint8_t *body, int g0, int kb, int la
         k_acc[lane] = 0;
         k_tot[lane] = 0xFFFFFFFFu;
     }
-    if (lane <= kb) { m_a[lane] = r.ma; m_s[lane] = r.ms; }
+    if (lane < (int)re) { m_a[lane] = r.ma; m_s[lane] = r.ms; }   // lanes beyond kb hold the full set
 }
 
 constexpr int kBuildThreads = 512;
@@ -412,7 +413,109 @@ __device__ __forceinline__ uint32_t acc_threshold(int32_t min_acc, int32_t acc_b
     return (uint32_t)(d < 1 ? 1 : (d > 65536 ? 65536 : d));
 }
 
-template <bool kLds>
+// ---- closest variant (the suggestion of Section 4.1 for a query that nothing satisfies): the
+// variant of the slice that is first by (requirements missed, latency overshoot, accuracy
+// shortfall, rank).  It is always a step.  If some step fits the latency bound it is the most
+// accurate of those; else if some step is accurate enough, the fastest of those; else the fastest
+// of all, the most accurate among equally fast ones; ties go to the earlier rank throughout.
+
+// Counts of one body: accuracy keys >= dd and latency keys <= lim (none when the bound is negative).
+template <class Mem>
+__device__ __forceinline__ void body_counts(const Mem &mem, int nit, uint32_t body, uint32_t re, uint32_t dd,
+                                            uint32_t lim, bool lim_ok, uint32_t &pa, uint32_t &ps)
+{
+    const uint32_t la = body + 2u * re, lt = la + 4u * re;
+    uint32_t a = body, t = la;
+#pragma unroll
+    for (int it = 4; it >= 0; --it) {
+        if (it < nit) {
+            const uint32_t ca = a + (2u << it), ct = t + (4u << it);
+            const uint32_t ka = mem.ld16(ca < la ? ca : la, 2u);
+            const uint32_t kt = mem.ld32(ct < lt ? ct : lt, 0u);
+            a = ka >= dd ? ca : a;
+            t = kt <= lim ? ct : t;
+        }
+    }
+    pa = (a - body) >> 1;
+    ps = lim_ok ? (t - la) >> 2 : 0u;
+}
+
+// Smallest p in 1..re-1 whose set (tbl = address of entry 0 of A or of S, minus 4) meets `mask`.
+template <class Mem>
+__device__ __forceinline__ uint32_t first_meeting(const Mem &mem, uint32_t tbl, uint32_t re, uint32_t mask)
+{
+    uint32_t p = 0;   // the largest p found so far whose set misses the mask (set 0 is empty)
+#pragma unroll
+    for (uint32_t step = 16; step; step >>= 1) {
+        const uint32_t c = p + step < re - 1u ? p + step : re - 1u;
+        const uint32_t set = mem.ld32(tbl + 4u * c, 4u);
+        p = (p + step <= re - 1u && (set & mask) == 0u) ? p + step : p;
+    }
+    return p + 1u;
+}
+
+// What one body offers: the step, and the keys the bodies are compared by.
+struct Offer {
+    uint32_t tot, acc, step;   // latency-plus-queue key, accuracy key, step number in the body
+};
+// kind 1: most accurate step among those within the latency bound (ps > 0 of them);
+// kind 2: fastest step among those accurate enough (pa > 0 of them);
+// kind 3: fastest step of all, the most accurate of equally fast ones.  The body has >= 1 step.
+template <class Mem>
+__device__ __forceinline__ Offer body_offer(const Mem &mem, int nit, uint32_t body, uint32_t re, int kind,
+                                            uint32_t pa, uint32_t ps)
+{
+    const uint32_t acc_k = body, tot_k = body + 2u * re, a_tbl = body + 6u * re, s_tbl = body + 10u * re;
+    Offer o;
+    if (kind == 2) {
+        const uint32_t mask = mem.ld32(a_tbl + 4u * pa, 4u);
+        const uint32_t p = first_meeting(mem, s_tbl, re, mask);
+        o.tot = mem.ld32(tot_k + 4u * p, 0u);
+        o.acc = 0u;
+        o.step = (uint32_t)__builtin_ctz(mem.ld32(s_tbl + 4u * p, 4u) & mask);
+        return o;
+    }
+    uint32_t fast = ps;   // kind 3: the steps that share the smallest latency key
+    o.tot = mem.ld32(tot_k + 4u, 0u);
+    if (kind == 3) {
+        uint32_t unused;
+        body_counts(mem, nit, body, re, 0x20000u, o.tot, true, unused, fast);
+    }
+    const uint32_t mask = mem.ld32(s_tbl + 4u * fast, 4u);
+    const uint32_t p = first_meeting(mem, a_tbl, re, mask);
+    o.acc = mem.ld16(acc_k + 2u * p, 2u);
+    o.step = (uint32_t)__builtin_ctz(mem.ld32(a_tbl + 4u * p, 4u) & mask);
+    return o;
+}
+
+// Closest step of a slice with one or two bodies (re1 = 0: one); returns the step number in the
+// slice, or -1 when the slice has no steps.  body1 follows body0 in memory.
+template <class Mem>
+__device__ __forceinline__ int32_t closest_step(const Mem &mem, int nit, uint32_t body0, uint32_t re0, uint32_t re1,
+                                                uint32_t dd, int32_t slo)
+{
+    if (mem.ld32(body0 + 2u * re0 + 4u, 0u) == 0xFFFFFFFFu) return -1;   // first latency key is the sentinel: no steps
+    const uint32_t body1 = body0 + body_bytes(re0);
+    const bool lim_ok = slo >= 0;
+    uint32_t pa0, ps0, pa1 = 0, ps1 = 0;
+    body_counts(mem, nit, body0, re0, dd, (uint32_t)slo, lim_ok, pa0, ps0);
+    if (re1) body_counts(mem, nit, body1, re1, dd, (uint32_t)slo, lim_ok, pa1, ps1);
+    const int kind = (ps0 | ps1) ? 1 : ((pa0 | pa1) ? 2 : 3);
+    const bool use0 = kind == 1 ? ps0 > 0 : (kind == 2 ? pa0 > 0 : true);
+    const bool use1 = re1 && (kind == 1 ? ps1 > 0 : (kind == 2 ? pa1 > 0 : true));
+    Offer o0{0, 0, 0}, o1{0, 0, 0};
+    if (use0) o0 = body_offer(mem, nit, body0, re0, kind, pa0, ps0);
+    if (use1) o1 = body_offer(mem, nit, body1, re1, kind, pa1, ps1);
+    bool second = use1 && !use0;
+    if (use0 && use1) {   // ties go to the first body, whose steps rank earlier
+        if (kind == 1) second = o1.acc > o0.acc;
+        else if (kind == 2) second = o1.tot < o0.tot;
+        else second = o1.tot < o0.tot || (o1.tot == o0.tot && o1.acc > o0.acc);
+    }
+    return second ? (int32_t)(kBodySteps + o1.step) : (int32_t)o0.step;
+}
+
+template <bool kLds, bool kClosest>
 __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, IndexView ix, QueryView q,
                                                               int32_t *__restrict__ park_mem, uint32_t lds_cap)
 {
@@ -424,7 +527,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     const uint32_t lds_hdr0 = lds_base + kLdsCtrlBytes;
     const uint32_t rebase = lds_hdr0 + hdr_bytes;      // LDS address of pool offset 0
     const bool aligned = ((((uintptr_t)q.task) | ((uintptr_t)q.slo) | ((uintptr_t)q.min_acc) |
-                           ((uintptr_t)q.bidx) | ((uintptr_t)q.out)) & 15u) == 0;
+                           ((uintptr_t)q.bidx) | ((uintptr_t)q.out) | ((uintptr_t)q.closest)) & 15u) == 0;
     // Work units of one wavefront: 64 lanes x kPerThread consecutive queries.  The units are split
     // evenly and contiguously over the workgroups; inside a workgroup the wavefronts draw them from
     // a counter in LDS, because the wavefronts of a SIMD do not advance at the same speed.
@@ -561,11 +664,15 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             for (int h = 0; h < kPerThread / 4; ++h) {
                 const v4i r = {p_val(4 * h), p_val(4 * h + 1), p_val(4 * h + 2), p_val(4 * h + 3)};
                 __builtin_nontemporal_store(r, (v4i *)((char *)q.out + (uint32_t)p_i0 * 4u) + 64 * h);
+                if (kClosest) __builtin_nontemporal_store(r, (v4i *)((char *)q.closest + (uint32_t)p_i0 * 4u) + 64 * h);
             }
         } else {
 #pragma unroll
             for (int k = 0; k < kPerThread; ++k)
-                if (p_i0 + qoff(k) < q.n) q.out[p_i0 + qoff(k)] = p_val(k);
+                if (p_i0 + qoff(k) < q.n) {
+                    q.out[p_i0 + qoff(k)] = p_val(k);
+                    if (kClosest) q.closest[p_i0 + qoff(k)] = p_val(k);
+                }
         }
     };
     // One pipeline stage: search the unit in `cur`, then request the unit after the next into it.
@@ -577,11 +684,11 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             lim[kPerThread], m[kPerThread], sl_of[kPerThread], rbase[kPerThread];
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) {
-            const uint32_t ok = ((uint32_t)cur.tk[k] < (uint32_t)tv.T) & ((uint32_t)cur.bi[k] < (uint32_t)tv.B) &
-                                (uint32_t)(cur.sl[k] >= 0);
-            const uint32_t s = ok ? __umul24((uint32_t)cur.tk[k], (uint32_t)tv.B) + (uint32_t)cur.bi[k]
-                                  : (uint32_t)tv.S;
-            sl_of[k] = s;
+            const uint32_t inside = ((uint32_t)cur.tk[k] < (uint32_t)tv.T) & ((uint32_t)cur.bi[k] < (uint32_t)tv.B);
+            const uint32_t ok = inside & (uint32_t)(cur.sl[k] >= 0);   // a negative bound admits nothing
+            const uint32_t own = __umul24((uint32_t)cur.tk[k], (uint32_t)tv.B) + (uint32_t)cur.bi[k];
+            const uint32_t s = ok ? own : (uint32_t)tv.S;
+            sl_of[k] = kClosest ? (inside ? own : (uint32_t)tv.S) : s;   // the slice a parked record names
             if (kLds) {
                 const v2u h = lmem.ld64(lds_hdr0 + s * kLdsHdrBytes);
                 body[k] = h.x & ((1u << kLdsAddrBits) - 1u); y[k] = h.y; rec[k] = h.y & 0xFFFFu;
@@ -613,8 +720,10 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             p_base[k] = (rbase[k] >> ((step * ix.row_hi_bits) & 31u)) & row_hi_mask;
             p_grow[k] = *(const int32_t *)((const char *)ix.step_row + ((hit && !inl) ? (rec[k] + step) * 4u : 0u));
             p_inl[k] = inl;
-            // parked: a miss that the second body / the scan may still turn into a hit
-            df[k] = !hit && (int32_t)y[k] < 0;
+            // parked: a miss that the second body / the scan may still turn into a hit; in the
+            // closest-variant mode also every final miss of a query inside the table
+            df[k] = !hit && ((int32_t)y[k] < 0 || (kClosest && sl_of[k] != (uint32_t)tv.S));
+            if (kClosest && (int32_t)y[k] >= 0) sl_of[k] |= kParkFinal;   // nothing feasible: only the suggestion is open
         }
         p_i0 = i0;
 #pragma unroll
@@ -639,7 +748,8 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         const int32_t slo = __hip_atomic_load(e + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         const int32_t min_acc = __hip_atomic_load(e + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         const int32_t s_ld = __hip_atomic_load(e + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        const uint32_t s = have ? (uint32_t)s_ld : (uint32_t)tv.S;   // idle lanes: the empty slice
+        const bool final_miss = kClosest && have && ((uint32_t)s_ld & kParkFinal);
+        const uint32_t s = have ? ((uint32_t)s_ld & ~kParkFinal) : (uint32_t)tv.S;   // idle lanes: the empty slice
         uint32_t y = 0, rec = 0, lbody = rebase, gbody = 0;
         bool resident = false;
         if (kLds) {
@@ -656,9 +766,9 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         const uint32_t size0 = body_bytes(keys0);
         const uint32_t dd[1] = {acc_threshold(min_acc, acc_base_m1)}, lim[1] = {(uint32_t)slo};
         int32_t ans = -1;
-        bool done = false;
+        bool done = final_miss;
         // first body from global memory: only if the main loop could not use an LDS copy
-        const bool need_g0 = have && indexed && kLds && !resident;
+        const bool need_g0 = have && indexed && kLds && !resident && !done;
         if (__ballot(need_g0)) {
             const uint32_t bd[1] = {need_g0 ? gbody : 0u}, ks[1] = {need_g0 ? keys0 : 2u};
             uint32_t m[1];
@@ -702,7 +812,57 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                 if (lane == l) ans = found >= 0 ? tv.orig_r[col + found] : -1;
             }
         }
-        if (have) q.out[qi] = ans;
+        if (have && !final_miss) q.out[qi] = ans;
+        if (kClosest) {
+            // the suggestion for the queries that ended with nothing feasible
+            const bool open = have && ans < 0;
+            const bool by_index = open && indexed && !(y & kHdrTrunc);
+            int32_t sug = ans;
+            const bool in_lds = by_index && resident, in_mem = by_index && !resident;
+            if (kLds && __ballot(in_lds)) {
+                const int32_t st = closest_step(lmem, nit, in_lds ? lbody : rebase, in_lds ? keys0 : 2u,
+                                                in_lds ? keys1 : 0u, dd[0], slo);
+                if (in_lds && st >= 0) sug = ix.step_row[rec + (uint32_t)st];
+            }
+            if (__ballot(in_mem)) {
+                const int32_t st = closest_step(gmem, nit, in_mem ? gbody : 0u, in_mem ? keys0 : 2u,
+                                                in_mem ? keys1 : 0u, dd[0], slo);
+                if (in_mem && st >= 0) sug = ix.step_row[rec + (uint32_t)st];
+            }
+            // slices without a complete index: the whole slice, in rank order, by the wavefront
+            uint64_t rest = __ballot(open && !by_index);
+            if (rest) {
+                const int32_t task = (int32_t)(s / (uint32_t)tv.B), bidx = (int32_t)(s - (uint32_t)task * (uint32_t)tv.B);
+                while (rest) {
+                    const int l = __builtin_ctzll(rest);
+                    rest &= rest - 1;
+                    const int32_t t = __builtin_amdgcn_readlane(task, l), b = __builtin_amdgcn_readlane(bidx, l);
+                    const int64_t am = __builtin_amdgcn_readlane(min_acc, l), bound = __builtin_amdgcn_readlane(slo, l);
+                    const int32_t seg = tv.seg_off[t], L = tv.seg_len[t];
+                    const int64_t col = (int64_t)b * tv.Vp + seg;
+                    // per lane the best of its entries by (missed, overshoot, shortfall), earlier rank first
+                    int32_t b_missed = 3, b_pos = 0x7FFFFFFF;
+                    int64_t b_over = 0, b_short = 0;
+                    for (int32_t pos = lane; pos < L; pos += 64) {
+                        const int64_t tt = (int64_t)tv.tot_r[col + pos], a = (int64_t)tv.acc_r[col + pos];
+                        const int64_t over = tt > bound ? tt - bound : 0, shortf = a < am ? am - a : 0;
+                        const int32_t missed = (over > 0) + (shortf > 0);
+                        const bool better = missed < b_missed || (missed == b_missed && (over < b_over ||
+                                            (over == b_over && shortf < b_short)));
+                        if (better) { b_missed = missed; b_over = over; b_short = shortf; b_pos = pos; }
+                    }
+                    for (int off = 32; off; off >>= 1) {   // then the best of the wavefront
+                        const int32_t o_missed = __shfl_xor(b_missed, off), o_pos = __shfl_xor(b_pos, off);
+                        const int64_t o_over = __shfl_xor(b_over, off), o_short = __shfl_xor(b_short, off);
+                        const bool better = o_missed < b_missed || (o_missed == b_missed && (o_over < b_over ||
+                                            (o_over == b_over && (o_short < b_short || (o_short == b_short && o_pos < b_pos)))));
+                        if (better) { b_missed = o_missed; b_over = o_over; b_short = o_short; b_pos = o_pos; }
+                    }
+                    if (lane == l) sug = L > 0 ? tv.orig_r[col + b_pos] : -1;
+                }
+            }
+            if (have) q.closest[qi] = sug;
+        }
     };
 
     {
@@ -758,13 +918,16 @@ hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const Q
     if (lds_bytes > 0) {
         const uint32_t fixed = kLdsCtrlBytes + lds_header_bytes(tv.S);
         lds_bytes = fixed + ((lds_bytes - fixed) & ~15u);
-        hipError_t e = hipFuncSetAttribute((const void *)k_index_select<true>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        auto kernel = q.closest ? k_index_select<true, true> : k_index_select<true, false>;
+        hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)lds_bytes);
         if (e != hipSuccess) return e;
-        return launch_kernel(ev, k_index_select<true>, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), lds_bytes, st, tv, ix, q, park_mem, lds_bytes - fixed);
-    } else {
-        return launch_kernel(ev, k_index_select<false>, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), kLdsCtrlBytes, st, tv, ix, q, park_mem, 0u);
+        return launch_kernel(ev, kernel, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), lds_bytes, st, tv, ix, q,
+                             park_mem, lds_bytes - fixed);
     }
+    auto kernel = q.closest ? k_index_select<false, true> : k_index_select<false, false>;
+    return launch_kernel(ev, kernel, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), kLdsCtrlBytes, st, tv, ix, q,
+                         park_mem, 0u);
 }
 
 }  // namespace infaas

@@ -56,6 +56,7 @@ struct TableView {
 //   2 Re         totk  : u32[Re]  tot, ascending; then 0xFFFFFFFF (sentinels)
 //   6 Re         A     : u32[Re]  A[0] = 0, A[p] for p = 1..K
 //   10 Re        S     : u32[Re]  S[0] = 0, S[p] for p = 1..K
+// (when Re = K + 2 the last entry of A and of S repeats the full set, so that every entry is valid)
 // A slice's block in the pool is  [rows][first body][second body]:  rows holds the low 16 bits
 // of the caller rows of the first r = min(K, hot_rows) steps of the first body, in REVERSE order
 // and padded in front to 4 bytes, so that those of step i are at (first body start) - 2 - 2 i.
@@ -124,6 +125,7 @@ struct QueryView {
     int32_t n;
     const int32_t *task, *slo, *min_acc, *bidx;
     int32_t *out;
+    int32_t *closest;    // second result array of the closest-variant mode, else null
 };
 
 // A pair of events that a launcher attaches to its kernel's dispatch (the events then carry the

@@ -38,3 +38,13 @@ def table_args(tb, queue=None):
 
 def query_args(q):
     return (q.task, q.slo_us, q.min_acc_bp, q.batch_idx)
+
+
+def gpu_select_closest(sel, task, slo, min_acc, bidx):
+    """Run infaas_sel_select_closest on host arrays; returns (selection, suggestion) on the host."""
+    import torch
+    dq = DeviceQueries(task, slo, min_acc, bidx)
+    closest = torch.full_like(dq.out, -54321)
+    sel.select_closest(dq.task, dq.slo, dq.min_acc, dq.bidx, dq.out, closest, n=dq.n)
+    torch.cuda.synchronize()
+    return dq.out[:dq.n].cpu().numpy(), closest[:dq.n].cpu().numpy()
