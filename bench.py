@@ -5,6 +5,9 @@ configuration (default: configuration 2 -- 50 tasks x 2,000 variants, 16M querie
 task popularity), inputs already resident in HBM.  For the streaming configuration (4) a step
 is one 4M-query chunk preceded by its load update (10% of the variants).
 
+With --closest a step is one call of infaas_sel_select_closest (the selection plus a suggestion
+for the queries that nothing satisfies; 24 B per decision).
+
 Prints ONE JSON line: decisions/s, the roofline of the dominant kernel (algorithmic bytes:
 20 B per decision + the variant table once, against 8 TB/s of HBM) timed with HIP events on
 the launch stream, and the CPU oracle timed on a bounded sample of the same queries.
@@ -62,6 +65,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, choices=[0, 1, 2, 3, 4])
     ap.add_argument("--engine", default="auto", choices=["auto", "scan"])
+    ap.add_argument("--closest", action="store_true",
+                    help="time infaas_sel_select_closest (selection plus a suggestion where nothing is "
+                         "feasible; 24 B per decision) instead of infaas_sel_select")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -94,6 +100,9 @@ def main() -> int:
     chunks = spec["chunks"]
     per_step = spec["num_queries"] // chunks
     engine = pkg.ENGINE_AUTO if args.engine == "auto" else pkg.ENGINE_SCAN
+    if args.closest and args.engine != "auto":
+        print("bench.py: --closest needs the index engine (--engine auto)", file=sys.stderr)
+        return 2
 
     sel = pkg.Selector(tb.num_tasks, tb.batch_sizes, device=0, engine=engine)
     sel.load_variants(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us)
@@ -106,6 +115,8 @@ def main() -> int:
     dev_q = [[torch.from_numpy(x).cuda() for x in (q.task, q.slo_us, q.min_acc_bp, q.batch_idx)]
              for q in host_q]
     out = torch.empty(per_step, dtype=torch.int32, device="cuda")
+    closest = torch.empty(per_step, dtype=torch.int32, device="cuda") if args.closest else None
+    per_decision = BYTES_PER_DECISION + (4 if args.closest else 0)   # the second result array
     updates = []
     if chunks > 1:
         for c in range(1, n_sets + 1):
@@ -116,7 +127,10 @@ def main() -> int:
         if updates:
             u = updates[i % len(updates)]
             sel.update_load(u[0], u[1])
-        sel.select(*dev_q[i % n_sets], out)
+        if args.closest:
+            sel.select_closest(*dev_q[i % n_sets], out, closest)
+        else:
+            sel.select(*dev_q[i % n_sets], out)
 
     for i in range(args.warmup):
         step(i)
@@ -144,14 +158,14 @@ def main() -> int:
     elif dom == "update_load":
         algo_bytes = UPDATE_BYTES * updates[0][2].variant_idx.size
     else:                        # a select kernel: every query in, every result out, the table once
-        algo_bytes = (BYTES_PER_DECISION * per_step + table_bytes(tb)) / launches_per_step
+        algo_bytes = (per_decision * per_step + table_bytes(tb)) / launches_per_step
     achieved = algo_bytes / (dom_avg_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
-                "traffic": measured_traffic(dom, cfg, args.engine),
+                "traffic": measured_traffic(dom, cfg, args.engine + ("/closest" if args.closest else "")),
                 "avg_kernel_ms": round(dom_avg_ms, 5),
                 "algorithmic_bytes_per_launch": int(algo_bytes)}
-    whole_bytes = BYTES_PER_DECISION * per_step + table_bytes(tb) + \
+    whole_bytes = per_decision * per_step + table_bytes(tb) + \
         (UPDATE_BYTES * updates[0][2].variant_idx.size if updates else 0)
     whole_frac = whole_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
 
@@ -171,14 +185,17 @@ def main() -> int:
         fields = (q.task, q.slo_us, q.min_acc_bp, q.batch_idx)
         n0 = min(per_step, 100_000)
         s0 = time.perf_counter()
-        ref.select(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, queue, *(f[:n0] for f in fields))
+        ref_fn = ref.select_closest if args.closest else ref.select
+        ref_fn(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, queue, *(f[:n0] for f in fields))
         rate0 = n0 / (time.perf_counter() - s0)
         n = int(min(per_step, max(n0, rate0 * args.cpu_seconds)))
         s0 = time.perf_counter()
-        want = ref.select(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, queue, *(f[:n] for f in fields))
+        want = ref_fn(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, queue, *(f[:n] for f in fields))
         dt = time.perf_counter() - s0
-        got = out[:n].cpu().numpy()
-        mismatches = int((got != want).sum())
+        if args.closest:
+            mismatches = int((out[:n].cpu().numpy() != want[0]).sum() + (closest[:n].cpu().numpy() != want[1]).sum())
+        else:
+            mismatches = int((out[:n].cpu().numpy() != want).sum())
         cpu = {"value": round(n / dt, 1), "unit": "decisions/s", "cores": ref.num_threads(),
                "kind": "oracle", "sample": f"first {n} queries of the last timed batch, {dt:.1f} s"}
 
@@ -189,7 +206,8 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
         "config": {"workload": f"config {cfg} ({spec['name']}): {tb.num_tasks} tasks, {tb.V} variants, "
                                f"{tb.B} batch sizes, {per_step} queries per step"
-                               + (f", load report of {updates[0][2].variant_idx.size} rows before every step" if updates else ""),
+                               + (f", load report of {updates[0][2].variant_idx.size} rows before every step" if updates else "")
+                               + (", closest-variant mode (two result arrays)" if args.closest else ""),
                    "engine": args.engine},
         "roofline": roofline,
         "whole_step_frac_of_hbm_roofline": round(whole_frac, 5),
