@@ -432,3 +432,37 @@ def test_results_do_not_depend_on_run(oracle_lib):
         b = gpu_select(sel, *query_args(q))
         assert np.array_equal(a, b)
         sel.destroy()
+
+
+def test_more_queries_than_one_pass(oracle_lib):
+    """2^28 + 5000 queries in one call: the library splits the call into passes of 2^28.  Queries
+    are drawn on the device; those around the seam, at both ends and a random sample are checked
+    against the oracle, for the plain call and for the closest-variant call."""
+    import torch
+    tb = workloads.make_table(0)
+    sel = make_selector(tb, engine=0)
+    n = (1 << 28) + 5000
+    g = torch.Generator(device="cuda"); g.manual_seed(28)
+    task = torch.randint(0, tb.num_tasks, (n,), generator=g, device="cuda", dtype=torch.int32)
+    slo = torch.randint(1000, 400_000, (n,), generator=g, device="cuda", dtype=torch.int32)
+    acc = torch.randint(5000, 9501, (n,), generator=g, device="cuda", dtype=torch.int32)
+    bidx = torch.randint(0, tb.B, (n,), generator=g, device="cuda", dtype=torch.int32)
+    out = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    seam = 1 << 28
+    pick = np.unique(np.concatenate([np.arange(2000), seam - 2000 + np.arange(4000), n - 2000 + np.arange(2000),
+                                     np.random.default_rng(1).integers(0, n, 100_000)]))
+    pick_d = torch.from_numpy(pick).cuda()
+    qs = tuple(x[pick_d].cpu().numpy() for x in (task, slo, acc, bidx))
+    want_sel, want_clo = oracle_lib.select_closest(*table_args(tb), *qs)
+    sel.select(task, slo, acc, bidx, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out[pick_d].cpu().numpy(), want_sel)
+    assert int((out == -7).sum()) == 0, "some results were never written"
+    clo = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    out.fill_(-7)
+    sel.select_closest(task, slo, acc, bidx, out, clo)
+    torch.cuda.synchronize()
+    assert np.array_equal(out[pick_d].cpu().numpy(), want_sel)
+    assert np.array_equal(clo[pick_d].cpu().numpy(), want_clo)
+    assert int((clo == -7).sum()) == 0 and int((out == -7).sum()) == 0
+    sel.destroy()
