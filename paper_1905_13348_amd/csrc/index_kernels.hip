@@ -14,7 +14,9 @@
 //                    are parked in a queue of the wavefront and finished by it, 64 at a time or
 //                    when it runs out of work: second body, index copy in global memory, and last
 //                    a wavefront-wide scan of the rank-ordered slice that stops at the first
-//                    feasible variant.
+//                    feasible variant.  In its closest-variant mode the kernel also parks the
+//                    queries that end without a feasible variant and finds, in the same bodies,
+//                    the variant that comes closest to their requirements.
 #include "internal.h"
 
 namespace infaas {
@@ -25,10 +27,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef uint32_t v2u __attribute__((ext_vector_type(2)));
 
 constexpr int kSelThreads = 1024;
-#ifndef INFAAS_PER_THREAD
-#define INFAAS_PER_THREAD 4
-#endif
-constexpr int kPerThread = INFAAS_PER_THREAD;   // queries per lane and tile (4 or 8)
+constexpr int kPerThread = 4;   // queries per lane and unit, searched interleaved (8 does not fit in 128 VGPRs)
 constexpr uint32_t kParkFinal = 1u << 31;          // in a parked record's slice word: the selection is known to be -1
 constexpr int kWaveQueue = 64 + 64 * kPerThread;   // parked queries a wavefront can hold: a full pass plus one unit
 

@@ -78,7 +78,6 @@ constexpr uint32_t kHdrDeep = 1u << 31;      // a miss in the first body is not 
                                              // no usable body); the sign bit, so that one compare tests it
 constexpr uint32_t kLdsHdrBytes = 8;         // per slice in the lookup kernel's LDS: {body address, y | first step}
 constexpr uint32_t kLdsCtrlBytes = 16;       // control words at the start of the lookup kernel's LDS
-constexpr int kIndexTile = 8192;             // most queries per workgroup step of the index lookup kernel
 
 // LDS bytes of the S + 1 slice headers, padded so that the bodies behind them are 16-byte aligned
 __host__ __device__ inline uint32_t lds_header_bytes(int32_t S) { return (((uint32_t)S + 1u) * kLdsHdrBytes + 15u) & ~15u; }
