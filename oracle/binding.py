@@ -56,6 +56,12 @@ class Oracle:
             fn = getattr(lib, name)
             fn.argtypes = sel_args + [_I32P]
             fn.restype = ctypes.c_int
+        for name in ("oracle_select_tiered", "oracle_select_tiered_literal"):
+            fn = getattr(lib, name)
+            fn.argtypes = [ctypes.c_int64, ctypes.c_int32] + [_I32P] * 7 + [ctypes.c_int64] + [_I32P] * 6
+            fn.restype = ctypes.c_int
+        lib.oracle_update_state.argtypes = [ctypes.c_int64, _I32P, ctypes.c_int64, _I32P, _I32P]
+        lib.oracle_update_state.restype = None
         lib.oracle_count_feasible.argtypes = [ctypes.c_int64, ctypes.c_int32, _I32P, _I32P, _I32P,
                                               _I32P, ctypes.c_int64, _I32P, _I32P, _I32P, _I32P,
                                               _I32P]
@@ -123,6 +129,34 @@ class Oracle:
         """The same by the literal O(N*V) scan."""
         return self._closest(self._lib.oracle_select_closest_literal, task_id, acc_bp, lat_us, cost,
                              queue_us, q_task, q_slo, q_min_acc, q_bidx)
+
+    def select_tiered(self, task_id, acc_bp, lat_us, cost, queue_us, state, load_us,
+                      q_task, q_slo, q_min_acc, q_bidx, literal=False):
+        """(variant or -1, tier 1 = Active / 2 = Inactive / 0 = none) per query."""
+        task_id, acc_bp, queue_us = _i32(task_id), _i32(acc_bp), _i32(queue_us)
+        lat_us, cost, state, load_us = _i32(lat_us), _i32(cost), _i32(state), _i32(load_us)
+        V, B = lat_us.shape
+        assert cost.shape == lat_us.shape
+        for a in (task_id, acc_bp, queue_us, state, load_us):
+            assert a.shape == (V,)
+        q_task, q_slo, q_min_acc, q_bidx = _i32(q_task), _i32(q_slo), _i32(q_min_acc), _i32(q_bidx)
+        N = q_task.shape[0]
+        out = np.empty(N, dtype=np.int32)
+        tier = np.empty(N, dtype=np.int32)
+        fn = self._lib.oracle_select_tiered_literal if literal else self._lib.oracle_select_tiered
+        rc = fn(V, B, _ptr(task_id), _ptr(acc_bp), _ptr(lat_us), _ptr(cost),
+                                            _ptr(queue_us), _ptr(state), _ptr(load_us), N, _ptr(q_task),
+                                            _ptr(q_slo), _ptr(q_min_acc), _ptr(q_bidx), _ptr(out), _ptr(tier))
+        if rc != 0:
+            raise ValueError("oracle rejected its arguments")
+        return out, tier
+
+    def update_state(self, state: np.ndarray, variant_idx, new_state) -> None:
+        """In place: state[variant_idx[i]] = new_state[i], array order."""
+        assert state.dtype == np.int32 and state.flags["C_CONTIGUOUS"]
+        variant_idx, new_state = _i32(variant_idx), _i32(new_state)
+        self._lib.oracle_update_state(state.shape[0], _ptr(state), variant_idx.shape[0],
+                                      _ptr(variant_idx), _ptr(new_state))
 
     def count_feasible(self, task_id, acc_bp, lat_us, queue_us, q_task, q_slo, q_min_acc, q_bidx):
         task_id, acc_bp, queue_us, lat_us = _i32(task_id), _i32(acc_bp), _i32(queue_us), _i32(lat_us)

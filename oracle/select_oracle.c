@@ -44,7 +44,11 @@
  * this file that each pin set must reject.  The closest-variant search further
  * down follows a reading of this file's own (the paper names no distance); it is
  * pinned by two independently written numpy enumerators (one by cases, one by a
- * sorted key), structural properties, extreme values and its own mutants.
+ * sorted key), structural properties, extreme values and its own mutants.  The
+ * state-aware selection at the end follows Sections 4 and 4.1 with the readings
+ * listed there; it is pinned by a numpy enumerator, by two special cases that
+ * reduce to the plain selection (all variants Active; all Inactive), by hand-built
+ * policy cases and by twelve mutants.
  * The only statement that stays
  * "parity unpinned" is the count of valid options printed in Table 7, because
  * the profiles behind it are not published.
@@ -349,6 +353,161 @@ int oracle_select_closest(int64_t V, int32_t B,
     }
     free(first); free(rows); free(fill);
     return 0;
+}
+
+/*
+ * State-aware selection (Section 4, "State machine for the lifecycle of model-variants", and
+ * the full text of Case I in Section 4.1, plus "Mitigating performance degradation"):
+ * every variant is Inactive (registered, not loaded), Active (loaded, below its peak
+ * throughput), Overloaded (at its peak) or Interfered (slower than profiled).  The policy
+ * first looks among the ACTIVE variants that match the query's requirements, because they
+ * incur no loading latency; only if there is none it turns to the INACTIVE ones and takes
+ * the one with the lowest combined loading and inference latency that matches the
+ * requirements; Overloaded and Interfered variants are avoided.
+ *
+ * Readings taken where the text is silent:
+ *   - tier 1 (Active): requirements as in the plain selection (accuracy, and latency plus
+ *     queueing delay within the objective); among several matches the cheapest, by the plain
+ *     key (cost, lat, row);
+ *   - tier 2 (Inactive): accuracy as before; the latency requirement applies to the combined
+ *     latency load_us[v] + lat_us[v][b] (an unloaded variant has no queue); the order is
+ *     (load_us + lat_us[b], lat_us[b], row);
+ *   - states are coded 0 Inactive, 1 Active, 2 Overloaded, 3 Interfered; any other code is
+ *     never selected.
+ * out_tier is 1 or 2 for the tier the answer comes from and 0 with out_variant = -1.
+ */
+enum { STATE_INACTIVE = 0, STATE_ACTIVE = 1, STATE_OVERLOADED = 2, STATE_INTERFERED = 3 };
+
+/* 1 when the unloaded variant v comes before w: lower load + inference latency, then lower
+ * inference latency, then lower row. */
+static int loads_sooner(const int32_t *lat_us, const int32_t *load_us, int32_t B, int32_t b,
+                        int64_t v, int64_t w)
+{
+    int64_t tv = (int64_t)load_us[v] + (int64_t)lat_us[v * B + b];
+    int64_t tw = (int64_t)load_us[w] + (int64_t)lat_us[w * B + b];
+    if (tv != tw)
+        return tv < tw;
+    int32_t run_v = lat_us[v * B + b], run_w = lat_us[w * B + b];
+    if (run_v != run_w)
+        return run_v < run_w;
+    return v < w;
+}
+
+/* One query of the state-aware selection against the rows rows[0..n) (all of the query's task). */
+static void tiered_one(const int64_t *rows, int64_t n, int32_t B,
+                       const int32_t *acc_bp, const int32_t *lat_us, const int32_t *cost,
+                       const int32_t *queue_us, const int32_t *state, const int32_t *load_us,
+                       int32_t slo_us, int32_t min_acc_bp, int32_t b,
+                       int32_t *out_variant, int32_t *out_tier)
+{
+    int64_t active = -1, inactive = -1;
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t v = rows[i];
+        if (state[v] == STATE_ACTIVE) {
+            if (!feasible(acc_bp, lat_us, queue_us, B, v, slo_us, min_acc_bp, b))
+                continue;
+            if (active < 0 || cheaper(lat_us, cost, B, b, v, active))
+                active = v;
+        } else if (state[v] == STATE_INACTIVE) {
+            if (acc_bp[v] < min_acc_bp)
+                continue;
+            if ((int64_t)load_us[v] + (int64_t)lat_us[v * B + b] > (int64_t)slo_us)
+                continue;
+            if (inactive < 0 || loads_sooner(lat_us, load_us, B, b, v, inactive))
+                inactive = v;
+        }
+    }
+    *out_variant = (int32_t)(active >= 0 ? active : inactive);
+    *out_tier = active >= 0 ? 1 : (inactive >= 0 ? 2 : 0);
+}
+
+/* Literal form: every query looks at every row of the table. */
+int oracle_select_tiered_literal(int64_t V, int32_t B,
+                                 const int32_t *task_id, const int32_t *acc_bp,
+                                 const int32_t *lat_us, const int32_t *cost, const int32_t *queue_us,
+                                 const int32_t *state, const int32_t *load_us,
+                                 int64_t N,
+                                 const int32_t *q_task, const int32_t *q_slo_us,
+                                 const int32_t *q_min_acc_bp, const int32_t *q_batch_idx,
+                                 int32_t *out_variant, int32_t *out_tier)
+{
+    if (V < 0 || B <= 0 || N < 0)
+        return -1;
+    int64_t *rows = (int64_t *)malloc(sizeof(int64_t) * (size_t)(V > 0 ? V : 1));
+    if (!rows)
+        return -1;
+    for (int64_t q = 0; q < N; ++q) {
+        int64_t n = 0;
+        int32_t b = q_batch_idx[q];
+        if (b >= 0 && b < B)
+            for (int64_t v = 0; v < V; ++v)
+                if (task_id[v] == q_task[q])
+                    rows[n++] = v;
+        tiered_one(rows, n, B, acc_bp, lat_us, cost, queue_us, state, load_us, q_slo_us[q],
+                   q_min_acc_bp[q], b, &out_variant[q], &out_tier[q]);
+    }
+    free(rows);
+    return 0;
+}
+
+/* Grouped form (rows listed per task once, queries on several host threads). */
+int oracle_select_tiered(int64_t V, int32_t B,
+                         const int32_t *task_id, const int32_t *acc_bp,
+                         const int32_t *lat_us, const int32_t *cost, const int32_t *queue_us,
+                         const int32_t *state, const int32_t *load_us,
+                         int64_t N,
+                         const int32_t *q_task, const int32_t *q_slo_us,
+                         const int32_t *q_min_acc_bp, const int32_t *q_batch_idx,
+                         int32_t *out_variant, int32_t *out_tier)
+{
+    if (V < 0 || B <= 0 || N < 0)
+        return -1;
+    int64_t T = 0;
+    for (int64_t v = 0; v < V; ++v) {
+        if (task_id[v] < 0)
+            return -1;
+        if ((int64_t)task_id[v] + 1 > T)
+            T = (int64_t)task_id[v] + 1;
+    }
+    int64_t *first = (int64_t *)calloc((size_t)T + 1, sizeof(int64_t));
+    int64_t *rows = (int64_t *)malloc(sizeof(int64_t) * (size_t)(V > 0 ? V : 1));
+    int64_t *fill = (int64_t *)calloc((size_t)T + 1, sizeof(int64_t));
+    if (!first || !rows || !fill) {
+        free(first); free(rows); free(fill);
+        return -1;
+    }
+    for (int64_t v = 0; v < V; ++v)
+        first[task_id[v] + 1] += 1;
+    for (int64_t t = 0; t < T; ++t)
+        first[t + 1] += first[t];
+    for (int64_t v = 0; v < V; ++v) {
+        int64_t t = task_id[v];
+        rows[first[t] + fill[t]] = v;
+        fill[t] += 1;
+    }
+#pragma omp parallel for schedule(dynamic, 4096)
+    for (int64_t q = 0; q < N; ++q) {
+        int32_t b = q_batch_idx[q];
+        int64_t t = q_task[q];
+        int64_t n = (b >= 0 && b < B && t >= 0 && t < T) ? first[t + 1] - first[t] : 0;
+        tiered_one(n ? rows + first[t] : rows, n, B, acc_bp, lat_us, cost, queue_us, state, load_us,
+                   q_slo_us[q], q_min_acc_bp[q], b, &out_variant[q], &out_tier[q]);
+    }
+    free(first); free(rows); free(fill);
+    return 0;
+}
+
+/* State report: state[row[i]] = value[i], in array order; entries with a row outside 0..V-1 or
+ * a code outside 0..3 are skipped. */
+void oracle_update_state(int64_t V, int32_t *state, int64_t n,
+                         const int32_t *variant_idx, const int32_t *new_state)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t v = variant_idx[i];
+        if (v < 0 || v >= V || new_state[i] < 0 || new_state[i] > 3)
+            continue;
+        state[v] = new_state[i];
+    }
 }
 
 /* Host threads the grouped form uses. */

@@ -107,3 +107,34 @@ def closest_key_np(task_id, acc_bp, lat_us, cost, queue_us, q_task, q_slo, q_min
         missed = (over > 0).astype(np.int64) + (short > 0)
         out[q] = rows[np.lexsort((rows, lat_us[rows, b], cost[rows, b], short, over, missed))[0]]
     return out
+
+
+def tiered_np(task_id, acc_bp, lat_us, cost, queue_us, state, load_us, q_task, q_slo, q_min_acc, q_bidx):
+    """State-aware selection: cheapest matching Active variant, else the matching Inactive variant
+    with the lowest load + inference latency; returns (variant, tier)."""
+    task_id = np.asarray(task_id, dtype=np.int64)
+    acc_bp = np.asarray(acc_bp, dtype=np.int64)
+    lat_us = np.asarray(lat_us, dtype=np.int64)
+    cost = np.asarray(cost, dtype=np.int64)
+    queue_us = np.asarray(queue_us, dtype=np.int64)
+    state = np.asarray(state, dtype=np.int64)
+    load_us = np.asarray(load_us, dtype=np.int64)
+    V, B = lat_us.shape
+    rows = np.arange(V, dtype=np.int64)
+    out = np.full(len(q_task), -1, dtype=np.int32)
+    tier = np.zeros(len(q_task), dtype=np.int32)
+    for q in range(len(q_task)):
+        b = int(q_bidx[q])
+        if not 0 <= b < B:
+            continue
+        mine = (task_id == int(q_task[q])) & (acc_bp >= int(q_min_acc[q]))
+        act = rows[mine & (state == 1) & (lat_us[:, b] + queue_us <= int(q_slo[q]))]
+        if act.size:
+            out[q] = act[np.lexsort((act, lat_us[act, b], cost[act, b]))[0]]
+            tier[q] = 1
+            continue
+        ina = rows[mine & (state == 0) & (load_us + lat_us[:, b] <= int(q_slo[q]))]
+        if ina.size:
+            out[q] = ina[np.lexsort((ina, lat_us[ina, b], load_us[ina] + lat_us[ina, b]))[0]]
+            tier[q] = 2
+    return out, tier

@@ -9,7 +9,7 @@ import os
 import numpy as np
 
 import workloads
-from bruteforce_np import closest_key_np, closest_np, count_np, select_np
+from bruteforce_np import closest_key_np, closest_np, count_np, select_np, tiered_np
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 I32MAX = 2**31 - 1
@@ -400,4 +400,92 @@ CLOSEST_PINS = [
     pin_closest_numpy,
     pin_closest_structure,
     pin_closest_no_wraparound,
+]
+
+
+# ---------------------------------------------------------------- state-aware selection (Sections 4 and 4.1)
+
+def _both_tiered(o, *args):
+    a = o.select_tiered(*args)
+    b = o.select_tiered(*args, literal=True)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]), "grouped and literal oracle disagree"
+    return a
+
+
+def pin_tiered_numpy(o):
+    """Tiny tables with ties against the numpy enumerator."""
+    rng = np.random.default_rng(13)
+    for trial in range(40):
+        V = int(rng.integers(1, 65)); T = int(rng.integers(1, 6)); B = int(rng.integers(1, 5))
+        span = int(rng.choice([2, 3, 5, 9, 50]))
+        tab, qry = _tiny_random(rng, V, T, B, 300, span)
+        state = rng.integers(-1, 6, V).astype(np.int32)          # codes outside 0..3 are never selected
+        load = rng.integers(0, span, V).astype(np.int32)
+        got = _both_tiered(o, *tab, state, load, *qry)
+        want = tiered_np(*tab, state, load, *qry)
+        assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1]), f"trial {trial}"
+
+
+def pin_tiered_reduces_to_plain(o):
+    """Two special cases that reduce to the plain selection, which is pinned on its own:
+    every variant Active -> exactly the plain selection; every variant Inactive -> the plain
+    selection on the table with cost := load + lat, queue := load (same filter, same order)."""
+    tb = workloads.make_table(0)
+    q = workloads.make_queries(0, n=4000)
+    st = workloads.make_states(0, tb.V)
+    table = (tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us)
+    queries = (q.task, q.slo_us, q.min_acc_bp, q.batch_idx)
+    got, tier = _both_tiered(o, *table, np.ones(tb.V, np.int32), st.load_us, *queries)
+    plain = o.select(*table, *queries)
+    assert np.array_equal(got, plain) and np.array_equal(tier, (plain >= 0).astype(np.int32))
+    got, tier = _both_tiered(o, *table, np.zeros(tb.V, np.int32), st.load_us, *queries)
+    combined = (tb.lat_us.astype(np.int64) + st.load_us.astype(np.int64)[:, None]).astype(np.int32)
+    plain2 = o.select(tb.task_id, tb.acc_bp, tb.lat_us, combined, st.load_us, *queries)
+    assert np.array_equal(got, plain2) and np.array_equal(tier, 2 * (plain2 >= 0).astype(np.int32))
+    assert (plain2 >= 0).sum() > 100 and (plain2 < 0).sum() > 100
+
+
+def pin_tiered_policy(o):
+    """Hand-built cases: an Active match wins over a cheaper and faster Inactive one; Overloaded and
+    Interfered variants are never chosen; the Inactive tier ignores the queue, charges the loading
+    latency against the objective, and orders by load + latency, then latency, then row."""
+    task = np.zeros(5, np.int32)
+    acc = np.full(5, 8000, np.int32)
+    lat = np.array([[100], [10], [10], [10], [50]], np.int32)
+    cost = np.array([[9], [1], [1], [1], [1]], np.int32)
+    queue = np.array([0, 0, 0, 0, 900], np.int32)
+    load = np.array([0, 20, 0, 0, 40], np.int32)
+    sel = lambda state, slo, amin=0: tuple(x[0] for x in _both_tiered(
+        o, task, acc, lat, cost, queue, np.array(state, np.int32), load, [0], [slo], [amin], [0]))
+    assert sel([1, 0, 2, 3, 0], 1000) == (0, 1)          # the Active one, although dearest and slowest
+    assert sel([1, 0, 2, 3, 0], 99) == (1, 2)            # Active misses the bound: best Inactive (30 us combined)
+    assert sel([2, 0, 2, 3, 0], 1000) == (1, 2)          # Overloaded / Interfered rows 0, 2, 3 are skipped
+    assert sel([3, 2, 2, 3, 0], 1000) == (4, 2)          # row 4: queue 900 does not count, load 40 + lat 50 does
+    assert sel([3, 2, 2, 3, 0], 89) == (-1, 0)           # 90 us combined misses an objective of 89
+    assert sel([3, 2, 2, 3, 0], 90) == (4, 2)
+    assert sel([0, 0, 0, 0, 0], 1000) == (2, 2)          # combined 100, 30, 10, 10, 90: rows 2, 3 tie -> lower row
+    assert sel([0, 0, 2, 0, 0], 1000) == (3, 2)
+    assert sel([0, 0, 0, 0, 0], 1000, 8001) == (-1, 0)   # accuracy applies to both tiers
+    lat2 = np.array([[10], [20], [15], [15], [50]], np.int32)
+    load2 = np.array([20, 10, 15, 15, 40], np.int32)     # all combine to 30: the lower inference latency first
+    got = _both_tiered(o, task, acc, lat2, cost, queue, np.zeros(5, np.int32), load2, [0], [1000], [0], [0])
+    assert (got[0][0], got[1][0]) == (0, 2)
+    # no wrap in load + lat
+    big = np.array([[I32MAX]] * 5, np.int32)
+    got = _both_tiered(o, task, acc, big, cost, queue, np.zeros(5, np.int32), np.full(5, I32MAX, np.int32),
+                       [0], [I32MAX], [0], [0])
+    assert got[0][0] == -1
+
+
+def pin_update_state(o):
+    st = np.array([0, 1, 2, 3], np.int32)
+    o.update_state(st, [3, 0, 9, -1, 1, 3], [1, 2, 1, 1, 7, 0])
+    assert st.tolist() == [2, 1, 2, 0]
+
+
+TIERED_PINS = [
+    pin_tiered_numpy,
+    pin_tiered_reduces_to_plain,
+    pin_tiered_policy,
+    pin_update_state,
 ]

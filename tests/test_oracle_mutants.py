@@ -85,6 +85,45 @@ def test_closest_mutant_is_caught(tmp_path, source_text, name, find, repl):
     assert caught, f"no pin notices the planted mistake '{name}'"
 
 
+# planted mistakes in the state-aware selection
+TIERED_MUTANTS = [
+    ("tiered_inactive_before_active", "out_variant = (int32_t)(active >= 0 ? active : inactive);",
+     "out_variant = (int32_t)(inactive >= 0 ? inactive : active);"),
+    ("tiered_overloaded_counts_as_active", "if (state[v] == STATE_ACTIVE) {", "if (state[v] == STATE_ACTIVE || state[v] == STATE_OVERLOADED) {"),
+    ("tiered_interfered_counts_as_inactive", "} else if (state[v] == STATE_INACTIVE) {", "} else if (state[v] == STATE_INACTIVE || state[v] == STATE_INTERFERED) {"),
+    ("tiered_load_not_charged", "if ((int64_t)load_us[v] + (int64_t)lat_us[v * B + b] > (int64_t)slo_us)", "if ((int64_t)lat_us[v * B + b] > (int64_t)slo_us)"),
+    ("tiered_load_sum_wraps", "if ((int64_t)load_us[v] + (int64_t)lat_us[v * B + b] > (int64_t)slo_us)",
+     "if ((int64_t)(int32_t)((uint32_t)load_us[v] + (uint32_t)lat_us[v * B + b]) > (int64_t)slo_us)"),
+    ("tiered_inactive_uses_queue", "if ((int64_t)load_us[v] + (int64_t)lat_us[v * B + b] > (int64_t)slo_us)",
+     "if ((int64_t)load_us[v] + (int64_t)lat_us[v * B + b] + (int64_t)queue_us[v] > (int64_t)slo_us)"),
+    ("tiered_inactive_accuracy_dropped", "if (acc_bp[v] < min_acc_bp)\n                continue;\n            if ((int64_t)load_us[v]",
+     "if ((int64_t)load_us[v]"),
+    ("tiered_inactive_by_cost", "if (inactive < 0 || loads_sooner(lat_us, load_us, B, b, v, inactive))",
+     "if (inactive < 0 || cheaper(lat_us, cost, B, b, v, inactive))"),
+    ("tiered_order_flipped", "if (tv != tw)\n        return tv < tw;", "if (tv != tw)\n        return tv > tw;"),
+    ("tiered_latency_tie_skipped", "int64_t tw = (int64_t)load_us[w] + (int64_t)lat_us[w * B + b];\n    if (tv != tw)\n        return tv < tw;",
+     "int64_t tw = (int64_t)load_us[w] + (int64_t)lat_us[w * B + b];\n    if (tv != tw)\n        return tv < tw;\n    return v < w;"),
+    ("tiered_tier_code_swapped", "*out_tier = active >= 0 ? 1 : (inactive >= 0 ? 2 : 0);", "*out_tier = active >= 0 ? 2 : (inactive >= 0 ? 1 : 0);"),
+    ("state_update_keeps_bad_codes", "if (v < 0 || v >= V || new_state[i] < 0 || new_state[i] > 3)", "if (v < 0 || v >= V)"),
+]
+
+
+@pytest.mark.parametrize("name,find,repl", TIERED_MUTANTS, ids=[m[0] for m in TIERED_MUTANTS])
+def test_tiered_mutant_is_caught(tmp_path, source_text, name, find, repl):
+    assert find in source_text, f"mutant {name}: pattern not in the oracle source any more"
+    src = tmp_path / f"{name}.c"
+    src.write_text(source_text.replace(find, repl))
+    lib = oracle.build_oracle(src=str(src), out=str(tmp_path / f"lib{name}.so"), force=True)
+    mutant = oracle.Oracle(lib)
+    caught = []
+    for pin in pins.TIERED_PINS:
+        try:
+            pin(mutant)
+        except AssertionError:
+            caught.append(pin.__name__)
+    assert caught, f"no pin notices the planted mistake '{name}'"
+
+
 @pytest.fixture(scope="module")
 def source_text():
     with open(SRC) as f:

@@ -14,4 +14,8 @@ from .configs import (  # noqa: F401
     make_queries,
     make_load_update,
     base_seed,
+    VariantStates,
+    StateUpdate,
+    make_states,
+    make_state_update,
 )

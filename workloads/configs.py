@@ -208,3 +208,49 @@ def make_load_update(cfg: int, V: int, chunk: int, fraction: float = 0.10,
     rows = rng.choice(V, size=n, replace=False)
     vals = rng.integers(0, 200001, size=n, dtype=np.int64)
     return LoadUpdate(variant_idx=rows.astype(np.int32), queue_us=vals.astype(np.int32))
+
+
+# ---------------------------------------------------------------- variant states (state-aware selection)
+
+@dataclass
+class VariantStates:
+    """Dynamic state and loading latency of every variant (Section 4: Inactive 0, Active 1,
+    Overloaded 2, Interfered 3)."""
+    state: np.ndarray     # [V] int32
+    load_us: np.ndarray   # [V] int32
+
+
+@dataclass
+class StateUpdate:
+    variant_idx: np.ndarray   # [n] int32, distinct rows
+    state: np.ndarray         # [n] int32
+
+
+_STATE_P = (0.50, 0.40, 0.05, 0.05)   # Inactive, Active, Overloaded, Interfered
+
+
+def make_states(cfg: int, V: int, seed: Optional[int] = None) -> VariantStates:
+    """Stand-in for the state the paper's monitoring daemons keep (it publishes no population):
+    state drawn with probabilities (0.50, 0.40, 0.05, 0.05) for (Inactive, Active, Overloaded,
+    Interfered); loading latency = clamp(lognormal(ln 20000, 1.5), 100, 5,000,000) microseconds,
+    so that part of the unloaded variants can still meet the latency objectives of the query
+    generator.  Seed: _SEED0 + cfg + 7000.  Draw order: states, loading latencies."""
+    if seed is None:
+        seed = _SEED0 + cfg + 7000
+    rng = np.random.default_rng(np.random.PCG64(seed))
+    state = rng.choice(4, size=V, p=_STATE_P).astype(np.int32)
+    load = np.clip(np.rint(rng.lognormal(np.log(20000.0), 1.5, size=V)), 100, 5_000_000)
+    return VariantStates(state=state, load_us=load.astype(np.int32))
+
+
+def make_state_update(cfg: int, V: int, chunk: int, fraction: float = 0.05,
+                      seed: Optional[int] = None) -> StateUpdate:
+    """State report before chunk ``chunk``: ``fraction`` of the variants, chosen without
+    replacement, get a new state drawn as in make_states.  Seed: _SEED0 + cfg + 9000 + chunk."""
+    if seed is None:
+        seed = _SEED0 + cfg + 9000 + chunk
+    rng = np.random.default_rng(np.random.PCG64(seed))
+    n = int(round(V * fraction))
+    rows = rng.choice(V, size=n, replace=False)
+    vals = rng.choice(4, size=n, p=_STATE_P)
+    return StateUpdate(variant_idx=rows.astype(np.int32), state=vals.astype(np.int32))
