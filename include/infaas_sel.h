@@ -155,6 +155,54 @@ int infaas_sel_select_closest(infaas_sel_t *h, int64_t N,
                               const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
                               int32_t *d_out_variant, int32_t *d_out_closest, void *hip_stream);
 
+/*
+ * ---- State-aware selection: the complete Case I of Section 4.1 ------------------------------
+ *
+ * Section 4 tracks every variant in a state machine: Inactive (registered, not loaded), Active
+ * (loaded, below its peak throughput), Overloaded (at its peak) and Interfered (slower than
+ * profiled).  Case I first looks for a match among the Active variants, which incur no loading
+ * latency; only if there is none it turns to the Inactive ones and takes the one with the lowest
+ * combined loading and inference latency that matches the requirements; Overloaded and
+ * Interfered variants are avoided ("Mitigating performance degradation").  Readings where the
+ * text is silent: among several Active matches the cheapest, by infaas_sel_select's key; for
+ * an Inactive variant the latency requirement is load_us[v] + lat_us[v][b] <= slo_us (no
+ * queue: it is not loaded) and the order is (load_us + lat_us[b], lat_us[b], v).
+ */
+enum { INFAAS_SEL_STATE_INACTIVE = 0, INFAAS_SEL_STATE_ACTIVE = 1,
+       INFAAS_SEL_STATE_OVERLOADED = 2, INFAAS_SEL_STATE_INTERFERED = 3 };
+
+/*
+ * Give the loaded table its dynamic state.  HOST arrays, copied:
+ *   state   [V]  INFAAS_SEL_STATE_*
+ *   load_us [V]  loading latency, >= 0, with load_us[v] + lat_us[v][b] <= INT32_MAX
+ * Synchronous.  Needs the staircase index (not INFAAS_SEL_ENGINE_SCAN).  From here on
+ * infaas_sel_select answers from the Active variants only, infaas_sel_select_closest is not
+ * available, and infaas_sel_update_load keeps acting on queue_us (which only the Active tier
+ * reads).  A later infaas_sel_load_variants drops the states again.
+ * Errors: INVALID_ARG, NOT_LOADED, OUT_OF_RANGE, HIP, OOM.
+ */
+int infaas_sel_load_states(infaas_sel_t *h, const int32_t *state, const int32_t *load_us);
+
+/*
+ * State report of the monitoring daemons: state[d_variant_idx[i]] = d_state[i] for i < n.
+ * Both arrays are DEVICE memory; the rows must be distinct; an entry whose row is outside
+ * 0..V-1 or whose code is outside 0..3 is skipped.  Enqueues on hip_stream and returns.
+ * Errors: INVALID_ARG, NOT_LOADED (no states loaded), HIP.
+ */
+int infaas_sel_update_state(infaas_sel_t *h, int32_t n, const int32_t *d_variant_idx,
+                            const int32_t *d_state, void *hip_stream);
+
+/*
+ * Decide N queries by the two-tier policy above.  Arrays as for infaas_sel_select, plus
+ *   d_out_tier  [N]  DEVICE: 1 = the answer is an Active variant, 2 = an Inactive one,
+ *                    0 = none (d_out_variant = -1)
+ * Errors: INVALID_ARG, NOT_LOADED (no states loaded), HIP.
+ */
+int infaas_sel_select_tiered(infaas_sel_t *h, int64_t N,
+                             const int32_t *d_task, const int32_t *d_slo_us,
+                             const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
+                             int32_t *d_out_variant, int32_t *d_out_tier, void *hip_stream);
+
 /* Free the handle and everything it owns.  NULL is a no-op. */
 void infaas_sel_destroy(infaas_sel_t *h);
 
@@ -182,7 +230,9 @@ enum {
     INFAAS_SEL_K_FINISH_WIDE = 6,/* scan engine: decode the device-wide minima */
     INFAAS_SEL_K_INDEX_BUILD = 7,/* staircase index (re)build */
     INFAAS_SEL_K_INDEX_SELECT = 8,/* staircase index lookup, one lane per query */
-    INFAAS_SEL_K_COUNT = 9
+    INFAAS_SEL_K_UPDATE_STATE = 9,/* state report: masks of the rank-ordered columns */
+    INFAAS_SEL_K_TIER_MERGE = 10, /* state-aware selection: merge of the two tiers */
+    INFAAS_SEL_K_COUNT = 11
 };
 typedef struct {
     int64_t launches[INFAAS_SEL_K_COUNT];

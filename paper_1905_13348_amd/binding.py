@@ -20,7 +20,7 @@ ENGINE_SCAN = 1
 ENGINE_INDEX = 2
 
 KERNEL_NAMES = ("update_load", "histogram", "plan", "scatter", "scan_lds", "scan_wide",
-                "finish_wide", "index_build", "index_select")
+                "finish_wide", "index_build", "index_select", "update_state", "tier_merge")
 _K_COUNT = len(KERNEL_NAMES)
 
 _I32P = ctypes.POINTER(ctypes.c_int32)
@@ -57,7 +57,8 @@ _lib: Optional[ctypes.CDLL] = None
 
 # every symbol include/infaas_sel.h declares
 EXPORTED = ("infaas_sel_create", "infaas_sel_load_variants", "infaas_sel_update_load",
-            "infaas_sel_select", "infaas_sel_select_closest", "infaas_sel_destroy", "infaas_sel_reserve",
+            "infaas_sel_select", "infaas_sel_select_closest", "infaas_sel_load_states",
+            "infaas_sel_update_state", "infaas_sel_select_tiered", "infaas_sel_destroy", "infaas_sel_reserve",
             "infaas_sel_read_load", "infaas_sel_set_timing", "infaas_sel_get_timings",
             "infaas_sel_get_info", "infaas_sel_strerror", "infaas_sel_last_error")
 
@@ -88,6 +89,9 @@ def load_library() -> ctypes.CDLL:
     lib.infaas_sel_update_load.argtypes = [vp, ctypes.c_int32, vp, vp, vp]
     lib.infaas_sel_select.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp]
     lib.infaas_sel_select_closest.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp]
+    lib.infaas_sel_load_states.argtypes = [vp, _I32P, _I32P]
+    lib.infaas_sel_update_state.argtypes = [vp, ctypes.c_int32, vp, vp, vp]
+    lib.infaas_sel_select_tiered.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp]
     lib.infaas_sel_destroy.argtypes = [vp]
     lib.infaas_sel_destroy.restype = None
     lib.infaas_sel_reserve.argtypes = [vp, ctypes.c_int64]
@@ -186,6 +190,28 @@ class Selector:
             self._h, n, _dev_ptr(d_task, n, "d_task"), _dev_ptr(d_slo_us, n, "d_slo_us"),
             _dev_ptr(d_min_acc_bp, n, "d_min_acc_bp"), _dev_ptr(d_batch_idx, n, "d_batch_idx"),
             _dev_ptr(d_out_variant, n, "d_out_variant"), _dev_ptr(d_out_closest, n, "d_out_closest"),
+            _stream_ptr(stream)))
+
+    def load_states(self, state, load_us) -> None:
+        """Host arrays [V]: state codes 0..3 (Inactive, Active, Overloaded, Interfered), loading latency."""
+        state, load_us = _host_i32(state), _host_i32(load_us)
+        assert state.shape == load_us.shape and state.ndim == 1
+        _check(self._lib.infaas_sel_load_states(self._h, state.ctypes.data_as(_I32P),
+                                                load_us.ctypes.data_as(_I32P)))
+
+    def update_state(self, d_variant_idx, d_state, stream=None, n: Optional[int] = None) -> None:
+        n = int(d_variant_idx.numel()) if n is None else int(n)
+        _check(self._lib.infaas_sel_update_state(
+            self._h, n, _dev_ptr(d_variant_idx, n, "d_variant_idx"), _dev_ptr(d_state, n, "d_state"),
+            _stream_ptr(stream)))
+
+    def select_tiered(self, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, d_out_tier,
+                      stream=None, n: Optional[int] = None) -> None:
+        n = int(d_task.numel()) if n is None else int(n)
+        _check(self._lib.infaas_sel_select_tiered(
+            self._h, n, _dev_ptr(d_task, n, "d_task"), _dev_ptr(d_slo_us, n, "d_slo_us"),
+            _dev_ptr(d_min_acc_bp, n, "d_min_acc_bp"), _dev_ptr(d_batch_idx, n, "d_batch_idx"),
+            _dev_ptr(d_out_variant, n, "d_out_variant"), _dev_ptr(d_out_tier, n, "d_out_tier"),
             _stream_ptr(stream)))
 
     def destroy(self) -> None:

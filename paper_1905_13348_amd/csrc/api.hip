@@ -74,6 +74,11 @@ struct infaas_sel {
     int64_t table_bytes = 0;
     int32_t max_segment = 0, max_lds_segment = 0, wide_segments = 0;
     TableView tv{};
+    // state-aware selection: this table then serves the Active variants, `inactive` (a handle of
+    // its own, built from the same rows) the Inactive ones
+    std::vector<int32_t> h_task, h_acc, h_lat;   // host copies of the static columns, for building `inactive`
+    int32_t *d_state = nullptr;                  // [Vp] state per slot (see TableView::state)
+    infaas_sel *inactive = nullptr;
 
     // staircase index
     IndexView ix{};
@@ -107,10 +112,14 @@ struct infaas_sel {
         d_acc_r = d_lat_r = d_orig_r = d_gpos = nullptr;
         d_tot_r = nullptr;
         d_rank = d_perm = nullptr;
+        (void)hipFree(d_state);
+        d_state = nullptr;
         loaded = false;
         table_bytes = 0;
         free_index();
+        drop_inactive();
     }
+    void drop_inactive();
     void free_index()
     {
         (void)hipFree(ix.pool); (void)hipFree(ix.step_row); (void)hipFree(ix.ctrl);  // hdr lives in pool's allocation
@@ -132,6 +141,12 @@ struct infaas_sel {
         scratch_bytes = 0;
     }
 };
+
+void infaas_sel::drop_inactive()
+{
+    if (inactive) infaas_sel_destroy(inactive);
+    inactive = nullptr;
+}
 
 namespace {
 
@@ -407,6 +422,9 @@ int infaas_sel_load_variants(infaas_sel_t *h, int32_t V, const int32_t *task_id,
             if (lat_us[v * B + b] < 0 || cost[v * B + b] < 0) return INFAAS_SEL_ERR_OUT_OF_RANGE;
     }
 
+    std::vector<int32_t> keep_task(task_id, task_id + V), keep_acc(acc_bp, acc_bp + V),
+        keep_lat(lat_us, lat_us + (size_t)V * B);
+
     // ---- group rows by task (stable), pad every segment to a multiple of 4 slots
     std::vector<int32_t> seg_len(T, 0), seg_off((size_t)T + 1, 0);
     for (int64_t v = 0; v < V; ++v) seg_len[task_id[v]] += 1;
@@ -523,7 +541,10 @@ int infaas_sel_load_variants(infaas_sel_t *h, int32_t V, const int32_t *task_id,
     for (int64_t v = 0; v < V; ++v) tv.acc_base = (v == 0 || acc_bp[v] < tv.acc_base) ? acc_bp[v] : tv.acc_base;
     // the lookup forms acc_base - 1; a slice that holds the one accuracy below this base is not indexed
     if (tv.acc_base == INT32_MIN) tv.acc_base = INT32_MIN + 1;
+    tv.state = nullptr;
+    tv.want_state = 1;
     h->tv = tv;
+    h->h_task.swap(keep_task); h->h_acc.swap(keep_acc); h->h_lat.swap(keep_lat);
     h->loaded = true;
     if ((h->flags & INFAAS_SEL_ENGINE_MASK) != INFAAS_SEL_ENGINE_SCAN) {
         int rc = create_index(h);
@@ -560,6 +581,102 @@ int infaas_sel_update_load(infaas_sel_t *h, int32_t n, const int32_t *d_variant_
 
 namespace {
 
+// Gives the table of `h` the states (device copy of the caller's [V] array) and rebuilds its index.
+int apply_states(infaas_sel *h, const int32_t *d_states, hipStream_t st)
+{
+    if (!HIP_OK(launch_update_state(h->tv, h->V, nullptr, d_states, h->have_index ? h->ix.ctrl : nullptr, st)))
+        return INFAAS_SEL_ERR_HIP;
+    if (h->have_index && !HIP_OK(launch_index_build(h->tv, h->ix, st))) return INFAAS_SEL_ERR_HIP;
+    return INFAAS_SEL_OK;
+}
+
+}  // namespace
+
+int infaas_sel_load_states(infaas_sel_t *h, const int32_t *state, const int32_t *load_us)
+{
+    if (!h) return INFAAS_SEL_ERR_INVALID_ARG;
+    if (!h->loaded) return INFAAS_SEL_ERR_NOT_LOADED;
+    if (!h->have_index || (h->V > 0 && (!state || !load_us))) return INFAAS_SEL_ERR_INVALID_ARG;
+    const int32_t V = h->V, B = h->B;
+    std::vector<int32_t> combined((size_t)V * B);   // load + inference latency: the Inactive tier's order
+    for (int64_t v = 0; v < V; ++v) {
+        if (state[v] < 0 || state[v] > 3 || load_us[v] < 0) return INFAAS_SEL_ERR_OUT_OF_RANGE;
+        for (int32_t b = 0; b < B; ++b) {
+            const int64_t c = (int64_t)load_us[v] + h->h_lat[(size_t)v * B + b];
+            if (c > INT32_MAX) return INFAAS_SEL_ERR_OUT_OF_RANGE;
+            combined[(size_t)v * B + b] = (int32_t)c;
+        }
+    }
+    DeviceGuard g(h->device);
+    if (!g.ok) return INFAAS_SEL_ERR_HIP;
+    if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
+    h->drop_inactive();
+    // The Inactive tier is a table of its own over the same rows: cost := load + latency (its order
+    // is (load + latency, latency, row)) and queue := load (its latency test is load + latency <= slo).
+    infaas_sel_config cfg{};
+    cfg.num_tasks = h->T; cfg.num_batch_sizes = B; cfg.batch_sizes = h->batch_sizes.data();
+    cfg.device = h->device; cfg.flags = INFAAS_SEL_ENGINE_INDEX; cfg.lds_segment_limit = h->lds_limit;
+    infaas_sel *sub = nullptr;
+    int rc = infaas_sel_create(&cfg, &sub);
+    if (rc == INFAAS_SEL_OK)
+        rc = infaas_sel_load_variants(sub, V, h->h_task.data(), h->h_acc.data(), h->h_lat.data(), combined.data(), load_us);
+    if (rc == INFAAS_SEL_OK && !sub->have_index) rc = INFAAS_SEL_ERR_INVALID_ARG;
+    int32_t *d_states = nullptr;
+    if (rc == INFAAS_SEL_OK) {
+        const size_t vp = (size_t)h->Vp;
+        if (!h->d_state && dev_alloc(&h->d_state, vp) != hipSuccess) rc = INFAAS_SEL_ERR_OOM;
+        if (rc == INFAAS_SEL_OK && dev_alloc(&sub->d_state, vp) != hipSuccess) rc = INFAAS_SEL_ERR_OOM;
+        if (rc == INFAAS_SEL_OK && dev_alloc(&d_states, (size_t)std::max(V, 1)) != hipSuccess) rc = INFAAS_SEL_ERR_OOM;
+        if (rc == INFAAS_SEL_ERR_OOM) (void)hipGetLastError();
+    }
+    if (rc == INFAAS_SEL_OK) {
+        // padding slots get a state no table serves
+        if (!HIP_OK(hipMemset(h->d_state, 0x7F, (size_t)h->Vp * 4)) || !HIP_OK(hipMemset(sub->d_state, 0x7F, (size_t)h->Vp * 4)) ||
+            (V > 0 && !HIP_OK(hipMemcpy(d_states, state, (size_t)V * 4, hipMemcpyHostToDevice))))
+            rc = INFAAS_SEL_ERR_HIP;
+    }
+    if (rc == INFAAS_SEL_OK) {
+        h->tv.state = h->d_state; h->tv.want_state = 1;       // Active
+        sub->tv.state = sub->d_state; sub->tv.want_state = 0; // Inactive
+        rc = apply_states(h, d_states, nullptr);
+        if (rc == INFAAS_SEL_OK) rc = apply_states(sub, d_states, nullptr);
+        if (rc == INFAAS_SEL_OK && !HIP_OK(hipDeviceSynchronize())) rc = INFAAS_SEL_ERR_HIP;
+    }
+    (void)hipFree(d_states);
+    if (rc != INFAAS_SEL_OK) {
+        if (sub) infaas_sel_destroy(sub);
+        h->tv.state = nullptr;
+        return rc;
+    }
+    sub->timing = h->timing;
+    h->inactive = sub;
+    return INFAAS_SEL_OK;
+}
+
+int infaas_sel_update_state(infaas_sel_t *h, int32_t n, const int32_t *d_variant_idx,
+                            const int32_t *d_state, void *hip_stream)
+{
+    if (!h || n < 0) return INFAAS_SEL_ERR_INVALID_ARG;
+    if (!h->loaded || !h->inactive) return INFAAS_SEL_ERR_NOT_LOADED;
+    if (n == 0) return INFAAS_SEL_OK;
+    if (!d_variant_idx || !d_state) return INFAAS_SEL_ERR_INVALID_ARG;
+    DeviceGuard g(h->device);
+    if (!g.ok) return INFAAS_SEL_ERR_HIP;
+    hipStream_t st = (hipStream_t)hip_stream;
+    for (infaas_sel *t : {h, h->inactive}) {
+        {
+            LaunchTimer tm(t, INFAAS_SEL_K_UPDATE_STATE, st);
+            if (!HIP_OK(launch_update_state(t->tv, n, d_variant_idx, d_state, t->ix.ctrl, st, tm.ev())))
+                return INFAAS_SEL_ERR_HIP;
+        }
+        LaunchTimer tm(t, INFAAS_SEL_K_INDEX_BUILD, st);
+        if (!HIP_OK(launch_index_build(t->tv, t->ix, st, tm.ev()))) return INFAAS_SEL_ERR_HIP;
+    }
+    return INFAAS_SEL_OK;
+}
+
+namespace {
+
 // Common part of the two select calls; d_out_closest is null for the plain one.
 int select_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,
                 const int32_t *d_min_acc_bp, const int32_t *d_batch_idx, int32_t *d_out_variant,
@@ -567,9 +684,9 @@ int select_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t
 {
     if (!h || N < 0) return INFAAS_SEL_ERR_INVALID_ARG;
     if (!h->loaded) return INFAAS_SEL_ERR_NOT_LOADED;
-    if (closest && !h->have_index) {
+    if (closest && (!h->have_index || h->inactive)) {
         snprintf(g_last_error, sizeof(g_last_error),
-                 "infaas_sel_select_closest needs the staircase index, which this handle does not have");
+                 "infaas_sel_select_closest needs the staircase index and a handle without variant states");
         return INFAAS_SEL_ERR_INVALID_ARG;
     }
     if (N == 0) return INFAAS_SEL_OK;
@@ -600,6 +717,36 @@ int infaas_sel_select(infaas_sel_t *h, int64_t N, const int32_t *d_task, const i
                       int32_t *d_out_variant, void *hip_stream)
 {
     return select_impl(h, N, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, nullptr, false, hip_stream);
+}
+
+int infaas_sel_select_tiered(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,
+                             const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
+                             int32_t *d_out_variant, int32_t *d_out_tier, void *hip_stream)
+{
+    if (!h || N < 0) return INFAAS_SEL_ERR_INVALID_ARG;
+    if (!h->loaded || !h->inactive) return INFAAS_SEL_ERR_NOT_LOADED;
+    if (N == 0) return INFAAS_SEL_OK;
+    if (!d_task || !d_slo_us || !d_min_acc_bp || !d_batch_idx || !d_out_variant || !d_out_tier)
+        return INFAAS_SEL_ERR_INVALID_ARG;
+    DeviceGuard g(h->device);
+    if (!g.ok) return INFAAS_SEL_ERR_HIP;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // Active tier into the result array, Inactive tier into the tier array, then one pass merges them.
+    for (int64_t done = 0; done < N; done += kMaxPass) {
+        QueryView q{};
+        q.n = (int32_t)std::min(kMaxPass, N - done);
+        q.task = d_task + done; q.slo = d_slo_us + done; q.min_acc = d_min_acc_bp + done;
+        q.bidx = d_batch_idx + done; q.closest = nullptr;
+        q.out = d_out_variant + done;
+        int rc = index_pass(h, q, st);
+        if (rc != INFAAS_SEL_OK) return rc;
+        q.out = d_out_tier + done;
+        rc = index_pass(h->inactive, q, st);
+        if (rc != INFAAS_SEL_OK) return rc;
+    }
+    LaunchTimer t(h, INFAAS_SEL_K_TIER_MERGE, st);
+    if (!HIP_OK(launch_tier_merge(N, d_out_variant, d_out_tier, st, t.ev()))) return INFAAS_SEL_ERR_HIP;
+    return INFAAS_SEL_OK;
 }
 
 int infaas_sel_select_closest(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,
@@ -661,6 +808,7 @@ int infaas_sel_set_timing(infaas_sel_t *h, int32_t enabled)
     h->pending.clear();
     h->acc = infaas_sel_timings{};
     h->timing = enabled != 0;
+    if (h->inactive) return infaas_sel_set_timing(h->inactive, enabled);
     return INFAAS_SEL_OK;
 }
 
@@ -684,6 +832,12 @@ int infaas_sel_get_timings(infaas_sel_t *h, infaas_sel_timings *out)
     }
     h->pending.clear();
     *out = h->acc;
+    if (h->inactive) {   // the kernels of the Inactive tier's table count with this handle's
+        infaas_sel_timings sub{};
+        const int rc2 = infaas_sel_get_timings(h->inactive, &sub);
+        for (int k = 0; k < INFAAS_SEL_K_COUNT; ++k) { out->launches[k] += sub.launches[k]; out->total_ms[k] += sub.total_ms[k]; }
+        if (rc == INFAAS_SEL_OK) rc = rc2;
+    }
     return rc;
 }
 

@@ -27,12 +27,17 @@ struct TableView {
     const int32_t *slot_of;     // [V] caller row -> slot
     // The same slices once more, stored in rank order: entry seg_off[t] + r of column b is the
     // variant of rank r in slice (t, b).  tot_r = lat_r + queue is kept current by load updates.
-    const int32_t *acc_r;       // [B][Vp]
+    int32_t *acc_r;             // [B][Vp]
     uint32_t *tot_r;            // [B][Vp]
     const int32_t *lat_r;       // [B][Vp]
     const int32_t *orig_r;      // [B][Vp] caller row
     const int32_t *gpos;        // [B][Vp] slot -> its entry in the rank-ordered column b
     int32_t acc_base;           // smallest accuracy in the table; index keys are acc - acc_base + 1
+    // State-aware selection: a table serves one state (Active or Inactive).  Variants in another
+    // state are masked in the rank-ordered columns (accuracy = acc_base, latency-plus-queue =
+    // 0xFFFFFFFF): nothing selects them and every entry ranked before them dominates them.
+    int32_t *state;             // [Vp] state of each slot, or null when the table is not state-aware
+    int32_t want_state;         // the state this table serves
 };
 
 // ---------------------------------------------------------------- staircase index
@@ -146,6 +151,11 @@ inline hipError_t launch_kernel(const LaunchEvents *ev, void (*kernel)(P...), di
 // Kernel launchers (scan engine).  Each returns the hipError_t of its launch.
 hipError_t launch_update_load(const TableView &tv, int32_t n, const int32_t *idx,
                               const int32_t *val, uint32_t *index_ctrl, hipStream_t st, const LaunchEvents *ev = nullptr);
+// State report: state of row idx[i] := val[i] (idx null: row i, all V rows), masks refreshed.
+hipError_t launch_update_state(const TableView &tv, int32_t n, const int32_t *idx,
+                               const int32_t *val, uint32_t *index_ctrl, hipStream_t st, const LaunchEvents *ev = nullptr);
+// out[q] = first[q] >= 0 ? first[q] : second[q], tier[q] = 1 / 2 / 0; `tier` holds `second` on entry.
+hipError_t launch_tier_merge(int64_t n, int32_t *out, int32_t *tier, hipStream_t st, const LaunchEvents *ev = nullptr);
 hipError_t launch_histogram(const TableView &tv, const QueryView &q, const ScanScratch &sc,
                             hipStream_t st, const LaunchEvents *ev = nullptr);
 hipError_t launch_plan(const TableView &tv, const ScanScratch &sc, hipStream_t st, const LaunchEvents *ev = nullptr);

@@ -98,7 +98,49 @@ __global__ __launch_bounds__(256) void k_update_load(TableView tv, int32_t n,
     const int32_t slot = tv.slot_of[v];
     if (b == 0) tv.queue[slot] = x;
     const int64_t g = (int64_t)b * tv.Vp + tv.gpos[(int64_t)b * tv.Vp + slot];
-    tv.tot_r[g] = (uint32_t)tv.lat_r[g] + (uint32_t)x;
+    const bool masked = tv.state && tv.state[slot] != tv.want_state;
+    tv.tot_r[g] = masked ? 0xFFFFFFFFu : (uint32_t)tv.lat_r[g] + (uint32_t)x;
+}
+
+// One thread per (report entry, batch size): the state itself, and the masked or restored entry
+// of the variant in each rank-ordered column.  idx null: entry i is row i.  Rewinds the index
+// allocator like a load update, because the index is rebuilt afterwards.
+__global__ __launch_bounds__(256) void k_update_state(TableView tv, int32_t n,
+                                                      const int32_t *__restrict__ idx,
+                                                      const int32_t *__restrict__ val,
+                                                      uint32_t *__restrict__ index_ctrl)
+{
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (tid == 0 && index_ctrl) {
+        index_ctrl[kCtlPool] = kDummyBodyBytes;
+        index_ctrl[kCtlSteps] = 1;
+        index_ctrl[kCtlMaxK0] = 1;
+        index_ctrl[kCtlTrunc] = 0;
+        index_ctrl[kCtlNoBody] = 0;
+        index_ctrl[kCtlMaxK] = 0;
+    }
+    if (tid >= (int64_t)n * tv.B)
+        return;
+    const int32_t i = (int32_t)(tid / tv.B), b = (int32_t)(tid - (int64_t)i * tv.B);
+    const int32_t v = idx ? idx[i] : i;
+    const int32_t x = val[i];
+    if ((uint32_t)v >= (uint32_t)tv.V || (uint32_t)x > 3u)
+        return;
+    const int32_t slot = tv.slot_of[v];
+    if (b == 0) tv.state[slot] = x;
+    const int64_t g = (int64_t)b * tv.Vp + tv.gpos[(int64_t)b * tv.Vp + slot];
+    const bool masked = x != tv.want_state;
+    tv.tot_r[g] = masked ? 0xFFFFFFFFu : (uint32_t)tv.lat_r[g] + (uint32_t)tv.queue[slot];
+    tv.acc_r[g] = masked ? tv.acc_base : tv.acc[slot];
+}
+
+__global__ __launch_bounds__(256) void k_tier_merge(int64_t n, int32_t *__restrict__ out, int32_t *__restrict__ tier)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t first = out[i], second = tier[i];
+        out[i] = first >= 0 ? first : second;
+        tier[i] = first >= 0 ? 1 : (second >= 0 ? 2 : 0);
+    }
 }
 
 // ---------------------------------------------------------------- bucketing
@@ -392,6 +434,22 @@ hipError_t launch_update_load(const TableView &tv, int32_t n, const int32_t *idx
     if (n <= 0) return hipSuccess;
     const int64_t threads = (int64_t)n * tv.B;
     return launch_kernel(ev, k_update_load, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tv, n, idx, val, index_ctrl);
+}
+
+hipError_t launch_update_state(const TableView &tv, int32_t n, const int32_t *idx,
+                               const int32_t *val, uint32_t *index_ctrl, hipStream_t st, const LaunchEvents *ev)
+{
+    if (n <= 0) return hipSuccess;
+    const int64_t threads = (int64_t)n * tv.B;
+    return launch_kernel(ev, k_update_state, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tv, n, idx, val, index_ctrl);
+}
+
+hipError_t launch_tier_merge(int64_t n, int32_t *out, int32_t *tier, hipStream_t st, const LaunchEvents *ev)
+{
+    if (n <= 0) return hipSuccess;
+    int64_t blocks = (n + 1023) / 1024;
+    if (blocks > 4096) blocks = 4096;
+    return launch_kernel(ev, k_tier_merge, dim3((unsigned)blocks), dim3(256), 0, st, n, out, tier);
 }
 
 hipError_t launch_histogram(const TableView &tv, const QueryView &q, const ScanScratch &sc,
