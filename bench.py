@@ -6,7 +6,10 @@ task popularity), inputs already resident in HBM.  For the streaming configurati
 is one 4M-query chunk preceded by its load update (10% of the variants).
 
 With --closest a step is one call of infaas_sel_select_closest (the selection plus a suggestion
-for the queries that nothing satisfies; 24 B per decision).
+for the queries that nothing satisfies; 24 B per decision).  With --tiered a step is one call of
+infaas_sel_select_tiered over seeded variant states (Active variants first, else an Inactive one
+by loading + inference latency; variant and tier arrays, 24 B per decision); its two lookup
+launches are priced together.
 
 Prints ONE JSON line: decisions/s, the roofline of the dominant kernel (algorithmic bytes:
 20 B per decision + the variant table once, against 8 TB/s of HBM) timed with HIP events on
@@ -68,6 +71,9 @@ def main() -> int:
     ap.add_argument("--closest", action="store_true",
                     help="time infaas_sel_select_closest (selection plus a suggestion where nothing is "
                          "feasible; 24 B per decision) instead of infaas_sel_select")
+    ap.add_argument("--tiered", action="store_true",
+                    help="time infaas_sel_select_tiered (state-aware two-tier selection over seeded variant "
+                         "states; 24 B per decision) instead of infaas_sel_select")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -100,13 +106,18 @@ def main() -> int:
     chunks = spec["chunks"]
     per_step = spec["num_queries"] // chunks
     engine = pkg.ENGINE_AUTO if args.engine == "auto" else pkg.ENGINE_SCAN
-    if args.closest and args.engine != "auto":
-        print("bench.py: --closest needs the index engine (--engine auto)", file=sys.stderr)
+    if (args.closest or args.tiered) and (args.engine != "auto" or (args.closest and args.tiered)):
+        print("bench.py: --closest and --tiered need the index engine (--engine auto), one at a time",
+              file=sys.stderr)
         return 2
 
     sel = pkg.Selector(tb.num_tasks, tb.batch_sizes, device=0, engine=engine)
     sel.load_variants(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us)
     sel.reserve(per_step)
+    states = None
+    if args.tiered:
+        states = workloads.make_states(cfg, tb.V)
+        sel.load_states(states.state, states.load_us)
 
     # inputs resident in HBM before the timed region.  The streaming configuration cycles over a
     # few distinct chunks and load reports; the others reuse one batch.
@@ -115,8 +126,9 @@ def main() -> int:
     dev_q = [[torch.from_numpy(x).cuda() for x in (q.task, q.slo_us, q.min_acc_bp, q.batch_idx)]
              for q in host_q]
     out = torch.empty(per_step, dtype=torch.int32, device="cuda")
-    closest = torch.empty(per_step, dtype=torch.int32, device="cuda") if args.closest else None
-    per_decision = BYTES_PER_DECISION + (4 if args.closest else 0)   # the second result array
+    two_results = args.closest or args.tiered                        # suggestion, or tier
+    closest = torch.empty(per_step, dtype=torch.int32, device="cuda") if two_results else None
+    per_decision = BYTES_PER_DECISION + (4 if two_results else 0)
     updates = []
     if chunks > 1:
         for c in range(1, n_sets + 1):
@@ -129,6 +141,8 @@ def main() -> int:
             sel.update_load(u[0], u[1])
         if args.closest:
             sel.select_closest(*dev_q[i % n_sets], out, closest)
+        elif args.tiered:
+            sel.select_tiered(*dev_q[i % n_sets], out, closest)
         else:
             sel.select(*dev_q[i % n_sets], out)
 
@@ -153,19 +167,25 @@ def main() -> int:
     dom = max(active, key=lambda k: active[k]["total_ms"])
     dom_avg_ms = active[dom]["total_ms"] / active[dom]["launches"]
     launches_per_step = active[dom]["launches"] / args.steps
-    if dom == "index_build":     # reads the rank-ordered accuracy and latency+queue columns once
+    mode = "/closest" if args.closest else "/tiered" if args.tiered else ""
+    fixed_bytes = table_bytes(tb) + (8 * tb.V if args.tiered else 0)   # + state and loading latency
+    if args.tiered and dom == "index_select":
+        # one lookup per tier: the pair is priced as one launch against the bytes of the whole call
+        algo_bytes = per_decision * per_step + fixed_bytes
+        dom_avg_ms = active[dom]["total_ms"] / args.steps
+    elif dom == "index_build":     # reads the rank-ordered accuracy and latency+queue columns once
         algo_bytes = 8 * tb.B * tb.V
     elif dom == "update_load":
         algo_bytes = UPDATE_BYTES * updates[0][2].variant_idx.size
     else:                        # a select kernel: every query in, every result out, the table once
-        algo_bytes = (per_decision * per_step + table_bytes(tb)) / launches_per_step
+        algo_bytes = (per_decision * per_step + fixed_bytes) / launches_per_step
     achieved = algo_bytes / (dom_avg_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
-                "traffic": measured_traffic(dom, cfg, args.engine + ("/closest" if args.closest else "")),
+                "traffic": measured_traffic(dom, cfg, args.engine + mode),
                 "avg_kernel_ms": round(dom_avg_ms, 5),
                 "algorithmic_bytes_per_launch": int(algo_bytes)}
-    whole_bytes = per_decision * per_step + table_bytes(tb) + \
+    whole_bytes = per_decision * per_step + fixed_bytes + \
         (UPDATE_BYTES * updates[0][2].variant_idx.size if updates else 0)
     whole_frac = whole_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
 
@@ -185,14 +205,18 @@ def main() -> int:
         fields = (q.task, q.slo_us, q.min_acc_bp, q.batch_idx)
         n0 = min(per_step, 100_000)
         s0 = time.perf_counter()
-        ref_fn = ref.select_closest if args.closest else ref.select
+        if args.tiered:
+            def ref_fn(*a):
+                return ref.select_tiered(*a[:5], states.state, states.load_us, *a[5:])
+        else:
+            ref_fn = ref.select_closest if args.closest else ref.select
         ref_fn(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, queue, *(f[:n0] for f in fields))
         rate0 = n0 / (time.perf_counter() - s0)
         n = int(min(per_step, max(n0, rate0 * args.cpu_seconds)))
         s0 = time.perf_counter()
         want = ref_fn(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, queue, *(f[:n] for f in fields))
         dt = time.perf_counter() - s0
-        if args.closest:
+        if two_results:
             mismatches = int((out[:n].cpu().numpy() != want[0]).sum() + (closest[:n].cpu().numpy() != want[1]).sum())
         else:
             mismatches = int((out[:n].cpu().numpy() != want).sum())
@@ -207,7 +231,8 @@ def main() -> int:
         "config": {"workload": f"config {cfg} ({spec['name']}): {tb.num_tasks} tasks, {tb.V} variants, "
                                f"{tb.B} batch sizes, {per_step} queries per step"
                                + (f", load report of {updates[0][2].variant_idx.size} rows before every step" if updates else "")
-                               + (", closest-variant mode (two result arrays)" if args.closest else ""),
+                               + (", closest-variant mode (two result arrays)" if args.closest else "")
+                               + (", state-aware two-tier selection (variant and tier arrays)" if args.tiered else ""),
                    "engine": args.engine},
         "roofline": roofline,
         "whole_step_frac_of_hbm_roofline": round(whole_frac, 5),

@@ -231,8 +231,7 @@ enum {
     INFAAS_SEL_K_INDEX_BUILD = 7,/* staircase index (re)build */
     INFAAS_SEL_K_INDEX_SELECT = 8,/* staircase index lookup, one lane per query */
     INFAAS_SEL_K_UPDATE_STATE = 9,/* state report: masks of the rank-ordered columns */
-    INFAAS_SEL_K_TIER_MERGE = 10, /* state-aware selection: merge of the two tiers */
-    INFAAS_SEL_K_COUNT = 11
+    INFAAS_SEL_K_COUNT = 10
 };
 typedef struct {
     int64_t launches[INFAAS_SEL_K_COUNT];

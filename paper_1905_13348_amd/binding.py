@@ -20,7 +20,7 @@ ENGINE_SCAN = 1
 ENGINE_INDEX = 2
 
 KERNEL_NAMES = ("update_load", "histogram", "plan", "scatter", "scan_lds", "scan_wide",
-                "finish_wide", "index_build", "index_select", "update_state", "tier_merge")
+                "finish_wide", "index_build", "index_select", "update_state")
 _K_COUNT = len(KERNEL_NAMES)
 
 _I32P = ctypes.POINTER(ctypes.c_int32)

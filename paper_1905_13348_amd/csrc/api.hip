@@ -731,21 +731,19 @@ int infaas_sel_select_tiered(infaas_sel_t *h, int64_t N, const int32_t *d_task, 
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     hipStream_t st = (hipStream_t)hip_stream;
-    // Active tier into the result array, Inactive tier into the tier array, then one pass merges them.
+    // Active tier into the result array; the Inactive tier's lookup reads it back, fills in the
+    // queries it left open and writes the tier array.
     for (int64_t done = 0; done < N; done += kMaxPass) {
         QueryView q{};
         q.n = (int32_t)std::min(kMaxPass, N - done);
         q.task = d_task + done; q.slo = d_slo_us + done; q.min_acc = d_min_acc_bp + done;
-        q.bidx = d_batch_idx + done; q.closest = nullptr;
-        q.out = d_out_variant + done;
+        q.bidx = d_batch_idx + done; q.out = d_out_variant + done;
         int rc = index_pass(h, q, st);
         if (rc != INFAAS_SEL_OK) return rc;
-        q.out = d_out_tier + done;
+        q.tier = d_out_tier + done;
         rc = index_pass(h->inactive, q, st);
         if (rc != INFAAS_SEL_OK) return rc;
     }
-    LaunchTimer t(h, INFAAS_SEL_K_TIER_MERGE, st);
-    if (!HIP_OK(launch_tier_merge(N, d_out_variant, d_out_tier, st, t.ev()))) return INFAAS_SEL_ERR_HIP;
     return INFAAS_SEL_OK;
 }
 

@@ -514,10 +514,14 @@ __device__ __forceinline__ int32_t closest_step(const Mem &mem, int nit, uint32_
     return second ? (int32_t)(kBodySteps + o1.step) : (int32_t)o0.step;
 }
 
-template <bool kLds, bool kClosest>
+// kMode 0: selection.  1: selection plus closest-variant suggestion (q.closest).  2: second tier of
+// the state-aware selection: q.out holds the first tier's answers on entry; only the queries it
+// left at -1 are looked up, and q.tier is written (1 = first tier, 2 = this one, 0 = none).
+template <bool kLds, int kMode>
 __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, IndexView ix, QueryView q,
                                                               int32_t *__restrict__ park_mem, uint32_t lds_cap)
 {
+    constexpr bool kClosest = kMode == 1, kSecond = kMode == 2;
     extern __shared__ __align__(16) uint32_t lds_w[];  // [16 B control][S + 1 headers][lds_cap bytes of bodies]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t nhdr = (uint32_t)tv.S + 1u;
@@ -526,7 +530,8 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     const uint32_t lds_hdr0 = lds_base + kLdsCtrlBytes;
     const uint32_t rebase = lds_hdr0 + hdr_bytes;      // LDS address of pool offset 0
     const bool aligned = ((((uintptr_t)q.task) | ((uintptr_t)q.slo) | ((uintptr_t)q.min_acc) |
-                           ((uintptr_t)q.bidx) | ((uintptr_t)q.out) | ((uintptr_t)q.closest)) & 15u) == 0;
+                           ((uintptr_t)q.bidx) | ((uintptr_t)q.out) | ((uintptr_t)q.closest) |
+                           ((uintptr_t)q.tier)) & 15u) == 0;
     // Work units of one wavefront: 64 lanes x kPerThread consecutive queries.  The units are split
     // evenly and contiguously over the workgroups; inside a workgroup the wavefronts draw them from
     // a counter in LDS, because the wavefronts of a SIMD do not advance at the same speed.
@@ -542,13 +547,14 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     // query outside the table).
     struct Fields {
         int32_t tk[kPerThread], sl[kPerThread], am[kPerThread], bi[kPerThread], unit;
+        int32_t fr[kPerThread];   // second tier only: the first tier's answer
     };
     auto load_unit = [&](Fields &f, int32_t unit) {
         f.unit = unit;
         const int32_t i0 = unit * kUnit + lane * 4;
         if (unit < 0) {
 #pragma unroll
-            for (int k = 0; k < kPerThread; ++k) { f.tk[k] = -1; f.sl[k] = 0; f.am[k] = 0; f.bi[k] = 0; }
+            for (int k = 0; k < kPerThread; ++k) { f.tk[k] = -1; f.sl[k] = 0; f.am[k] = 0; f.bi[k] = 0; f.fr[k] = -1; }
         } else if (aligned && i0 + kSpan <= q.n) {
             const uint32_t off = (uint32_t)i0 * 4u;   // one 32-bit byte offset for all four arrays (n <= 2^28)
 #pragma unroll
@@ -561,6 +567,10 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                 f.sl[4 * h] = b.x; f.sl[4 * h + 1] = b.y; f.sl[4 * h + 2] = b.z; f.sl[4 * h + 3] = b.w;
                 f.am[4 * h] = c.x; f.am[4 * h + 1] = c.y; f.am[4 * h + 2] = c.z; f.am[4 * h + 3] = c.w;
                 f.bi[4 * h] = d.x; f.bi[4 * h + 1] = d.y; f.bi[4 * h + 2] = d.z; f.bi[4 * h + 3] = d.w;
+                if (kSecond) {
+                    const v4i e = __builtin_nontemporal_load((const v4i *)((const char *)q.out + off) + 64 * h);
+                    f.fr[4 * h] = e.x; f.fr[4 * h + 1] = e.y; f.fr[4 * h + 2] = e.z; f.fr[4 * h + 3] = e.w;
+                }
             }
         } else {
 #pragma unroll
@@ -571,7 +581,12 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                 f.sl[k] = in ? q.slo[i] : 0;
                 f.am[k] = in ? q.min_acc[i] : 0;
                 f.bi[k] = in ? q.bidx[i] : 0;
+                if (kSecond) f.fr[k] = in ? q.out[i] : -1;
             }
+        }
+        if (kSecond) {   // answered by the first tier: nothing to look up, like a query outside the table
+#pragma unroll
+            for (int k = 0; k < kPerThread; ++k) f.tk[k] = f.fr[k] >= 0 ? -1 : f.tk[k];
         }
     };
 
@@ -655,7 +670,10 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     int32_t p_lrow[kPerThread], p_grow[kPerThread], p_i0 = -1;
     uint32_t p_base[kPerThread];
     bool p_inl[kPerThread];
-    auto p_val = [&](int k) -> int32_t { return p_inl[k] ? (int32_t)((p_base[k] << 16) | (uint32_t)p_lrow[k]) : p_grow[k]; };
+    int32_t p_first[kPerThread];   // second tier only
+    auto p_own = [&](int k) -> int32_t { return p_inl[k] ? (int32_t)((p_base[k] << 16) | (uint32_t)p_lrow[k]) : p_grow[k]; };
+    auto p_val = [&](int k) -> int32_t { return kSecond && p_first[k] >= 0 ? p_first[k] : p_own(k); };
+    auto p_tier = [&](int k) -> int32_t { return p_first[k] >= 0 ? 1 : (p_own(k) >= 0 ? 2 : 0); };
     auto store_unit = [&]() {
         if (p_i0 < 0) return;
         if (aligned && p_i0 + kSpan <= q.n) {
@@ -664,6 +682,10 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                 const v4i r = {p_val(4 * h), p_val(4 * h + 1), p_val(4 * h + 2), p_val(4 * h + 3)};
                 __builtin_nontemporal_store(r, (v4i *)((char *)q.out + (uint32_t)p_i0 * 4u) + 64 * h);
                 if (kClosest) __builtin_nontemporal_store(r, (v4i *)((char *)q.closest + (uint32_t)p_i0 * 4u) + 64 * h);
+                if (kSecond) {
+                    const v4i t4 = {p_tier(4 * h), p_tier(4 * h + 1), p_tier(4 * h + 2), p_tier(4 * h + 3)};
+                    __builtin_nontemporal_store(t4, (v4i *)((char *)q.tier + (uint32_t)p_i0 * 4u) + 64 * h);
+                }
             }
         } else {
 #pragma unroll
@@ -671,6 +693,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                 if (p_i0 + qoff(k) < q.n) {
                     q.out[p_i0 + qoff(k)] = p_val(k);
                     if (kClosest) q.closest[p_i0 + qoff(k)] = p_val(k);
+                    if (kSecond) q.tier[p_i0 + qoff(k)] = p_tier(k);
                 }
         }
     };
@@ -719,6 +742,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             p_base[k] = (rbase[k] >> ((step * ix.row_hi_bits) & 31u)) & row_hi_mask;
             p_grow[k] = *(const int32_t *)((const char *)ix.step_row + ((hit && !inl) ? (rec[k] + step) * 4u : 0u));
             p_inl[k] = inl;
+            if (kSecond) p_first[k] = cur.fr[k];
             // parked: a miss that the second body / the scan may still turn into a hit; in the
             // closest-variant mode also every final miss of a query inside the table
             df[k] = !hit && ((int32_t)y[k] < 0 || (kClosest && sl_of[k] != (uint32_t)tv.S));
@@ -812,6 +836,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             }
         }
         if (have && !final_miss) q.out[qi] = ans;
+        if (kSecond && have) q.tier[qi] = ans >= 0 ? 2 : 0;   // a parked query was left open by the first tier
         if (kClosest) {
             // the suggestion for the queries that ended with nothing feasible
             const bool open = have && ans < 0;
@@ -917,14 +942,14 @@ hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const Q
     if (lds_bytes > 0) {
         const uint32_t fixed = kLdsCtrlBytes + lds_header_bytes(tv.S);
         lds_bytes = fixed + ((lds_bytes - fixed) & ~15u);
-        auto kernel = q.closest ? k_index_select<true, true> : k_index_select<true, false>;
+        auto kernel = q.closest ? k_index_select<true, 1> : (q.tier ? k_index_select<true, 2> : k_index_select<true, 0>);
         hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes);
         if (e != hipSuccess) return e;
         return launch_kernel(ev, kernel, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), lds_bytes, st, tv, ix, q,
                              park_mem, lds_bytes - fixed);
     }
-    auto kernel = q.closest ? k_index_select<false, true> : k_index_select<false, false>;
+    auto kernel = q.closest ? k_index_select<false, 1> : (q.tier ? k_index_select<false, 2> : k_index_select<false, 0>);
     return launch_kernel(ev, kernel, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), kLdsCtrlBytes, st, tv, ix, q,
                          park_mem, 0u);
 }

@@ -130,6 +130,7 @@ struct QueryView {
     const int32_t *task, *slo, *min_acc, *bidx;
     int32_t *out;
     int32_t *closest;    // second result array of the closest-variant mode, else null
+    int32_t *tier;       // tier array of the second pass of the state-aware selection, else null
 };
 
 // A pair of events that a launcher attaches to its kernel's dispatch (the events then carry the
@@ -154,8 +155,6 @@ hipError_t launch_update_load(const TableView &tv, int32_t n, const int32_t *idx
 // State report: state of row idx[i] := val[i] (idx null: row i, all V rows), masks refreshed.
 hipError_t launch_update_state(const TableView &tv, int32_t n, const int32_t *idx,
                                const int32_t *val, uint32_t *index_ctrl, hipStream_t st, const LaunchEvents *ev = nullptr);
-// out[q] = first[q] >= 0 ? first[q] : second[q], tier[q] = 1 / 2 / 0; `tier` holds `second` on entry.
-hipError_t launch_tier_merge(int64_t n, int32_t *out, int32_t *tier, hipStream_t st, const LaunchEvents *ev = nullptr);
 hipError_t launch_histogram(const TableView &tv, const QueryView &q, const ScanScratch &sc,
                             hipStream_t st, const LaunchEvents *ev = nullptr);
 hipError_t launch_plan(const TableView &tv, const ScanScratch &sc, hipStream_t st, const LaunchEvents *ev = nullptr);

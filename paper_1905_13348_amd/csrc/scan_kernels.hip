@@ -134,15 +134,6 @@ __global__ __launch_bounds__(256) void k_update_state(TableView tv, int32_t n,
     tv.acc_r[g] = masked ? tv.acc_base : tv.acc[slot];
 }
 
-__global__ __launch_bounds__(256) void k_tier_merge(int64_t n, int32_t *__restrict__ out, int32_t *__restrict__ tier)
-{
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
-        const int32_t first = out[i], second = tier[i];
-        out[i] = first >= 0 ? first : second;
-        tier[i] = first >= 0 ? 1 : (second >= 0 ? 2 : 0);
-    }
-}
-
 // ---------------------------------------------------------------- bucketing
 
 template <bool kLds>
@@ -442,14 +433,6 @@ hipError_t launch_update_state(const TableView &tv, int32_t n, const int32_t *id
     if (n <= 0) return hipSuccess;
     const int64_t threads = (int64_t)n * tv.B;
     return launch_kernel(ev, k_update_state, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tv, n, idx, val, index_ctrl);
-}
-
-hipError_t launch_tier_merge(int64_t n, int32_t *out, int32_t *tier, hipStream_t st, const LaunchEvents *ev)
-{
-    if (n <= 0) return hipSuccess;
-    int64_t blocks = (n + 1023) / 1024;
-    if (blocks > 4096) blocks = 4096;
-    return launch_kernel(ev, k_tier_merge, dim3((unsigned)blocks), dim3(256), 0, st, n, out, tier);
 }
 
 hipError_t launch_histogram(const TableView &tv, const QueryView &q, const ScanScratch &sc,
