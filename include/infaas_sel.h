@@ -196,7 +196,10 @@ int infaas_sel_update_state(infaas_sel_t *h, int32_t n, const int32_t *d_variant
  * Decide N queries by the two-tier policy above.  Arrays as for infaas_sel_select, plus
  *   d_out_tier  [N]  DEVICE: 1 = the answer is an Active variant, 2 = an Inactive one,
  *                    0 = none (d_out_variant = -1)
- * Errors: INVALID_ARG, NOT_LOADED (no states loaded), HIP.
+ * Keeps 16 bytes of device memory per query of the largest call so far (at most 2^26 queries'
+ * worth; longer calls run in passes) for the queries the Active tier leaves open; it is
+ * allocated on the first call that needs more, or ahead of time by infaas_sel_reserve.
+ * Errors: INVALID_ARG, NOT_LOADED (no states loaded), HIP, OOM.
  */
 int infaas_sel_select_tiered(infaas_sel_t *h, int64_t N,
                              const int32_t *d_task, const int32_t *d_slo_us,
@@ -209,7 +212,8 @@ void infaas_sel_destroy(infaas_sel_t *h);
 /* ---- helpers around the five calls above -------------------------------------- */
 
 /* Pre-grow the scratch memory for calls of up to max_queries queries, so that
- * infaas_sel_select does not allocate.  Errors: INVALID_ARG, HIP, OOM. */
+ * infaas_sel_select (with states loaded: infaas_sel_select_tiered) does not allocate.
+ * Errors: INVALID_ARG, HIP, OOM. */
 int infaas_sel_reserve(infaas_sel_t *h, int64_t max_queries);
 
 /* Copy the current queue_us back to HOST memory [V], in the caller's row order, after

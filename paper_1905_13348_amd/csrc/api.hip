@@ -79,6 +79,9 @@ struct infaas_sel {
     std::vector<int32_t> h_task, h_acc, h_lat;   // host copies of the static columns, for building `inactive`
     int32_t *d_state = nullptr;                  // [Vp] state per slot (see TableView::state)
     infaas_sel *inactive = nullptr;
+    int32_t *d_open = nullptr;                   // lists of the queries the Active tier leaves open (grows)
+    int32_t *d_open_count = nullptr;             // [workgroups of the lookup kernel]
+    int64_t open_queries = 0, open_bytes = 0;    // pass size d_open is good for; its size
 
     // staircase index
     IndexView ix{};
@@ -144,6 +147,9 @@ struct infaas_sel {
 
 void infaas_sel::drop_inactive()
 {
+    (void)hipFree(d_open); (void)hipFree(d_open_count);
+    d_open = d_open_count = nullptr;
+    open_queries = open_bytes = 0;
     if (inactive) infaas_sel_destroy(inactive);
     inactive = nullptr;
 }
@@ -289,6 +295,24 @@ int create_index(infaas_sel *h)
     return INFAAS_SEL_OK;
 }
 
+// Lists for the queries that the first tier of a state-aware pass over up to n queries leaves open.
+int ensure_open(infaas_sel *h, int64_t n)
+{
+    if (h->d_open && h->open_queries >= n) return INFAAS_SEL_OK;
+    // growing: nothing enqueued earlier may still use the old lists
+    if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
+    (void)hipFree(h->d_open);
+    h->d_open = nullptr;
+    h->open_queries = h->open_bytes = 0;
+    const int blocks = index_select_blocks(h->num_cus);
+    const size_t words = (size_t)blocks * (size_t)index_open_cap((int32_t)n, h->num_cus) * 4;
+    if (!h->d_open_count && dev_alloc(&h->d_open_count, (size_t)blocks) != hipSuccess) return INFAAS_SEL_ERR_OOM;
+    if (dev_alloc(&h->d_open, words) != hipSuccess) return INFAAS_SEL_ERR_OOM;
+    h->open_queries = n;
+    h->open_bytes = (int64_t)words * 4;
+    return INFAAS_SEL_OK;
+}
+
 // One pass of the index engine over n <= 2^28 queries.
 int index_pass(infaas_sel *h, const QueryView &q, hipStream_t st)
 {
@@ -351,6 +375,8 @@ int scan_pass(infaas_sel *h, const QueryView &q, hipStream_t st)
 }
 
 constexpr int64_t kMaxPass = (int64_t)1 << 28;
+// State-aware selection: 16 bytes of list memory per query of a pass, hence shorter passes.
+constexpr int64_t kMaxTierPass = (int64_t)1 << 26;
 
 }  // namespace
 
@@ -704,6 +730,7 @@ int select_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t
         q.task = d_task + done; q.slo = d_slo_us + done; q.min_acc = d_min_acc_bp + done;
         q.bidx = d_batch_idx + done; q.out = d_out_variant + done;
         q.closest = closest ? d_out_closest + done : nullptr;
+        q.pass = closest ? 1 : 0;
         rc = idx ? index_pass(h, q, st) : scan_pass(h, q, st);
         if (rc != INFAAS_SEL_OK) return rc;
     }
@@ -731,16 +758,21 @@ int infaas_sel_select_tiered(infaas_sel_t *h, int64_t N, const int32_t *d_task, 
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     hipStream_t st = (hipStream_t)hip_stream;
-    // Active tier into the result array; the Inactive tier's lookup reads it back, fills in the
-    // queries it left open and writes the tier array.
-    for (int64_t done = 0; done < N; done += kMaxPass) {
+    int rc = ensure_open(h, std::min(N, kMaxTierPass));
+    if (rc != INFAAS_SEL_OK) return rc;
+    // The Active tier's lookup writes both result arrays and lists the valid queries it could not
+    // answer; the Inactive tier's lookup reads only those lists and fills in what it can answer.
+    for (int64_t done = 0; done < N; done += kMaxTierPass) {
         QueryView q{};
-        q.n = (int32_t)std::min(kMaxPass, N - done);
+        q.n = (int32_t)std::min(kMaxTierPass, N - done);
         q.task = d_task + done; q.slo = d_slo_us + done; q.min_acc = d_min_acc_bp + done;
-        q.bidx = d_batch_idx + done; q.out = d_out_variant + done;
-        int rc = index_pass(h, q, st);
+        q.bidx = d_batch_idx + done; q.out = d_out_variant + done; q.tier = d_out_tier + done;
+        q.open = h->d_open; q.open_count = h->d_open_count;
+        q.open_cap = index_open_cap(q.n, h->num_cus);
+        q.pass = 2;
+        rc = index_pass(h, q, st);
         if (rc != INFAAS_SEL_OK) return rc;
-        q.tier = d_out_tier + done;
+        q.pass = 3;
         rc = index_pass(h->inactive, q, st);
         if (rc != INFAAS_SEL_OK) return rc;
     }
@@ -775,6 +807,7 @@ int infaas_sel_reserve(infaas_sel_t *h, int64_t max_queries)
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     const int64_t cap = std::max<int64_t>(1, std::min(max_queries, kMaxPass));
+    if (h->loaded && h->inactive) return ensure_open(h, std::min(cap, kMaxTierPass));
     if (h->loaded && use_index(h)) return INFAAS_SEL_OK;   // the index engine needs no per-query scratch
     return ensure_scratch(h, cap);
 }
@@ -849,7 +882,7 @@ int infaas_sel_get_info(infaas_sel_t *h, infaas_sel_info *out)
     out->lds_segment_limit = h->lds_limit;
     out->wide_segments = h->wide_segments;
     out->table_bytes = h->table_bytes;
-    out->scratch_bytes = h->scratch_bytes + h->park_bytes;
+    out->scratch_bytes = h->scratch_bytes + h->park_bytes + h->open_bytes;
     if (h->have_index) {
         out->index_in_lds = h->index_lds_bytes > 0 ? 1 : 0;
         out->index_truncated = (int32_t)(h->ix_stats[kCtlTrunc] + h->ix_stats[kCtlNoBody]);

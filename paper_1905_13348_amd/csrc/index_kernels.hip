@@ -514,14 +514,19 @@ __device__ __forceinline__ int32_t closest_step(const Mem &mem, int nit, uint32_
     return second ? (int32_t)(kBodySteps + o1.step) : (int32_t)o0.step;
 }
 
-// kMode 0: selection.  1: selection plus closest-variant suggestion (q.closest).  2: second tier of
-// the state-aware selection: q.out holds the first tier's answers on entry; only the queries it
-// left at -1 are looked up, and q.tier is written (1 = first tier, 2 = this one, 0 = none).
+// kMode 0: selection.  1: selection plus closest-variant suggestion (q.closest).
+// 2 and 3: the two tiers of the state-aware selection.  2 is the selection over the first tier's
+// table; it also writes q.tier (1 = answered, 0 = not) and lists every valid query it leaves
+// unanswered, as a (query, latency bound, accuracy bound, slice) record, in its workgroup's part of
+// q.open (q.open_cap records each, as many as the workgroup has queries), the number of records in
+// q.open_count[workgroup].  3 takes the records of its workgroup's list instead of the query
+// arrays, looks them up in the second tier's table and writes q.out and q.tier (= 2) of those it
+// can answer; it must be launched with the same grid as the pass that wrote the lists.
 template <bool kLds, int kMode>
 __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, IndexView ix, QueryView q,
                                                               int32_t *__restrict__ park_mem, uint32_t lds_cap)
 {
-    constexpr bool kClosest = kMode == 1, kSecond = kMode == 2;
+    constexpr bool kClosest = kMode == 1, kFirst = kMode == 2, kSecond = kMode == 3;
     extern __shared__ __align__(16) uint32_t lds_w[];  // [16 B control][S + 1 headers][lds_cap bytes of bodies]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t nhdr = (uint32_t)tv.S + 1u;
@@ -540,21 +545,34 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     constexpr int kUnit = 64 * kPerThread;
     constexpr int kSpan = (kPerThread / 4 - 1) * 256 + 4;           // from a lane's first query to behind its last
     auto qoff = [](int k) -> int32_t { return (k >> 2) * 256 + (k & 3); };   // offset of query k of a lane
-    const int32_t nunits = (q.n + kUnit - 1) / kUnit;
-    const int32_t u_begin = (int32_t)(((int64_t)nunits * blockIdx.x) / gridDim.x);
-    const int32_t u_end = (int32_t)(((int64_t)nunits * (blockIdx.x + 1)) / gridDim.x);
+    // second tier: the units are blocks of 256 records of the workgroup's own list
+    const v4i *open_in = (const v4i *)q.open + (int64_t)blockIdx.x * q.open_cap;
+    v4i *open_out = (v4i *)q.open + (int64_t)blockIdx.x * q.open_cap;
+    const int32_t open_n = kSecond ? q.open_count[blockIdx.x] : 0;
+    const int32_t nunits = ((kSecond ? open_n : q.n) + kUnit - 1) / kUnit;
+    const int32_t u_begin = kSecond ? 0 : (int32_t)(((int64_t)nunits * blockIdx.x) / gridDim.x);
+    const int32_t u_end = kSecond ? nunits : (int32_t)(((int64_t)nunits * (blockIdx.x + 1)) / gridDim.x);
     // Query fields of one unit for this lane (unit < 0: nothing left; the fields then describe a
-    // query outside the table).
+    // query outside the table).  Second tier: tk holds the slice and bi the query's number (-1: no
+    // record).
     struct Fields {
         int32_t tk[kPerThread], sl[kPerThread], am[kPerThread], bi[kPerThread], unit;
-        int32_t fr[kPerThread];   // second tier only: the first tier's answer
     };
     auto load_unit = [&](Fields &f, int32_t unit) {
         f.unit = unit;
         const int32_t i0 = unit * kUnit + lane * 4;
         if (unit < 0) {
 #pragma unroll
-            for (int k = 0; k < kPerThread; ++k) { f.tk[k] = -1; f.sl[k] = 0; f.am[k] = 0; f.bi[k] = 0; f.fr[k] = -1; }
+            for (int k = 0; k < kPerThread; ++k) { f.tk[k] = kSecond ? tv.S : -1; f.sl[k] = 0; f.am[k] = 0; f.bi[k] = kSecond ? -1 : 0; }
+        } else if (kSecond) {
+#pragma unroll
+            for (int k = 0; k < kPerThread; ++k) {   // record k of a lane: 64 records behind record k - 1
+                const int32_t r = unit * kUnit + k * 64 + lane;
+                const v4i e = open_in[r < open_n ? r : 0];
+                f.bi[k] = r < open_n ? e.x : -1;
+                f.sl[k] = e.y; f.am[k] = e.z;
+                f.tk[k] = r < open_n ? e.w : tv.S;
+            }
         } else if (aligned && i0 + kSpan <= q.n) {
             const uint32_t off = (uint32_t)i0 * 4u;   // one 32-bit byte offset for all four arrays (n <= 2^28)
 #pragma unroll
@@ -567,10 +585,6 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                 f.sl[4 * h] = b.x; f.sl[4 * h + 1] = b.y; f.sl[4 * h + 2] = b.z; f.sl[4 * h + 3] = b.w;
                 f.am[4 * h] = c.x; f.am[4 * h + 1] = c.y; f.am[4 * h + 2] = c.z; f.am[4 * h + 3] = c.w;
                 f.bi[4 * h] = d.x; f.bi[4 * h + 1] = d.y; f.bi[4 * h + 2] = d.z; f.bi[4 * h + 3] = d.w;
-                if (kSecond) {
-                    const v4i e = __builtin_nontemporal_load((const v4i *)((const char *)q.out + off) + 64 * h);
-                    f.fr[4 * h] = e.x; f.fr[4 * h + 1] = e.y; f.fr[4 * h + 2] = e.z; f.fr[4 * h + 3] = e.w;
-                }
             }
         } else {
 #pragma unroll
@@ -581,12 +595,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                 f.sl[k] = in ? q.slo[i] : 0;
                 f.am[k] = in ? q.min_acc[i] : 0;
                 f.bi[k] = in ? q.bidx[i] : 0;
-                if (kSecond) f.fr[k] = in ? q.out[i] : -1;
             }
-        }
-        if (kSecond) {   // answered by the first tier: nothing to look up, like a query outside the table
-#pragma unroll
-            for (int k = 0; k < kPerThread; ++k) f.tk[k] = f.fr[k] >= 0 ? -1 : f.tk[k];
         }
     };
 
@@ -670,20 +679,22 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     int32_t p_lrow[kPerThread], p_grow[kPerThread], p_i0 = -1;
     uint32_t p_base[kPerThread];
     bool p_inl[kPerThread];
-    int32_t p_first[kPerThread];   // second tier only
-    auto p_own = [&](int k) -> int32_t { return p_inl[k] ? (int32_t)((p_base[k] << 16) | (uint32_t)p_lrow[k]) : p_grow[k]; };
-    auto p_val = [&](int k) -> int32_t { return kSecond && p_first[k] >= 0 ? p_first[k] : p_own(k); };
-    auto p_tier = [&](int k) -> int32_t { return p_first[k] >= 0 ? 1 : (p_own(k) >= 0 ? 2 : 0); };
+    int32_t p_qi[kPerThread];   // second tier only: where each result goes
+    auto p_val = [&](int k) -> int32_t { return p_inl[k] ? (int32_t)((p_base[k] << 16) | (uint32_t)p_lrow[k]) : p_grow[k]; };
     auto store_unit = [&]() {
         if (p_i0 < 0) return;
-        if (aligned && p_i0 + kSpan <= q.n) {
+        if (kSecond) {   // only the answers: the first tier has written "none" for all of the list
+#pragma unroll
+            for (int k = 0; k < kPerThread; ++k)
+                if (p_qi[k] >= 0 && p_val(k) >= 0) { q.out[p_qi[k]] = p_val(k); q.tier[p_qi[k]] = 2; }
+        } else if (aligned && p_i0 + kSpan <= q.n) {
 #pragma unroll
             for (int h = 0; h < kPerThread / 4; ++h) {
                 const v4i r = {p_val(4 * h), p_val(4 * h + 1), p_val(4 * h + 2), p_val(4 * h + 3)};
                 __builtin_nontemporal_store(r, (v4i *)((char *)q.out + (uint32_t)p_i0 * 4u) + 64 * h);
                 if (kClosest) __builtin_nontemporal_store(r, (v4i *)((char *)q.closest + (uint32_t)p_i0 * 4u) + 64 * h);
-                if (kSecond) {
-                    const v4i t4 = {p_tier(4 * h), p_tier(4 * h + 1), p_tier(4 * h + 2), p_tier(4 * h + 3)};
+                if (kFirst) {
+                    const v4i t4 = {r.x >= 0, r.y >= 0, r.z >= 0, r.w >= 0};
                     __builtin_nontemporal_store(t4, (v4i *)((char *)q.tier + (uint32_t)p_i0 * 4u) + 64 * h);
                 }
             }
@@ -693,13 +704,20 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                 if (p_i0 + qoff(k) < q.n) {
                     q.out[p_i0 + qoff(k)] = p_val(k);
                     if (kClosest) q.closest[p_i0 + qoff(k)] = p_val(k);
-                    if (kSecond) q.tier[p_i0 + qoff(k)] = p_tier(k);
+                    if (kFirst) q.tier[p_i0 + qoff(k)] = p_val(k) >= 0;
                 }
         }
     };
     // One pipeline stage: search the unit in `cur`, then request the unit after the next into it.
+    uint32_t &s_open = lds_w[3];   // first tier: records in the workgroup's list so far
+    // Room for `count` (wave-uniform, > 0) more records in the workgroup's list: one LDS atomic.
+    auto open_room = [&](uint32_t count) -> uint32_t {
+        uint32_t at = 0;
+        if (lane == 0) at = atomicAdd(&s_open, count);
+        return (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+    };
     auto stage = [&](Fields &cur) {
-        const int32_t i0 = cur.unit * kUnit + lane * 4;
+        const int32_t i0 = kSecond ? 0 : cur.unit * kUnit + lane * 4;
         store_unit();                                   // results of the previous unit
         // slice header; queries outside the table use the header of the empty slice (entry S)
         uint32_t body[kPerThread], y[kPerThread], rec[kPerThread], keys[kPerThread], dd[kPerThread],
@@ -709,7 +727,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             const uint32_t inside = ((uint32_t)cur.tk[k] < (uint32_t)tv.T) & ((uint32_t)cur.bi[k] < (uint32_t)tv.B);
             const uint32_t ok = inside & (uint32_t)(cur.sl[k] >= 0);   // a negative bound admits nothing
             const uint32_t own = __umul24((uint32_t)cur.tk[k], (uint32_t)tv.B) + (uint32_t)cur.bi[k];
-            const uint32_t s = ok ? own : (uint32_t)tv.S;
+            const uint32_t s = kSecond ? (uint32_t)cur.tk[k] : (ok ? own : (uint32_t)tv.S);
             sl_of[k] = kClosest ? (inside ? own : (uint32_t)tv.S) : s;   // the slice a parked record names
             if (kLds) {
                 const v2u h = lmem.ld64(lds_hdr0 + s * kLdsHdrBytes);
@@ -742,7 +760,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             p_base[k] = (rbase[k] >> ((step * ix.row_hi_bits) & 31u)) & row_hi_mask;
             p_grow[k] = *(const int32_t *)((const char *)ix.step_row + ((hit && !inl) ? (rec[k] + step) * 4u : 0u));
             p_inl[k] = inl;
-            if (kSecond) p_first[k] = cur.fr[k];
+            if (kSecond) p_qi[k] = cur.bi[k];
             // parked: a miss that the second body / the scan may still turn into a hit; in the
             // closest-variant mode also every final miss of a query inside the table
             df[k] = !hit && ((int32_t)y[k] < 0 || (kClosest && sl_of[k] != (uint32_t)tv.S));
@@ -753,8 +771,26 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         for (int k = 0; k < kPerThread; ++k) {
             const uint64_t mask = __ballot(df[k]);
             if (mask) {   // parked queries are always inside the table
-                if (df[k]) wq[cnt + lanes_below(mask)] = v4i{i0 + qoff(k), cur.sl[k], cur.am[k], (int32_t)sl_of[k]};
+                if (df[k]) wq[cnt + lanes_below(mask)] = v4i{kSecond ? cur.bi[k] : i0 + qoff(k), cur.sl[k], cur.am[k], (int32_t)sl_of[k]};
                 cnt += (uint32_t)__builtin_popcountll(mask);
+            }
+        }
+        if (kFirst) {   // valid queries that end here without an answer go to the second tier
+            uint64_t om[kPerThread];
+            uint32_t total = 0;
+#pragma unroll
+            for (int k = 0; k < kPerThread; ++k) {
+                om[k] = __ballot(m[k] == 0u && !df[k] && sl_of[k] != (uint32_t)tv.S);
+                total += (uint32_t)__builtin_popcountll(om[k]);
+            }
+            if (total) {
+                uint32_t at = open_room(total);
+#pragma unroll
+                for (int k = 0; k < kPerThread; ++k) {
+                    if ((om[k] >> lane) & 1u)
+                        open_out[at + lanes_below(om[k])] = v4i{i0 + qoff(k), cur.sl[k], cur.am[k], (int32_t)sl_of[k]};
+                    at += (uint32_t)__builtin_popcountll(om[k]);
+                }
             }
         }
         load_unit(cur, next_unit());
@@ -835,8 +871,19 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                 if (lane == l) ans = found >= 0 ? tv.orig_r[col + found] : -1;
             }
         }
-        if (have && !final_miss) q.out[qi] = ans;
-        if (kSecond && have) q.tier[qi] = ans >= 0 ? 2 : 0;   // a parked query was left open by the first tier
+        if (kSecond) {
+            if (have && ans >= 0) { q.out[qi] = ans; q.tier[qi] = 2; }
+        } else if (have && !final_miss) {
+            q.out[qi] = ans;
+        }
+        if (kFirst) {   // the main loop has stored tier 0 for a parked query
+            if (have && ans >= 0) q.tier[qi] = 1;
+            const uint64_t om = __ballot(have && ans < 0);
+            if (om) {
+                const uint32_t at = open_room((uint32_t)__builtin_popcountll(om));
+                if (have && ans < 0) open_out[at + lanes_below(om)] = v4i{qi, slo, min_acc, (int32_t)s};
+            }
+        }
         if (kClosest) {
             // the suggestion for the queries that ended with nothing feasible
             const bool open = have && ans < 0;
@@ -916,6 +963,10 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             }
         }
     }
+    if (kFirst) {
+        __syncthreads();
+        if (tid == 0) q.open_count[blockIdx.x] = (int32_t)s_open;
+    }
 }
 
 }  // namespace
@@ -930,6 +981,15 @@ hipError_t launch_index_build(const TableView &tv, const IndexView &ix, hipStrea
 
 int index_select_blocks(int num_cus) { return num_cus; }
 
+// Records per workgroup of the lists a first-tier pass over n queries may write: every query of
+// the workgroup's share of the units.
+int32_t index_open_cap(int32_t n, int num_cus)
+{
+    const int64_t unit = 64 * kPerThread, blocks = index_select_blocks(num_cus);
+    const int64_t nunits = (n + unit - 1) / unit;
+    return (int32_t)(((nunits + blocks - 1) / blocks) * unit);
+}
+
 size_t index_park_bytes(int num_cus)
 {
     return (size_t)index_select_blocks(num_cus) * (kSelThreads / 64) * kWaveQueue * sizeof(v4i);
@@ -942,14 +1002,16 @@ hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const Q
     if (lds_bytes > 0) {
         const uint32_t fixed = kLdsCtrlBytes + lds_header_bytes(tv.S);
         lds_bytes = fixed + ((lds_bytes - fixed) & ~15u);
-        auto kernel = q.closest ? k_index_select<true, 1> : (q.tier ? k_index_select<true, 2> : k_index_select<true, 0>);
+        auto kernel = q.pass == 1 ? k_index_select<true, 1> : q.pass == 2 ? k_index_select<true, 2> :
+                      q.pass == 3 ? k_index_select<true, 3> : k_index_select<true, 0>;
         hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes);
         if (e != hipSuccess) return e;
         return launch_kernel(ev, kernel, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), lds_bytes, st, tv, ix, q,
                              park_mem, lds_bytes - fixed);
     }
-    auto kernel = q.closest ? k_index_select<false, 1> : (q.tier ? k_index_select<false, 2> : k_index_select<false, 0>);
+    auto kernel = q.pass == 1 ? k_index_select<false, 1> : q.pass == 2 ? k_index_select<false, 2> :
+                  q.pass == 3 ? k_index_select<false, 3> : k_index_select<false, 0>;
     return launch_kernel(ev, kernel, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), kLdsCtrlBytes, st, tv, ix, q,
                          park_mem, 0u);
 }

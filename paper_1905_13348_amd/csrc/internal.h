@@ -130,7 +130,12 @@ struct QueryView {
     const int32_t *task, *slo, *min_acc, *bidx;
     int32_t *out;
     int32_t *closest;    // second result array of the closest-variant mode, else null
-    int32_t *tier;       // tier array of the second pass of the state-aware selection, else null
+    int32_t *tier;       // tier array of the state-aware selection, else null
+    // state-aware selection: the lists of queries the first tier leaves open, one per workgroup of
+    // the lookup kernel (open_cap records of 16 bytes each), and the number of records in each
+    int32_t *open, *open_count;
+    int32_t open_cap;
+    int32_t pass;        // 0 selection, 1 with closest-variant suggestion, 2 first tier, 3 second tier
 };
 
 // A pair of events that a launcher attaches to its kernel's dispatch (the events then carry the
@@ -175,6 +180,7 @@ hipError_t launch_index_build(const TableView &tv, const IndexView &ix, hipStrea
 hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const QueryView &q,
                                int32_t *park_mem, uint32_t lds_bytes, int num_cus, hipStream_t st, const LaunchEvents *ev = nullptr);
 int index_select_blocks(int num_cus);
+int32_t index_open_cap(int32_t n, int num_cus);   // records per workgroup of QueryView::open for a pass over n queries
 size_t index_park_bytes(int num_cus);
 
 }  // namespace infaas

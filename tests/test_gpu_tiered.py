@@ -126,6 +126,41 @@ def test_tiered_config2_sampled(oracle_lib):
     sel.destroy()
 
 
+def test_tiered_more_queries_than_one_pass(oracle_lib):
+    """2^26 + 5000 queries in one call (the state-aware call works in passes of 2^26), on a table
+    where most queries reach the second tier: the seam, both ends and a random sample against the
+    oracle; every element written; answer and tier consistent everywhere."""
+    import torch
+    tb = workloads.make_table(0)
+    rng = np.random.default_rng(26)
+    state = rng.choice(4, size=tb.V, p=(0.7, 0.1, 0.1, 0.1)).astype(np.int32)
+    load = rng.integers(100, 100_000, tb.V).astype(np.int32)
+    sel = make_selector(tb, engine=0)
+    sel.load_states(state, load)
+    n = (1 << 26) + 5000
+    g = torch.Generator(device="cuda"); g.manual_seed(26)
+    task = torch.randint(-1, tb.num_tasks + 1, (n,), generator=g, device="cuda", dtype=torch.int32)
+    slo = torch.randint(-1000, 400_000, (n,), generator=g, device="cuda", dtype=torch.int32)
+    acc = torch.randint(5000, 9501, (n,), generator=g, device="cuda", dtype=torch.int32)
+    bidx = torch.randint(0, tb.B, (n,), generator=g, device="cuda", dtype=torch.int32)
+    out = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    tier = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    seam = 1 << 26
+    pick = np.unique(np.concatenate([np.arange(2000), seam - 2000 + np.arange(4000), n - 2000 + np.arange(2000),
+                                     np.random.default_rng(1).integers(0, n, 100_000)]))
+    pick_d = torch.from_numpy(pick).cuda()
+    qs = tuple(x[pick_d].cpu().numpy() for x in (task, slo, acc, bidx))
+    want, want_tier = oracle_lib.select_tiered(*table_args(tb), state, load, *qs)
+    print(f"tiered case two passes: N={n}, tiers of the sample {np.bincount(want_tier, minlength=3)}", flush=True)
+    sel.select_tiered(task, slo, acc, bidx, out, tier)
+    torch.cuda.synchronize()
+    assert np.array_equal(out[pick_d].cpu().numpy(), want)
+    assert np.array_equal(tier[pick_d].cpu().numpy(), want_tier)
+    assert int((out == -7).sum()) == 0 and int((tier == -7).sum()) == 0, "some results were never written"
+    assert bool(((out >= 0) == (tier > 0)).all())
+    sel.destroy()
+
+
 def test_tiered_errors():
     import paper_1905_13348_amd as lib
     import torch
