@@ -60,6 +60,15 @@ class Oracle:
             fn = getattr(lib, name)
             fn.argtypes = [ctypes.c_int64, ctypes.c_int32] + [_I32P] * 7 + [ctypes.c_int64] + [_I32P] * 6
             fn.restype = ctypes.c_int
+        for name in ("oracle_select_workers", "oracle_select_workers_literal"):
+            fn = getattr(lib, name)
+            fn.argtypes = ([ctypes.c_int64, ctypes.c_int32] + [_I32P] * 8 + [ctypes.c_int64, _I32P, _I32P]
+                           + [ctypes.c_int64, _I32P, _I32P, _I32P] + [ctypes.c_int64] + [_I32P] * 7)
+            fn.restype = ctypes.c_int
+        for name in ("oracle_update_worker_util", "oracle_update_instance_load"):
+            fn = getattr(lib, name)
+            fn.argtypes = [ctypes.c_int64, _I32P, ctypes.c_int64, _I32P, _I32P]
+            fn.restype = None
         lib.oracle_update_state.argtypes = [ctypes.c_int64, _I32P, ctypes.c_int64, _I32P, _I32P]
         lib.oracle_update_state.restype = None
         lib.oracle_count_feasible.argtypes = [ctypes.c_int64, ctypes.c_int32, _I32P, _I32P, _I32P,
@@ -150,6 +159,47 @@ class Oracle:
         if rc != 0:
             raise ValueError("oracle rejected its arguments")
         return out, tier
+
+    def select_workers(self, task_id, acc_bp, lat_us, cost, queue_us, state, load_us, variant_hw,
+                       worker_hw, worker_util, inst_variant, inst_worker, inst_load,
+                       q_task, q_slo, q_min_acc, q_bidx, literal=False):
+        """(variant or -1, tier, worker or -1) per query: the state-aware selection followed by
+        the choice of the worker."""
+        task_id, acc_bp, queue_us = _i32(task_id), _i32(acc_bp), _i32(queue_us)
+        lat_us, cost, state, load_us = _i32(lat_us), _i32(cost), _i32(state), _i32(load_us)
+        variant_hw, worker_hw, worker_util = _i32(variant_hw), _i32(worker_hw), _i32(worker_util)
+        inst_variant, inst_worker, inst_load = _i32(inst_variant), _i32(inst_worker), _i32(inst_load)
+        V, B = lat_us.shape
+        assert cost.shape == lat_us.shape
+        for a in (task_id, acc_bp, queue_us, state, load_us, variant_hw):
+            assert a.shape == (V,)
+        W, n_inst = worker_hw.shape[0], inst_variant.shape[0]
+        assert worker_util.shape == (W,) and inst_worker.shape == (n_inst,) and inst_load.shape == (n_inst,)
+        q_task, q_slo, q_min_acc, q_bidx = _i32(q_task), _i32(q_slo), _i32(q_min_acc), _i32(q_bidx)
+        N = q_task.shape[0]
+        out, tier, worker = (np.empty(N, dtype=np.int32) for _ in range(3))
+        fn = self._lib.oracle_select_workers_literal if literal else self._lib.oracle_select_workers
+        rc = fn(V, B, _ptr(task_id), _ptr(acc_bp), _ptr(lat_us), _ptr(cost), _ptr(queue_us), _ptr(state),
+                _ptr(load_us), _ptr(variant_hw), W, _ptr(worker_hw), _ptr(worker_util),
+                n_inst, _ptr(inst_variant), _ptr(inst_worker), _ptr(inst_load),
+                N, _ptr(q_task), _ptr(q_slo), _ptr(q_min_acc), _ptr(q_bidx), _ptr(out), _ptr(tier), _ptr(worker))
+        if rc != 0:
+            raise ValueError("oracle rejected its arguments")
+        return out, tier, worker
+
+    def update_worker_util(self, worker_util: np.ndarray, worker_idx, new_util) -> None:
+        """In place: worker_util[worker_idx[i]] = new_util[i], array order, invalid entries skipped."""
+        assert worker_util.dtype == np.int32 and worker_util.flags["C_CONTIGUOUS"]
+        worker_idx, new_util = _i32(worker_idx), _i32(new_util)
+        self._lib.oracle_update_worker_util(worker_util.shape[0], _ptr(worker_util), worker_idx.shape[0],
+                                            _ptr(worker_idx), _ptr(new_util))
+
+    def update_instance_load(self, inst_load: np.ndarray, inst_idx, new_load) -> None:
+        """In place: inst_load[inst_idx[i]] = new_load[i], array order, invalid entries skipped."""
+        assert inst_load.dtype == np.int32 and inst_load.flags["C_CONTIGUOUS"]
+        inst_idx, new_load = _i32(inst_idx), _i32(new_load)
+        self._lib.oracle_update_instance_load(inst_load.shape[0], _ptr(inst_load), inst_idx.shape[0],
+                                              _ptr(inst_idx), _ptr(new_load))
 
     def update_state(self, state: np.ndarray, variant_idx, new_state) -> None:
         """In place: state[variant_idx[i]] = new_state[i], array order."""

@@ -48,7 +48,10 @@
  * state-aware selection at the end follows Sections 4 and 4.1 with the readings
  * listed there; it is pinned by a numpy enumerator, by two special cases that
  * reduce to the plain selection (all variants Active; all Inactive), by hand-built
- * policy cases and by twelve mutants.
+ * policy cases and by twelve mutants.  The worker selection behind it (the second
+ * output of Case I) is pinned by a numpy enumerator, by hand-built cases (one
+ * instance, one hardware class, ties, no instance, no worker of the hardware),
+ * by invariance under reordering of the instance list and by its own mutants.
  * The only statement that stays
  * "parity unpinned" is the count of valid options printed in Table 7, because
  * the profiles behind it are not published.
@@ -507,6 +510,178 @@ void oracle_update_state(int64_t V, int32_t *state, int64_t n,
         if (v < 0 || v >= V || new_state[i] < 0 || new_state[i] > 3)
             continue;
         state[v] = new_state[i];
+    }
+}
+
+/*
+ * Worker selection (Section 4.1, Case I: the output of the policy is the variant AND the worker
+ * that serves the query; Section 6.4 counts it as the second decision on the critical path).
+ *
+ *   The selected variant is Active   -> the query goes to the least-loaded worker that runs an
+ *                                       instance of the variant;
+ *   the selected variant is Inactive -> the query goes to the worker with the lowest utilisation
+ *                                       among the workers that have the variant's target hardware;
+ *   no variant                       -> no worker (-1).
+ *
+ * A running instance is a {variant, worker} pair (Section 5) with a load figure of its own.
+ * Readings where the text is silent: "least loaded" compares the instances' load figures and, among
+ * equal ones, takes the lower worker number; equal utilisations likewise go to the lower worker
+ * number; an Active variant without any instance, or an Inactive one whose hardware no worker
+ * has, gets worker -1 while the variant and tier stand; reports of utilisation or instance load
+ * are applied in array order and skip entries with an index outside the table or a negative
+ * value.
+ */
+static int32_t least_loaded_worker(int64_t n_inst, const int32_t *inst_variant,
+                                   const int32_t *inst_worker, const int32_t *inst_load,
+                                   const int64_t *list, int64_t n_list, int32_t variant)
+{
+    /* list == NULL: look at every instance; else only at the n_list instances listed */
+    int64_t best = -1;
+    int64_t count = list ? n_list : n_inst;
+    for (int64_t j = 0; j < count; ++j) {
+        int64_t i = list ? list[j] : j;
+        if (inst_variant[i] != variant)
+            continue;
+        if (best < 0 || inst_load[i] < inst_load[best] ||
+            (inst_load[i] == inst_load[best] && inst_worker[i] < inst_worker[best]))
+            best = i;
+    }
+    return best >= 0 ? inst_worker[best] : -1;
+}
+
+static int32_t least_utilised_worker(int64_t W, const int32_t *worker_hw,
+                                     const int32_t *worker_util, int32_t hw)
+{
+    int64_t best = -1;
+    for (int64_t w = 0; w < W; ++w) {
+        if (worker_hw[w] != hw)
+            continue;
+        if (best < 0 || worker_util[w] < worker_util[best])
+            best = w;   /* equal utilisation: the earlier (lower) worker stays */
+    }
+    return (int32_t)best;
+}
+
+static int workers_args_ok(int64_t V, int64_t W, int64_t n_inst, const int32_t *inst_variant,
+                           const int32_t *inst_worker)
+{
+    if (W < 0 || n_inst < 0)
+        return 0;
+    for (int64_t i = 0; i < n_inst; ++i)
+        if (inst_variant[i] < 0 || inst_variant[i] >= V || inst_worker[i] < 0 || inst_worker[i] >= W)
+            return 0;
+    return 1;
+}
+
+/* Literal form: state-aware selection by the literal routine, then every instance / every worker
+ * is looked at for every query. */
+int oracle_select_workers_literal(int64_t V, int32_t B,
+                                  const int32_t *task_id, const int32_t *acc_bp,
+                                  const int32_t *lat_us, const int32_t *cost, const int32_t *queue_us,
+                                  const int32_t *state, const int32_t *load_us,
+                                  const int32_t *variant_hw,
+                                  int64_t W, const int32_t *worker_hw, const int32_t *worker_util,
+                                  int64_t n_inst, const int32_t *inst_variant,
+                                  const int32_t *inst_worker, const int32_t *inst_load,
+                                  int64_t N,
+                                  const int32_t *q_task, const int32_t *q_slo_us,
+                                  const int32_t *q_min_acc_bp, const int32_t *q_batch_idx,
+                                  int32_t *out_variant, int32_t *out_tier, int32_t *out_worker)
+{
+    if (!workers_args_ok(V, W, n_inst, inst_variant, inst_worker))
+        return -1;
+    int rc = oracle_select_tiered_literal(V, B, task_id, acc_bp, lat_us, cost, queue_us, state, load_us,
+                                          N, q_task, q_slo_us, q_min_acc_bp, q_batch_idx,
+                                          out_variant, out_tier);
+    if (rc != 0)
+        return rc;
+    for (int64_t q = 0; q < N; ++q) {
+        if (out_tier[q] == 1)
+            out_worker[q] = least_loaded_worker(n_inst, inst_variant, inst_worker, inst_load,
+                                                NULL, 0, out_variant[q]);
+        else if (out_tier[q] == 2)
+            out_worker[q] = least_utilised_worker(W, worker_hw, worker_util,
+                                                  variant_hw[out_variant[q]]);
+        else
+            out_worker[q] = -1;
+    }
+    return 0;
+}
+
+/* Grouped form: the instances are listed per variant once (as the rows are per task); each query
+ * still walks the whole list of its variant, or all workers.  Queries on several host threads. */
+int oracle_select_workers(int64_t V, int32_t B,
+                          const int32_t *task_id, const int32_t *acc_bp,
+                          const int32_t *lat_us, const int32_t *cost, const int32_t *queue_us,
+                          const int32_t *state, const int32_t *load_us,
+                          const int32_t *variant_hw,
+                          int64_t W, const int32_t *worker_hw, const int32_t *worker_util,
+                          int64_t n_inst, const int32_t *inst_variant,
+                          const int32_t *inst_worker, const int32_t *inst_load,
+                          int64_t N,
+                          const int32_t *q_task, const int32_t *q_slo_us,
+                          const int32_t *q_min_acc_bp, const int32_t *q_batch_idx,
+                          int32_t *out_variant, int32_t *out_tier, int32_t *out_worker)
+{
+    if (!workers_args_ok(V, W, n_inst, inst_variant, inst_worker))
+        return -1;
+    int rc = oracle_select_tiered(V, B, task_id, acc_bp, lat_us, cost, queue_us, state, load_us,
+                                  N, q_task, q_slo_us, q_min_acc_bp, q_batch_idx,
+                                  out_variant, out_tier);
+    if (rc != 0)
+        return rc;
+    int64_t *first = (int64_t *)calloc((size_t)V + 1, sizeof(int64_t));
+    int64_t *fill = (int64_t *)calloc((size_t)V + 1, sizeof(int64_t));
+    int64_t *list = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n_inst > 0 ? n_inst : 1));
+    if (!first || !fill || !list) {
+        free(first); free(fill); free(list);
+        return -1;
+    }
+    for (int64_t i = 0; i < n_inst; ++i)
+        first[inst_variant[i] + 1] += 1;
+    for (int64_t v = 0; v < V; ++v)
+        first[v + 1] += first[v];
+    for (int64_t i = 0; i < n_inst; ++i) {
+        int64_t v = inst_variant[i];
+        list[first[v] + fill[v]] = i;
+        fill[v] += 1;
+    }
+#pragma omp parallel for schedule(dynamic, 4096)
+    for (int64_t q = 0; q < N; ++q) {
+        int32_t v = out_variant[q];
+        if (out_tier[q] == 1)
+            out_worker[q] = least_loaded_worker(n_inst, inst_variant, inst_worker, inst_load,
+                                                list + first[v], first[v + 1] - first[v], v);
+        else if (out_tier[q] == 2)
+            out_worker[q] = least_utilised_worker(W, worker_hw, worker_util, variant_hw[v]);
+        else
+            out_worker[q] = -1;
+    }
+    free(first); free(fill); free(list);
+    return 0;
+}
+
+/* Utilisation report: worker_util[idx[i]] = value[i], array order, invalid entries skipped. */
+void oracle_update_worker_util(int64_t W, int32_t *worker_util, int64_t n,
+                               const int32_t *worker_idx, const int32_t *new_util)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t w = worker_idx[i];
+        if (w < 0 || w >= W || new_util[i] < 0)
+            continue;
+        worker_util[w] = new_util[i];
+    }
+}
+
+/* Instance load report: inst_load[idx[i]] = value[i], array order, invalid entries skipped. */
+void oracle_update_instance_load(int64_t n_inst, int32_t *inst_load, int64_t n,
+                                 const int32_t *inst_idx, const int32_t *new_load)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t j = inst_idx[i];
+        if (j < 0 || j >= n_inst || new_load[i] < 0)
+            continue;
+        inst_load[j] = new_load[i];
     }
 }
 

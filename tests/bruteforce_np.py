@@ -138,3 +138,28 @@ def tiered_np(task_id, acc_bp, lat_us, cost, queue_us, state, load_us, q_task, q
             out[q] = ina[np.lexsort((ina, lat_us[ina, b], load_us[ina] + lat_us[ina, b]))[0]]
             tier[q] = 2
     return out, tier
+
+
+def workers_np(variant, tier, variant_hw, worker_hw, worker_util, inst_variant, inst_worker, inst_load):
+    """Worker for every (variant, tier) decision: tier 1 -> the worker of the variant's instance
+    with the smallest (load, worker); tier 2 -> the worker of the variant's hardware class with the
+    smallest (utilisation, worker); otherwise, or when there is no candidate, -1."""
+    variant_hw = np.asarray(variant_hw, dtype=np.int64)
+    worker_hw = np.asarray(worker_hw, dtype=np.int64)
+    worker_util = np.asarray(worker_util, dtype=np.int64)
+    inst_variant = np.asarray(inst_variant, dtype=np.int64)
+    inst_worker = np.asarray(inst_worker, dtype=np.int64)
+    inst_load = np.asarray(inst_load, dtype=np.int64)
+    ids = np.arange(worker_hw.size, dtype=np.int64)
+    out = np.full(len(variant), -1, dtype=np.int32)
+    for q in range(len(variant)):
+        v = int(variant[q])
+        if tier[q] == 1:
+            mine = np.flatnonzero(inst_variant == v)
+            if mine.size:
+                out[q] = inst_worker[mine[np.lexsort((inst_worker[mine], inst_load[mine]))[0]]]
+        elif tier[q] == 2:
+            cand = ids[worker_hw == variant_hw[v]]
+            if cand.size:
+                out[q] = cand[np.lexsort((cand, worker_util[cand]))[0]]
+    return out

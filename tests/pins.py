@@ -9,7 +9,7 @@ import os
 import numpy as np
 
 import workloads
-from bruteforce_np import closest_key_np, closest_np, count_np, select_np, tiered_np
+from bruteforce_np import closest_key_np, closest_np, count_np, select_np, tiered_np, workers_np
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 I32MAX = 2**31 - 1
@@ -488,4 +488,138 @@ TIERED_PINS = [
     pin_tiered_reduces_to_plain,
     pin_tiered_policy,
     pin_update_state,
+]
+
+
+# ---- worker selection (Section 4.1: the second output of Case I) ----------------------------------
+
+def _both_workers(o, *args):
+    a = o.select_workers(*args)
+    b = o.select_workers(*args, literal=True)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y), "grouped and literal oracle disagree"
+    return a
+
+
+def _tiny_cluster(rng, V, span):
+    W = int(rng.integers(1, 12)); H = int(rng.integers(1, 4)); I = int(rng.integers(0, 4 * V + 1))
+    variant_hw = rng.integers(0, H + 1, V).astype(np.int32)      # class H: no worker has it
+    worker_hw = rng.integers(0, H, W).astype(np.int32)
+    worker_util = rng.integers(0, span, W).astype(np.int32)
+    inst_variant = rng.integers(0, V, I).astype(np.int32)
+    inst_worker = rng.integers(0, W, I).astype(np.int32)
+    inst_load = rng.integers(0, span, I).astype(np.int32)
+    return variant_hw, worker_hw, worker_util, inst_variant, inst_worker, inst_load
+
+
+def pin_workers_numpy(o):
+    """Tiny tables and clusters with ties everywhere against the numpy enumerators; variant and tier
+    must be those of the state-aware selection."""
+    rng = np.random.default_rng(17)
+    for trial in range(40):
+        V = int(rng.integers(1, 49)); T = int(rng.integers(1, 5)); B = int(rng.integers(1, 4))
+        span = int(rng.choice([2, 3, 5, 50]))
+        tab, qry = _tiny_random(rng, V, T, B, 300, span)
+        state = rng.integers(0, 4, V).astype(np.int32)
+        load = rng.integers(0, span, V).astype(np.int32)
+        cl = _tiny_cluster(rng, V, span)
+        got = _both_workers(o, *tab, state, load, *cl, *qry)
+        want = tiered_np(*tab, state, load, *qry)
+        assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1]), f"trial {trial}"
+        assert np.array_equal(got[2], workers_np(want[0], want[1], *cl)), f"trial {trial}"
+
+
+def pin_workers_policy(o):
+    """Hand-built cases on one task with an Active row 0 (hardware 0), an Inactive row 1 (hardware
+    1) and an Inactive row 2 (hardware 2, which no worker has)."""
+    task = np.zeros(3, np.int32); acc = np.array([8000, 9000, 9500], np.int32)
+    lat = np.array([[10], [10], [10]], np.int32); cost = np.array([[1], [1], [1]], np.int32)
+    queue = np.zeros(3, np.int32); load = np.zeros(3, np.int32)
+    state = np.array([1, 0, 0], np.int32)
+    vhw = np.array([0, 1, 2], np.int32)
+    whw = np.array([0, 0, 1, 1, 0, 1], np.int32)
+    util = np.array([50, 10, 70, 30, 10, 30], np.int32)
+
+    def run(min_acc, iv, iw, il, state=state, util=util, slo=1000):
+        r = _both_workers(o, task, acc, lat, cost, queue, state, load, vhw, whw, util,
+                          np.array(iv, np.int32), np.array(iw, np.int32), np.array(il, np.int32),
+                          [0], [slo], [min_acc], [0])
+        return tuple(int(x[0]) for x in r)
+
+    inst = ([0, 0, 0], [0, 1, 4], [5, 3, 9])
+    assert run(8000, *inst) == (0, 1, 1)                    # Active: instance load 3 on worker 1 is the least
+    assert run(8000, [0], [4], [999]) == (0, 1, 4)          # a single instance: its worker, whatever its load
+    assert run(8000, [0, 0, 0], [4, 0, 1], [3, 3, 3]) == (0, 1, 0)    # equal loads: the lowest worker number
+    assert run(8000, [0, 0, 0], [1, 0, 4], [3, 3, 2]) == (0, 1, 4)    # ...but load comes first
+    assert run(8000, [0, 0], [0, 1], [7, 2], util=np.array([0, 9999, 0, 0, 0, 0], np.int32)) == (0, 1, 1)  # utilisation is not looked at for an Active variant
+    assert run(8000, [1, 2, 1], [0, 1, 4], [0, 0, 0]) == (0, 1, -1)   # instances of other variants only: no worker
+    assert run(8000, [], [], []) == (0, 1, -1)
+    # Inactive row 1 (hardware 1: workers 2, 3, 5 with utilisation 70, 30, 30): worker 3; instances do not matter
+    assert run(8500, *inst) == (1, 2, 3)
+    assert run(8500, [1, 1], [2, 5], [0, 0]) == (1, 2, 3)
+    assert run(8500, *inst, util=np.array([0, 0, 20, 30, 0, 30], np.int32)) == (1, 2, 2)
+    assert run(8500, *inst, util=np.array([0, 0, 31, 31, 0, 30], np.int32)) == (1, 2, 5)
+    assert run(9200, *inst) == (2, 2, -1)                   # hardware 2: nobody has it; variant and tier stand
+    assert run(9600, *inst) == (-1, 0, -1)
+    assert run(8000, *inst, slo=5) == (-1, 0, -1)
+    # instance arguments outside the tables are rejected
+    for bad in (([3], [0], [0]), ([0], [6], [0]), ([-1], [0], [0]), ([0], [-1], [0])):
+        try:
+            run(8000, *bad)
+        except ValueError:
+            continue
+        raise AssertionError("instance outside the tables accepted")
+
+
+def pin_workers_structure(o):
+    """Config 0 with its seeded cluster: the worker depends on (variant, tier) only; an Active
+    answer's worker runs an instance of it and no instance of it has a smaller (load, worker); an
+    Inactive answer's worker has the variant's hardware and no such worker is less utilised; the
+    result does not change when the instance list is reordered or all loads are doubled."""
+    tb = workloads.make_table(0); st = workloads.make_states(0, tb.V); wk = workloads.make_workers(0, st)
+    q = workloads.make_queries(0, n=6000)
+    table = (tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us, st.state, st.load_us)
+    queries = (q.task, q.slo_us, q.min_acc_bp, q.batch_idx)
+    cl = (wk.variant_hw, wk.worker_hw, wk.worker_util, wk.inst_variant, wk.inst_worker, wk.inst_load)
+    v, t, w = _both_workers(o, *table, *cl, *queries)
+    plain = o.select_tiered(*table, *queries)
+    assert np.array_equal(v, plain[0]) and np.array_equal(t, plain[1])
+    assert (t == 1).sum() > 500 and (t == 2).sum() > 500 and (t == 0).sum() > 100
+    assert np.all(w[t == 0] == -1)
+    seen = {}
+    for i in range(len(v)):
+        assert seen.setdefault((int(v[i]), int(t[i])), int(w[i])) == int(w[i])
+    for i in np.flatnonzero(t == 1)[:400]:
+        mine = np.flatnonzero(wk.inst_variant == v[i])
+        assert mine.size and w[i] in wk.inst_worker[mine]
+        best = min((int(wk.inst_load[j]), int(wk.inst_worker[j])) for j in mine)
+        assert best[1] == w[i]
+    for i in np.flatnonzero(t == 2)[:400]:
+        hw = wk.variant_hw[v[i]]
+        assert wk.worker_hw[w[i]] == hw
+        cand = np.flatnonzero(wk.worker_hw == hw)
+        assert (int(wk.worker_util[w[i]]), int(w[i])) == min((int(wk.worker_util[c]), int(c)) for c in cand)
+    perm = np.random.default_rng(3).permutation(wk.I)
+    again = _both_workers(o, *table, wk.variant_hw, wk.worker_hw, wk.worker_util, wk.inst_variant[perm],
+                          wk.inst_worker[perm], wk.inst_load[perm], *queries)
+    assert np.array_equal(again[2], w)
+    again = _both_workers(o, *table, wk.variant_hw, wk.worker_hw, 2 * wk.worker_util, wk.inst_variant,
+                          wk.inst_worker, 2 * wk.inst_load, *queries)
+    assert np.array_equal(again[2], w)
+
+
+def pin_worker_reports(o):
+    util = np.array([5, 6, 7], np.int32)
+    o.update_worker_util(util, [2, 0, 3, -1, 1, 2], [1, 9, 4, 4, -1, 8])
+    assert util.tolist() == [9, 6, 8]
+    load = np.array([5, 6, 7, 8], np.int32)
+    o.update_instance_load(load, [3, 3, 4, 0, -2, 1], [1, 2, 9, -5, 3, 0])
+    assert load.tolist() == [5, 0, 7, 2]
+
+
+WORKER_PINS = [
+    pin_workers_numpy,
+    pin_workers_policy,
+    pin_workers_structure,
+    pin_worker_reports,
 ]

@@ -124,6 +124,48 @@ def test_tiered_mutant_is_caught(tmp_path, source_text, name, find, repl):
     assert caught, f"no pin notices the planted mistake '{name}'"
 
 
+# planted mistakes in the worker selection
+WORKER_MUTANTS = [
+    ("worker_most_loaded", "if (best < 0 || inst_load[i] < inst_load[best] ||", "if (best < 0 || inst_load[i] > inst_load[best] ||"),
+    ("worker_load_tie_to_higher_number", "(inst_load[i] == inst_load[best] && inst_worker[i] < inst_worker[best]))",
+     "(inst_load[i] == inst_load[best] && inst_worker[i] > inst_worker[best]))"),
+    ("worker_load_tie_keeps_first_listed", "(inst_load[i] == inst_load[best] && inst_worker[i] < inst_worker[best]))", "0)"),
+    ("worker_any_variants_instance", "if (inst_variant[i] != variant)\n            continue;", ""),
+    ("worker_returns_instance_number", "return best >= 0 ? inst_worker[best] : -1;", "return best >= 0 ? (int32_t)best : -1;"),
+    ("worker_most_utilised", "if (best < 0 || worker_util[w] < worker_util[best])", "if (best < 0 || worker_util[w] > worker_util[best])"),
+    ("worker_util_tie_to_higher_number", "if (best < 0 || worker_util[w] < worker_util[best])", "if (best < 0 || worker_util[w] <= worker_util[best])"),
+    ("worker_hardware_ignored", "if (worker_hw[w] != hw)\n            continue;", ""),
+    ("worker_hardware_by_variant_number", "out_worker[q] = least_utilised_worker(W, worker_hw, worker_util, variant_hw[v]);",
+     "out_worker[q] = least_utilised_worker(W, worker_hw, worker_util, v);"),
+    ("worker_tiers_swapped", "        if (out_tier[q] == 1)\n            out_worker[q] = least_loaded_worker(n_inst, inst_variant, inst_worker, inst_load,\n                                                list + first[v]",
+     "        if (out_tier[q] == 2)\n            out_worker[q] = least_loaded_worker(n_inst, inst_variant, inst_worker, inst_load,\n                                                list + first[v]"),
+    ("worker_inactive_by_instances", "else if (out_tier[q] == 2)\n            out_worker[q] = least_utilised_worker(W, worker_hw, worker_util, variant_hw[v]);",
+     "else if (out_tier[q] == 2)\n            out_worker[q] = least_loaded_worker(n_inst, inst_variant, inst_worker, inst_load, list + first[v], first[v + 1] - first[v], v);"),
+    ("worker_for_unanswered_query", "        else\n            out_worker[q] = -1;\n    }\n    free(first);", "        else\n            out_worker[q] = 0;\n    }\n    free(first);"),
+    ("worker_list_off_by_one", "list + first[v], first[v + 1] - first[v], v);", "list + first[v], first[v + 1] - first[v] - 1, v);"),
+    ("worker_args_unchecked", "if (inst_variant[i] < 0 || inst_variant[i] >= V || inst_worker[i] < 0 || inst_worker[i] >= W)\n            return 0;",
+     "if (inst_variant[i] < 0 || inst_variant[i] >= V || inst_worker[i] < 0)\n            return 0;"),   # (a variant outside the table would make the mutant write outside its lists)
+    ("util_report_keeps_negative", "if (w < 0 || w >= W || new_util[i] < 0)", "if (w < 0 || w >= W)"),
+    ("instance_report_out_of_order", "for (int64_t i = 0; i < n; ++i) {\n        int64_t j = inst_idx[i];", "for (int64_t i = n - 1; i >= 0; --i) {\n        int64_t j = inst_idx[i];"),
+]
+
+
+@pytest.mark.parametrize("name,find,repl", WORKER_MUTANTS, ids=[m[0] for m in WORKER_MUTANTS])
+def test_worker_mutant_is_caught(tmp_path, source_text, name, find, repl):
+    assert find in source_text, f"mutant {name}: pattern not in the oracle source any more"
+    src = tmp_path / f"{name}.c"
+    src.write_text(source_text.replace(find, repl))
+    lib = oracle.build_oracle(src=str(src), out=str(tmp_path / f"lib{name}.so"), force=True)
+    mutant = oracle.Oracle(lib)
+    caught = []
+    for pin in pins.WORKER_PINS:
+        try:
+            pin(mutant)
+        except (AssertionError, ValueError):
+            caught.append(pin.__name__)
+    assert caught, f"no pin notices the planted mistake '{name}'"
+
+
 @pytest.fixture(scope="module")
 def source_text():
     with open(SRC) as f:

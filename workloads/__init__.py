@@ -18,4 +18,8 @@ from .configs import (  # noqa: F401
     StateUpdate,
     make_states,
     make_state_update,
+    WorkerTables,
+    WorkerUpdate,
+    make_workers,
+    make_worker_update,
 )

@@ -254,3 +254,87 @@ def make_state_update(cfg: int, V: int, chunk: int, fraction: float = 0.05,
     rows = rng.choice(V, size=n, replace=False)
     vals = rng.choice(4, size=n, p=_STATE_P)
     return StateUpdate(variant_idx=rows.astype(np.int32), state=vals.astype(np.int32))
+
+
+@dataclass
+class WorkerTables:
+    """Workers and running instances (Sections 4.1 and 5: an instance is a {variant, worker} pair)."""
+    variant_hw: np.ndarray    # [V] int32, target hardware class of every variant
+    worker_hw: np.ndarray     # [W] int32, hardware class of every worker
+    worker_util: np.ndarray   # [W] int32, utilisation in basis points
+    inst_variant: np.ndarray  # [I] int32
+    inst_worker: np.ndarray   # [I] int32
+    inst_load: np.ndarray     # [I] int32, load figure of the instance (outstanding queries)
+
+    @property
+    def W(self) -> int:
+        return int(self.worker_hw.shape[0])
+
+    @property
+    def I(self) -> int:
+        return int(self.inst_variant.shape[0])
+
+
+@dataclass
+class WorkerUpdate:
+    worker_idx: np.ndarray    # [n] int32, distinct workers
+    worker_util: np.ndarray   # [n] int32
+    inst_idx: np.ndarray      # [m] int32, distinct instances
+    inst_load: np.ndarray     # [m] int32
+
+
+_NUM_WORKERS = {0: 48, 1: 256, 2: 1024, 3: 2048, 4: 1024}
+_NUM_HW = 3   # the paper's cluster has three kinds of hardware (CPU, GPU, Inferentia)
+
+
+def make_workers(cfg: int, states: VariantStates, seed: Optional[int] = None) -> WorkerTables:
+    """Stand-in for the cluster the paper's controller sees (it publishes no such table): W workers
+    (48 / 256 / 1024 / 2048 / 1024 for configs 0..4) of hardware class U{0,1,2} with utilisation
+    U{0..10000} basis points; every variant has a target class U{0,1,2}; every variant that is
+    loaded (state Active, Overloaded or Interfered) runs min(1 + Poisson(1), 8) instances on
+    distinct workers of its class, each with a load U{0..1000}; Inactive variants run none.  The
+    instance list is shuffled.  Seed: _SEED0 + cfg + 11000.  Draw order: worker classes, worker
+    utilisations, variant classes, instance counts, then per loaded variant its workers, then all
+    loads, then the shuffle."""
+    if seed is None:
+        seed = _SEED0 + cfg + 11000
+    rng = np.random.default_rng(np.random.PCG64(seed))
+    V = int(states.state.shape[0])
+    W = _NUM_WORKERS[cfg]
+    worker_hw = rng.integers(0, _NUM_HW, size=W).astype(np.int32)
+    worker_util = rng.integers(0, 10001, size=W).astype(np.int32)
+    variant_hw = rng.integers(0, _NUM_HW, size=V).astype(np.int32)
+    count = np.minimum(1 + rng.poisson(1.0, size=V), 8)
+    by_class = [np.flatnonzero(worker_hw == c) for c in range(_NUM_HW)]
+    iv, iw = [], []
+    for v in np.flatnonzero(states.state != 0):
+        pool = by_class[variant_hw[v]]
+        k = min(int(count[v]), pool.size)
+        if k:
+            iw.append(rng.choice(pool, size=k, replace=False))
+            iv.append(np.full(k, v))
+    inst_variant = np.concatenate(iv) if iv else np.zeros(0, dtype=np.int64)
+    inst_worker = np.concatenate(iw) if iw else np.zeros(0, dtype=np.int64)
+    inst_load = rng.integers(0, 1001, size=inst_variant.size)
+    order = rng.permutation(inst_variant.size)
+    return WorkerTables(variant_hw=variant_hw, worker_hw=worker_hw, worker_util=worker_util,
+                        inst_variant=inst_variant[order].astype(np.int32),
+                        inst_worker=inst_worker[order].astype(np.int32),
+                        inst_load=inst_load[order].astype(np.int32))
+
+
+def make_worker_update(cfg: int, W: int, I: int, chunk: int, fraction: float = 0.10,
+                       seed: Optional[int] = None) -> WorkerUpdate:
+    """Report before chunk ``chunk``: ``fraction`` of the workers get a new utilisation
+    U{0..10000} and ``fraction`` of the instances a new load U{0..1000}, both chosen without
+    replacement.  Seed: _SEED0 + cfg + 13000 + chunk."""
+    if seed is None:
+        seed = _SEED0 + cfg + 13000 + chunk
+    rng = np.random.default_rng(np.random.PCG64(seed))
+    n, m = int(round(W * fraction)), int(round(I * fraction))
+    widx = rng.choice(W, size=n, replace=False) if n else np.zeros(0, dtype=np.int64)
+    util = rng.integers(0, 10001, size=n)
+    iidx = rng.choice(I, size=m, replace=False) if m else np.zeros(0, dtype=np.int64)
+    load = rng.integers(0, 1001, size=m)
+    return WorkerUpdate(worker_idx=widx.astype(np.int32), worker_util=util.astype(np.int32),
+                        inst_idx=iidx.astype(np.int32), inst_load=load.astype(np.int32))
