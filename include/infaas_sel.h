@@ -206,6 +206,58 @@ int infaas_sel_select_tiered(infaas_sel_t *h, int64_t N,
                              const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
                              int32_t *d_out_variant, int32_t *d_out_tier, void *hip_stream);
 
+/*
+ * ---- Worker selection: the second output of Case I (Section 4.1) ------------------------------
+ *
+ * The policy returns the variant and the worker that serves the query: for an Active variant
+ * the least-loaded worker running an instance of it, for an Inactive one the worker with the
+ * lowest utilisation among those that have the variant's target hardware.  A running instance
+ * is a {variant, worker} pair (Section 5) with a load figure of its own.  Readings where the
+ * text is silent: "least loaded" compares the load figures of the variant's instances, equal
+ * ones go to the lower worker number; equal utilisations go to the lower worker number; an
+ * Active variant without an instance, or an Inactive one whose hardware no worker has, gets
+ * worker -1 while variant and tier stand.
+ *
+ * Register the cluster.  HOST arrays, copied:
+ *   worker_hw    [num_workers]    hardware code of every worker (any int32; compared for equality)
+ *   worker_util  [num_workers]    utilisation, >= 0 (e.g. basis points)
+ *   variant_hw   [V]              target hardware code of every variant, caller row order
+ *   inst_variant [num_instances]  row of the variant the instance runs, 0..V-1
+ *   inst_worker  [num_instances]  worker it runs on, 0..num_workers-1
+ *   inst_load    [num_instances]  its load, >= 0
+ * Synchronous.  Needs infaas_sel_load_states first; a later infaas_sel_load_states or
+ * infaas_sel_load_variants drops the cluster again.
+ * Errors: INVALID_ARG, NOT_LOADED, OUT_OF_RANGE, HIP, OOM.
+ */
+int infaas_sel_load_workers(infaas_sel_t *h, int32_t num_workers, const int32_t *worker_hw,
+                            const int32_t *worker_util, const int32_t *variant_hw,
+                            int32_t num_instances, const int32_t *inst_variant,
+                            const int32_t *inst_worker, const int32_t *inst_load);
+
+/*
+ * Report of the monitoring daemons: worker_util[d_worker_idx[i]] = d_worker_util[i] for i < n
+ * and inst_load[d_inst_idx[j]] = d_inst_load[j] for j < m (instances numbered as they were
+ * passed to infaas_sel_load_workers).  DEVICE arrays; either part may be empty (count 0, null
+ * pointers); the indices of a part must be distinct; an entry whose index is outside its table
+ * or whose value is negative is skipped.  Enqueues on hip_stream and returns.
+ * Errors: INVALID_ARG, NOT_LOADED (no workers loaded), HIP.
+ */
+int infaas_sel_update_workers(infaas_sel_t *h, int32_t n, const int32_t *d_worker_idx,
+                              const int32_t *d_worker_util, int32_t m, const int32_t *d_inst_idx,
+                              const int32_t *d_inst_load, void *hip_stream);
+
+/*
+ * infaas_sel_select_tiered plus the worker: arrays as there, and
+ *   d_out_worker  [N]  DEVICE: the worker that serves d_out_variant, or -1 (no variant, or no
+ *                      worker for it, see above)
+ * Errors: INVALID_ARG, NOT_LOADED (no states or no workers loaded), HIP, OOM.
+ */
+int infaas_sel_select_workers(infaas_sel_t *h, int64_t N,
+                              const int32_t *d_task, const int32_t *d_slo_us,
+                              const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
+                              int32_t *d_out_variant, int32_t *d_out_tier, int32_t *d_out_worker,
+                              void *hip_stream);
+
 /* Free the handle and everything it owns.  NULL is a no-op. */
 void infaas_sel_destroy(infaas_sel_t *h);
 
@@ -235,7 +287,10 @@ enum {
     INFAAS_SEL_K_INDEX_BUILD = 7,/* staircase index (re)build */
     INFAAS_SEL_K_INDEX_SELECT = 8,/* staircase index lookup, one lane per query */
     INFAAS_SEL_K_UPDATE_STATE = 9,/* state report: masks of the rank-ordered columns */
-    INFAAS_SEL_K_COUNT = 10
+    INFAAS_SEL_K_WORKER_REPORT = 10,/* utilisation and instance-load report */
+    INFAAS_SEL_K_WORKER_TABLES = 11,/* worker of every variant (two kernels) */
+    INFAAS_SEL_K_STEP_WORKERS = 12,/* worker of every step of an index */
+    INFAAS_SEL_K_COUNT = 13
 };
 typedef struct {
     int64_t launches[INFAAS_SEL_K_COUNT];

@@ -20,7 +20,8 @@ ENGINE_SCAN = 1
 ENGINE_INDEX = 2
 
 KERNEL_NAMES = ("update_load", "histogram", "plan", "scatter", "scan_lds", "scan_wide",
-                "finish_wide", "index_build", "index_select", "update_state")
+                "finish_wide", "index_build", "index_select", "update_state", "worker_report",
+                "worker_tables", "step_workers")
 _K_COUNT = len(KERNEL_NAMES)
 
 _I32P = ctypes.POINTER(ctypes.c_int32)
@@ -58,7 +59,8 @@ _lib: Optional[ctypes.CDLL] = None
 # every symbol include/infaas_sel.h declares
 EXPORTED = ("infaas_sel_create", "infaas_sel_load_variants", "infaas_sel_update_load",
             "infaas_sel_select", "infaas_sel_select_closest", "infaas_sel_load_states",
-            "infaas_sel_update_state", "infaas_sel_select_tiered", "infaas_sel_destroy", "infaas_sel_reserve",
+            "infaas_sel_update_state", "infaas_sel_select_tiered", "infaas_sel_load_workers",
+            "infaas_sel_update_workers", "infaas_sel_select_workers", "infaas_sel_destroy", "infaas_sel_reserve",
             "infaas_sel_read_load", "infaas_sel_set_timing", "infaas_sel_get_timings",
             "infaas_sel_get_info", "infaas_sel_strerror", "infaas_sel_last_error")
 
@@ -92,6 +94,9 @@ def load_library() -> ctypes.CDLL:
     lib.infaas_sel_load_states.argtypes = [vp, _I32P, _I32P]
     lib.infaas_sel_update_state.argtypes = [vp, ctypes.c_int32, vp, vp, vp]
     lib.infaas_sel_select_tiered.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp]
+    lib.infaas_sel_load_workers.argtypes = [vp, ctypes.c_int32, _I32P, _I32P, _I32P, ctypes.c_int32, _I32P, _I32P, _I32P]
+    lib.infaas_sel_update_workers.argtypes = [vp, ctypes.c_int32, vp, vp, ctypes.c_int32, vp, vp, vp]
+    lib.infaas_sel_select_workers.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.infaas_sel_destroy.argtypes = [vp]
     lib.infaas_sel_destroy.restype = None
     lib.infaas_sel_reserve.argtypes = [vp, ctypes.c_int64]
@@ -213,6 +218,38 @@ class Selector:
             _dev_ptr(d_min_acc_bp, n, "d_min_acc_bp"), _dev_ptr(d_batch_idx, n, "d_batch_idx"),
             _dev_ptr(d_out_variant, n, "d_out_variant"), _dev_ptr(d_out_tier, n, "d_out_tier"),
             _stream_ptr(stream)))
+
+    def load_workers(self, worker_hw, worker_util, variant_hw, inst_variant, inst_worker, inst_load) -> None:
+        """Host arrays: hardware code and utilisation of every worker [W], target hardware of every
+        variant [V], and the running instances (variant row, worker, load) [I]."""
+        worker_hw, worker_util, variant_hw = _host_i32(worker_hw), _host_i32(worker_util), _host_i32(variant_hw)
+        inst_variant, inst_worker, inst_load = _host_i32(inst_variant), _host_i32(inst_worker), _host_i32(inst_load)
+        assert worker_hw.shape == worker_util.shape and worker_hw.ndim == 1 and variant_hw.ndim == 1
+        assert inst_variant.shape == inst_worker.shape == inst_load.shape and inst_variant.ndim == 1
+        _check(self._lib.infaas_sel_load_workers(
+            self._h, worker_hw.shape[0], worker_hw.ctypes.data_as(_I32P), worker_util.ctypes.data_as(_I32P),
+            variant_hw.ctypes.data_as(_I32P), inst_variant.shape[0], inst_variant.ctypes.data_as(_I32P),
+            inst_worker.ctypes.data_as(_I32P), inst_load.ctypes.data_as(_I32P)))
+
+    def update_workers(self, d_worker_idx=None, d_worker_util=None, d_inst_idx=None, d_inst_load=None,
+                       stream=None) -> None:
+        """Device tensors; either pair may be left out."""
+        n = int(d_worker_idx.numel()) if d_worker_idx is not None else 0
+        m = int(d_inst_idx.numel()) if d_inst_idx is not None else 0
+        _check(self._lib.infaas_sel_update_workers(
+            self._h, n, _dev_ptr(d_worker_idx, n, "d_worker_idx") if n else None,
+            _dev_ptr(d_worker_util, n, "d_worker_util") if n else None,
+            m, _dev_ptr(d_inst_idx, m, "d_inst_idx") if m else None,
+            _dev_ptr(d_inst_load, m, "d_inst_load") if m else None, _stream_ptr(stream)))
+
+    def select_workers(self, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, d_out_tier,
+                       d_out_worker, stream=None, n: Optional[int] = None) -> None:
+        n = int(d_task.numel()) if n is None else int(n)
+        _check(self._lib.infaas_sel_select_workers(
+            self._h, n, _dev_ptr(d_task, n, "d_task"), _dev_ptr(d_slo_us, n, "d_slo_us"),
+            _dev_ptr(d_min_acc_bp, n, "d_min_acc_bp"), _dev_ptr(d_batch_idx, n, "d_batch_idx"),
+            _dev_ptr(d_out_variant, n, "d_out_variant"), _dev_ptr(d_out_tier, n, "d_out_tier"),
+            _dev_ptr(d_out_worker, n, "d_out_worker"), _stream_ptr(stream)))
 
     def destroy(self) -> None:
         if self._h:

@@ -82,6 +82,11 @@ struct infaas_sel {
     int32_t *d_open = nullptr;                   // lists of the queries the Active tier leaves open (grows)
     int32_t *d_open_count = nullptr;             // [workgroups of the lookup kernel]
     int64_t open_queries = 0, open_bytes = 0;    // pass size d_open is good for; its size
+    // worker selection (on the handle the caller holds; the step_worker arrays hang off both indexes)
+    WorkerView wv{};
+    std::vector<void *> worker_mem;              // the device arrays wv points into
+    bool workers_loaded = false, workers_dirty = false;
+    bool steps_stale = false;                    // this table's ix.step_worker is older than its index or the workers
 
     // staircase index
     IndexView ix{};
@@ -126,6 +131,7 @@ struct infaas_sel {
     void free_index()
     {
         (void)hipFree(ix.pool); (void)hipFree(ix.step_row); (void)hipFree(ix.ctrl);  // hdr lives in pool's allocation
+        (void)hipFree(ix.step_worker);
         (void)hipFree(d_park);
         d_park = nullptr;
         park_bytes = 0;
@@ -147,6 +153,12 @@ struct infaas_sel {
 
 void infaas_sel::drop_inactive()
 {
+    for (void *p : worker_mem) (void)hipFree(p);
+    worker_mem.clear();
+    wv = WorkerView{};
+    workers_loaded = workers_dirty = false;
+    (void)hipFree(ix.step_worker);
+    ix.step_worker = nullptr;
     (void)hipFree(d_open); (void)hipFree(d_open_count);
     d_open = d_open_count = nullptr;
     open_queries = open_bytes = 0;
@@ -599,6 +611,7 @@ int infaas_sel_update_load(infaas_sel_t *h, int32_t n, const int32_t *d_variant_
             return INFAAS_SEL_ERR_HIP;
     }
     if (h->have_index) {  // the steps depend on the load: rebuild them behind the update
+        h->steps_stale = true;
         LaunchTimer t(h, INFAAS_SEL_K_INDEX_BUILD, st);
         if (!HIP_OK(launch_index_build(h->tv, h->ix, st, t.ev()))) return INFAAS_SEL_ERR_HIP;
     }
@@ -612,6 +625,7 @@ int apply_states(infaas_sel *h, const int32_t *d_states, hipStream_t st)
 {
     if (!HIP_OK(launch_update_state(h->tv, h->V, nullptr, d_states, h->have_index ? h->ix.ctrl : nullptr, st)))
         return INFAAS_SEL_ERR_HIP;
+    h->steps_stale = true;
     if (h->have_index && !HIP_OK(launch_index_build(h->tv, h->ix, st))) return INFAAS_SEL_ERR_HIP;
     return INFAAS_SEL_OK;
 }
@@ -695,6 +709,7 @@ int infaas_sel_update_state(infaas_sel_t *h, int32_t n, const int32_t *d_variant
             if (!HIP_OK(launch_update_state(t->tv, n, d_variant_idx, d_state, t->ix.ctrl, st, tm.ev())))
                 return INFAAS_SEL_ERR_HIP;
         }
+        t->steps_stale = true;
         LaunchTimer tm(t, INFAAS_SEL_K_INDEX_BUILD, st);
         if (!HIP_OK(launch_index_build(t->tv, t->ix, st, tm.ev()))) return INFAAS_SEL_ERR_HIP;
     }
@@ -746,21 +761,47 @@ int infaas_sel_select(infaas_sel_t *h, int64_t N, const int32_t *d_task, const i
     return select_impl(h, N, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, nullptr, false, hip_stream);
 }
 
-int infaas_sel_select_tiered(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,
-                             const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
-                             int32_t *d_out_variant, int32_t *d_out_tier, void *hip_stream)
+namespace {
+
+// The state-aware selection, with the worker of every answer when d_out_worker is given.
+int tiered_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,
+                const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
+                int32_t *d_out_variant, int32_t *d_out_tier, int32_t *d_out_worker, bool workers, void *hip_stream)
 {
     if (!h || N < 0) return INFAAS_SEL_ERR_INVALID_ARG;
-    if (!h->loaded || !h->inactive) return INFAAS_SEL_ERR_NOT_LOADED;
+    if (!h->loaded || !h->inactive || (workers && !h->workers_loaded)) return INFAAS_SEL_ERR_NOT_LOADED;
     if (N == 0) return INFAAS_SEL_OK;
-    if (!d_task || !d_slo_us || !d_min_acc_bp || !d_batch_idx || !d_out_variant || !d_out_tier)
+    if (!d_task || !d_slo_us || !d_min_acc_bp || !d_batch_idx || !d_out_variant || !d_out_tier ||
+        (workers && !d_out_worker))
         return INFAAS_SEL_ERR_INVALID_ARG;
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     hipStream_t st = (hipStream_t)hip_stream;
     int rc = ensure_open(h, std::min(N, kMaxTierPass));
     if (rc != INFAAS_SEL_OK) return rc;
-    // The Active tier's lookup writes both result arrays and lists the valid queries it could not
+    if (workers) {
+        // bring the worker of every variant, then of every step of both indexes, up to date
+        if (h->workers_dirty) {
+            {
+                LaunchTimer t(h, INFAAS_SEL_K_WORKER_TABLES, st);
+                if (!HIP_OK(launch_best_per_class(h->wv, st, t.ev()))) return INFAAS_SEL_ERR_HIP;
+            }
+            LaunchTimer t(h, INFAAS_SEL_K_WORKER_TABLES, st);
+            if (!HIP_OK(launch_worker_tables(h->wv, st, t.ev()))) return INFAAS_SEL_ERR_HIP;
+            h->workers_dirty = false;
+            h->steps_stale = h->inactive->steps_stale = true;
+        }
+        infaas_sel *tables[2] = {h, h->inactive};
+        for (int tier = 0; tier < 2; ++tier) {
+            infaas_sel *t = tables[tier];
+            if (!t->steps_stale) continue;
+            LaunchTimer tm(h, INFAAS_SEL_K_STEP_WORKERS, st);
+            if (!HIP_OK(launch_step_workers(t->ix, h->wv.row_worker + (int64_t)tier * h->V, h->V, st, tm.ev())))
+                return INFAAS_SEL_ERR_HIP;
+            t->steps_stale = false;
+        }
+    }
+    // The Active tier's lookup writes all result arrays and lists the valid queries it could not
     // answer; the Inactive tier's lookup reads only those lists and fills in what it can answer.
     for (int64_t done = 0; done < N; done += kMaxTierPass) {
         QueryView q{};
@@ -769,13 +810,140 @@ int infaas_sel_select_tiered(infaas_sel_t *h, int64_t N, const int32_t *d_task, 
         q.bidx = d_batch_idx + done; q.out = d_out_variant + done; q.tier = d_out_tier + done;
         q.open = h->d_open; q.open_count = h->d_open_count;
         q.open_cap = index_open_cap(q.n, h->num_cus);
-        q.pass = 2;
+        if (workers) { q.worker = d_out_worker + done; q.row_worker = h->wv.row_worker; }
+        q.pass = workers ? 4 : 2;
         rc = index_pass(h, q, st);
         if (rc != INFAAS_SEL_OK) return rc;
-        q.pass = 3;
+        if (workers) q.row_worker = h->wv.row_worker + h->V;
+        q.pass = workers ? 5 : 3;
         rc = index_pass(h->inactive, q, st);
         if (rc != INFAAS_SEL_OK) return rc;
     }
+    return INFAAS_SEL_OK;
+}
+
+}  // namespace
+
+int infaas_sel_select_tiered(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,
+                             const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
+                             int32_t *d_out_variant, int32_t *d_out_tier, void *hip_stream)
+{
+    return tiered_impl(h, N, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, d_out_tier, nullptr, false,
+                       hip_stream);
+}
+
+int infaas_sel_select_workers(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,
+                              const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
+                              int32_t *d_out_variant, int32_t *d_out_tier, int32_t *d_out_worker, void *hip_stream)
+{
+    return tiered_impl(h, N, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, d_out_tier, d_out_worker, true,
+                       hip_stream);
+}
+
+int infaas_sel_load_workers(infaas_sel_t *h, int32_t num_workers, const int32_t *worker_hw, const int32_t *worker_util,
+                            const int32_t *variant_hw, int32_t num_instances, const int32_t *inst_variant,
+                            const int32_t *inst_worker, const int32_t *inst_load)
+{
+    if (!h || num_workers < 0 || num_instances < 0) return INFAAS_SEL_ERR_INVALID_ARG;
+    if (!h->loaded || !h->inactive) return INFAAS_SEL_ERR_NOT_LOADED;
+    const int32_t V = h->V, W = num_workers, I = num_instances;
+    if ((W > 0 && (!worker_hw || !worker_util)) || (V > 0 && !variant_hw) ||
+        (I > 0 && (!inst_variant || !inst_worker || !inst_load)))
+        return INFAAS_SEL_ERR_INVALID_ARG;
+    for (int32_t w = 0; w < W; ++w)
+        if (worker_util[w] < 0) return INFAAS_SEL_ERR_OUT_OF_RANGE;
+    for (int32_t i = 0; i < I; ++i)
+        if (inst_variant[i] < 0 || inst_variant[i] >= V || inst_worker[i] < 0 || inst_worker[i] >= W || inst_load[i] < 0)
+            return INFAAS_SEL_ERR_OUT_OF_RANGE;
+    // hardware classes that have workers, numbered in ascending order of the caller's codes
+    std::vector<int32_t> codes(worker_hw, worker_hw + W);
+    std::sort(codes.begin(), codes.end());
+    codes.erase(std::unique(codes.begin(), codes.end()), codes.end());
+    const int32_t H = (int32_t)codes.size();
+    auto class_of = [&](int32_t code) -> int32_t {
+        auto it = std::lower_bound(codes.begin(), codes.end(), code);
+        return it != codes.end() && *it == code ? (int32_t)(it - codes.begin()) : -1;
+    };
+    std::vector<int32_t> cls_off((size_t)H + 1, 0), cls_worker((size_t)W), var_cls((size_t)V);
+    for (int32_t w = 0; w < W; ++w) cls_off[(size_t)class_of(worker_hw[w]) + 1] += 1;
+    for (int32_t c = 0; c < H; ++c) cls_off[(size_t)c + 1] += cls_off[(size_t)c];
+    {
+        std::vector<int32_t> at(cls_off.begin(), cls_off.end() - 1);
+        for (int32_t w = 0; w < W; ++w) cls_worker[(size_t)at[(size_t)class_of(worker_hw[w])]++] = w;
+    }
+    for (int32_t v = 0; v < V; ++v) var_cls[(size_t)v] = class_of(variant_hw[v]);
+    // instances grouped by variant
+    std::vector<int32_t> inst_off((size_t)V + 1, 0), inst_w((size_t)I), inst_l((size_t)I), inst_pos((size_t)I);
+    for (int32_t i = 0; i < I; ++i) inst_off[(size_t)inst_variant[i] + 1] += 1;
+    for (int32_t v = 0; v < V; ++v) inst_off[(size_t)v + 1] += inst_off[(size_t)v];
+    {
+        std::vector<int32_t> at(inst_off.begin(), inst_off.end() - 1);
+        for (int32_t i = 0; i < I; ++i) {
+            const int32_t p = at[(size_t)inst_variant[i]]++;
+            inst_w[(size_t)p] = inst_worker[i]; inst_l[(size_t)p] = inst_load[i]; inst_pos[(size_t)i] = p;
+        }
+    }
+    DeviceGuard g(h->device);
+    if (!g.ok) return INFAAS_SEL_ERR_HIP;
+    if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
+    for (void *p : h->worker_mem) (void)hipFree(p);
+    h->worker_mem.clear();
+    h->workers_loaded = false;
+    bool ok = true;
+    auto upload = [&](const std::vector<int32_t> &src, size_t count) -> int32_t * {
+        int32_t *d = nullptr;
+        if (!ok) return nullptr;
+        if (dev_alloc(&d, count) != hipSuccess) { ok = false; (void)hipGetLastError(); return nullptr; }
+        h->worker_mem.push_back(d);
+        if (!src.empty() && !HIP_OK(hipMemcpy(d, src.data(), src.size() * 4, hipMemcpyHostToDevice))) ok = false;
+        return d;
+    };
+    WorkerView wv{};
+    wv.V = V; wv.W = W; wv.I = I; wv.H = H;
+    wv.util = upload(std::vector<int32_t>(worker_util, worker_util + W), (size_t)W);
+    wv.cls_off = upload(cls_off, cls_off.size());
+    wv.cls_worker = upload(cls_worker, (size_t)W);
+    wv.var_cls = upload(var_cls, (size_t)V);
+    wv.inst_off = upload(inst_off, inst_off.size());
+    wv.inst_worker = upload(inst_w, (size_t)I);
+    wv.inst_load = upload(inst_l, (size_t)I);
+    wv.inst_pos = upload(inst_pos, (size_t)I);
+    wv.best_cls = upload({}, (size_t)H);
+    wv.row_worker = upload({}, (size_t)2 * V);
+    for (infaas_sel *t : {h, h->inactive}) {
+        if (ok && !t->ix.step_worker && dev_alloc(&t->ix.step_worker, t->ix.step_cap) != hipSuccess) {
+            ok = false;
+            (void)hipGetLastError();
+        }
+        t->steps_stale = true;
+    }
+    if (!ok) {
+        for (void *p : h->worker_mem) (void)hipFree(p);
+        h->worker_mem.clear();
+        h->wv = WorkerView{};
+        return INFAAS_SEL_ERR_OOM;
+    }
+    h->wv = wv;
+    h->workers_loaded = true;
+    h->workers_dirty = true;
+    return INFAAS_SEL_OK;
+}
+
+int infaas_sel_update_workers(infaas_sel_t *h, int32_t n, const int32_t *d_worker_idx, const int32_t *d_worker_util,
+                              int32_t m, const int32_t *d_inst_idx, const int32_t *d_inst_load, void *hip_stream)
+{
+    if (!h || n < 0 || m < 0) return INFAAS_SEL_ERR_INVALID_ARG;
+    if (!h->loaded || !h->workers_loaded) return INFAAS_SEL_ERR_NOT_LOADED;
+    if ((n > 0 && (!d_worker_idx || !d_worker_util)) || (m > 0 && (!d_inst_idx || !d_inst_load)))
+        return INFAAS_SEL_ERR_INVALID_ARG;
+    if (n == 0 && m == 0) return INFAAS_SEL_OK;
+    DeviceGuard g(h->device);
+    if (!g.ok) return INFAAS_SEL_ERR_HIP;
+    hipStream_t st = (hipStream_t)hip_stream;
+    LaunchTimer t(h, INFAAS_SEL_K_WORKER_REPORT, st);
+    if (!HIP_OK(launch_worker_report(h->wv, n, d_worker_idx, d_worker_util, m, d_inst_idx, d_inst_load, st, t.ev())))
+        return INFAAS_SEL_ERR_HIP;
+    h->workers_dirty = true;
     return INFAAS_SEL_OK;
 }
 

@@ -522,11 +522,14 @@ __device__ __forceinline__ int32_t closest_step(const Mem &mem, int nit, uint32_
 // q.open_count[workgroup].  3 takes the records of its workgroup's list instead of the query
 // arrays, looks them up in the second tier's table and writes q.out and q.tier (= 2) of those it
 // can answer; it must be launched with the same grid as the pass that wrote the lists.
+// 4 and 5: as 2 and 3, and the worker that serves each answer goes to q.worker (ix.step_worker for
+// answers that are steps of the index, q.row_worker for answers found by the scan).
 template <bool kLds, int kMode>
 __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, IndexView ix, QueryView q,
                                                               int32_t *__restrict__ park_mem, uint32_t lds_cap)
 {
-    constexpr bool kClosest = kMode == 1, kFirst = kMode == 2, kSecond = kMode == 3;
+    constexpr bool kClosest = kMode == 1, kFirst = kMode == 2 || kMode == 4, kSecond = kMode == 3 || kMode == 5;
+    constexpr bool kWorker = kMode >= 4;
     extern __shared__ __align__(16) uint32_t lds_w[];  // [16 B control][S + 1 headers][lds_cap bytes of bodies]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t nhdr = (uint32_t)tv.S + 1u;
@@ -536,7 +539,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     const uint32_t rebase = lds_hdr0 + hdr_bytes;      // LDS address of pool offset 0
     const bool aligned = ((((uintptr_t)q.task) | ((uintptr_t)q.slo) | ((uintptr_t)q.min_acc) |
                            ((uintptr_t)q.bidx) | ((uintptr_t)q.out) | ((uintptr_t)q.closest) |
-                           ((uintptr_t)q.tier)) & 15u) == 0;
+                           ((uintptr_t)q.tier) | ((uintptr_t)q.worker)) & 15u) == 0;
     // Work units of one wavefront: 64 lanes x kPerThread consecutive queries.  The units are split
     // evenly and contiguously over the workgroups; inside a workgroup the wavefronts draw them from
     // a counter in LDS, because the wavefronts of a SIMD do not advance at the same speed.
@@ -680,13 +683,17 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     uint32_t p_base[kPerThread];
     bool p_inl[kPerThread];
     int32_t p_qi[kPerThread];   // second tier only: where each result goes
+    int32_t p_wk[kPerThread];   // worker selection only: the worker of each answer
     auto p_val = [&](int k) -> int32_t { return p_inl[k] ? (int32_t)((p_base[k] << 16) | (uint32_t)p_lrow[k]) : p_grow[k]; };
     auto store_unit = [&]() {
         if (p_i0 < 0) return;
         if (kSecond) {   // only the answers: the first tier has written "none" for all of the list
 #pragma unroll
             for (int k = 0; k < kPerThread; ++k)
-                if (p_qi[k] >= 0 && p_val(k) >= 0) { q.out[p_qi[k]] = p_val(k); q.tier[p_qi[k]] = 2; }
+                if (p_qi[k] >= 0 && p_val(k) >= 0) {
+                    q.out[p_qi[k]] = p_val(k); q.tier[p_qi[k]] = 2;
+                    if (kWorker) q.worker[p_qi[k]] = p_wk[k];
+                }
         } else if (aligned && p_i0 + kSpan <= q.n) {
 #pragma unroll
             for (int h = 0; h < kPerThread / 4; ++h) {
@@ -697,6 +704,10 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                     const v4i t4 = {r.x >= 0, r.y >= 0, r.z >= 0, r.w >= 0};
                     __builtin_nontemporal_store(t4, (v4i *)((char *)q.tier + (uint32_t)p_i0 * 4u) + 64 * h);
                 }
+                if (kWorker) {
+                    const v4i w4 = {p_wk[4 * h], p_wk[4 * h + 1], p_wk[4 * h + 2], p_wk[4 * h + 3]};
+                    __builtin_nontemporal_store(w4, (v4i *)((char *)q.worker + (uint32_t)p_i0 * 4u) + 64 * h);
+                }
             }
         } else {
 #pragma unroll
@@ -705,6 +716,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                     q.out[p_i0 + qoff(k)] = p_val(k);
                     if (kClosest) q.closest[p_i0 + qoff(k)] = p_val(k);
                     if (kFirst) q.tier[p_i0 + qoff(k)] = p_val(k) >= 0;
+                    if (kWorker) q.worker[p_i0 + qoff(k)] = p_wk[k];
                 }
         }
     };
@@ -760,6 +772,8 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             p_base[k] = (rbase[k] >> ((step * ix.row_hi_bits) & 31u)) & row_hi_mask;
             p_grow[k] = *(const int32_t *)((const char *)ix.step_row + ((hit && !inl) ? (rec[k] + step) * 4u : 0u));
             p_inl[k] = inl;
+            // the worker of the step, by the same kind of gather (entry 0, for no step, is -1)
+            if (kWorker) p_wk[k] = *(const int32_t *)((const char *)ix.step_worker + (hit ? (rec[k] + step) * 4u : 0u));
             if (kSecond) p_qi[k] = cur.bi[k];
             // parked: a miss that the second body / the scan may still turn into a hit; in the
             // closest-variant mode also every final miss of a query inside the table
@@ -824,7 +838,11 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         const uint32_t keys0 = (y >> kHdrK0Shift) & 0x3Fu, keys1 = (y >> kHdrK1Shift) & 0x3Fu;   // Re of the bodies
         const uint32_t size0 = body_bytes(keys0);
         const uint32_t dd[1] = {acc_threshold(min_acc, acc_base_m1)}, lim[1] = {(uint32_t)slo};
-        int32_t ans = -1;
+        int32_t ans = -1, wk = -1;
+        auto take_step = [&](uint32_t at) {   // the answer is step `at` of the index
+            ans = ix.step_row[at];
+            if (kWorker) wk = ix.step_worker[at];
+        };
         bool done = final_miss;
         // first body from global memory: only if the main loop could not use an LDS copy
         const bool need_g0 = have && indexed && kLds && !resident && !done;
@@ -832,7 +850,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             const uint32_t bd[1] = {need_g0 ? gbody : 0u}, ks[1] = {need_g0 ? keys0 : 2u};
             uint32_t m[1];
             search_bodies<1>(gmem, nit, bd, ks, dd, lim, m);
-            if (need_g0 && m[0]) { ans = ix.step_row[rec + __builtin_ctz(m[0])]; done = true; }
+            if (need_g0 && m[0]) { take_step(rec + __builtin_ctz(m[0])); done = true; }
         }
         // second body: LDS copy when resident, global memory otherwise
         const bool need1 = have && indexed && keys1 != 0u && !done;
@@ -841,13 +859,13 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             const uint32_t bd[1] = {need_l1 ? lbody + size0 : rebase}, ks[1] = {need_l1 ? keys1 : 2u};
             uint32_t m[1];
             search_bodies<1>(lmem, nit, bd, ks, dd, lim, m);
-            if (need_l1 && m[0]) { ans = ix.step_row[rec + kBodySteps + __builtin_ctz(m[0])]; done = true; }
+            if (need_l1 && m[0]) { take_step(rec + kBodySteps + __builtin_ctz(m[0])); done = true; }
         }
         if (__ballot(need_g1)) {
             const uint32_t bd[1] = {need_g1 ? gbody + size0 : 0u}, ks[1] = {need_g1 ? keys1 : 2u};
             uint32_t m[1];
             search_bodies<1>(gmem, nit, bd, ks, dd, lim, m);
-            if (need_g1 && m[0]) { ans = ix.step_row[rec + kBodySteps + __builtin_ctz(m[0])]; done = true; }
+            if (need_g1 && m[0]) { take_step(rec + kBodySteps + __builtin_ctz(m[0])); done = true; }
         }
         // no body, or both bodies missed and more steps exist: scan the slice in rank order
         uint64_t todo = __ballot(have && !done && (!indexed || (y & kHdrTrunc)));
@@ -868,16 +886,25 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                     const uint64_t bm = __ballot(ok);
                     if (bm) { found = blk + (int32_t)__builtin_ctzll(bm); break; }
                 }
-                if (lane == l) ans = found >= 0 ? tv.orig_r[col + found] : -1;
+                if (lane == l) {
+                    ans = found >= 0 ? tv.orig_r[col + found] : -1;
+                    if (kWorker) wk = found >= 0 ? q.row_worker[ans] : -1;
+                }
             }
         }
         if (kSecond) {
-            if (have && ans >= 0) { q.out[qi] = ans; q.tier[qi] = 2; }
+            if (have && ans >= 0) {
+                q.out[qi] = ans; q.tier[qi] = 2;
+                if (kWorker) q.worker[qi] = wk;
+            }
         } else if (have && !final_miss) {
             q.out[qi] = ans;
         }
         if (kFirst) {   // the main loop has stored tier 0 for a parked query
-            if (have && ans >= 0) q.tier[qi] = 1;
+            if (have && ans >= 0) {
+                q.tier[qi] = 1;
+                if (kWorker) q.worker[qi] = wk;
+            }
             const uint64_t om = __ballot(have && ans < 0);
             if (om) {
                 const uint32_t at = open_room((uint32_t)__builtin_popcountll(om));
@@ -1003,7 +1030,8 @@ hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const Q
         const uint32_t fixed = kLdsCtrlBytes + lds_header_bytes(tv.S);
         lds_bytes = fixed + ((lds_bytes - fixed) & ~15u);
         auto kernel = q.pass == 1 ? k_index_select<true, 1> : q.pass == 2 ? k_index_select<true, 2> :
-                      q.pass == 3 ? k_index_select<true, 3> : k_index_select<true, 0>;
+                      q.pass == 3 ? k_index_select<true, 3> : q.pass == 4 ? k_index_select<true, 4> :
+                      q.pass == 5 ? k_index_select<true, 5> : k_index_select<true, 0>;
         hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes);
         if (e != hipSuccess) return e;
@@ -1011,7 +1039,8 @@ hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const Q
                              park_mem, lds_bytes - fixed);
     }
     auto kernel = q.pass == 1 ? k_index_select<false, 1> : q.pass == 2 ? k_index_select<false, 2> :
-                  q.pass == 3 ? k_index_select<false, 3> : k_index_select<false, 0>;
+                  q.pass == 3 ? k_index_select<false, 3> : q.pass == 4 ? k_index_select<false, 4> :
+                  q.pass == 5 ? k_index_select<false, 5> : k_index_select<false, 0>;
     return launch_kernel(ev, kernel, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), kLdsCtrlBytes, st, tv, ix, q,
                          park_mem, 0u);
 }

@@ -95,6 +95,7 @@ struct IndexView {
     uint8_t *pool;       // bodies; an empty dummy body sits at offset 4 (its address is 0)
     uint32_t pool_bytes;
     int32_t *step_row;   // caller row of every step; entry 0 is unused
+    int32_t *step_worker;// worker that serves the row of every step (worker selection), else null; entry 0 is -1
     uint32_t step_cap;
     uint32_t hot_rows;   // rows kept in front of the first body of every slice (fills the LDS left over)
     uint32_t row_hi_bits;// bits of a row number above its low 16
@@ -135,6 +136,10 @@ struct QueryView {
     // the lookup kernel (open_cap records of 16 bytes each), and the number of records in each
     int32_t *open, *open_count;
     int32_t open_cap;
+    // worker selection: third result array, and the worker of every caller row for the tier the
+    // pass looks at (for answers that do not come from a step of the index)
+    int32_t *worker;
+    const int32_t *row_worker;
     int32_t pass;        // 0 selection, 1 with closest-variant suggestion, 2 first tier, 3 second tier
 };
 
@@ -182,5 +187,30 @@ hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const Q
 int index_select_blocks(int num_cus);
 int32_t index_open_cap(int32_t n, int num_cus);   // records per workgroup of QueryView::open for a pass over n queries
 size_t index_park_bytes(int num_cus);
+
+// Worker selection (Section 4.1: the worker that serves the selected variant).
+struct WorkerView {
+    int32_t V, W, I, H;           // variants, workers, instances, hardware classes that have workers
+    int32_t *util;                // [W] utilisation, caller's worker numbers
+    const int32_t *cls_off;       // [H + 1] workers grouped by hardware class ...
+    const int32_t *cls_worker;    // [W]     ... worker numbers, ascending inside a class
+    const int32_t *var_cls;       // [V] class of the variant's target hardware, -1 when no worker has it
+    const int32_t *inst_off;      // [V + 1] instances grouped by variant (caller row) ...
+    const int32_t *inst_worker;   // [I]     ... their workers
+    int32_t *inst_load;           // [I]     ... their loads
+    const int32_t *inst_pos;      // [I] caller's instance number -> position in the grouped arrays
+    int32_t *best_cls;            // [H] least-utilised worker of every class
+    int32_t *row_worker;          // [2 V] worker by caller row: for an Active answer, then for an Inactive one
+};
+// Utilisation and instance-load report (either part may be empty).
+hipError_t launch_worker_report(const WorkerView &wv, int32_t n, const int32_t *worker_idx, const int32_t *util,
+                                int32_t m, const int32_t *inst_idx, const int32_t *load, hipStream_t st,
+                                const LaunchEvents *ev = nullptr);
+// best_cls, then row_worker, from the current utilisations and loads (in this order).
+hipError_t launch_best_per_class(const WorkerView &wv, hipStream_t st, const LaunchEvents *ev = nullptr);
+hipError_t launch_worker_tables(const WorkerView &wv, hipStream_t st, const LaunchEvents *ev = nullptr);
+// ix.step_worker[j] = row_worker[ix.step_row[j]] for every step of the index (row_worker: num_rows entries).
+hipError_t launch_step_workers(const IndexView &ix, const int32_t *row_worker, int32_t num_rows, hipStream_t st,
+                               const LaunchEvents *ev = nullptr);
 
 }  // namespace infaas
