@@ -9,7 +9,8 @@ With --closest a step is one call of infaas_sel_select_closest (the selection pl
 for the queries that nothing satisfies; 24 B per decision).  With --tiered a step is one call of
 infaas_sel_select_tiered over seeded variant states (Active variants first, else an Inactive one
 by loading + inference latency; variant and tier arrays, 24 B per decision); its two lookup
-launches are priced together.
+launches are priced together.  With --workers a step is one call of infaas_sel_select_workers
+(the same plus the worker that serves each answer, over a seeded cluster; 28 B per decision).
 
 Prints ONE JSON line: decisions/s, the roofline of the dominant kernel (algorithmic bytes:
 20 B per decision + the variant table once, against 8 TB/s of HBM) timed with HIP events on
@@ -74,6 +75,9 @@ def main() -> int:
     ap.add_argument("--tiered", action="store_true",
                     help="time infaas_sel_select_tiered (state-aware two-tier selection over seeded variant "
                          "states; 24 B per decision) instead of infaas_sel_select")
+    ap.add_argument("--workers", action="store_true",
+                    help="time infaas_sel_select_workers (two-tier selection plus the worker of every answer, "
+                         "over a seeded cluster of workers and instances; 28 B per decision)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -106,8 +110,9 @@ def main() -> int:
     chunks = spec["chunks"]
     per_step = spec["num_queries"] // chunks
     engine = pkg.ENGINE_AUTO if args.engine == "auto" else pkg.ENGINE_SCAN
-    if (args.closest or args.tiered) and (args.engine != "auto" or (args.closest and args.tiered)):
-        print("bench.py: --closest and --tiered need the index engine (--engine auto), one at a time",
+    if (args.closest or args.tiered or args.workers) and \
+            (args.engine != "auto" or args.closest + args.tiered + args.workers > 1):
+        print("bench.py: --closest, --tiered and --workers need the index engine (--engine auto), one at a time",
               file=sys.stderr)
         return 2
 
@@ -115,9 +120,14 @@ def main() -> int:
     sel.load_variants(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us)
     sel.reserve(per_step)
     states = None
-    if args.tiered:
+    cluster = None
+    if args.tiered or args.workers:
         states = workloads.make_states(cfg, tb.V)
         sel.load_states(states.state, states.load_us)
+    if args.workers:
+        cluster = workloads.make_workers(cfg, states)
+        sel.load_workers(cluster.worker_hw, cluster.worker_util, cluster.variant_hw, cluster.inst_variant,
+                         cluster.inst_worker, cluster.inst_load)
 
     # inputs resident in HBM before the timed region.  The streaming configuration cycles over a
     # few distinct chunks and load reports; the others reuse one batch.
@@ -126,10 +136,17 @@ def main() -> int:
     dev_q = [[torch.from_numpy(x).cuda() for x in (q.task, q.slo_us, q.min_acc_bp, q.batch_idx)]
              for q in host_q]
     out = torch.empty(per_step, dtype=torch.int32, device="cuda")
-    two_results = args.closest or args.tiered                        # suggestion, or tier
+    two_results = args.closest or args.tiered or args.workers        # suggestion, or tier
     closest = torch.empty(per_step, dtype=torch.int32, device="cuda") if two_results else None
-    per_decision = BYTES_PER_DECISION + (4 if two_results else 0)
+    worker = torch.empty(per_step, dtype=torch.int32, device="cuda") if args.workers else None
+    per_decision = BYTES_PER_DECISION + (4 if two_results else 0) + (4 if args.workers else 0)
     updates = []
+    worker_updates = []
+    if chunks > 1 and args.workers:   # a report of the cluster before every step as well
+        for c in range(1, n_sets + 1):
+            wu = workloads.make_worker_update(cfg, cluster.W, cluster.I, c)
+            worker_updates.append(([torch.from_numpy(x).cuda() for x in
+                                    (wu.worker_idx, wu.worker_util, wu.inst_idx, wu.inst_load)], wu))
     if chunks > 1:
         for c in range(1, n_sets + 1):
             up = workloads.make_load_update(cfg, tb.V, c)
@@ -143,6 +160,10 @@ def main() -> int:
             sel.select_closest(*dev_q[i % n_sets], out, closest)
         elif args.tiered:
             sel.select_tiered(*dev_q[i % n_sets], out, closest)
+        elif args.workers:
+            if worker_updates:
+                sel.update_workers(*worker_updates[i % len(worker_updates)][0])
+            sel.select_workers(*dev_q[i % n_sets], out, closest, worker)
         else:
             sel.select(*dev_q[i % n_sets], out)
 
@@ -167,9 +188,11 @@ def main() -> int:
     dom = max(active, key=lambda k: active[k]["total_ms"])
     dom_avg_ms = active[dom]["total_ms"] / active[dom]["launches"]
     launches_per_step = active[dom]["launches"] / args.steps
-    mode = "/closest" if args.closest else "/tiered" if args.tiered else ""
-    fixed_bytes = table_bytes(tb) + (8 * tb.V if args.tiered else 0)   # + state and loading latency
-    if args.tiered and dom == "index_select":
+    mode = "/closest" if args.closest else "/tiered" if args.tiered else "/workers" if args.workers else ""
+    fixed_bytes = table_bytes(tb) + (8 * tb.V if args.tiered or args.workers else 0)   # + state and loading latency
+    if args.workers:   # + hardware of every variant, the workers, the instances
+        fixed_bytes += 4 * tb.V + 8 * cluster.W + 12 * cluster.I
+    if (args.tiered or args.workers) and dom == "index_select":
         # one lookup per tier: the pair is priced as one launch against the bytes of the whole call
         algo_bytes = per_decision * per_step + fixed_bytes
         dom_avg_ms = active[dom]["total_ms"] / args.steps
@@ -205,7 +228,18 @@ def main() -> int:
         fields = (q.task, q.slo_us, q.min_acc_bp, q.batch_idx)
         n0 = min(per_step, 100_000)
         s0 = time.perf_counter()
-        if args.tiered:
+        if args.workers:
+            util, iload = cluster.worker_util.copy(), cluster.inst_load.copy()
+            if worker_updates:
+                for i in range(args.warmup + args.steps):
+                    wu = worker_updates[i % len(worker_updates)][1]
+                    ref.update_worker_util(util, wu.worker_idx, wu.worker_util)
+                    ref.update_instance_load(iload, wu.inst_idx, wu.inst_load)
+
+            def ref_fn(*a):
+                return ref.select_workers(*a[:5], states.state, states.load_us, cluster.variant_hw, cluster.worker_hw,
+                                          util, cluster.inst_variant, cluster.inst_worker, iload, *a[5:])
+        elif args.tiered:
             def ref_fn(*a):
                 return ref.select_tiered(*a[:5], states.state, states.load_us, *a[5:])
         else:
@@ -216,7 +250,9 @@ def main() -> int:
         s0 = time.perf_counter()
         want = ref_fn(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, queue, *(f[:n] for f in fields))
         dt = time.perf_counter() - s0
-        if two_results:
+        if args.workers:
+            mismatches = int(sum((g[:n].cpu().numpy() != w).sum() for g, w in zip((out, closest, worker), want)))
+        elif two_results:
             mismatches = int((out[:n].cpu().numpy() != want[0]).sum() + (closest[:n].cpu().numpy() != want[1]).sum())
         else:
             mismatches = int((out[:n].cpu().numpy() != want).sum())
@@ -232,7 +268,9 @@ def main() -> int:
                                f"{tb.B} batch sizes, {per_step} queries per step"
                                + (f", load report of {updates[0][2].variant_idx.size} rows before every step" if updates else "")
                                + (", closest-variant mode (two result arrays)" if args.closest else "")
-                               + (", state-aware two-tier selection (variant and tier arrays)" if args.tiered else ""),
+                               + (", state-aware two-tier selection (variant and tier arrays)" if args.tiered else "")
+                               + (f", two-tier selection with worker selection over {cluster.W} workers and "
+                                  f"{cluster.I} instances (variant, tier and worker arrays)" if args.workers else ""),
                    "engine": args.engine},
         "roofline": roofline,
         "whole_step_frac_of_hbm_roofline": round(whole_frac, 5),
