@@ -69,6 +69,9 @@ class Oracle:
             fn = getattr(lib, name)
             fn.argtypes = [ctypes.c_int64, _I32P, ctypes.c_int64, _I32P, _I32P]
             fn.restype = None
+        lib.oracle_scale.argtypes = ([ctypes.c_int64, ctypes.c_int32] + [_I32P] * 5 + [ctypes.c_int32, ctypes.c_int32]
+                                     + [ctypes.c_int64] + [_I32P] * 8)
+        lib.oracle_scale.restype = ctypes.c_int
         lib.oracle_update_state.argtypes = [ctypes.c_int64, _I32P, ctypes.c_int64, _I32P, _I32P]
         lib.oracle_update_state.restype = None
         lib.oracle_count_feasible.argtypes = [ctypes.c_int64, ctypes.c_int32, _I32P, _I32P, _I32P,
@@ -200,6 +203,29 @@ class Oracle:
         inst_idx, new_load = _i32(inst_idx), _i32(new_load)
         self._lib.oracle_update_instance_load(inst_load.shape[0], _ptr(inst_load), inst_idx.shape[0],
                                               _ptr(inst_idx), _ptr(new_load))
+
+    def scale(self, arch_id, sat_qps, hw_cost, load_us, lat_us, lambda_per_s, slack_pct,
+              r_variant, r_instances, r_load_qps, r_slo, r_bidx):
+        """Scaling decision per request: (action 0 none / 1 replicate / 2 upgrade / 3 impossible,
+        variant to load or -1, instances of it to load)."""
+        arch_id, sat_qps, hw_cost, load_us = _i32(arch_id), _i32(sat_qps), _i32(hw_cost), _i32(load_us)
+        lat_us = _i32(lat_us)
+        V, B = lat_us.shape
+        for a in (arch_id, sat_qps, hw_cost, load_us):
+            assert a.shape == (V,)
+        r_variant, r_instances, r_load_qps = _i32(r_variant), _i32(r_instances), _i32(r_load_qps)
+        r_slo, r_bidx = _i32(r_slo), _i32(r_bidx)
+        R = r_variant.shape[0]
+        for a in (r_instances, r_load_qps, r_slo, r_bidx):
+            assert a.shape == (R,)
+        action, variant, inst = (np.empty(R, dtype=np.int32) for _ in range(3))
+        rc = self._lib.oracle_scale(V, B, _ptr(arch_id), _ptr(sat_qps), _ptr(hw_cost), _ptr(load_us), _ptr(lat_us),
+                                    int(lambda_per_s), int(slack_pct), R, _ptr(r_variant), _ptr(r_instances),
+                                    _ptr(r_load_qps), _ptr(r_slo), _ptr(r_bidx), _ptr(action), _ptr(variant),
+                                    _ptr(inst))
+        if rc != 0:
+            raise ValueError("oracle rejected its arguments")
+        return action, variant, inst
 
     def update_state(self, state: np.ndarray, variant_idx, new_state) -> None:
         """In place: state[variant_idx[i]] = new_state[i], array order."""

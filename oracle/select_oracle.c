@@ -52,6 +52,10 @@
  * output of Case I) is pinned by a numpy enumerator, by hand-built cases (one
  * instance, one hardware class, ties, no instance, no worker of the hardware),
  * by invariance under reordering of the instance list and by its own mutants.
+ * The scaling decision (last routine) is pinned by the instance counts and costs
+ * the paper prints in Tables 2 and 3, by an enumerator in Python's unbounded
+ * integers, by closed forms (lambda = 0: the hardware cost of the resulting
+ * configuration decides) and by its own mutants.
  * The only statement that stays
  * "parity unpinned" is the count of valid options printed in Table 7, because
  * the profiles behind it are not published.
@@ -683,6 +687,116 @@ void oracle_update_instance_load(int64_t n_inst, int32_t *inst_load, int64_t n,
             continue;
         inst_load[j] = new_load[i];
     }
+}
+
+/*
+ * Scaling decision on a change in query load (Section 4.2.2, "scaling up"; cost function and
+ * constraints of the integer program of Section 4.2.1; instance counts and costs as in the
+ * worked example of Section 2.2, Tables 2 and 3).
+ *
+ * A request names a running variant cur with n_cur instances, the incoming load L (queries per
+ * second), the application's latency objective S and a batch index b.  With Q the saturation
+ * throughput, C the hardware cost per second, T_load the loading latency of a variant and
+ * T_inf = lat_us[.][b] its inference latency:
+ *
+ *   no action          when Q[cur] * n_cur already covers the load with the required headroom
+ *                      (constraint 1; headroom = slack_pct percent of the load, the
+ *                      slack-threshold of Section 5 is 1.05 = 105 percent);
+ *   replicate          load d = inst(cur) - n_cur more instances of cur, allowed when
+ *                      T_inf[cur] <= S (constraint 2 binds every newly loaded instance);
+ *   upgrade            switch to a variant u of the same model architecture with T_inf[u] <= S
+ *                      and Q[u] > Q[cur]: load inst(u) instances of u, unload the n_cur of cur;
+ *   where inst(v) = ceil(L * slack_pct / (100 * Q[v])) instances of v alone carry the load.
+ *
+ * The options are compared by the integer program's objective, the sum over the touched variants
+ * of  C * (delta + lambda * T_load * max(delta, 0)):
+ *     replicate:  C[cur] * d * (1 + lambda * T_load[cur])
+ *     upgrade:    C[u] * inst(u) * (1 + lambda * T_load[u])  -  C[cur] * n_cur
+ * and the cheapest is taken.  Everything is an integer: lambda is per second and T_load in
+ * microseconds, so all costs are carried times 1,000,000 and compared exactly in 128 bits.
+ *
+ * Readings where the text is silent: the cheapest upgrade wins ties by the lower row; replication
+ * wins a tie against the cheapest upgrade (no switch without a gain); a request whose running
+ * variant or batch index is outside the table, or with n_cur outside 0..1,000,000 or a load
+ * outside 0..1,000,000,000 queries per second, gets no action (the limits keep every instance
+ * count inside 32 bits; likewise lambda <= 1000 per second, slack_pct <= 200 and C <= 2^20);
+ * when scaling is needed and neither option is allowed the action code is 3 (the worker has to
+ * turn to the controller, step (d) of Section 4.2.2).  Resource limits of the worker
+ * (constraint 3) and scaling down are not part of this routine.
+ *
+ * Outputs per request: action (0 none, 1 replicate, 2 upgrade, 3 needed but impossible), the
+ * variant to load (-1 for actions 0 and 3) and the number of its instances to load.
+ */
+typedef __int128 wide_t;
+
+int oracle_scale(int64_t V, int32_t B,
+                 const int32_t *arch_id, const int32_t *sat_qps, const int32_t *hw_cost,
+                 const int32_t *load_us, const int32_t *lat_us,
+                 int32_t lambda_per_s, int32_t slack_pct,
+                 int64_t R,
+                 const int32_t *r_variant, const int32_t *r_instances, const int32_t *r_load_qps,
+                 const int32_t *r_slo_us, const int32_t *r_batch_idx,
+                 int32_t *out_action, int32_t *out_variant, int32_t *out_instances)
+{
+    if (V < 0 || B <= 0 || R < 0 || lambda_per_s < 0 || lambda_per_s > 1000 || slack_pct < 0 ||
+        slack_pct > 200)
+        return -1;
+    for (int64_t v = 0; v < V; ++v)
+        if (sat_qps[v] < 1 || hw_cost[v] < 0 || hw_cost[v] > 1048576 || load_us[v] < 0)
+            return -1;
+#pragma omp parallel for schedule(dynamic, 1024)
+    for (int64_t r = 0; r < R; ++r) {
+        int64_t cur = r_variant[r];
+        int32_t b = r_batch_idx[r];
+        out_action[r] = 0;
+        out_variant[r] = -1;
+        out_instances[r] = 0;
+        if (cur < 0 || cur >= V || b < 0 || b >= B || r_instances[r] < 0 || r_load_qps[r] < 0 ||
+            r_instances[r] > 1000000 || r_load_qps[r] > 1000000000)
+            continue;
+        int64_t n_cur = r_instances[r];
+        int64_t need = (int64_t)r_load_qps[r] * (int64_t)slack_pct;        /* hundredths of a query per second */
+        if ((int64_t)sat_qps[cur] * n_cur * 100 >= need)
+            continue;                                                       /* constraint 1 holds already */
+        int64_t slo = r_slo_us[r];
+        int have = 0;
+        int64_t best_v = -1, best_n = 0;
+        wide_t best_cost = 0;
+        if ((int64_t)lat_us[cur * B + b] <= slo) {                          /* replicate */
+            int64_t per = 100 * (int64_t)sat_qps[cur];
+            int64_t inst = (need + per - 1) / per;
+            best_n = inst - n_cur;
+            best_v = cur;
+            best_cost = (wide_t)hw_cost[cur] * best_n *
+                        ((wide_t)1000000 + (wide_t)lambda_per_s * load_us[cur]);
+            have = 1;
+        }
+        wide_t saved = (wide_t)hw_cost[cur] * n_cur * 1000000;              /* unloading cur */
+        for (int64_t u = 0; u < V; ++u) {                                   /* upgrade */
+            if (u == cur || arch_id[u] != arch_id[cur])
+                continue;
+            if ((int64_t)lat_us[u * B + b] > slo || sat_qps[u] <= sat_qps[cur])
+                continue;
+            int64_t per = 100 * (int64_t)sat_qps[u];
+            int64_t inst = (need + per - 1) / per;
+            wide_t cost = (wide_t)hw_cost[u] * inst *
+                          ((wide_t)1000000 + (wide_t)lambda_per_s * load_us[u]) - saved;
+            if (!have || cost < best_cost) {        /* rows ascend: an equal cost keeps the earlier choice */
+                best_cost = cost;
+                best_v = u;
+                best_n = inst;
+                have = 1;
+            }
+        }
+        if (!have) {
+            out_action[r] = 3;
+            continue;
+        }
+        out_action[r] = best_v == cur ? 1 : 2;
+        out_variant[r] = (int32_t)best_v;
+        out_instances[r] = (int32_t)best_n;
+    }
+    return 0;
 }
 
 /* Host threads the grouped form uses. */

@@ -623,3 +623,164 @@ WORKER_PINS = [
     pin_workers_structure,
     pin_worker_reports,
 ]
+
+
+# ---- scaling decision on a change in load (Section 4.2) --------------------------------------------
+
+def scale_py(arch_id, sat_qps, hw_cost, load_us, lat_us, lam, slack_pct, r_variant, r_instances, r_load,
+             r_slo, r_bidx):
+    """The decision in Python's unbounded integers, costs as exact fractions times 1,000,000."""
+    V, B = np.asarray(lat_us).shape
+    out = []
+    for cur, n_cur, L, slo, b in zip(*(np.asarray(x).tolist() for x in (r_variant, r_instances, r_load, r_slo, r_bidx))):
+        if not (0 <= cur < V and 0 <= b < B and 0 <= n_cur <= 10**6 and 0 <= L <= 10**9):
+            out.append((0, -1, 0)); continue
+        need = L * slack_pct
+        if int(sat_qps[cur]) * n_cur * 100 >= need:
+            out.append((0, -1, 0)); continue
+        inst = lambda v: -((-need) // (100 * int(sat_qps[v])))
+        unit = lambda v: int(hw_cost[v]) * (10**6 + lam * int(load_us[v]))
+        options = []   # (cost, order, action, variant, instances); replication first among equals
+        if int(lat_us[cur][b]) <= slo:
+            d = inst(cur) - n_cur
+            options.append((unit(cur) * d, -1, 1, cur, d))
+        for u in range(V):
+            if u != cur and arch_id[u] == arch_id[cur] and int(lat_us[u][b]) <= slo and sat_qps[u] > sat_qps[cur]:
+                options.append((unit(u) * inst(u) - int(hw_cost[cur]) * n_cur * 10**6, u, 2, u, inst(u)))
+        out.append(min(options)[2:] if options else (3, -1, 0))
+    return tuple(np.array(x, dtype=np.int32) for x in zip(*out)) if out else (np.zeros(0, np.int32),) * 3
+
+
+def _scaling_example():
+    names, lat, qps, cost, alone, decide = [], [], [], [], [], []
+    with open(os.path.join(GOLDEN, "tables_2_3_scaling_example.txt")) as f:
+        for line in f:
+            p = line.split()
+            if not p or p[0].startswith("#"):
+                continue
+            if p[0] == "variant":
+                names.append(p[1]); lat.append(int(p[2]) * 1000); qps.append(int(p[3])); cost.append(int(p[4]))
+            elif p[0] == "alone":
+                alone.append((int(p[1]), p[2], int(p[3]), int(p[4])))
+            elif p[0] == "decide":
+                decide.append((int(p[1]), int(p[2]) * 1000, p[3], int(p[4]), p[5], p[6], int(p[7])))
+    return names, np.array(lat, np.int32)[:, None], np.array(qps, np.int32), np.array(cost, np.int32), alone, decide
+
+
+def pin_scaling_paper_example(o):
+    """Instance counts, costs and decisions of the printed example (Tables 2 and 3), in every
+    registration order of the three variants.  An instance count is read off a replication from
+    zero instances; a cost ratio off the decision between two variants."""
+    import itertools
+    names, lat, qps, cost, alone, decide = _scaling_example()
+    for perm in itertools.permutations(range(3)):
+        perm = list(perm)
+        row = {names[p]: i for i, p in enumerate(perm)}
+        tab = (np.zeros(3, np.int32), qps[perm], cost[perm], np.zeros(3, np.int32), lat[perm])
+        for load, name, inst, total in alone:
+            a, v, n = o.scale(*tab, 0, 100, [row[name]], [0], [load], [10**9], [0])
+            # from nothing, with every latency allowed: replicate unless a faster variant is cheaper
+            alone_cost = inst * int(cost[names.index(name)])
+            assert alone_cost == total, "fixture inconsistent"
+            if a[0] == 1:
+                assert (v[0], n[0]) == (row[name], inst), (name, load)
+            else:   # an upgrade won: it must be strictly cheaper than the printed cost of replication
+                u = perm[v[0]]
+                assert a[0] == 2 and int(cost[u]) * int(n[0]) < total
+        # the replication counts themselves, with upgrades ruled out by separate architectures
+        solo = (np.arange(3, dtype=np.int32),) + tab[1:]
+        for load, name, inst, total in alone:
+            a, v, n = o.scale(*solo, 0, 100, [row[name]], [0], [load], [10**9], [0])
+            assert (a[0], v[0], n[0]) == (1, row[name], inst), (name, load)
+        for load, slo, name, running, action, target, inst in decide:
+            a, v, n = o.scale(*tab, 0, 100, [row[name]], [running], [load], [slo], [0])
+            assert (a[0], v[0], n[0]) == ({"replicate": 1, "upgrade": 2}[action], row[target], inst), (load, slo)
+
+
+def pin_scaling_python(o):
+    """Random small tables (ties in every field, invalid requests) against the enumerator in
+    Python integers, with several lambdas and headrooms."""
+    rng = np.random.default_rng(19)
+    for trial in range(60):
+        V = int(rng.integers(1, 40)); B = int(rng.integers(1, 4))
+        span = int(rng.choice([2, 4, 9, 1000]))
+        arch = rng.integers(0, max(1, V // 6) + 1, V).astype(np.int32)
+        qps = rng.integers(1, span + 1, V).astype(np.int32)
+        cost = rng.integers(0, span + 1, V).astype(np.int32)
+        load = rng.integers(0, 50 * span, V).astype(np.int32)
+        lat = rng.integers(1, span + 1, (V, B)).astype(np.int32)
+        R = 200
+        rv = rng.integers(-1, V + 1, R); rn = rng.integers(-1, 4, R); rl = rng.integers(-1, 12 * span, R)
+        rs = rng.integers(0, span + 2, R); rb = rng.integers(-1, B + 1, R)
+        lam = int(rng.choice([0, 1, 37, 1000])); slack = int(rng.choice([0, 100, 105, 200]))
+        got = o.scale(arch, qps, cost, load, lat, lam, slack, rv, rn, rl, rs, rb)
+        want = scale_py(arch, qps, cost, load, lat, lam, slack, rv, rn, rl, rs, rb)
+        for g, w in zip(got, want):
+            assert np.array_equal(g, w), f"trial {trial}"
+
+
+def pin_scaling_closed_forms(o):
+    """Hand-built cases and limits."""
+    one = lambda *a: tuple(int(x[0]) for x in o.scale(*a))
+    arch = np.zeros(3, np.int32); lat = np.array([[10], [10], [10]], np.int32)
+    qps = np.array([10, 40, 40], np.int32); cost = np.array([5, 30, 30], np.int32); load = np.array([0, 0, 0], np.int32)
+    tab = (arch, qps, cost, load, lat)
+    req = lambda n, L, slo=100: ([0], [n], [L], [slo], [0])
+    # headroom: 2 x 10 qps carry 20 qps at 100% but not at 105%
+    assert one(*tab, 0, 100, *req(2, 20)) == (0, -1, 0)
+    assert one(*tab, 0, 105, *req(2, 20))[0] != 0
+    # lambda = 0: resulting hardware cost decides.  40 qps: 4 x row 0 = 20 against 1 x row 1 = 30 -> replicate 2
+    assert one(*tab, 0, 100, *req(2, 40)) == (1, 0, 2)
+    # 80 qps: 8 x 5 = 40 against 2 x 30 = 60 -> replicate 6; 41 qps: 5 x 5 = 25 against 2 x 30 = 60
+    assert one(*tab, 0, 100, *req(2, 80)) == (1, 0, 6)
+    assert one(*tab, 0, 100, *req(2, 41)) == (1, 0, 3)
+    # dearer replicas: cost 31 each -> 4 x 31 = 124 against 30: upgrade to the lower of the equal rows 1, 2
+    dear = (arch, qps, np.array([31, 30, 30], np.int32), load, lat)
+    assert one(*dear, 0, 100, *req(2, 40)) == (2, 1, 1)
+    # a tie between replication and upgrade goes to replication: 2 more x 15 = 30 = 30 + 2 x 15 - 2 x 15
+    tie = (arch, qps, np.array([15, 60, 60], np.int32), load, lat)
+    assert one(*tie, 0, 100, *req(2, 40)) == (1, 0, 2)
+    # lambda: loading latency of 1 s doubles the cost of every loaded instance of that variant per unit of lambda
+    slow = (arch, qps, np.array([31, 30, 30], np.int32), np.array([0, 10**6, 3 * 10**6], np.int32), lat)
+    assert one(*slow, 0, 100, *req(2, 40)) == (2, 1, 1)        # 30 - 62 against 62
+    assert one(*slow, 3, 100, *req(2, 40)) == (2, 1, 1)        # 30 x 4 - 62 = 58 against 62
+    assert one(*slow, 4, 100, *req(2, 40)) == (1, 0, 2)        # 30 x 5 - 62 = 88 against 62
+    # the latency objective binds new instances only: the running variant too slow -> no replication
+    late = (arch, qps, cost, load, np.array([[200], [10], [300]], np.int32))
+    assert one(*late, 0, 100, *req(2, 40, slo=100)) == (2, 1, 1)
+    assert one(*late, 0, 100, *req(2, 40, slo=5)) == (3, -1, 0)
+    assert one(*late, 0, 100, *req(2, 40, slo=250)) == (1, 0, 2)
+    # upgrades need a strictly higher throughput and the same architecture
+    flat = (arch, np.array([10, 10, 9], np.int32), np.array([99, 1, 1], np.int32), load, lat)
+    assert one(*flat, 0, 100, *req(1, 40)) == (1, 0, 3)
+    other = (np.array([0, 1, 1], np.int32), qps, np.array([99, 1, 1], np.int32), load, lat)
+    assert one(*other, 0, 100, *req(1, 40)) == (1, 0, 3)
+    # the largest values do not wrap: 10^9 qps on a 1 qps variant at 200% headroom, dearest hardware, lambda 1000
+    big = (np.zeros(2, np.int32), np.array([1, 2], np.int32), np.array([2**20, 2**20], np.int32),
+           np.array([I32MAX, I32MAX], np.int32), np.array([[1], [1]], np.int32))
+    assert one(*big, 1000, 200, [0], [0], [10**9], [1], [0]) == (2, 1, 10**9)
+    assert one(*big, 1000, 200, [1], [10**6], [10**9], [1], [0]) == (1, 1, 10**9 - 10**6)
+    # an upgrade that costs 2.25 * 10^27 (its low 64 bits read as a negative number) against 2 * 10^15 for replicas
+    wrap = (np.zeros(2, np.int32), np.array([1, 2], np.int32), np.array([1, 2**20], np.int32),
+            np.array([0, 2147483641], np.int32), np.array([[1], [1]], np.int32))
+    assert one(*wrap, 1000, 200, [0], [0], [10**9], [1], [0]) == (1, 0, 2 * 10**9)
+    # and the other way round: replicas at 4.5 * 10^27 (low 64 bits negative) against an upgrade at 10^15
+    wrap2 = (np.zeros(2, np.int32), np.array([1, 2], np.int32), np.array([2**20, 1], np.int32),
+             np.array([2147483641, 0], np.int32), np.array([[1], [1]], np.int32))
+    assert one(*wrap2, 1000, 200, [0], [0], [10**9], [1], [0]) == (2, 1, 10**9)
+    # out-of-range parameters are rejected, out-of-range requests get no action
+    for bad in ((1001, 100), (-1, 100), (0, 201), (0, -1)):
+        try:
+            o.scale(*tab, *bad, *req(2, 40))
+        except ValueError:
+            continue
+        raise AssertionError("parameters outside their limits accepted")
+    assert one(*tab, 0, 100, [0], [10**6 + 1], [40], [100], [0]) == (0, -1, 0)
+    assert one(*tab, 0, 100, [0], [1], [10**9 + 1], [100], [0]) == (0, -1, 0)
+
+
+SCALING_PINS = [
+    pin_scaling_paper_example,
+    pin_scaling_python,
+    pin_scaling_closed_forms,
+]

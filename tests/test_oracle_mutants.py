@@ -166,6 +166,51 @@ def test_worker_mutant_is_caught(tmp_path, source_text, name, find, repl):
     assert caught, f"no pin notices the planted mistake '{name}'"
 
 
+# planted mistakes in the scaling decision
+SCALING_MUTANTS = [
+    ("scale_headroom_ignored", "int64_t need = (int64_t)r_load_qps[r] * (int64_t)slack_pct;", "int64_t need = (int64_t)r_load_qps[r] * 100;"),
+    ("scale_capacity_of_one_instance", "if ((int64_t)sat_qps[cur] * n_cur * 100 >= need)", "if ((int64_t)sat_qps[cur] * 100 >= need)"),
+    ("scale_strict_capacity_test", "if ((int64_t)sat_qps[cur] * n_cur * 100 >= need)", "if ((int64_t)sat_qps[cur] * n_cur * 100 > need)"),
+    ("scale_instances_rounded_down", "int64_t inst = (need + per - 1) / per;\n            best_n = inst - n_cur;", "int64_t inst = need / per;\n            best_n = inst - n_cur;"),
+    ("scale_upgrade_instances_rounded_down", "int64_t inst = (need + per - 1) / per;\n            wide_t cost", "int64_t inst = need / per + 1;\n            wide_t cost"),
+    ("scale_replicas_not_net", "best_n = inst - n_cur;", "best_n = inst;"),
+    ("scale_replication_ignores_slo", "if ((int64_t)lat_us[cur * B + b] <= slo) {", "if (1) {"),
+    ("scale_upgrade_ignores_slo", "if ((int64_t)lat_us[u * B + b] > slo || sat_qps[u] <= sat_qps[cur])", "if (sat_qps[u] <= sat_qps[cur])"),
+    ("scale_upgrade_to_equal_throughput", "|| sat_qps[u] <= sat_qps[cur])", "|| sat_qps[u] < sat_qps[cur])"),
+    ("scale_wrong_batch_column", "if ((int64_t)lat_us[u * B + b] > slo", "if ((int64_t)lat_us[u * B] > slo"),
+    ("scale_any_architecture", "if (u == cur || arch_id[u] != arch_id[cur])", "if (u == cur)"),
+    ("scale_unloading_not_credited", "((wide_t)1000000 + (wide_t)lambda_per_s * load_us[u]) - saved;", "((wide_t)1000000 + (wide_t)lambda_per_s * load_us[u]);"),
+    ("scale_unloading_credited_unscaled", "wide_t saved = (wide_t)hw_cost[cur] * n_cur * 1000000;", "wide_t saved = (wide_t)hw_cost[cur] * n_cur;"),
+    ("scale_lambda_dropped", "((wide_t)1000000 + (wide_t)lambda_per_s * load_us[u]) - saved;", "((wide_t)1000000) - saved;"),
+    ("scale_lambda_dropped_for_replicas", "((wide_t)1000000 + (wide_t)lambda_per_s * load_us[cur]);", "((wide_t)1000000);"),
+    ("scale_cost_in_64_bits", "wide_t cost = (wide_t)hw_cost[u] * inst *\n                          ((wide_t)1000000 + (wide_t)lambda_per_s * load_us[u]) - saved;",
+     "wide_t cost = (wide_t)(int64_t)((uint64_t)hw_cost[u] * (uint64_t)inst * (uint64_t)(1000000 + (int64_t)lambda_per_s * load_us[u])) - saved;"),
+    ("scale_replica_cost_in_64_bits", "best_cost = (wide_t)hw_cost[cur] * best_n *\n                        ((wide_t)1000000 + (wide_t)lambda_per_s * load_us[cur]);",
+     "best_cost = (wide_t)(int64_t)((uint64_t)hw_cost[cur] * (uint64_t)best_n * (uint64_t)(1000000 + (int64_t)lambda_per_s * load_us[cur]));"),
+    ("scale_tie_to_upgrade", "if (!have || cost < best_cost) {", "if (!have || cost <= best_cost) {"),
+    ("scale_impossible_reported_as_none", "out_action[r] = 3;", "out_action[r] = 0;"),
+    ("scale_action_codes_swapped", "out_action[r] = best_v == cur ? 1 : 2;", "out_action[r] = best_v == cur ? 2 : 1;"),
+    ("scale_limits_unchecked", "r_instances[r] > 1000000 || r_load_qps[r] > 1000000000)", "0)"),
+    ("scale_lambda_limit_unchecked", "lambda_per_s > 1000 ||", ""),
+]
+
+
+@pytest.mark.parametrize("name,find,repl", SCALING_MUTANTS, ids=[m[0] for m in SCALING_MUTANTS])
+def test_scaling_mutant_is_caught(tmp_path, source_text, name, find, repl):
+    assert find in source_text, f"mutant {name}: pattern not in the oracle source any more"
+    src = tmp_path / f"{name}.c"
+    src.write_text(source_text.replace(find, repl))
+    lib = oracle.build_oracle(src=str(src), out=str(tmp_path / f"lib{name}.so"), force=True)
+    mutant = oracle.Oracle(lib)
+    caught = []
+    for pin in pins.SCALING_PINS:
+        try:
+            pin(mutant)
+        except (AssertionError, ValueError):
+            caught.append(pin.__name__)
+    assert caught, f"no pin notices the planted mistake '{name}'"
+
+
 @pytest.fixture(scope="module")
 def source_text():
     with open(SRC) as f:

@@ -22,4 +22,8 @@ from .configs import (  # noqa: F401
     WorkerUpdate,
     make_workers,
     make_worker_update,
+    ScalingProfile,
+    ScaleRequests,
+    make_scaling,
+    make_scale_requests,
 )

@@ -338,3 +338,70 @@ def make_worker_update(cfg: int, W: int, I: int, chunk: int, fraction: float = 0
     load = rng.integers(0, 1001, size=m)
     return WorkerUpdate(worker_idx=widx.astype(np.int32), worker_util=util.astype(np.int32),
                         inst_idx=iidx.astype(np.int32), inst_load=load.astype(np.int32))
+
+
+@dataclass
+class ScalingProfile:
+    """What the scaling decision of Section 4.2 reads per variant, besides the latency profile."""
+    arch_id: np.ndarray   # [V] int32, model architecture (variants of one architecture share a task)
+    sat_qps: np.ndarray   # [V] int32, saturation throughput in queries per second
+    hw_cost: np.ndarray   # [V] int32, hardware cost per second
+    load_us: np.ndarray   # [V] int32, loading latency
+
+
+@dataclass
+class ScaleRequests:
+    variant: np.ndarray    # [R] int32, the running variant
+    instances: np.ndarray  # [R] int32, its running instances
+    load_qps: np.ndarray   # [R] int32, incoming load
+    slo_us: np.ndarray     # [R] int32
+    batch_idx: np.ndarray  # [R] int32
+
+    @property
+    def R(self) -> int:
+        return int(self.variant.shape[0])
+
+
+def make_scaling(cfg: int, tb: VariantTable, seed: Optional[int] = None) -> ScalingProfile:
+    """Stand-in for the profiles behind the paper's autoscaler (not published): every task's
+    variants are dealt uniformly to max(1, round(size / 12)) architectures (the paper's 175
+    variants come from 22 architectures, 8 per architecture on average); saturation throughput
+    clamp(lognormal(ln 200, 1.2), 1, 200000) queries per second; hardware cost U{50..2000}; loading
+    latency clamp(lognormal(ln 20000, 1.5), 100, 5,000,000) microseconds.  Seed: _SEED0 + cfg +
+    15000.  Draw order: architecture of every variant (tasks in ascending order), throughput,
+    cost, loading latency."""
+    if seed is None:
+        seed = _SEED0 + cfg + 15000
+    rng = np.random.default_rng(np.random.PCG64(seed))
+    V = tb.V
+    arch = np.zeros(V, dtype=np.int64)
+    nxt = 0
+    for t in range(tb.num_tasks):
+        rows = np.flatnonzero(tb.task_id == t)
+        k = max(1, int(round(rows.size / 12.0)))
+        arch[rows] = nxt + rng.integers(0, k, size=rows.size)
+        nxt += k
+    qps = np.clip(np.rint(rng.lognormal(np.log(200.0), 1.2, size=V)), 1, 200_000)
+    cost = rng.integers(50, 2001, size=V)
+    load = np.clip(np.rint(rng.lognormal(np.log(20000.0), 1.5, size=V)), 100, 5_000_000)
+    return ScalingProfile(arch_id=arch.astype(np.int32), sat_qps=qps.astype(np.int32),
+                          hw_cost=cost.astype(np.int32), load_us=load.astype(np.int32))
+
+
+def make_scale_requests(cfg: int, tb: VariantTable, sc: ScalingProfile, n: int, chunk: int = 0,
+                        seed: Optional[int] = None) -> ScaleRequests:
+    """``n`` scaling requests: running variant uniform over the table, 1 + Poisson(1) running
+    instances, incoming load = their combined saturation throughput times U(0.5, 4) (so about a
+    sixth of the requests need no scaling at a slack of 105%), latency objective and batch index
+    as in the query generator (unimodal).  Seed: _SEED0 + cfg + 17000 + chunk."""
+    if seed is None:
+        seed = _SEED0 + cfg + 17000 + chunk
+    rng = np.random.default_rng(np.random.PCG64(seed))
+    variant = rng.integers(0, tb.V, size=n)
+    inst = 1 + rng.poisson(1.0, size=n)
+    load = np.rint(sc.sat_qps[variant].astype(np.float64) * inst * rng.uniform(0.5, 4.0, size=n))
+    slo = np.clip(rng.lognormal(np.log(20000.0), 1.0, size=n), 1000.0, 2_000_000.0)
+    bidx = rng.integers(0, tb.B, size=n)
+    return ScaleRequests(variant=variant.astype(np.int32), instances=inst.astype(np.int32),
+                         load_qps=np.minimum(load, 1_000_000_000).astype(np.int32),
+                         slo_us=np.rint(slo).astype(np.int32), batch_idx=bidx.astype(np.int32))
