@@ -258,6 +258,55 @@ int infaas_sel_select_workers(infaas_sel_t *h, int64_t N,
                               int32_t *d_out_variant, int32_t *d_out_tier, int32_t *d_out_worker,
                               void *hip_stream);
 
+/*
+ * ---- Scaling decision on a change in query load: Case II, scaling up (Section 4.2.2) ----------
+ *
+ * For a running variant cur with n_cur instances and an incoming load of L queries per second:
+ * nothing, when Q[cur] * n_cur already carries slack_pct percent of L (constraint 1 of the
+ * integer program of Section 4.2.1; the paper's slack-threshold 1.05 is 105); else either
+ * REPLICATE, load inst(cur) - n_cur more instances of cur, allowed when lat_us[cur][b] <= slo_us
+ * (constraint 2 binds every newly loaded instance), or UPGRADE, load inst(u) instances of a
+ * variant u of the same model architecture with lat_us[u][b] <= slo_us and Q[u] > Q[cur] and
+ * unload cur -- where inst(v) = ceil(L * slack_pct / (100 * Q[v])).  The cheaper one by the
+ * program's objective wins:
+ *     replicate:  C[cur] * (inst(cur) - n_cur) * (1 + lambda * T_load[cur])
+ *     upgrade:    C[u] * inst(u) * (1 + lambda * T_load[u]) - C[cur] * n_cur
+ * in exact integer arithmetic (lambda per second, T_load in microseconds, 128-bit products).
+ * Readings where the text is silent: among upgrades of equal cost the lower row; replication
+ * wins a tie against the cheapest upgrade; worker resources (constraint 3) and scaling down are
+ * not part of the decision.
+ *
+ * Register what the decision reads per variant.  HOST arrays [V], caller row order, copied:
+ *   arch_id   model architecture (any int32; compared for equality)
+ *   sat_qps   saturation throughput Q in queries per second, >= 1
+ *   hw_cost   hardware cost C per second, 0..1,048,576
+ *   load_us   loading latency T_load, >= 0
+ * and lambda_per_s in 0..1000, slack_pct in 0..200.  Synchronous.  Independent of
+ * infaas_sel_load_states / _load_workers; a later infaas_sel_load_variants drops it.
+ * Errors: INVALID_ARG, NOT_LOADED, OUT_OF_RANGE, HIP, OOM.
+ */
+int infaas_sel_load_scaling(infaas_sel_t *h, const int32_t *arch_id, const int32_t *sat_qps,
+                            const int32_t *hw_cost, const int32_t *load_us,
+                            int32_t lambda_per_s, int32_t slack_pct);
+
+/*
+ * Decide R requests.  DEVICE arrays [R]:
+ *   d_variant, d_instances, d_load_qps, d_slo_us, d_batch_idx   the running variant (row), its
+ *       running instances (0..1,000,000), the incoming load (0..1,000,000,000), the latency
+ *       objective and the batch-size index; a request outside these ranges gets no action
+ *   d_out_action     0 nothing to do, 1 replicate, 2 upgrade, 3 scaling needed but neither
+ *                    option is allowed (the worker has to turn to the controller)
+ *   d_out_variant    the variant to load (the running one for 1), -1 for actions 0 and 3
+ *   d_out_instances  instances of it to load, 0 for actions 0 and 3
+ * Enqueues on hip_stream and returns; allocates nothing.
+ * Errors: INVALID_ARG, NOT_LOADED (no scaling profile loaded), HIP.
+ */
+int infaas_sel_scale(infaas_sel_t *h, int64_t R,
+                     const int32_t *d_variant, const int32_t *d_instances, const int32_t *d_load_qps,
+                     const int32_t *d_slo_us, const int32_t *d_batch_idx,
+                     int32_t *d_out_action, int32_t *d_out_variant, int32_t *d_out_instances,
+                     void *hip_stream);
+
 /* Free the handle and everything it owns.  NULL is a no-op. */
 void infaas_sel_destroy(infaas_sel_t *h);
 
@@ -290,7 +339,8 @@ enum {
     INFAAS_SEL_K_WORKER_REPORT = 10,/* utilisation and instance-load report */
     INFAAS_SEL_K_WORKER_TABLES = 11,/* worker of every variant (two kernels) */
     INFAAS_SEL_K_STEP_WORKERS = 12,/* worker of every step of an index */
-    INFAAS_SEL_K_COUNT = 13
+    INFAAS_SEL_K_SCALE = 13,     /* scaling decisions */
+    INFAAS_SEL_K_COUNT = 14
 };
 typedef struct {
     int64_t launches[INFAAS_SEL_K_COUNT];

@@ -21,7 +21,7 @@ ENGINE_INDEX = 2
 
 KERNEL_NAMES = ("update_load", "histogram", "plan", "scatter", "scan_lds", "scan_wide",
                 "finish_wide", "index_build", "index_select", "update_state", "worker_report",
-                "worker_tables", "step_workers")
+                "worker_tables", "step_workers", "scale")
 _K_COUNT = len(KERNEL_NAMES)
 
 _I32P = ctypes.POINTER(ctypes.c_int32)
@@ -60,7 +60,8 @@ _lib: Optional[ctypes.CDLL] = None
 EXPORTED = ("infaas_sel_create", "infaas_sel_load_variants", "infaas_sel_update_load",
             "infaas_sel_select", "infaas_sel_select_closest", "infaas_sel_load_states",
             "infaas_sel_update_state", "infaas_sel_select_tiered", "infaas_sel_load_workers",
-            "infaas_sel_update_workers", "infaas_sel_select_workers", "infaas_sel_destroy", "infaas_sel_reserve",
+            "infaas_sel_update_workers", "infaas_sel_select_workers", "infaas_sel_load_scaling",
+            "infaas_sel_scale", "infaas_sel_destroy", "infaas_sel_reserve",
             "infaas_sel_read_load", "infaas_sel_set_timing", "infaas_sel_get_timings",
             "infaas_sel_get_info", "infaas_sel_strerror", "infaas_sel_last_error")
 
@@ -97,6 +98,8 @@ def load_library() -> ctypes.CDLL:
     lib.infaas_sel_load_workers.argtypes = [vp, ctypes.c_int32, _I32P, _I32P, _I32P, ctypes.c_int32, _I32P, _I32P, _I32P]
     lib.infaas_sel_update_workers.argtypes = [vp, ctypes.c_int32, vp, vp, ctypes.c_int32, vp, vp, vp]
     lib.infaas_sel_select_workers.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.infaas_sel_load_scaling.argtypes = [vp, _I32P, _I32P, _I32P, _I32P, ctypes.c_int32, ctypes.c_int32]
+    lib.infaas_sel_scale.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.infaas_sel_destroy.argtypes = [vp]
     lib.infaas_sel_destroy.restype = None
     lib.infaas_sel_reserve.argtypes = [vp, ctypes.c_int64]
@@ -250,6 +253,23 @@ class Selector:
             _dev_ptr(d_min_acc_bp, n, "d_min_acc_bp"), _dev_ptr(d_batch_idx, n, "d_batch_idx"),
             _dev_ptr(d_out_variant, n, "d_out_variant"), _dev_ptr(d_out_tier, n, "d_out_tier"),
             _dev_ptr(d_out_worker, n, "d_out_worker"), _stream_ptr(stream)))
+
+    def load_scaling(self, arch_id, sat_qps, hw_cost, load_us, lambda_per_s: int, slack_pct: int) -> None:
+        """Host arrays [V]: model architecture, saturation throughput, hardware cost, loading latency."""
+        arrs = [_host_i32(x) for x in (arch_id, sat_qps, hw_cost, load_us)]
+        assert all(a.ndim == 1 and a.shape == arrs[0].shape for a in arrs)
+        _check(self._lib.infaas_sel_load_scaling(self._h, *(a.ctypes.data_as(_I32P) for a in arrs),
+                                                 int(lambda_per_s), int(slack_pct)))
+
+    def scale(self, d_variant, d_instances, d_load_qps, d_slo_us, d_batch_idx, d_out_action, d_out_variant,
+              d_out_instances, stream=None, n: Optional[int] = None) -> None:
+        n = int(d_variant.numel()) if n is None else int(n)
+        _check(self._lib.infaas_sel_scale(
+            self._h, n, _dev_ptr(d_variant, n, "d_variant"), _dev_ptr(d_instances, n, "d_instances"),
+            _dev_ptr(d_load_qps, n, "d_load_qps"), _dev_ptr(d_slo_us, n, "d_slo_us"),
+            _dev_ptr(d_batch_idx, n, "d_batch_idx"), _dev_ptr(d_out_action, n, "d_out_action"),
+            _dev_ptr(d_out_variant, n, "d_out_variant"), _dev_ptr(d_out_instances, n, "d_out_instances"),
+            _stream_ptr(stream)))
 
     def destroy(self) -> None:
         if self._h:

@@ -82,6 +82,10 @@ struct infaas_sel {
     int32_t *d_open = nullptr;                   // lists of the queries the Active tier leaves open (grows)
     int32_t *d_open_count = nullptr;             // [workgroups of the lookup kernel]
     int64_t open_queries = 0, open_bytes = 0;    // pass size d_open is good for; its size
+    // scaling decisions
+    ScaleView sv{};
+    std::vector<void *> scale_mem;               // the device arrays sv points into
+    bool scaling_loaded = false;
     // worker selection (on the handle the caller holds; the step_worker arrays hang off both indexes)
     WorkerView wv{};
     std::vector<void *> worker_mem;              // the device arrays wv points into
@@ -124,6 +128,10 @@ struct infaas_sel {
         d_state = nullptr;
         loaded = false;
         table_bytes = 0;
+        for (void *p : scale_mem) (void)hipFree(p);
+        scale_mem.clear();
+        sv = ScaleView{};
+        scaling_loaded = false;
         free_index();
         drop_inactive();
     }
@@ -953,6 +961,89 @@ int infaas_sel_select_closest(infaas_sel_t *h, int64_t N, const int32_t *d_task,
 {
     return select_impl(h, N, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, d_out_closest, true,
                        hip_stream);
+}
+
+int infaas_sel_load_scaling(infaas_sel_t *h, const int32_t *arch_id, const int32_t *sat_qps, const int32_t *hw_cost,
+                            const int32_t *load_us, int32_t lambda_per_s, int32_t slack_pct)
+{
+    if (!h) return INFAAS_SEL_ERR_INVALID_ARG;
+    if (!h->loaded) return INFAAS_SEL_ERR_NOT_LOADED;
+    const int32_t V = h->V, B = h->B;
+    if (V > 0 && (!arch_id || !sat_qps || !hw_cost || !load_us)) return INFAAS_SEL_ERR_INVALID_ARG;
+    if (lambda_per_s < 0 || lambda_per_s > 1000 || slack_pct < 0 || slack_pct > 200) return INFAAS_SEL_ERR_OUT_OF_RANGE;
+    for (int32_t v = 0; v < V; ++v)
+        if (sat_qps[v] < 1 || hw_cost[v] < 0 || hw_cost[v] > 1048576 || load_us[v] < 0) return INFAAS_SEL_ERR_OUT_OF_RANGE;
+    // places: variants grouped by architecture, rows ascending inside a group
+    std::vector<int32_t> row_of((size_t)V);
+    std::iota(row_of.begin(), row_of.end(), 0);
+    std::stable_sort(row_of.begin(), row_of.end(), [&](int32_t a, int32_t b) { return arch_id[a] < arch_id[b]; });
+    std::vector<int4> info((size_t)std::max(V, 1));
+    for (int32_t first = 0; first < V;) {
+        int32_t end = first;
+        while (end < V && arch_id[row_of[(size_t)end]] == arch_id[row_of[(size_t)first]]) ++end;
+        for (int32_t p = first; p < end; ++p) info[(size_t)row_of[(size_t)p]] = make_int4(first, end, p, hw_cost[row_of[(size_t)p]]);
+        first = end;
+    }
+    std::vector<ScaleRec> recs((size_t)std::max<int64_t>((int64_t)B * V, 1));
+    for (int32_t b = 0; b < B; ++b)
+        for (int32_t p = 0; p < V; ++p) {
+            const int32_t v = row_of[(size_t)p];
+            ScaleRec &r = recs[(size_t)b * V + p];
+            r.qps = (uint32_t)sat_qps[v];
+            r.lat = h->h_lat[(size_t)v * B + b];
+            r.unit = (uint64_t)hw_cost[v] * (1000000ull + (uint64_t)lambda_per_s * (uint64_t)load_us[v]);   // < 2^62
+        }
+    DeviceGuard g(h->device);
+    if (!g.ok) return INFAAS_SEL_ERR_HIP;
+    if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
+    for (void *p : h->scale_mem) (void)hipFree(p);
+    h->scale_mem.clear();
+    h->scaling_loaded = false;
+    int4 *d_info = nullptr;
+    ScaleRec *d_recs = nullptr;
+    int32_t *d_row_of = nullptr;
+    bool ok = dev_alloc(&d_info, info.size()) == hipSuccess;
+    if (ok) h->scale_mem.push_back(d_info);
+    ok = ok && dev_alloc(&d_recs, recs.size()) == hipSuccess;
+    if (ok) h->scale_mem.push_back(d_recs);
+    ok = ok && dev_alloc(&d_row_of, (size_t)V) == hipSuccess;
+    if (ok) h->scale_mem.push_back(d_row_of);
+    if (!ok) {
+        (void)hipGetLastError();
+        for (void *p : h->scale_mem) (void)hipFree(p);
+        h->scale_mem.clear();
+        return INFAAS_SEL_ERR_OOM;
+    }
+    if (!HIP_OK(hipMemcpy(d_info, info.data(), info.size() * sizeof(int4), hipMemcpyHostToDevice)) ||
+        !HIP_OK(hipMemcpy(d_recs, recs.data(), recs.size() * sizeof(ScaleRec), hipMemcpyHostToDevice)) ||
+        (V > 0 && !HIP_OK(hipMemcpy(d_row_of, row_of.data(), (size_t)V * 4, hipMemcpyHostToDevice)))) {
+        for (void *p : h->scale_mem) (void)hipFree(p);
+        h->scale_mem.clear();
+        return INFAAS_SEL_ERR_HIP;
+    }
+    h->sv = ScaleView{V, B, slack_pct, d_info, d_recs, d_row_of};
+    h->scaling_loaded = true;
+    return INFAAS_SEL_OK;
+}
+
+int infaas_sel_scale(infaas_sel_t *h, int64_t R, const int32_t *d_variant, const int32_t *d_instances,
+                     const int32_t *d_load_qps, const int32_t *d_slo_us, const int32_t *d_batch_idx,
+                     int32_t *d_out_action, int32_t *d_out_variant, int32_t *d_out_instances, void *hip_stream)
+{
+    if (!h || R < 0) return INFAAS_SEL_ERR_INVALID_ARG;
+    if (!h->loaded || !h->scaling_loaded) return INFAAS_SEL_ERR_NOT_LOADED;
+    if (R == 0) return INFAAS_SEL_OK;
+    if (!d_variant || !d_instances || !d_load_qps || !d_slo_us || !d_batch_idx || !d_out_action || !d_out_variant ||
+        !d_out_instances)
+        return INFAAS_SEL_ERR_INVALID_ARG;
+    DeviceGuard g(h->device);
+    if (!g.ok) return INFAAS_SEL_ERR_HIP;
+    hipStream_t st = (hipStream_t)hip_stream;
+    LaunchTimer t(h, INFAAS_SEL_K_SCALE, st);
+    if (!HIP_OK(launch_scale(h->sv, R, d_variant, d_instances, d_load_qps, d_slo_us, d_batch_idx, d_out_action,
+                             d_out_variant, d_out_instances, h->num_cus, st, t.ev())))
+        return INFAAS_SEL_ERR_HIP;
+    return INFAAS_SEL_OK;
 }
 
 void infaas_sel_destroy(infaas_sel_t *h)

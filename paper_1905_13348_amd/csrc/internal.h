@@ -213,4 +213,22 @@ hipError_t launch_worker_tables(const WorkerView &wv, hipStream_t st, const Laun
 hipError_t launch_step_workers(const IndexView &ix, const int32_t *row_worker, int32_t num_rows, hipStream_t st,
                                const LaunchEvents *ev = nullptr);
 
+// Scaling decision on a change in load (Section 4.2.2).
+struct ScaleRec {
+    uint32_t qps;     // saturation throughput
+    int32_t lat;      // inference latency at the record's batch size
+    uint64_t unit;    // cost of one loaded instance: C * (1,000,000 + lambda * T_load)
+};
+struct ScaleView {
+    int32_t V, B;
+    int32_t slack_pct;
+    const int4 *row_info;     // [V] by caller row: {first, end} of its architecture's run, its own place, hardware cost
+    const ScaleRec *recs;     // [B][V] grouped by architecture, rows ascending inside a run
+    const int32_t *row_of;    // [V] caller row of every place
+};
+hipError_t launch_scale(const ScaleView &sv, int64_t R, const int32_t *r_variant, const int32_t *r_instances,
+                        const int32_t *r_load_qps, const int32_t *r_slo_us, const int32_t *r_batch_idx,
+                        int32_t *out_action, int32_t *out_variant, int32_t *out_instances, int num_cus,
+                        hipStream_t st, const LaunchEvents *ev = nullptr);
+
 }  // namespace infaas

@@ -1,0 +1,103 @@
+// Scaling decision on a change in query load (Section 4.2.2, scaling up): for a running variant,
+// its instance count and the incoming load, either nothing, or replicate the variant, or upgrade
+// to a variant of the same model architecture with a higher saturation throughput that meets the
+// latency objective -- whichever is cheaper by the cost function of the integer program of
+// Section 4.2.1, C * (delta + lambda * T_load * max(delta, 0)) summed over the touched variants.
+//
+// One lane per request.  The variants are stored grouped by architecture, so the candidates of a
+// request are one contiguous run of 16-byte records {throughput, latency at the batch size, cost
+// of one loaded instance}; a lane walks its run and keeps the cheapest.  All costs are exact
+// integers (times 1,000,000, because lambda is per second and the loading latency in
+// microseconds), compared in 128 bits.
+#include "internal.h"
+
+namespace infaas {
+
+namespace {
+
+constexpr int kThreads = 256;
+typedef unsigned __int128 u128;
+
+// ceil(need / per) for need < 2^53, 1 <= per < 2^53: the correctly rounded double quotient is the
+// exact one or one above it.
+__device__ __forceinline__ uint64_t ceil_div(uint64_t need, uint64_t per)
+{
+    uint64_t q = (uint64_t)((double)need / (double)per);
+    q -= (q * per > need) ? 1u : 0u;
+    return q + ((q * per < need) ? 1u : 0u);
+}
+
+__global__ __launch_bounds__(kThreads) void k_scale(ScaleView sv, int64_t R, const int32_t *__restrict__ r_variant,
+                                                    const int32_t *__restrict__ r_instances,
+                                                    const int32_t *__restrict__ r_load_qps,
+                                                    const int32_t *__restrict__ r_slo_us,
+                                                    const int32_t *__restrict__ r_batch_idx,
+                                                    int32_t *__restrict__ out_action, int32_t *__restrict__ out_variant,
+                                                    int32_t *__restrict__ out_instances)
+{
+    for (int64_t r0 = (int64_t)blockIdx.x * kThreads; r0 < R; r0 += (int64_t)gridDim.x * kThreads) {
+        const int64_t r = r0 + threadIdx.x;
+        const bool in = r < R;
+        const int32_t cur = in ? __builtin_nontemporal_load(r_variant + r) : -1;
+        const int32_t n_cur = in ? __builtin_nontemporal_load(r_instances + r) : 0;
+        const int32_t load = in ? __builtin_nontemporal_load(r_load_qps + r) : 0;
+        const int32_t slo = in ? __builtin_nontemporal_load(r_slo_us + r) : 0;
+        const int32_t b = in ? __builtin_nontemporal_load(r_batch_idx + r) : 0;
+        const bool valid = (uint32_t)cur < (uint32_t)sv.V && (uint32_t)b < (uint32_t)sv.B &&
+                           (uint32_t)n_cur <= 1000000u && (uint32_t)load <= 1000000000u;
+        const int4 info = sv.row_info[valid ? cur : 0];                 // {first, end of the run, own place, hardware cost}
+        const ScaleRec *recs = sv.recs + (int64_t)(valid ? b : 0) * sv.V;
+        const ScaleRec own = recs[info.z];
+        const uint64_t need = (uint64_t)(uint32_t)load * (uint32_t)sv.slack_pct;   // hundredths of a query per second
+        const bool scaling = valid && (uint64_t)own.qps * (uint32_t)n_cur * 100u < need;
+        int32_t action = 0, variant = -1, instances = 0;
+        if (scaling) {
+            // everything is compared with the credit for unloading the running instances added, so
+            // that no difference can become negative
+            const u128 saved = (u128)((uint64_t)(uint32_t)info.w * (uint32_t)n_cur) * 1000000u;
+            bool have = false;
+            u128 best = 0;
+            int32_t best_at = -1;
+            uint64_t best_n = 0;
+            if (own.lat <= slo) {   // replicate
+                best_n = ceil_div(need, 100u * (uint64_t)own.qps) - (uint32_t)n_cur;
+                best = (u128)own.unit * best_n + saved;
+                best_at = info.z;
+                have = true;
+            }
+            for (int32_t i = info.x; i < info.y; ++i) {   // upgrade; rows ascend along the run
+                const ScaleRec c = recs[i];
+                if (i == info.z || c.lat > slo || c.qps <= own.qps) continue;
+                const uint64_t inst = ceil_div(need, 100u * (uint64_t)c.qps);
+                const u128 cost = (u128)c.unit * inst;
+                if (!have || cost < best) { best = cost; best_at = i; best_n = inst; have = true; }
+            }
+            action = !have ? 3 : (best_at == info.z ? 1 : 2);
+            if (have) {
+                variant = best_at == info.z ? cur : sv.row_of[best_at];
+                instances = (int32_t)best_n;
+            }
+        }
+        if (in) {
+            __builtin_nontemporal_store(action, out_action + r);
+            __builtin_nontemporal_store(variant, out_variant + r);
+            __builtin_nontemporal_store(instances, out_instances + r);
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_scale(const ScaleView &sv, int64_t R, const int32_t *r_variant, const int32_t *r_instances,
+                        const int32_t *r_load_qps, const int32_t *r_slo_us, const int32_t *r_batch_idx,
+                        int32_t *out_action, int32_t *out_variant, int32_t *out_instances, int num_cus,
+                        hipStream_t st, const LaunchEvents *ev)
+{
+    if (R <= 0) return hipSuccess;
+    const int64_t want = (R + kThreads - 1) / kThreads;
+    const int64_t blocks = want < (int64_t)num_cus * 32 ? want : (int64_t)num_cus * 32;
+    return launch_kernel(ev, k_scale, dim3((unsigned)blocks), dim3(kThreads), 0, st, sv, R, r_variant, r_instances,
+                         r_load_qps, r_slo_us, r_batch_idx, out_action, out_variant, out_instances);
+}
+
+}  // namespace infaas
