@@ -11,6 +11,8 @@ infaas_sel_select_tiered over seeded variant states (Active variants first, else
 by loading + inference latency; variant and tier arrays, 24 B per decision); its two lookup
 launches are priced together.  With --workers a step is one call of infaas_sel_select_workers
 (the same plus the worker that serves each answer, over a seeded cluster; 28 B per decision).
+With --scale a step is one call of infaas_sel_scale over 4M seeded scaling requests on the table of
+the configuration (replicate or upgrade on a change in load; 32 B per decision).
 
 Prints ONE JSON line: decisions/s, the roofline of the dominant kernel (algorithmic bytes:
 20 B per decision + the variant table once, against 8 TB/s of HBM) timed with HIP events on
@@ -62,6 +64,92 @@ def measured_traffic(kernel: str, cfg: int, engine: str):
     return rec.get("bytes_per_launch", {}).get(f"config{cfg}/{engine}/{kernel}")
 
 
+SCALE_REQUESTS = 4_000_000
+SCALE_LAMBDA, SCALE_SLACK = 50, 105
+SCALE_BYTES_PER_DECISION = 32    # 5 int32 request fields read + 3 int32 results written
+
+
+def bench_scale(args, cfg, spec, tb) -> int:
+    """The scaling-decision call (Section 4.2.2) timed like the selection."""
+    import numpy as np
+    import torch
+
+    import paper_1905_13348_amd as pkg
+    import workloads
+
+    if args.closest or args.tiered or args.workers or args.engine != "auto":
+        print("bench.py: --scale goes alone", file=sys.stderr)
+        return 2
+    n = min(SCALE_REQUESTS, spec["num_queries"])
+    sc = workloads.make_scaling(cfg, tb)
+    sel = pkg.Selector(tb.num_tasks, tb.batch_sizes, device=0, engine=pkg.ENGINE_AUTO)
+    sel.load_variants(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us)
+    sel.load_scaling(sc.arch_id, sc.sat_qps, sc.hw_cost, sc.load_us, SCALE_LAMBDA, SCALE_SLACK)
+    n_sets = 4
+    host = [workloads.make_scale_requests(cfg, tb, sc, n, chunk=c) for c in range(n_sets)]
+    dev = [[torch.from_numpy(x).cuda() for x in (r.variant, r.instances, r.load_qps, r.slo_us, r.batch_idx)]
+           for r in host]
+    outs = [torch.empty(n, dtype=torch.int32, device="cuda") for _ in range(3)]
+    for i in range(args.warmup):
+        sel.scale(*dev[i % n_sets], *outs)
+    torch.cuda.synchronize()
+    sel.set_timing(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        sel.scale(*dev[(args.warmup + i) % n_sets], *outs)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    timings = sel.get_timings()
+    sel.set_timing(False)
+    ms_per_step = 1e3 * elapsed / args.steps
+    k = timings["scale"]
+    avg_ms = k["total_ms"] / k["launches"]
+    # every request in, every result out, and what the decision reads of the table once: a 16-byte
+    # record per variant and batch size, 20 bytes per variant of places and hardware cost
+    fixed = tb.V * (16 * tb.B + 20)
+    algo = SCALE_BYTES_PER_DECISION * n + fixed
+    achieved = algo / (avg_ms * 1e-3) / 1e9
+    cpu, mismatches = None, None
+    if not args.no_cpu_baseline:
+        import oracle
+        ref = oracle.load_oracle()
+        rq = host[(args.warmup + args.steps - 1) % n_sets]
+        fields = (rq.variant, rq.instances, rq.load_qps, rq.slo_us, rq.batch_idx)
+        prof = (sc.arch_id, sc.sat_qps, sc.hw_cost, sc.load_us, tb.lat_us, SCALE_LAMBDA, SCALE_SLACK)
+        n0 = min(n, 20_000)
+        s0 = time.perf_counter()
+        ref.scale(*prof, *(f[:n0] for f in fields))
+        rate0 = n0 / (time.perf_counter() - s0)
+        m = int(min(n, max(n0, rate0 * args.cpu_seconds)))
+        s0 = time.perf_counter()
+        want = ref.scale(*prof, *(f[:m] for f in fields))
+        dt = time.perf_counter() - s0
+        mismatches = int(sum((g[:m].cpu().numpy() != w).sum() for g, w in zip(outs, want)))
+        cpu = {"value": round(m / dt, 1), "unit": "decisions/s", "cores": ref.num_threads(), "kind": "oracle",
+               "sample": f"first {m} requests of the last timed batch, {dt:.1f} s"}
+    line = {
+        "metric": "variant-selection decisions/sec on 1 MI355X; % of HBM roofline",
+        "value": round(n * args.steps / elapsed, 1), "unit": "decisions/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
+        "config": {"workload": f"scaling decisions (replicate or upgrade on a change in load): {n} requests per step on "
+                               f"the table of config {cfg} ({tb.V} variants in {int(np.unique(sc.arch_id).size)} "
+                               f"architectures, {tb.B} batch sizes), lambda {SCALE_LAMBDA}/s, headroom {SCALE_SLACK}%",
+                   "engine": "auto"},
+        "roofline": {"bound": "hbm", "kernel": "scale", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
+                     "traffic": measured_traffic("scale", cfg, "auto/scale"), "avg_kernel_ms": round(avg_ms, 5),
+                     "algorithmic_bytes_per_launch": int(algo)},
+        "kernels_ms_per_step": {"scale": round(k["total_ms"] / args.steps, 5)},
+        "cpu_baseline": cpu,
+        "parity_sample_mismatches": mismatches,
+    }
+    print(json.dumps(line))
+    sel.destroy()
+    return 0 if not mismatches else 1
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -78,6 +166,9 @@ def main() -> int:
     ap.add_argument("--workers", action="store_true",
                     help="time infaas_sel_select_workers (two-tier selection plus the worker of every answer, "
                          "over a seeded cluster of workers and instances; 28 B per decision)")
+    ap.add_argument("--scale", action="store_true",
+                    help="time infaas_sel_scale (scaling decisions on a change in load: 4M seeded requests, "
+                         "lambda 50/s, headroom 105%%; 32 B per decision) instead of the selection")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -107,6 +198,8 @@ def main() -> int:
     cfg = args.config
     spec = workloads.config_spec(cfg)
     tb = workloads.make_table(cfg)
+    if args.scale:
+        return bench_scale(args, cfg, spec, tb)
     chunks = spec["chunks"]
     per_step = spec["num_queries"] // chunks
     engine = pkg.ENGINE_AUTO if args.engine == "auto" else pkg.ENGINE_SCAN

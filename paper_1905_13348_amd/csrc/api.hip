@@ -973,55 +973,82 @@ int infaas_sel_load_scaling(infaas_sel_t *h, const int32_t *arch_id, const int32
     if (lambda_per_s < 0 || lambda_per_s > 1000 || slack_pct < 0 || slack_pct > 200) return INFAAS_SEL_ERR_OUT_OF_RANGE;
     for (int32_t v = 0; v < V; ++v)
         if (sat_qps[v] < 1 || hw_cost[v] < 0 || hw_cost[v] > 1048576 || load_us[v] < 0) return INFAAS_SEL_ERR_OUT_OF_RANGE;
-    // places: variants grouped by architecture, rows ascending inside a group
-    std::vector<int32_t> row_of((size_t)V);
-    std::iota(row_of.begin(), row_of.end(), 0);
-    std::stable_sort(row_of.begin(), row_of.end(), [&](int32_t a, int32_t b) { return arch_id[a] < arch_id[b]; });
-    std::vector<int4> info((size_t)std::max(V, 1));
-    for (int32_t first = 0; first < V;) {
-        int32_t end = first;
-        while (end < V && arch_id[row_of[(size_t)end]] == arch_id[row_of[(size_t)first]]) ++end;
-        for (int32_t p = first; p < end; ++p) info[(size_t)row_of[(size_t)p]] = make_int4(first, end, p, hw_cost[row_of[(size_t)p]]);
-        first = end;
+    // architectures numbered in ascending order of the caller's codes; their variants, rows ascending
+    std::vector<int32_t> by_arch((size_t)V);
+    std::iota(by_arch.begin(), by_arch.end(), 0);
+    std::stable_sort(by_arch.begin(), by_arch.end(), [&](int32_t a, int32_t b) { return arch_id[a] < arch_id[b]; });
+    std::vector<int2> info((size_t)std::max(V, 1), make_int2(0, 0));
+    std::vector<int32_t> arch_first;   // [A + 1] into by_arch
+    for (int32_t p = 0; p < V; ++p) {
+        if (p == 0 || arch_id[by_arch[(size_t)p]] != arch_id[by_arch[(size_t)p - 1]]) arch_first.push_back(p);
+        info[(size_t)by_arch[(size_t)p]] = make_int2((int32_t)arch_first.size() - 1, hw_cost[by_arch[(size_t)p]]);
     }
-    std::vector<ScaleRec> recs((size_t)std::max<int64_t>((int64_t)B * V, 1));
+    const int32_t A = (int32_t)arch_first.size();
+    arch_first.push_back(V);
+    auto unit_of = [&](int32_t v) {   // cost of one loaded instance, < 2^62
+        return (uint64_t)hw_cost[v] * (1000000ull + (uint64_t)lambda_per_s * (uint64_t)load_us[v]);
+    };
+    std::vector<ScaleRec> own((size_t)std::max<int64_t>((int64_t)B * V, 1), ScaleRec{1u, 0, 0ull});
     for (int32_t b = 0; b < B; ++b)
-        for (int32_t p = 0; p < V; ++p) {
-            const int32_t v = row_of[(size_t)p];
-            ScaleRec &r = recs[(size_t)b * V + p];
-            r.qps = (uint32_t)sat_qps[v];
-            r.lat = h->h_lat[(size_t)v * B + b];
-            r.unit = (uint64_t)hw_cost[v] * (1000000ull + (uint64_t)lambda_per_s * (uint64_t)load_us[v]);   // < 2^62
+        for (int32_t v = 0; v < V; ++v)
+            own[(size_t)b * V + v] = ScaleRec{(uint32_t)sat_qps[v], h->h_lat[(size_t)v * B + b], unit_of(v)};
+    // Candidates of an architecture at a batch size: by descending throughput, and only those that
+    // no other variant beats for every request (at least the throughput, at most the latency, and
+    // a lower cost per instance or the same with a lower row).  Sorted so that whatever beats a
+    // variant comes before it; being beaten is transitive, so the survivors so far are enough to
+    // compare with.
+    std::vector<int2> run((size_t)std::max<int64_t>((int64_t)B * A, 1), make_int2(0, 0));
+    std::vector<ScaleRec> cand;
+    std::vector<int32_t> cand_row;
+    std::vector<int32_t> order;
+    for (int32_t b = 0; b < B; ++b)
+        for (int32_t a = 0; a < A; ++a) {
+            order.assign(by_arch.begin() + arch_first[(size_t)a], by_arch.begin() + arch_first[(size_t)a + 1]);
+            std::sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+                if (sat_qps[x] != sat_qps[y]) return sat_qps[x] > sat_qps[y];
+                const uint64_t ux = unit_of(x), uy = unit_of(y);
+                if (ux != uy) return ux < uy;
+                return x < y;
+            });
+            const size_t first = cand.size();
+            for (int32_t v : order) {
+                const ScaleRec r = own[(size_t)b * V + v];
+                bool beaten = false;
+                for (size_t k = first; k < cand.size() && !beaten; ++k)
+                    beaten = cand[k].lat <= r.lat && (cand[k].unit < r.unit || (cand[k].unit == r.unit && cand_row[k] < v));
+                if (!beaten) { cand.push_back(r); cand_row.push_back(v); }
+            }
+            run[(size_t)b * A + a] = make_int2((int32_t)first, (int32_t)cand.size());
         }
+    if (cand.empty()) { cand.push_back(ScaleRec{1u, 0, 0ull}); cand_row.push_back(0); }
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
     for (void *p : h->scale_mem) (void)hipFree(p);
     h->scale_mem.clear();
     h->scaling_loaded = false;
-    int4 *d_info = nullptr;
-    ScaleRec *d_recs = nullptr;
-    int32_t *d_row_of = nullptr;
-    bool ok = dev_alloc(&d_info, info.size()) == hipSuccess;
-    if (ok) h->scale_mem.push_back(d_info);
-    ok = ok && dev_alloc(&d_recs, recs.size()) == hipSuccess;
-    if (ok) h->scale_mem.push_back(d_recs);
-    ok = ok && dev_alloc(&d_row_of, (size_t)V) == hipSuccess;
-    if (ok) h->scale_mem.push_back(d_row_of);
+    bool ok = true;
+    auto upload = [&](const void *src, size_t bytes) -> void * {
+        void *d = nullptr;
+        if (!ok) return nullptr;
+        if (hipMalloc(&d, std::max<size_t>(bytes, 16)) != hipSuccess) { ok = false; (void)hipGetLastError(); return nullptr; }
+        h->scale_mem.push_back(d);
+        if (bytes && !HIP_OK(hipMemcpy(d, src, bytes, hipMemcpyHostToDevice))) ok = false;
+        return d;
+    };
+    ScaleView sv{};
+    sv.V = V; sv.B = B; sv.A = std::max(A, 1); sv.slack_pct = slack_pct;
+    sv.row_info = (const int2 *)upload(info.data(), info.size() * sizeof(int2));
+    sv.own = (const ScaleRec *)upload(own.data(), own.size() * sizeof(ScaleRec));
+    sv.run = (const int2 *)upload(run.data(), run.size() * sizeof(int2));
+    sv.cand = (const ScaleRec *)upload(cand.data(), cand.size() * sizeof(ScaleRec));
+    sv.cand_row = (const int32_t *)upload(cand_row.data(), cand_row.size() * 4);
     if (!ok) {
-        (void)hipGetLastError();
         for (void *p : h->scale_mem) (void)hipFree(p);
         h->scale_mem.clear();
         return INFAAS_SEL_ERR_OOM;
     }
-    if (!HIP_OK(hipMemcpy(d_info, info.data(), info.size() * sizeof(int4), hipMemcpyHostToDevice)) ||
-        !HIP_OK(hipMemcpy(d_recs, recs.data(), recs.size() * sizeof(ScaleRec), hipMemcpyHostToDevice)) ||
-        (V > 0 && !HIP_OK(hipMemcpy(d_row_of, row_of.data(), (size_t)V * 4, hipMemcpyHostToDevice)))) {
-        for (void *p : h->scale_mem) (void)hipFree(p);
-        h->scale_mem.clear();
-        return INFAAS_SEL_ERR_HIP;
-    }
-    h->sv = ScaleView{V, B, slack_pct, d_info, d_recs, d_row_of};
+    h->sv = sv;
     h->scaling_loaded = true;
     return INFAAS_SEL_OK;
 }

@@ -220,11 +220,14 @@ struct ScaleRec {
     uint64_t unit;    // cost of one loaded instance: C * (1,000,000 + lambda * T_load)
 };
 struct ScaleView {
-    int32_t V, B;
+    int32_t V, B, A;          // variants, batch sizes, architectures
     int32_t slack_pct;
-    const int4 *row_info;     // [V] by caller row: {first, end} of its architecture's run, its own place, hardware cost
-    const ScaleRec *recs;     // [B][V] grouped by architecture, rows ascending inside a run
-    const int32_t *row_of;    // [V] caller row of every place
+    const int2 *row_info;     // [V] by caller row: {number of its architecture, hardware cost}
+    const ScaleRec *own;      // [B][V] by caller row: the running variant's own figures
+    const int2 *run;          // [B][A] {first, end} of the architecture's candidates at that batch size
+    const ScaleRec *cand;     // candidates: per (batch size, architecture) the variants that can ever win an
+                              // upgrade, by descending throughput
+    const int32_t *cand_row;  // their caller rows
 };
 hipError_t launch_scale(const ScaleView &sv, int64_t R, const int32_t *r_variant, const int32_t *r_instances,
                         const int32_t *r_load_qps, const int32_t *r_slo_us, const int32_t *r_batch_idx,
