@@ -5,7 +5,7 @@
 // Section 4.2.1, C * (delta + lambda * T_load * max(delta, 0)) summed over the touched variants.
 //
 // One lane per request.  Per batch size and architecture the library keeps the candidates for an
-// upgrade as 16-byte records {throughput, latency, cost of one loaded instance}, sorted by descending
+// upgrade as records {throughput, latency, cost of one loaded instance, row}, sorted by descending
 // throughput and without the variants that can never win: v loses to w for every request when w has
 // at least v's throughput, at most v's latency and a lower cost per instance (or the same and a lower
 // row), because w then passes every test v passes and needs no more instances.  A lane walks its run
@@ -48,40 +48,42 @@ __global__ __launch_bounds__(kThreads) void k_scale(ScaleView sv, int64_t R, con
         const int32_t b = in ? __builtin_nontemporal_load(r_batch_idx + r) : 0;
         const bool valid = (uint32_t)cur < (uint32_t)sv.V && (uint32_t)b < (uint32_t)sv.B &&
                            (uint32_t)n_cur <= 1000000u && (uint32_t)load <= 1000000000u;
-        const int2 info = sv.row_info[valid ? cur : 0];                 // {architecture, hardware cost}
-        const int64_t col = (int64_t)(valid ? b : 0);
-        const ScaleRec own = sv.own[col * sv.V + (valid ? cur : 0)];
-        const int2 run = sv.run[col * sv.A + info.x];
+        const uint32_t *mine = sv.rows + (int64_t)(valid ? cur : 0) * sv.row_words;
+        const uint4 head = *(const uint4 *)mine;                        // {throughput, architecture, hardware cost, -}
+        const uint64_t own_unit = *(const uint64_t *)(mine + 4);
+        const int32_t own_lat = (int32_t)mine[kScaleRowLat + (valid ? b : 0)];
+        const uint32_t own_qps = head.x;
+        const int2 run = sv.run[(int64_t)(valid ? b : 0) * sv.A + (int32_t)head.y];
         const uint64_t need = (uint64_t)(uint32_t)load * (uint32_t)sv.slack_pct;   // hundredths of a query per second
-        const bool scaling = valid && (uint64_t)own.qps * (uint32_t)n_cur * 100u < need;
+        const bool scaling = valid && (uint64_t)own_qps * (uint32_t)n_cur * 100u < need;
         int32_t action = 0, variant = -1, instances = 0;
         if (scaling) {
             // everything is compared with the credit for unloading the running instances added, so
             // that no difference can become negative
-            const u128 saved = (u128)((uint64_t)(uint32_t)info.y * (uint32_t)n_cur) * 1000000u;
+            const u128 saved = (u128)((uint64_t)head.z * (uint32_t)n_cur) * 1000000u;
             bool have = false;
             u128 best = 0;
-            int32_t best_at = -1;     // place of the best upgrade among the candidates, -1: replication
+            int32_t best_row = -1;    // row of the best upgrade, -1: replication is best
             uint64_t best_n = 0;
-            if (own.lat <= slo) {   // replicate
-                best_n = ceil_div(need, 100u * (uint64_t)own.qps) - (uint32_t)n_cur;
-                best = (u128)own.unit * best_n + saved;
+            if (own_lat <= slo) {   // replicate
+                best_n = ceil_div(need, 100u * (uint64_t)own_qps) - (uint32_t)n_cur;
+                best = (u128)own_unit * best_n + saved;
                 have = true;
             }
             for (int32_t i = run.x; i < run.y; ++i) {   // upgrade
-                const ScaleRec c = sv.cand[i];
-                if (c.qps <= own.qps) break;              // descending: nothing further supports more than cur
+                const ScaleCand c = sv.cand[i];
+                if (c.qps <= own_qps) break;              // descending: nothing further supports more than cur
                 if (c.lat > slo) continue;
                 const uint64_t inst = ceil_div(need, 100u * (uint64_t)c.qps);
                 const u128 cost = (u128)c.unit * inst;
                 // replication keeps a tie; among upgrades of equal cost the lower row wins
                 const bool better = !have || cost < best ||
-                                    (cost == best && best_at >= 0 && sv.cand_row[i] < sv.cand_row[best_at]);
-                if (better) { best = cost; best_at = i; best_n = inst; have = true; }
+                                    (cost == best && best_row >= 0 && c.row < best_row);
+                if (better) { best = cost; best_row = c.row; best_n = inst; have = true; }
             }
-            action = !have ? 3 : (best_at < 0 ? 1 : 2);
+            action = !have ? 3 : (best_row < 0 ? 1 : 2);
             if (have) {
-                variant = best_at < 0 ? cur : sv.cand_row[best_at];
+                variant = best_row < 0 ? cur : best_row;
                 instances = (int32_t)best_n;
             }
         }
