@@ -977,25 +977,25 @@ int infaas_sel_load_scaling(infaas_sel_t *h, const int32_t *arch_id, const int32
     std::vector<int32_t> by_arch((size_t)V);
     std::iota(by_arch.begin(), by_arch.end(), 0);
     std::stable_sort(by_arch.begin(), by_arch.end(), [&](int32_t a, int32_t b) { return arch_id[a] < arch_id[b]; });
-    std::vector<int32_t> arch_no((size_t)std::max(V, 1), 0);
     std::vector<int32_t> arch_first;   // [A + 1] into by_arch
-    for (int32_t p = 0; p < V; ++p) {
+    for (int32_t p = 0; p < V; ++p)
         if (p == 0 || arch_id[by_arch[(size_t)p]] != arch_id[by_arch[(size_t)p - 1]]) arch_first.push_back(p);
-        arch_no[(size_t)by_arch[(size_t)p]] = (int32_t)arch_first.size() - 1;
-    }
     const int32_t A = (int32_t)arch_first.size();
     arch_first.push_back(V);
     auto unit_of = [&](int32_t v) {   // cost of one loaded instance, < 2^62
         return (uint64_t)hw_cost[v] * (1000000ull + (uint64_t)lambda_per_s * (uint64_t)load_us[v]);
     };
-    const int32_t row_words = (kScaleRowLat + B + 7) & ~7;
+    const int32_t Be = (B + 1) & ~1;   // latencies padded to an even count: the pairs behind them stay 8-byte aligned
+    const int32_t row_words = (kScaleRowLat + Be + 2 * B + 7) & ~7;
     std::vector<uint32_t> rows((size_t)std::max(V, 1) * (size_t)row_words, 0u);
-    if (V == 0) rows[0] = 1u;   // the block an invalid request reads: throughput 1, everything else 0
+    if (V == 0) rows[0] = 1u;   // the block an invalid request reads: throughput 1, everything else 0 (it is never used)
     for (int32_t v = 0; v < V; ++v) {
         uint32_t *w = &rows[(size_t)v * (size_t)row_words];
         const uint64_t unit = unit_of(v);
-        w[0] = (uint32_t)sat_qps[v]; w[1] = (uint32_t)arch_no[(size_t)v]; w[2] = (uint32_t)hw_cost[v];
-        w[4] = (uint32_t)unit; w[5] = (uint32_t)(unit >> 32);
+        const double per_inv = 1.0 / (100.0 * (double)sat_qps[v]);
+        w[0] = (uint32_t)sat_qps[v]; w[1] = (uint32_t)hw_cost[v];
+        w[2] = (uint32_t)unit; w[3] = (uint32_t)(unit >> 32);
+        std::memcpy(&w[4], &per_inv, 8);
         for (int32_t b = 0; b < B; ++b) w[kScaleRowLat + b] = (uint32_t)h->h_lat[(size_t)v * B + b];
     }
     // Candidates of an architecture at a batch size: by descending throughput, and only those that
@@ -1003,8 +1003,8 @@ int infaas_sel_load_scaling(infaas_sel_t *h, const int32_t *arch_id, const int32
     // a lower cost per instance or the same with a lower row).  Sorted so that whatever beats a
     // variant comes before it; being beaten is transitive, so the survivors so far are enough to
     // compare with.
-    std::vector<int2> run((size_t)std::max<int64_t>((int64_t)B * A, 1), make_int2(0, 0));
     std::vector<ScaleCand> cand;
+    std::vector<int32_t> cand_row;
     std::vector<int32_t> order;
     for (int32_t b = 0; b < B; ++b)
         for (int32_t a = 0; a < A; ++a) {
@@ -1017,15 +1017,18 @@ int infaas_sel_load_scaling(infaas_sel_t *h, const int32_t *arch_id, const int32
             });
             const size_t first = cand.size();
             for (int32_t v : order) {
-                const ScaleCand r{(uint32_t)sat_qps[v], h->h_lat[(size_t)v * B + b], unit_of(v), v, {0, 0, 0}};
+                const ScaleCand r{(uint32_t)sat_qps[v], h->h_lat[(size_t)v * B + b], unit_of(v)};
                 bool beaten = false;
                 for (size_t k = first; k < cand.size() && !beaten; ++k)
-                    beaten = cand[k].lat <= r.lat && (cand[k].unit < r.unit || (cand[k].unit == r.unit && cand[k].row < v));
-                if (!beaten) cand.push_back(r);
+                    beaten = cand[k].lat <= r.lat && (cand[k].unit < r.unit || (cand[k].unit == r.unit && cand_row[k] < v));
+                if (!beaten) { cand.push_back(r); cand_row.push_back(v); }
             }
-            run[(size_t)b * A + a] = make_int2((int32_t)first, (int32_t)cand.size());
+            for (int32_t p = arch_first[(size_t)a]; p < arch_first[(size_t)a + 1]; ++p) {   // into every row's block
+                uint32_t *w = &rows[(size_t)by_arch[(size_t)p] * (size_t)row_words + kScaleRowLat + Be + 2 * b];
+                w[0] = (uint32_t)first; w[1] = (uint32_t)cand.size();
+            }
         }
-    if (cand.empty()) cand.push_back(ScaleCand{1u, 0, 0ull, 0, {0, 0, 0}});
+    if (cand.empty()) { cand.push_back(ScaleCand{1u, 0, 0ull}); cand_row.push_back(0); }
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
@@ -1042,11 +1045,11 @@ int infaas_sel_load_scaling(infaas_sel_t *h, const int32_t *arch_id, const int32
         return d;
     };
     ScaleView sv{};
-    sv.V = V; sv.B = B; sv.A = std::max(A, 1); sv.slack_pct = slack_pct;
+    sv.V = V; sv.B = B; sv.slack_pct = slack_pct; sv.pairs_at = kScaleRowLat + Be;
     sv.row_words = row_words;
     sv.rows = (const uint32_t *)upload(rows.data(), rows.size() * 4);
-    sv.run = (const int2 *)upload(run.data(), run.size() * sizeof(int2));
     sv.cand = (const ScaleCand *)upload(cand.data(), cand.size() * sizeof(ScaleCand));
+    sv.cand_row = (const int32_t *)upload(cand_row.data(), cand_row.size() * 4);
     if (!ok) {
         for (void *p : h->scale_mem) (void)hipFree(p);
         h->scale_mem.clear();

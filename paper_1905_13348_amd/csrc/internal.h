@@ -215,25 +215,26 @@ hipError_t launch_step_workers(const IndexView &ix, const int32_t *row_worker, i
 
 // Scaling decision on a change in load (Section 4.2.2).
 // What a request reads about its running variant sits in one block of row_words 32-bit words per
-// caller row (a multiple of 8 words, so a block never straddles more cache lines than it must):
-// word 0 saturation throughput, 1 number of its architecture, 2 hardware cost, 4-5 cost of one
-// loaded instance C * (1,000,000 + lambda * T_load), 6 + b inference latency at batch size b.
+// caller row (a multiple of 8 words; 32 words = one 128-byte line for 8 batch sizes):
+// word 0 saturation throughput Q, 1 hardware cost, 2-3 cost of one loaded instance
+// C * (1,000,000 + lambda * T_load), 4-5 the double 1 / (100 Q), 6 + b inference latency at batch
+// size b, then from word
+// 6 + B (rounded up to even) on, for every batch size, {first, end} of the candidates of its architecture.
 constexpr int kScaleRowLat = 6;
 struct ScaleCand {    // one candidate for an upgrade
     uint32_t qps;     // saturation throughput
     int32_t lat;      // inference latency at the list's batch size
     uint64_t unit;    // cost of one loaded instance
-    int32_t row;      // caller row
-    int32_t pad[3];
 };
 struct ScaleView {
-    int32_t V, B, A;          // variants, batch sizes, architectures
+    int32_t V, B;             // variants, batch sizes
     int32_t slack_pct;
     int32_t row_words;
+    int32_t pairs_at;         // word of a block where the {first, end} pairs start (even)
     const uint32_t *rows;     // [V][row_words]
-    const int2 *run;          // [B][A] {first, end} of the architecture's candidates at that batch size
     const ScaleCand *cand;    // per (batch size, architecture) the variants that can ever win an upgrade, by
                               // descending throughput
+    const int32_t *cand_row;  // their caller rows
 };
 hipError_t launch_scale(const ScaleView &sv, int64_t R, const int32_t *r_variant, const int32_t *r_instances,
                         const int32_t *r_load_qps, const int32_t *r_slo_us, const int32_t *r_batch_idx,
