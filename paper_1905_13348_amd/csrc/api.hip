@@ -139,7 +139,7 @@ struct infaas_sel {
     void free_index()
     {
         (void)hipFree(ix.pool); (void)hipFree(ix.step_row); (void)hipFree(ix.ctrl);  // hdr lives in pool's allocation
-        (void)hipFree(ix.step_worker);
+        (void)hipFree(ix.step_worker); (void)hipFree(ix.hot_worker);
         (void)hipFree(d_park);
         d_park = nullptr;
         park_bytes = 0;
@@ -165,8 +165,9 @@ void infaas_sel::drop_inactive()
     worker_mem.clear();
     wv = WorkerView{};
     workers_loaded = workers_dirty = false;
-    (void)hipFree(ix.step_worker);
+    (void)hipFree(ix.step_worker); (void)hipFree(ix.hot_worker);
     ix.step_worker = nullptr;
+    ix.hot_worker = nullptr;
     (void)hipFree(d_open); (void)hipFree(d_open_count);
     d_open = d_open_count = nullptr;
     open_queries = open_bytes = 0;
@@ -806,6 +807,7 @@ int tiered_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t
             LaunchTimer tm(h, INFAAS_SEL_K_STEP_WORKERS, st);
             if (!HIP_OK(launch_step_workers(t->ix, h->wv.row_worker + (int64_t)tier * h->V, h->V, st, tm.ev())))
                 return INFAAS_SEL_ERR_HIP;
+            if (!HIP_OK(launch_hot_workers(t->ix, t->T * t->B, st))) return INFAAS_SEL_ERR_HIP;
             t->steps_stale = false;
         }
     }
@@ -920,6 +922,15 @@ int infaas_sel_load_workers(infaas_sel_t *h, int32_t num_workers, const int32_t 
     wv.row_worker = upload({}, (size_t)2 * V);
     for (infaas_sel *t : {h, h->inactive}) {
         if (ok && !t->ix.step_worker && dev_alloc(&t->ix.step_worker, t->ix.step_cap) != hipSuccess) {
+            ok = false;
+            (void)hipGetLastError();
+        }
+        // 16-bit copies of the workers of the hot steps, for the lookup kernel's LDS
+        (void)hipFree(t->ix.hot_worker);
+        t->ix.hot_worker = nullptr;
+        const size_t hot = (size_t)t->T * t->B * t->ix.hot_rows;
+        if (ok && hot > 0 && t->index_lds_bytes > 0 && W <= 65535 &&
+            dev_alloc(&t->ix.hot_worker, hot + 8) != hipSuccess) {
             ok = false;
             (void)hipGetLastError();
         }

@@ -648,6 +648,15 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             if ((uint32_t)wave * per_wave + c0 < nchunks && i < nvec) lp[i] = gp[i];
         }
     }
+    // worker selection: 16-bit workers of the hot steps behind the bodies (lds_cap excludes them)
+    const bool hot_w = kLds && kWorker && ix.hot_worker != nullptr;
+    const uint32_t hotw_base = rebase + lds_cap;
+    if (hot_w) {
+        const uint32_t nw = (nhdr - 1u) * ix.hot_rows;   // 16-bit entries; the array has 8 more behind them
+        const uint32_t *gw = (const uint32_t *)ix.hot_worker;
+        uint32_t *lw = lds_w + ((kLdsCtrlBytes + hdr_bytes + lds_cap) >> 2);
+        for (uint32_t i = tid; i < (nw + 1u) >> 1; i += kSelThreads) lw[i] = gw[i];
+    }
     if (tid < 4) lds_w[tid] = 0u;
     __syncthreads();
 
@@ -683,7 +692,9 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     uint32_t p_base[kPerThread];
     bool p_inl[kPerThread];
     int32_t p_qi[kPerThread];   // second tier only: where each result goes
-    int32_t p_wk[kPerThread];   // worker selection only: the worker of each answer
+    int32_t p_wk[kPerThread];   // worker selection only: the worker of each answer, gathered from global memory ...
+    int32_t p_wl[kPerThread];   // ... or its 16-bit copy from LDS (-1: not there)
+    auto p_worker = [&](int k) -> int32_t { return p_wl[k] >= 0 ? (p_wl[k] == 0xFFFF ? -1 : p_wl[k]) : p_wk[k]; };
     auto p_val = [&](int k) -> int32_t { return p_inl[k] ? (int32_t)((p_base[k] << 16) | (uint32_t)p_lrow[k]) : p_grow[k]; };
     auto store_unit = [&]() {
         if (p_i0 < 0) return;
@@ -692,7 +703,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             for (int k = 0; k < kPerThread; ++k)
                 if (p_qi[k] >= 0 && p_val(k) >= 0) {
                     q.out[p_qi[k]] = p_val(k); q.tier[p_qi[k]] = 2;
-                    if (kWorker) q.worker[p_qi[k]] = p_wk[k];
+                    if (kWorker) q.worker[p_qi[k]] = p_worker(k);
                 }
         } else if (aligned && p_i0 + kSpan <= q.n) {
 #pragma unroll
@@ -705,7 +716,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                     __builtin_nontemporal_store(t4, (v4i *)((char *)q.tier + (uint32_t)p_i0 * 4u) + 64 * h);
                 }
                 if (kWorker) {
-                    const v4i w4 = {p_wk[4 * h], p_wk[4 * h + 1], p_wk[4 * h + 2], p_wk[4 * h + 3]};
+                    const v4i w4 = {p_worker(4 * h), p_worker(4 * h + 1), p_worker(4 * h + 2), p_worker(4 * h + 3)};
                     __builtin_nontemporal_store(w4, (v4i *)((char *)q.worker + (uint32_t)p_i0 * 4u) + 64 * h);
                 }
             }
@@ -716,7 +727,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                     q.out[p_i0 + qoff(k)] = p_val(k);
                     if (kClosest) q.closest[p_i0 + qoff(k)] = p_val(k);
                     if (kFirst) q.tier[p_i0 + qoff(k)] = p_val(k) >= 0;
-                    if (kWorker) q.worker[p_i0 + qoff(k)] = p_wk[k];
+                    if (kWorker) q.worker[p_i0 + qoff(k)] = p_worker(k);
                 }
         }
     };
@@ -772,8 +783,18 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             p_base[k] = (rbase[k] >> ((step * ix.row_hi_bits) & 31u)) & row_hi_mask;
             p_grow[k] = *(const int32_t *)((const char *)ix.step_row + ((hit && !inl) ? (rec[k] + step) * 4u : 0u));
             p_inl[k] = inl;
-            // the worker of the step, by the same kind of gather (entry 0, for no step, is -1)
-            if (kWorker) p_wk[k] = *(const int32_t *)((const char *)ix.step_worker + (hit ? (rec[k] + step) * 4u : 0u));
+            // the worker of the step: of a hot step from LDS, else by the same kind of gather as the
+            // row (entry 0, for no step, is -1)
+            if (kWorker) {
+                const bool wl = hot_w && inl;
+                p_wk[k] = *(const int32_t *)((const char *)ix.step_worker + ((hit && !wl) ? (rec[k] + step) * 4u : 0u));
+                p_wl[k] = -1;
+                if (hot_w) {   // every lane reads (lanes without a hot step the first entry) and keeps it only if it is its own
+                    const uint32_t slice = kSecond ? (uint32_t)cur.tk[k] : sl_of[k];
+                    const uint32_t w16 = lmem.ld16(hotw_base + (wl ? (__umul24(slice, ix.hot_rows) + step) * 2u : 0u), 0u);
+                    p_wl[k] = wl ? (int32_t)w16 : -1;
+                }
+            }
             if (kSecond) p_qi[k] = cur.bi[k];
             // parked: a miss that the second body / the scan may still turn into a hit; in the
             // closest-variant mode also every final miss of a query inside the table
@@ -1035,8 +1056,14 @@ hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const Q
         hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes);
         if (e != hipSuccess) return e;
-        return launch_kernel(ev, kernel, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), lds_bytes, st, tv, ix, q,
-                             park_mem, lds_bytes - fixed);
+        // the worker modes keep the 16-bit workers of the hot steps behind the bodies
+        uint32_t hot = 0;
+        if (q.pass >= 4 && ix.hot_worker) hot = ((uint32_t)tv.S * ix.hot_rows * 2u + 15u) & ~15u;
+        if (hot + 1024u > lds_bytes - fixed) hot = 0;   // (never with a sensible table; the kernel then must not look for them)
+        IndexView ixk = ix;
+        if (!hot) ixk.hot_worker = nullptr;
+        return launch_kernel(ev, kernel, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), lds_bytes, st, tv, ixk, q,
+                             park_mem, lds_bytes - fixed - hot);
     }
     auto kernel = q.pass == 1 ? k_index_select<false, 1> : q.pass == 2 ? k_index_select<false, 2> :
                   q.pass == 3 ? k_index_select<false, 3> : q.pass == 4 ? k_index_select<false, 4> :

@@ -96,6 +96,8 @@ struct IndexView {
     uint32_t pool_bytes;
     int32_t *step_row;   // caller row of every step; entry 0 is unused
     int32_t *step_worker;// worker that serves the row of every step (worker selection), else null; entry 0 is -1
+    uint16_t *hot_worker;// [S][hot_rows] the same for the first hot_rows steps of every slice, 0xFFFF for -1, for
+                         // the lookup kernel's LDS; null when there are no hot rows or workers above 65534
     uint32_t step_cap;
     uint32_t hot_rows;   // rows kept in front of the first body of every slice (fills the LDS left over)
     uint32_t row_hi_bits;// bits of a row number above its low 16
@@ -212,6 +214,8 @@ hipError_t launch_worker_tables(const WorkerView &wv, hipStream_t st, const Laun
 // ix.step_worker[j] = row_worker[ix.step_row[j]] for every step of the index (row_worker: num_rows entries).
 hipError_t launch_step_workers(const IndexView &ix, const int32_t *row_worker, int32_t num_rows, hipStream_t st,
                                const LaunchEvents *ev = nullptr);
+// ix.hot_worker from ix.step_worker (num_slices = S of the table the index belongs to); no-op without hot_worker.
+hipError_t launch_hot_workers(const IndexView &ix, int32_t num_slices, hipStream_t st, const LaunchEvents *ev = nullptr);
 
 // Scaling decision on a change in load (Section 4.2.2).
 // What a request reads about its running variant sits in one block of row_words 32-bit words per

@@ -92,7 +92,28 @@ __global__ __launch_bounds__(kThreads) void k_step_workers(IndexView ix, const i
     ix.step_worker[j] = (uint32_t)row < (uint32_t)num_rows ? row_worker[row] : -1;
 }
 
+// One lane per (slice, hot step): the 16-bit copy of the step's worker that the lookup kernel keeps
+// in LDS.  Places past the slice's last step are never read by the lookup.
+__global__ __launch_bounds__(kThreads) void k_hot_workers(IndexView ix, int32_t num_slices)
+{
+    const uint32_t i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= (uint32_t)num_slices * ix.hot_rows) return;
+    const uint32_t s = i / ix.hot_rows, step = i - s * ix.hot_rows;
+    const uint4 hdr = ix.hdr[s];
+    const uint32_t at = hdr.z + step;   // the slice's first entry in step_row / step_worker, plus the step
+    const int32_t w = ((hdr.y & kHdrPark) || at >= ix.step_cap) ? -1 : ix.step_worker[at];
+    ix.hot_worker[i] = (uint32_t)w < 0xFFFFu ? (uint16_t)w : (uint16_t)0xFFFFu;
+}
+
 }  // namespace
+
+hipError_t launch_hot_workers(const IndexView &ix, int32_t num_slices, hipStream_t st, const LaunchEvents *ev)
+{
+    const int64_t n = (int64_t)num_slices * ix.hot_rows;
+    if (!ix.hot_worker || n <= 0) return hipSuccess;
+    return launch_kernel(ev, k_hot_workers, dim3((unsigned)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, st, ix,
+                         num_slices);
+}
 
 hipError_t launch_worker_report(const WorkerView &wv, int32_t n, const int32_t *worker_idx, const int32_t *util,
                                 int32_t m, const int32_t *inst_idx, const int32_t *load, hipStream_t st,
