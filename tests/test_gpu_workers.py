@@ -108,6 +108,21 @@ def test_workers_long_staircases(oracle_lib, steps):
     sel.destroy()
 
 
+def test_workers_more_than_16_bits(oracle_lib):
+    """70,000 workers: worker numbers no longer fit the 16-bit copies the lookup keeps for the first
+    steps of every slice, so every worker comes from the full-width tables."""
+    rng = np.random.default_rng(29)
+    tb = workloads.make_table(0)
+    st = workloads.make_states(0, tb.V)
+    cl = _random_cluster(rng, tb.V, st.state, 1000, W=70_000)
+    sel = make_selector(tb, engine=0)
+    sel.load_states(st.state, st.load_us)
+    load_cluster(sel, cl)
+    want = _check(oracle_lib, sel, tb, st.state, st.load_us, cl, query_args(workloads.make_queries(0)), "70000 workers")
+    assert want[2].max() > 65535
+    sel.destroy()
+
+
 def test_workers_empty_cluster(oracle_lib):
     """No workers and no instances at all: variant and tier as ever, worker -1 everywhere."""
     tb = workloads.make_table(0)
