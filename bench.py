@@ -169,6 +169,10 @@ def main() -> int:
     ap.add_argument("--scale", action="store_true",
                     help="time infaas_sel_scale (scaling decisions on a change in load: 4M seeded requests, "
                          "lambda 50/s, headroom 105%%; 32 B per decision) instead of the selection")
+    ap.add_argument("--graph", action="store_true",
+                    help="after the timed steps (which give the kernel times), capture the steps into HIP graphs "
+                         "and time the same number of steps again as graph replays: value and ms_per_step are "
+                         "then those of the replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -273,6 +277,22 @@ def main() -> int:
     timings = sel.get_timings()
     sel.set_timing(False)
     elapsed = t1 - t0
+    if args.graph:
+        # the same steps once more as graph replays, continuing the sequence of load reports
+        period = n_sets
+        graphs = []
+        for j in range(period):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                step(j)
+            graphs.append(g)
+        first = args.warmup + args.steps
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graphs[(first + i) % period].replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
     value = per_step * args.steps / elapsed
 
@@ -311,11 +331,11 @@ def main() -> int:
     if not args.no_cpu_baseline:
         import oracle
         ref = oracle.load_oracle()
-        last = (args.warmup + args.steps - 1)
+        last = (args.warmup + args.steps * (2 if args.graph else 1) - 1)
         q = host_q[last % n_sets]
         queue = tb.queue_us.copy()
         if updates:  # replay the load reports in the order the steps applied them
-            for i in range(args.warmup + args.steps):
+            for i in range(last + 1):
                 up = updates[i % len(updates)][2]
                 ref.update_load(queue, up.variant_idx, up.queue_us)
         fields = (q.task, q.slo_us, q.min_acc_bp, q.batch_idx)
@@ -324,7 +344,7 @@ def main() -> int:
         if args.workers:
             util, iload = cluster.worker_util.copy(), cluster.inst_load.copy()
             if worker_updates:
-                for i in range(args.warmup + args.steps):
+                for i in range(last + 1):
                     wu = worker_updates[i % len(worker_updates)][1]
                     ref.update_worker_util(util, wu.worker_idx, wu.worker_util)
                     ref.update_instance_load(iload, wu.inst_idx, wu.inst_load)
@@ -364,7 +384,7 @@ def main() -> int:
                                + (", state-aware two-tier selection (variant and tier arrays)" if args.tiered else "")
                                + (f", two-tier selection with worker selection over {cluster.W} workers and "
                                   f"{cluster.I} instances (variant, tier and worker arrays)" if args.workers else ""),
-                   "engine": args.engine},
+                   "engine": args.engine, "launch": "hip graph replay" if args.graph else "stream"},
         "roofline": roofline,
         "whole_step_frac_of_hbm_roofline": round(whole_frac, 5),
         "kernels_ms_per_step": {k: round(v["total_ms"] / args.steps, 5) for k, v in active.items()},

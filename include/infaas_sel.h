@@ -250,6 +250,9 @@ int infaas_sel_update_workers(infaas_sel_t *h, int32_t n, const int32_t *d_worke
  * infaas_sel_select_tiered plus the worker: arrays as there, and
  *   d_out_worker  [N]  DEVICE: the worker that serves d_out_variant, or -1 (no variant, or no
  *                      worker for it, see above)
+ * The first call after a report (of load, state or workers) also enqueues the small kernels
+ * that bring the per-variant workers up to date: a caller who captures this call into a HIP
+ * graph has to capture the reports with it, or capture again after a report.
  * Errors: INVALID_ARG, NOT_LOADED (no states or no workers loaded), HIP, OOM.
  */
 int infaas_sel_select_workers(infaas_sel_t *h, int64_t N,
