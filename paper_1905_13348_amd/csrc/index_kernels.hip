@@ -556,25 +556,27 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     const int32_t u_begin = kSecond ? 0 : (int32_t)(((int64_t)nunits * blockIdx.x) / gridDim.x);
     const int32_t u_end = kSecond ? nunits : (int32_t)(((int64_t)nunits * (blockIdx.x + 1)) / gridDim.x);
     // Query fields of one unit for this lane (unit < 0: nothing left; the fields then describe a
-    // query outside the table).  Second tier: tk holds the slice and bi the query's number (-1: no
+    // query outside the table).  Second tier: tk holds the slice and bi the query's number (negative: no
     // record).
     struct Fields {
-        int32_t tk[kPerThread], sl[kPerThread], am[kPerThread], bi[kPerThread], unit;
+        int32_t unit;   // (first: behind bi, the compiler reads bi[k] and it with one wide load, through memory)
+        int32_t tk[kPerThread], sl[kPerThread], am[kPerThread], bi[kPerThread];
     };
-    auto load_unit = [&](Fields &f, int32_t unit) {
+    constexpr int32_t kNoRecord = -1;
+    auto load_unit = [&](Fields &f, int32_t unit) __attribute__((always_inline)) {
         f.unit = unit;
         const int32_t i0 = unit * kUnit + lane * 4;
         if (unit < 0) {
 #pragma unroll
-            for (int k = 0; k < kPerThread; ++k) { f.tk[k] = kSecond ? tv.S : -1; f.sl[k] = 0; f.am[k] = 0; f.bi[k] = kSecond ? -1 : 0; }
+            for (int k = 0; k < kPerThread; ++k) { f.tk[k] = kSecond ? tv.S : -1; f.sl[k] = 0; f.am[k] = 0; f.bi[k] = kSecond ? kNoRecord : 0; }
         } else if (kSecond) {
 #pragma unroll
             for (int k = 0; k < kPerThread; ++k) {   // record k of a lane: 64 records behind record k - 1
                 const int32_t r = unit * kUnit + k * 64 + lane;
                 const v4i e = open_in[r < open_n ? r : 0];
-                f.bi[k] = r < open_n ? e.x : -1;
-                f.sl[k] = e.y; f.am[k] = e.z;
-                f.tk[k] = r < open_n ? e.w : tv.S;
+                f.tk[k] = r < open_n ? e.w : tv.S;   // (members in the order of the branch above: the compiler
+                f.sl[k] = e.y; f.am[k] = e.z;        // merges the branches' last stores, and through a pointer
+                f.bi[k] = r < open_n ? e.x : kNoRecord;   // if they go to different members)
             }
         } else if (aligned && i0 + kSpan <= q.n) {
             const uint32_t off = (uint32_t)i0 * 4u;   // one 32-bit byte offset for all four arrays (n <= 2^28)
@@ -739,7 +741,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         if (lane == 0) at = atomicAdd(&s_open, count);
         return (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
     };
-    auto stage = [&](Fields &cur) {
+    auto stage = [&](Fields &cur) __attribute__((always_inline)) {
         const int32_t i0 = kSecond ? 0 : cur.unit * kUnit + lane * 4;
         store_unit();                                   // results of the previous unit
         // slice header; queries outside the table use the header of the empty slice (entry S)
