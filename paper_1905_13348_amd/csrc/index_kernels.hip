@@ -552,6 +552,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     const v4i *open_in = (const v4i *)q.open + (int64_t)blockIdx.x * q.open_cap;
     v4i *open_out = (v4i *)q.open + (int64_t)blockIdx.x * q.open_cap;
     const int32_t open_n = kSecond ? q.open_count[blockIdx.x] : 0;
+    if (kSecond && open_n == 0) return;   // the whole workgroup: nothing was left open in its share
     const int32_t nunits = ((kSecond ? open_n : q.n) + kUnit - 1) / kUnit;
     const int32_t u_begin = kSecond ? 0 : (int32_t)(((int64_t)nunits * blockIdx.x) / gridDim.x);
     const int32_t u_end = kSecond ? nunits : (int32_t)(((int64_t)nunits * (blockIdx.x + 1)) / gridDim.x);
