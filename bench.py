@@ -180,7 +180,7 @@ def main() -> int:
                          "scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; queries would shard across GPUs with no "
+        print("bench.py: this library runs on ONE GPU; queries would shard across GPUs with no "
               "exchange step, but no multi-GPU path exists here. Use --gpus 1.", file=sys.stderr)
         return 2
 
