@@ -54,3 +54,62 @@ def test_load_update():
     u = workloads.make_load_update(4, 100_000, chunk=1)
     assert u.variant_idx.size == 10_000 and np.unique(u.variant_idx).size == 10_000
     assert u.queue_us.min() >= 0 and u.queue_us.max() <= 200_000
+
+
+def test_states_and_state_reports():
+    tb = workloads.make_table(1)
+    a, b = workloads.make_states(1, tb.V), workloads.make_states(1, tb.V)
+    assert np.array_equal(a.state, b.state) and np.array_equal(a.load_us, b.load_us)
+    assert a.state.dtype == np.int32 and a.state.shape == (tb.V,) and set(np.unique(a.state)) == {0, 1, 2, 3}
+    frac = np.bincount(a.state) / tb.V
+    assert abs(frac[0] - 0.5) < 0.02 and abs(frac[1] - 0.4) < 0.02
+    assert a.load_us.min() >= 100 and a.load_us.max() <= 5_000_000
+    assert (a.load_us.astype(np.int64)[:, None] + tb.lat_us <= np.iinfo(np.int32).max).all()
+    u, v = workloads.make_state_update(1, tb.V, 1), workloads.make_state_update(1, tb.V, 2)
+    assert np.unique(u.variant_idx).size == u.variant_idx.size == round(0.05 * tb.V)
+    assert not np.array_equal(u.variant_idx, v.variant_idx)
+    assert u.state.min() >= 0 and u.state.max() <= 3
+
+
+def test_cluster_and_worker_reports():
+    tb = workloads.make_table(1)
+    st = workloads.make_states(1, tb.V)
+    a, b = workloads.make_workers(1, st), workloads.make_workers(1, st)
+    for x, y in zip((a.variant_hw, a.worker_hw, a.worker_util, a.inst_variant, a.inst_worker, a.inst_load),
+                    (b.variant_hw, b.worker_hw, b.worker_util, b.inst_variant, b.inst_worker, b.inst_load)):
+        assert x.dtype == np.int32 and np.array_equal(x, y)
+    assert a.W == 256 and a.variant_hw.shape == (tb.V,)
+    assert a.worker_util.min() >= 0 and a.worker_util.max() <= 10_000 and a.inst_load.min() >= 0
+    # instances: only of loaded variants, on workers of the variant's hardware, at most 8 each, distinct workers
+    assert (st.state[a.inst_variant] != 0).all()
+    assert np.array_equal(a.worker_hw[a.inst_worker], a.variant_hw[a.inst_variant])
+    per = np.bincount(a.inst_variant, minlength=tb.V)
+    assert per.max() <= 8 and (per[st.state != 0] >= 1).all() and (per[st.state == 0] == 0).all()
+    pairs = a.inst_variant.astype(np.int64) * a.W + a.inst_worker
+    assert np.unique(pairs).size == pairs.size
+    u = workloads.make_worker_update(1, a.W, a.I, 1)
+    assert np.unique(u.worker_idx).size == u.worker_idx.size == round(0.1 * a.W)
+    assert np.unique(u.inst_idx).size == u.inst_idx.size == round(0.1 * a.I)
+    assert u.worker_util.max() <= 10_000 and u.inst_load.max() <= 1000 and u.inst_idx.max() < a.I
+
+
+def test_scaling_profiles_and_requests():
+    tb = workloads.make_table(1)
+    a, b = workloads.make_scaling(1, tb), workloads.make_scaling(1, tb)
+    for x, y in zip((a.arch_id, a.sat_qps, a.hw_cost, a.load_us), (b.arch_id, b.sat_qps, b.hw_cost, b.load_us)):
+        assert x.dtype == np.int32 and x.shape == (tb.V,) and np.array_equal(x, y)
+    assert a.sat_qps.min() >= 1 and a.hw_cost.min() >= 50 and a.hw_cost.max() <= 2000 and a.load_us.min() >= 100
+    # an architecture belongs to one task; about 12 variants each
+    task_of = {}
+    for arch, task in zip(a.arch_id.tolist(), tb.task_id.tolist()):
+        assert task_of.setdefault(arch, task) == task
+    sizes = np.bincount(a.arch_id)
+    assert 8 < sizes.mean() < 16
+    r = workloads.make_scale_requests(1, tb, a, 50_000)
+    assert r.R == 50_000 and r.variant.min() >= 0 and r.variant.max() < tb.V
+    assert r.instances.min() >= 1 and r.load_qps.min() >= 0 and r.load_qps.max() <= 1_000_000_000
+    assert r.batch_idx.min() >= 0 and r.batch_idx.max() < tb.B
+    need = r.load_qps.astype(np.int64) * 105 > a.sat_qps[r.variant].astype(np.int64) * r.instances * 100
+    assert 0.75 < need.mean() < 0.95     # most requests need scaling, some do not
+    r2 = workloads.make_scale_requests(1, tb, a, 50_000, chunk=1)
+    assert not np.array_equal(r.variant, r2.variant)
