@@ -205,6 +205,32 @@ def test_workers_config2_sampled(oracle_lib):
     sel.destroy()
 
 
+def test_workers_config3_sampled(oracle_lib):
+    """Config 3's table (1,000 tasks, 8,000 slices: only part of either index fits in LDS, so both
+    tiers also answer from the copies in global memory) with 4M queries: variant, tier and worker of
+    120,000 sampled queries against the oracle, and the cheap properties on all of them."""
+    cfg, n = 3, 4_000_000
+    tb = workloads.make_table(cfg)
+    st = workloads.make_states(cfg, tb.V)
+    wk = workloads.make_workers(cfg, st)
+    q = workloads.make_queries(cfg, n=n)
+    sel = make_selector(tb, engine=0)
+    sel.load_states(st.state, st.load_us)
+    load_cluster(sel, cluster_args(wk))
+    print(f"worker case config3: V={tb.V} T={tb.num_tasks} W={wk.W} I={wk.I} N={n}", flush=True)
+    got = gpu_select_workers(sel, *query_args(q))
+    rng = np.random.default_rng(8)
+    pick = np.concatenate([np.arange(2000), n - 1 - np.arange(2000), rng.choice(n, 116_000, replace=False)])
+    want = oracle_lib.select_workers(*table_args(tb), st.state, st.load_us, *cluster_args(wk),
+                                     *(x[pick] for x in query_args(q)))
+    for g, w in zip(got, want):
+        assert np.array_equal(g[pick], w)
+    assert all((want[1] == t).sum() > 1000 for t in (0, 1, 2))
+    assert np.array_equal(got[0] >= 0, got[1] > 0) and np.array_equal(got[0] >= 0, got[2] >= 0)
+    assert (tb.task_id[got[0][got[0] >= 0]] == q.task[got[0] >= 0]).all()
+    sel.destroy()
+
+
 def test_workers_errors():
     import paper_1905_13348_amd as lib
     import torch
