@@ -1014,8 +1014,11 @@ int infaas_sel_load_scaling(infaas_sel_t *h, const int32_t *arch_id, const int32
     // a lower cost per instance or the same with a lower row).  Sorted so that whatever beats a
     // variant comes before it; being beaten is transitive, so the survivors so far are enough to
     // compare with.
-    std::vector<ScaleCand> cand;
-    std::vector<int32_t> cand_row;
+    // A list's block: its candidates (16 bytes each), then their caller rows (4 bytes each), starting
+    // on a 128-byte line, so that a lookup of up to six candidates touches one line.
+    std::vector<ScaleCand> cand;          // all blocks, in units of 16 bytes
+    std::vector<ScaleCand> list;
+    std::vector<int32_t> list_row;
     std::vector<int32_t> order;
     for (int32_t b = 0; b < B; ++b)
         for (int32_t a = 0; a < A; ++a) {
@@ -1026,20 +1029,26 @@ int infaas_sel_load_scaling(infaas_sel_t *h, const int32_t *arch_id, const int32
                 if (ux != uy) return ux < uy;
                 return x < y;
             });
-            const size_t first = cand.size();
+            list.clear();
+            list_row.clear();
             for (int32_t v : order) {
                 const ScaleCand r{(uint32_t)sat_qps[v], h->h_lat[(size_t)v * B + b], unit_of(v)};
                 bool beaten = false;
-                for (size_t k = first; k < cand.size() && !beaten; ++k)
-                    beaten = cand[k].lat <= r.lat && (cand[k].unit < r.unit || (cand[k].unit == r.unit && cand_row[k] < v));
-                if (!beaten) { cand.push_back(r); cand_row.push_back(v); }
+                for (size_t k = 0; k < list.size() && !beaten; ++k)
+                    beaten = list[k].lat <= r.lat && (list[k].unit < r.unit || (list[k].unit == r.unit && list_row[k] < v));
+                if (!beaten) { list.push_back(r); list_row.push_back(v); }
             }
+            const size_t first = (cand.size() + 7) & ~(size_t)7, n = list.size();
+            if ((first + n + (n + 3) / 4) * sizeof(ScaleCand) > 0x7FFFFFF0ull) return INFAAS_SEL_ERR_OUT_OF_RANGE;
+            cand.resize(first + n + (n + 3) / 4, ScaleCand{0u, 0, 0ull});
+            std::copy(list.begin(), list.end(), cand.begin() + (ptrdiff_t)first);
+            if (n) std::memcpy(&cand[first + n], list_row.data(), n * 4);
             for (int32_t p = arch_first[(size_t)a]; p < arch_first[(size_t)a + 1]; ++p) {   // into every row's block
                 uint32_t *w = &rows[(size_t)by_arch[(size_t)p] * (size_t)row_words + kScaleRowLat + Be + 2 * b];
-                w[0] = (uint32_t)first; w[1] = (uint32_t)cand.size();
+                w[0] = (uint32_t)first; w[1] = (uint32_t)n;
             }
         }
-    if (cand.empty()) { cand.push_back(ScaleCand{1u, 0, 0ull}); cand_row.push_back(0); }
+    cand.resize(((cand.size() + 7) & ~(size_t)7) + 8, ScaleCand{0u, 0, 0ull});   // an empty list still reads one candidate
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
@@ -1060,7 +1069,6 @@ int infaas_sel_load_scaling(infaas_sel_t *h, const int32_t *arch_id, const int32
     sv.row_words = row_words;
     sv.rows = (const uint32_t *)upload(rows.data(), rows.size() * 4);
     sv.cand = (const ScaleCand *)upload(cand.data(), cand.size() * sizeof(ScaleCand));
-    sv.cand_row = (const int32_t *)upload(cand_row.data(), cand_row.size() * 4);
     if (!ok) {
         for (void *p : h->scale_mem) (void)hipFree(p);
         h->scale_mem.clear();

@@ -223,7 +223,7 @@ hipError_t launch_hot_workers(const IndexView &ix, int32_t num_slices, hipStream
 // word 0 saturation throughput Q, 1 hardware cost, 2-3 cost of one loaded instance
 // C * (1,000,000 + lambda * T_load), 4-5 the double 1 / (100 Q), 6 + b inference latency at batch
 // size b, then from word
-// 6 + B (rounded up to even) on, for every batch size, {first, end} of the candidates of its architecture.
+// 6 + B (rounded up to even) on, for every batch size, {first, count} of the candidates of its architecture.
 constexpr int kScaleRowLat = 6;
 struct ScaleCand {    // one candidate for an upgrade
     uint32_t qps;     // saturation throughput
@@ -236,9 +236,9 @@ struct ScaleView {
     int32_t row_words;
     int32_t pairs_at;         // word of a block where the {first, end} pairs start (even)
     const uint32_t *rows;     // [V][row_words]
-    const ScaleCand *cand;    // per (batch size, architecture) the variants that can ever win an upgrade, by
-                              // descending throughput
-    const int32_t *cand_row;  // their caller rows
+    const ScaleCand *cand;    // per (batch size, architecture) a block that starts on a 128-byte line: the variants
+                              // that can ever win an upgrade, by descending throughput, then their caller rows
+                              // (int32 each) -- one line for up to six candidates
 };
 hipError_t launch_scale(const ScaleView &sv, int64_t R, const int32_t *r_variant, const int32_t *r_instances,
                         const int32_t *r_load_qps, const int32_t *r_slo_us, const int32_t *r_batch_idx,

@@ -78,10 +78,12 @@ __global__ __launch_bounds__(kThreads) void k_scale(ScaleView sv, int64_t R, con
             }
             // upgrade: the list is read four candidates at a time, so that their loads overlap
             // instead of each waiting for the decision on the one before
-            for (int32_t i0 = run.x; i0 < run.y; i0 += kChunk) {
+            const ScaleCand *list = sv.cand + run.x;                       // run = {first, count}
+            const int32_t *list_row = (const int32_t *)(list + run.y);    // the rows sit behind the candidates
+            for (int32_t i0 = 0; i0 < run.y; i0 += kChunk) {
                 ScaleCand c[kChunk];
 #pragma unroll
-                for (int j = 0; j < kChunk; ++j) c[j] = sv.cand[i0 + j < run.y ? i0 + j : run.y - 1];
+                for (int j = 0; j < kChunk; ++j) c[j] = list[i0 + j < run.y ? i0 + j : run.y - 1];
                 bool more = true;
 #pragma unroll
                 for (int j = 0; j < kChunk; ++j) {
@@ -93,7 +95,7 @@ __global__ __launch_bounds__(kThreads) void k_scale(ScaleView sv, int64_t R, con
                         const u128 cost = (u128)c[j].unit * inst;
                         // replication keeps a tie; among upgrades of equal cost the lower row wins
                         bool better = !have || cost < best;
-                        if (cost == best && best_at >= 0) better = sv.cand_row[i0 + j] < sv.cand_row[best_at];
+                        if (cost == best && best_at >= 0) better = list_row[i0 + j] < list_row[best_at];
                         if (better) { best = cost; best_at = i0 + j; best_n = inst; have = true; }
                     }
                 }
@@ -101,7 +103,7 @@ __global__ __launch_bounds__(kThreads) void k_scale(ScaleView sv, int64_t R, con
             }
             action = !have ? 3 : (best_at < 0 ? 1 : 2);
             if (have) {
-                variant = best_at < 0 ? cur : sv.cand_row[best_at];
+                variant = best_at < 0 ? cur : list_row[best_at];
                 instances = (int32_t)best_n;
             }
         }
