@@ -105,9 +105,9 @@ def bench_scale(args, cfg, spec, tb) -> int:
     ms_per_step = 1e3 * elapsed / args.steps
     k = timings["scale"]
     avg_ms = k["total_ms"] / k["launches"]
-    # every request in, every result out, and what the decision reads of the table once: a 16-byte
-    # record per variant and batch size, 20 bytes per variant of places and hardware cost
-    fixed = tb.V * (16 * tb.B + 20)
+    # every request in, every result out, and what the decision reads of the table once: per variant
+    # its architecture, throughput, hardware cost, loading latency and the latency at every batch size
+    fixed = tb.V * (16 + 4 * tb.B)
     algo = SCALE_BYTES_PER_DECISION * n + fixed
     achieved = algo / (avg_ms * 1e-3) / 1e9
     cpu, mismatches = None, None

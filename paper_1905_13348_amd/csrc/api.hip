@@ -996,29 +996,16 @@ int infaas_sel_load_scaling(infaas_sel_t *h, const int32_t *arch_id, const int32
     auto unit_of = [&](int32_t v) {   // cost of one loaded instance, < 2^62
         return (uint64_t)hw_cost[v] * (1000000ull + (uint64_t)lambda_per_s * (uint64_t)load_us[v]);
     };
-    const int32_t Be = (B + 1) & ~1;   // latencies padded to an even count: the pairs behind them stay 8-byte aligned
-    const int32_t row_words = (kScaleRowLat + Be + 2 * B + 7) & ~7;
-    std::vector<uint32_t> rows((size_t)std::max(V, 1) * (size_t)row_words, 0u);
-    if (V == 0) rows[0] = 1u;   // the block an invalid request reads: throughput 1, everything else 0 (it is never used)
-    for (int32_t v = 0; v < V; ++v) {
-        uint32_t *w = &rows[(size_t)v * (size_t)row_words];
-        const uint64_t unit = unit_of(v);
-        const double per_inv = 1.0 / (100.0 * (double)sat_qps[v]);
-        w[0] = (uint32_t)sat_qps[v]; w[1] = (uint32_t)hw_cost[v];
-        w[2] = (uint32_t)unit; w[3] = (uint32_t)(unit >> 32);
-        std::memcpy(&w[4], &per_inv, 8);
-        for (int32_t b = 0; b < B; ++b) w[kScaleRowLat + b] = (uint32_t)h->h_lat[(size_t)v * B + b];
-    }
     // Candidates of an architecture at a batch size: by descending throughput, and only those that
     // no other variant beats for every request (at least the throughput, at most the latency, and
     // a lower cost per instance or the same with a lower row).  Sorted so that whatever beats a
     // variant comes before it; being beaten is transitive, so the survivors so far are enough to
-    // compare with.
-    // A list's block: its candidates (16 bytes each), then their caller rows (4 bytes each), starting
-    // on a 128-byte line, so that a lookup of up to six candidates touches one line.
-    std::vector<ScaleCand> cand;          // all blocks, in units of 16 bytes
-    std::vector<ScaleCand> list;
-    std::vector<int32_t> list_row;
+    // compare with.  Every row of the architecture then gets its block: its own figures and the
+    // first candidates of the prefix of the list whose throughput is above its own.
+    if ((int64_t)B * V * kScaleBlockWords * 4 > ((int64_t)1 << 33)) return INFAAS_SEL_ERR_OOM;   // 8 GB of blocks
+    std::vector<uint32_t> blocks((size_t)std::max<int64_t>((int64_t)B * V, 1) * kScaleBlockWords, 0u);
+    if (V == 0) blocks[0] = 1u;   // the block an invalid request reads: throughput 1, no candidates (it is never used)
+    std::vector<ScaleCand> cand;
     std::vector<int32_t> order;
     for (int32_t b = 0; b < B; ++b)
         for (int32_t a = 0; a < A; ++a) {
@@ -1029,26 +1016,33 @@ int infaas_sel_load_scaling(infaas_sel_t *h, const int32_t *arch_id, const int32
                 if (ux != uy) return ux < uy;
                 return x < y;
             });
-            list.clear();
-            list_row.clear();
+            const size_t first = cand.size();
             for (int32_t v : order) {
-                const ScaleCand r{(uint32_t)sat_qps[v], h->h_lat[(size_t)v * B + b], unit_of(v)};
+                const ScaleCand r{(uint32_t)sat_qps[v], h->h_lat[(size_t)v * B + b], unit_of(v), v, {0, 0, 0}};
                 bool beaten = false;
-                for (size_t k = 0; k < list.size() && !beaten; ++k)
-                    beaten = list[k].lat <= r.lat && (list[k].unit < r.unit || (list[k].unit == r.unit && list_row[k] < v));
-                if (!beaten) { list.push_back(r); list_row.push_back(v); }
+                for (size_t k = first; k < cand.size() && !beaten; ++k)
+                    beaten = cand[k].lat <= r.lat && (cand[k].unit < r.unit || (cand[k].unit == r.unit && cand[k].row < v));
+                if (!beaten) cand.push_back(r);
             }
-            const size_t first = (cand.size() + 7) & ~(size_t)7, n = list.size();
-            if ((first + n + (n + 3) / 4) * sizeof(ScaleCand) > 0x7FFFFFF0ull) return INFAAS_SEL_ERR_OUT_OF_RANGE;
-            cand.resize(first + n + (n + 3) / 4, ScaleCand{0u, 0, 0ull});
-            std::copy(list.begin(), list.end(), cand.begin() + (ptrdiff_t)first);
-            if (n) std::memcpy(&cand[first + n], list_row.data(), n * 4);
-            for (int32_t p = arch_first[(size_t)a]; p < arch_first[(size_t)a + 1]; ++p) {   // into every row's block
-                uint32_t *w = &rows[(size_t)by_arch[(size_t)p] * (size_t)row_words + kScaleRowLat + Be + 2 * b];
-                w[0] = (uint32_t)first; w[1] = (uint32_t)n;
+            if (cand.size() > 0x7FFFFFFFull) return INFAAS_SEL_ERR_OUT_OF_RANGE;
+            const size_t n = cand.size() - first;
+            for (int32_t v : order) {
+                uint32_t *w = &blocks[((size_t)b * V + v) * kScaleBlockWords];
+                const uint64_t unit = unit_of(v);
+                size_t m = 0;   // candidates with a higher throughput: a prefix of the list
+                while (m < n && cand[first + m].qps > (uint32_t)sat_qps[v]) ++m;
+                w[0] = (uint32_t)sat_qps[v]; w[1] = (uint32_t)hw_cost[v];
+                w[2] = (uint32_t)unit; w[3] = (uint32_t)(unit >> 32);
+                w[4] = (uint32_t)h->h_lat[(size_t)v * B + b]; w[5] = (uint32_t)m; w[6] = (uint32_t)first;
+                for (size_t j = 0; j < std::min<size_t>(m, kScaleInBlock); ++j) {
+                    const ScaleCand &c = cand[first + j];
+                    uint32_t *sl = w + 8 + 4 * j;
+                    sl[0] = c.qps; sl[1] = (uint32_t)c.lat; sl[2] = (uint32_t)c.unit; sl[3] = (uint32_t)(c.unit >> 32);
+                    w[j < 4 ? 28 + j : 7] = (uint32_t)c.row;
+                }
             }
         }
-    cand.resize(((cand.size() + 7) & ~(size_t)7) + 8, ScaleCand{0u, 0, 0ull});   // an empty list still reads one candidate
+    if (cand.empty()) cand.push_back(ScaleCand{1u, 0, 0ull, 0, {0, 0, 0}});
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
@@ -1065,9 +1059,8 @@ int infaas_sel_load_scaling(infaas_sel_t *h, const int32_t *arch_id, const int32
         return d;
     };
     ScaleView sv{};
-    sv.V = V; sv.B = B; sv.slack_pct = slack_pct; sv.pairs_at = kScaleRowLat + Be;
-    sv.row_words = row_words;
-    sv.rows = (const uint32_t *)upload(rows.data(), rows.size() * 4);
+    sv.V = V; sv.B = B; sv.slack_pct = slack_pct;
+    sv.blocks = (const uint32_t *)upload(blocks.data(), blocks.size() * 4);
     sv.cand = (const ScaleCand *)upload(cand.data(), cand.size() * sizeof(ScaleCand));
     if (!ok) {
         for (void *p : h->scale_mem) (void)hipFree(p);

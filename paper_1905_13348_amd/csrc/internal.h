@@ -218,27 +218,28 @@ hipError_t launch_step_workers(const IndexView &ix, const int32_t *row_worker, i
 hipError_t launch_hot_workers(const IndexView &ix, int32_t num_slices, hipStream_t st, const LaunchEvents *ev = nullptr);
 
 // Scaling decision on a change in load (Section 4.2.2).
-// What a request reads about its running variant sits in one block of row_words 32-bit words per
-// caller row (a multiple of 8 words; 32 words = one 128-byte line for 8 batch sizes):
-// word 0 saturation throughput Q, 1 hardware cost, 2-3 cost of one loaded instance
-// C * (1,000,000 + lambda * T_load), 4-5 the double 1 / (100 Q), 6 + b inference latency at batch
-// size b, then from word
-// 6 + B (rounded up to even) on, for every batch size, {first, count} of the candidates of its architecture.
-constexpr int kScaleRowLat = 6;
-struct ScaleCand {    // one candidate for an upgrade
+// Everything a request reads sits in ONE 128-byte block per (batch size, caller row) -- 32 words:
+//   0 saturation throughput Q of the row, 1 its hardware cost, 2-3 the cost of one loaded instance
+//   C * (1,000,000 + lambda * T_load), 4 its inference latency at the batch size, 5 the number m of
+//   candidates for an upgrade (those of its architecture's list with a higher throughput: a prefix
+//   of the list), 6 where that list starts in `cand`, 7 | 28-31 the caller rows of
+//   the first five candidates (the fifth in word 7), 8-27 those candidates, four words each.
+// Candidates beyond the fifth are read from the shared list.
+constexpr int kScaleBlockWords = 32;
+constexpr int kScaleInBlock = 5;
+struct ScaleCand {    // one candidate for an upgrade, as the shared lists hold it
     uint32_t qps;     // saturation throughput
     int32_t lat;      // inference latency at the list's batch size
     uint64_t unit;    // cost of one loaded instance
+    int32_t row;      // caller row
+    int32_t pad[3];
 };
 struct ScaleView {
     int32_t V, B;             // variants, batch sizes
     int32_t slack_pct;
-    int32_t row_words;
-    int32_t pairs_at;         // word of a block where the {first, end} pairs start (even)
-    const uint32_t *rows;     // [V][row_words]
-    const ScaleCand *cand;    // per (batch size, architecture) a block that starts on a 128-byte line: the variants
-                              // that can ever win an upgrade, by descending throughput, then their caller rows
-                              // (int32 each) -- one line for up to six candidates
+    const uint32_t *blocks;   // [B][V][32]
+    const ScaleCand *cand;    // per (batch size, architecture) the variants that can ever win an upgrade, by
+                              // descending throughput
 };
 hipError_t launch_scale(const ScaleView &sv, int64_t R, const int32_t *r_variant, const int32_t *r_instances,
                         const int32_t *r_load_qps, const int32_t *r_slo_us, const int32_t *r_batch_idx,

@@ -4,13 +4,15 @@
 // latency objective -- whichever is cheaper by the cost function of the integer program of
 // Section 4.2.1, C * (delta + lambda * T_load * max(delta, 0)) summed over the touched variants.
 //
-// One lane per request.  Per batch size and architecture the library keeps the candidates for an
-// upgrade as 16-byte records {throughput, latency, cost of one loaded instance}, sorted by descending
-// throughput and without the variants that can never win: v loses to w for every request when w has
-// at least v's throughput, at most v's latency and a lower cost per instance (or the same and a lower
-// row), because w then passes every test v passes and needs no more instances.  A lane walks its run
-// until the throughput drops to the running variant's and keeps the cheapest.  All costs are exact
-// integers (times 1,000,000, because lambda is per second and the loading latency in
+// One lane per request, one cache line per request.  Per batch size and architecture the host keeps
+// the candidates for an upgrade sorted by descending throughput and without the variants that can
+// never win: v loses to w for every request when w has at least v's throughput, at most v's latency
+// and a lower cost per instance (or the same and a lower row), because w then passes every test v
+// passes and needs no more instances.  The candidates of a running variant are the prefix of that
+// list with a higher throughput than its own; the first five of them are copied, with everything
+// else the decision reads about the variant, into a 128-byte block per (batch size, variant), so a
+// request costs one uncoalesced line (longer prefixes continue in the shared list).  All costs are
+// exact integers (times 1,000,000, because lambda is per second and the loading latency in
 // microseconds), compared in 128 bits.
 #include "internal.h"
 
@@ -53,13 +55,20 @@ __global__ __launch_bounds__(kThreads) void k_scale(ScaleView sv, int64_t R, con
         const int32_t b = in ? __builtin_nontemporal_load(r_batch_idx + r) : 0;
         const bool valid = (uint32_t)cur < (uint32_t)sv.V && (uint32_t)b < (uint32_t)sv.B &&
                            (uint32_t)n_cur <= 1000000u && (uint32_t)load <= 1000000000u;
-        const uint32_t *mine = sv.rows + (int64_t)(valid ? cur : 0) * sv.row_words;
-        const uint4 head = *(const uint4 *)mine;                        // {throughput, hardware cost, cost of one instance}
-        const uint64_t own_unit = ((uint64_t)head.w << 32) | head.z;
-        const double own_inv = *(const double *)(mine + 4);
-        const int32_t own_lat = (int32_t)mine[kScaleRowLat + (valid ? b : 0)];
+        // the request's block: one cache line, all of it requested at once
+        const uint4 *blk = (const uint4 *)(sv.blocks + ((int64_t)(valid ? b : 0) * sv.V + (valid ? cur : 0)) * kScaleBlockWords);
+        const uint4 head = blk[0];      // {throughput, hardware cost, cost of one instance}
+        const uint4 more = blk[1];      // {latency, candidates, their list, row of the fifth}
+        uint4 slot[kScaleInBlock];
+#pragma unroll
+        for (int j = 0; j < kScaleInBlock; ++j) slot[j] = blk[2 + j];   // {throughput, latency, cost of one instance}
+        const uint4 rows4 = blk[7];
+        const int32_t slot_row[kScaleInBlock] = {(int32_t)rows4.x, (int32_t)rows4.y, (int32_t)rows4.z, (int32_t)rows4.w,
+                                                 (int32_t)more.w};
         const uint32_t own_qps = head.x;
-        const int2 run = *(const int2 *)(mine + sv.pairs_at + 2 * (valid ? b : 0));   // its architecture's list at b
+        const uint64_t own_unit = ((uint64_t)head.w << 32) | head.z;
+        const int32_t own_lat = (int32_t)more.x;
+        const int32_t m = (int32_t)more.y;
         const uint64_t need = (uint64_t)(uint32_t)load * (uint32_t)sv.slack_pct;   // hundredths of a query per second
         const bool scaling = valid && (uint64_t)own_qps * (uint32_t)n_cur * 100u < need;
         int32_t action = 0, variant = -1, instances = 0;
@@ -69,41 +78,41 @@ __global__ __launch_bounds__(kThreads) void k_scale(ScaleView sv, int64_t R, con
             const uint64_t saved = (uint64_t)head.y * (uint32_t)n_cur * 1000000u;   // < 2^61
             bool have = false;
             u128 best = 0;
-            int32_t best_at = -1;     // place of the best upgrade in the list, -1: replication is best
+            int32_t best_row = -1;    // row of the best upgrade, -1: replication is best
             uint32_t best_n = 0;
             if (own_lat <= slo) {   // replicate
-                best_n = ceil_div(need, 100u * (uint64_t)own_qps, own_inv) - (uint32_t)n_cur;
+                const uint64_t per = 100u * (uint64_t)own_qps;
+                best_n = ceil_div(need, per, 1.0 / (double)per) - (uint32_t)n_cur;
                 best = (u128)own_unit * best_n + saved;
                 have = true;
             }
-            // upgrade: the list is read four candidates at a time, so that their loads overlap
-            // instead of each waiting for the decision on the one before
-            const ScaleCand *list = sv.cand + run.x;                       // run = {first, count}
-            const int32_t *list_row = (const int32_t *)(list + run.y);    // the rows sit behind the candidates
-            for (int32_t i0 = 0; i0 < run.y; i0 += kChunk) {
-                ScaleCand c[kChunk];
+            // upgrade: a candidate has a higher throughput than cur by construction
+            auto offer = [&](uint32_t qps, int32_t lat, uint64_t unit, int32_t row) {
+                if (lat > slo) return;
+                const uint64_t per = 100u * (uint64_t)qps;
+                const uint32_t inst = ceil_div(need, per, 1.0 / (double)per);
+                const u128 cost = (u128)unit * inst;
+                // replication keeps a tie; among upgrades of equal cost the lower row wins
+                const bool better = !have || cost < best || (cost == best && best_row >= 0 && row < best_row);
+                if (better) { best = cost; best_row = row; best_n = inst; have = true; }
+            };
 #pragma unroll
-                for (int j = 0; j < kChunk; ++j) c[j] = list[i0 + j < run.y ? i0 + j : run.y - 1];
-                bool more = true;
+            for (int j = 0; j < kScaleInBlock; ++j)
+                if (j < m) offer(slot[j].x, (int32_t)slot[j].y, ((uint64_t)slot[j].w << 32) | slot[j].z, slot_row[j]);
+            if (m > kScaleInBlock) {   // the rest of the prefix from the shared list, four at a time
+                const ScaleCand *list = sv.cand + more.z;
+                for (int32_t i0 = kScaleInBlock; i0 < m; i0 += kChunk) {
+                    ScaleCand c[kChunk];
 #pragma unroll
-                for (int j = 0; j < kChunk; ++j) {
-                    // descending throughput: nothing from here on supports more than cur
-                    more = more && i0 + j < run.y && c[j].qps > own_qps;
-                    if (more && c[j].lat <= slo) {
-                        const uint64_t per = 100u * (uint64_t)c[j].qps;
-                        const uint32_t inst = ceil_div(need, per, 1.0 / (double)per);
-                        const u128 cost = (u128)c[j].unit * inst;
-                        // replication keeps a tie; among upgrades of equal cost the lower row wins
-                        bool better = !have || cost < best;
-                        if (cost == best && best_at >= 0) better = list_row[i0 + j] < list_row[best_at];
-                        if (better) { best = cost; best_at = i0 + j; best_n = inst; have = true; }
-                    }
+                    for (int j = 0; j < kChunk; ++j) c[j] = list[i0 + j < m ? i0 + j : m - 1];
+#pragma unroll
+                    for (int j = 0; j < kChunk; ++j)
+                        if (i0 + j < m) offer(c[j].qps, c[j].lat, c[j].unit, c[j].row);
                 }
-                if (!more) break;
             }
-            action = !have ? 3 : (best_at < 0 ? 1 : 2);
+            action = !have ? 3 : (best_row < 0 ? 1 : 2);
             if (have) {
-                variant = best_at < 0 ? cur : list_row[best_at];
+                variant = best_row < 0 ? cur : best_row;
                 instances = (int32_t)best_n;
             }
         }
