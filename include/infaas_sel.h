@@ -18,11 +18,18 @@
  * where b = batch_idx, or -1 when no row qualifies (also for a task or batch index
  * outside the table and for a negative slo_us).
  *
+ * Further down: the suggestion of the closest variant when nothing qualifies
+ * (infaas_sel_select_closest), the state-aware form of the same decision
+ * (infaas_sel_load_states / _update_state / _select_tiered), the worker that serves the
+ * chosen variant (infaas_sel_load_workers / _update_workers / _select_workers) and the
+ * decision on a change in load, Case II of Section 4.2 (infaas_sel_load_scaling /
+ * infaas_sel_scale).  They follow the conventions stated here.
+ *
  * Plain C ABI: opaque handle, plain pointers and sizes.  Each pointer below is marked
  * HOST or DEVICE.  Nothing here allocates or frees memory the caller passed in.
  *
- * Threading / ordering: a handle is not thread-safe.  infaas_sel_update_load and
- * infaas_sel_select only ENQUEUE work on the HIP stream they are given and return; the
+ * Threading / ordering: a handle is not thread-safe.  The calls that take a hip_stream
+ * (reports, selections, scaling decisions) only ENQUEUE work on the HIP stream they are given and return; the
  * outputs are valid once the caller has synchronised that stream.  Work enqueued on
  * one handle must be ordered by the caller (same stream, or events between streams),
  * because all calls share the handle's table and scratch memory.
