@@ -29,8 +29,8 @@
  * HOST or DEVICE.  Nothing here allocates or frees memory the caller passed in.
  *
  * Threading / ordering: a handle is not thread-safe.  The calls that take a hip_stream
- * (reports, selections, scaling decisions) only ENQUEUE work on the HIP stream they are given and return; the
- * outputs are valid once the caller has synchronised that stream.  Work enqueued on
+ * (reports, selections, scaling decisions) only ENQUEUE work on that stream and return;
+ * the outputs are valid once the caller has synchronised it.  Work enqueued on
  * one handle must be ordered by the caller (same stream, or events between streams),
  * because all calls share the handle's table and scratch memory.
  */
