@@ -31,6 +31,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 BYTES_PER_DECISION = 20          # 4 int32 query fields read + 1 int32 result written
 UPDATE_BYTES = 8                 # one (row, value) pair of a load report
+ROTATE_BYTES = 1_400_000_000     # bytes touched between two uses of one buffer (last-level cache: 256 MB)
+MAX_SETS = 64                    # (tiny configurations cannot reach ROTATE_BYTES with a sensible number of buffers)
+MAX_DISTINCT = 18                # batches drawn from seeds of their own; sets beyond them are device copies
 
 
 def table_bytes(tb) -> int:
@@ -85,23 +88,31 @@ def bench_scale(args, cfg, spec, tb) -> int:
     sel = pkg.Selector(tb.num_tasks, tb.batch_sizes, device=0, engine=pkg.ENGINE_AUTO)
     sel.load_variants(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us)
     sel.load_scaling(sc.arch_id, sc.sat_qps, sc.hw_cost, sc.load_us, SCALE_LAMBDA, SCALE_SLACK)
-    n_sets = 4
+    n_sets = int(min(MAX_SETS, max(4, -(-ROTATE_BYTES // (n * SCALE_BYTES_PER_DECISION)))))   # see main()
     host = [workloads.make_scale_requests(cfg, tb, sc, n, chunk=c) for c in range(n_sets)]
     dev = [[torch.from_numpy(x).cuda() for x in (r.variant, r.instances, r.load_qps, r.slo_us, r.batch_idx)]
            for r in host]
-    outs = [torch.empty(n, dtype=torch.int32, device="cuda") for _ in range(3)]
-    for i in range(args.warmup):
-        sel.scale(*dev[i % n_sets], *outs)
-    torch.cuda.synchronize()
-    sel.set_timing(True)
+    out_sets = [[torch.empty(n, dtype=torch.int32, device="cuda") for _ in range(3)] for _ in range(n_sets)]
+    done = 0
+    for _ in range(args.warmup):
+        sel.scale(*dev[done % n_sets], *out_sets[done % n_sets])
+        done += 1
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        sel.scale(*dev[(args.warmup + i) % n_sets], *outs)
+    for _ in range(args.steps):   # the timed region, instrumentation off
+        sel.scale(*dev[done % n_sets], *out_sets[done % n_sets])
+        done += 1
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    sel.set_timing(True)          # the same steps again for the kernel's own duration
+    torch.cuda.synchronize()
+    for _ in range(args.steps):
+        sel.scale(*dev[done % n_sets], *out_sets[done % n_sets])
+        done += 1
+    torch.cuda.synchronize()
     timings = sel.get_timings()
     sel.set_timing(False)
+    outs = out_sets[(done - 1) % n_sets]
     ms_per_step = 1e3 * elapsed / args.steps
     k = timings["scale"]
     avg_ms = k["total_ms"] / k["launches"]
@@ -114,7 +125,7 @@ def bench_scale(args, cfg, spec, tb) -> int:
     if not args.no_cpu_baseline:
         import oracle
         ref = oracle.load_oracle()
-        rq = host[(args.warmup + args.steps - 1) % n_sets]
+        rq = host[(done - 1) % n_sets]
         fields = (rq.variant, rq.instances, rq.load_qps, rq.slo_us, rq.batch_idx)
         prof = (sc.arch_id, sc.sat_qps, sc.hw_cost, sc.load_us, tb.lat_us, SCALE_LAMBDA, SCALE_SLACK)
         n0 = min(n, 20_000)
@@ -192,12 +203,19 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.calibrate_copy:
-        src = torch.arange(64 * 1024 * 1024, dtype=torch.int32, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(5):
+        # eight 256 MiB source / destination pairs taken in turn: 4 GiB pass between two uses of
+        # the same buffer, so that no copy finds its data in a cache
+        pairs = [(torch.arange(64 * 1024 * 1024, dtype=torch.int32, device="cuda") + k,
+                  torch.empty(64 * 1024 * 1024, dtype=torch.int32, device="cuda")) for k in range(8)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for r in range(16):
+            src, dst = pairs[r % len(pairs)]
             dst.copy_(src)
         torch.cuda.synchronize()
-        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4}))
+        dt = (time.perf_counter() - t0) / 16
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4,
+                          "copies": 16, "pairs": len(pairs), "ms_per_copy_wall": round(1e3 * dt, 4)}))
         return 0
     cfg = args.config
     spec = workloads.config_spec(cfg)
@@ -226,17 +244,27 @@ def main() -> int:
         sel.load_workers(cluster.worker_hw, cluster.worker_util, cluster.variant_hw, cluster.inst_variant,
                          cluster.inst_worker, cluster.inst_load)
 
-    # inputs resident in HBM before the timed region.  The streaming configuration cycles over a
-    # few distinct chunks and load reports; the others reuse one batch.
-    n_sets = min(4, chunks)
-    host_q = [workloads.make_queries(cfg, chunk=c) for c in range(n_sets)]
-    dev_q = [[torch.from_numpy(x).cuda() for x in (q.task, q.slo_us, q.min_acc_bp, q.batch_idx)]
-             for q in host_q]
-    out = torch.empty(per_step, dtype=torch.int32, device="cuda")
+    # Inputs resident in HBM before the timed region.  The steps rotate over n_sets distinct query
+    # batches (different seeds; the streaming configuration: consecutive chunks, each with its load
+    # report) and as many result arrays, enough that at least ROTATE_BYTES are touched between two
+    # uses of the same buffer: nothing a step reads or writes can still sit in a cache (the part has
+    # 256 MB of last-level cache) from the step that used it before.
     two_results = args.closest or args.tiered or args.workers        # suggestion, or tier
-    closest = torch.empty(per_step, dtype=torch.int32, device="cuda") if two_results else None
-    worker = torch.empty(per_step, dtype=torch.int32, device="cuda") if args.workers else None
     per_decision = BYTES_PER_DECISION + (4 if two_results else 0) + (4 if args.workers else 0)
+    set_bytes = per_step * per_decision
+    n_sets = int(min(MAX_SETS, max(4, -(-ROTATE_BYTES // set_bytes))))
+    if chunks > 1:
+        n_sets = min(n_sets, chunks)
+    n_distinct = min(n_sets, MAX_DISTINCT)
+    host_q = [workloads.make_queries(cfg, chunk=c) for c in range(n_distinct)]
+    dev_q = []
+    for c in range(n_sets):   # beyond MAX_DISTINCT seeds: device copies (other addresses, same values)
+        src = host_q[c % n_distinct]
+        dev_q.append([torch.from_numpy(x).cuda() for x in (src.task, src.slo_us, src.min_acc_bp, src.batch_idx)])
+    outs = [torch.empty(per_step, dtype=torch.int32, device="cuda") for _ in range(n_sets)]
+    seconds = [torch.empty(per_step, dtype=torch.int32, device="cuda") if two_results else None for _ in range(n_sets)]
+    workers_out = [torch.empty(per_step, dtype=torch.int32, device="cuda") if args.workers else None
+                   for _ in range(n_sets)]
     updates = []
     worker_updates = []
     if chunks > 1 and args.workers:   # a report of the cluster before every step as well
@@ -250,35 +278,45 @@ def main() -> int:
             updates.append((torch.from_numpy(up.variant_idx).cuda(), torch.from_numpy(up.queue_us).cuda(), up))
 
     def step(i: int) -> None:
+        k = i % n_sets
         if updates:
             u = updates[i % len(updates)]
             sel.update_load(u[0], u[1])
         if args.closest:
-            sel.select_closest(*dev_q[i % n_sets], out, closest)
+            sel.select_closest(*dev_q[k], outs[k], seconds[k])
         elif args.tiered:
-            sel.select_tiered(*dev_q[i % n_sets], out, closest)
+            sel.select_tiered(*dev_q[k], outs[k], seconds[k])
         elif args.workers:
             if worker_updates:
                 sel.update_workers(*worker_updates[i % len(worker_updates)][0])
-            sel.select_workers(*dev_q[i % n_sets], out, closest, worker)
+            sel.select_workers(*dev_q[k], outs[k], seconds[k], workers_out[k])
         else:
-            sel.select(*dev_q[i % n_sets], out)
+            sel.select(*dev_q[k], outs[k])
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    sel.set_timing(True)
+    done = 0      # steps enqueued so far (the load reports of the streaming configuration follow it)
+    for _ in range(args.warmup):
+        step(done)
+        done += 1
+    # 1. the timed region: exactly args.steps steps, library instrumentation off
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
+    for _ in range(args.steps):
+        step(done)
+        done += 1
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    elapsed = time.perf_counter() - t0
+    # 2. the same steps once more with an event pair attached to every kernel launch: per-kernel
+    #    durations for the roofline (not part of value / ms_per_step)
+    sel.set_timing(True)
+    torch.cuda.synchronize()
+    for _ in range(args.steps):
+        step(done)
+        done += 1
+    torch.cuda.synchronize()
     timings = sel.get_timings()
     sel.set_timing(False)
-    elapsed = t1 - t0
     if args.graph:
-        # the same steps once more as graph replays, continuing the sequence of load reports
+        # and as graph replays, continuing the sequence of load reports
         period = n_sets
         graphs = []
         for j in range(period):
@@ -286,13 +324,14 @@ def main() -> int:
             with torch.cuda.graph(g):
                 step(j)
             graphs.append(g)
-        first = args.warmup + args.steps
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for i in range(args.steps):
-            graphs[(first + i) % period].replay()
+        for _ in range(args.steps):
+            graphs[done % period].replay()
+            done += 1
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
+    last = done - 1
     ms_per_step = 1e3 * elapsed / args.steps
     value = per_step * args.steps / elapsed
 
@@ -331,8 +370,8 @@ def main() -> int:
     if not args.no_cpu_baseline:
         import oracle
         ref = oracle.load_oracle()
-        last = (args.warmup + args.steps * (2 if args.graph else 1) - 1)
-        q = host_q[last % n_sets]
+        q = host_q[(last % n_sets) % n_distinct]
+        out, closest, worker = outs[last % n_sets], seconds[last % n_sets], workers_out[last % n_sets]
         queue = tb.queue_us.copy()
         if updates:  # replay the load reports in the order the steps applied them
             for i in range(last + 1):
@@ -379,12 +418,14 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
         "config": {"workload": f"config {cfg} ({spec['name']}): {tb.num_tasks} tasks, {tb.V} variants, "
                                f"{tb.B} batch sizes, {per_step} queries per step"
+                               + f", rotating over {n_sets} batches and result arrays ({n_distinct} seeds)"
                                + (f", load report of {updates[0][2].variant_idx.size} rows before every step" if updates else "")
                                + (", closest-variant mode (two result arrays)" if args.closest else "")
                                + (", state-aware two-tier selection (variant and tier arrays)" if args.tiered else "")
                                + (f", two-tier selection with worker selection over {cluster.W} workers and "
                                   f"{cluster.I} instances (variant, tier and worker arrays)" if args.workers else ""),
-                   "engine": args.engine, "launch": "hip graph replay" if args.graph else "stream"},
+                   "engine": args.engine, "launch": "hip graph replay" if args.graph else "stream",
+                   "timed_region": "library instrumentation off; kernel durations from a second pass of the same steps"},
         "roofline": roofline,
         "whole_step_frac_of_hbm_roofline": round(whole_frac, 5),
         "kernels_ms_per_step": {k: round(v["total_ms"] / args.steps, 5) for k, v in active.items()},
