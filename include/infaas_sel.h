@@ -375,6 +375,15 @@ typedef struct {
     int64_t index_steps;        /* steps over all slices */
     int64_t table_bytes;        /* device bytes of the variant store */
     int64_t scratch_bytes;      /* device bytes of scratch currently reserved */
+    /* The most recent launch of the index lookup kernel on this handle (for a state-aware call: the
+     * Inactive tier's): the queries whose answer the first group of their slice's staircase, as
+     * mirrored in LDS, could not decide, and what became of them.  Valid once the caller has
+     * synchronised the stream of that call; infaas_sel_get_info copies them with a blocking hipMemcpy. */
+    int64_t lookup_parked;      /* queries set aside for the slower paths */
+    int64_t lookup_second_body; /* ... answered by the second group of steps */
+    int64_t lookup_global_body; /* ... answered by a first group read from global memory (slice not in LDS) */
+    int64_t lookup_scanned;     /* ... sent through the rank-ordered scan of the slice */
+    int64_t lookup_unanswered;  /* ... that ended without a feasible variant */
 } infaas_sel_info;
 int infaas_sel_get_info(infaas_sel_t *h, infaas_sel_info *out);
 

@@ -51,7 +51,10 @@ class _Info(ctypes.Structure):
                 ("index_hot_rows", ctypes.c_int32),
                 ("index_bytes", ctypes.c_int64), ("index_steps", ctypes.c_int64),
                 ("table_bytes", ctypes.c_int64),
-                ("scratch_bytes", ctypes.c_int64)]
+                ("scratch_bytes", ctypes.c_int64),
+                ("lookup_parked", ctypes.c_int64), ("lookup_second_body", ctypes.c_int64),
+                ("lookup_global_body", ctypes.c_int64), ("lookup_scanned", ctypes.c_int64),
+                ("lookup_unanswered", ctypes.c_int64)]
 
 
 _lib: Optional[ctypes.CDLL] = None

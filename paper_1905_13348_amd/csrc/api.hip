@@ -99,6 +99,7 @@ struct infaas_sel {
     uint32_t ix_stats[kCtlWords] = {0};      // copy of ix.ctrl taken after the build at load time
     int32_t *d_park = nullptr;        // queues of parked queries of the lookup kernel (fixed size)
     int64_t park_bytes = 0;
+    const uint32_t *last_stats = nullptr;   // statistics of the most recent lookup launch (this table's or the Inactive tier's)
 
     // scan scratch
     ScanScratch sc{};
@@ -139,11 +140,13 @@ struct infaas_sel {
     void free_index()
     {
         (void)hipFree(ix.pool); (void)hipFree(ix.step_row); (void)hipFree(ix.ctrl);  // hdr lives in pool's allocation
+        (void)hipFree(ix.stats);
         (void)hipFree(ix.step_worker); (void)hipFree(ix.hot_worker);
         (void)hipFree(d_park);
         d_park = nullptr;
         park_bytes = 0;
         ix = IndexView{};
+        last_stats = nullptr;
         have_index = false;
         index_lds_bytes = 0;
     }
@@ -173,6 +176,7 @@ void infaas_sel::drop_inactive()
     open_queries = open_bytes = 0;
     if (inactive) infaas_sel_destroy(inactive);
     inactive = nullptr;
+    last_stats = nullptr;
 }
 
 namespace {
@@ -261,7 +265,8 @@ int create_index(infaas_sel *h)
     // one allocation: the pool, then the headers, so that one 32-bit offset reaches both
     ix.pool_bytes &= ~15u;
     bool ok = dev_alloc(&ix.pool, (size_t)ix.pool_bytes + (size_t)(S + 1) * 16) == hipSuccess &&
-              dev_alloc(&ix.step_row, ix.step_cap) == hipSuccess && dev_alloc(&ix.ctrl, kCtlWords) == hipSuccess;
+              dev_alloc(&ix.step_row, ix.step_cap) == hipSuccess && dev_alloc(&ix.ctrl, kCtlWords) == hipSuccess &&
+              dev_alloc(&ix.stats, (size_t)index_select_blocks(h->num_cus) * kLookupStats) == hipSuccess;
     ix.hdr = ok ? (uint4 *)(ix.pool + ix.pool_bytes) : nullptr;
     h->ix = ix;
     const size_t park = index_park_bytes(h->num_cus);
@@ -279,7 +284,8 @@ int create_index(infaas_sel *h)
     uint32_t ctrl0[kCtlWords] = {0};
     ctrl0[kCtlPool] = kDummyBodyBytes; ctrl0[kCtlSteps] = 1u; ctrl0[kCtlMaxK0] = 1u;
     const uint32_t empty_hdr[4] = {0u, kEmptyHdrY, 0u, 4u + body_bytes(2)};
-    if (!HIP_OK(hipMemcpy(ix.pool, dummy, sizeof(dummy), hipMemcpyHostToDevice)) ||
+    if (!HIP_OK(hipMemset(ix.stats, 0, (size_t)index_select_blocks(h->num_cus) * kLookupStats * 4)) ||
+        !HIP_OK(hipMemcpy(ix.pool, dummy, sizeof(dummy), hipMemcpyHostToDevice)) ||
         !HIP_OK(hipMemcpy(ix.step_row, &none, 4, hipMemcpyHostToDevice)) ||
         !HIP_OK(hipMemcpy(ix.ctrl, ctrl0, sizeof(ctrl0), hipMemcpyHostToDevice)) ||
         !HIP_OK(hipMemcpy(&ix.hdr[S], empty_hdr, sizeof(empty_hdr), hipMemcpyHostToDevice)) ||
@@ -758,6 +764,7 @@ int select_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t
         rc = idx ? index_pass(h, q, st) : scan_pass(h, q, st);
         if (rc != INFAAS_SEL_OK) return rc;
     }
+    h->last_stats = idx ? h->ix.stats : nullptr;
     return INFAAS_SEL_OK;
 }
 
@@ -829,6 +836,7 @@ int tiered_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t
         rc = index_pass(h->inactive, q, st);
         if (rc != INFAAS_SEL_OK) return rc;
     }
+    h->last_stats = h->inactive->ix.stats;
     return INFAAS_SEL_OK;
 }
 
@@ -1195,6 +1203,15 @@ int infaas_sel_get_info(infaas_sel_t *h, infaas_sel_info *out)
         out->index_hot_rows = (int32_t)h->ix.hot_rows;
         out->index_bytes = (int64_t)h->ix_stats[kCtlPool] + (int64_t)h->T * h->B * 16 + (int64_t)h->ix_stats[kCtlSteps] * 4;
         out->index_steps = (int64_t)h->ix_stats[kCtlSteps] - 1;   // step_row entries handed out (entry 0 is unused)
+        // what the most recent lookup launch did with the queries its first probe could not decide
+        std::vector<uint32_t> st((size_t)index_select_blocks(h->num_cus) * kLookupStats, 0u);
+        DeviceGuard g(h->device);
+        if (h->last_stats &&
+            (!g.ok || !HIP_OK(hipMemcpy(st.data(), h->last_stats, st.size() * 4, hipMemcpyDeviceToHost)))) return INFAAS_SEL_ERR_HIP;
+        int64_t sum[kLookupStats] = {0};
+        for (size_t i = 0; i < st.size(); ++i) sum[i % kLookupStats] += st[i];
+        out->lookup_parked = sum[0]; out->lookup_second_body = sum[1]; out->lookup_global_body = sum[2];
+        out->lookup_scanned = sum[3]; out->lookup_unanswered = sum[4];
     }
     return INFAAS_SEL_OK;
 }

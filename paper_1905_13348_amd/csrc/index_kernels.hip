@@ -554,7 +554,10 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     const v4i *open_in = (const v4i *)q.open + (int64_t)blockIdx.x * q.open_cap;
     v4i *open_out = (v4i *)q.open + (int64_t)blockIdx.x * q.open_cap;
     const int32_t open_n = kSecond ? q.open_count[blockIdx.x] : 0;
-    if (kSecond && open_n == 0) return;   // the whole workgroup: nothing was left open in its share
+    if (kSecond && open_n == 0) {   // the whole workgroup: nothing was left open in its share
+        if (tid < kLookupStats) ix.stats[blockIdx.x * kLookupStats + tid] = 0u;
+        return;
+    }
     const int32_t nunits = ((kSecond ? open_n : q.n) + kUnit - 1) / kUnit;
     // Query fields of one unit for this lane (unit < 0: nothing left; the fields then describe a
     // query outside the table).  Second tier: tk holds the slice and bi the query's number (negative: no
@@ -665,7 +668,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         uint32_t *lw = lds_w + ((kLdsCtrlBytes + hdr_bytes + lds_cap) >> 2);
         for (uint32_t i = tid; i < (nw + 1u) >> 1; i += kSelThreads) lw[i] = gw[i];
     }
-    if (tid < 4) lds_w[tid] = 0u;
+    if (tid < (int)(kLdsCtrlBytes / 4)) lds_w[tid] = 0u;
     __syncthreads();
 
     const uint32_t row_hi_mask = (1u << ix.row_hi_bits) - 1u;
@@ -678,6 +681,8 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     // queue of its own in global memory, written and read by this wavefront only.
     v4i *wq = (v4i *)park_mem + ((int64_t)blockIdx.x * (kSelThreads / 64) + wave) * kWaveQueue;
     uint32_t cnt = 0;   // records in the queue (wave-uniform)
+    // what became of this wavefront's parked queries (wave-uniform; summed per workgroup at the end)
+    uint32_t st_parked = 0, st_second = 0, st_global = 0, st_scanned = 0, st_none = 0;
 
     uint32_t &s_next = lds_w[2];
     auto next_unit = [&]() -> int32_t {
@@ -816,6 +821,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             if (mask) {   // parked queries are always inside the table
                 if (df[k]) wq[cnt + lanes_below(mask)] = v4i{kSecond ? cur.bi[k] : i0 + qoff(k), cur.sl[k], cur.am[k], (int32_t)sl_of[k]};
                 cnt += (uint32_t)__builtin_popcountll(mask);
+                st_parked += (uint32_t)__builtin_popcountll(mask);
             }
         }
         if (kFirst) {   // valid queries that end here without an answer go to the second tier
@@ -880,6 +886,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             uint32_t m[1];
             search_bodies<1>(gmem, nit, bd, ks, dd, lim, m);
             if (need_g0 && m[0]) { take_step(rec + __builtin_ctz(m[0])); done = true; }
+            st_global += (uint32_t)__builtin_popcountll(__ballot(need_g0 && m[0]));
         }
         // second body: LDS copy when resident, global memory otherwise
         const bool need1 = have && indexed && keys1 != 0u && !done;
@@ -889,16 +896,19 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             uint32_t m[1];
             search_bodies<1>(lmem, nit, bd, ks, dd, lim, m);
             if (need_l1 && m[0]) { take_step(rec + kBodySteps + __builtin_ctz(m[0])); done = true; }
+            st_second += (uint32_t)__builtin_popcountll(__ballot(need_l1 && m[0]));
         }
         if (__ballot(need_g1)) {
             const uint32_t bd[1] = {need_g1 ? gbody + size0 : 0u}, ks[1] = {need_g1 ? keys1 : 2u};
             uint32_t m[1];
             search_bodies<1>(gmem, nit, bd, ks, dd, lim, m);
             if (need_g1 && m[0]) { take_step(rec + kBodySteps + __builtin_ctz(m[0])); done = true; }
+            st_second += (uint32_t)__builtin_popcountll(__ballot(need_g1 && m[0]));
         }
         // no body, or both bodies missed and more steps exist: scan the slice in rank order
         uint64_t todo = __ballot(have && !done && (!indexed || (y & kHdrTrunc)));
         if (todo) {
+            st_scanned += (uint32_t)__builtin_popcountll(todo);
             const int32_t task = (int32_t)(s / (uint32_t)tv.B), bidx = (int32_t)(s - (uint32_t)task * (uint32_t)tv.B);
             while (todo) {
                 const int l = __builtin_ctzll(todo);
@@ -921,6 +931,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                 }
             }
         }
+        st_none += (uint32_t)__builtin_popcountll(__ballot(have && !final_miss && ans < 0));
         if (kSecond) {
             if (have && ans >= 0) {
                 q.out[qi] = ans; q.tier[qi] = 2;
@@ -1019,10 +1030,16 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             }
         }
     }
-    if (kFirst) {
-        __syncthreads();
-        if (tid == 0) q.open_count[blockIdx.x] = (int32_t)s_open;
+    // statistics of this launch, per workgroup (plain stores: nothing waits for them)
+    if (lane == 0) {
+        const uint32_t st[kLookupStats] = {st_parked, st_second, st_global, st_scanned, st_none};
+#pragma unroll
+        for (int i = 0; i < kLookupStats; ++i)
+            if (st[i]) atomicAdd(&lds_w[4 + i], st[i]);
     }
+    __syncthreads();
+    if (tid < kLookupStats) ix.stats[blockIdx.x * kLookupStats + tid] = lds_w[4 + tid];
+    if (kFirst && tid == 0) q.open_count[blockIdx.x] = (int32_t)s_open;
 }
 
 }  // namespace

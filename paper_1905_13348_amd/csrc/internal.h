@@ -82,7 +82,11 @@ constexpr uint32_t kRowHiField = 32 - kLdsAddrBits;   // bits for the high row b
 constexpr uint32_t kHdrDeep = 1u << 31;      // a miss in the first body is not final (second body, truncation or
                                              // no usable body); the sign bit, so that one compare tests it
 constexpr uint32_t kLdsHdrBytes = 8;         // per slice in the lookup kernel's LDS: {body address, y | first step}
-constexpr uint32_t kLdsCtrlBytes = 16;       // control words at the start of the lookup kernel's LDS
+constexpr uint32_t kLdsCtrlBytes = 48;       // control words at the start of the lookup kernel's LDS: 2 next unit, 3 records
+                                             // in the open list, 4..8 the statistics below
+constexpr int kLookupStats = 5;              // per launch and workgroup: queries parked; of those, answered by a second body,
+                                             // by a first body read from global memory, sent through the rank-ordered
+                                             // scan, and left without an answer
 
 // LDS bytes of the S + 1 slice headers, padded so that the bodies behind them are 16-byte aligned
 __host__ __device__ inline uint32_t lds_header_bytes(int32_t S) { return (((uint32_t)S + 1u) * kLdsHdrBytes + 15u) & ~15u; }
@@ -102,6 +106,7 @@ struct IndexView {
     uint32_t hot_rows;   // rows kept in front of the first body of every slice (fills the LDS left over)
     uint32_t row_hi_bits;// bits of a row number above its low 16
     uint32_t *ctrl;      // [kCtlWords] counters of the build, see kCtl*
+    uint32_t *stats;     // [workgroups of the lookup kernel][kLookupStats] what the most recent lookup launch did
 };
 // Counters of the index build.  Every slice takes its room with one 64-bit add on the pair
 // (kCtlPool, kCtlSteps) and waits for the answer; the statistics live on a cache line of their
