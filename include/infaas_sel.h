@@ -139,6 +139,29 @@ int infaas_sel_select(infaas_sel_t *h, int64_t N,
                       int32_t *d_out_variant, void *hip_stream);
 
 /*
+ * infaas_sel_select for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results.  It calls
+ * no allocating routine, not even on its first use: the one scratch buffer of the lookup kernel
+ * (the queues in which its wavefronts park the queries their first probe cannot decide) is a
+ * static device array of 20 MiB inside the library, which every GPU the library runs on holds
+ * from the moment the library's code is loaded there until the process ends; its address is
+ * looked up in infaas_sel_create.  Limits: at most INFAAS_SEL_NOALLOC_MAX_QUERIES queries per
+ * call (more: INVALID_ARG; split the batch), a device with at most 256 compute units, and a
+ * handle that answers through the staircase index (not INFAAS_SEL_ENGINE_SCAN, whose bucketing
+ * needs 20 bytes of scratch per query).  After infaas_sel_load_states it answers from the Active
+ * variants only, like infaas_sel_select.  Kernel timing (infaas_sel_set_timing) does not cover it.
+ * All calls on one GPU share the array, whichever handle or stream they use: calls that
+ * overlap in time on one GPU race and give wrong answers; order them (one stream, or events).
+ * Nothing in the array has to survive from call to call and nothing in it needs clearing.
+ * Errors: INVALID_ARG (also the limits above; infaas_sel_last_error() says which), NOT_LOADED, HIP.
+ */
+#define INFAAS_SEL_NOALLOC_MAX_QUERIES ((int64_t)1 << 28)
+int infaas_sel_select_noalloc(infaas_sel_t *h, int64_t N,
+                              const int32_t *d_task, const int32_t *d_slo_us,
+                              const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
+                              int32_t *d_out_variant, void *hip_stream);
+
+/*
  * infaas_sel_select plus a suggestion for the queries that nothing satisfies: the last step
  * of Section 4.1's Case I, where a variant that comes closest to the accuracy and/or latency
  * target is proposed when no registered variant meets the requirements.  The paper names no

@@ -6,6 +6,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <numeric>
 #include <vector>
@@ -46,6 +47,35 @@ struct TimedLaunch {
     int kid;
     hipEvent_t a, b;
 };
+
+// ---- scratch memory for infaas_sel_select_noalloc
+// The lookup kernel keeps one queue of parked queries per wavefront; every other entry point takes
+// them from a hipMalloc'ed block of the handle.  For callers that may not allocate, the same queues
+// live in this array, which the code object brings with it: 256 workgroups x 16 wavefronts x 320
+// records x 16 bytes.  Every device the library runs on holds its own copy until the process ends.
+// Host code never passes the array's name to a kernel (on the host the name is only a stand-in for
+// the symbol): static_scratch() looks the device address up once per device and hands that out.
+constexpr int kStaticMaxCus = 256;
+constexpr size_t kStaticScratchBytes = (size_t)kStaticMaxCus * 16 * 320 * 16;   // 20 MiB
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on device `dev`, which must be the current device.  Null on failure
+// (the reason is then in infaas_sel_last_error()).
+void *static_scratch(int dev)
+{
+    if (dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (!hip_ok(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)")) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
 
 template <typename T>
 hipError_t dev_alloc(T **p, size_t count)
@@ -99,6 +129,7 @@ struct infaas_sel {
     uint32_t ix_stats[kCtlWords] = {0};      // copy of ix.ctrl taken after the build at load time
     int32_t *d_park = nullptr;        // queues of parked queries of the lookup kernel (fixed size)
     int64_t park_bytes = 0;
+    int32_t *static_park = nullptr;   // the same queues inside the library's static device array (may be null)
     const uint32_t *last_stats = nullptr;   // statistics of the most recent lookup launch (this table's or the Inactive tier's)
 
     // scan scratch
@@ -455,6 +486,12 @@ int infaas_sel_create(const infaas_sel_config *cfg, infaas_sel_t **out)
         return INFAAS_SEL_ERR_HIP;
     }
     h->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    {
+        // address of the static scratch array on this device, for infaas_sel_select_noalloc (a
+        // failure here only makes that one call unavailable)
+        DeviceGuard g(h->device);
+        if (g.ok) h->static_park = (int32_t *)static_scratch(h->device);
+    }
     *out = h;
     return INFAAS_SEL_OK;
 }
@@ -971,6 +1008,48 @@ int infaas_sel_update_workers(infaas_sel_t *h, int32_t n, const int32_t *d_worke
     if (!HIP_OK(launch_worker_report(h->wv, n, d_worker_idx, d_worker_util, m, d_inst_idx, d_inst_load, st, t.ev())))
         return INFAAS_SEL_ERR_HIP;
     h->workers_dirty = true;
+    return INFAAS_SEL_OK;
+}
+
+int infaas_sel_select_noalloc(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,
+                              const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
+                              int32_t *d_out_variant, void *hip_stream)
+{
+    if (!h || N < 0) return INFAAS_SEL_ERR_INVALID_ARG;
+    if (!h->loaded) return INFAAS_SEL_ERR_NOT_LOADED;
+    if (N > INFAAS_SEL_NOALLOC_MAX_QUERIES) {
+        snprintf(g_last_error, sizeof(g_last_error), "infaas_sel_select_noalloc: %lld queries exceed the limit of %lld per call",
+                 (long long)N, (long long)INFAAS_SEL_NOALLOC_MAX_QUERIES);
+        return INFAAS_SEL_ERR_INVALID_ARG;
+    }
+    if (!h->have_index || !use_index(h)) {
+        snprintf(g_last_error, sizeof(g_last_error),
+                 "infaas_sel_select_noalloc needs the staircase index (the exhaustive scan buckets the queries in memory it allocates)");
+        return INFAAS_SEL_ERR_INVALID_ARG;
+    }
+    if (index_park_bytes(h->num_cus) > kStaticScratchBytes) {
+        snprintf(g_last_error, sizeof(g_last_error),
+                 "infaas_sel_select_noalloc: the static scratch array is sized for %d compute units, this device has %d",
+                 kStaticMaxCus, h->num_cus);
+        return INFAAS_SEL_ERR_INVALID_ARG;
+    }
+    if (!h->static_park) {
+        snprintf(g_last_error, sizeof(g_last_error), "infaas_sel_select_noalloc: the address of the static scratch array is not known");
+        return INFAAS_SEL_ERR_HIP;
+    }
+    if (N == 0) return INFAAS_SEL_OK;
+    if (!d_task || !d_slo_us || !d_min_acc_bp || !d_batch_idx || !d_out_variant) return INFAAS_SEL_ERR_INVALID_ARG;
+    DeviceGuard g(h->device);
+    if (!g.ok) return INFAAS_SEL_ERR_HIP;
+    QueryView q{};
+    q.n = (int32_t)N;
+    q.task = d_task; q.slo = d_slo_us; q.min_acc = d_min_acc_bp; q.bidx = d_batch_idx; q.out = d_out_variant;
+    q.pass = 0;
+    // no event pair even when timing is on: taking one may create it
+    if (!HIP_OK(launch_index_select(h->tv, h->ix, q, h->static_park, h->index_lds_bytes, h->num_cus,
+                                    (hipStream_t)hip_stream, nullptr)))
+        return INFAAS_SEL_ERR_HIP;
+    h->last_stats = h->ix.stats;
     return INFAAS_SEL_OK;
 }
 
