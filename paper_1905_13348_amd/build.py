@@ -14,8 +14,8 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Wall", "-Wextra", "-Wno-unused-parameter", "-Wno-int-to-pointer-cast",
-    # keep the compiler from forming packed-fp32 instructions (no float code here, but the
-    # flag is part of how every HIP file of this library is built)
+    # keep the compiler from forming packed-fp32 instructions (the only float code is the
+    # double-precision quotient estimate of the scaling decisions)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
 

@@ -4,9 +4,9 @@
 // its brute-force search needs ~100 ms because its metadata store keeps sorted sets
 // (Sections 5 and 6.4); this is the exact, batched GPU counterpart of that idea.
 //
-//   k_index_build  : one workgroup per (task, batch) slice finds the "steps" (variants that no
-//                    cheaper one dominates) with block-wise and all-pairs tests, then writes
-//                    sorted keys and bit sets for them (layout: internal.h)
+//   k_index_build  : one wavefront per (task, batch) slice finds the "steps" (variants that no
+//                    cheaper one dominates), in rounds over a shrinking list of candidates, then
+//                    writes sorted keys and bit sets for them (layout: internal.h)
 //   k_index_select : one lane per query.  The whole index is mirrored in LDS; a query costs two
 //                    5-probe binary searches in LDS, two bit-set reads, one AND and one count-
 //                    trailing-zeros.  Queries the first body of their slice cannot decide (no
@@ -39,26 +39,51 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
 
 // ---------------------------------------------------------------- build
 
+// Orders the LDS traffic of ONE wavefront: what its lanes have written is visible to its other lanes.
+__device__ __forceinline__ void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+
 // Body of steps [g0, g0 + kb), held one per lane (lanes g0..g0+kb-1), in two parts: what can be
 // computed before the body's place in the pool is known, and the stores.
 struct BodyRegs {
     int32_t pa, ps;     // position of this lane's step in the sorted accuracy / latency keys
     uint32_t ma, ms;    // lane p: A[p] and S[p], the steps among the p most accurate / p fastest
 };
-__device__ __forceinline__ BodyRegs body_compute(int g0, int kb, int lane, int32_t st_acc, uint32_t st_tot)
+// Steps [g0, g0 + kb) of a slice: lane j holds step j in (st_acc, st_tot), and p_acc / p_tot hold all
+// steps in LDS.  `ranks` is scratch of the wavefront (2 x 64 words).  Values that all lanes need are
+// read from LDS (one address for all lanes), so the loops are plain vector code.
+__device__ __forceinline__ BodyRegs body_compute(int g0, int kb, int lane, int32_t st_acc, uint32_t st_tot,
+                                                 const int32_t *p_acc, const uint32_t *p_tot, int32_t *ranks)
 {
     BodyRegs r{0, 0, 0u, 0u};
-    for (int j = g0; j < g0 + kb; ++j) {
-        const int32_t aj = __builtin_amdgcn_readlane(st_acc, j);
-        const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)st_tot, j);
-        r.pa += (aj > st_acc || (aj == st_acc && j < lane)) ? 1 : 0;
-        r.ps += (tj < st_tot || (tj == st_tot && j < lane)) ? 1 : 0;
+    const int g1 = g0 + kb;
+    for (int j0 = g0; j0 < g1; j0 += 4) {   // four steps per turn, so that their LDS reads overlap
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int j = j0 + u < g1 ? j0 + u : g1 - 1;
+            const bool in = j0 + u < g1;
+            const int32_t aj = p_acc[j];
+            const uint32_t tj = p_tot[j];
+            r.pa += (int32_t)(in & ((aj > st_acc) | ((aj == st_acc) & (j < lane))));   // (no short-circuit: no branches)
+            r.ps += (int32_t)(in & ((tj < st_tot) | ((tj == st_tot) & (j < lane))));
+        }
     }
-    for (int j = g0; j < g0 + kb; ++j) {
-        const int32_t paj = __builtin_amdgcn_readlane(r.pa, j), psj = __builtin_amdgcn_readlane(r.ps, j);
-        const uint32_t bit = 1u << (j - g0);
-        r.ma |= paj < lane ? bit : 0u;
-        r.ms |= psj < lane ? bit : 0u;
+    wave_sync();   // (an earlier body's ranks have been read)
+    ranks[lane] = r.pa;
+    ranks[64 + lane] = r.ps;
+    wave_sync();
+    for (int j0 = g0; j0 < g1; j0 += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int j = j0 + u < g1 ? j0 + u : g1 - 1;
+            const uint32_t bit = j0 + u < g1 ? 1u << (j - g0) : 0u;
+            r.ma |= ranks[j] < lane ? bit : 0u;
+            r.ms |= ranks[64 + j] < lane ? bit : 0u;
+        }
     }
     return r;
 }
@@ -81,265 +106,280 @@ __device__ __forceinline__ void body_store(uint8_t *body, int g0, int kb, int la
     if (lane < (int)re) { m_a[lane] = r.ma; m_s[lane] = r.ms; }   // lanes beyond kb hold the full set
 }
 
-constexpr int kBuildThreads = 512;
-constexpr int kBuildWaves = kBuildThreads / 64;
-constexpr int kBuildChunk = 2048;                          // entries of a slice staged in LDS at a time
-constexpr int kBuildBlocks = kBuildChunk / 64;             // blocks of 64 entries in a chunk
-constexpr int kBlocksPerWave = kBuildBlocks / kBuildWaves;
+constexpr int kBuildWaves = 4;                    // slices (wavefronts) per workgroup
 
-// alive &= none of the entries held by lanes [j0, j1) of (ra, rt) -- entry j of them being number
-// first + j of some rank-ordered list -- precedes entry number `me` and dominates (a, tt).
-// The loop reads lanes, not memory, so that nothing in it waits.
-__device__ __forceinline__ bool not_dominated(bool alive, int32_t a, uint32_t tt, int32_t ra, uint32_t rt,
-                                              int j0, int j1, int32_t first, int32_t me)
+// One wavefront per slice, kBuildWaves slices per workgroup.  An entry of the slice is a step exactly
+// when no entry ranked before it has at least its accuracy and at most its latency-plus-queue; that
+// relation is transitive, so it is enough to test an entry against the earlier STEPS.  The wavefront
+// takes in a chunk of the rank-ordered columns, kBuildPer (32 or 16) entries per lane, in registers.  Then
+//   1. (first chunk) the steps among the first 64 entries: the first of them is a step (nothing
+//      earlier is left), it retires what it dominates among the 64, the next one left is a step, ...;
+//   2. a coarse filter: from the steps known so far, a table over ~32 accuracy buckets of the lowest
+//      latency-plus-queue among the steps that are at least as accurate as EVERYTHING in the bucket;
+//      an entry at or above its bucket's value is dominated for certain and dropped (one LDS read
+//      and a compare per entry; nine entries in ten go here).  The others are compacted into a list
+//      of candidates in LDS, in rank order;
+//   3. rounds over the list until it is empty: the candidates are tested exactly against the steps
+//      they have not been tested against yet (four blocks of 64 at a time, a step's values read
+//      from its lane once per group; survivors compacted in place), then the steps among the first
+//      64 survivors are found as in 1 and leave the list.
+// Steps come out in rank order, so when a slice has more than the index keeps, the ones kept are
+// its first ones.  The steps sit one per lane (and in LDS); the same wavefront computes the bodies.
+// Room in the pool is taken by ONE 64-bit add per workgroup (with one per slice, every slice waited
+// microseconds for its turn at the counter).  The larger chunk is faster for slices of thousands of
+// variants; the smaller one takes half the LDS and registers, so that twice as many workgroups run
+// at a time when there are thousands of slices.
+template <int kBuildPer>
+__global__ __launch_bounds__(64 * kBuildWaves) void k_index_build(TableView tv, IndexView ix)
 {
-    for (int j = j0; j < j1; ++j) {
-        const int32_t aj = __builtin_amdgcn_readlane(ra, j);
-        const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)rt, j);
-        alive = alive && !(first + j < me && aj >= a && tj <= tt);
-    }
-    return alive;
-}
-
-// One workgroup per slice.  An entry of the slice is a step exactly when no entry ranked before it
-// has at least its accuracy and at most its latency-plus-queue; because that relation is
-// transitive it is enough to test against earlier STEPS, or against any set of earlier entries
-// that contains them.  Per staged chunk of the rank-ordered columns:
-//   0. (first chunk) the first wavefront finds the steps among the first 64 entries;
-//   1. every wavefront, for its blocks of 64 entries: drop what a step known so far dominates,
-//      then what an earlier entry of the same block dominates;
-//   2. the survivors ("candidates", a few per block) are compacted in rank order;
-//   3. 512 candidates at a time, each is tested against the steps accepted since the chunk began
-//      and against the candidates in front of it in its batch; what is left are steps.
-// Nothing in it is sequential in the number of steps.  The first wavefront then writes the bodies.
-__global__ __launch_bounds__(kBuildThreads) void k_index_build(TableView tv, IndexView ix)
-{
-    __shared__ int32_t s_acc[kBuildChunk];
-    __shared__ uint32_t s_tot[kBuildChunk];
-    __shared__ v2u c_at[kBuildChunk];            // candidates: {accuracy, latency + queue}
-    __shared__ int32_t c_pos[kBuildChunk];       //             rank position in the slice
-    __shared__ int32_t p_acc[kIndexCap];         // steps, in rank order
-    __shared__ uint32_t p_tot[kIndexCap];
-    __shared__ int32_t p_pos[kIndexCap];
-    __shared__ int32_t s_cnt[kBuildBlocks];      // survivors per block; then accepted candidates per wavefront
-    __shared__ int32_t s_K, s_trunc;
-    const int32_t s = blockIdx.x;
-    if (s >= tv.S) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int32_t t = s / tv.B, b = s - t * tv.B;
-    const int32_t seg = tv.seg_off[t], L = tv.seg_len[t];
-    if (L == 0) {  // no variants: the empty dummy body at offset 0 answers "nothing feasible"
-        if (tid == 0) ix.hdr[s] = make_uint4(0u, kEmptyHdrY, 0u, 4u + body_bytes(2));
-        return;
-    }
+    constexpr int kBuildChunk = 64 * kBuildPer;   // entries of a slice taken in at a time
+    __shared__ int32_t c_acc_all[kBuildWaves][kBuildChunk];    // candidates: accuracy,
+    __shared__ uint32_t c_tot_all[kBuildWaves][kBuildChunk];   //   latency + queue,
+    __shared__ uint16_t c_pos_all[kBuildWaves][kBuildChunk];   //   position in the chunk
+    __shared__ int32_t p_acc_all[kBuildWaves][64];             // steps, in rank order
+    __shared__ uint32_t p_tot_all[kBuildWaves][64];
+    __shared__ int32_t p_pos_all[kBuildWaves][64];
+    __shared__ uint32_t f_tab_all[kBuildWaves][64];            // the coarse filter's table
+    __shared__ int32_t ranks_all[kBuildWaves][128];            // scratch of body_compute
+    __shared__ uint32_t s_size[kBuildWaves], s_steps[kBuildWaves], s_stat[4];
+    __shared__ unsigned long long s_room;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int32_t *c_acc = c_acc_all[wave], *p_acc = p_acc_all[wave], *p_pos = p_pos_all[wave];
+    uint32_t *c_tot = c_tot_all[wave], *p_tot = p_tot_all[wave], *f_tab = f_tab_all[wave];
+    uint16_t *c_pos = c_pos_all[wave];
+    const int32_t s = blockIdx.x * kBuildWaves + wave;
+    const bool inside = s < tv.S;
+    const int32_t t = inside ? s / tv.B : 0, b = inside ? s - t * tv.B : 0;
+    const int32_t seg = tv.seg_off[t], L = inside ? tv.seg_len[t] : 0;
     const int32_t *__restrict__ accc = tv.acc_r + (int64_t)b * tv.Vp + seg;
     const uint32_t *__restrict__ totc = tv.tot_r + (int64_t)b * tv.Vp + seg;
 
-    // ---- phase A: the steps, in rank order
-    if (tid == 0) { s_K = 0; s_trunc = 0; }
-    for (int32_t c0 = 0; c0 < L; c0 += kBuildChunk) {
+    // ---- phase A: the steps, in rank order; lane j < K holds step j, p_acc / p_tot / p_pos all of them
+    int32_t K = 0;
+    bool trunc = false;
+    int32_t st_acc = 0, st_pos = 0;
+    uint32_t st_tot = 0u;
+    // Steps among up to 64 candidates held one per lane, lanes [0, nh), in rank order, none of them
+    // dominated by a known step.  The new steps are appended to the step registers.
+    auto take_head = [&](int32_t nh, int32_t a, uint32_t tt, int32_t pos) {
+        bool alive = lane < nh;
+        uint64_t rest = __ballot(alive);
+        while (rest) {   // candidate l is a step (nothing alive precedes it): retire what it dominates
+            const int l = __builtin_ctzll(rest);
+            const int32_t al = __builtin_amdgcn_readlane(a, l);
+            const uint32_t tl = (uint32_t)__builtin_amdgcn_readlane((int)tt, l);
+            alive = alive & !((l < lane) & (al >= a) & (tl <= tt));
+            rest = __ballot(alive) & ~((2ull << l) - 1ull);
+        }
+        const uint64_t ok = __ballot(alive);
+        const int32_t k_new = (int32_t)__builtin_popcountll(ok);
+        const int32_t at = K + (int32_t)lanes_below(ok);
+        if (alive && at < kIndexCap) { p_acc[at] = a; p_tot[at] = tt; p_pos[at] = pos; }
+        trunc = K + k_new > kIndexCap;   // more steps than the index keeps: its first ones stay
+        K = trunc ? kIndexCap : K + k_new;
+        wave_sync();
+        st_acc = lane < K ? p_acc[lane] : 0;
+        st_tot = lane < K ? p_tot[lane] : 0u;
+        st_pos = lane < K ? p_pos[lane] : 0;
+    };
+    for (int32_t c0 = 0; c0 < L && !trunc; c0 += kBuildChunk) {
         const int32_t n = L - c0 < kBuildChunk ? L - c0 : kBuildChunk;
-        const int32_t nblk = (n + 63) >> 6;
+        int32_t va[kBuildPer];
+        uint32_t vt[kBuildPer];
+        uint32_t dead = 0u;   // bit k: entry k of this lane is outside the chunk, dominated, or taken care of
+#pragma unroll
+        for (int k = 0; k < kBuildPer; ++k) {   // unconditional loads (clamped), so that they overlap
+            const int32_t i = k * 64 + lane;
+            const int32_t j = c0 + (i < n ? i : n - 1);
+            va[k] = accc[j];
+            vt[k] = totc[j];
+            dead |= i >= n ? 1u << k : 0u;
+        }
+        if (K == 0) {   // 1. nothing is known yet: the first 64 entries, exactly
+            take_head(n < 64 ? n : 64, va[0], vt[0], c0 + lane);
+            if (trunc) break;
+            dead |= 1u;
+        }
+        // 2. coarse filter.  Accuracies from the lowest (mn) to the highest (mx) of the steps are cut
+        // into buckets of 2^sh; table entry 0 is for entries below mn, entry 1 + q for bucket q, entry
+        // 33 for entries above mx.
         {
-            constexpr int kPer = kBuildChunk / kBuildThreads;
-            int32_t va[kPer];
-            uint32_t vt[kPer];
+            int32_t mn = p_acc[0], mx = mn;
+            for (int j0 = 1; j0 < K; j0 += 8) {   // (eight per turn: the LDS reads overlap)
 #pragma unroll
-            for (int u = 0; u < kPer; ++u) {   // unconditional loads (clamped), so that they overlap
-                const int32_t i = u * kBuildThreads + tid;
-                const int32_t j = c0 + (i < n ? i : n - 1);
-                va[u] = accc[j];
-                vt[u] = totc[j];
-            }
-#pragma unroll
-            for (int u = 0; u < kPer; ++u) {
-                const int32_t i = u * kBuildThreads + tid;
-                s_acc[i] = va[u];
-                s_tot[i] = vt[u];
-            }
-        }
-        __syncthreads();
-        // 0. (first chunk) the steps among the first 64 entries, found by the first wavefront alone:
-        //    nothing precedes them, and they already dominate most of what follows
-        if (c0 == 0) {
-            if (wave == 0) {
-                const int32_t a = s_acc[lane];
-                const uint32_t tt = s_tot[lane];
-                bool alive = lane < n;
-                uint64_t rest = __ballot(alive);
-                while (rest) {   // entry l is a step (nothing alive precedes it): retire what it dominates
-                    const int l = __builtin_ctzll(rest);
-                    const int32_t al = __builtin_amdgcn_readlane(a, l);
-                    const uint32_t tl = (uint32_t)__builtin_amdgcn_readlane((int)tt, l);
-                    alive = alive && !(l < lane && al >= a && tl <= tt);
-                    rest = __ballot(alive) & ~((2ull << l) - 1ull);
+                for (int u = 0; u < 8; ++u) {
+                    const int32_t aj = p_acc[j0 + u < K ? j0 + u : 0];
+                    mn = aj < mn ? aj : mn;
+                    mx = aj > mx ? aj : mx;
                 }
-                const uint64_t ok = __ballot(alive);
-                const int32_t at = (int32_t)lanes_below(ok), k = (int32_t)__builtin_popcountll(ok);
-                if (alive && at < kIndexCap) { p_acc[at] = a; p_tot[at] = tt; p_pos[at] = lane; }
-                if (lane == 0) { s_K = k < kIndexCap ? k : kIndexCap; s_trunc = k > kIndexCap; }
             }
-            __syncthreads();
-            if (s_trunc) break;
-        }
-        // The first chunk goes in two groups of blocks, 1..7 and the rest: the steps of the first 512
-        // entries leave very little of the rest alive.
-        bool stop = false;
-        for (int32_t gb = c0 == 0 ? 1 : 0; gb < nblk && !stop;) {
-            const int32_t ge = (c0 == 0 && gb == 1 && nblk > 8) ? 8 : nblk;
-            const int32_t K0 = s_K;   // steps known when the group starts
-
-            // 1. survivors of every block of the group (blocks dealt round-robin to the wavefronts)
-            const int32_t ka = lane < K0 ? p_acc[lane] : 0;   // lane j holds step j
-            const uint32_t kt = lane < K0 ? p_tot[lane] : 0u;
-            uint64_t live[kBlocksPerWave];
+            const uint32_t range = (uint32_t)mx - (uint32_t)mn;
+            const int bits = 32 - __builtin_clz(range | 1u);
+            const uint32_t sh = bits > 5 ? (uint32_t)(bits - 5) : 0u;   // range >> sh < 32
+            // lane i: the lowest latency-plus-queue among the steps at least as accurate as all of
+            // bucket i, i.e. with (accuracy - mn + 1) >> sh >= i (entry 0: every step); none: all ones
+            uint32_t f = 0xFFFFFFFFu;
+            for (int j0 = 0; j0 < K; j0 += 4) {
 #pragma unroll
-            for (int u = 0; u < kBlocksPerWave; ++u) {
-                const int32_t blk = gb + wave + kBuildWaves * u;
-                live[u] = 0;
-                if (blk < ge) {
-                    const int32_t i = blk * 64 + lane;
-                    const int32_t a = s_acc[i];
-                    const uint32_t tt = s_tot[i];
-                    bool alive = not_dominated(i < n, a, tt, ka, kt, 0, K0, 0, 0x7FFFFFFF);
-                    uint64_t rest = __ballot(alive);
-                    while (rest) {   // what is left, against the entries of the block in front of it
-                        const int l = __builtin_ctzll(rest);
-                        rest &= rest - 1;
-                        const int32_t al = __builtin_amdgcn_readlane(a, l);
-                        const uint32_t tl = (uint32_t)__builtin_amdgcn_readlane((int)tt, l);
-                        alive = alive && !(l < lane && al >= a && tl <= tt);
+                for (int u = 0; u < 4; ++u) {
+                    const int j = j0 + u < K ? j0 + u : 0;   // (step 0 again: harmless)
+                    const uint64_t uj = (uint64_t)((uint32_t)p_acc[j] - (uint32_t)mn) + 1u;
+                    const uint32_t tj = p_tot[j];
+                    const bool covers = (uint32_t)(uj >> sh) >= (uint32_t)lane;
+                    f = (covers & (tj < f)) ? tj : f;
+                }
+            }
+            f_tab[lane] = lane <= 33 ? f : 0xFFFFFFFFu;
+            if (lane == 33) f_tab[33] = 0xFFFFFFFFu;   // above every step: never dominated
+            wave_sync();
+#pragma unroll
+            for (int k = 0; k < kBuildPer; ++k) {
+                const uint32_t u = (uint32_t)va[k] - (uint32_t)mn;
+                uint32_t idx = 1u + (u >> sh);
+                idx = idx > 33u ? 33u : idx;
+                idx = va[k] < mn ? 0u : idx;
+                const uint32_t fv = f_tab[idx];
+                dead |= ((fv != 0xFFFFFFFFu) & (fv <= vt[k])) ? 1u << k : 0u;
+            }
+        }
+        // what is left becomes the candidate list, entries [beg, end) of the LDS arrays
+        int32_t beg = 0, end = 0;
+#pragma unroll
+        for (int k = 0; k < kBuildPer; ++k) {
+            const bool live = !((dead >> k) & 1u);
+            const uint64_t m = __ballot(live);
+            const int32_t at = end + (int32_t)lanes_below(m);
+            if (live) { c_acc[at] = va[k]; c_tot[at] = vt[k]; c_pos[at] = (uint16_t)(k * 64 + lane); }
+            end += (int32_t)__builtin_popcountll(m);
+        }
+        wave_sync();
+        // 3. rounds
+        int32_t applied = 0;   // the list has been tested exactly against steps [0, applied)
+        while (beg < end) {
+            // the candidates against the steps they have not met; survivors compacted in place (four
+            // blocks are read before anything is written, and written at or below where they were read)
+            int32_t out = beg;
+            for (int32_t i0 = beg; i0 < end; i0 += 256) {
+                int32_t ca[4];
+                uint32_t ct[4];
+                uint16_t cp[4];
+                bool gone[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int32_t i = i0 + u * 64 + lane;
+                    const int32_t ci = i < end ? i : beg;
+                    ca[u] = c_acc[ci]; ct[u] = c_tot[ci]; cp[u] = c_pos[ci];
+                    gone[u] = i >= end;
+                }
+                for (int j = applied; j < K; ++j) {
+                    const int32_t aj = __builtin_amdgcn_readlane(st_acc, j);
+                    const uint32_t tj = (uint32_t)__builtin_amdgcn_readlane((int)st_tot, j);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) gone[u] = gone[u] | ((aj >= ca[u]) & (tj <= ct[u]));
+                }
+                wave_sync();
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint64_t m = __ballot(!gone[u]);
+                    if (!gone[u]) {
+                        const int32_t to = out + (int32_t)lanes_below(m);
+                        c_acc[to] = ca[u]; c_tot[to] = ct[u]; c_pos[to] = cp[u];
                     }
-                    live[u] = __ballot(alive);
-                    if (lane == 0) s_cnt[blk] = (int32_t)__builtin_popcountll(live[u]);
+                    out += (int32_t)__builtin_popcountll(m);
                 }
             }
-            __syncthreads();
-
-            // 2. candidates, compacted in rank order
-            int32_t pre[kBlocksPerWave], total = 0;
-            const int32_t cnt_l = gb + lane < ge ? s_cnt[gb + lane] : 0;   // lane k: block gb + k
-            for (int32_t k = 0; k < ge - gb; ++k) {
-#pragma unroll
-                for (int u = 0; u < kBlocksPerWave; ++u)
-                    if (k == wave + kBuildWaves * u) pre[u] = total;
-                total += __builtin_amdgcn_readlane(cnt_l, k);
-            }
-#pragma unroll
-            for (int u = 0; u < kBlocksPerWave; ++u) {
-                const int32_t i = (gb + wave + kBuildWaves * u) * 64 + lane;
-                if ((live[u] >> lane) & 1ull) {   // only set for blocks of the group
-                    const int32_t at = pre[u] + (int32_t)lanes_below(live[u]);
-                    c_at[at] = v2u{(uint32_t)s_acc[i], s_tot[i]};
-                    c_pos[at] = c0 + i;
-                }
-            }
-            __syncthreads();
-
-            // 3. steps among the candidates, one batch of kBuildThreads at a time
-            for (int32_t b0 = 0; b0 < total && !stop; b0 += kBuildThreads) {
-                const int32_t K1 = s_K;   // steps accepted so far
-                const int32_t c = b0 + tid;
-                const bool have = c < total;
-                const v2u me = c_at[have ? c : 0];
-                const int32_t a = (int32_t)me.x;
-                const uint32_t tt = me.y;
-                const int32_t na = lane < K1 ? p_acc[lane] : 0;   // steps accepted in this group before the batch
-                const uint32_t nt = lane < K1 ? p_tot[lane] : 0u;
-                bool alive = not_dominated(have, a, tt, na, nt, K0, K1, 0, 0x7FFFFFFF);
-                const int32_t w0 = b0 + wave * 64;   // first and last candidate of this wavefront
-                const int32_t last = w0 >= total ? b0 : (w0 + 63 < total ? w0 + 63 : total - 1);
-                for (int32_t e0 = b0; e0 < last; e0 += 64) {   // the candidates in front, 64 at a time
-                    const v2u o = c_at[e0 + lane < total ? e0 + lane : 0];
-                    alive = not_dominated(alive, a, tt, (int32_t)o.x, o.y, 0, last - e0 < 64 ? last - e0 : 64, e0, c);
-                }
-                const uint64_t ok = __ballot(alive);
-                if (lane == 0) s_cnt[wave] = (int32_t)__builtin_popcountll(ok);
-                __syncthreads();
-                int32_t at = K1, accepted = 0;
-                const int32_t cnt_w = lane < kBuildWaves ? s_cnt[lane] : 0;
-#pragma unroll
-                for (int w = 0; w < kBuildWaves; ++w) {
-                    const int32_t cw = __builtin_amdgcn_readlane(cnt_w, w);
-                    accepted += cw;
-                    at += w < wave ? cw : 0;
-                }
-                at += (int32_t)lanes_below(ok);
-                if (alive && at < kIndexCap) { p_acc[at] = a; p_tot[at] = tt; p_pos[at] = c_pos[c]; }
-                stop = K1 + accepted > kIndexCap;   // more steps than the index keeps: truncated
-                __syncthreads();
-                if (tid == 0) { s_K = stop ? kIndexCap : K1 + accepted; if (stop) s_trunc = 1; }
-                __syncthreads();
-            }
-            gb = ge;
+            end = out;
+            applied = K;
+            wave_sync();
+            if (beg >= end) break;
+            // the steps among the first 64 of them
+            const int32_t nh = end - beg < 64 ? end - beg : 64;
+            const int32_t hi = beg + (lane < nh ? lane : 0);
+            take_head(nh, c_acc[hi], c_tot[hi], c0 + (int32_t)c_pos[hi]);
+            if (trunc) break;
+            beg += nh;
         }
-        if (stop) break;
     }
-    // ---- phase B: one or two bodies of sorted keys and bit sets.  The first wavefront takes the
-    // first body, the rows and the header, the second wavefront the second body; both compute
-    // their part while the request for room in the pool is under way.
-    if (wave > 1) return;
-    const int32_t K = s_K;
-    const bool trunc = s_trunc != 0;
-    const int32_t st_acc = lane < K ? p_acc[lane] : 0, st_pos = lane < K ? p_pos[lane] : 0;
-    const uint32_t st_tot = lane < K ? p_tot[lane] : 0u;
+
+    // ---- phase B: one or two bodies of sorted keys and bit sets, computed while the workgroup's
+    // request for room in the pool is under way
     const int k0 = K < kBodySteps ? K : kBodySteps, k1 = K - k0;
-    if (wave == 1 && k1 == 0) return;
     const uint32_t r0 = (uint32_t)k0 < ix.hot_rows ? (uint32_t)k0 : ix.hot_rows;
     const uint32_t re0 = body_re(k0), re1 = k1 ? body_re(k1) : 0u;
-    const uint32_t rows = (2u * r0 + 3u) & ~3u, size0 = body_bytes(re0), size = rows + size0 + body_bytes(re1);
-    __shared__ uint32_t s_off, s_fits;
-    int32_t row = 0;
-    uint32_t row_hi = 0;
-    if (wave == 0) {
-        // room in the pool and in step_row: one 64-bit add on the pair of counters (pool in the low word)
-        unsigned long long old = 0;
-        if (lane == 0) old = atomicAdd((unsigned long long *)(ix.ctrl + kCtlPool), ((unsigned long long)K << 32) | size);
-        // caller rows of the steps; of the first ones the low 16 bits go in front of the body, the
-        // bits above into the header
-        row = lane < K ? tv.orig_r[(int64_t)b * tv.Vp + seg + st_pos] : 0;
-        int32_t hi = __builtin_amdgcn_readlane(st_acc, 0), lo = hi;
-        for (int32_t j = 1; j < K; ++j) {
-            const int32_t aj = __builtin_amdgcn_readlane(st_acc, j);
+    const uint32_t rows = (2u * r0 + 3u) & ~3u, size0 = body_bytes(re0);
+    const uint32_t size = L > 0 ? rows + size0 + body_bytes(re1) : 0u;   // (a multiple of 4)
+    if (lane == 0) { s_size[wave] = size; s_steps[wave] = (uint32_t)K; }
+    if (threadIdx.x < 4) s_stat[threadIdx.x] = 0u;
+    // caller rows of the steps (requested here, used after the bodies have been computed)
+    const int32_t row = lane < K ? tv.orig_r[(int64_t)b * tv.Vp + seg + st_pos] : 0;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        // room in the pool and in step_row for all slices of the workgroup: one 64-bit add on the
+        // pair of counters (pool in the low word)
+        uint32_t bytes = 0, steps = 0;
+        for (int w = 0; w < kBuildWaves; ++w) { bytes += s_size[w]; steps += s_steps[w]; }
+        s_room = bytes ? atomicAdd((unsigned long long *)(ix.ctrl + kCtlPool), ((unsigned long long)steps << 32) | bytes) : 0ull;
+    }
+    int32_t hi = st_acc, lo = st_acc;   // (of lane 0, a step whenever the slice has variants)
+    hi = __builtin_amdgcn_readfirstlane(hi); lo = hi;
+    for (int32_t j0 = 1; j0 < K; j0 += 8) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int32_t aj = p_acc[j0 + u < K ? j0 + u : 0];
             hi = aj > hi ? aj : hi;
             lo = aj < lo ? aj : lo;
         }
-        const BodyRegs r = body_compute(0, k0, lane, st_acc, st_tot);
-        for (uint32_t j = 0; j < r0; ++j)
-            row_hi |= ((uint32_t)__builtin_amdgcn_readlane(row, (int)j) >> 16) << (j * ix.row_hi_bits);
-        const uint32_t off = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)old);
-        const uint32_t rec = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(old >> 32));
-        const bool fits = (uint64_t)off + size <= ix.pool_bytes && (uint64_t)rec + K <= ix.step_cap &&
-                          (int64_t)hi - (int64_t)tv.acc_base <= 65533 && lo >= tv.acc_base;   // 16-bit accuracy keys
-        if (lane == 0) { s_off = off; s_fits = fits; }
-        __syncthreads();
-        if (!fits) {  // no body: every query of this slice goes to the rank-ordered scan
-            if (lane == 0) {
-                ix.hdr[s] = make_uint4(0u, kEmptyHdrY | kHdrPark | kHdrTrunc | kHdrDeep, 0u, 0u);
-                atomicAdd(&ix.ctrl[kCtlNoBody], 1u);
-            }
-            return;
-        }
+    }
+    const BodyRegs b0 = body_compute(0, k0, lane, st_acc, st_tot, p_acc, p_tot, ranks_all[wave]);
+    BodyRegs b1{0, 0, 0u, 0u};
+    if (k1) b1 = body_compute(k0, k1, lane, st_acc, st_tot, p_acc, p_tot, ranks_all[wave]);
+    // of the first steps' rows the low 16 bits go in front of the body, the bits above into the header
+    uint32_t row_hi = 0;
+    for (uint32_t j = 0; j < r0; ++j)
+        row_hi |= ((uint32_t)__builtin_amdgcn_readlane(row, (int)j) >> 16) << (j * ix.row_hi_bits);
+    __syncthreads();
+    const bool has = inside && L > 0;
+    uint32_t off = (uint32_t)s_room, rec = (uint32_t)(s_room >> 32);
+    for (int w = 0; w < wave; ++w) { off += s_size[w]; rec += s_steps[w]; }
+    const bool fits = has && (uint64_t)off + size <= ix.pool_bytes && (uint64_t)rec + K <= ix.step_cap &&
+                      (int64_t)hi - (int64_t)tv.acc_base <= 65533 && lo >= tv.acc_base;   // 16-bit accuracy keys
+    if (fits) {
         uint8_t *body0 = ix.pool + off + rows;
-        body_store(body0, 0, k0, lane, st_acc, st_tot, tv.acc_base, r);
+        body_store(body0, 0, k0, lane, st_acc, st_tot, tv.acc_base, b0);
+        if (k1) body_store(body0 + size0, k0, k1, lane, st_acc, st_tot, tv.acc_base, b1);
         if (lane < K) {
             ix.step_row[rec + lane] = row;
             if ((uint32_t)lane < r0)   // in reverse in front of the body
                 *(uint16_t *)(body0 - 2 - 2 * lane) = (uint16_t)row;
         }
-        if (lane == 0) {
+    }
+    if (lane == 0 && inside) {
+        if (fits) {
             const uint32_t y = (re0 << kHdrK0Shift) | (re1 << kHdrK1Shift) | (trunc ? kHdrTrunc : 0u) |
                                ((k1 || trunc) ? kHdrDeep : 0u) | row_hi;
             ix.hdr[s] = make_uint4(off + rows - 4u, y, rec, off + size);
-            atomicMax(&ix.ctrl[kCtlMaxK0], (uint32_t)k0);   // statistics: nobody waits for these
-            atomicMax(&ix.ctrl[kCtlMaxK], (uint32_t)K);
-            if (trunc) atomicAdd(&ix.ctrl[kCtlTrunc], 1u);
+        } else if (has) {   // no body: every query of this slice goes to the rank-ordered scan
+            ix.hdr[s] = make_uint4(0u, kEmptyHdrY | kHdrPark | kHdrTrunc | kHdrDeep, 0u, 0u);
+        } else {            // no variants: the empty dummy body at offset 0 answers "nothing feasible"
+            ix.hdr[s] = make_uint4(0u, kEmptyHdrY, 0u, 4u + body_bytes(2));
         }
-    } else {
-        const BodyRegs r = body_compute(k0, k1, lane, st_acc, st_tot);
-        __syncthreads();
-        if (!s_fits) return;
-        body_store(ix.pool + s_off + rows + size0, k0, k1, lane, st_acc, st_tot, tv.acc_base, r);
+        // statistics, gathered per workgroup first: thousands of slices adding to one word of global
+        // memory take their turns at ~10 ns each, and the kernel does not end before the last one
+        if (fits) {
+            atomicMax(&s_stat[0], (uint32_t)k0);
+            atomicMax(&s_stat[1], (uint32_t)K);
+            if (trunc) atomicAdd(&s_stat[2], 1u);
+        } else if (has) {
+            atomicAdd(&s_stat[3], 1u);
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < 4 && s_stat[threadIdx.x]) {
+        constexpr int word[4] = {kCtlMaxK0, kCtlMaxK, kCtlTrunc, kCtlNoBody};
+        const uint32_t v = s_stat[threadIdx.x];
+        uint32_t *g = &ix.ctrl[word[threadIdx.x]];
+        if (threadIdx.x >= 2) atomicAdd(g, v);
+        else if (v > __hip_atomic_load(g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMax(g, v);   // (mostly not)
     }
 }
 
@@ -1049,7 +1089,10 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
 hipError_t launch_index_build(const TableView &tv, const IndexView &ix, hipStream_t st, const LaunchEvents *ev)
 {
     if (tv.S <= 0) return hipSuccess;
-    return launch_kernel(ev, k_index_build, dim3((unsigned)(tv.S)), dim3((unsigned)kBuildThreads), 0, st, tv, ix);
+    const dim3 grid((unsigned)((tv.S + kBuildWaves - 1) / kBuildWaves)), block(64 * kBuildWaves);
+    // up to 1024 slices every workgroup is resident at once whatever its size: the larger chunk
+    if (tv.S <= 1024) return launch_kernel(ev, k_index_build<32>, grid, block, 0, st, tv, ix);
+    return launch_kernel(ev, k_index_build<16>, grid, block, 0, st, tv, ix);
 }
 
 int index_select_blocks(int num_cus) { return num_cus; }
