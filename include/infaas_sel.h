@@ -59,7 +59,8 @@ enum {
 enum {
     /* Default: the staircase index (per slice, the variants no cheaper variant dominates; a
      * query is two binary searches and a bit-set intersection), mirrored in one compute unit's
-     * LDS when it fits and read from global memory otherwise.  Queries the index cannot decide
+     * LDS when it fits; when it does not, large batches are binned by groups of tasks whose part of
+     * the index fits and looked up group by group, small ones read it from global memory.  Queries the index cannot decide
      * (its per-slice capacity was exceeded) are finished by a rank-ordered scan inside the same
      * kernel, so results never depend on the engine.  If more than half of the slices exceed the
      * capacity when the table is loaded, the exhaustive scan is used instead. */
@@ -373,7 +374,10 @@ enum {
     INFAAS_SEL_K_WORKER_TABLES = 11,/* worker of every variant (two kernels) */
     INFAAS_SEL_K_STEP_WORKERS = 12,/* worker of every step of an index */
     INFAAS_SEL_K_SCALE = 13,     /* scaling decisions */
-    INFAAS_SEL_K_COUNT = 14
+    INFAAS_SEL_K_GROUP_BIN = 14, /* grouped index: queries binned by group of tasks */
+    INFAAS_SEL_K_GROUP_LOOKUP = 15,/* grouped index: lookup, one group's bodies in LDS per workgroup */
+    INFAAS_SEL_K_GROUP_FINISH = 16,/* grouped index: answers back into query order */
+    INFAAS_SEL_K_COUNT = 17
 };
 typedef struct {
     int64_t launches[INFAAS_SEL_K_COUNT];
@@ -407,6 +411,10 @@ typedef struct {
     int64_t lookup_global_body; /* ... answered by a first group read from global memory (slice not in LDS) */
     int64_t lookup_scanned;     /* ... sent through the rank-ordered scan of the slice */
     int64_t lookup_unanswered;  /* ... that ended without a feasible variant */
+    int32_t index_groups;       /* 1: one LDS holds (part of) the whole index; more: the tasks are dealt to this many
+                                   groups whose staircases fit one LDS each, and calls of a million queries or more
+                                   are binned by group and looked up group by group */
+    int32_t reserved0;
 } infaas_sel_info;
 int infaas_sel_get_info(infaas_sel_t *h, infaas_sel_info *out);
 

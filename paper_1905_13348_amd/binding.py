@@ -21,7 +21,8 @@ ENGINE_INDEX = 2
 
 KERNEL_NAMES = ("update_load", "histogram", "plan", "scatter", "scan_lds", "scan_wide",
                 "finish_wide", "index_build", "index_select", "update_state", "worker_report",
-                "worker_tables", "step_workers", "scale")
+                "worker_tables", "step_workers", "scale", "group_bin", "group_lookup",
+                "group_finish")
 _K_COUNT = len(KERNEL_NAMES)
 
 _I32P = ctypes.POINTER(ctypes.c_int32)
@@ -54,7 +55,7 @@ class _Info(ctypes.Structure):
                 ("scratch_bytes", ctypes.c_int64),
                 ("lookup_parked", ctypes.c_int64), ("lookup_second_body", ctypes.c_int64),
                 ("lookup_global_body", ctypes.c_int64), ("lookup_scanned", ctypes.c_int64),
-                ("lookup_unanswered", ctypes.c_int64)]
+                ("lookup_unanswered", ctypes.c_int64), ("index_groups", ctypes.c_int32), ("reserved0", ctypes.c_int32)]
 
 
 _lib: Optional[ctypes.CDLL] = None

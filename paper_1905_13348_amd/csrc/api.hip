@@ -127,6 +127,10 @@ struct infaas_sel {
     bool have_index = false;
     uint32_t index_lds_bytes = 0;     // dynamic LDS of the lookup kernel; 0 = read the index from global memory
     uint32_t ix_stats[kCtlWords] = {0};      // copy of ix.ctrl taken after the build at load time
+    std::vector<int32_t> group_task0;        // host copy of ix.group_task0 (empty: one group)
+    int64_t ix_bytes = 0, ix_steps = 0;      // pool bytes and steps of the index when it was loaded
+    GroupScratch gs{};                       // scratch of the group-by-group selection (grows with the batch)
+    int64_t gs_queries = 0, gs_bytes = 0;    // batch size it is good for; its size
     int32_t *d_park = nullptr;        // queues of parked queries of the lookup kernel (fixed size)
     int64_t park_bytes = 0;
     int32_t *static_park = nullptr;   // the same queues inside the library's static device array (may be null)
@@ -172,14 +176,24 @@ struct infaas_sel {
     {
         (void)hipFree(ix.pool); (void)hipFree(ix.step_row); (void)hipFree(ix.ctrl);  // hdr lives in pool's allocation
         (void)hipFree(ix.stats);
+        (void)hipFree((void *)ix.task_group); (void)hipFree((void *)ix.group_task0); (void)hipFree(ix.gctrl);
         (void)hipFree(ix.step_worker); (void)hipFree(ix.hot_worker);
         (void)hipFree(d_park);
         d_park = nullptr;
         park_bytes = 0;
         ix = IndexView{};
+        group_task0.clear();
+        free_group_scratch();
         last_stats = nullptr;
         have_index = false;
         index_lds_bytes = 0;
+    }
+    void free_group_scratch()
+    {
+        (void)hipFree(gs.rec); (void)hipFree(gs.perm); (void)hipFree(gs.res); (void)hipFree(gs.desc);
+        (void)hipFree(gs.gcount);
+        gs = GroupScratch{};
+        gs_queries = gs_bytes = 0;
     }
     void free_scratch()
     {
@@ -282,6 +296,41 @@ int ensure_scratch(infaas_sel *h, int64_t capacity)
 
 constexpr uint32_t kLdsMax = 160 * 1024;  // dynamic LDS the lookup kernel may ask for
 
+constexpr uint32_t kGroupRegionBytes = 144 * 1024;   // a group's bodies: what one LDS holds next to its slices' headers
+constexpr uint32_t kGroupMaxSlices = 1900;           // ... 8 bytes of header each
+constexpr uint32_t kGroupStepCap = 16384;            // entries of step_row per group (a region holds at most 10,532 steps)
+constexpr int32_t kGroupMaxGroups = 120;
+constexpr int32_t kGroupMaxTasks = 16384;            // the binning kernel keeps the group of every task in LDS
+constexpr uint32_t kGroupHotRows = 8;
+
+// Starting values of the allocator counters and the statistics, then one build, then the counters back.
+int build_index_now(infaas_sel *h)
+{
+    IndexView &ix = h->ix;
+    const bool grouped = ix.num_groups > 1;
+    uint32_t ctrl0[kCtlWords] = {0};
+    ctrl0[kCtlPool] = ctrl0[kCtlPool0] = grouped ? ix.num_groups * ix.region_bytes : kDummyBodyBytes;
+    ctrl0[kCtlSteps] = ctrl0[kCtlSteps0] = grouped ? ix.num_groups * ix.group_step_cap : 1u;
+    ctrl0[kCtlMaxK0] = 1u;
+    std::vector<uint32_t> g0;
+    for (uint32_t g = 0; grouped && g < ix.num_groups; ++g) { g0.push_back(kDummyBodyBytes); g0.push_back(g == 0 ? 1u : 0u); }
+    if (!HIP_OK(hipMemcpy(ix.ctrl, ctrl0, sizeof(ctrl0), hipMemcpyHostToDevice)) ||
+        (grouped && !HIP_OK(hipMemcpy(ix.gctrl, g0.data(), g0.size() * 4, hipMemcpyHostToDevice))) ||
+        !HIP_OK(launch_index_build(h->tv, ix, nullptr)) || !HIP_OK(hipDeviceSynchronize()) ||
+        !HIP_OK(hipMemcpy(h->ix_stats, ix.ctrl, sizeof(ctrl0), hipMemcpyDeviceToHost)))
+        return INFAAS_SEL_ERR_HIP;
+    // bytes and steps of the index as a whole (info only)
+    h->ix_bytes = h->ix_stats[kCtlPool];
+    h->ix_steps = (int64_t)h->ix_stats[kCtlSteps] - 1;   // (entry 0 of step_row is unused)
+    if (grouped) {
+        if (!HIP_OK(hipMemcpy(g0.data(), ix.gctrl, g0.size() * 4, hipMemcpyDeviceToHost))) return INFAAS_SEL_ERR_HIP;
+        h->ix_bytes -= (int64_t)ix.num_groups * ix.region_bytes;
+        h->ix_steps -= (int64_t)ix.num_groups * ix.group_step_cap;
+        for (uint32_t g = 0; g < ix.num_groups; ++g) { h->ix_bytes += g0[2 * g]; h->ix_steps += g0[2 * g + 1]; }
+    }
+    return INFAAS_SEL_OK;
+}
+
 // Allocate the staircase index for the loaded table, build it and read its sizes back.
 int create_index(infaas_sel *h)
 {
@@ -289,15 +338,19 @@ int create_index(infaas_sel *h)
     const uint32_t worst = 2 * body_bytes(body_re(kBodySteps)) + 2 * (kBodySteps + 1);
     // The build takes room with one add on a pair of 32-bit counters; their sums must not carry.
     // A table with that many slices (millions) gets no index and is answered by the scan engine.
-    if (kDummyBodyBytes + S * worst > 0xFFFF0000ll || 1 + S * kIndexCap > 0xFFFF0000ll) return INFAAS_SEL_OK;
+    const int64_t regions = (int64_t)kGroupMaxGroups * kGroupRegionBytes, region_steps = (int64_t)kGroupMaxGroups * kGroupStepCap;
+    if (regions + kDummyBodyBytes + S * worst > 0xFFFF0000ll || region_steps + 1 + S * kIndexCap > 0xFFFF0000ll) return INFAAS_SEL_OK;
     IndexView ix{};
-    ix.pool_bytes = (uint32_t)std::min<int64_t>(kDummyBodyBytes + S * worst + 64, (int64_t)1 << 30);
-    ix.step_cap = (uint32_t)std::min<int64_t>(1 + S * kIndexCap, (int64_t)1 << 28);
+    ix.num_groups = 1;
+    // room for the regions of a grouped layout in front of what an ungrouped one needs
+    ix.pool_bytes = (uint32_t)std::min<int64_t>(regions + kDummyBodyBytes + S * worst + 64, (int64_t)3 << 30);
+    ix.step_cap = (uint32_t)std::min<int64_t>(region_steps + 1 + S * kIndexCap, (int64_t)1 << 29);
     // one allocation: the pool, then the headers, so that one 32-bit offset reaches both
     ix.pool_bytes &= ~15u;
+    const size_t nstats = (size_t)index_select_blocks(h->num_cus) * kLookupStats;
     bool ok = dev_alloc(&ix.pool, (size_t)ix.pool_bytes + (size_t)(S + 1) * 16) == hipSuccess &&
               dev_alloc(&ix.step_row, ix.step_cap) == hipSuccess && dev_alloc(&ix.ctrl, kCtlWords) == hipSuccess &&
-              dev_alloc(&ix.stats, (size_t)index_select_blocks(h->num_cus) * kLookupStats) == hipSuccess;
+              dev_alloc(&ix.stats, nstats) == hipSuccess && dev_alloc(&ix.gctrl, 2 * (size_t)kGroupMaxGroups) == hipSuccess;
     ix.hdr = ok ? (uint4 *)(ix.pool + ix.pool_bytes) : nullptr;
     h->ix = ix;
     const size_t park = index_park_bytes(h->num_cus);
@@ -312,16 +365,12 @@ int create_index(infaas_sel *h)
     uint8_t dummy[kDummyBodyBytes] = {0};
     for (uint32_t i = 8; i < 16; ++i) dummy[i] = 0xFF;  // latency sentinels of the empty body (Re = 2)
     const int32_t none = -1;
-    uint32_t ctrl0[kCtlWords] = {0};
-    ctrl0[kCtlPool] = kDummyBodyBytes; ctrl0[kCtlSteps] = 1u; ctrl0[kCtlMaxK0] = 1u;
     const uint32_t empty_hdr[4] = {0u, kEmptyHdrY, 0u, 4u + body_bytes(2)};
-    if (!HIP_OK(hipMemset(ix.stats, 0, (size_t)index_select_blocks(h->num_cus) * kLookupStats * 4)) ||
+    if (!HIP_OK(hipMemset(ix.stats, 0, nstats * 4)) ||
         !HIP_OK(hipMemcpy(ix.pool, dummy, sizeof(dummy), hipMemcpyHostToDevice)) ||
         !HIP_OK(hipMemcpy(ix.step_row, &none, 4, hipMemcpyHostToDevice)) ||
-        !HIP_OK(hipMemcpy(ix.ctrl, ctrl0, sizeof(ctrl0), hipMemcpyHostToDevice)) ||
         !HIP_OK(hipMemcpy(&ix.hdr[S], empty_hdr, sizeof(empty_hdr), hipMemcpyHostToDevice)) ||
-        !HIP_OK(launch_index_build(h->tv, ix, nullptr)) || !HIP_OK(hipDeviceSynchronize()) ||
-        !HIP_OK(hipMemcpy(h->ix_stats, ix.ctrl, sizeof(ctrl0), hipMemcpyDeviceToHost))) {
+        build_index_now(h) != INFAAS_SEL_OK) {
         h->free_index();
         return INFAAS_SEL_ERR_HIP;
     }
@@ -333,19 +382,64 @@ int create_index(infaas_sel *h)
     // path inside the same kernel.  With more headers than that the kernel reads everything from
     // global memory.
     h->index_lds_bytes = fixed <= (int64_t)kLdsMax / 2 ? kLdsMax : 0u;
+    // 2 bytes of a step's caller row sit in front of its body, the bits above in a 14-bit header field
+    const uint32_t row_bits = h->V > 1 ? 64u - (uint32_t)__builtin_clzll((unsigned long long)(h->V - 1)) : 1u;
+    h->ix.row_hi_bits = row_bits > 16 ? row_bits - 16 : 0u;
+    const uint32_t hot_max = std::min<uint32_t>(h->ix.row_hi_bits ? kRowHiField / h->ix.row_hi_bits : (uint32_t)kBodySteps, kBodySteps);
+    if (need > 2 * (int64_t)kLdsMax && h->T <= kGroupMaxTasks) {
+        // Not even half of the bodies fit one LDS: deal the tasks, in order, to groups whose bodies do (with a
+        // fifth of the region left free, because staircases grow and shrink with the load), and build
+        // again with one region of the pool per group.  Large batches of queries are then binned by
+        // group and looked up group by group, every workgroup with its group's bodies in LDS.
+        std::vector<uint32_t> hdr((size_t)S * 4);
+        if (!HIP_OK(hipMemcpy(hdr.data(), h->ix.hdr, (size_t)S * 16, hipMemcpyDeviceToHost))) { h->free_index(); return INFAAS_SEL_ERR_HIP; }
+        const uint32_t hot = std::min(kGroupHotRows, hot_max) & ~1u;
+        const uint32_t target = (kGroupRegionBytes - kDummyBodyBytes) / 5 * 4;
+        std::vector<uint16_t> task_group((size_t)h->T);
+        std::vector<int32_t> task0{0};
+        uint32_t bytes = 0, slices = 0;
+        for (int32_t t = 0; t < h->T; ++t) {
+            uint32_t tb = 0;
+            for (int32_t b = 0; b < h->B; ++b) {
+                const uint32_t *e = &hdr[((size_t)t * h->B + b) * 4];   // {body address, y, first step, end of bodies}
+                if (e[0] != 0u) tb += e[3] - (e[0] + 4u) + 2u * hot + 4u;   // bodies, and room for the first steps' rows
+            }
+            if (slices > 0 && (bytes + tb > target || slices + (uint32_t)h->B > kGroupMaxSlices)) {
+                task0.push_back(t);
+                bytes = slices = 0;
+            }
+            bytes += tb; slices += (uint32_t)h->B;
+            task_group[(size_t)t] = (uint16_t)(task0.size() - 1);
+        }
+        task0.push_back(h->T);
+        const int32_t G = (int32_t)task0.size() - 1;
+        if (G > 1 && G <= kGroupMaxGroups && (uint32_t)h->B <= kGroupMaxSlices) {
+            uint16_t *d_tg = nullptr;
+            int32_t *d_t0 = nullptr;
+            if (dev_alloc(&d_tg, (size_t)h->T) != hipSuccess || dev_alloc(&d_t0, (size_t)G + 1) != hipSuccess) {
+                (void)hipFree(d_tg); (void)hipFree(d_t0); (void)hipGetLastError();
+                h->free_index();
+                return INFAAS_SEL_ERR_OOM;
+            }
+            h->ix.task_group = d_tg; h->ix.group_task0 = d_t0;
+            h->ix.num_groups = (uint32_t)G; h->ix.region_bytes = kGroupRegionBytes; h->ix.group_step_cap = kGroupStepCap;
+            h->ix.hot_rows = hot;
+            bool up = HIP_OK(hipMemcpy(d_tg, task_group.data(), (size_t)h->T * 2, hipMemcpyHostToDevice)) &&
+                      HIP_OK(hipMemcpy(d_t0, task0.data(), ((size_t)G + 1) * 4, hipMemcpyHostToDevice));
+            for (int32_t g = 1; up && g < G; ++g)   // every region begins with the dummy body
+                up = HIP_OK(hipMemcpy(h->ix.pool + (size_t)g * kGroupRegionBytes, dummy, sizeof(dummy), hipMemcpyHostToDevice));
+            if (!up || build_index_now(h) != INFAAS_SEL_OK) { h->free_index(); return INFAAS_SEL_ERR_HIP; }
+            h->group_task0.assign(task0.begin(), task0.end());
+            return INFAAS_SEL_OK;
+        }
+    }
     // LDS left over holds the caller rows of the first steps of every slice (the steps most answers
     // come from), which saves those answers a gather from global memory.  Rebuild with that many.
     const int64_t spare = (int64_t)kLdsMax - need - 1024;   // keep room for staircases that grow with load
-    // 2 bytes each, in pairs; the bits of a row number above 16 go into a 14-bit header field
-    const uint32_t row_bits = h->V > 1 ? 64u - (uint32_t)__builtin_clzll((unsigned long long)(h->V - 1)) : 1u;
-    h->ix.row_hi_bits = row_bits > 16 ? row_bits - 16 : 0u;
-    const uint32_t hot_max = h->ix.row_hi_bits ? kRowHiField / h->ix.row_hi_bits : (uint32_t)kBodySteps;
-    const uint32_t hot = spare > 0 ? (uint32_t)std::min<int64_t>((spare / (4 * S)) * 2, std::min<uint32_t>(hot_max, kBodySteps)) : 0u;
+    const uint32_t hot = spare > 0 ? (uint32_t)std::min<int64_t>((spare / (4 * S)) * 2, hot_max) : 0u;
     if (h->index_lds_bytes && hot > 0) {
         h->ix.hot_rows = hot;
-        if (!HIP_OK(hipMemcpy(h->ix.ctrl, ctrl0, sizeof(ctrl0), hipMemcpyHostToDevice)) ||
-            !HIP_OK(launch_index_build(h->tv, h->ix, nullptr)) || !HIP_OK(hipDeviceSynchronize()) ||
-            !HIP_OK(hipMemcpy(h->ix_stats, h->ix.ctrl, sizeof(ctrl0), hipMemcpyDeviceToHost))) {
+        if (build_index_now(h) != INFAAS_SEL_OK) {
             h->free_index();
             return INFAAS_SEL_ERR_HIP;
         }
@@ -377,6 +471,61 @@ int index_pass(infaas_sel *h, const QueryView &q, hipStream_t st)
     LaunchTimer t(h, INFAAS_SEL_K_INDEX_SELECT, st);
     if (!HIP_OK(launch_index_select(h->tv, h->ix, q, h->d_park, h->index_lds_bytes, h->num_cus, st, t.ev())))
         return INFAAS_SEL_ERR_HIP;
+    return INFAAS_SEL_OK;
+}
+
+// Below this many queries a call is answered by the one-kernel lookup even when the index is laid
+// out in groups: the four launches of the group-by-group path cost more than they save.
+constexpr int64_t kGroupMinQueries = (int64_t)1 << 20;
+
+// Scratch of the group-by-group selection for batches of up to n queries.
+int ensure_group_scratch(infaas_sel *h, int64_t n)
+{
+    if (h->gs.rec && h->gs_queries >= n) return INFAAS_SEL_OK;
+    // growing: nothing enqueued earlier may still use the old buffers
+    if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
+    h->free_group_scratch();
+    const int64_t tiles = (n + kGroupTile - 1) / kGroupTile, padded = tiles * kGroupTile;
+    const size_t G1 = (size_t)h->ix.num_groups + 1;
+    GroupScratch gs{};
+    bool ok = dev_alloc(&gs.rec, (size_t)padded) == hipSuccess && dev_alloc(&gs.perm, (size_t)padded) == hipSuccess &&
+              dev_alloc(&gs.res, (size_t)padded) == hipSuccess && dev_alloc(&gs.desc, (size_t)tiles * G1) == hipSuccess &&
+              dev_alloc(&gs.gcount, G1) == hipSuccess;
+    h->gs = gs;
+    if (!ok) {
+        h->free_group_scratch();
+        (void)hipGetLastError();
+        return INFAAS_SEL_ERR_OOM;
+    }
+    if (!HIP_OK(hipMemset(gs.gcount, 0, G1 * 4))) { h->free_group_scratch(); return INFAAS_SEL_ERR_HIP; }
+    int32_t most = 0;
+    for (size_t g = 0; g + 1 < h->group_task0.size(); ++g) most = std::max(most, (h->group_task0[g + 1] - h->group_task0[g]) * h->B);
+    h->gs.max_group_slices = most;
+    h->gs.stat_blocks = index_select_blocks(h->num_cus);
+    h->gs_queries = padded;
+    h->gs_bytes = padded * 14 + (int64_t)tiles * (int64_t)G1 * 4;
+    return INFAAS_SEL_OK;
+}
+
+bool use_groups(const infaas_sel *h, int64_t n)
+{
+    return h->have_index && h->ix.num_groups > 1 && n >= kGroupMinQueries && (int)h->ix.num_groups <= h->num_cus &&
+           group_bin_lds_bytes(h->T, (int32_t)h->ix.num_groups) <= 64 * 1024;
+}
+
+// One pass of the group-by-group selection over n <= 2^28 queries (scratch must be there).
+int group_pass(infaas_sel *h, const QueryView &q, hipStream_t st)
+{
+    {
+        LaunchTimer t(h, INFAAS_SEL_K_GROUP_BIN, st);
+        if (!HIP_OK(launch_group_bin(h->tv, h->ix, q, h->gs, h->num_cus, st, t.ev()))) return INFAAS_SEL_ERR_HIP;
+    }
+    {
+        LaunchTimer t(h, INFAAS_SEL_K_GROUP_LOOKUP, st);
+        if (!HIP_OK(launch_group_lookup(h->tv, h->ix, q, h->gs, h->num_cus, st, t.ev()))) return INFAAS_SEL_ERR_HIP;
+    }
+    LaunchTimer t(h, INFAAS_SEL_K_GROUP_FINISH, st);
+    if (!HIP_OK(launch_group_finish(h->tv, h->ix, q, h->gs, h->num_cus, st, t.ev()))) return INFAAS_SEL_ERR_HIP;
     return INFAAS_SEL_OK;
 }
 
@@ -659,7 +808,7 @@ int infaas_sel_update_load(infaas_sel_t *h, int32_t n, const int32_t *d_variant_
     {
         LaunchTimer t(h, INFAAS_SEL_K_UPDATE, st);
         if (!HIP_OK(launch_update_load(h->tv, n, d_variant_idx, d_queue_us,
-                                       h->have_index ? h->ix.ctrl : nullptr, st, t.ev())))
+                                       h->have_index ? &h->ix : nullptr, st, t.ev())))
             return INFAAS_SEL_ERR_HIP;
     }
     if (h->have_index) {  // the steps depend on the load: rebuild them behind the update
@@ -675,7 +824,7 @@ namespace {
 // Gives the table of `h` the states (device copy of the caller's [V] array) and rebuilds its index.
 int apply_states(infaas_sel *h, const int32_t *d_states, hipStream_t st)
 {
-    if (!HIP_OK(launch_update_state(h->tv, h->V, nullptr, d_states, h->have_index ? h->ix.ctrl : nullptr, st)))
+    if (!HIP_OK(launch_update_state(h->tv, h->V, nullptr, d_states, h->have_index ? &h->ix : nullptr, st)))
         return INFAAS_SEL_ERR_HIP;
     h->steps_stale = true;
     if (h->have_index && !HIP_OK(launch_index_build(h->tv, h->ix, st))) return INFAAS_SEL_ERR_HIP;
@@ -758,7 +907,7 @@ int infaas_sel_update_state(infaas_sel_t *h, int32_t n, const int32_t *d_variant
     for (infaas_sel *t : {h, h->inactive}) {
         {
             LaunchTimer tm(t, INFAAS_SEL_K_UPDATE_STATE, st);
-            if (!HIP_OK(launch_update_state(t->tv, n, d_variant_idx, d_state, t->ix.ctrl, st, tm.ev())))
+            if (!HIP_OK(launch_update_state(t->tv, n, d_variant_idx, d_state, &t->ix, st, tm.ev())))
                 return INFAAS_SEL_ERR_HIP;
         }
         t->steps_stale = true;
@@ -789,7 +938,8 @@ int select_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     hipStream_t st = (hipStream_t)hip_stream;
     const bool idx = closest || use_index(h);
-    int rc = idx ? INFAAS_SEL_OK : ensure_scratch(h, std::min(N, kMaxPass));
+    const bool groups = idx && !closest && !h->inactive && use_groups(h, std::min(N, kMaxPass));
+    int rc = groups ? ensure_group_scratch(h, std::min(N, kMaxPass)) : idx ? INFAAS_SEL_OK : ensure_scratch(h, std::min(N, kMaxPass));
     if (rc != INFAAS_SEL_OK) return rc;
     for (int64_t done = 0; done < N; done += kMaxPass) {
         QueryView q{};
@@ -798,7 +948,7 @@ int select_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t
         q.bidx = d_batch_idx + done; q.out = d_out_variant + done;
         q.closest = closest ? d_out_closest + done : nullptr;
         q.pass = closest ? 1 : 0;
-        rc = idx ? index_pass(h, q, st) : scan_pass(h, q, st);
+        rc = groups && q.n >= kGroupMinQueries ? group_pass(h, q, st) : idx ? index_pass(h, q, st) : scan_pass(h, q, st);
         if (rc != INFAAS_SEL_OK) return rc;
     }
     h->last_stats = idx ? h->ix.stats : nullptr;
@@ -1200,7 +1350,8 @@ int infaas_sel_reserve(infaas_sel_t *h, int64_t max_queries)
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     const int64_t cap = std::max<int64_t>(1, std::min(max_queries, kMaxPass));
     if (h->loaded && h->inactive) return ensure_open(h, std::min(cap, kMaxTierPass));
-    if (h->loaded && use_index(h)) return INFAAS_SEL_OK;   // the index engine needs no per-query scratch
+    if (h->loaded && use_index(h))   // the index engine needs per-query scratch only where it works group by group
+        return use_groups(h, cap) ? ensure_group_scratch(h, cap) : INFAAS_SEL_OK;
     return ensure_scratch(h, cap);
 }
 
@@ -1274,14 +1425,15 @@ int infaas_sel_get_info(infaas_sel_t *h, infaas_sel_info *out)
     out->lds_segment_limit = h->lds_limit;
     out->wide_segments = h->wide_segments;
     out->table_bytes = h->table_bytes;
-    out->scratch_bytes = h->scratch_bytes + h->park_bytes + h->open_bytes;
+    out->scratch_bytes = h->scratch_bytes + h->park_bytes + h->open_bytes + h->gs_bytes;
     if (h->have_index) {
         out->index_in_lds = h->index_lds_bytes > 0 ? 1 : 0;
+        out->index_groups = (int32_t)h->ix.num_groups;
         out->index_truncated = (int32_t)(h->ix_stats[kCtlTrunc] + h->ix_stats[kCtlNoBody]);
         out->index_max_steps = (int32_t)h->ix_stats[kCtlMaxK];
         out->index_hot_rows = (int32_t)h->ix.hot_rows;
-        out->index_bytes = (int64_t)h->ix_stats[kCtlPool] + (int64_t)h->T * h->B * 16 + (int64_t)h->ix_stats[kCtlSteps] * 4;
-        out->index_steps = (int64_t)h->ix_stats[kCtlSteps] - 1;   // step_row entries handed out (entry 0 is unused)
+        out->index_bytes = h->ix_bytes + (int64_t)h->T * h->B * 16 + (h->ix_steps + 1) * 4;
+        out->index_steps = h->ix_steps;
         // what the most recent lookup launch did with the queries its first probe could not decide
         std::vector<uint32_t> st((size_t)index_select_blocks(h->num_cus) * kLookupStats, 0u);
         DeviceGuard g(h->device);

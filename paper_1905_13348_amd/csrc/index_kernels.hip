@@ -18,24 +18,16 @@
 //                    queries that end without a feasible variant and finds, in the same bodies,
 //                    the variant that comes closest to their requirements.
 #include "internal.h"
+#include "lookup_common.h"
 
 namespace infaas {
 
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef uint32_t v2u __attribute__((ext_vector_type(2)));
-
 constexpr int kSelThreads = 1024;
 constexpr int kPerThread = 4;   // queries per lane and unit, searched interleaved (8 does not fit in 128 VGPRs)
 constexpr uint32_t kParkFinal = 1u << 31;          // in a parked record's slice word: the selection is known to be -1
 constexpr int kWaveQueue = 64 + 64 * kPerThread;   // parked queries a wavefront can hold: a full pass plus one unit
-
-__device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
-{
-    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
-                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-}
 
 // ---------------------------------------------------------------- build
 
@@ -142,7 +134,7 @@ __global__ __launch_bounds__(64 * kBuildWaves) void k_index_build(TableView tv, 
     __shared__ uint32_t f_tab_all[kBuildWaves][64];            // the coarse filter's table
     __shared__ int32_t ranks_all[kBuildWaves][128];            // scratch of body_compute
     __shared__ uint32_t s_size[kBuildWaves], s_steps[kBuildWaves], s_stat[4];
-    __shared__ unsigned long long s_room;
+    __shared__ uint32_t s_group[kBuildWaves], s_off[kBuildWaves], s_rec[kBuildWaves];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int32_t *c_acc = c_acc_all[wave], *p_acc = p_acc_all[wave], *p_pos = p_pos_all[wave];
     uint32_t *c_tot = c_tot_all[wave], *p_tot = p_tot_all[wave], *f_tab = f_tab_all[wave];
@@ -308,17 +300,43 @@ __global__ __launch_bounds__(64 * kBuildWaves) void k_index_build(TableView tv, 
     const uint32_t re0 = body_re(k0), re1 = k1 ? body_re(k1) : 0u;
     const uint32_t rows = (2u * r0 + 3u) & ~3u, size0 = body_bytes(re0);
     const uint32_t size = L > 0 ? rows + size0 + body_bytes(re1) : 0u;   // (a multiple of 4)
-    if (lane == 0) { s_size[wave] = size; s_steps[wave] = (uint32_t)K; }
+    if (lane == 0) {
+        s_size[wave] = size; s_steps[wave] = (uint32_t)K;
+        s_group[wave] = ix.num_groups > 1 ? (uint32_t)ix.task_group[t] : 0u;
+    }
     if (threadIdx.x < 4) s_stat[threadIdx.x] = 0u;
     // caller rows of the steps (requested here, used after the bodies have been computed)
     const int32_t row = lane < K ? tv.orig_r[(int64_t)b * tv.Vp + seg + st_pos] : 0;
     __syncthreads();
     if (threadIdx.x == 0) {
-        // room in the pool and in step_row for all slices of the workgroup: one 64-bit add on the
-        // pair of counters (pool in the low word)
-        uint32_t bytes = 0, steps = 0;
-        for (int w = 0; w < kBuildWaves; ++w) { bytes += s_size[w]; steps += s_steps[w]; }
-        s_room = bytes ? atomicAdd((unsigned long long *)(ix.ctrl + kCtlPool), ((unsigned long long)steps << 32) | bytes) : 0ull;
+        // room in the pool and in step_row for the slices of the workgroup: one 64-bit add on a pair
+        // of counters (bytes in the low word) for every run of slices of one group -- one in all,
+        // unless the workgroup straddles two groups.  A slice that its group's region has no room for
+        // takes its room behind the regions.
+        unsigned long long *whole = (unsigned long long *)(ix.ctrl + kCtlPool);
+        for (int w0 = 0; w0 < kBuildWaves;) {
+            int w1 = w0;
+            uint32_t bytes = 0, steps = 0;
+            while (w1 < kBuildWaves && s_group[w1] == s_group[w0]) { bytes += s_size[w1]; steps += s_steps[w1]; ++w1; }
+            if (bytes) {
+                const uint32_t g = s_group[w0];
+                const bool grouped = ix.num_groups > 1;
+                unsigned long long *pair = grouped ? (unsigned long long *)(ix.gctrl + 2 * g) : whole;
+                const unsigned long long old = atomicAdd(pair, ((unsigned long long)steps << 32) | bytes);
+                uint32_t off = (uint32_t)old, rec = (uint32_t)(old >> 32);
+                for (int w = w0; w < w1; ++w) {
+                    if (!grouped) { s_off[w] = off; s_rec[w] = rec; }
+                    else if (off + s_size[w] <= ix.region_bytes && rec + s_steps[w] <= ix.group_step_cap) {
+                        s_off[w] = g * ix.region_bytes + off; s_rec[w] = g * ix.group_step_cap + rec;
+                    } else if (s_size[w]) {
+                        const unsigned long long o2 = atomicAdd(whole, ((unsigned long long)s_steps[w] << 32) | s_size[w]);
+                        s_off[w] = (uint32_t)o2; s_rec[w] = (uint32_t)(o2 >> 32);
+                    }
+                    off += s_size[w]; rec += s_steps[w];
+                }
+            }
+            w0 = w1;
+        }
     }
     int32_t hi = st_acc, lo = st_acc;   // (of lane 0, a step whenever the slice has variants)
     hi = __builtin_amdgcn_readfirstlane(hi); lo = hi;
@@ -339,8 +357,7 @@ __global__ __launch_bounds__(64 * kBuildWaves) void k_index_build(TableView tv, 
         row_hi |= ((uint32_t)__builtin_amdgcn_readlane(row, (int)j) >> 16) << (j * ix.row_hi_bits);
     __syncthreads();
     const bool has = inside && L > 0;
-    uint32_t off = (uint32_t)s_room, rec = (uint32_t)(s_room >> 32);
-    for (int w = 0; w < wave; ++w) { off += s_size[w]; rec += s_steps[w]; }
+    const uint32_t off = s_off[wave], rec = s_rec[wave];
     const bool fits = has && (uint64_t)off + size <= ix.pool_bytes && (uint64_t)rec + K <= ix.step_cap &&
                       (int64_t)hi - (int64_t)tv.acc_base <= 65533 && lo >= tv.acc_base;   // 16-bit accuracy keys
     if (fits) {
@@ -384,73 +401,6 @@ __global__ __launch_bounds__(64 * kBuildWaves) void k_index_build(TableView tv, 
 }
 
 // ---------------------------------------------------------------- lookup
-
-#define INFAAS_LDS __attribute__((address_space(3)))
-
-// Readers of index memory by 32-bit byte address: an LDS address, or an offset from a global base.
-struct LdsMem {
-    __device__ __forceinline__ uint32_t ld32(uint32_t a, uint32_t imm) const { return *(const INFAAS_LDS uint32_t *)(a + imm); }
-    __device__ __forceinline__ uint32_t ld16(uint32_t a, uint32_t imm) const { return *(const INFAAS_LDS uint16_t *)(a + imm); }
-    __device__ __forceinline__ v2u ld64(uint32_t a) const { return *(const INFAAS_LDS v2u *)a; }
-};
-struct GlobalMem {
-    const uint8_t *p;
-    __device__ __forceinline__ uint32_t ld32(uint32_t a, uint32_t imm) const { return *(const uint32_t *)(p + a + imm); }
-    __device__ __forceinline__ uint32_t ld16(uint32_t a, uint32_t imm) const { return *(const uint16_t *)(p + a + imm); }
-};
-
-// First fitting step of kN bodies (one per query of this lane), as bit sets; the kN searches are
-// interleaved so that their dependent reads overlap.  Branch-free apart from the wave-uniform
-// probe count.  body[k] / re[k]: address and keys per array (Re) of the body; dd[k]: accuracy
-// threshold in key space; lim[k]: latency bound.
-template <int kN, class Mem>
-__device__ __forceinline__ void search_bodies(const Mem &mem, int nit, const uint32_t (&body)[kN],
-                                              const uint32_t (&re)[kN], const uint32_t (&dd)[kN],
-                                              const uint32_t (&lim)[kN], uint32_t (&m)[kN])
-{
-    uint32_t pa[kN], la[kN], pt[kN], lt[kN];
-#pragma unroll
-    for (int k = 0; k < kN; ++k) {
-        pa[k] = body[k];                       // accuracy key j (1-based) at body + 2 + 2j
-        la[k] = body[k] + 2u * re[k];          // probes beyond the keys land on the last sentinel
-        pt[k] = la[k];                         // latency key j at body + 2 Re + 4j
-        lt[k] = pt[k] + 4u * re[k];
-    }
-#pragma unroll
-    for (int it = 4; it >= 0; --it) {
-        if (it < nit) {
-            uint32_t ca[kN], ct[kN], ka[kN], kt[kN];
-#pragma unroll
-            for (int k = 0; k < kN; ++k) {   // all reads of a level first, so that they overlap
-                ca[k] = pa[k] + (2u << it);
-                ct[k] = pt[k] + (4u << it);
-                ka[k] = mem.ld16(ca[k] < la[k] ? ca[k] : la[k], 2u);
-                kt[k] = mem.ld32(ct[k] < lt[k] ? ct[k] : lt[k], 0u);
-            }
-#pragma unroll
-            for (int k = 0; k < kN; ++k) {
-                pa[k] = ka[k] >= dd[k] ? ca[k] : pa[k];
-                pt[k] = kt[k] <= lim[k] ? ct[k] : pt[k];
-            }
-        }
-    }
-#pragma unroll
-    for (int k = 0; k < kN; ++k) {
-        // A[p] at body + 4 + 6 Re + 4p with pa = body + 2p;  S[ps] at body + 4 + 10 Re + 4 ps with
-        // pt = body + 2 Re + 4 ps
-        const uint32_t a_at = 2u * pa[k] + (6u * re[k] - body[k]);
-        const uint32_t s_at = pt[k] + 8u * re[k];
-        m[k] = mem.ld32(a_at, 4u) & mem.ld32(s_at, 4u);
-    }
-}
-
-// Accuracy bound in key space: keys are acc - acc_base + 1 >= 1, so the bound is
-// min_acc - acc_base + 1 limited to [1, 65536] (65536 is above every key).
-__device__ __forceinline__ uint32_t acc_threshold(int32_t min_acc, int32_t acc_base_m1)
-{
-    const int32_t d = __builtin_elementwise_sub_sat(min_acc, acc_base_m1);   // acc_base_m1 = acc_base - 1
-    return (uint32_t)(d < 1 ? 1 : (d > 65536 ? 65536 : d));
-}
 
 // ---- closest variant (the suggestion of Section 4.1 for a query that nothing satisfies): the
 // variant of the slice that is first by (requirements missed, latency overshoot, accuracy

@@ -106,13 +106,25 @@ struct IndexView {
     uint32_t hot_rows;   // rows kept in front of the first body of every slice (fills the LDS left over)
     uint32_t row_hi_bits;// bits of a row number above its low 16
     uint32_t *ctrl;      // [kCtlWords] counters of the build, see kCtl*
+    // Groups.  When the bodies of all slices do not fit one compute unit's LDS, the tasks are dealt, in
+    // order, to num_groups groups whose bodies do: group g owns the tasks [group_task0[g],
+    // group_task0[g + 1]), the bytes [g * region_bytes, (g + 1) * region_bytes) of the pool (every region
+    // starts with a copy of the empty dummy body) and the entries [g * group_step_cap, ...) of step_row;
+    // a slice that finds its group's region full is stored behind the regions.  num_groups == 1: one
+    // region, the whole pool.
+    uint32_t num_groups, region_bytes, group_step_cap;
+    const uint16_t *task_group;   // [T] group of every task; null when num_groups == 1
+    const int32_t *group_task0;   // [num_groups + 1]
+    uint32_t *gctrl;              // [2 num_groups] per group: bytes of its region and steps handed out
     uint32_t *stats;     // [workgroups of the lookup kernel][kLookupStats] what the most recent lookup launch did
 };
 // Counters of the index build.  Every slice takes its room with one 64-bit add on the pair
 // (kCtlPool, kCtlSteps) and waits for the answer; the statistics live on a cache line of their
 // own so that their updates, which nobody waits for, do not queue in front of those requests.
-constexpr int kCtlPool = 0;       // bytes of the pool handed out
+constexpr int kCtlPool = 0;       // bytes of the pool handed out (with groups: behind the regions)
 constexpr int kCtlSteps = 1;      // entries of step_row handed out (entry 0 is unused)
+constexpr int kCtlPool0 = 8;      // what the two counters above start from at every rebuild
+constexpr int kCtlSteps0 = 9;
 constexpr int kCtlMaxK0 = 32;     // most steps in a first body (sets the probe count of the lookup)
 constexpr int kCtlTrunc = 33;     // slices with more steps than the index keeps
 constexpr int kCtlNoBody = 34;    // slices without a body
@@ -167,11 +179,12 @@ inline hipError_t launch_kernel(const LaunchEvents *ev, void (*kernel)(P...), di
 }
 
 // Kernel launchers (scan engine).  Each returns the hipError_t of its launch.
+// index: the index that is rebuilt afterwards (its allocator counters are rewound), or null.
 hipError_t launch_update_load(const TableView &tv, int32_t n, const int32_t *idx,
-                              const int32_t *val, uint32_t *index_ctrl, hipStream_t st, const LaunchEvents *ev = nullptr);
+                              const int32_t *val, const IndexView *index, hipStream_t st, const LaunchEvents *ev = nullptr);
 // State report: state of row idx[i] := val[i] (idx null: row i, all V rows), masks refreshed.
 hipError_t launch_update_state(const TableView &tv, int32_t n, const int32_t *idx,
-                               const int32_t *val, uint32_t *index_ctrl, hipStream_t st, const LaunchEvents *ev = nullptr);
+                               const int32_t *val, const IndexView *index, hipStream_t st, const LaunchEvents *ev = nullptr);
 hipError_t launch_histogram(const TableView &tv, const QueryView &q, const ScanScratch &sc,
                             hipStream_t st, const LaunchEvents *ev = nullptr);
 hipError_t launch_plan(const TableView &tv, const ScanScratch &sc, hipStream_t st, const LaunchEvents *ev = nullptr);
@@ -194,6 +207,26 @@ hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const Q
 int index_select_blocks(int num_cus);
 int32_t index_open_cap(int32_t n, int num_cus);   // records per workgroup of QueryView::open for a pass over n queries
 size_t index_park_bytes(int num_cus);
+
+// Selection group by group, for an index laid out in groups (IndexView::num_groups > 1).
+constexpr int kGroupTile = 16384;   // queries binned at a time
+struct GroupScratch {
+    uint2 *rec;          // [tiles * kGroupTile] records {latency bound, accuracy threshold (key space) | slice in its group << 16},
+                         //   the records of a tile grouped by group
+    uint16_t *perm;      // [tiles * kGroupTile] query -> where its record sits in its tile
+    int32_t *res;        // [tiles * kGroupTile] answers, in record order
+    uint32_t *desc;      // [tiles][groups + 1] the tile's run of every group: offset in the tile | length << 15
+    uint32_t *gcount;    // [groups + 1] records per group (cleared again by the last kernel of a call)
+    int32_t max_group_slices;   // slices of the largest group
+    int32_t stat_blocks;        // workgroups IndexView::stats has room for
+};
+size_t group_bin_lds_bytes(int32_t T, int32_t G);
+hipError_t launch_group_bin(const TableView &tv, const IndexView &ix, const QueryView &q, const GroupScratch &gs,
+                            int num_cus, hipStream_t st, const LaunchEvents *ev = nullptr);
+hipError_t launch_group_lookup(const TableView &tv, const IndexView &ix, const QueryView &q, const GroupScratch &gs,
+                               int num_cus, hipStream_t st, const LaunchEvents *ev = nullptr);
+hipError_t launch_group_finish(const TableView &tv, const IndexView &ix, const QueryView &q, const GroupScratch &gs,
+                               int num_cus, hipStream_t st, const LaunchEvents *ev = nullptr);
 
 // Worker selection (Section 4.1: the worker that serves the selected variant).
 struct WorkerView {

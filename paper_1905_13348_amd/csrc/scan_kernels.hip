@@ -71,23 +71,36 @@ __device__ __forceinline__ int32_t wave_incl_scan(int32_t v)
 
 // ---------------------------------------------------------------- load update
 
+// Rewinds the allocator of the index and clears its statistics (the index is rebuilt after every
+// report): thread 0 the counters of the pool as a whole, threads 0 .. groups - 1 those of the groups'
+// regions (every region begins with the dummy body; entry 0 of step_row, in group 0's part, is unused).
+__device__ __forceinline__ void rewind_index(const IndexView &ix, int64_t tid)
+{
+    if (!ix.ctrl) return;
+    if (tid == 0) {
+        ix.ctrl[kCtlPool] = ix.ctrl[kCtlPool0];
+        ix.ctrl[kCtlSteps] = ix.ctrl[kCtlSteps0];
+        ix.ctrl[kCtlMaxK0] = 1;
+        ix.ctrl[kCtlTrunc] = 0;
+        ix.ctrl[kCtlNoBody] = 0;
+        ix.ctrl[kCtlMaxK] = 0;
+    }
+    if (ix.num_groups > 1 && tid < (int64_t)ix.num_groups) {
+        ix.gctrl[2 * tid] = kDummyBodyBytes;
+        ix.gctrl[2 * tid + 1] = tid == 0 ? 1u : 0u;
+    }
+}
+
 // One thread per (update, batch size): the queue itself, and latency-plus-queue of the variant's
 // entry in each rank-ordered column.  Thread 0 also rewinds the index allocator, because the
 // index is rebuilt after every load report.
 __global__ __launch_bounds__(256) void k_update_load(TableView tv, int32_t n,
                                                      const int32_t *__restrict__ idx,
                                                      const int32_t *__restrict__ val,
-                                                     uint32_t *__restrict__ index_ctrl)
+                                                     IndexView ix)
 {
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (tid == 0 && index_ctrl) {
-        index_ctrl[kCtlPool] = kDummyBodyBytes;
-        index_ctrl[kCtlSteps] = 1;
-        index_ctrl[kCtlMaxK0] = 1;
-        index_ctrl[kCtlTrunc] = 0;
-        index_ctrl[kCtlNoBody] = 0;
-        index_ctrl[kCtlMaxK] = 0;
-    }
+    rewind_index(ix, tid);
     if (tid >= (int64_t)n * tv.B)
         return;
     const int32_t i = (int32_t)(tid / tv.B), b = (int32_t)(tid - (int64_t)i * tv.B);
@@ -108,17 +121,10 @@ __global__ __launch_bounds__(256) void k_update_load(TableView tv, int32_t n,
 __global__ __launch_bounds__(256) void k_update_state(TableView tv, int32_t n,
                                                       const int32_t *__restrict__ idx,
                                                       const int32_t *__restrict__ val,
-                                                      uint32_t *__restrict__ index_ctrl)
+                                                      IndexView ix)
 {
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (tid == 0 && index_ctrl) {
-        index_ctrl[kCtlPool] = kDummyBodyBytes;
-        index_ctrl[kCtlSteps] = 1;
-        index_ctrl[kCtlMaxK0] = 1;
-        index_ctrl[kCtlTrunc] = 0;
-        index_ctrl[kCtlNoBody] = 0;
-        index_ctrl[kCtlMaxK] = 0;
-    }
+    rewind_index(ix, tid);
     if (tid >= (int64_t)n * tv.B)
         return;
     const int32_t i = (int32_t)(tid / tv.B), b = (int32_t)(tid - (int64_t)i * tv.B);
@@ -420,19 +426,21 @@ __global__ __launch_bounds__(256) void k_finish_wide(TableView tv, QueryView q, 
 // ---------------------------------------------------------------- launchers
 
 hipError_t launch_update_load(const TableView &tv, int32_t n, const int32_t *idx,
-                              const int32_t *val, uint32_t *index_ctrl, hipStream_t st, const LaunchEvents *ev)
+                              const int32_t *val, const IndexView *index, hipStream_t st, const LaunchEvents *ev)
 {
     if (n <= 0) return hipSuccess;
-    const int64_t threads = (int64_t)n * tv.B;
-    return launch_kernel(ev, k_update_load, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tv, n, idx, val, index_ctrl);
+    const int64_t threads = (int64_t)n * tv.B;   // (n >= 1: at least 256 threads, more than there are groups)
+    return launch_kernel(ev, k_update_load, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tv, n, idx, val,
+                         index ? *index : IndexView{});
 }
 
 hipError_t launch_update_state(const TableView &tv, int32_t n, const int32_t *idx,
-                               const int32_t *val, uint32_t *index_ctrl, hipStream_t st, const LaunchEvents *ev)
+                               const int32_t *val, const IndexView *index, hipStream_t st, const LaunchEvents *ev)
 {
     if (n <= 0) return hipSuccess;
     const int64_t threads = (int64_t)n * tv.B;
-    return launch_kernel(ev, k_update_state, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tv, n, idx, val, index_ctrl);
+    return launch_kernel(ev, k_update_state, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, tv, n, idx, val,
+                         index ? *index : IndexView{});
 }
 
 hipError_t launch_histogram(const TableView &tv, const QueryView &q, const ScanScratch &sc,
