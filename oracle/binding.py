@@ -60,6 +60,10 @@ class Oracle:
             fn = getattr(lib, name)
             fn.argtypes = [ctypes.c_int64, ctypes.c_int32] + [_I32P] * 7 + [ctypes.c_int64] + [_I32P] * 6
             fn.restype = ctypes.c_int
+        for name in ("oracle_select_case1", "oracle_select_case1_literal"):
+            fn = getattr(lib, name)
+            fn.argtypes = [ctypes.c_int64, ctypes.c_int32] + [_I32P] * 7 + [ctypes.c_int64] + [_I32P] * 7
+            fn.restype = ctypes.c_int
         for name in ("oracle_select_workers", "oracle_select_workers_literal"):
             fn = getattr(lib, name)
             fn.argtypes = ([ctypes.c_int64, ctypes.c_int32] + [_I32P] * 8 + [ctypes.c_int64, _I32P, _I32P]
@@ -162,6 +166,27 @@ class Oracle:
         if rc != 0:
             raise ValueError("oracle rejected its arguments")
         return out, tier
+
+    def select_case1(self, task_id, acc_bp, lat_us, cost, queue_us, state, load_us,
+                     q_task, q_slo, q_min_acc, q_bidx, literal=False):
+        """(variant or -1, tier, suggestion) per query: the state-aware selection and, where it
+        finds nothing, the closest Active or Inactive variant."""
+        task_id, acc_bp, queue_us = _i32(task_id), _i32(acc_bp), _i32(queue_us)
+        lat_us, cost, state, load_us = _i32(lat_us), _i32(cost), _i32(state), _i32(load_us)
+        V, B = lat_us.shape
+        assert cost.shape == lat_us.shape
+        for a in (task_id, acc_bp, queue_us, state, load_us):
+            assert a.shape == (V,)
+        q_task, q_slo, q_min_acc, q_bidx = _i32(q_task), _i32(q_slo), _i32(q_min_acc), _i32(q_bidx)
+        N = q_task.shape[0]
+        out, tier, closest = (np.empty(N, dtype=np.int32) for _ in range(3))
+        fn = self._lib.oracle_select_case1_literal if literal else self._lib.oracle_select_case1
+        rc = fn(V, B, _ptr(task_id), _ptr(acc_bp), _ptr(lat_us), _ptr(cost), _ptr(queue_us), _ptr(state),
+                _ptr(load_us), N, _ptr(q_task), _ptr(q_slo), _ptr(q_min_acc), _ptr(q_bidx), _ptr(out), _ptr(tier),
+                _ptr(closest))
+        if rc != 0:
+            raise ValueError("oracle rejected its arguments")
+        return out, tier, closest
 
     def select_workers(self, task_id, acc_bp, lat_us, cost, queue_us, state, load_us, variant_hw,
                        worker_hw, worker_util, inst_variant, inst_worker, inst_load,

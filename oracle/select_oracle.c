@@ -504,6 +504,155 @@ int oracle_select_tiered(int64_t V, int32_t B,
     return 0;
 }
 
+/*
+ * The complete Case I of Section 4.1 in one pass: a match among the Active variants; else a
+ * match among the Inactive ones; else -- no registered variant meets the requirements -- the
+ * suggestion of the variant that comes closest to the accuracy and/or latency target.
+ *
+ * Readings taken for the last step, on top of those of the state-aware selection and of the
+ * closest-variant suggestion above:
+ *   - only variants that the policy may select at all are suggested: Active and Inactive ones,
+ *     never Overloaded or Interfered ones;
+ *   - the latency a variant is measured by is the one its tier is selected by: lat + queue for
+ *     an Active variant, load + lat for an Inactive one;
+ *   - the order is (requirements missed, latency beyond the objective, accuracy below the
+ *     minimum), exact 64-bit differences; then an Active variant before an Inactive one (it
+ *     needs no loading); then the order of the variant's tier -- (cost, lat, row) among Active,
+ *     (load + lat, lat, row) among Inactive variants.
+ * out_closest is out_variant where a variant was selected, else the suggestion, else -1 (the
+ * task has no Active or Inactive variant at that batch index).
+ */
+static distance_t tier_distance(const int32_t *acc_bp, const int32_t *lat_us, const int32_t *queue_us,
+                                const int32_t *state, const int32_t *load_us, int32_t B, int64_t v,
+                                int32_t slo_us, int32_t min_acc_bp, int32_t b)
+{
+    distance_t d;
+    int64_t wait = state[v] == STATE_ACTIVE ? (int64_t)queue_us[v] : (int64_t)load_us[v];
+    int64_t total = (int64_t)lat_us[v * B + b] + wait;
+    d.over_us = total > (int64_t)slo_us ? total - (int64_t)slo_us : 0;
+    d.short_bp = acc_bp[v] < min_acc_bp ? (int64_t)min_acc_bp - (int64_t)acc_bp[v] : 0;
+    d.missed = (d.over_us > 0) + (d.short_bp > 0);
+    return d;
+}
+
+/* 1 when v comes before w as a suggestion; both are Active or Inactive. */
+static int suggested_before(const int32_t *acc_bp, const int32_t *lat_us, const int32_t *cost,
+                            const int32_t *queue_us, const int32_t *state, const int32_t *load_us,
+                            int32_t B, int32_t slo_us, int32_t min_acc_bp, int32_t b, int64_t v, int64_t w)
+{
+    distance_t dv = tier_distance(acc_bp, lat_us, queue_us, state, load_us, B, v, slo_us, min_acc_bp, b);
+    distance_t dw = tier_distance(acc_bp, lat_us, queue_us, state, load_us, B, w, slo_us, min_acc_bp, b);
+    if (dv.missed != dw.missed)
+        return dv.missed < dw.missed;
+    if (dv.over_us != dw.over_us)
+        return dv.over_us < dw.over_us;
+    if (dv.short_bp != dw.short_bp)
+        return dv.short_bp < dw.short_bp;
+    if (state[v] != state[w])
+        return state[v] == STATE_ACTIVE;
+    return state[v] == STATE_ACTIVE ? cheaper(lat_us, cost, B, b, v, w) : loads_sooner(lat_us, load_us, B, b, v, w);
+}
+
+static void case1_one(const int64_t *rows, int64_t n, int32_t B,
+                      const int32_t *acc_bp, const int32_t *lat_us, const int32_t *cost,
+                      const int32_t *queue_us, const int32_t *state, const int32_t *load_us,
+                      int32_t slo_us, int32_t min_acc_bp, int32_t b,
+                      int32_t *out_variant, int32_t *out_tier, int32_t *out_closest)
+{
+    tiered_one(rows, n, B, acc_bp, lat_us, cost, queue_us, state, load_us, slo_us, min_acc_bp, b,
+               out_variant, out_tier);
+    if (*out_variant >= 0) {
+        *out_closest = *out_variant;
+        return;
+    }
+    int64_t best = -1;
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t v = rows[i];
+        if (state[v] != STATE_ACTIVE && state[v] != STATE_INACTIVE)
+            continue;
+        if (best < 0 || suggested_before(acc_bp, lat_us, cost, queue_us, state, load_us, B, slo_us,
+                                         min_acc_bp, b, v, best))
+            best = v;
+    }
+    *out_closest = (int32_t)best;
+}
+
+/* Literal form: every query looks at every row of the table. */
+int oracle_select_case1_literal(int64_t V, int32_t B,
+                                const int32_t *task_id, const int32_t *acc_bp,
+                                const int32_t *lat_us, const int32_t *cost, const int32_t *queue_us,
+                                const int32_t *state, const int32_t *load_us,
+                                int64_t N,
+                                const int32_t *q_task, const int32_t *q_slo_us,
+                                const int32_t *q_min_acc_bp, const int32_t *q_batch_idx,
+                                int32_t *out_variant, int32_t *out_tier, int32_t *out_closest)
+{
+    if (V < 0 || B <= 0 || N < 0)
+        return -1;
+    int64_t *rows = (int64_t *)malloc(sizeof(int64_t) * (size_t)(V > 0 ? V : 1));
+    if (!rows)
+        return -1;
+    for (int64_t q = 0; q < N; ++q) {
+        int64_t n = 0;
+        int32_t b = q_batch_idx[q];
+        if (b >= 0 && b < B)
+            for (int64_t v = 0; v < V; ++v)
+                if (task_id[v] == q_task[q])
+                    rows[n++] = v;
+        case1_one(rows, n, B, acc_bp, lat_us, cost, queue_us, state, load_us, q_slo_us[q],
+                  q_min_acc_bp[q], b, &out_variant[q], &out_tier[q], &out_closest[q]);
+    }
+    free(rows);
+    return 0;
+}
+
+/* Grouped form (rows listed per task once, queries on several host threads). */
+int oracle_select_case1(int64_t V, int32_t B,
+                        const int32_t *task_id, const int32_t *acc_bp,
+                        const int32_t *lat_us, const int32_t *cost, const int32_t *queue_us,
+                        const int32_t *state, const int32_t *load_us,
+                        int64_t N,
+                        const int32_t *q_task, const int32_t *q_slo_us,
+                        const int32_t *q_min_acc_bp, const int32_t *q_batch_idx,
+                        int32_t *out_variant, int32_t *out_tier, int32_t *out_closest)
+{
+    if (V < 0 || B <= 0 || N < 0)
+        return -1;
+    int64_t T = 0;
+    for (int64_t v = 0; v < V; ++v) {
+        if (task_id[v] < 0)
+            return -1;
+        if ((int64_t)task_id[v] + 1 > T)
+            T = (int64_t)task_id[v] + 1;
+    }
+    int64_t *first = (int64_t *)calloc((size_t)T + 1, sizeof(int64_t));
+    int64_t *rows = (int64_t *)malloc(sizeof(int64_t) * (size_t)(V > 0 ? V : 1));
+    int64_t *fill = (int64_t *)calloc((size_t)T + 1, sizeof(int64_t));
+    if (!first || !rows || !fill) {
+        free(first); free(rows); free(fill);
+        return -1;
+    }
+    for (int64_t v = 0; v < V; ++v)
+        first[task_id[v] + 1] += 1;
+    for (int64_t t = 0; t < T; ++t)
+        first[t + 1] += first[t];
+    for (int64_t v = 0; v < V; ++v) {
+        int64_t t = task_id[v];
+        rows[first[t] + fill[t]] = v;
+        fill[t] += 1;
+    }
+#pragma omp parallel for schedule(dynamic, 4096)
+    for (int64_t q = 0; q < N; ++q) {
+        int32_t b = q_batch_idx[q];
+        int64_t t = q_task[q];
+        int64_t n = (b >= 0 && b < B && t >= 0 && t < T) ? first[t + 1] - first[t] : 0;
+        case1_one(n ? rows + first[t] : rows, n, B, acc_bp, lat_us, cost, queue_us, state, load_us,
+                  q_slo_us[q], q_min_acc_bp[q], b, &out_variant[q], &out_tier[q], &out_closest[q]);
+    }
+    free(first); free(rows); free(fill);
+    return 0;
+}
+
 /* State report: state[row[i]] = value[i], in array order; entries with a row outside 0..V-1 or
  * a code outside 0..3 are skipped. */
 void oracle_update_state(int64_t V, int32_t *state, int64_t n,

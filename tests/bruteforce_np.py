@@ -140,6 +140,38 @@ def tiered_np(task_id, acc_bp, lat_us, cost, queue_us, state, load_us, q_task, q
     return out, tier
 
 
+def case1_np(task_id, acc_bp, lat_us, cost, queue_us, state, load_us, q_task, q_slo, q_min_acc, q_bidx):
+    """Complete Case I: tiered_np, and where that finds nothing the first Active or Inactive variant
+    of the task under (requirements missed, latency beyond the objective, accuracy below the minimum,
+    Active before Inactive, the tier's own order); latency = lat + queue (Active), load + lat (Inactive).
+    Returns (variant, tier, suggestion)."""
+    out, tier = tiered_np(task_id, acc_bp, lat_us, cost, queue_us, state, load_us, q_task, q_slo, q_min_acc, q_bidx)
+    task_id = np.asarray(task_id, dtype=np.int64)
+    acc_bp = np.asarray(acc_bp, dtype=np.int64)
+    lat_us = np.asarray(lat_us, dtype=np.int64)
+    cost = np.asarray(cost, dtype=np.int64)
+    queue_us = np.asarray(queue_us, dtype=np.int64)
+    state = np.asarray(state, dtype=np.int64)
+    load_us = np.asarray(load_us, dtype=np.int64)
+    V, B = lat_us.shape
+    closest = out.copy()
+    for q in np.flatnonzero(out < 0):
+        b = int(q_bidx[q])
+        if not 0 <= b < B:
+            continue
+        rows = np.flatnonzero((task_id == int(q_task[q])) & ((state == 0) | (state == 1)))
+        if rows.size == 0:
+            continue
+        act = state[rows] == 1
+        total = lat_us[rows, b] + np.where(act, queue_us[rows], load_us[rows])
+        over = np.maximum(total - int(q_slo[q]), 0)
+        short = np.maximum(int(q_min_acc[q]) - acc_bp[rows], 0)
+        missed = (over > 0).astype(np.int64) + (short > 0)
+        first_key = np.where(act, cost[rows, b], load_us[rows] + lat_us[rows, b])   # the tier's own order: its first part
+        closest[q] = rows[np.lexsort((rows, lat_us[rows, b], first_key, ~act, short, over, missed))[0]]
+    return out, tier, closest
+
+
 def workers_np(variant, tier, variant_hw, worker_hw, worker_util, inst_variant, inst_worker, inst_load):
     """Worker for every (variant, tier) decision: tier 1 -> the worker of the variant's instance
     with the smallest (load, worker); tier 2 -> the worker of the variant's hardware class with the

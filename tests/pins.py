@@ -9,7 +9,7 @@ import os
 import numpy as np
 
 import workloads
-from bruteforce_np import closest_key_np, closest_np, count_np, select_np, tiered_np, workers_np
+from bruteforce_np import case1_np, closest_key_np, closest_np, count_np, select_np, tiered_np, workers_np
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 I32MAX = 2**31 - 1
@@ -483,12 +483,97 @@ def pin_update_state(o):
     assert st.tolist() == [2, 1, 2, 0]
 
 
+def _both_case1(o, *args):
+    a = o.select_case1(*args)
+    b = o.select_case1(*args, literal=True)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b)), "grouped and literal oracle disagree"
+    return a
+
+
+def pin_case1_numpy(o):
+    """Tiny tables with ties and all state codes against the numpy enumerator."""
+    rng = np.random.default_rng(29)
+    for trial in range(40):
+        V = int(rng.integers(1, 65)); T = int(rng.integers(1, 6)); B = int(rng.integers(1, 5))
+        span = int(rng.choice([2, 3, 5, 9, 50]))
+        tab, qry = _tiny_random(rng, V, T, B, 300, span)
+        state = rng.integers(-1, 6, V).astype(np.int32)
+        load = rng.integers(0, span, V).astype(np.int32)
+        got = _both_case1(o, *tab, state, load, *qry)
+        want = case1_np(*tab, state, load, *qry)
+        for g, w, name in zip(got, want, ("variant", "tier", "suggestion")):
+            assert np.array_equal(g, w), f"trial {trial}: {name}"
+
+
+def pin_case1_reductions(o):
+    """Reductions to routines that are pinned on their own: variant and tier are those of the
+    state-aware selection; the suggestion equals the variant wherever one was selected; with
+    every variant Active it is the plain closest-variant suggestion; with every variant Inactive
+    it is that of the table with cost := load + lat and queue := load."""
+    tb = workloads.make_table(0)
+    q = workloads.make_queries(0, n=4000)
+    st = workloads.make_states(0, tb.V)
+    table = (tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us)
+    queries = (q.task, q.slo_us, q.min_acc_bp, q.batch_idx)
+    var, tier, sug = _both_case1(o, *table, st.state, st.load_us, *queries)
+    var2, tier2 = o.select_tiered(*table, st.state, st.load_us, *queries)
+    assert np.array_equal(var, var2) and np.array_equal(tier, tier2)
+    assert np.array_equal(sug[var >= 0], var[var >= 0]) and (var < 0).sum() > 100
+    ok = (st.state == 0) | (st.state == 1)
+    assert ok[sug[sug >= 0]].all() and (tb.task_id[sug[sug >= 0]] == q.task[sug >= 0]).all()
+    _, _, sug_a = _both_case1(o, *table, np.ones(tb.V, np.int32), st.load_us, *queries)
+    assert np.array_equal(sug_a, o.select_closest(*table, *queries)[1])
+    _, _, sug_i = _both_case1(o, *table, np.zeros(tb.V, np.int32), st.load_us, *queries)
+    combined = (tb.lat_us.astype(np.int64) + st.load_us.astype(np.int64)[:, None]).astype(np.int32)
+    assert np.array_equal(sug_i, o.select_closest(tb.task_id, tb.acc_bp, tb.lat_us, combined, st.load_us, *queries)[1])
+
+
+def pin_case1_policy(o):
+    """Hand-built cases for the last step: Overloaded and Interfered variants are never suggested;
+    an Active variant is measured with its queue (not its loading latency), an Inactive one with
+    its loading latency (not its queue); fewer missed requirements first, then the smaller
+    overshoot, then the smaller shortfall, then Active before Inactive, then the tier's own order;
+    -1 only without an Active or Inactive variant; no 32-bit wrap in the differences."""
+    task = np.zeros(6, np.int32)
+    acc = np.array([9000, 7000, 9500, 7500, 9000, 9000], np.int32)
+    lat = np.array([[100], [100], [10], [100], [100], [100]], np.int32)
+    cost = np.array([[5], [1], [1], [9], [9], [1]], np.int32)
+    queue = np.array([50, 999, 0, 999, 999, 50], np.int32)     # Active rows 0, 5 take 150 us; row 2 would fit anything
+    load = np.array([999, 30, 0, 30, 50, 999], np.int32)       # Inactive rows 1, 3 take 130 us, row 4 150 us
+    one = lambda state, slo, amin, bidx=0: tuple(int(x[0]) for x in _both_case1(
+        o, task, acc, lat, cost, queue, np.array(state, np.int32), load, [0], [slo], [amin], [bidx]))
+    X, Y = 2, 3
+    assert one([1, 0, X, Y, Y, Y], 120, 9200) == (-1, 0, 1)   # rows 0 and 1 miss both: overshoot 10 (row 1) against 30
+    assert one([1, 0, X, Y, Y, Y], 140, 9200) == (-1, 0, 1)   # row 1 misses one requirement, row 0 two
+    assert one([1, 0, X, Y, Y, Y], 140, 8000) == (-1, 0, 1)   # one each: no overshoot (row 1) before no shortfall (row 0)
+    assert one([X, 0, X, 0, Y, Y], 100, 8000) == (-1, 0, 3)   # equal overshoot: shortfall 500 (row 3) against 1000 (row 1)
+    assert one([1, Y, X, Y, 0, Y], 100, 9500) == (-1, 0, 0)   # rows 0 and 4 equally far: the Active one
+    assert one([1, Y, X, Y, 0, 1], 100, 9500) == (-1, 0, 5)   # two Active ones equally far: the cheaper
+    assert one([0, Y, X, Y, 0, Y], 100, 9500) == (-1, 0, 4)   # row 0 Inactive: its loading latency counts now
+    assert one([X, Y, X, Y, Y, X], 100, 9500) == (-1, 0, -1)  # nothing that may be selected at all
+    assert one([1, 0, 1, 0, 0, 1], 100, 9500, bidx=1) == (-1, 0, -1)
+    assert one([1, 0, 1, 0, 0, 1], 1000, 0) == (2, 1, 2)      # where a variant is selected it is the suggestion
+    assert one([X, 0, X, 0, 0, Y], 1000, 7200) == (3, 2, 3)
+    big = np.array([[I32MAX], [I32MAX]], np.int32)
+    got = _both_case1(o, [0, 0], [5, 5], big, [[1], [1]], [0, 0], [0, 0], [I32MAX, 0], [0], [0], [0], [0])
+    assert int(got[2][0]) == 1                                 # 2 * I32MAX must not wrap to a small overshoot
+    got = _both_case1(o, [0, 0], [I32MAX, 0], [[1], [1]], [[1], [1]], [0, 0], [1, 1], [0, 0], [0], [5], [-I32MAX - 1], [0])
+    assert int(got[0][0]) == 0                                 # an accuracy bound of INT32_MIN is met by everything
+
+
 TIERED_PINS = [
     pin_tiered_numpy,
     pin_tiered_reduces_to_plain,
     pin_tiered_policy,
     pin_update_state,
 ]
+
+CASE1_PINS = [
+    pin_case1_numpy,
+    pin_case1_reductions,
+    pin_case1_policy,
+]
+
 
 
 # ---- worker selection (Section 4.1: the second output of Case I) ----------------------------------

@@ -124,6 +124,47 @@ def test_tiered_mutant_is_caught(tmp_path, source_text, name, find, repl):
     assert caught, f"no pin notices the planted mistake '{name}'"
 
 
+# planted mistakes in the last step of the complete Case I (suggestion among Active and Inactive variants)
+_DW = "distance_t dw = tier_distance(acc_bp, lat_us, queue_us, state, load_us, B, w, slo_us, min_acc_bp, b);\n"
+CASE1_MUTANTS = [
+    ("case1_suggests_any_state", "if (state[v] != STATE_ACTIVE && state[v] != STATE_INACTIVE)\n            continue;", ""),
+    ("case1_active_measured_with_load", "int64_t wait = state[v] == STATE_ACTIVE ? (int64_t)queue_us[v] : (int64_t)load_us[v];",
+     "int64_t wait = state[v] == STATE_ACTIVE ? (int64_t)load_us[v] : (int64_t)queue_us[v];"),
+    ("case1_inactive_measured_with_queue", "int64_t wait = state[v] == STATE_ACTIVE ? (int64_t)queue_us[v] : (int64_t)load_us[v];",
+     "int64_t wait = (int64_t)queue_us[v];"),
+    ("case1_latency_term_dropped", "int64_t total = (int64_t)lat_us[v * B + b] + wait;", "int64_t total = wait;"),
+    ("case1_overshoot_wraps", "+ wait;\n    d.over_us = total > (int64_t)slo_us ? total - (int64_t)slo_us : 0;",
+     "+ wait;\n    d.over_us = total > (int64_t)slo_us ? (int64_t)(int32_t)(uint32_t)(total - (int64_t)slo_us) : 0;"),
+    ("case1_missed_count_ignored", _DW + "    if (dv.missed != dw.missed)\n        return dv.missed < dw.missed;", _DW),
+    ("case1_overshoot_flipped", _DW + "    if (dv.missed != dw.missed)\n        return dv.missed < dw.missed;\n    if (dv.over_us != dw.over_us)\n        return dv.over_us < dw.over_us;",
+     _DW + "    if (dv.missed != dw.missed)\n        return dv.missed < dw.missed;\n    if (dv.over_us != dw.over_us)\n        return dv.over_us > dw.over_us;"),
+    ("case1_shortfall_ignored", "return dv.short_bp < dw.short_bp;\n    if (state[v] != state[w])", "return 0;\n    if (state[v] != state[w])"),
+    ("case1_inactive_before_active", "return state[v] == STATE_ACTIVE;", "return state[v] == STATE_INACTIVE;"),
+    ("case1_tier_ignored", "if (state[v] != state[w])\n        return state[v] == STATE_ACTIVE;", ""),
+    ("case1_inactive_ordered_by_cost", "return state[v] == STATE_ACTIVE ? cheaper(lat_us, cost, B, b, v, w) : loads_sooner(lat_us, load_us, B, b, v, w);",
+     "return cheaper(lat_us, cost, B, b, v, w);"),
+    ("case1_active_ordered_by_load", "return state[v] == STATE_ACTIVE ? cheaper(lat_us, cost, B, b, v, w) : loads_sooner(lat_us, load_us, B, b, v, w);",
+     "return loads_sooner(lat_us, load_us, B, b, v, w);"),
+    ("case1_suggestion_where_selected_dropped", "*out_closest = *out_variant;\n        return;", "*out_closest = -1;\n        return;"),
+]
+
+
+@pytest.mark.parametrize("name,find,repl", CASE1_MUTANTS, ids=[m[0] for m in CASE1_MUTANTS])
+def test_case1_mutant_is_caught(tmp_path, source_text, name, find, repl):
+    assert find in source_text, f"mutant {name}: pattern not in the oracle source any more"
+    src = tmp_path / f"{name}.c"
+    src.write_text(source_text.replace(find, repl))
+    lib = oracle.build_oracle(src=str(src), out=str(tmp_path / f"lib{name}.so"), force=True)
+    mutant = oracle.Oracle(lib)
+    caught = []
+    for pin in pins.CASE1_PINS:
+        try:
+            pin(mutant)
+        except AssertionError:
+            caught.append(pin.__name__)
+    assert caught, f"no pin notices the planted mistake '{name}'"
+
+
 # planted mistakes in the worker selection
 WORKER_MUTANTS = [
     ("worker_most_loaded", "if (best < 0 || inst_load[i] < inst_load[best] ||", "if (best < 0 || inst_load[i] > inst_load[best] ||"),

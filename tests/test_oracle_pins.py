@@ -21,6 +21,11 @@ def test_tiered_pin(oracle_lib, pin):
     pin(oracle_lib)
 
 
+@pytest.mark.parametrize("pin", pins.CASE1_PINS, ids=lambda f: f.__name__)
+def test_case1_pin(oracle_lib, pin):
+    pin(oracle_lib)
+
+
 @pytest.mark.parametrize("pin", pins.WORKER_PINS, ids=lambda f: f.__name__)
 def test_worker_pin(oracle_lib, pin):
     pin(oracle_lib)
