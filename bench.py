@@ -174,6 +174,9 @@ def main() -> int:
     ap.add_argument("--tiered", action="store_true",
                     help="time infaas_sel_select_tiered (state-aware two-tier selection over seeded variant "
                          "states; 24 B per decision) instead of infaas_sel_select")
+    ap.add_argument("--case1", action="store_true",
+                    help="time infaas_sel_select_tiered_closest (the complete Case I: two-tier selection plus the "
+                         "closest Active or Inactive variant where neither tier answers; 28 B per decision)")
     ap.add_argument("--workers", action="store_true",
                     help="time infaas_sel_select_workers (two-tier selection plus the worker of every answer, "
                          "over a seeded cluster of workers and instances; 28 B per decision)")
@@ -225,9 +228,9 @@ def main() -> int:
     chunks = spec["chunks"]
     per_step = spec["num_queries"] // chunks
     engine = pkg.ENGINE_AUTO if args.engine == "auto" else pkg.ENGINE_SCAN
-    if (args.closest or args.tiered or args.workers) and \
-            (args.engine != "auto" or args.closest + args.tiered + args.workers > 1):
-        print("bench.py: --closest, --tiered and --workers need the index engine (--engine auto), one at a time",
+    if (args.closest or args.tiered or args.workers or args.case1) and \
+            (args.engine != "auto" or args.closest + args.tiered + args.workers + args.case1 > 1):
+        print("bench.py: --closest, --tiered, --case1 and --workers need the index engine (--engine auto), one at a time",
               file=sys.stderr)
         return 2
 
@@ -236,7 +239,7 @@ def main() -> int:
     sel.reserve(per_step)
     states = None
     cluster = None
-    if args.tiered or args.workers:
+    if args.tiered or args.workers or args.case1:
         states = workloads.make_states(cfg, tb.V)
         sel.load_states(states.state, states.load_us)
     if args.workers:
@@ -249,8 +252,9 @@ def main() -> int:
     # report) and as many result arrays, enough that at least ROTATE_BYTES are touched between two
     # uses of the same buffer: nothing a step reads or writes can still sit in a cache (the part has
     # 256 MB of last-level cache) from the step that used it before.
-    two_results = args.closest or args.tiered or args.workers        # suggestion, or tier
-    per_decision = BYTES_PER_DECISION + (4 if two_results else 0) + (4 if args.workers else 0)
+    two_results = args.closest or args.tiered or args.workers or args.case1       # suggestion, or tier
+    three_results = args.workers or args.case1                                     # worker, or suggestion beside the tier
+    per_decision = BYTES_PER_DECISION + (4 if two_results else 0) + (4 if three_results else 0)
     set_bytes = per_step * per_decision
     n_sets = int(min(MAX_SETS, max(4, -(-ROTATE_BYTES // set_bytes))))
     if chunks > 1:
@@ -263,7 +267,7 @@ def main() -> int:
         dev_q.append([torch.from_numpy(x).cuda() for x in (src.task, src.slo_us, src.min_acc_bp, src.batch_idx)])
     outs = [torch.empty(per_step, dtype=torch.int32, device="cuda") for _ in range(n_sets)]
     seconds = [torch.empty(per_step, dtype=torch.int32, device="cuda") if two_results else None for _ in range(n_sets)]
-    workers_out = [torch.empty(per_step, dtype=torch.int32, device="cuda") if args.workers else None
+    workers_out = [torch.empty(per_step, dtype=torch.int32, device="cuda") if three_results else None
                    for _ in range(n_sets)]
     updates = []
     worker_updates = []
@@ -286,6 +290,8 @@ def main() -> int:
             sel.select_closest(*dev_q[k], outs[k], seconds[k])
         elif args.tiered:
             sel.select_tiered(*dev_q[k], outs[k], seconds[k])
+        elif args.case1:
+            sel.select_tiered_closest(*dev_q[k], outs[k], seconds[k], workers_out[k])
         elif args.workers:
             if worker_updates:
                 sel.update_workers(*worker_updates[i % len(worker_updates)][0])
@@ -340,11 +346,12 @@ def main() -> int:
     dom = max(active, key=lambda k: active[k]["total_ms"])
     dom_avg_ms = active[dom]["total_ms"] / active[dom]["launches"]
     launches_per_step = active[dom]["launches"] / args.steps
-    mode = "/closest" if args.closest else "/tiered" if args.tiered else "/workers" if args.workers else ""
-    fixed_bytes = table_bytes(tb) + (8 * tb.V if args.tiered or args.workers else 0)   # + state and loading latency
+    mode = "/closest" if args.closest else "/tiered" if args.tiered else "/workers" if args.workers else \
+        "/case1" if args.case1 else ""
+    fixed_bytes = table_bytes(tb) + (8 * tb.V if args.tiered or args.workers or args.case1 else 0)   # + state and loading latency
     if args.workers:   # + hardware of every variant, the workers, the instances
         fixed_bytes += 4 * tb.V + 8 * cluster.W + 12 * cluster.I
-    if (args.tiered or args.workers) and dom == "index_select":
+    if (args.tiered or args.workers or args.case1) and dom == "index_select":
         # one lookup per tier: the pair is priced as one launch against the bytes of the whole call
         algo_bytes = per_decision * per_step + fixed_bytes
         dom_avg_ms = active[dom]["total_ms"] / args.steps
@@ -394,6 +401,9 @@ def main() -> int:
         elif args.tiered:
             def ref_fn(*a):
                 return ref.select_tiered(*a[:5], states.state, states.load_us, *a[5:])
+        elif args.case1:
+            def ref_fn(*a):
+                return ref.select_case1(*a[:5], states.state, states.load_us, *a[5:])
         else:
             ref_fn = ref.select_closest if args.closest else ref.select
         ref_fn(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, queue, *(f[:n0] for f in fields))
@@ -402,7 +412,7 @@ def main() -> int:
         s0 = time.perf_counter()
         want = ref_fn(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, queue, *(f[:n] for f in fields))
         dt = time.perf_counter() - s0
-        if args.workers:
+        if three_results:
             mismatches = int(sum((g[:n].cpu().numpy() != w).sum() for g, w in zip((out, closest, worker), want)))
         elif two_results:
             mismatches = int((out[:n].cpu().numpy() != want[0]).sum() + (closest[:n].cpu().numpy() != want[1]).sum())
@@ -422,6 +432,8 @@ def main() -> int:
                                + (f", load report of {updates[0][2].variant_idx.size} rows before every step" if updates else "")
                                + (", closest-variant mode (two result arrays)" if args.closest else "")
                                + (", state-aware two-tier selection (variant and tier arrays)" if args.tiered else "")
+                               + (", complete Case I: two tiers, then the closest variant (variant, tier and suggestion arrays)"
+                                  if args.case1 else "")
                                + (f", two-tier selection with worker selection over {cluster.W} workers and "
                                   f"{cluster.I} instances (variant, tier and worker arrays)" if args.workers else ""),
                    "engine": args.engine, "launch": "hip graph replay" if args.graph else "stream",

@@ -208,7 +208,7 @@ enum { INFAAS_SEL_STATE_INACTIVE = 0, INFAAS_SEL_STATE_ACTIVE = 1,
  *   load_us [V]  loading latency, >= 0, with load_us[v] + lat_us[v][b] <= INT32_MAX
  * Synchronous.  Needs the staircase index (not INFAAS_SEL_ENGINE_SCAN).  From here on
  * infaas_sel_select answers from the Active variants only, infaas_sel_select_closest is not
- * available, and infaas_sel_update_load keeps acting on queue_us (which only the Active tier
+ * available (infaas_sel_select_tiered_closest takes its place), and infaas_sel_update_load keeps acting on queue_us (which only the Active tier
  * reads).  A later infaas_sel_load_variants drops the states again.
  * Errors: INVALID_ARG, NOT_LOADED, OUT_OF_RANGE, HIP, OOM.
  */
@@ -236,6 +236,26 @@ int infaas_sel_select_tiered(infaas_sel_t *h, int64_t N,
                              const int32_t *d_task, const int32_t *d_slo_us,
                              const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
                              int32_t *d_out_variant, int32_t *d_out_tier, void *hip_stream);
+
+/*
+ * The complete Case I of Section 4.1 in one call: infaas_sel_select_tiered, and for the queries
+ * that no Active and no Inactive variant matches the suggestion the policy ends with -- a variant
+ * that comes closest to the accuracy and/or latency target.  Readings, on top of those of
+ * infaas_sel_select_closest and infaas_sel_select_tiered: only variants the policy may select are
+ * suggested (Active and Inactive, never Overloaded or Interfered); an Active variant is measured
+ * by lat_us + queue_us, an Inactive one by load_us + lat_us; the order is (requirements missed,
+ * latency beyond slo_us, accuracy below min_acc_bp), then an Active variant before an Inactive
+ * one, then the order of the variant's tier.
+ *   d_out_closest  [N]  DEVICE: d_out_variant where that is not -1, else the suggestion; -1 only
+ *                       when the task has no Active or Inactive variant (task or batch index
+ *                       outside the table included)
+ * Otherwise as infaas_sel_select_tiered.
+ */
+int infaas_sel_select_tiered_closest(infaas_sel_t *h, int64_t N,
+                                     const int32_t *d_task, const int32_t *d_slo_us,
+                                     const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
+                                     int32_t *d_out_variant, int32_t *d_out_tier, int32_t *d_out_closest,
+                                     void *hip_stream);
 
 /*
  * ---- Worker selection: the second output of Case I (Section 4.1) ------------------------------

@@ -63,7 +63,8 @@ _lib: Optional[ctypes.CDLL] = None
 # every symbol include/infaas_sel.h declares
 EXPORTED = ("infaas_sel_create", "infaas_sel_load_variants", "infaas_sel_update_load",
             "infaas_sel_select", "infaas_sel_select_noalloc", "infaas_sel_select_closest", "infaas_sel_load_states",
-            "infaas_sel_update_state", "infaas_sel_select_tiered", "infaas_sel_load_workers",
+            "infaas_sel_update_state", "infaas_sel_select_tiered", "infaas_sel_select_tiered_closest",
+            "infaas_sel_load_workers",
             "infaas_sel_update_workers", "infaas_sel_select_workers", "infaas_sel_load_scaling",
             "infaas_sel_scale", "infaas_sel_destroy", "infaas_sel_reserve",
             "infaas_sel_read_load", "infaas_sel_set_timing", "infaas_sel_get_timings",
@@ -100,6 +101,7 @@ def load_library() -> ctypes.CDLL:
     lib.infaas_sel_load_states.argtypes = [vp, _I32P, _I32P]
     lib.infaas_sel_update_state.argtypes = [vp, ctypes.c_int32, vp, vp, vp]
     lib.infaas_sel_select_tiered.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp]
+    lib.infaas_sel_select_tiered_closest.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.infaas_sel_load_workers.argtypes = [vp, ctypes.c_int32, _I32P, _I32P, _I32P, ctypes.c_int32, _I32P, _I32P, _I32P]
     lib.infaas_sel_update_workers.argtypes = [vp, ctypes.c_int32, vp, vp, ctypes.c_int32, vp, vp, vp]
     lib.infaas_sel_select_workers.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -235,6 +237,15 @@ class Selector:
             _dev_ptr(d_min_acc_bp, n, "d_min_acc_bp"), _dev_ptr(d_batch_idx, n, "d_batch_idx"),
             _dev_ptr(d_out_variant, n, "d_out_variant"), _dev_ptr(d_out_tier, n, "d_out_tier"),
             _stream_ptr(stream)))
+
+    def select_tiered_closest(self, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, d_out_tier,
+                              d_out_closest, stream=None, n: Optional[int] = None) -> None:
+        n = int(d_task.numel()) if n is None else int(n)
+        _check(self._lib.infaas_sel_select_tiered_closest(
+            self._h, n, _dev_ptr(d_task, n, "d_task"), _dev_ptr(d_slo_us, n, "d_slo_us"),
+            _dev_ptr(d_min_acc_bp, n, "d_min_acc_bp"), _dev_ptr(d_batch_idx, n, "d_batch_idx"),
+            _dev_ptr(d_out_variant, n, "d_out_variant"), _dev_ptr(d_out_tier, n, "d_out_tier"),
+            _dev_ptr(d_out_closest, n, "d_out_closest"), _stream_ptr(stream)))
 
     def load_workers(self, worker_hw, worker_util, variant_hw, inst_variant, inst_worker, inst_load) -> None:
         """Host arrays: hardware code and utilisation of every worker [W], target hardware of every

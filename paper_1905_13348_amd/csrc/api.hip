@@ -466,10 +466,10 @@ int ensure_open(infaas_sel *h, int64_t n)
 }
 
 // One pass of the index engine over n <= 2^28 queries.
-int index_pass(infaas_sel *h, const QueryView &q, hipStream_t st)
+int index_pass(infaas_sel *h, const QueryView &q, hipStream_t st, const TableView *first_tier = nullptr)
 {
     LaunchTimer t(h, INFAAS_SEL_K_INDEX_SELECT, st);
-    if (!HIP_OK(launch_index_select(h->tv, h->ix, q, h->d_park, h->index_lds_bytes, h->num_cus, st, t.ev())))
+    if (!HIP_OK(launch_index_select(h->tv, h->ix, q, h->d_park, h->index_lds_bytes, h->num_cus, st, t.ev(), first_tier)))
         return INFAAS_SEL_ERR_HIP;
     return INFAAS_SEL_OK;
 }
@@ -966,16 +966,18 @@ int infaas_sel_select(infaas_sel_t *h, int64_t N, const int32_t *d_task, const i
 
 namespace {
 
-// The state-aware selection, with the worker of every answer when d_out_worker is given.
+// The state-aware selection, with the worker of every answer when d_out_worker is given, or with
+// the closest variant for the queries neither tier answers when d_out_closest is given.
 int tiered_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,
                 const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
-                int32_t *d_out_variant, int32_t *d_out_tier, int32_t *d_out_worker, bool workers, void *hip_stream)
+                int32_t *d_out_variant, int32_t *d_out_tier, int32_t *d_out_worker, bool workers, void *hip_stream,
+                int32_t *d_out_closest = nullptr, bool closest = false)
 {
     if (!h || N < 0) return INFAAS_SEL_ERR_INVALID_ARG;
     if (!h->loaded || !h->inactive || (workers && !h->workers_loaded)) return INFAAS_SEL_ERR_NOT_LOADED;
     if (N == 0) return INFAAS_SEL_OK;
     if (!d_task || !d_slo_us || !d_min_acc_bp || !d_batch_idx || !d_out_variant || !d_out_tier ||
-        (workers && !d_out_worker))
+        (workers && !d_out_worker) || (closest && !d_out_closest))
         return INFAAS_SEL_ERR_INVALID_ARG;
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
@@ -1015,12 +1017,13 @@ int tiered_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t
         q.open = h->d_open; q.open_count = h->d_open_count;
         q.open_cap = index_open_cap(q.n, h->num_cus);
         if (workers) { q.worker = d_out_worker + done; q.row_worker = h->wv.row_worker; }
-        q.pass = workers ? 4 : 2;
+        if (closest) q.closest = d_out_closest + done;
+        q.pass = workers ? 4 : closest ? 6 : 2;
         rc = index_pass(h, q, st);
         if (rc != INFAAS_SEL_OK) return rc;
         if (workers) q.row_worker = h->wv.row_worker + h->V;
-        q.pass = workers ? 5 : 3;
-        rc = index_pass(h->inactive, q, st);
+        q.pass = workers ? 5 : closest ? 7 : 3;
+        rc = index_pass(h->inactive, q, st, &h->tv);
         if (rc != INFAAS_SEL_OK) return rc;
     }
     h->last_stats = h->inactive->ix.stats;
@@ -1035,6 +1038,14 @@ int infaas_sel_select_tiered(infaas_sel_t *h, int64_t N, const int32_t *d_task, 
 {
     return tiered_impl(h, N, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, d_out_tier, nullptr, false,
                        hip_stream);
+}
+
+int infaas_sel_select_tiered_closest(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,
+                                     const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
+                                     int32_t *d_out_variant, int32_t *d_out_tier, int32_t *d_out_closest, void *hip_stream)
+{
+    return tiered_impl(h, N, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, d_out_tier, nullptr, false,
+                       hip_stream, d_out_closest, true);
 }
 
 int infaas_sel_select_workers(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,

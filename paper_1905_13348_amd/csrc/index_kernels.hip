@@ -514,12 +514,18 @@ __device__ __forceinline__ int32_t closest_step(const Mem &mem, int nit, uint32_
 // can answer; it must be launched with the same grid as the pass that wrote the lists.
 // 4 and 5: as 2 and 3, and the worker that serves each answer goes to q.worker (ix.step_worker for
 // answers that are steps of the index, q.row_worker for answers found by the scan).
+// 6 and 7: as 2 and 3, and q.closest gets the complete Case I: the selected variant, or for a query
+// that neither tier can answer the closest variant of the two tiers (6 writes the first tier's
+// suggestion there, 7 -- which gets the first tier's table as tv2 -- compares it with its own).
 template <bool kLds, int kMode>
 __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, IndexView ix, QueryView q,
-                                                              int32_t *__restrict__ park_mem, uint32_t lds_cap)
+                                                              int32_t *__restrict__ park_mem, uint32_t lds_cap, TableView tv2)
 {
-    constexpr bool kClosest = kMode == 1, kFirst = kMode == 2 || kMode == 4, kSecond = kMode == 3 || kMode == 5;
-    constexpr bool kWorker = kMode >= 4;
+    constexpr bool kCase1 = kMode == 6 || kMode == 7;
+    constexpr bool kClosest = kMode == 1, kFirst = kMode == 2 || kMode == 4 || kMode == 6;
+    constexpr bool kSecond = kMode == 3 || kMode == 5 || kMode == 7;
+    constexpr bool kWorker = kMode == 4 || kMode == 5;
+    constexpr bool kSuggest = kClosest || kCase1;   // queries without a feasible variant are parked too, for the suggestion
     extern __shared__ __align__(16) uint32_t lds_w[];  // [16 B control][S + 1 headers][lds_cap bytes of bodies]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t nhdr = (uint32_t)tv.S + 1u;
@@ -706,6 +712,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             for (int k = 0; k < kPerThread; ++k)
                 if (p_qi[k] >= 0 && p_val(k) >= 0) {
                     q.out[p_qi[k]] = p_val(k); q.tier[p_qi[k]] = 2;
+                    if (kCase1) q.closest[p_qi[k]] = p_val(k);
                     if (kWorker) q.worker[p_qi[k]] = p_worker(k);
                 }
         } else if (aligned && p_i0 + kSpan <= q.n) {
@@ -713,7 +720,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             for (int h = 0; h < kPerThread / 4; ++h) {
                 const v4i r = {p_val(4 * h), p_val(4 * h + 1), p_val(4 * h + 2), p_val(4 * h + 3)};
                 __builtin_nontemporal_store(r, (v4i *)((char *)q.out + (uint32_t)p_i0 * 4u) + 64 * h);
-                if (kClosest) __builtin_nontemporal_store(r, (v4i *)((char *)q.closest + (uint32_t)p_i0 * 4u) + 64 * h);
+                if (kSuggest) __builtin_nontemporal_store(r, (v4i *)((char *)q.closest + (uint32_t)p_i0 * 4u) + 64 * h);
                 if (kFirst) {
                     const v4i t4 = {r.x >= 0, r.y >= 0, r.z >= 0, r.w >= 0};
                     __builtin_nontemporal_store(t4, (v4i *)((char *)q.tier + (uint32_t)p_i0 * 4u) + 64 * h);
@@ -728,7 +735,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             for (int k = 0; k < kPerThread; ++k)
                 if (p_i0 + qoff(k) < q.n) {
                     q.out[p_i0 + qoff(k)] = p_val(k);
-                    if (kClosest) q.closest[p_i0 + qoff(k)] = p_val(k);
+                    if (kSuggest) q.closest[p_i0 + qoff(k)] = p_val(k);
                     if (kFirst) q.tier[p_i0 + qoff(k)] = p_val(k) >= 0;
                     if (kWorker) q.worker[p_i0 + qoff(k)] = p_worker(k);
                 }
@@ -753,8 +760,11 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             const uint32_t inside = ((uint32_t)cur.tk[k] < (uint32_t)tv.T) & ((uint32_t)cur.bi[k] < (uint32_t)tv.B);
             const uint32_t ok = inside & (uint32_t)(cur.sl[k] >= 0);   // a negative bound admits nothing
             const uint32_t own = __umul24((uint32_t)cur.tk[k], (uint32_t)tv.B) + (uint32_t)cur.bi[k];
-            const uint32_t s = kSecond ? (uint32_t)cur.tk[k] : (ok ? own : (uint32_t)tv.S);
-            sl_of[k] = kClosest ? (inside ? own : (uint32_t)tv.S) : s;   // the slice a parked record names
+            // (a record of the second tier names its slice; one with a negative bound can only get a suggestion)
+            const uint32_t s = kSecond ? ((kCase1 && cur.sl[k] < 0) ? (uint32_t)tv.S : (uint32_t)cur.tk[k])
+                                       : (ok ? own : (uint32_t)tv.S);
+            // the slice a parked record names
+            sl_of[k] = kSecond ? (uint32_t)cur.tk[k] : (kSuggest ? (inside ? own : (uint32_t)tv.S) : s);
             if (kLds) {
                 const v2u h = lmem.ld64(lds_hdr0 + s * kLdsHdrBytes);
                 body[k] = h.x & ((1u << kLdsAddrBits) - 1u); y[k] = h.y; rec[k] = h.y & 0xFFFFu;
@@ -801,8 +811,8 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             if (kSecond) p_qi[k] = cur.bi[k];
             // parked: a miss that the second body / the scan may still turn into a hit; in the
             // closest-variant mode also every final miss of a query inside the table
-            df[k] = !hit && ((int32_t)y[k] < 0 || (kClosest && sl_of[k] != (uint32_t)tv.S));
-            if (kClosest && (int32_t)y[k] >= 0) sl_of[k] |= kParkFinal;   // nothing feasible: only the suggestion is open
+            df[k] = !hit && ((int32_t)y[k] < 0 || (kSuggest && sl_of[k] != (uint32_t)tv.S));
+            if (kSuggest && (int32_t)y[k] >= 0) sl_of[k] |= kParkFinal;   // nothing feasible: only the suggestion is open
         }
         p_i0 = i0;
 #pragma unroll
@@ -846,7 +856,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         const int32_t slo = __hip_atomic_load(e + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         const int32_t min_acc = __hip_atomic_load(e + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         const int32_t s_ld = __hip_atomic_load(e + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        const bool final_miss = kClosest && have && ((uint32_t)s_ld & kParkFinal);
+        const bool final_miss = kSuggest && have && ((uint32_t)s_ld & kParkFinal);
         const uint32_t s = have ? ((uint32_t)s_ld & ~kParkFinal) : (uint32_t)tv.S;   // idle lanes: the empty slice
         uint32_t y = 0, rec = 0, lbody = rebase, gbody = 0;
         bool resident = false;
@@ -925,6 +935,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         if (kSecond) {
             if (have && ans >= 0) {
                 q.out[qi] = ans; q.tier[qi] = 2;
+                if (kCase1) q.closest[qi] = ans;
                 if (kWorker) q.worker[qi] = wk;
             }
         } else if (have && !final_miss) {
@@ -941,7 +952,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                 if (have && ans < 0) open_out[at + lanes_below(om)] = v4i{qi, slo, min_acc, (int32_t)s};
             }
         }
-        if (kClosest) {
+        if (kSuggest) {
             // the suggestion for the queries that ended with nothing feasible
             const bool open = have && ans < 0;
             const bool by_index = open && indexed && !(y & kHdrTrunc);
@@ -975,8 +986,9 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                         const int64_t tt = (int64_t)tv.tot_r[col + pos], a = (int64_t)tv.acc_r[col + pos];
                         const int64_t over = tt > bound ? tt - bound : 0, shortf = a < am ? am - a : 0;
                         const int32_t missed = (over > 0) + (shortf > 0);
-                        const bool better = missed < b_missed || (missed == b_missed && (over < b_over ||
-                                            (over == b_over && shortf < b_short)));
+                        const bool masked = tv.state != nullptr && tt == 0xFFFFFFFFll;   // a variant of another state
+                        const bool better = !masked && (missed < b_missed || (missed == b_missed && (over < b_over ||
+                                            (over == b_over && shortf < b_short))));
                         if (better) { b_missed = missed; b_over = over; b_short = shortf; b_pos = pos; }
                     }
                     for (int off = 32; off; off >>= 1) {   // then the best of the wavefront
@@ -986,10 +998,39 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                                             (o_over == b_over && (o_short < b_short || (o_short == b_short && o_pos < b_pos)))));
                         if (better) { b_missed = o_missed; b_over = o_over; b_short = o_short; b_pos = o_pos; }
                     }
-                    if (lane == l) sug = L > 0 ? tv.orig_r[col + b_pos] : -1;
+                    if (lane == l) sug = b_missed < 3 ? tv.orig_r[col + b_pos] : -1;
                 }
             }
-            if (have) q.closest[qi] = sug;
+            // a table that serves one state keeps the variants of the other states as entries nothing
+            // selects; such an entry comes out here only when the slice has no variant of the table's state
+            if (tv.state != nullptr && open && sug >= 0 && tv.state[tv.slot_of[sug]] != tv.want_state) sug = -1;
+            if (kMode == 7) {
+                // the first tier's suggestion is in q.closest: the closer of the two, by (requirements
+                // missed, latency beyond the bound, accuracy below the bound), the first tier's at a tie
+                if (open) {
+                    const int32_t b = (int32_t)(s % (uint32_t)tv.B);
+                    auto far = [&](const TableView &t, int32_t row, int32_t &missed, int64_t &over, int64_t &shortf) {
+                        const int32_t slot = t.slot_of[row];
+                        const int64_t tot = (int64_t)((uint32_t)t.lat[(int64_t)b * t.Vp + slot] + (uint32_t)t.queue[slot]);
+                        const int64_t a = t.acc[slot];
+                        over = tot > (int64_t)slo ? tot - (int64_t)slo : 0;
+                        shortf = a < (int64_t)min_acc ? (int64_t)min_acc - a : 0;
+                        missed = (over > 0) + (shortf > 0);
+                    };
+                    const int32_t first = q.closest[qi];
+                    bool keep_first = first >= 0;
+                    if (first >= 0 && sug >= 0) {
+                        int32_t m1, m2;
+                        int64_t o1, o2, s1, s2;
+                        far(tv2, first, m1, o1, s1);
+                        far(tv, sug, m2, o2, s2);
+                        keep_first = m1 < m2 || (m1 == m2 && (o1 < o2 || (o1 == o2 && s1 <= s2)));
+                    }
+                    if (!keep_first) q.closest[qi] = sug;
+                }
+            } else if (have) {
+                q.closest[qi] = sug;
+            }
         }
     };
 
@@ -1062,15 +1103,18 @@ size_t index_park_bytes(int num_cus)
 }
 
 hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const QueryView &q,
-                               int32_t *park_mem, uint32_t lds_bytes, int num_cus, hipStream_t st, const LaunchEvents *ev)
+                               int32_t *park_mem, uint32_t lds_bytes, int num_cus, hipStream_t st, const LaunchEvents *ev,
+                               const TableView *first_tier)
 {
+    const TableView tv2 = first_tier ? *first_tier : tv;
     const int blocks = index_select_blocks(num_cus);
     if (lds_bytes > 0) {
         const uint32_t fixed = kLdsCtrlBytes + lds_header_bytes(tv.S);
         lds_bytes = fixed + ((lds_bytes - fixed) & ~15u);
         auto kernel = q.pass == 1 ? k_index_select<true, 1> : q.pass == 2 ? k_index_select<true, 2> :
                       q.pass == 3 ? k_index_select<true, 3> : q.pass == 4 ? k_index_select<true, 4> :
-                      q.pass == 5 ? k_index_select<true, 5> : k_index_select<true, 0>;
+                      q.pass == 5 ? k_index_select<true, 5> : q.pass == 6 ? k_index_select<true, 6> :
+                      q.pass == 7 ? k_index_select<true, 7> : k_index_select<true, 0>;
         hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes);
         if (e != hipSuccess) return e;
@@ -1081,13 +1125,14 @@ hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const Q
         IndexView ixk = ix;
         if (!hot) ixk.hot_worker = nullptr;
         return launch_kernel(ev, kernel, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), lds_bytes, st, tv, ixk, q,
-                             park_mem, lds_bytes - fixed - hot);
+                             park_mem, lds_bytes - fixed - hot, tv2);
     }
     auto kernel = q.pass == 1 ? k_index_select<false, 1> : q.pass == 2 ? k_index_select<false, 2> :
                   q.pass == 3 ? k_index_select<false, 3> : q.pass == 4 ? k_index_select<false, 4> :
-                  q.pass == 5 ? k_index_select<false, 5> : k_index_select<false, 0>;
+                  q.pass == 5 ? k_index_select<false, 5> : q.pass == 6 ? k_index_select<false, 6> :
+                  q.pass == 7 ? k_index_select<false, 7> : k_index_select<false, 0>;
     return launch_kernel(ev, kernel, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), kLdsCtrlBytes, st, tv, ix, q,
-                         park_mem, 0u);
+                         park_mem, 0u, tv2);
 }
 
 }  // namespace infaas

@@ -159,7 +159,8 @@ struct QueryView {
     // pass looks at (for answers that do not come from a step of the index)
     int32_t *worker;
     const int32_t *row_worker;
-    int32_t pass;        // 0 selection, 1 with closest-variant suggestion, 2 first tier, 3 second tier
+    int32_t pass;        // 0 selection, 1 with closest-variant suggestion, 2 / 3 first / second tier, 4 / 5 the same with
+                         // workers, 6 / 7 the tiers of the complete Case I (suggestion where neither tier answers)
 };
 
 // A pair of events that a launcher attaches to its kernel's dispatch (the events then carry the
@@ -202,8 +203,10 @@ hipError_t launch_index_build(const TableView &tv, const IndexView &ix, hipStrea
 // lds_bytes: dynamic LDS of the lookup kernel when the index is mirrored in LDS, 0 to read it
 // from global memory.  park_mem: index_park_bytes() of device memory (16-byte aligned) for the
 // queues of parked queries; its size does not depend on the number of queries.
+// first_tier: for pass 7 (second tier of the complete Case I), the table of the first tier.
 hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const QueryView &q,
-                               int32_t *park_mem, uint32_t lds_bytes, int num_cus, hipStream_t st, const LaunchEvents *ev = nullptr);
+                               int32_t *park_mem, uint32_t lds_bytes, int num_cus, hipStream_t st, const LaunchEvents *ev = nullptr,
+                               const TableView *first_tier = nullptr);
 int index_select_blocks(int num_cus);
 int32_t index_open_cap(int32_t n, int num_cus);   // records per workgroup of QueryView::open for a pass over n queries
 size_t index_park_bytes(int num_cus);
