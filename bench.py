@@ -167,7 +167,13 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, choices=[0, 1, 2, 3, 4])
-    ap.add_argument("--engine", default="auto", choices=["auto", "scan"])
+    ap.add_argument("--engine", default="auto", choices=["auto", "scan", "index"])
+    ap.add_argument("--table", default="config", choices=["config", "long_staircases", "wide_accuracy"],
+                    help="the configuration's own table, or the same table bent into a shape the staircase index "
+                         "cannot hold (every variant a possible answer; accuracies beyond its 16-bit keys)")
+    ap.add_argument("--degrade", action="store_true",
+                    help="before the steps, one load report over all rows that makes every variant a possible answer "
+                         "(queues that fall with the cost): the index built at load time no longer fits")
     ap.add_argument("--closest", action="store_true",
                     help="time infaas_sel_select_closest (selection plus a suggestion where nothing is "
                          "feasible; 24 B per decision) instead of infaas_sel_select")
@@ -222,12 +228,12 @@ def main() -> int:
         return 0
     cfg = args.config
     spec = workloads.config_spec(cfg)
-    tb = workloads.make_table(cfg)
+    tb = workloads.make_table(cfg) if args.table == "config" else workloads.make_cliff_table(args.table, cfg)
     if args.scale:
         return bench_scale(args, cfg, spec, tb)
     chunks = spec["chunks"]
     per_step = spec["num_queries"] // chunks
-    engine = pkg.ENGINE_AUTO if args.engine == "auto" else pkg.ENGINE_SCAN
+    engine = {"auto": pkg.ENGINE_AUTO, "scan": pkg.ENGINE_SCAN, "index": pkg.ENGINE_INDEX}[args.engine]
     if (args.closest or args.tiered or args.workers or args.case1) and \
             (args.engine != "auto" or args.closest + args.tiered + args.workers + args.case1 > 1):
         print("bench.py: --closest, --tiered, --case1 and --workers need the index engine (--engine auto), one at a time",
@@ -237,6 +243,12 @@ def main() -> int:
     sel = pkg.Selector(tb.num_tasks, tb.batch_sizes, device=0, engine=engine)
     sel.load_variants(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us)
     sel.reserve(per_step)
+    base_queue = tb.queue_us
+    if args.degrade:
+        worst = workloads.make_degrading_load_update(tb)
+        sel.update_load(torch.from_numpy(worst.variant_idx).cuda(), torch.from_numpy(worst.queue_us).cuda())
+        base_queue = worst.queue_us.copy()      # (the report covers every row)
+        torch.cuda.synchronize()
     states = None
     cluster = None
     if args.tiered or args.workers or args.case1:
@@ -379,7 +391,7 @@ def main() -> int:
         ref = oracle.load_oracle()
         q = host_q[(last % n_sets) % n_distinct]
         out, closest, worker = outs[last % n_sets], seconds[last % n_sets], workers_out[last % n_sets]
-        queue = tb.queue_us.copy()
+        queue = base_queue.copy()
         if updates:  # replay the load reports in the order the steps applied them
             for i in range(last + 1):
                 up = updates[i % len(updates)][2]
@@ -428,6 +440,8 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
         "config": {"workload": f"config {cfg} ({spec['name']}): {tb.num_tasks} tasks, {tb.V} variants, "
                                f"{tb.B} batch sizes, {per_step} queries per step"
+                               + (f", table bent to {args.table}" if args.table != "config" else "")
+                               + (", after a load report that makes every variant a possible answer" if args.degrade else "")
                                + f", rotating over {n_sets} batches and result arrays ({n_distinct} seeds)"
                                + (f", load report of {updates[0][2].variant_idx.size} rows before every step" if updates else "")
                                + (", closest-variant mode (two result arrays)" if args.closest else "")
@@ -443,7 +457,7 @@ def main() -> int:
         "kernels_ms_per_step": {k: round(v["total_ms"] / args.steps, 5) for k, v in active.items()},
         "cpu_baseline": cpu,
         "parity_sample_mismatches": mismatches,
-        "index": {k: v for k, v in sel.info().items() if k.startswith("index")},
+        "index": {k: v for k, v in sel.info().items() if k.startswith("index") or k.startswith("lookup")},
     }
     print(json.dumps(line))
     sel.destroy()

@@ -133,6 +133,7 @@ struct infaas_sel {
     int64_t gs_queries = 0, gs_bytes = 0;    // batch size it is good for; its size
     int32_t *d_park = nullptr;        // queues of parked queries of the lookup kernel (fixed size)
     int64_t park_bytes = 0;
+    uint32_t *host_stats = nullptr;   // pinned, device-visible: four counters of the latest index build (kCtlMaxK0 ..)
     int32_t *static_park = nullptr;   // the same queues inside the library's static device array (may be null)
     const uint32_t *last_stats = nullptr;   // statistics of the most recent lookup launch (this table's or the Inactive tier's)
 
@@ -319,6 +320,17 @@ int build_index_now(infaas_sel *h)
         !HIP_OK(launch_index_build(h->tv, ix, nullptr)) || !HIP_OK(hipDeviceSynchronize()) ||
         !HIP_OK(hipMemcpy(h->ix_stats, ix.ctrl, sizeof(ctrl0), hipMemcpyDeviceToHost)))
         return INFAAS_SEL_ERR_HIP;
+    // what the selections' first kernels keep up to date from now on
+    if (h->host_stats) {
+        void *dev = nullptr;
+        for (int i = 0; i < 4; ++i) h->host_stats[i] = h->ix_stats[kCtlMaxK0 + i];
+        if (hipHostGetDevicePointer(&dev, h->host_stats, 0) == hipSuccess) {
+            h->tv.stat_src = ix.ctrl;
+            h->tv.stat_dst = (uint32_t *)dev;
+        } else {
+            (void)hipGetLastError();
+        }
+    }
     // bytes and steps of the index as a whole (info only)
     h->ix_bytes = h->ix_stats[kCtlPool];
     h->ix_steps = (int64_t)h->ix_stats[kCtlSteps] - 1;   // (entry 0 of step_row is unused)
@@ -529,16 +541,25 @@ int group_pass(infaas_sel *h, const QueryView &q, hipStream_t st)
     return INFAAS_SEL_OK;
 }
 
-bool use_index(const infaas_sel *h)
+bool use_index(infaas_sel *h)
 {
     const uint32_t engine = h->flags & INFAAS_SEL_ENGINE_MASK;
     if (!h->have_index || engine == INFAAS_SEL_ENGINE_SCAN) return false;
     if (engine == INFAAS_SEL_ENGINE_INDEX) return true;
+    // The first kernel of every selection copies four counters of the latest index build into pinned
+    // host memory (TableView::stat_dst), so what is read here is at most one call behind, and no
+    // call ever waits for it.
+    uint32_t trunc = h->ix_stats[kCtlTrunc], nobody = h->ix_stats[kCtlNoBody];
+    if (h->host_stats) {
+        trunc = ((volatile uint32_t *)h->host_stats)[kCtlTrunc - kCtlMaxK0];
+        nobody = ((volatile uint32_t *)h->host_stats)[kCtlNoBody - kCtlMaxK0];
+    }
     // auto: the index (mirrored in LDS when it fits, read from global memory otherwise), unless
-    // at load time more than half of the slices could not be indexed completely -- their queries
-    // would mostly end in the in-kernel scan, which the bucketed scan engine does faster
+    // more than half of the slices could not be indexed completely when the table was loaded or, as
+    // far as is known by now, when the index was last rebuilt -- their queries would mostly end in
+    // the in-kernel scan, which the bucketed scan engine does faster
     const int64_t S = (int64_t)h->T * h->B;
-    return 2 * ((int64_t)h->ix_stats[kCtlTrunc] + h->ix_stats[kCtlNoBody]) <= S;
+    return 2 * ((int64_t)trunc + nobody) <= S;
 }
 
 // One pass of the scan engine over n <= 2^28 queries.
@@ -635,6 +656,13 @@ int infaas_sel_create(const infaas_sel_config *cfg, infaas_sel_t **out)
         return INFAAS_SEL_ERR_HIP;
     }
     h->num_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    {
+        DeviceGuard g(h->device);
+        if (g.ok && hipHostMalloc((void **)&h->host_stats, 64, hipHostMallocMapped) != hipSuccess) {
+            (void)hipGetLastError();
+            h->host_stats = nullptr;
+        }
+    }
     {
         // address of the static scratch array on this device, for infaas_sel_select_noalloc (a
         // failure here only makes that one call unavailable)
@@ -1350,6 +1378,7 @@ void infaas_sel_destroy(infaas_sel_t *h)
         h->free_scratch();
         for (auto &p : h->pending) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
         for (auto &e : h->free_events) (void)hipEventDestroy(e);
+        if (h->host_stats) (void)hipHostFree(h->host_stats);
     }
     delete h;
 }
@@ -1440,8 +1469,11 @@ int infaas_sel_get_info(infaas_sel_t *h, infaas_sel_info *out)
     if (h->have_index) {
         out->index_in_lds = h->index_lds_bytes > 0 ? 1 : 0;
         out->index_groups = (int32_t)h->ix.num_groups;
-        out->index_truncated = (int32_t)(h->ix_stats[kCtlTrunc] + h->ix_stats[kCtlNoBody]);
-        out->index_max_steps = (int32_t)h->ix_stats[kCtlMaxK];
+        // (as of the latest build that a selection has run behind, else as loaded)
+        const volatile uint32_t *now = h->host_stats;
+        out->index_truncated = (int32_t)(now ? now[kCtlTrunc - kCtlMaxK0] + now[kCtlNoBody - kCtlMaxK0]
+                                             : h->ix_stats[kCtlTrunc] + h->ix_stats[kCtlNoBody]);
+        out->index_max_steps = (int32_t)(now ? now[kCtlMaxK - kCtlMaxK0] : h->ix_stats[kCtlMaxK]);
         out->index_hot_rows = (int32_t)h->ix.hot_rows;
         out->index_bytes = h->ix_bytes + (int64_t)h->T * h->B * 16 + (h->ix_steps + 1) * 4;
         out->index_steps = h->ix_steps;

@@ -45,7 +45,9 @@ __global__ __launch_bounds__(kGrpThreads) void k_group_bin(TableView tv, IndexVi
 {
     extern __shared__ __align__(16) uint32_t lds[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int G = (int)ix.num_groups, G1 = G + 1;   // group G: queries outside the table (answer -1)
+    const int G = (int)ix.num_groups, G1 = G + 1;
+    publish_index_stats(tv);
+   // group G: queries outside the table (answer -1)
     uint16_t *l_tg = (uint16_t *)lds;
     int32_t *l_t0 = (int32_t *)(lds + ((tv.T + 1) >> 1));
     uint32_t *l_cnt = (uint32_t *)(l_t0 + G1);          // [16][G1]

@@ -527,6 +527,8 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
     constexpr bool kWorker = kMode == 4 || kMode == 5;
     constexpr bool kSuggest = kClosest || kCase1;   // queries without a feasible variant are parked too, for the suggestion
     extern __shared__ __align__(16) uint32_t lds_w[];  // [16 B control][S + 1 headers][lds_cap bytes of bodies]
+    publish_index_stats(tv);
+
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t nhdr = (uint32_t)tv.S + 1u;
     const uint32_t hdr_bytes = kLds ? lds_header_bytes(tv.S) : 0u;

@@ -148,6 +148,7 @@ __global__ __launch_bounds__(256) void k_histogram(TableView tv, QueryView q,
 {
     extern __shared__ int32_t lds_hist[];
     const int tid = threadIdx.x;
+    publish_index_stats(tv);
     if (kLds) {
         for (int i = tid; i < tv.S; i += 256) lds_hist[i] = 0;
         __syncthreads();

@@ -13,6 +13,8 @@ from .configs import (  # noqa: F401
     make_table,
     make_queries,
     make_load_update,
+    make_degrading_load_update,
+    make_cliff_table,
     base_seed,
     VariantStates,
     StateUpdate,

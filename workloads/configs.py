@@ -210,6 +210,45 @@ def make_load_update(cfg: int, V: int, chunk: int, fraction: float = 0.10,
     return LoadUpdate(variant_idx=rows.astype(np.int32), queue_us=vals.astype(np.int32))
 
 
+# ---------------------------------------------------------------- tables and reports the index handles badly
+
+def make_degrading_load_update(tb: VariantTable) -> LoadUpdate:
+    """A load report over ALL rows under which the cheaper a variant of a task is (at the first batch
+    size), the longer its queue: latency plus queue then falls along the cost order, so that (at the
+    first batch size exactly, at the others mostly) no variant dominates a dearer one and every variant
+    is a possible answer.  The worst case for an index of non-dominated variants; no randomness."""
+    queue = np.zeros(tb.V, dtype=np.int64)
+    for t in range(tb.num_tasks):
+        rows = np.flatnonzero(tb.task_id == t)
+        order = rows[np.argsort(tb.cost[rows, 0], kind="stable")]
+        queue[order] = (order.size - np.arange(order.size)) * 600_000
+    assert queue.max() < 2**31 - 1
+    return LoadUpdate(variant_idx=np.arange(tb.V, dtype=np.int32), queue_us=queue.astype(np.int32))
+
+
+def make_cliff_table(kind: str, cfg: int = 2) -> VariantTable:
+    """Configuration ``cfg``'s table bent into a shape the staircase index cannot hold:
+    'long_staircases': in every task accuracy rises and latency falls with the cost, so every variant
+    is a possible answer (thousands of steps per slice, of which the index keeps 62);
+    'wide_accuracy': accuracies spread over 200,001 values, more than the 16-bit keys of the index span."""
+    tb = make_table(cfg)
+    if kind == "wide_accuracy":
+        rng = np.random.default_rng(np.random.PCG64(_SEED0 + cfg + 21000))
+        tb.acc_bp = rng.integers(-100_000, 100_001, size=tb.V, dtype=np.int64).astype(np.int32)
+        return tb
+    if kind != "long_staircases":
+        raise ValueError(f"unknown table kind {kind}")
+    b = np.arange(tb.B, dtype=np.int64)[None, :]
+    for t in range(tb.num_tasks):
+        rows = np.flatnonzero(tb.task_id == t)
+        i = np.arange(rows.size, dtype=np.int64)
+        tb.acc_bp[rows] = 5000 + (4500 * i) // max(rows.size, 1)
+        tb.lat_us[rows] = (60_000 - (59_000 * i) // max(rows.size, 1))[:, None] + 10 * b
+        tb.cost[rows] = (100 + i)[:, None] + b
+        tb.queue_us[rows] = 0
+    return tb
+
+
 # ---------------------------------------------------------------- variant states (state-aware selection)
 
 @dataclass
