@@ -210,7 +210,8 @@ enum { INFAAS_SEL_STATE_INACTIVE = 0, INFAAS_SEL_STATE_ACTIVE = 1,
  * infaas_sel_select answers from the Active variants only, infaas_sel_select_closest is not
  * available (infaas_sel_select_tiered_closest takes its place), and infaas_sel_update_load keeps acting on queue_us (which only the Active tier
  * reads).  A later infaas_sel_load_variants drops the states again.
- * Errors: INVALID_ARG, NOT_LOADED, OUT_OF_RANGE, HIP, OOM.
+ * Errors: INVALID_ARG, NOT_LOADED, OUT_OF_RANGE (the table stays as it was), HIP, OOM (the table is
+ *         dropped: load it again).
  */
 int infaas_sel_load_states(infaas_sel_t *h, const int32_t *state, const int32_t *load_us);
 

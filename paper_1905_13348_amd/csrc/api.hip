@@ -914,7 +914,10 @@ int infaas_sel_load_states(infaas_sel_t *h, const int32_t *state, const int32_t 
     (void)hipFree(d_states);
     if (rc != INFAAS_SEL_OK) {
         if (sub) infaas_sel_destroy(sub);
-        h->tv.state = nullptr;
+        // the states may have been applied to this table's columns already: rather than leave a
+        // table that silently answers from some of its variants, drop it
+        (void)hipDeviceSynchronize();
+        h->free_table();
         return rc;
     }
     sub->timing = h->timing;
@@ -965,7 +968,8 @@ int select_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     hipStream_t st = (hipStream_t)hip_stream;
-    const bool idx = closest || use_index(h);
+    // (with variant states only the index honours them: its columns are masked, the scan's are not)
+    const bool idx = closest || h->inactive != nullptr || use_index(h);
     const bool groups = idx && !closest && !h->inactive && use_groups(h, std::min(N, kMaxPass));
     int rc = groups ? ensure_group_scratch(h, std::min(N, kMaxPass)) : idx ? INFAAS_SEL_OK : ensure_scratch(h, std::min(N, kMaxPass));
     if (rc != INFAAS_SEL_OK) return rc;

@@ -184,3 +184,24 @@ def test_tiered_errors():
     with pytest.raises(lib.InfaasSelError):                   # scan-only handle
         sel.load_states(st.state, st.load_us)
     sel.destroy()
+
+
+def test_plain_select_honours_states_whatever_the_engine(oracle_lib):
+    """A table whose staircases all exceed the index's capacity: a handle in automatic mode answers
+    it with the exhaustive scan.  Once states are loaded the plain call answers from the Active
+    variants only, as the header says -- also on such a handle."""
+    rng = np.random.default_rng(41)
+    tb = _staircase_table(4, 300)
+    state = rng.choice(4, tb.V, p=[0.45, 0.45, 0.05, 0.05]).astype(np.int32)
+    load = rng.integers(0, 60_000, tb.V).astype(np.int32)
+    qs = _staircase_queries(rng, tb, 30_000, 300)
+    sel = make_selector(tb, engine=0)
+    assert sel.info()["index_truncated"] == 8
+    plain = gpu_select(sel, *qs)
+    assert np.array_equal(plain, oracle_lib.select(*table_args(tb), *qs))
+    sel.load_states(state, load)
+    want, tier = oracle_lib.select_tiered(*table_args(tb), state, load, *qs)
+    got = gpu_select(sel, *qs)
+    assert np.array_equal(got, np.where(tier == 1, want, -1)) and (tier == 1).sum() > 1000
+    assert not np.array_equal(got, plain)
+    sel.destroy()
