@@ -363,7 +363,13 @@ def main() -> int:
     fixed_bytes = table_bytes(tb) + (8 * tb.V if args.tiered or args.workers or args.case1 else 0)   # + state and loading latency
     if args.workers:   # + hardware of every variant, the workers, the instances
         fixed_bytes += 4 * tb.V + 8 * cluster.W + 12 * cluster.I
-    if (args.tiered or args.workers or args.case1) and dom == "index_select":
+    if dom.startswith("group_"):
+        # the group-by-group path is three kernels that only together answer a query: they are
+        # priced as one launch, the bytes of the whole call against the sum of their durations
+        algo_bytes = per_decision * per_step + fixed_bytes
+        dom_avg_ms = sum(active[k]["total_ms"] for k in active if k.startswith("group_")) / args.steps
+        dom = "group_bin+group_lookup+group_finish"
+    elif (args.tiered or args.workers or args.case1) and dom == "index_select":
         # one lookup per tier: the pair is priced as one launch against the bytes of the whole call
         algo_bytes = per_decision * per_step + fixed_bytes
         dom_avg_ms = active[dom]["total_ms"] / args.steps
