@@ -17,6 +17,10 @@ FLAGS = [
     # keep the compiler from forming packed-fp32 instructions (the only float code is the
     # double-precision quotient estimate of the scaling decisions)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # no automatic wave-level merging of atomics: the kernels do that themselves where it pays (one
+    # lane asks), and the rewritten form waits for the atomic's result on the spot, which puts the
+    # allocator's microseconds of queueing on the build kernel's critical path
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
 ]
 
 

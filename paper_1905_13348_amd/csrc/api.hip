@@ -176,7 +176,7 @@ struct infaas_sel {
     void free_index()
     {
         (void)hipFree(ix.pool); (void)hipFree(ix.step_row); (void)hipFree(ix.ctrl);  // hdr lives in pool's allocation
-        (void)hipFree(ix.stats);
+        (void)hipFree(ix.stats); (void)hipFree(ix.slice_room);
         (void)hipFree((void *)ix.task_group); (void)hipFree((void *)ix.group_task0); (void)hipFree(ix.gctrl);
         (void)hipFree(ix.step_worker); (void)hipFree(ix.hot_worker);
         (void)hipFree(d_park);
@@ -313,9 +313,11 @@ int build_index_now(infaas_sel *h)
     ctrl0[kCtlPool] = ctrl0[kCtlPool0] = grouped ? ix.num_groups * ix.region_bytes : kDummyBodyBytes;
     ctrl0[kCtlSteps] = ctrl0[kCtlSteps0] = grouped ? ix.num_groups * ix.group_step_cap : 1u;
     ctrl0[kCtlMaxK0] = 1u;
+    ctrl0[kCtlEpoch] = 1u;   // (slice_room is cleared below: build number 0)
     std::vector<uint32_t> g0;
     for (uint32_t g = 0; grouped && g < ix.num_groups; ++g) { g0.push_back(kDummyBodyBytes); g0.push_back(g == 0 ? 1u : 0u); }
     if (!HIP_OK(hipMemcpy(ix.ctrl, ctrl0, sizeof(ctrl0), hipMemcpyHostToDevice)) ||
+        !HIP_OK(hipMemset(ix.slice_room, 0, (size_t)h->T * h->B * sizeof(unsigned long long))) ||
         (grouped && !HIP_OK(hipMemcpy(ix.gctrl, g0.data(), g0.size() * 4, hipMemcpyHostToDevice))) ||
         !HIP_OK(launch_index_build(h->tv, ix, nullptr)) || !HIP_OK(hipDeviceSynchronize()) ||
         !HIP_OK(hipMemcpy(h->ix_stats, ix.ctrl, sizeof(ctrl0), hipMemcpyDeviceToHost)))
@@ -362,7 +364,8 @@ int create_index(infaas_sel *h)
     const size_t nstats = (size_t)index_select_blocks(h->num_cus) * kLookupStats;
     bool ok = dev_alloc(&ix.pool, (size_t)ix.pool_bytes + (size_t)(S + 1) * 16) == hipSuccess &&
               dev_alloc(&ix.step_row, ix.step_cap) == hipSuccess && dev_alloc(&ix.ctrl, kCtlWords) == hipSuccess &&
-              dev_alloc(&ix.stats, nstats) == hipSuccess && dev_alloc(&ix.gctrl, 2 * (size_t)kGroupMaxGroups) == hipSuccess;
+              dev_alloc(&ix.stats, nstats) == hipSuccess && dev_alloc(&ix.gctrl, 2 * (size_t)kGroupMaxGroups) == hipSuccess &&
+              dev_alloc(&ix.slice_room, (size_t)S) == hipSuccess;
     ix.hdr = ok ? (uint4 *)(ix.pool + ix.pool_bytes) : nullptr;
     h->ix = ix;
     const size_t park = index_park_bytes(h->num_cus);

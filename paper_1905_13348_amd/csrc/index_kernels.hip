@@ -39,6 +39,14 @@ __device__ __forceinline__ void wave_sync()
 }
 
 
+// Workgroup barrier that orders LDS traffic only: what the wavefronts have written to LDS is visible
+// to each other behind it, while their requests to global memory stay in flight (__syncthreads also
+// waits for those -- for an atomic on a contended word, microseconds).
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Body of steps [g0, g0 + kb), held one per lane (lanes g0..g0+kb-1), in two parts: what can be
 // computed before the body's place in the pool is known, and the stores.
 struct BodyRegs {
@@ -121,25 +129,33 @@ constexpr int kBuildWaves = 4;                    // slices (wavefronts) per wor
 // microseconds for its turn at the counter).  The larger chunk is faster for slices of thousands of
 // variants; the smaller one takes half the LDS and registers, so that twice as many workgroups run
 // at a time when there are thousands of slices.
-template <int kBuildPer>
+//
+// kShare (few slices of thousands of variants each, where the time is one slice's chain of
+// dependent steps): ONE slice per workgroup.  Its first wavefront finds the steps as above; then all
+// four share the bodies -- each counts and collects over a quarter of the steps, the parts are put
+// together through LDS -- while one of them asks for the room in the pool.
+template <int kBuildPer, bool kShare>
 __global__ __launch_bounds__(64 * kBuildWaves) void k_index_build(TableView tv, IndexView ix)
 {
     constexpr int kBuildChunk = 64 * kBuildPer;   // entries of a slice taken in at a time
-    __shared__ int32_t c_acc_all[kBuildWaves][kBuildChunk];    // candidates: accuracy,
-    __shared__ uint32_t c_tot_all[kBuildWaves][kBuildChunk];   //   latency + queue,
-    __shared__ uint16_t c_pos_all[kBuildWaves][kBuildChunk];   //   position in the chunk
-    __shared__ int32_t p_acc_all[kBuildWaves][64];             // steps, in rank order
-    __shared__ uint32_t p_tot_all[kBuildWaves][64];
-    __shared__ int32_t p_pos_all[kBuildWaves][64];
-    __shared__ uint32_t f_tab_all[kBuildWaves][64];            // the coarse filter's table
-    __shared__ int32_t ranks_all[kBuildWaves][128];            // scratch of body_compute
+    constexpr int kLists = kShare ? 1 : kBuildWaves;   // wavefronts that look for steps
+    __shared__ int32_t c_acc_all[kLists][kBuildChunk];    // candidates: accuracy,
+    __shared__ uint32_t c_tot_all[kLists][kBuildChunk];   //   latency + queue,
+    __shared__ uint16_t c_pos_all[kLists][kBuildChunk];   //   position in the chunk
+    __shared__ int32_t p_acc_all[kLists][64];             // steps, in rank order
+    __shared__ uint32_t p_tot_all[kLists][64];
+    __shared__ int32_t p_pos_all[kLists][64];
+    __shared__ uint32_t f_tab_all[kLists][64];            // the coarse filter's table
+    __shared__ int32_t ranks_all[kLists][128];            // scratch of body_compute; kShare: the steps' places in their bodies
+    __shared__ uint32_t parts[kShare ? kBuildWaves : 1][4][64];   // kShare: what each wavefront found over its quarter of the steps
     __shared__ uint32_t s_size[kBuildWaves], s_steps[kBuildWaves], s_stat[4];
     __shared__ uint32_t s_group[kBuildWaves], s_off[kBuildWaves], s_rec[kBuildWaves];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int32_t *c_acc = c_acc_all[wave], *p_acc = p_acc_all[wave], *p_pos = p_pos_all[wave];
-    uint32_t *c_tot = c_tot_all[wave], *p_tot = p_tot_all[wave], *f_tab = f_tab_all[wave];
-    uint16_t *c_pos = c_pos_all[wave];
-    const int32_t s = blockIdx.x * kBuildWaves + wave;
+    const int mine = kShare ? 0 : wave;                   // the lists this wavefront works on
+    int32_t *c_acc = c_acc_all[mine], *p_acc = p_acc_all[mine], *p_pos = p_pos_all[mine];
+    uint32_t *c_tot = c_tot_all[mine], *p_tot = p_tot_all[mine], *f_tab = f_tab_all[mine];
+    uint16_t *c_pos = c_pos_all[mine];
+    const int32_t s = kShare ? (int32_t)blockIdx.x : (int32_t)blockIdx.x * kBuildWaves + wave;
     const bool inside = s < tv.S;
     const int32_t t = inside ? s / tv.B : 0, b = inside ? s - t * tv.B : 0;
     const int32_t seg = tv.seg_off[t], L = inside ? tv.seg_len[t] : 0;
@@ -174,7 +190,7 @@ __global__ __launch_bounds__(64 * kBuildWaves) void k_index_build(TableView tv, 
         st_tot = lane < K ? p_tot[lane] : 0u;
         st_pos = lane < K ? p_pos[lane] : 0;
     };
-    for (int32_t c0 = 0; c0 < L && !trunc; c0 += kBuildChunk) {
+    for (int32_t c0 = 0; c0 < L && !trunc && (!kShare || wave == 0); c0 += kBuildChunk) {
         const int32_t n = L - c0 < kBuildChunk ? L - c0 : kBuildChunk;
         int32_t va[kBuildPer];
         uint32_t vt[kBuildPer];
@@ -293,6 +309,174 @@ __global__ __launch_bounds__(64 * kBuildWaves) void k_index_build(TableView tv, 
         }
     }
 
+    if constexpr (kShare) {
+        // ---- phase B with one slice per workgroup: the steps are in LDS (p_acc / p_tot / p_pos);
+        // wavefront w counts and collects over steps [w q, w q + q), q = K / 4 rounded up
+        if (wave == 0 && lane == 0) { s_steps[0] = (uint32_t)K; s_size[0] = trunc ? 1u : 0u; }
+        lds_barrier();
+        K = (int32_t)s_steps[0];
+        trunc = s_size[0] != 0u;
+        st_acc = lane < K ? p_acc[lane] : 0;
+        st_tot = lane < K ? p_tot[lane] : 0u;
+        st_pos = lane < K ? p_pos[lane] : 0;
+        const int k0 = K < kBodySteps ? K : kBodySteps, k1 = K - k0;
+        const uint32_t r0 = (uint32_t)k0 < ix.hot_rows ? (uint32_t)k0 : ix.hot_rows;
+        const uint32_t re0 = body_re(k0), re1 = k1 ? body_re(k1) : 0u;
+        const uint32_t rows = (2u * r0 + 3u) & ~3u, size0 = body_bytes(re0);
+        const uint32_t size = L > 0 ? rows + size0 + body_bytes(re1) : 0u;   // (a multiple of 4)
+        const bool has = L > 0;
+        // requested now, used at the end: the caller rows of the steps and the two maxima of the statistics
+        const int32_t row = (wave == 0 && lane < K) ? tv.orig_r[(int64_t)b * tv.Vp + seg + st_pos] : 0;
+        uint32_t stat_now = 0u;
+        if (wave == 0 && lane < 2)
+            stat_now = __hip_atomic_load(&ix.ctrl[lane == 0 ? kCtlMaxK0 : kCtlMaxK], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // Room in the pool and in step_row.  Without groups the slices are placed in the order of their
+        // numbers, so that the layout does not depend on which workgroup was quicker: when the bodies
+        // outgrow the LDS mirror of the lookup kernel, the slices it leaves out are always those of the
+        // last tasks.  Every slice publishes what it needs; the last wavefront adds up what the slices
+        // before its own need, once they have all said so (below).  With groups: one add on the
+        // group's counter pair, asked for now by one lane and looked at after the sets.
+        const bool grouped = ix.num_groups > 1;
+        const unsigned long long add = ((unsigned long long)(uint32_t)K << 32) | size;
+        const uint32_t epoch = ix.ctrl[kCtlEpoch];
+        if (!grouped && threadIdx.x == 0)
+            __hip_atomic_store(ix.slice_room + s, add | ((unsigned long long)epoch << 20), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool asks = grouped && threadIdx.x == 192 && size != 0u;
+        const uint32_t grp = grouped ? (uint32_t)ix.task_group[t] : 0u;
+        unsigned long long *whole = (unsigned long long *)(ix.ctrl + kCtlPool);
+        unsigned long long old = 0;
+        if (asks) old = atomicAdd((unsigned long long *)(ix.gctrl + 2 * grp), add);
+        const int q = (K + kBuildWaves - 1) / kBuildWaves, j_lo = wave * q, j_hi = j_lo + q < K ? j_lo + q : K;
+        const bool second = lane >= k0;   // this lane's step belongs to the second body
+        // 1. the place of every step among the keys of its body: how many steps of the body come before it
+        uint32_t before = 0;              // by accuracy (low half) and by latency-plus-queue (high half)
+        for (int j0 = j_lo; j0 < j_hi; j0 += 4) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int j = j0 + u < j_hi ? j0 + u : j_hi - 1;
+                const bool in = (j0 + u < j_hi) & ((j >= k0) == second);
+                const int32_t aj = p_acc[j];
+                const uint32_t tj = p_tot[j];
+                before += (uint32_t)(in & ((aj > st_acc) | ((aj == st_acc) & (j < lane))));   // (no short-circuit: no branches)
+                before += (uint32_t)(in & ((tj < st_tot) | ((tj == st_tot) & (j < lane)))) << 16;
+            }
+        }
+        parts[wave][0][lane] = before;
+        lds_barrier();
+        before = parts[0][0][lane] + parts[1][0][lane] + parts[2][0][lane] + parts[3][0][lane];
+        const int32_t pa = (int32_t)(before & 0xFFFFu), ps = (int32_t)(before >> 16);
+        int32_t *ranks = ranks_all[0];
+        if (wave == 0) { ranks[lane] = pa; ranks[64 + lane] = ps; }
+        lds_barrier();
+        // 2. the sets: lane p collects A[p] and S[p] of both bodies
+        uint32_t ma0 = 0u, ms0 = 0u, ma1 = 0u, ms1 = 0u;
+        for (int j0 = j_lo; j0 < j_hi; j0 += 4) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int j = j0 + u < j_hi ? j0 + u : j_hi - 1;
+                const bool in = j0 + u < j_hi, first = j < k0;
+                const uint32_t bit = in ? 1u << (first ? j : j - k0) : 0u;
+                const bool a_in = ranks[j] < lane, s_in = ranks[64 + j] < lane;
+                ma0 |= (first & a_in) ? bit : 0u;
+                ms0 |= (first & s_in) ? bit : 0u;
+                ma1 |= (!first & a_in) ? bit : 0u;
+                ms1 |= (!first & s_in) ? bit : 0u;
+            }
+        }
+        parts[wave][0][lane] = ma0; parts[wave][1][lane] = ms0; parts[wave][2][lane] = ma1; parts[wave][3][lane] = ms1;
+        if (asks) {
+            uint32_t off = (uint32_t)old, rec = (uint32_t)(old >> 32);
+            if (off + size <= ix.region_bytes && rec + (uint32_t)K <= ix.group_step_cap) {
+                off += grp * ix.region_bytes; rec += grp * ix.group_step_cap;
+            } else {   // the group's region has no room: behind the regions
+                const unsigned long long o2 = atomicAdd(whole, add);
+                off = (uint32_t)o2; rec = (uint32_t)(o2 >> 32);
+            }
+            s_off[0] = off; s_rec[0] = rec;
+        }
+        if (!grouped && wave == 3) {
+            // What the slices before this one need, lane by lane.  An entry counts once it carries this
+            // build's number.  The wait is bounded: every slice publishes as soon as it knows its steps,
+            // whatever the others do, and workgroups start in the order of their numbers; should the
+            // entries still not be there after kRoomPolls rounds, the slice goes without a body and
+            // its queries are answered by the scan.
+            constexpr int kRoomPolls = 1 << 16;
+            unsigned long long sum = 0;
+            bool got = false;
+            for (int poll = 0; poll < kRoomPolls && !got; ++poll) {
+                bool ok = true;
+                sum = 0;
+                for (int32_t i = lane; i < s; i += 64) {
+                    const unsigned long long v = __hip_atomic_load(ix.slice_room + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    ok = ok && (((uint32_t)v >> 20) == epoch);
+                    sum += v & 0xFFFFFFFF000FFFFFull;
+                }
+                got = __ballot(!ok) == 0ull;
+                if (!got) __builtin_amdgcn_s_sleep(16);
+            }
+            for (int o = 32; o; o >>= 1) sum += __shfl_xor(sum, o);
+            if (lane == 0) {
+                s_off[0] = got ? ix.ctrl[kCtlPool0] + (uint32_t)sum : 0xFFFFFFFFu;
+                s_rec[0] = got ? ix.ctrl[kCtlSteps0] + (uint32_t)(sum >> 32) : 0xFFFFFFFFu;
+            }
+        }
+        if (wave == 2) {   // do the accuracies fit 16-bit keys?
+            int32_t hi = __builtin_amdgcn_readfirstlane(st_acc), lo = hi;   // (of lane 0, a step whenever the slice has variants)
+            for (int32_t j0 = 1; j0 < K; j0 += 8) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int32_t aj = p_acc[j0 + u < K ? j0 + u : 0];
+                    hi = aj > hi ? aj : hi;
+                    lo = aj < lo ? aj : lo;
+                }
+            }
+            if (lane == 0) s_group[0] = ((int64_t)hi - (int64_t)tv.acc_base <= 65533 && lo >= tv.acc_base) ? 1u : 0u;
+        }
+        lds_barrier();   // (also: the room and the verdict on the accuracies are in LDS)
+        const uint32_t off = s_off[0], rec = s_rec[0];
+        const bool fits = has && (uint64_t)off + size <= ix.pool_bytes && (uint64_t)rec + K <= ix.step_cap && s_group[0] != 0u;
+        uint8_t *body0 = ix.pool + off + rows;
+        if (!grouped && s == tv.S - 1 && threadIdx.x == 0 && off != 0xFFFFFFFFu) {   // the totals, for the statistics
+            ix.ctrl[kCtlPool] = off + size;
+            ix.ctrl[kCtlSteps] = rec + (uint32_t)K;
+        }
+        if (wave <= 1 && fits && (wave == 0 || k1)) {   // wavefront 0 writes the first body, wavefront 1 the second
+            const int h = 2 * wave;
+            BodyRegs r{pa, ps, parts[0][h][lane] | parts[1][h][lane] | parts[2][h][lane] | parts[3][h][lane],
+                       parts[0][h + 1][lane] | parts[1][h + 1][lane] | parts[2][h + 1][lane] | parts[3][h + 1][lane]};
+            if (wave == 0) body_store(body0, 0, k0, lane, st_acc, st_tot, tv.acc_base, r);
+            else body_store(body0 + size0, k0, k1, lane, st_acc, st_tot, tv.acc_base, r);
+        }
+        if (wave != 0) return;   // (no barrier follows)
+        if (fits && lane < K) {
+            ix.step_row[rec + lane] = row;
+            if ((uint32_t)lane < r0)   // in reverse in front of the body
+                *(uint16_t *)(body0 - 2 - 2 * lane) = (uint16_t)row;
+        }
+        uint32_t row_hi = 0;   // of the first steps' rows the bits above the low 16 go into the header
+        for (uint32_t j = 0; j < r0; ++j)
+            row_hi |= ((uint32_t)__builtin_amdgcn_readlane(row, (int)j) >> 16) << (j * ix.row_hi_bits);
+        if (lane == 0) {
+            if (fits) {
+                const uint32_t y = (re0 << kHdrK0Shift) | (re1 << kHdrK1Shift) | (trunc ? kHdrTrunc : 0u) |
+                                   ((k1 || trunc) ? kHdrDeep : 0u) | row_hi;
+                ix.hdr[s] = make_uint4(off + rows - 4u, y, rec, off + size);
+            } else if (has) {   // no body: every query of this slice goes to the rank-ordered scan
+                ix.hdr[s] = make_uint4(0u, kEmptyHdrY | kHdrPark | kHdrTrunc | kHdrDeep, 0u, 0u);
+            } else {            // no variants: the empty dummy body at offset 0 answers "nothing feasible"
+                ix.hdr[s] = make_uint4(0u, kEmptyHdrY, 0u, 4u + body_bytes(2));
+            }
+        }
+        // statistics: lanes 0..3 one word each; the maxima only where they raise what was read above
+        if (lane < 4) {
+            constexpr int word[4] = {kCtlMaxK0, kCtlMaxK, kCtlTrunc, kCtlNoBody};
+            const uint32_t v = lane == 0 ? (fits ? (uint32_t)k0 : 0u) : lane == 1 ? (fits ? (uint32_t)K : 0u)
+                             : lane == 2 ? ((fits && trunc) ? 1u : 0u) : ((has && !fits) ? 1u : 0u);
+            if (lane >= 2) { if (v) atomicAdd(&ix.ctrl[word[lane]], v); }
+            else if (v > stat_now) atomicMax(&ix.ctrl[word[lane]], v);
+        }
+        return;
+    }
     // ---- phase B: one or two bodies of sorted keys and bit sets, computed while the workgroup's
     // request for room in the pool is under way
     const int k0 = K < kBodySteps ? K : kBodySteps, k1 = K - k0;
@@ -881,31 +1065,31 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             if (kWorker) wk = ix.step_worker[at];
         };
         bool done = final_miss;
-        // first body from global memory: only if the main loop could not use an LDS copy
+        // bodies in global memory (the first one only if the main loop could not use an LDS copy):
+        // both are searched together, level by level, so that one body's trips to memory hide the other's
         const bool need_g0 = have && indexed && kLds && !resident && !done;
-        if (__ballot(need_g0)) {
-            const uint32_t bd[1] = {need_g0 ? gbody : 0u}, ks[1] = {need_g0 ? keys0 : 2u};
-            uint32_t m[1];
-            search_bodies<1>(gmem, nit, bd, ks, dd, lim, m);
-            if (need_g0 && m[0]) { take_step(rec + __builtin_ctz(m[0])); done = true; }
-            st_global += (uint32_t)__builtin_popcountll(__ballot(need_g0 && m[0]));
+        const bool need_g1 = have && indexed && keys1 != 0u && !resident && !done;
+        if (__ballot(need_g0 | need_g1)) {
+            const uint32_t bd[2] = {need_g0 ? gbody : 0u, need_g1 ? gbody + size0 : 0u};
+            const uint32_t ks[2] = {need_g0 ? keys0 : 2u, need_g1 ? keys1 : 2u};
+            const uint32_t dd2[2] = {dd[0], dd[0]}, lim2[2] = {lim[0], lim[0]};
+            uint32_t m[2];
+            search_bodies<2>(gmem, nit, bd, ks, dd2, lim2, m);
+            const bool hit0 = need_g0 && m[0], hit1 = need_g1 && !hit0 && m[1];
+            if (hit0) take_step(rec + __builtin_ctz(m[0]));
+            if (hit1) take_step(rec + kBodySteps + __builtin_ctz(m[1]));
+            done = done || hit0 || hit1;
+            st_global += (uint32_t)__builtin_popcountll(__ballot(hit0));
+            st_second += (uint32_t)__builtin_popcountll(__ballot(hit1));
         }
-        // second body: LDS copy when resident, global memory otherwise
-        const bool need1 = have && indexed && keys1 != 0u && !done;
-        const bool need_l1 = need1 && resident, need_g1 = need1 && !resident;
+        // second body of a slice whose bodies are in LDS
+        const bool need_l1 = have && indexed && keys1 != 0u && resident && !done;
         if (kLds && __ballot(need_l1)) {
             const uint32_t bd[1] = {need_l1 ? lbody + size0 : rebase}, ks[1] = {need_l1 ? keys1 : 2u};
             uint32_t m[1];
             search_bodies<1>(lmem, nit, bd, ks, dd, lim, m);
             if (need_l1 && m[0]) { take_step(rec + kBodySteps + __builtin_ctz(m[0])); done = true; }
             st_second += (uint32_t)__builtin_popcountll(__ballot(need_l1 && m[0]));
-        }
-        if (__ballot(need_g1)) {
-            const uint32_t bd[1] = {need_g1 ? gbody + size0 : 0u}, ks[1] = {need_g1 ? keys1 : 2u};
-            uint32_t m[1];
-            search_bodies<1>(gmem, nit, bd, ks, dd, lim, m);
-            if (need_g1 && m[0]) { take_step(rec + kBodySteps + __builtin_ctz(m[0])); done = true; }
-            st_second += (uint32_t)__builtin_popcountll(__ballot(need_g1 && m[0]));
         }
         // no body, or both bodies missed and more steps exist: scan the slice in rank order
         uint64_t todo = __ballot(have && !done && (!indexed || (y & kHdrTrunc)));
@@ -1082,10 +1266,14 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
 hipError_t launch_index_build(const TableView &tv, const IndexView &ix, hipStream_t st, const LaunchEvents *ev)
 {
     if (tv.S <= 0) return hipSuccess;
-    const dim3 grid((unsigned)((tv.S + kBuildWaves - 1) / kBuildWaves)), block(64 * kBuildWaves);
+    const dim3 block(64 * kBuildWaves);
+    // few slices of many variants each: one slice per workgroup, its wavefronts share the bodies
+    if (tv.S <= 512 && (int64_t)tv.Vp >= 512 * (int64_t)tv.T)
+        return launch_kernel(ev, k_index_build<32, true>, dim3((unsigned)tv.S), block, 0, st, tv, ix);
+    const dim3 grid((unsigned)((tv.S + kBuildWaves - 1) / kBuildWaves));
     // up to 1024 slices every workgroup is resident at once whatever its size: the larger chunk
-    if (tv.S <= 1024) return launch_kernel(ev, k_index_build<32>, grid, block, 0, st, tv, ix);
-    return launch_kernel(ev, k_index_build<16>, grid, block, 0, st, tv, ix);
+    if (tv.S <= 1024) return launch_kernel(ev, k_index_build<32, false>, grid, block, 0, st, tv, ix);
+    return launch_kernel(ev, k_index_build<16, false>, grid, block, 0, st, tv, ix);
 }
 
 int index_select_blocks(int num_cus) { return num_cus; }

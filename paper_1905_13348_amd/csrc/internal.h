@@ -110,6 +110,8 @@ struct IndexView {
     uint32_t hot_rows;   // rows kept in front of the first body of every slice (fills the LDS left over)
     uint32_t row_hi_bits;// bits of a row number above its low 16
     uint32_t *ctrl;      // [kCtlWords] counters of the build, see kCtl*
+    unsigned long long *slice_room;   // [S] what slice s needs, published by the build that places the slices in the
+                         // order of their numbers: steps << 32 | build number (12 bits) << 20 | bytes
     // Groups.  When the bodies of all slices do not fit one compute unit's LDS, the tasks are dealt, in
     // order, to num_groups groups whose bodies do: group g owns the tasks [group_task0[g],
     // group_task0[g + 1]), the bytes [g * region_bytes, (g + 1) * region_bytes) of the pool (every region
@@ -129,6 +131,7 @@ constexpr int kCtlPool = 0;       // bytes of the pool handed out (with groups: 
 constexpr int kCtlSteps = 1;      // entries of step_row handed out (entry 0 is unused)
 constexpr int kCtlPool0 = 8;      // what the two counters above start from at every rebuild
 constexpr int kCtlSteps0 = 9;
+constexpr int kCtlEpoch = 10;     // number of the build (12 bits), so that what earlier builds left in slice_room is told apart
 constexpr int kCtlMaxK0 = 32;     // most steps in a first body (sets the probe count of the lookup)
 constexpr int kCtlTrunc = 33;     // slices with more steps than the index keeps
 constexpr int kCtlNoBody = 34;    // slices without a body

@@ -80,6 +80,7 @@ __device__ __forceinline__ void rewind_index(const IndexView &ix, int64_t tid)
     if (tid == 0) {
         ix.ctrl[kCtlPool] = ix.ctrl[kCtlPool0];
         ix.ctrl[kCtlSteps] = ix.ctrl[kCtlSteps0];
+        ix.ctrl[kCtlEpoch] = (ix.ctrl[kCtlEpoch] + 1u) & 0xFFFu;
         ix.ctrl[kCtlMaxK0] = 1;
         ix.ctrl[kCtlTrunc] = 0;
         ix.ctrl[kCtlNoBody] = 0;
