@@ -176,25 +176,25 @@ def test_update_load_then_select(oracle_lib, engine):
     sel.destroy()
 
 
-def _staircase_table(T, n, B=2, acc0=1000, acc_step=1):
+def _staircase_table(T, n, B=2, acc0=1000, acc_step=1, lat0=100_000):
     """Every variant of a task is a step: cost, accuracy rise and latency falls with the row, so no
     cheaper variant dominates a dearer one.  The staircase of a slice has n entries."""
     task = np.repeat(np.arange(T, dtype=np.int32), n)
     i = np.tile(np.arange(n, dtype=np.int64), T)
     acc = acc0 + acc_step * i
-    lat = np.stack([100_000 - 100 * i + 7 * b for b in range(B)], axis=1)
+    lat = np.stack([lat0 - 100 * i + 7 * b for b in range(B)], axis=1)
     cost = np.stack([10 + i + b for b in range(B)], axis=1)
     queue = np.zeros(T * n, np.int64)
     return _table(T, list(range(1, B + 1)), task, acc, lat, cost, queue)
 
 
-def _staircase_queries(rng, tb, n_queries, n):
+def _staircase_queries(rng, tb, n_queries, n, lat0=100_000):
     T, B = tb.num_tasks, tb.B
     task = rng.integers(0, T, n_queries)
     bidx = rng.integers(0, B, n_queries)
     want_row = rng.integers(-3, n + 3, n_queries)           # aim at a given depth of the staircase
     acc = tb.acc_bp.min() + (tb.acc_bp[1] - tb.acc_bp[0]) * want_row
-    slo = rng.choice([100_000 + 50, 60_000, 20_000, 99_000], n_queries) + rng.integers(-300, 300, n_queries)
+    slo = rng.choice([lat0 + 50, lat0 * 6 // 10, lat0 // 5, lat0 * 99 // 100], n_queries) + rng.integers(-300, 300, n_queries)
     return tuple(np.asarray(x, np.int32) for x in (task, slo, acc, bidx))
 
 
@@ -524,4 +524,62 @@ def test_more_queries_than_one_pass(oracle_lib):
     assert np.array_equal(out[pick_d].cpu().numpy(), want_sel)
     assert np.array_equal(clo[pick_d].cpu().numpy(), want_clo)
     assert int((clo == -7).sum()) == 0 and int((out == -7).sum()) == 0
+    sel.destroy()
+
+
+def test_few_long_slices_with_reports(oracle_lib):
+    """Few slices of thousands of variants each -- the index build that gives every slice a
+    workgroup of its own and places the slices in the order of their numbers: segments of more than
+    one 2048-entry chunk, one exactly at the chunk's edge, an empty task; the index rebuilt behind
+    load reports, every query against the oracle each time."""
+    rng = np.random.default_rng(77)
+    sizes = np.array([5000, 0, 2500, 4100, 2048, 6000])
+    tb = _random_table(rng, 6, sizes, 3)
+    qs = _random_queries(rng, 6, 3, 60_000)
+    sel = make_selector(tb, engine=2)
+    queue = tb.queue_us.copy()
+    for rnd in range(4):
+        if rnd:
+            idx = rng.choice(tb.V, tb.V // 5, replace=False).astype(np.int32)
+            val = rng.integers(0, 150_000, idx.size).astype(np.int32)
+            sel.update_load(to_dev(idx), to_dev(val))
+            oracle_lib.update_load(queue, idx, val)
+        got = gpu_select(sel, *qs)
+        want = oracle_lib.select(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, queue, *qs)
+        bad = np.flatnonzero(got != want)
+        assert bad.size == 0, f"round {rnd}: {bad.size} mismatches, first at {bad[:5]}"
+    info = sel.info()
+    assert info["index_truncated"] == 0 and 20 <= info["index_max_steps"] <= 62
+    sel.destroy()
+
+
+@pytest.mark.parametrize("engine", [0, 2], ids=["auto", "index"])
+def test_few_slices_of_nothing_but_steps(oracle_lib, engine):
+    """The same build on slices where every variant is a step (2100 of them, the index keeps 62):
+    every slice truncated, the queries finished by the scan."""
+    rng = np.random.default_rng(78)
+    tb = _staircase_table(3, 2100, B=2, lat0=300_000)
+    qs = _staircase_queries(rng, tb, 20_000, 2100, lat0=300_000)
+    _compare(oracle_lib, tb, qs, engine, label="staircase2100")
+    sel = make_selector(tb, engine=engine)
+    info = sel.info()
+    assert info["index_truncated"] == 6 and info["index_max_steps"] == 62
+    sel.destroy()
+
+
+def test_512_slices_in_groups(oracle_lib):
+    """512 slices of 600 steps each: one workgroup per slice in the build, and bodies (62 steps kept
+    per slice, 470 KB) that need groups; a call below and one above the size from which queries are
+    binned by group."""
+    rng = np.random.default_rng(79)
+    tb = _staircase_table(64, 600, B=8)
+    sel = make_selector(tb, engine=2)
+    info = sel.info()
+    assert info["index_groups"] > 1 and info["index_truncated"] == 512
+    for n in (50_000, (1 << 20) + 3000):
+        qs = _staircase_queries(rng, tb, n, 600)
+        got = gpu_select(sel, *qs)
+        want = oracle_lib.select(*table_args(tb), *qs)
+        bad = np.flatnonzero(got != want)
+        assert bad.size == 0, f"N={n}: {bad.size} mismatches, first at {bad[:5]}"
     sel.destroy()
