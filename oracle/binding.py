@@ -73,6 +73,14 @@ class Oracle:
             fn = getattr(lib, name)
             fn.argtypes = [ctypes.c_int64, _I32P, ctypes.c_int64, _I32P, _I32P]
             fn.restype = None
+        lib.oracle_derive_states.argtypes = [ctypes.c_int64, ctypes.c_int64, _I32P, _I32P, _I32P]
+        lib.oracle_derive_states.restype = ctypes.c_int
+        lib.oracle_select_instances.argtypes = ([ctypes.c_int64, ctypes.c_int32] + [_I32P] * 7
+                                                + [ctypes.c_int64, _I32P, _I32P] + [ctypes.c_int64] + [_I32P] * 4
+                                                + [ctypes.c_int32, ctypes.c_int64] + [_I32P] * 7)
+        lib.oracle_select_instances.restype = ctypes.c_int
+        lib.oracle_update_instance_state.argtypes = [ctypes.c_int64, _I32P, ctypes.c_int64, _I32P, _I32P]
+        lib.oracle_update_instance_state.restype = None
         lib.oracle_scale.argtypes = ([ctypes.c_int64, ctypes.c_int32] + [_I32P] * 5 + [ctypes.c_int32, ctypes.c_int32]
                                      + [ctypes.c_int64] + [_I32P] * 8)
         lib.oracle_scale.restype = ctypes.c_int
@@ -228,6 +236,52 @@ class Oracle:
         inst_idx, new_load = _i32(inst_idx), _i32(new_load)
         self._lib.oracle_update_instance_load(inst_load.shape[0], _ptr(inst_load), inst_idx.shape[0],
                                               _ptr(inst_idx), _ptr(new_load))
+
+    def derive_states(self, num_variants, inst_variant, inst_state):
+        """State of every variant from the states of its instances (Inactive without any)."""
+        inst_variant, inst_state = _i32(inst_variant), _i32(inst_state)
+        assert inst_variant.shape == inst_state.shape
+        out = np.empty(num_variants, dtype=np.int32)
+        if self._lib.oracle_derive_states(num_variants, inst_variant.shape[0], _ptr(inst_variant), _ptr(inst_state),
+                                          _ptr(out)) != 0:
+            raise ValueError("oracle rejected its arguments")
+        return out
+
+    def select_instances(self, task_id, acc_bp, lat_us, cost, queue_us, load_us, variant_hw,
+                         worker_hw, worker_util, inst_variant, inst_worker, inst_load, inst_state,
+                         q_task, q_slo, q_min_acc, q_bidx, literal=False):
+        """(variant or -1, tier, worker or -1) per query with the state kept per running instance."""
+        task_id, acc_bp, queue_us = _i32(task_id), _i32(acc_bp), _i32(queue_us)
+        lat_us, cost, load_us = _i32(lat_us), _i32(cost), _i32(load_us)
+        variant_hw, worker_hw, worker_util = _i32(variant_hw), _i32(worker_hw), _i32(worker_util)
+        inst_variant, inst_worker = _i32(inst_variant), _i32(inst_worker)
+        inst_load, inst_state = _i32(inst_load), _i32(inst_state)
+        V, B = lat_us.shape
+        assert cost.shape == lat_us.shape
+        for a in (task_id, acc_bp, queue_us, load_us, variant_hw):
+            assert a.shape == (V,)
+        W, n_inst = worker_hw.shape[0], inst_variant.shape[0]
+        assert worker_util.shape == (W,)
+        for a in (inst_worker, inst_load, inst_state):
+            assert a.shape == (n_inst,)
+        q_task, q_slo, q_min_acc, q_bidx = _i32(q_task), _i32(q_slo), _i32(q_min_acc), _i32(q_bidx)
+        N = q_task.shape[0]
+        out, tier, worker = (np.empty(N, dtype=np.int32) for _ in range(3))
+        rc = self._lib.oracle_select_instances(
+            V, B, _ptr(task_id), _ptr(acc_bp), _ptr(lat_us), _ptr(cost), _ptr(queue_us), _ptr(load_us), _ptr(variant_hw),
+            W, _ptr(worker_hw), _ptr(worker_util), n_inst, _ptr(inst_variant), _ptr(inst_worker), _ptr(inst_load),
+            _ptr(inst_state), 1 if literal else 0, N, _ptr(q_task), _ptr(q_slo), _ptr(q_min_acc), _ptr(q_bidx),
+            _ptr(out), _ptr(tier), _ptr(worker))
+        if rc != 0:
+            raise ValueError("oracle rejected its arguments")
+        return out, tier, worker
+
+    def update_instance_state(self, inst_state: np.ndarray, inst_idx, new_state) -> None:
+        """In place: inst_state[inst_idx[i]] = new_state[i], array order, invalid entries skipped."""
+        assert inst_state.dtype == np.int32 and inst_state.flags["C_CONTIGUOUS"]
+        inst_idx, new_state = _i32(inst_idx), _i32(new_state)
+        self._lib.oracle_update_instance_state(inst_state.shape[0], _ptr(inst_state), inst_idx.shape[0],
+                                               _ptr(inst_idx), _ptr(new_state))
 
     def scale(self, arch_id, sat_qps, hw_cost, load_us, lat_us, lambda_per_s, slack_pct,
               r_variant, r_instances, r_load_qps, r_slo, r_bidx):

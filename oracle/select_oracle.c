@@ -839,6 +839,155 @@ void oracle_update_instance_load(int64_t n_inst, int32_t *inst_load, int64_t n,
 }
 
 /*
+ * State per running instance (Section 4, "State machine for the lifecycle of model-variants": the
+ * state is tracked per variant INSTANCE by the monitoring daemon of the worker that runs it;
+ * Section 5 encodes an instance as a {variant, worker} pair).  A loaded instance is Active,
+ * Overloaded or Interfered; a variant that runs nowhere is Inactive.  Case I (Section 4.1) then
+ * reads:
+ *
+ *   a variant is looked at in the first step when at least one of its instances is Active, and the
+ *   query goes to the least-loaded worker among those that run an ACTIVE instance of it (an
+ *   Overloaded or Interfered instance is avoided even when another instance of the same variant
+ *   serves);
+ *   a variant without any instance is looked at in the second step, as before;
+ *   a variant whose instances are all Overloaded or Interfered is not selected at all.
+ *
+ * Readings where the text is silent: the state of a variant with instances but no Active one is
+ * reported as Overloaded when any instance is Overloaded, else Interfered (nothing depends on
+ * which); instance state reports are applied in array order and skip entries whose index is
+ * outside the table or whose code is not Active, Overloaded or Interfered (an instance cannot be
+ * Inactive: it is loaded).
+ */
+int oracle_derive_states(int64_t V, int64_t n_inst, const int32_t *inst_variant,
+                         const int32_t *inst_state, int32_t *out_state)
+{
+    for (int64_t i = 0; i < n_inst; ++i)
+        if (inst_variant[i] < 0 || inst_variant[i] >= V)
+            return -1;
+    int64_t *running = (int64_t *)calloc((size_t)V + 1, sizeof(int64_t));
+    int64_t *active = (int64_t *)calloc((size_t)V + 1, sizeof(int64_t));
+    int64_t *overloaded = (int64_t *)calloc((size_t)V + 1, sizeof(int64_t));
+    if (!running || !active || !overloaded) {
+        free(running); free(active); free(overloaded);
+        return -1;
+    }
+    for (int64_t i = 0; i < n_inst; ++i) {
+        int64_t v = inst_variant[i];
+        running[v] += 1;
+        active[v] += inst_state[i] == STATE_ACTIVE;
+        overloaded[v] += inst_state[i] == STATE_OVERLOADED;
+    }
+    for (int64_t v = 0; v < V; ++v) {
+        if (running[v] == 0)
+            out_state[v] = STATE_INACTIVE;
+        else if (active[v] > 0)
+            out_state[v] = STATE_ACTIVE;
+        else
+            out_state[v] = overloaded[v] > 0 ? STATE_OVERLOADED : STATE_INTERFERED;
+    }
+    free(running); free(active); free(overloaded);
+    return 0;
+}
+
+/* Least-loaded worker among those that run an Active instance of the variant; equal loads go to
+ * the lower worker number; -1 when there is none.  list == NULL: every instance is looked at;
+ * else only the n_list instances listed. */
+static int32_t least_loaded_active_worker(int64_t n_inst, const int32_t *inst_variant,
+                                          const int32_t *inst_worker, const int32_t *inst_load,
+                                          const int32_t *inst_state,
+                                          const int64_t *list, int64_t n_list, int32_t variant)
+{
+    int64_t best = -1;
+    int64_t count = list ? n_list : n_inst;
+    for (int64_t j = 0; j < count; ++j) {
+        int64_t i = list ? list[j] : j;
+        if (inst_variant[i] != variant || inst_state[i] != STATE_ACTIVE)
+            continue;
+        if (best < 0 || inst_load[i] < inst_load[best] ||
+            (inst_load[i] == inst_load[best] && inst_worker[i] < inst_worker[best]))
+            best = i;
+    }
+    return best >= 0 ? inst_worker[best] : -1;
+}
+
+/* Case I with the state kept per instance: (variant, tier, worker) per query.  literal != 0: every
+ * query walks all V rows and all instances; else the rows are listed per task and the instances
+ * per variant once, and each query walks the lists of its own (queries on several host threads). */
+int oracle_select_instances(int64_t V, int32_t B,
+                            const int32_t *task_id, const int32_t *acc_bp,
+                            const int32_t *lat_us, const int32_t *cost, const int32_t *queue_us,
+                            const int32_t *load_us, const int32_t *variant_hw,
+                            int64_t W, const int32_t *worker_hw, const int32_t *worker_util,
+                            int64_t n_inst, const int32_t *inst_variant,
+                            const int32_t *inst_worker, const int32_t *inst_load,
+                            const int32_t *inst_state, int32_t literal,
+                            int64_t N,
+                            const int32_t *q_task, const int32_t *q_slo_us,
+                            const int32_t *q_min_acc_bp, const int32_t *q_batch_idx,
+                            int32_t *out_variant, int32_t *out_tier, int32_t *out_worker)
+{
+    if (!workers_args_ok(V, W, n_inst, inst_variant, inst_worker))
+        return -1;
+    for (int64_t i = 0; i < n_inst; ++i)
+        if (inst_state[i] != STATE_ACTIVE && inst_state[i] != STATE_OVERLOADED && inst_state[i] != STATE_INTERFERED)
+            return -1;
+    int32_t *state = (int32_t *)malloc(sizeof(int32_t) * (size_t)(V > 0 ? V : 1));
+    int64_t *first = (int64_t *)calloc((size_t)V + 1, sizeof(int64_t));
+    int64_t *fill = (int64_t *)calloc((size_t)V + 1, sizeof(int64_t));
+    int64_t *list = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n_inst > 0 ? n_inst : 1));
+    int rc = (state && first && fill && list) ? 0 : -1;
+    if (rc == 0)
+        rc = oracle_derive_states(V, n_inst, inst_variant, inst_state, state);
+    if (rc == 0)
+        rc = literal ? oracle_select_tiered_literal(V, B, task_id, acc_bp, lat_us, cost, queue_us, state, load_us,
+                                                    N, q_task, q_slo_us, q_min_acc_bp, q_batch_idx, out_variant, out_tier)
+                     : oracle_select_tiered(V, B, task_id, acc_bp, lat_us, cost, queue_us, state, load_us,
+                                            N, q_task, q_slo_us, q_min_acc_bp, q_batch_idx, out_variant, out_tier);
+    if (rc != 0) {
+        free(state); free(first); free(fill); free(list);
+        return rc;
+    }
+    for (int64_t i = 0; i < n_inst; ++i)
+        first[inst_variant[i] + 1] += 1;
+    for (int64_t v = 0; v < V; ++v)
+        first[v + 1] += first[v];
+    for (int64_t i = 0; i < n_inst; ++i) {
+        int64_t v = inst_variant[i];
+        list[first[v] + fill[v]] = i;
+        fill[v] += 1;
+    }
+#pragma omp parallel for schedule(dynamic, 4096)
+    for (int64_t q = 0; q < N; ++q) {
+        int32_t v = out_variant[q];
+        if (out_tier[q] == 1)
+            out_worker[q] = literal
+                ? least_loaded_active_worker(n_inst, inst_variant, inst_worker, inst_load, inst_state, NULL, 0, v)
+                : least_loaded_active_worker(n_inst, inst_variant, inst_worker, inst_load, inst_state,
+                                             list + first[v], first[v + 1] - first[v], v);
+        else if (out_tier[q] == 2)
+            out_worker[q] = least_utilised_worker(W, worker_hw, worker_util, variant_hw[v]);
+        else
+            out_worker[q] = -1;
+    }
+    free(state); free(first); free(fill); free(list);
+    return 0;
+}
+
+/* Instance state report: inst_state[idx[i]] = value[i], array order, invalid entries skipped. */
+void oracle_update_instance_state(int64_t n_inst, int32_t *inst_state, int64_t n,
+                                  const int32_t *inst_idx, const int32_t *new_state)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t j = inst_idx[i];
+        if (j < 0 || j >= n_inst)
+            continue;
+        if (new_state[i] != STATE_ACTIVE && new_state[i] != STATE_OVERLOADED && new_state[i] != STATE_INTERFERED)
+            continue;
+        inst_state[j] = new_state[i];
+    }
+}
+
+/*
  * Scaling decision on a change in query load (Section 4.2.2, "scaling up"; cost function and
  * constraints of the integer program of Section 4.2.1; instance counts and costs as in the
  * worked example of Section 2.2, Tables 2 and 3).

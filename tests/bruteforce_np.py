@@ -195,3 +195,46 @@ def workers_np(variant, tier, variant_hw, worker_hw, worker_util, inst_variant, 
             if cand.size:
                 out[q] = cand[np.lexsort((cand, worker_util[cand]))[0]]
     return out
+
+
+def instances_np(task_id, acc_bp, lat_us, cost, queue_us, load_us, variant_hw, worker_hw, worker_util,
+                 inst_variant, inst_worker, inst_load, inst_state, q_task, q_slo, q_min_acc, q_bidx):
+    """Case I with the state kept per running instance, written out per query and per variant: a
+    variant with an Active instance (code 1) competes in the first step and is served by the Active
+    instance with the smallest (load, worker); a variant that runs nowhere competes in the second
+    step and is served by the least-utilised worker of its hardware; any other variant is skipped.
+    Returns (variant, tier, worker)."""
+    lat_us = np.asarray(lat_us, dtype=np.int64)
+    cost = np.asarray(cost, dtype=np.int64)
+    V, B = lat_us.shape
+    inst_variant = np.asarray(inst_variant, dtype=np.int64)
+    inst_state = np.asarray(inst_state, dtype=np.int64)
+    out = np.full(len(q_task), -1, dtype=np.int32)
+    tier = np.zeros(len(q_task), dtype=np.int32)
+    worker = np.full(len(q_task), -1, dtype=np.int32)
+    for q in range(len(q_task)):
+        b = int(q_bidx[q])
+        if not 0 <= b < B:
+            continue
+        best1 = best2 = None
+        for v in range(V):
+            if int(task_id[v]) != int(q_task[q]) or int(acc_bp[v]) < int(q_min_acc[q]):
+                continue
+            mine = np.flatnonzero(inst_variant == v)
+            serving = [int(i) for i in mine if inst_state[i] == 1]
+            if serving:
+                if int(lat_us[v, b]) + int(queue_us[v]) <= int(q_slo[q]):
+                    key = (int(cost[v, b]), int(lat_us[v, b]), v)
+                    if best1 is None or key < best1[0]:
+                        best1 = (key, min((int(inst_load[i]), int(inst_worker[i])) for i in serving)[1])
+            elif mine.size == 0:
+                if int(load_us[v]) + int(lat_us[v, b]) <= int(q_slo[q]):
+                    key = (int(load_us[v]) + int(lat_us[v, b]), int(lat_us[v, b]), v)
+                    if best2 is None or key < best2[0]:
+                        cand = [(int(worker_util[w]), w) for w in range(len(worker_hw)) if int(worker_hw[w]) == int(variant_hw[v])]
+                        best2 = (key, min(cand)[1] if cand else -1)
+        if best1 is not None:
+            out[q], tier[q], worker[q] = best1[0][2], 1, best1[1]
+        elif best2 is not None:
+            out[q], tier[q], worker[q] = best2[0][2], 2, best2[1]
+    return out, tier, worker

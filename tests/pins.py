@@ -9,7 +9,8 @@ import os
 import numpy as np
 
 import workloads
-from bruteforce_np import case1_np, closest_key_np, closest_np, count_np, select_np, tiered_np, workers_np
+from bruteforce_np import (case1_np, closest_key_np, closest_np, count_np, instances_np, select_np, tiered_np,
+                           workers_np)
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 I32MAX = 2**31 - 1
@@ -707,6 +708,123 @@ WORKER_PINS = [
     pin_workers_policy,
     pin_workers_structure,
     pin_worker_reports,
+]
+
+
+# ---- state per running instance (Section 4: the state machine is kept per variant instance) --------
+
+def _both_instances(o, *args):
+    a = o.select_instances(*args)
+    b = o.select_instances(*args, literal=True)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y), "grouped and literal oracle disagree"
+    return a
+
+
+def pin_instances_numpy(o):
+    """Tiny tables and clusters with ties everywhere and all three instance states against the numpy
+    enumerator, which never forms a state per variant."""
+    rng = np.random.default_rng(23)
+    for trial in range(40):
+        V = int(rng.integers(1, 33)); T = int(rng.integers(1, 5)); B = int(rng.integers(1, 4))
+        span = int(rng.choice([2, 3, 5, 50]))
+        tab, qry = _tiny_random(rng, V, T, B, 200, span)
+        load = rng.integers(0, span, V).astype(np.int32)
+        vhw, whw, util, iv, iw, il = _tiny_cluster(rng, V, span)
+        ist = rng.choice([1, 2, 3], iv.size, p=[0.5, 0.3, 0.2]).astype(np.int32)
+        got = _both_instances(o, *tab, load, vhw, whw, util, iv, iw, il, ist, *qry)
+        want = instances_np(*tab, load, vhw, whw, util, iv, iw, il, ist, *qry)
+        for g, w, name in zip(got, want, ("variant", "tier", "worker")):
+            assert np.array_equal(g, w), f"trial {trial}: {name}"
+
+
+def pin_instances_reduction(o):
+    """Against the worker selection with a state per variant, which is pinned on its own: the same
+    answers when that routine is given the states derived here by numpy and only the Active
+    instances; and, with every instance Active, when it is given all of them."""
+    tb = workloads.make_table(0); st = workloads.make_states(0, tb.V); wk = workloads.make_workers(0, st)
+    q = workloads.make_queries(0, n=6000)
+    rng = np.random.default_rng(5)
+    ist = rng.choice([1, 2, 3], wk.I, p=[0.6, 0.25, 0.15]).astype(np.int32)
+    table = (tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us)
+    queries = (q.task, q.slo_us, q.min_acc_bp, q.batch_idx)
+    got = _both_instances(o, *table, st.load_us, wk.variant_hw, wk.worker_hw, wk.worker_util, wk.inst_variant,
+                          wk.inst_worker, wk.inst_load, ist, *queries)
+    running = np.bincount(wk.inst_variant, minlength=tb.V)
+    serving = np.bincount(wk.inst_variant[ist == 1], minlength=tb.V)
+    crowded = np.bincount(wk.inst_variant[ist == 2], minlength=tb.V)
+    state = np.where(running == 0, 0, np.where(serving > 0, 1, np.where(crowded > 0, 2, 3))).astype(np.int32)
+    assert np.array_equal(o.derive_states(tb.V, wk.inst_variant, ist), state)
+    assert all((state == c).sum() > 3 for c in (0, 1, 2, 3))
+    keep = ist == 1
+    want = o.select_workers(*table, state, st.load_us, wk.variant_hw, wk.worker_hw, wk.worker_util,
+                            wk.inst_variant[keep], wk.inst_worker[keep], wk.inst_load[keep], *queries)
+    for g, w in zip(got, want):
+        assert np.array_equal(g, w)
+    assert (got[1] == 1).sum() > 300 and (got[1] == 2).sum() > 300
+    ones = np.ones(wk.I, np.int32)
+    got = _both_instances(o, *table, st.load_us, wk.variant_hw, wk.worker_hw, wk.worker_util, wk.inst_variant,
+                          wk.inst_worker, wk.inst_load, ones, *queries)
+    want = o.select_workers(*table, np.minimum(running, 1).astype(np.int32), st.load_us, wk.variant_hw, wk.worker_hw,
+                            wk.worker_util, wk.inst_variant, wk.inst_worker, wk.inst_load, *queries)
+    for g, w in zip(got, want):
+        assert np.array_equal(g, w)
+
+
+def pin_instances_policy(o):
+    """Hand-built cases: one task, rows 0..3 of rising accuracy and cost; hardware 0 for all; workers
+    0..3 with utilisation 40, 10, 30, 20."""
+    task = np.zeros(4, np.int32); acc = np.array([7000, 8000, 9000, 9500], np.int32)
+    lat = np.array([[10], [10], [10], [10]], np.int32); cost = np.array([[1], [2], [3], [4]], np.int32)
+    queue = np.zeros(4, np.int32); load = np.array([5, 5, 5, 5], np.int32)
+    vhw = np.zeros(4, np.int32); whw = np.zeros(4, np.int32); util = np.array([40, 10, 30, 20], np.int32)
+
+    def run(min_acc, iv, iw, il, ist, slo=1000):
+        r = _both_instances(o, task, acc, lat, cost, queue, load, vhw, whw, util, np.array(iv, np.int32),
+                            np.array(iw, np.int32), np.array(il, np.int32), np.array(ist, np.int32),
+                            [0], [slo], [min_acc], [0])
+        return tuple(int(x[0]) for x in r)
+
+    # row 0 runs on workers 0 (load 1, Overloaded) and 2 (load 9, Active): selected, served by worker 2
+    assert run(7000, [0, 0], [0, 2], [1, 9], [2, 1]) == (0, 1, 2)
+    assert run(7000, [0, 0], [0, 2], [1, 9], [3, 1]) == (0, 1, 2)          # the same with an Interfered instance
+    assert run(7000, [0, 0], [0, 2], [1, 9], [1, 1]) == (0, 1, 0)          # both Active: the smaller load
+    assert run(7000, [0, 0, 0], [3, 2, 1], [4, 4, 4], [1, 1, 2]) == (0, 1, 2)   # equal loads: the lower Active worker
+    # row 0's instances are all Overloaded / Interfered: it is not selected at all; rows 1..3 run
+    # nowhere, so the second step takes row 1 and the least-utilised worker (1)
+    assert run(7000, [0, 0], [0, 2], [1, 9], [2, 3]) == (1, 2, 1)
+    assert run(7000, [0], [0], [1], [3]) == (1, 2, 1)
+    # ... and when row 0 is the only row accurate enough for nothing else to match: no variant
+    assert run(7000, [0, 1, 2, 3], [0, 1, 2, 3], [0, 0, 0, 0], [2, 3, 2, 3]) == (-1, 0, -1)
+    # an Active instance of a dearer row beats an idle cheaper row (first step before second)
+    assert run(7000, [2], [3], [7], [1]) == (2, 1, 3)
+    # a row that runs somewhere is never taken in the second step, whatever the states
+    assert run(9200, [3], [0], [0], [2]) == (-1, 0, -1)
+    assert run(9200, [2], [0], [0], [2]) == (3, 2, 1)
+    # the Active tier needs lat + queue <= slo, the second one load + lat <= slo
+    assert run(7000, [0], [1], [0], [1], slo=12) == (0, 1, 1)
+    assert run(8000, [0], [1], [0], [1], slo=12) == (-1, 0, -1)
+    # states outside Active / Overloaded / Interfered are rejected: a loaded instance is not Inactive
+    for bad in (0, 4, -1):
+        try:
+            run(7000, [0], [0], [0], [bad])
+        except ValueError:
+            continue
+        raise AssertionError("instance state accepted")
+
+
+def pin_instance_reports(o):
+    ist = np.array([1, 1, 2, 3], np.int32)
+    o.update_instance_state(ist, [0, 1, 1, 4, -1, 2, 3, 3], [2, 3, 1, 1, 1, 0, 4, 1])
+    assert ist.tolist() == [2, 1, 2, 1]     # entry 1: 3 then 1; code 0 and code 4 skipped; indices 4, -1 skipped
+    assert o.derive_states(5, [0, 0, 2, 3, 3, 4], [2, 1, 3, 3, 2, 1]).tolist() == [1, 0, 3, 2, 1]
+
+
+INSTANCE_PINS = [
+    pin_instances_numpy,
+    pin_instances_reduction,
+    pin_instances_policy,
+    pin_instance_reports,
 ]
 
 

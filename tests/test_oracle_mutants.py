@@ -207,6 +207,49 @@ def test_worker_mutant_is_caught(tmp_path, source_text, name, find, repl):
     assert caught, f"no pin notices the planted mistake '{name}'"
 
 
+# planted mistakes in the selection with a state per running instance
+INSTANCE_MUTANTS = [
+    ("inst_variant_active_only_if_all_are", "else if (active[v] > 0)", "else if (active[v] == running[v])"),
+    ("inst_overloaded_counts_as_active", "active[v] += inst_state[i] == STATE_ACTIVE;", "active[v] += inst_state[i] != STATE_INTERFERED;"),
+    ("inst_busy_variant_taken_for_inactive", "if (running[v] == 0)\n            out_state[v] = STATE_INACTIVE;",
+     "if (active[v] == 0)\n            out_state[v] = STATE_INACTIVE;"),
+    ("inst_avoided_states_swapped", "out_state[v] = overloaded[v] > 0 ? STATE_OVERLOADED : STATE_INTERFERED;",
+     "out_state[v] = overloaded[v] > 0 ? STATE_INTERFERED : STATE_OVERLOADED;"),
+    ("inst_worker_ignores_the_state", "if (inst_variant[i] != variant || inst_state[i] != STATE_ACTIVE)", "if (inst_variant[i] != variant)"),
+    ("inst_worker_may_be_overloaded", "if (inst_variant[i] != variant || inst_state[i] != STATE_ACTIVE)",
+     "if (inst_variant[i] != variant || inst_state[i] == STATE_INTERFERED)"),
+    ("inst_second_step_worker_from_instances",
+     "out_worker[q] = least_utilised_worker(W, worker_hw, worker_util, variant_hw[v]);\n        else\n            out_worker[q] = -1;\n    }\n    free(state);",
+     "out_worker[q] = least_loaded_active_worker(n_inst, inst_variant, inst_worker, inst_load, inst_state, NULL, 0, v);\n        else\n            out_worker[q] = -1;\n    }\n    free(state);"),
+    ("inst_list_off_by_one", "inst_state,\n                                             list + first[v], first[v + 1] - first[v], v);",
+     "inst_state,\n                                             list + first[v], first[v + 1] - first[v] - 1, v);"),
+    ("inst_select_accepts_any_code",
+     "if (inst_state[i] != STATE_ACTIVE && inst_state[i] != STATE_OVERLOADED && inst_state[i] != STATE_INTERFERED)\n            return -1;",
+     "if (0)\n            return -1;"),
+    ("inst_report_accepts_any_code",
+     "if (new_state[i] != STATE_ACTIVE && new_state[i] != STATE_OVERLOADED && new_state[i] != STATE_INTERFERED)\n            continue;",
+     ""),
+    ("inst_report_out_of_order", "for (int64_t i = 0; i < n; ++i) {\n        int64_t j = inst_idx[i];\n        if (j < 0 || j >= n_inst)\n            continue;\n        if (new_state",
+     "for (int64_t i = n - 1; i >= 0; --i) {\n        int64_t j = inst_idx[i];\n        if (j < 0 || j >= n_inst)\n            continue;\n        if (new_state"),
+]
+
+
+@pytest.mark.parametrize("name,find,repl", INSTANCE_MUTANTS, ids=[m[0] for m in INSTANCE_MUTANTS])
+def test_instance_mutant_is_caught(tmp_path, source_text, name, find, repl):
+    assert find in source_text, f"mutant {name}: pattern not in the oracle source any more"
+    src = tmp_path / f"{name}.c"
+    src.write_text(source_text.replace(find, repl))
+    lib = oracle.build_oracle(src=str(src), out=str(tmp_path / f"lib{name}.so"), force=True)
+    mutant = oracle.Oracle(lib)
+    caught = []
+    for pin in pins.INSTANCE_PINS:
+        try:
+            pin(mutant)
+        except (AssertionError, ValueError):
+            caught.append(pin.__name__)
+    assert caught, f"no pin notices the planted mistake '{name}'"
+
+
 # planted mistakes in the scaling decision
 SCALING_MUTANTS = [
     ("scale_headroom_ignored", "int64_t need = (int64_t)r_load_qps[r] * (int64_t)slack_pct;", "int64_t need = (int64_t)r_load_qps[r] * 100;"),

@@ -31,6 +31,11 @@ def test_worker_pin(oracle_lib, pin):
     pin(oracle_lib)
 
 
+@pytest.mark.parametrize("pin", pins.INSTANCE_PINS, ids=lambda f: f.__name__)
+def test_instance_pin(oracle_lib, pin):
+    pin(oracle_lib)
+
+
 @pytest.mark.parametrize("pin", pins.SCALING_PINS, ids=lambda f: f.__name__)
 def test_scaling_pin(oracle_lib, pin):
     pin(oracle_lib)
