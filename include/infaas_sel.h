@@ -299,6 +299,35 @@ int infaas_sel_update_workers(infaas_sel_t *h, int32_t n, const int32_t *d_worke
                               const int32_t *d_inst_load, void *hip_stream);
 
 /*
+ * State per running instance.  Section 4 keeps the state machine per variant INSTANCE (the
+ * monitoring daemon of the worker that runs it maintains it): a loaded instance is Active,
+ * Overloaded or Interfered, a variant that runs nowhere is Inactive.  With instance states the
+ * state of a variant is no longer given but follows from its instances: Inactive without any,
+ * Active when at least one instance is Active, else Overloaded when some instance is, else
+ * Interfered; and the worker of an Active variant is the least-loaded one among those that run
+ * an ACTIVE instance of it -- an Overloaded or Interfered instance is avoided while another
+ * instance of the same variant serves.  Everything else is as above.
+ *   inst_state  [num_instances]  HOST: INFAAS_SEL_STATE_ACTIVE, _OVERLOADED or _INTERFERED, for the
+ *                                instances in the order they were passed to infaas_sel_load_workers
+ * Synchronous; the states of the variants are replaced by the derived ones.  From here on
+ * infaas_sel_update_state is refused (INVALID_ARG): a variant's state changes through its
+ * instances.  A later infaas_sel_load_workers drops the instance states (the variants keep the
+ * states they had at that moment).
+ * Errors: INVALID_ARG, NOT_LOADED (no workers loaded), OUT_OF_RANGE, HIP, OOM.
+ */
+int infaas_sel_load_instance_states(infaas_sel_t *h, const int32_t *inst_state);
+
+/*
+ * Instance state report: the state of instance d_inst_idx[i] becomes d_state[i], i < n.  DEVICE
+ * arrays; the indices must be distinct; an entry whose index is outside the table or whose code is
+ * not Active, Overloaded or Interfered is skipped.  Enqueues on hip_stream and returns: the
+ * report, the states of all variants derived anew, and the rebuild of both tiers' indexes.
+ * Errors: INVALID_ARG, NOT_LOADED (no instance states loaded), HIP.
+ */
+int infaas_sel_update_instance_states(infaas_sel_t *h, int32_t n, const int32_t *d_inst_idx,
+                                      const int32_t *d_state, void *hip_stream);
+
+/*
  * infaas_sel_select_tiered plus the worker: arrays as there, and
  *   d_out_worker  [N]  DEVICE: the worker that serves d_out_variant, or -1 (no variant, or no
  *                      worker for it, see above)
@@ -398,7 +427,8 @@ enum {
     INFAAS_SEL_K_GROUP_BIN = 14, /* grouped index: queries binned by group of tasks */
     INFAAS_SEL_K_GROUP_LOOKUP = 15,/* grouped index: lookup, one group's bodies in LDS per workgroup */
     INFAAS_SEL_K_GROUP_FINISH = 16,/* grouped index: answers back into query order */
-    INFAAS_SEL_K_COUNT = 17
+    INFAAS_SEL_K_INSTANCE_STATES = 17,/* instance state report and the variants' states derived from it */
+    INFAAS_SEL_K_COUNT = 18
 };
 typedef struct {
     int64_t launches[INFAAS_SEL_K_COUNT];

@@ -22,7 +22,7 @@ ENGINE_INDEX = 2
 KERNEL_NAMES = ("update_load", "histogram", "plan", "scatter", "scan_lds", "scan_wide",
                 "finish_wide", "index_build", "index_select", "update_state", "worker_report",
                 "worker_tables", "step_workers", "scale", "group_bin", "group_lookup",
-                "group_finish")
+                "group_finish", "instance_states")
 _K_COUNT = len(KERNEL_NAMES)
 
 _I32P = ctypes.POINTER(ctypes.c_int32)
@@ -65,7 +65,8 @@ EXPORTED = ("infaas_sel_create", "infaas_sel_load_variants", "infaas_sel_update_
             "infaas_sel_select", "infaas_sel_select_noalloc", "infaas_sel_select_closest", "infaas_sel_load_states",
             "infaas_sel_update_state", "infaas_sel_select_tiered", "infaas_sel_select_tiered_closest",
             "infaas_sel_load_workers",
-            "infaas_sel_update_workers", "infaas_sel_select_workers", "infaas_sel_load_scaling",
+            "infaas_sel_update_workers", "infaas_sel_load_instance_states", "infaas_sel_update_instance_states",
+            "infaas_sel_select_workers", "infaas_sel_load_scaling",
             "infaas_sel_scale", "infaas_sel_destroy", "infaas_sel_reserve",
             "infaas_sel_read_load", "infaas_sel_set_timing", "infaas_sel_get_timings",
             "infaas_sel_get_info", "infaas_sel_strerror", "infaas_sel_last_error")
@@ -104,6 +105,8 @@ def load_library() -> ctypes.CDLL:
     lib.infaas_sel_select_tiered_closest.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.infaas_sel_load_workers.argtypes = [vp, ctypes.c_int32, _I32P, _I32P, _I32P, ctypes.c_int32, _I32P, _I32P, _I32P]
     lib.infaas_sel_update_workers.argtypes = [vp, ctypes.c_int32, vp, vp, ctypes.c_int32, vp, vp, vp]
+    lib.infaas_sel_load_instance_states.argtypes = [vp, _I32P]
+    lib.infaas_sel_update_instance_states.argtypes = [vp, ctypes.c_int32, vp, vp, vp]
     lib.infaas_sel_select_workers.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.infaas_sel_load_scaling.argtypes = [vp, _I32P, _I32P, _I32P, _I32P, ctypes.c_int32, ctypes.c_int32]
     lib.infaas_sel_scale.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -269,6 +272,18 @@ class Selector:
             _dev_ptr(d_worker_util, n, "d_worker_util") if n else None,
             m, _dev_ptr(d_inst_idx, m, "d_inst_idx") if m else None,
             _dev_ptr(d_inst_load, m, "d_inst_load") if m else None, _stream_ptr(stream)))
+
+    def load_instance_states(self, inst_state) -> None:
+        """Host array [I]: the state of every running instance, in the order of load_workers."""
+        inst_state = _host_i32(inst_state)
+        assert inst_state.ndim == 1
+        _check(self._lib.infaas_sel_load_instance_states(self._h, inst_state.ctypes.data_as(_I32P)))
+
+    def update_instance_states(self, d_inst_idx, d_state, stream=None, n: Optional[int] = None) -> None:
+        n = int(d_inst_idx.numel()) if n is None else int(n)
+        _check(self._lib.infaas_sel_update_instance_states(
+            self._h, n, _dev_ptr(d_inst_idx, n, "d_inst_idx"), _dev_ptr(d_state, n, "d_state"),
+            _stream_ptr(stream)))
 
     def select_workers(self, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, d_out_tier,
                        d_out_worker, stream=None, n: Optional[int] = None) -> None:

@@ -120,6 +120,7 @@ struct infaas_sel {
     WorkerView wv{};
     std::vector<void *> worker_mem;              // the device arrays wv points into
     bool workers_loaded = false, workers_dirty = false;
+    bool instance_states = false;                // the variants' states follow from their instances' (wv.inst_state)
     bool steps_stale = false;                    // this table's ix.step_worker is older than its index or the workers
 
     // staircase index
@@ -213,7 +214,7 @@ void infaas_sel::drop_inactive()
     for (void *p : worker_mem) (void)hipFree(p);
     worker_mem.clear();
     wv = WorkerView{};
-    workers_loaded = workers_dirty = false;
+    workers_loaded = workers_dirty = instance_states = false;
     (void)hipFree(ix.step_worker); (void)hipFree(ix.hot_worker);
     ix.step_worker = nullptr;
     ix.hot_worker = nullptr;
@@ -933,6 +934,7 @@ int infaas_sel_update_state(infaas_sel_t *h, int32_t n, const int32_t *d_variant
 {
     if (!h || n < 0) return INFAAS_SEL_ERR_INVALID_ARG;
     if (!h->loaded || !h->inactive) return INFAAS_SEL_ERR_NOT_LOADED;
+    if (h->instance_states) return INFAAS_SEL_ERR_INVALID_ARG;   // a variant's state follows from its instances now
     if (n == 0) return INFAAS_SEL_OK;
     if (!d_variant_idx || !d_state) return INFAAS_SEL_ERR_INVALID_ARG;
     DeviceGuard g(h->device);
@@ -1140,6 +1142,7 @@ int infaas_sel_load_workers(infaas_sel_t *h, int32_t num_workers, const int32_t 
     for (void *p : h->worker_mem) (void)hipFree(p);
     h->worker_mem.clear();
     h->workers_loaded = false;
+    h->instance_states = false;
     bool ok = true;
     auto upload = [&](const std::vector<int32_t> &src, size_t count) -> int32_t * {
         int32_t *d = nullptr;
@@ -1205,6 +1208,80 @@ int infaas_sel_update_workers(infaas_sel_t *h, int32_t n, const int32_t *d_worke
         return INFAAS_SEL_ERR_HIP;
     h->workers_dirty = true;
     return INFAAS_SEL_OK;
+}
+
+namespace {
+
+// The variants' states derived anew from the instances', applied to both tiers' tables, both indexes
+// rebuilt behind it (as after a state report).
+int apply_instance_states(infaas_sel *h, hipStream_t st)
+{
+    {
+        LaunchTimer t(h, INFAAS_SEL_K_INSTANCE_STATES, st);
+        if (!HIP_OK(launch_derive_states(h->wv, st, t.ev()))) return INFAAS_SEL_ERR_HIP;
+    }
+    for (infaas_sel *t : {h, h->inactive}) {
+        {
+            LaunchTimer tm(t, INFAAS_SEL_K_UPDATE_STATE, st);
+            if (!HIP_OK(launch_update_state(t->tv, h->V, nullptr, h->wv.derived, &t->ix, st, tm.ev())))
+                return INFAAS_SEL_ERR_HIP;
+        }
+        t->steps_stale = true;
+        LaunchTimer tm(t, INFAAS_SEL_K_INDEX_BUILD, st);
+        if (!HIP_OK(launch_index_build(t->tv, t->ix, st, tm.ev()))) return INFAAS_SEL_ERR_HIP;
+    }
+    h->workers_dirty = true;
+    return INFAAS_SEL_OK;
+}
+
+}  // namespace
+
+int infaas_sel_load_instance_states(infaas_sel_t *h, const int32_t *inst_state)
+{
+    if (!h) return INFAAS_SEL_ERR_INVALID_ARG;
+    if (!h->loaded || !h->inactive || !h->workers_loaded) return INFAAS_SEL_ERR_NOT_LOADED;
+    const int32_t I = h->wv.I;
+    if (I > 0 && !inst_state) return INFAAS_SEL_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < I; ++i)
+        if (inst_state[i] < INFAAS_SEL_STATE_ACTIVE || inst_state[i] > INFAAS_SEL_STATE_INTERFERED) return INFAAS_SEL_ERR_OUT_OF_RANGE;
+    DeviceGuard g(h->device);
+    if (!g.ok) return INFAAS_SEL_ERR_HIP;
+    if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
+    // in the order the instances are kept in: grouped by variant
+    std::vector<int32_t> pos((size_t)I), grouped((size_t)I);
+    if (I > 0 && !HIP_OK(hipMemcpy(pos.data(), h->wv.inst_pos, (size_t)I * 4, hipMemcpyDeviceToHost))) return INFAAS_SEL_ERR_HIP;
+    for (int32_t i = 0; i < I; ++i) grouped[(size_t)pos[(size_t)i]] = inst_state[i];
+    if (!h->wv.inst_state) {
+        int32_t *d_st = nullptr, *d_der = nullptr;
+        if (dev_alloc(&d_st, (size_t)std::max(I, 1)) != hipSuccess || dev_alloc(&d_der, (size_t)std::max(h->V, 1)) != hipSuccess) {
+            (void)hipFree(d_st); (void)hipFree(d_der); (void)hipGetLastError();
+            return INFAAS_SEL_ERR_OOM;
+        }
+        h->worker_mem.push_back(d_st); h->worker_mem.push_back(d_der);
+        h->wv.inst_state = d_st; h->wv.derived = d_der;
+    }
+    if (I > 0 && !HIP_OK(hipMemcpy(h->wv.inst_state, grouped.data(), (size_t)I * 4, hipMemcpyHostToDevice))) return INFAAS_SEL_ERR_HIP;
+    h->instance_states = true;
+    int rc = apply_instance_states(h, nullptr);
+    if (rc == INFAAS_SEL_OK && !HIP_OK(hipDeviceSynchronize())) rc = INFAAS_SEL_ERR_HIP;
+    return rc;
+}
+
+int infaas_sel_update_instance_states(infaas_sel_t *h, int32_t n, const int32_t *d_inst_idx, const int32_t *d_state,
+                                      void *hip_stream)
+{
+    if (!h || n < 0) return INFAAS_SEL_ERR_INVALID_ARG;
+    if (!h->loaded || !h->inactive || !h->workers_loaded || !h->instance_states) return INFAAS_SEL_ERR_NOT_LOADED;
+    if (n == 0) return INFAAS_SEL_OK;
+    if (!d_inst_idx || !d_state) return INFAAS_SEL_ERR_INVALID_ARG;
+    DeviceGuard g(h->device);
+    if (!g.ok) return INFAAS_SEL_ERR_HIP;
+    hipStream_t st = (hipStream_t)hip_stream;
+    {
+        LaunchTimer t(h, INFAAS_SEL_K_INSTANCE_STATES, st);
+        if (!HIP_OK(launch_instance_state_report(h->wv, n, d_inst_idx, d_state, st, t.ev()))) return INFAAS_SEL_ERR_HIP;
+    }
+    return apply_instance_states(h, st);
 }
 
 int infaas_sel_select_noalloc(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,

@@ -254,6 +254,8 @@ struct WorkerView {
     const int32_t *inst_off;      // [V + 1] instances grouped by variant (caller row) ...
     const int32_t *inst_worker;   // [I]     ... their workers
     int32_t *inst_load;           // [I]     ... their loads
+    int32_t *inst_state;          // [I]     ... their states (Active, Overloaded, Interfered), or null: all Active
+    int32_t *derived;             // [V] with instance states: the state of every variant as its instances give it
     const int32_t *inst_pos;      // [I] caller's instance number -> position in the grouped arrays
     int32_t *best_cls;            // [H] least-utilised worker of every class
     int32_t *row_worker;          // [2 V] worker by caller row: for an Active answer, then for an Inactive one
@@ -262,6 +264,13 @@ struct WorkerView {
 hipError_t launch_worker_report(const WorkerView &wv, int32_t n, const int32_t *worker_idx, const int32_t *util,
                                 int32_t m, const int32_t *inst_idx, const int32_t *load, hipStream_t st,
                                 const LaunchEvents *ev = nullptr);
+// Instance state report: the state of instance inst_idx[i] = state[i]; entries outside the table or with a
+// code that is not Active, Overloaded or Interfered are skipped.
+hipError_t launch_instance_state_report(const WorkerView &wv, int32_t n, const int32_t *inst_idx, const int32_t *state,
+                                        hipStream_t st, const LaunchEvents *ev = nullptr);
+// wv.derived from wv.inst_state: Inactive without instances, Active with an Active one, else Overloaded if
+// some instance is, else Interfered.
+hipError_t launch_derive_states(const WorkerView &wv, hipStream_t st, const LaunchEvents *ev = nullptr);
 // best_cls, then row_worker, from the current utilisations and loads (in this order).
 hipError_t launch_best_per_class(const WorkerView &wv, hipStream_t st, const LaunchEvents *ev = nullptr);
 hipError_t launch_worker_tables(const WorkerView &wv, hipStream_t st, const LaunchEvents *ev = nullptr);

@@ -32,6 +32,33 @@ __global__ __launch_bounds__(kThreads) void k_worker_report(WorkerView wv, int32
     }
 }
 
+// State of instance inst_idx[i] = state[i]; a loaded instance is Active (1), Overloaded (2) or Interfered (3).
+__global__ __launch_bounds__(kThreads) void k_instance_state_report(WorkerView wv, int32_t n, const int32_t *__restrict__ inst_idx,
+                                                                   const int32_t *__restrict__ state)
+{
+    const int32_t i = (int32_t)(blockIdx.x * kThreads + threadIdx.x);
+    if (i >= n) return;
+    const int32_t j = inst_idx[i], c = state[i];
+    if ((uint32_t)j < (uint32_t)wv.I && c >= 1 && c <= 3) wv.inst_state[wv.inst_pos[j]] = c;
+}
+
+// One lane per variant: its state as its instances give it (Section 4 keeps the state machine per
+// variant instance): Inactive when it runs nowhere, Active when some instance is, else Overloaded when
+// some instance is, else Interfered.
+__global__ __launch_bounds__(kThreads) void k_derive_states(WorkerView wv)
+{
+    const int32_t v = (int32_t)(blockIdx.x * kThreads + threadIdx.x);
+    if (v >= wv.V) return;
+    const int32_t lo = wv.inst_off[v], hi = wv.inst_off[v + 1];
+    bool active = false, overloaded = false;
+    for (int32_t i = lo; i < hi; ++i) {
+        const int32_t c = wv.inst_state[i];
+        active = active || c == 1;
+        overloaded = overloaded || c == 2;
+    }
+    wv.derived[v] = hi == lo ? 0 : (active ? 1 : (overloaded ? 2 : 3));
+}
+
 __device__ __forceinline__ uint64_t wave_min_u64(uint64_t v)
 {
 #pragma unroll
@@ -64,14 +91,15 @@ __global__ __launch_bounds__(kThreads) void k_best_per_class(WorkerView wv)
     }
 }
 
-// One lane per variant: the worker of its instance with the smallest (load, worker), and the best
-// worker of its hardware class.
+// One lane per variant: the worker of its instance with the smallest (load, worker) -- of its Active
+// instances, when the instances carry states -- and the best worker of its hardware class.
 __global__ __launch_bounds__(kThreads) void k_worker_tables(WorkerView wv)
 {
     const int32_t v = (int32_t)(blockIdx.x * kThreads + threadIdx.x);
     if (v >= wv.V) return;
     uint64_t best = ~0ull;
     for (int32_t i = wv.inst_off[v]; i < wv.inst_off[v + 1]; ++i) {
+        if (wv.inst_state && wv.inst_state[i] != 1) continue;
         const uint64_t key = ((uint64_t)(uint32_t)wv.inst_load[i] << 32) | (uint32_t)wv.inst_worker[i];
         best = key < best ? key : best;
     }
@@ -123,6 +151,20 @@ hipError_t launch_worker_report(const WorkerView &wv, int32_t n, const int32_t *
     if (total <= 0) return hipSuccess;
     return launch_kernel(ev, k_worker_report, dim3((unsigned)((total + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
                          wv, n, worker_idx, util, m, inst_idx, load);
+}
+
+hipError_t launch_instance_state_report(const WorkerView &wv, int32_t n, const int32_t *inst_idx, const int32_t *state,
+                                        hipStream_t st, const LaunchEvents *ev)
+{
+    if (n <= 0 || !wv.inst_state) return hipSuccess;
+    return launch_kernel(ev, k_instance_state_report, dim3((unsigned)((n + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
+                         wv, n, inst_idx, state);
+}
+
+hipError_t launch_derive_states(const WorkerView &wv, hipStream_t st, const LaunchEvents *ev)
+{
+    if (wv.V <= 0 || !wv.inst_state || !wv.derived) return hipSuccess;
+    return launch_kernel(ev, k_derive_states, dim3((unsigned)((wv.V + kThreads - 1) / kThreads)), dim3(kThreads), 0, st, wv);
 }
 
 hipError_t launch_best_per_class(const WorkerView &wv, hipStream_t st, const LaunchEvents *ev)

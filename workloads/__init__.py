@@ -24,6 +24,8 @@ from .configs import (  # noqa: F401
     WorkerUpdate,
     make_workers,
     make_worker_update,
+    make_instance_states,
+    make_instance_state_update,
     ScalingProfile,
     ScaleRequests,
     make_scaling,

@@ -379,6 +379,30 @@ def make_worker_update(cfg: int, W: int, I: int, chunk: int, fraction: float = 0
                         inst_idx=iidx.astype(np.int32), inst_load=load.astype(np.int32))
 
 
+def make_instance_states(cfg: int, I: int, seed: Optional[int] = None) -> np.ndarray:
+    """State of every running instance (the paper publishes no population): Active, Overloaded,
+    Interfered with probabilities (0.80, 0.12, 0.08), so that of the variants with 1 + Poisson(1)
+    instances about one in eight has no Active instance left.  Seed: _SEED0 + cfg + 19000."""
+    if seed is None:
+        seed = _SEED0 + cfg + 19000
+    rng = np.random.default_rng(np.random.PCG64(seed))
+    return rng.choice(np.array([1, 2, 3], dtype=np.int32), size=I, p=(0.80, 0.12, 0.08)).astype(np.int32)
+
+
+def make_instance_state_update(cfg: int, I: int, chunk: int, fraction: float = 0.05,
+                               seed: Optional[int] = None):
+    """Report before chunk ``chunk``: ``fraction`` of the instances, chosen without replacement,
+    get a new state from the distribution of make_instance_states.  Returns (inst_idx, state).
+    Seed: _SEED0 + cfg + 21000 + chunk."""
+    if seed is None:
+        seed = _SEED0 + cfg + 21000 + chunk
+    rng = np.random.default_rng(np.random.PCG64(seed))
+    n = int(round(I * fraction))
+    idx = rng.choice(I, size=n, replace=False) if n else np.zeros(0, dtype=np.int64)
+    val = rng.choice(np.array([1, 2, 3], dtype=np.int32), size=n, p=(0.80, 0.12, 0.08))
+    return idx.astype(np.int32), val.astype(np.int32)
+
+
 @dataclass
 class ScalingProfile:
     """What the scaling decision of Section 4.2 reads per variant, besides the latency profile."""
