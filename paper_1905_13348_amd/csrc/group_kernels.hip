@@ -60,10 +60,11 @@ __global__ __launch_bounds__(kGrpThreads) void k_group_bin(TableView tv, IndexVi
         for (int i = tid; i < gs.stat_blocks * kLookupStats; i += kGrpThreads) ix.stats[i] = 0u;
     const int32_t acc_base_m1 = tv.acc_base - 1;
     const bool aligned = ((((uintptr_t)q.task) | ((uintptr_t)q.slo) | ((uintptr_t)q.min_acc) | ((uintptr_t)q.bidx)) & 15u) == 0;
+    // (barriers that order LDS traffic only: the previous tile's stores stay in flight across them)
     for (int32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        __syncthreads();   // tables ready; the previous tile's offsets have been read
+        lds_barrier();   // tables ready; the previous tile's offsets have been read
         for (int i = tid; i < kGrpWaves * G1; i += kGrpThreads) l_cnt[i] = 0u;
-        __syncthreads();
+        lds_barrier();
         const int64_t tile_base = (int64_t)tile * kTile;
         uint32_t w0[4 * kTileRounds], w1[4 * kTileRounds], gr[4 * kTileRounds];   // record words; group | rank << 8
 #pragma unroll
@@ -98,20 +99,20 @@ __global__ __launch_bounds__(kGrpThreads) void k_group_bin(TableView tv, IndexVi
                 gr[4 * r + e] = g | (rank << 8);
             }
         }
-        __syncthreads();
+        lds_barrier();
         if (tid < G1) {   // records per group
             uint32_t t = 0;
             for (int w = 0; w < kGrpWaves; ++w) t += l_cnt[w * G1 + tid];
             l_sum[tid] += t;
             l_tot[tid + 1] = t;
         }
-        __syncthreads();
+        lds_barrier();
         if (tid == 0) {   // exclusive prefix over the groups (at most 121 of them); entry G1: all records
             uint32_t run = 0;
             for (int g = 0; g < G1; ++g) { const uint32_t t = l_tot[g + 1]; l_tot[g] = run; run += t; }
             l_tot[G1] = run;
         }
-        __syncthreads();
+        lds_barrier();
         for (int i = tid; i < kGrpWaves * G1; i += kGrpThreads) {   // where (wavefront, group) starts in the tile
             const int w = i / G1, g = i - w * G1;
             uint32_t at = l_tot[g];
@@ -122,7 +123,7 @@ __global__ __launch_bounds__(kGrpThreads) void k_group_bin(TableView tv, IndexVi
             const uint32_t start = l_tot[tid], len = l_tot[tid + 1] - start;
             gs.desc[(int64_t)tile * G1 + tid] = start | (len << 15);
         }
-        __syncthreads();
+        lds_barrier();
 #pragma unroll
         for (int r = 0; r < kTileRounds; ++r) {
             const int64_t i0 = tile_base + (int64_t)r * (4 * kGrpThreads) + tid * 4;
@@ -383,17 +384,27 @@ __global__ __launch_bounds__(kGrpThreads) void k_group_finish(TableView tv, Inde
     if (tid < kLookupStats) l_st[tid] = 0u;
     if (blockIdx.x == 0 && tid <= (int)ix.num_groups) gs.gcount[tid] = 0u;   // for the next call's binning
     const bool aligned = (((uintptr_t)q.out) & 15u) == 0;
+    // The barriers order LDS traffic only, so a tile's stores, and the loads of the next tile's answers,
+    // stay in flight across them.
+    constexpr int kResRounds = kTile / (4 * kGrpThreads);
+    v4i nxt[kResRounds];   // the answers of the tile that comes next, in binned order
+    if ((int32_t)blockIdx.x < ntiles) {
+#pragma unroll
+        for (int r = 0; r < kResRounds; ++r)
+            nxt[r] = *(const v4i *)(gs.res + (int64_t)blockIdx.x * kTile + r * 4 * kGrpThreads + tid * 4);
+    }
     for (int32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t tile_base = (int64_t)tile * kTile;
-        __syncthreads();   // the previous tile's answers have been read
+        lds_barrier();   // the previous tile's answers have been read
 #pragma unroll
-        for (int r = 0; r < kTile / (4 * kGrpThreads); ++r)
-            *(v4i *)&l_res[r * 4 * kGrpThreads + tid * 4] = *(const v4i *)(gs.res + tile_base + r * 4 * kGrpThreads + tid * 4);
-        __syncthreads();
+        for (int r = 0; r < kResRounds; ++r) *(v4i *)&l_res[r * 4 * kGrpThreads + tid * 4] = nxt[r];
+        // where each query's answer is (requested before the barrier, used behind it)
+        uint32_t pos_all[kTileRounds][4];
 #pragma unroll
         for (int r = 0; r < kTileRounds; ++r) {
             const int64_t i0 = tile_base + (int64_t)r * (4 * kGrpThreads) + tid * 4;
-            uint32_t pos[4] = {0u, 0u, 0u, 0u};
+            uint32_t *pos = pos_all[r];
+            pos[0] = pos[1] = pos[2] = pos[3] = 0u;
             if (i0 + 4 <= q.n) {
                 const uint2 p = *(const uint2 *)(gs.perm + i0);
                 pos[0] = p.x & 0xFFFFu; pos[1] = p.x >> 16; pos[2] = p.y & 0xFFFFu; pos[3] = p.y >> 16;
@@ -402,6 +413,17 @@ __global__ __launch_bounds__(kGrpThreads) void k_group_finish(TableView tv, Inde
                 for (int e = 0; e < 4; ++e)
                     if (i0 + e < q.n) pos[e] = gs.perm[i0 + e];
             }
+        }
+        lds_barrier();
+        if (tile + (int32_t)gridDim.x < ntiles) {
+#pragma unroll
+            for (int r = 0; r < kResRounds; ++r)
+                nxt[r] = *(const v4i *)(gs.res + (int64_t)(tile + (int32_t)gridDim.x) * kTile + r * 4 * kGrpThreads + tid * 4);
+        }
+#pragma unroll
+        for (int r = 0; r < kTileRounds; ++r) {
+            const int64_t i0 = tile_base + (int64_t)r * (4 * kGrpThreads) + tid * 4;
+            const uint32_t *pos = pos_all[r];
             int32_t a[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) a[e] = i0 + e < q.n ? l_res[pos[e] & (kTile - 1)] : -1;

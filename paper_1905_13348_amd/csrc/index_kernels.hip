@@ -39,14 +39,6 @@ __device__ __forceinline__ void wave_sync()
 }
 
 
-// Workgroup barrier that orders LDS traffic only: what the wavefronts have written to LDS is visible
-// to each other behind it, while their requests to global memory stay in flight (__syncthreads also
-// waits for those -- for an atomic on a contended word, microseconds).
-__device__ __forceinline__ void lds_barrier()
-{
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
 // Body of steps [g0, g0 + kb), held one per lane (lanes g0..g0+kb-1), in two parts: what can be
 // computed before the body's place in the pool is known, and the stores.
 struct BodyRegs {

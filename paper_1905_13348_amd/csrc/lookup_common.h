@@ -17,6 +17,15 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask)
 
 #define INFAAS_LDS __attribute__((address_space(3)))
 
+// Workgroup barrier that orders LDS traffic only: what the wavefronts have written to LDS is visible
+// to each other behind it, while their requests to global memory stay in flight (__syncthreads also
+// waits for those -- for an atomic on a contended word, microseconds).
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+
 // Readers of index memory by 32-bit byte address: an LDS address, or an offset from a global base.
 struct LdsMem {
     __device__ __forceinline__ uint32_t ld32(uint32_t a, uint32_t imm) const { return *(const INFAAS_LDS uint32_t *)(a + imm); }
