@@ -177,8 +177,10 @@ int infaas_sel_select_noalloc(infaas_sel_t *h, int64_t N,
  *   d_out_variant  [N]  as infaas_sel_select
  *   d_out_closest  [N]  d_out_variant where that is not -1, else the suggestion; -1 only when
  *                       the task has no variants (task or batch index outside the table included)
- * Both DEVICE memory.  Needs the staircase index: a handle created with
- * INFAAS_SEL_ENGINE_SCAN, or whose table is too large for the index, gets INVALID_ARG.
+ * Both DEVICE memory.  On a handle without the staircase index (INFAAS_SEL_ENGINE_SCAN, or a
+ * table too large for the index) the suggestions come from an exhaustive pass over the slices
+ * of the queries without a selection, behind the scan engine's selection.  A handle with
+ * variant states gets INVALID_ARG (infaas_sel_select_tiered_closest is the call for it).
  * Otherwise as infaas_sel_select.
  */
 int infaas_sel_select_closest(infaas_sel_t *h, int64_t N,
@@ -428,7 +430,8 @@ enum {
     INFAAS_SEL_K_GROUP_LOOKUP = 15,/* grouped index: lookup, one group's bodies in LDS per workgroup */
     INFAAS_SEL_K_GROUP_FINISH = 16,/* grouped index: answers back into query order */
     INFAAS_SEL_K_INSTANCE_STATES = 17,/* instance state report and the variants' states derived from it */
-    INFAAS_SEL_K_COUNT = 18
+    INFAAS_SEL_K_CLOSEST_SCAN = 18,/* closest-variant suggestions by exhaustive scan (no index) */
+    INFAAS_SEL_K_COUNT = 19
 };
 typedef struct {
     int64_t launches[INFAAS_SEL_K_COUNT];

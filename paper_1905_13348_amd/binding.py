@@ -22,7 +22,7 @@ ENGINE_INDEX = 2
 KERNEL_NAMES = ("update_load", "histogram", "plan", "scatter", "scan_lds", "scan_wide",
                 "finish_wide", "index_build", "index_select", "update_state", "worker_report",
                 "worker_tables", "step_workers", "scale", "group_bin", "group_lookup",
-                "group_finish", "instance_states")
+                "group_finish", "instance_states", "closest_scan")
 _K_COUNT = len(KERNEL_NAMES)
 
 _I32P = ctypes.POINTER(ctypes.c_int32)

@@ -962,9 +962,9 @@ int select_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t
 {
     if (!h || N < 0) return INFAAS_SEL_ERR_INVALID_ARG;
     if (!h->loaded) return INFAAS_SEL_ERR_NOT_LOADED;
-    if (closest && (!h->have_index || h->inactive)) {
+    if (closest && h->inactive) {
         snprintf(g_last_error, sizeof(g_last_error),
-                 "infaas_sel_select_closest needs the staircase index and a handle without variant states");
+                 "infaas_sel_select_closest needs a handle without variant states (with states: infaas_sel_select_tiered_closest)");
         return INFAAS_SEL_ERR_INVALID_ARG;
     }
     if (N == 0) return INFAAS_SEL_OK;
@@ -974,7 +974,9 @@ int select_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     hipStream_t st = (hipStream_t)hip_stream;
     // (with variant states only the index honours them: its columns are masked, the scan's are not)
-    const bool idx = closest || h->inactive != nullptr || use_index(h);
+    // (the suggestion comes from the index whenever there is one; without one, from an exhaustive scan behind
+    // the scan engine's selection)
+    const bool idx = (closest && h->have_index) || h->inactive != nullptr || use_index(h);
     const bool groups = idx && !closest && !h->inactive && use_groups(h, std::min(N, kMaxPass));
     int rc = groups ? ensure_group_scratch(h, std::min(N, kMaxPass)) : idx ? INFAAS_SEL_OK : ensure_scratch(h, std::min(N, kMaxPass));
     if (rc != INFAAS_SEL_OK) return rc;
@@ -987,6 +989,10 @@ int select_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t
         q.pass = closest ? 1 : 0;
         rc = groups && q.n >= kGroupMinQueries ? group_pass(h, q, st) : idx ? index_pass(h, q, st) : scan_pass(h, q, st);
         if (rc != INFAAS_SEL_OK) return rc;
+        if (closest && !idx) {
+            LaunchTimer t(h, INFAAS_SEL_K_CLOSEST_SCAN, st);
+            if (!HIP_OK(launch_closest_scan(h->tv, q, h->num_cus, st, t.ev()))) return INFAAS_SEL_ERR_HIP;
+        }
     }
     h->last_stats = idx ? h->ix.stats : nullptr;
     return INFAAS_SEL_OK;

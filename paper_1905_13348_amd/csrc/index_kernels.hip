@@ -1155,28 +1155,8 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                     rest &= rest - 1;
                     const int32_t t = __builtin_amdgcn_readlane(task, l), b = __builtin_amdgcn_readlane(bidx, l);
                     const int64_t am = __builtin_amdgcn_readlane(min_acc, l), bound = __builtin_amdgcn_readlane(slo, l);
-                    const int32_t seg = tv.seg_off[t], L = tv.seg_len[t];
-                    const int64_t col = (int64_t)b * tv.Vp + seg;
-                    // per lane the best of its entries by (missed, overshoot, shortfall), earlier rank first
-                    int32_t b_missed = 3, b_pos = 0x7FFFFFFF;
-                    int64_t b_over = 0, b_short = 0;
-                    for (int32_t pos = lane; pos < L; pos += 64) {
-                        const int64_t tt = (int64_t)tv.tot_r[col + pos], a = (int64_t)tv.acc_r[col + pos];
-                        const int64_t over = tt > bound ? tt - bound : 0, shortf = a < am ? am - a : 0;
-                        const int32_t missed = (over > 0) + (shortf > 0);
-                        const bool masked = tv.state != nullptr && tt == 0xFFFFFFFFll;   // a variant of another state
-                        const bool better = !masked && (missed < b_missed || (missed == b_missed && (over < b_over ||
-                                            (over == b_over && shortf < b_short))));
-                        if (better) { b_missed = missed; b_over = over; b_short = shortf; b_pos = pos; }
-                    }
-                    for (int off = 32; off; off >>= 1) {   // then the best of the wavefront
-                        const int32_t o_missed = __shfl_xor(b_missed, off), o_pos = __shfl_xor(b_pos, off);
-                        const int64_t o_over = __shfl_xor(b_over, off), o_short = __shfl_xor(b_short, off);
-                        const bool better = o_missed < b_missed || (o_missed == b_missed && (o_over < b_over ||
-                                            (o_over == b_over && (o_short < b_short || (o_short == b_short && o_pos < b_pos)))));
-                        if (better) { b_missed = o_missed; b_over = o_over; b_short = o_short; b_pos = o_pos; }
-                    }
-                    if (lane == l) sug = b_missed < 3 ? tv.orig_r[col + b_pos] : -1;
+                    const int32_t found = closest_by_scan(tv, t, b, am, bound, lane);
+                    if (lane == l) sug = found;
                 }
             }
             // a table that serves one state keeps the variants of the other states as entries nothing

@@ -210,6 +210,10 @@ hipError_t launch_scan_wide(const TableView &tv, const QueryView &q, const ScanS
                             int num_cus, hipStream_t st, const LaunchEvents *ev = nullptr);
 hipError_t launch_finish_wide(const TableView &tv, const QueryView &q, const ScanScratch &sc,
                               hipStream_t st, const LaunchEvents *ev = nullptr);
+// q.closest from q.out: the selection where there is one, else the closest variant of the query's slice by an
+// exhaustive scan (handles without the staircase index).
+hipError_t launch_closest_scan(const TableView &tv, const QueryView &q, int num_cus, hipStream_t st,
+                               const LaunchEvents *ev = nullptr);
 
 // Kernel launchers (staircase index).
 hipError_t launch_index_build(const TableView &tv, const IndexView &ix, hipStream_t st, const LaunchEvents *ev = nullptr);

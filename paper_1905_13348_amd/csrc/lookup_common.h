@@ -83,6 +83,37 @@ __device__ __forceinline__ void search_bodies(const Mem &mem, int nit, const uin
     }
 }
 
+// The closest variant of slice (t, b) for a query that nothing satisfies, by the whole wavefront over
+// the whole slice in rank order: first by (requirements missed, latency beyond `bound`, accuracy
+// below `am`), the earlier rank at a tie.  Entries of a table that serves one state which belong to
+// variants of other states (latency key all ones) are passed over.  Returns the caller's row, the
+// same in every lane, or -1 when the slice has no entry to offer.
+__device__ __forceinline__ int32_t closest_by_scan(const TableView &tv, int32_t t, int32_t b, int64_t am, int64_t bound, int lane)
+{
+    const int32_t seg = tv.seg_off[t], L = tv.seg_len[t];
+    const int64_t col = (int64_t)b * tv.Vp + seg;
+    // per lane the best of its entries, earlier rank first
+    int32_t b_missed = 3, b_pos = 0x7FFFFFFF;
+    int64_t b_over = 0, b_short = 0;
+    for (int32_t pos = lane; pos < L; pos += 64) {
+        const int64_t tt = (int64_t)tv.tot_r[col + pos], a = (int64_t)tv.acc_r[col + pos];
+        const int64_t over = tt > bound ? tt - bound : 0, shortf = a < am ? am - a : 0;
+        const int32_t missed = (over > 0) + (shortf > 0);
+        const bool masked = tv.state != nullptr && tt == 0xFFFFFFFFll;   // a variant of another state
+        const bool better = !masked && (missed < b_missed || (missed == b_missed && (over < b_over ||
+                            (over == b_over && shortf < b_short))));
+        if (better) { b_missed = missed; b_over = over; b_short = shortf; b_pos = pos; }
+    }
+    for (int off = 32; off; off >>= 1) {   // then the best of the wavefront
+        const int32_t o_missed = __shfl_xor(b_missed, off), o_pos = __shfl_xor(b_pos, off);
+        const int64_t o_over = __shfl_xor(b_over, off), o_short = __shfl_xor(b_short, off);
+        const bool better = o_missed < b_missed || (o_missed == b_missed && (o_over < b_over ||
+                            (o_over == b_over && (o_short < b_short || (o_short == b_short && o_pos < b_pos)))));
+        if (better) { b_missed = o_missed; b_over = o_over; b_short = o_short; b_pos = o_pos; }
+    }
+    return b_missed < 3 ? tv.orig_r[col + b_pos] : -1;
+}
+
 // Accuracy bound in key space: keys are acc - acc_base + 1 >= 1, so the bound is
 // min_acc - acc_base + 1 limited to [1, 65536] (65536 is above every key).
 __device__ __forceinline__ uint32_t acc_threshold(int32_t min_acc, int32_t acc_base_m1)

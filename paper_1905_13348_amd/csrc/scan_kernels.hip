@@ -13,6 +13,7 @@
 // its rank inside its slice, computed once when the table is loaded, so the argmin runs on
 // 32-bit integers and its result is unique.
 #include "internal.h"
+#include "lookup_common.h"
 
 namespace infaas {
 
@@ -423,6 +424,35 @@ __global__ __launch_bounds__(256) void k_finish_wide(TableView tv, QueryView q, 
     }
 }
 
+// The closest-variant suggestion (Section 4.1, last step of Case I) for a handle without the
+// staircase index: q.out holds the selection already; q.closest becomes the selection where there is
+// one, else the variant of the query's slice that comes closest, found by the whole wavefront, one
+// such query at a time.  Exhaustive like the engine it belongs to.
+__global__ __launch_bounds__(256) void k_closest_scan(TableView tv, QueryView q)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6, nwaves = (int64_t)gridDim.x * 4;
+    for (int64_t base = wave * 64; base < q.n; base += nwaves * 64) {
+        const int64_t i = base + lane;
+        const bool in = i < q.n;
+        const int32_t sel = in ? q.out[i] : 0;
+        const int32_t task = in ? q.task[i] : -1, bidx = in ? q.bidx[i] : -1;
+        const int32_t slo = in ? q.slo[i] : 0, min_acc = in ? q.min_acc[i] : 0;
+        const bool inside = in && (uint32_t)task < (uint32_t)tv.T && (uint32_t)bidx < (uint32_t)tv.B;
+        int32_t sug = sel;   // (a query outside the table has no selection and gets no suggestion)
+        uint64_t rest = __ballot(inside && sel < 0);
+        while (rest) {
+            const int l = __builtin_ctzll(rest);
+            rest &= rest - 1;
+            const int32_t t = __builtin_amdgcn_readlane(task, l), b = __builtin_amdgcn_readlane(bidx, l);
+            const int64_t am = __builtin_amdgcn_readlane(min_acc, l), bound = __builtin_amdgcn_readlane(slo, l);
+            const int32_t found = closest_by_scan(tv, t, b, am, bound, lane);
+            if (lane == l) sug = found;
+        }
+        if (in) q.closest[i] = sug;
+    }
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------- launchers
@@ -516,6 +546,13 @@ hipError_t launch_finish_wide(const TableView &tv, const QueryView &q, const Sca
     if (blocks > 4096) blocks = 4096;
     if (blocks < 1) blocks = 1;
     return launch_kernel(ev, k_finish_wide, dim3((unsigned)blocks), dim3(256), 0, st, tv, q, sc);
+}
+
+hipError_t launch_closest_scan(const TableView &tv, const QueryView &q, int num_cus, hipStream_t st, const LaunchEvents *ev)
+{
+    if (q.n <= 0) return hipSuccess;
+    const int64_t want = ((int64_t)q.n + 255) / 256, most = (int64_t)num_cus * 8;
+    return launch_kernel(ev, k_closest_scan, dim3((unsigned)(want < most ? want : most)), dim3(256), 0, st, tv, q);
 }
 
 }  // namespace infaas

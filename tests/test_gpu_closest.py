@@ -10,8 +10,8 @@ from test_gpu_parity import _random_queries, _random_table, _staircase_queries, 
 
 pytestmark = pytest.mark.gpu
 
-ENGINES = [0, 2]          # auto and index; the scan engine has no closest-variant mode
-ENGINE_IDS = ["auto", "index"]
+ENGINES = [0, 1, 2]       # auto, scan (suggestions by an exhaustive pass behind the selection), index
+ENGINE_IDS = ["auto", "scan", "index"]
 
 
 def _compare(oracle_lib, tb, queries, engine, label, queue=None, sel=None):
@@ -144,12 +144,20 @@ def test_closest_config2_every_query(oracle_lib):
     sel.destroy()
 
 
-def test_closest_needs_the_index():
-    import paper_1905_13348_amd as lib
+def test_closest_without_the_index_on_a_wide_slice(oracle_lib):
+    """A handle of the scan engine whose largest slice takes the device-wide path of the selection:
+    the suggestions still come from the exhaustive pass; unaligned arrays and a ragged count."""
     import torch
-    tb = workloads.make_table(0)
-    sel = make_selector(tb, engine=1)
-    z = torch.zeros(4, dtype=torch.int32, device="cuda")
-    with pytest.raises(lib.InfaasSelError):
-        sel.select_closest(z, z, z, z, z.clone(), z.clone())
+    rng = np.random.default_rng(91)
+    tb = _random_table(rng, 3, np.array([9000, 40, 700]), 2)
+    qs = _random_queries(rng, 3, 2, 50_001)
+    sel = make_selector(tb, engine=1, lds_segment_limit=4096)
+    want_sel, want_clo = oracle_lib.select_closest(*table_args(tb), *qs)
+    dev = [torch.from_numpy(np.concatenate([[0], x]).astype(np.int32)).cuda()[1:] for x in qs]
+    out = torch.full((len(qs[0]) + 1,), -9, dtype=torch.int32, device="cuda")[1:]
+    clo = torch.full((len(qs[0]) + 1,), -9, dtype=torch.int32, device="cuda")[1:]
+    sel.select_closest(*dev, out, clo)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), want_sel) and np.array_equal(clo.cpu().numpy(), want_clo)
+    assert (want_sel < 0).sum() > 1000
     sel.destroy()
