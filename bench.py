@@ -94,6 +94,12 @@ def bench_scale(args, cfg, spec, tb) -> int:
            for r in host]
     out_sets = [[torch.empty(n, dtype=torch.int32, device="cuda") for _ in range(3)] for _ in range(n_sets)]
     done = 0
+    t_heat = time.perf_counter()
+    while args.preheat_ms > 0 and 1e3 * (time.perf_counter() - t_heat) < args.preheat_ms:
+        for _ in range(16):
+            sel.scale(*dev[done % n_sets], *out_sets[done % n_sets])
+            done += 1
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         sel.scale(*dev[done % n_sets], *out_sets[done % n_sets])
         done += 1
@@ -169,6 +175,9 @@ def main() -> int:
     # default warm-up is long enough to time the steady state)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=400)
+    ap.add_argument("--preheat-ms", type=float, default=30.0,
+                    help="before the warm-up steps: the same steps, untimed, for at least this long, so that the "
+                         "steady state is timed whatever --warmup says (0: none)")
     ap.add_argument("--config", type=int, default=2, choices=[0, 1, 2, 3, 4])
     ap.add_argument("--engine", default="auto", choices=["auto", "scan", "index"])
     ap.add_argument("--table", default="config", choices=["config", "long_staircases", "wide_accuracy"],
@@ -315,6 +324,12 @@ def main() -> int:
             sel.select(*dev_q[k], outs[k])
 
     done = 0      # steps enqueued so far (the load reports of the streaming configuration follow it)
+    t_heat = time.perf_counter()
+    while args.preheat_ms > 0 and 1e3 * (time.perf_counter() - t_heat) < args.preheat_ms:
+        for _ in range(16):
+            step(done)
+            done += 1
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step(done)
         done += 1
@@ -460,7 +475,8 @@ def main() -> int:
                                + (f", two-tier selection with worker selection over {cluster.W} workers and "
                                   f"{cluster.I} instances (variant, tier and worker arrays)" if args.workers else ""),
                    "engine": args.engine, "launch": "hip graph replay" if args.graph else "stream",
-                   "timed_region": "library instrumentation off; kernel durations from a second pass of the same steps"},
+                   "timed_region": "library instrumentation off; kernel durations from a second pass of the same steps; "
+                                   f"{args.preheat_ms:g} ms of the same steps before the warm-up steps"},
         "roofline": roofline,
         "whole_step_frac_of_hbm_roofline": round(whole_frac, 5),
         "kernels_ms_per_step": {k: round(v["total_ms"] / args.steps, 5) for k, v in active.items()},
