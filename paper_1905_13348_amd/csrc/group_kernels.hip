@@ -44,7 +44,7 @@ __global__ __launch_bounds__(kGrpThreads) void k_group_bin(TableView tv, IndexVi
                                                            int32_t ntiles)
 {
     extern __shared__ __align__(16) uint32_t lds[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, wave = tid >> 6;
     const int G = (int)ix.num_groups, G1 = G + 1;
     publish_index_stats(tv);
    // group G: queries outside the table (answer -1)
