@@ -583,3 +583,34 @@ def test_512_slices_in_groups(oracle_lib):
         bad = np.flatnonzero(got != want)
         assert bad.size == 0, f"N={n}: {bad.size} mismatches, first at {bad[:5]}"
     sel.destroy()
+
+
+@pytest.mark.parametrize("steps", [1, 2, 30, 31, 32, 33, 61, 62, 63])
+def test_few_long_slices_with_exact_step_counts(oracle_lib, steps):
+    """Slices of 640+ variants (the build with one workgroup per slice, the bodies shared by its four
+    wavefronts) whose staircases have exactly `steps` steps: `steps` variants that are steps by
+    construction and 640 fillers that the first of them dominates, shuffled through the ranks by
+    their cost.  One step, the edges of the first body (31 | 32), of the index (62 | 63)."""
+    rng = np.random.default_rng(400 + steps)
+    T, B, fill = 2, 2, 640
+    n = steps + fill
+    task = np.repeat(np.arange(T, dtype=np.int32), n)
+    i = np.arange(steps, dtype=np.int64)
+    acc1 = np.concatenate([2000 + 10 * i, rng.integers(0, 2000, fill)])              # fillers: less accurate than step 0,
+    lat1 = np.concatenate([200_000 - 1000 * i, rng.integers(200_001, 400_000, fill)])  # slower,
+    cost1 = np.concatenate([1000 + 50 * i, rng.integers(1001, 1000 + 50 * steps + 500, fill)])  # and dearer than it
+    acc = np.tile(acc1, T)
+    lat = np.stack([np.tile(lat1, T) + 3 * b for b in range(B)], axis=1)
+    cost = np.stack([np.tile(cost1, T) + b for b in range(B)], axis=1)
+    tb = _table(T, [1, 2], task, acc, lat, cost, np.zeros(T * n, np.int64))
+    nq = 30_000
+    want_step = rng.integers(-2, steps + 2, nq)
+    qs = (rng.integers(0, T, nq), rng.choice([250_000, 200_000 - 1000 * (steps // 2), 150_000, 199_999], nq) + rng.integers(-1500, 1500, nq),
+          2000 + 10 * want_step - rng.integers(0, 2, nq), rng.integers(0, B, nq))
+    qs = tuple(np.asarray(x, np.int32) for x in qs)
+    for engine in (0, 2):
+        _compare(oracle_lib, tb, qs, engine, label=f"{steps} steps among {n}")
+    sel = make_selector(tb, engine=2)
+    info = sel.info()
+    assert info["index_max_steps"] == min(steps, 62) and info["index_truncated"] == (T * B if steps > 62 else 0)
+    sel.destroy()
