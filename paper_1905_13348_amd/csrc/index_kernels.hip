@@ -677,6 +677,11 @@ __device__ __forceinline__ int32_t closest_step(const Mem &mem, int nit, uint32_
         else if (kind == 2) second = o1.tot < o0.tot;
         else second = o1.tot < o0.tot || (o1.tot == o0.tot && o1.acc > o0.acc);
     }
+    // A table that serves one state keeps the variants of the other states as entries nothing selects
+    // (lowest accuracy key, latency key all ones).  Such an entry can be a step, and it is the closest one
+    // exactly when the slice has no variant of the table's state: then there is nothing to suggest.  (Of
+    // kind 1 the step is within the latency bound, so it is never such an entry.)
+    if (kind != 1 && (second ? o1.tot : o0.tot) == 0xFFFFFFFFu) return -1;
     return second ? (int32_t)(kBodySteps + o1.step) : (int32_t)o0.step;
 }
 
@@ -1159,9 +1164,6 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                     if (lane == l) sug = found;
                 }
             }
-            // a table that serves one state keeps the variants of the other states as entries nothing
-            // selects; such an entry comes out here only when the slice has no variant of the table's state
-            if (tv.state != nullptr && open && sug >= 0 && tv.state[tv.slot_of[sug]] != tv.want_state) sug = -1;
             if (kMode == 7) {
                 // the first tier's suggestion is in q.closest: the closer of the two, by (requirements
                 // missed, latency beyond the bound, accuracy below the bound), the first tier's at a tie
