@@ -252,7 +252,9 @@ int infaas_sel_select_tiered(infaas_sel_t *h, int64_t N,
  *   d_out_closest  [N]  DEVICE: d_out_variant where that is not -1, else the suggestion; -1 only
  *                       when the task has no Active or Inactive variant (task or batch index
  *                       outside the table included)
- * Otherwise as infaas_sel_select_tiered.
+ * Otherwise as infaas_sel_select_tiered; the device memory kept for the queries the Active tier
+ * leaves open is 32 bytes per query of the largest call here (beside each of them goes what the
+ * Active tier suggests and how far that is from the requirements).
  */
 int infaas_sel_select_tiered_closest(infaas_sel_t *h, int64_t N,
                                      const int32_t *d_task, const int32_t *d_slo_us,

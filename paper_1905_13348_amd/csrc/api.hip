@@ -112,6 +112,8 @@ struct infaas_sel {
     int32_t *d_open = nullptr;                   // lists of the queries the Active tier leaves open (grows)
     int32_t *d_open_count = nullptr;             // [workgroups of the lookup kernel]
     int64_t open_queries = 0, open_bytes = 0;    // pass size d_open is good for; its size
+    int64_t open_words = 0;                      // 32-bit words of the lists proper; the side lists, if any, follow them
+    bool open_side = false;
     // scaling decisions
     ScaleView sv{};
     std::vector<void *> scale_mem;               // the device arrays sv points into
@@ -220,7 +222,8 @@ void infaas_sel::drop_inactive()
     ix.hot_worker = nullptr;
     (void)hipFree(d_open); (void)hipFree(d_open_count);
     d_open = d_open_count = nullptr;
-    open_queries = open_bytes = 0;
+    open_queries = open_bytes = open_words = 0;
+    open_side = false;
     if (inactive) infaas_sel_destroy(inactive);
     inactive = nullptr;
     last_stats = nullptr;
@@ -464,28 +467,34 @@ int create_index(infaas_sel *h)
 }
 
 // Lists for the queries that the first tier of a state-aware pass over up to n queries leaves open.
-int ensure_open(infaas_sel *h, int64_t n)
+// side: also the lists of the first tier's suggestions beside them (complete Case I), the same size again.
+int ensure_open(infaas_sel *h, int64_t n, bool side)
 {
-    if (h->d_open && h->open_queries >= n) return INFAAS_SEL_OK;
+    if (h->d_open && h->open_queries >= n && (h->open_side || !side)) return INFAAS_SEL_OK;
+    n = std::max(n, h->open_queries);
+    side = side || h->open_side;
     // growing: nothing enqueued earlier may still use the old lists
     if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
     (void)hipFree(h->d_open);
     h->d_open = nullptr;
     h->open_queries = h->open_bytes = 0;
     const int blocks = index_select_blocks(h->num_cus);
+    h->open_side = false;
     const size_t words = (size_t)blocks * (size_t)index_open_cap((int32_t)n, h->num_cus) * 4;
     if (!h->d_open_count && dev_alloc(&h->d_open_count, (size_t)blocks) != hipSuccess) return INFAAS_SEL_ERR_OOM;
-    if (dev_alloc(&h->d_open, words) != hipSuccess) return INFAAS_SEL_ERR_OOM;
+    if (dev_alloc(&h->d_open, words * (side ? 2 : 1)) != hipSuccess) return INFAAS_SEL_ERR_OOM;
     h->open_queries = n;
-    h->open_bytes = (int64_t)words * 4;
+    h->open_words = (int64_t)words;
+    h->open_side = side;
+    h->open_bytes = (int64_t)words * 4 * (side ? 2 : 1);
     return INFAAS_SEL_OK;
 }
 
 // One pass of the index engine over n <= 2^28 queries.
-int index_pass(infaas_sel *h, const QueryView &q, hipStream_t st, const TableView *first_tier = nullptr)
+int index_pass(infaas_sel *h, const QueryView &q, hipStream_t st)
 {
     LaunchTimer t(h, INFAAS_SEL_K_INDEX_SELECT, st);
-    if (!HIP_OK(launch_index_select(h->tv, h->ix, q, h->d_park, h->index_lds_bytes, h->num_cus, st, t.ev(), first_tier)))
+    if (!HIP_OK(launch_index_select(h->tv, h->ix, q, h->d_park, h->index_lds_bytes, h->num_cus, st, t.ev())))
         return INFAAS_SEL_ERR_HIP;
     return INFAAS_SEL_OK;
 }
@@ -1025,7 +1034,7 @@ int tiered_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     hipStream_t st = (hipStream_t)hip_stream;
-    int rc = ensure_open(h, std::min(N, kMaxTierPass));
+    int rc = ensure_open(h, std::min(N, kMaxTierPass), closest);
     if (rc != INFAAS_SEL_OK) return rc;
     if (workers) {
         // bring the worker of every variant, then of every step of both indexes, up to date
@@ -1058,6 +1067,7 @@ int tiered_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t
         q.task = d_task + done; q.slo = d_slo_us + done; q.min_acc = d_min_acc_bp + done;
         q.bidx = d_batch_idx + done; q.out = d_out_variant + done; q.tier = d_out_tier + done;
         q.open = h->d_open; q.open_count = h->d_open_count;
+        q.open_side = closest ? h->d_open + h->open_words : nullptr;
         q.open_cap = index_open_cap(q.n, h->num_cus);
         if (workers) { q.worker = d_out_worker + done; q.row_worker = h->wv.row_worker; }
         if (closest) q.closest = d_out_closest + done;
@@ -1066,7 +1076,7 @@ int tiered_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t
         if (rc != INFAAS_SEL_OK) return rc;
         if (workers) q.row_worker = h->wv.row_worker + h->V;
         q.pass = workers ? 5 : closest ? 7 : 3;
-        rc = index_pass(h->inactive, q, st, &h->tv);
+        rc = index_pass(h->inactive, q, st);
         if (rc != INFAAS_SEL_OK) return rc;
     }
     h->last_stats = h->inactive->ix.stats;
@@ -1479,7 +1489,7 @@ int infaas_sel_reserve(infaas_sel_t *h, int64_t max_queries)
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     const int64_t cap = std::max<int64_t>(1, std::min(max_queries, kMaxPass));
-    if (h->loaded && h->inactive) return ensure_open(h, std::min(cap, kMaxTierPass));
+    if (h->loaded && h->inactive) return ensure_open(h, std::min(cap, kMaxTierPass), h->open_side);
     if (h->loaded && use_index(h))   // the index engine needs per-query scratch only where it works group by group
         return use_groups(h, cap) ? ensure_group_scratch(h, cap) : INFAAS_SEL_OK;
     return ensure_scratch(h, cap);

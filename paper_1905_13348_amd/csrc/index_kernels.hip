@@ -653,13 +653,32 @@ __device__ __forceinline__ Offer body_offer(const Mem &mem, int nit, uint32_t bo
     return o;
 }
 
-// Closest step of a slice with one or two bodies (re1 = 0: one); returns the step number in the
-// slice, or -1 when the slice has no steps.  body1 follows body0 in memory.
-template <class Mem>
-__device__ __forceinline__ int32_t closest_step(const Mem &mem, int nit, uint32_t body0, uint32_t re0, uint32_t re1,
-                                                uint32_t dd, int32_t slo)
+// Closest step of a slice with one or two bodies (re1 = 0: one): the step number in the slice, or -1
+// when the slice has nothing to suggest, and how far that step is from the requirements (from its keys:
+// no other memory is read).  body1 follows body0 in memory.  min_acc and acc_base_m1 (= accuracy
+// base - 1) turn an accuracy key back into an accuracy.
+struct ClosestStep {
+    int32_t step;
+    HowFar how;
+};
+// A suggestion and its distance as the 16-byte record the first tier of the complete Case I leaves
+// beside every query it lists for the second tier (latency overshoot < 2^33, accuracy shortfall < 2^32).
+__device__ __forceinline__ v4i pack_side(int32_t row, const HowFar &h)
 {
-    if (mem.ld32(body0 + 2u * re0 + 4u, 0u) == 0xFFFFFFFFu) return -1;   // first latency key is the sentinel: no steps
+    return v4i{row, (int32_t)(uint32_t)h.over, (int32_t)(uint32_t)h.shortf,
+               h.missed | (int32_t)((h.over >> 32) & 1) << 2 | (int32_t)((h.shortf >> 32) & 1) << 3};
+}
+__device__ __forceinline__ HowFar unpack_side(const v4i &r)
+{
+    return HowFar{r.w & 3, (int64_t)(uint32_t)r.y | ((int64_t)((r.w >> 2) & 1) << 32),
+                  (int64_t)(uint32_t)r.z | ((int64_t)((r.w >> 3) & 1) << 32)};
+}
+template <class Mem>
+__device__ __forceinline__ ClosestStep closest_step(const Mem &mem, int nit, uint32_t body0, uint32_t re0, uint32_t re1,
+                                                    uint32_t dd, int32_t slo, int32_t min_acc, int32_t acc_base_m1)
+{
+    const ClosestStep none{-1, HowFar{3, 0, 0}};
+    if (mem.ld32(body0 + 2u * re0 + 4u, 0u) == 0xFFFFFFFFu) return none;   // first latency key is the sentinel: no steps
     const uint32_t body1 = body0 + body_bytes(re0);
     const bool lim_ok = slo >= 0;
     uint32_t pa0, ps0, pa1 = 0, ps1 = 0;
@@ -681,8 +700,15 @@ __device__ __forceinline__ int32_t closest_step(const Mem &mem, int nit, uint32_
     // (lowest accuracy key, latency key all ones).  Such an entry can be a step, and it is the closest one
     // exactly when the slice has no variant of the table's state: then there is nothing to suggest.  (Of
     // kind 1 the step is within the latency bound, so it is never such an entry.)
-    if (kind != 1 && (second ? o1.tot : o0.tot) == 0xFFFFFFFFu) return -1;
-    return second ? (int32_t)(kBodySteps + o1.step) : (int32_t)o0.step;
+    const Offer o = second ? o1 : o0;
+    if (kind != 1 && o.tot == 0xFFFFFFFFu) return none;
+    // kind 1: within the latency bound, not accurate enough; 2: accurate enough, too slow; 3: neither
+    ClosestStep c;
+    c.step = second ? (int32_t)(kBodySteps + o.step) : (int32_t)o.step;
+    c.how.missed = kind == 3 ? 2 : 1;
+    c.how.over = kind == 1 ? 0 : (int64_t)o.tot - (int64_t)slo;
+    c.how.shortf = kind == 2 ? 0 : (int64_t)min_acc - ((int64_t)o.acc + (int64_t)acc_base_m1);
+    return c;
 }
 
 // kMode 0: selection.  1: selection plus closest-variant suggestion (q.closest).
@@ -697,10 +723,11 @@ __device__ __forceinline__ int32_t closest_step(const Mem &mem, int nit, uint32_
 // answers that are steps of the index, q.row_worker for answers found by the scan).
 // 6 and 7: as 2 and 3, and q.closest gets the complete Case I: the selected variant, or for a query
 // that neither tier can answer the closest variant of the two tiers (6 writes the first tier's
-// suggestion there, 7 -- which gets the first tier's table as tv2 -- compares it with its own).
+// suggestion, and how far it is from the requirements, beside every record of its lists (q.open_side);
+// 7 compares it with its own).
 template <bool kLds, int kMode>
 __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, IndexView ix, QueryView q,
-                                                              int32_t *__restrict__ park_mem, uint32_t lds_cap, TableView tv2)
+                                                              int32_t *__restrict__ park_mem, uint32_t lds_cap)
 {
     constexpr bool kCase1 = kMode == 6 || kMode == 7;
     constexpr bool kClosest = kMode == 1, kFirst = kMode == 2 || kMode == 4 || kMode == 6;
@@ -1002,7 +1029,10 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         for (int k = 0; k < kPerThread; ++k) {
             const uint64_t mask = __ballot(df[k]);
             if (mask) {   // parked queries are always inside the table
-                if (df[k]) wq[cnt + lanes_below(mask)] = v4i{kSecond ? cur.bi[k] : i0 + qoff(k), cur.sl[k], cur.am[k], (int32_t)sl_of[k]};
+                // (first word: the query; in the last pass of the complete Case I the record's place in the
+                // workgroup's list, where the query and the first tier's suggestion are found)
+                if (df[k]) wq[cnt + lanes_below(mask)] = v4i{kMode == 7 ? cur.unit * kUnit + k * 64 + lane : kSecond ? cur.bi[k] : i0 + qoff(k),
+                                                              cur.sl[k], cur.am[k], (int32_t)sl_of[k]};
                 cnt += (uint32_t)__builtin_popcountll(mask);
                 st_parked += (uint32_t)__builtin_popcountll(mask);
             }
@@ -1035,7 +1065,13 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
         const bool have = (uint32_t)lane < count;
         const int32_t *e = (const int32_t *)(wq + first + (have ? lane : 0));
-        const int32_t qi = __hip_atomic_load(e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        int32_t qi = __hip_atomic_load(e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        v4i side{-1, 0, 0, 3};   // last pass of the complete Case I: what the first tier suggests, and how far that is
+        if (kMode == 7) {
+            const int32_t r = have ? qi : 0;
+            qi = open_in[r].x;
+            side = ((const v4i *)q.open_side + (int64_t)blockIdx.x * q.open_cap)[r];
+        }
         const int32_t slo = __hip_atomic_load(e + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         const int32_t min_acc = __hip_atomic_load(e + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         const int32_t s_ld = __hip_atomic_load(e + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -1124,6 +1160,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         } else if (have && !final_miss) {
             q.out[qi] = ans;
         }
+        uint32_t open_at = 0;   // first tier: where this lane's query went in the workgroup's list
         if (kFirst) {   // the main loop has stored tier 0 for a parked query
             if (have && ans >= 0) {
                 q.tier[qi] = 1;
@@ -1131,8 +1168,8 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             }
             const uint64_t om = __ballot(have && ans < 0);
             if (om) {
-                const uint32_t at = open_room((uint32_t)__builtin_popcountll(om));
-                if (have && ans < 0) open_out[at + lanes_below(om)] = v4i{qi, slo, min_acc, (int32_t)s};
+                open_at = open_room((uint32_t)__builtin_popcountll(om)) + lanes_below(om);
+                if (have && ans < 0) open_out[open_at] = v4i{qi, slo, min_acc, (int32_t)s};
             }
         }
         if (kSuggest) {
@@ -1140,16 +1177,17 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             const bool open = have && ans < 0;
             const bool by_index = open && indexed && !(y & kHdrTrunc);
             int32_t sug = ans;
+            HowFar mine{3, 0, 0};   // how far the suggestion is from the requirements
             const bool in_lds = by_index && resident, in_mem = by_index && !resident;
             if (kLds && __ballot(in_lds)) {
-                const int32_t st = closest_step(lmem, nit, in_lds ? lbody : rebase, in_lds ? keys0 : 2u,
-                                                in_lds ? keys1 : 0u, dd[0], slo);
-                if (in_lds && st >= 0) sug = ix.step_row[rec + (uint32_t)st];
+                const ClosestStep c = closest_step(lmem, nit, in_lds ? lbody : rebase, in_lds ? keys0 : 2u,
+                                                   in_lds ? keys1 : 0u, dd[0], slo, min_acc, acc_base_m1);
+                if (in_lds && c.step >= 0) { sug = ix.step_row[rec + (uint32_t)c.step]; mine = c.how; }
             }
             if (__ballot(in_mem)) {
-                const int32_t st = closest_step(gmem, nit, in_mem ? gbody : 0u, in_mem ? keys0 : 2u,
-                                                in_mem ? keys1 : 0u, dd[0], slo);
-                if (in_mem && st >= 0) sug = ix.step_row[rec + (uint32_t)st];
+                const ClosestStep c = closest_step(gmem, nit, in_mem ? gbody : 0u, in_mem ? keys0 : 2u,
+                                                   in_mem ? keys1 : 0u, dd[0], slo, min_acc, acc_base_m1);
+                if (in_mem && c.step >= 0) { sug = ix.step_row[rec + (uint32_t)c.step]; mine = c.how; }
             }
             // slices without a complete index: the whole slice, in rank order, by the wavefront
             uint64_t rest = __ballot(open && !by_index);
@@ -1160,32 +1198,18 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                     rest &= rest - 1;
                     const int32_t t = __builtin_amdgcn_readlane(task, l), b = __builtin_amdgcn_readlane(bidx, l);
                     const int64_t am = __builtin_amdgcn_readlane(min_acc, l), bound = __builtin_amdgcn_readlane(slo, l);
-                    const int32_t found = closest_by_scan(tv, t, b, am, bound, lane);
-                    if (lane == l) sug = found;
+                    HowFar how;
+                    const int32_t found = closest_by_scan(tv, t, b, am, bound, lane, &how);
+                    if (lane == l) { sug = found; mine = how; }
                 }
             }
+            if (kMode == 6 && open)   // for the second tier: this tier's suggestion and how far it is
+                ((v4i *)q.open_side + (int64_t)blockIdx.x * q.open_cap)[open_at] = pack_side(sug, mine);
             if (kMode == 7) {
-                // the first tier's suggestion is in q.closest: the closer of the two, by (requirements
-                // missed, latency beyond the bound, accuracy below the bound), the first tier's at a tie
-                if (open) {
-                    const int32_t b = (int32_t)(s % (uint32_t)tv.B);
-                    auto far = [&](const TableView &t, int32_t row, int32_t &missed, int64_t &over, int64_t &shortf) {
-                        const int32_t slot = t.slot_of[row];
-                        const int64_t tot = (int64_t)((uint32_t)t.lat[(int64_t)b * t.Vp + slot] + (uint32_t)t.queue[slot]);
-                        const int64_t a = t.acc[slot];
-                        over = tot > (int64_t)slo ? tot - (int64_t)slo : 0;
-                        shortf = a < (int64_t)min_acc ? (int64_t)min_acc - a : 0;
-                        missed = (over > 0) + (shortf > 0);
-                    };
-                    const int32_t first = q.closest[qi];
-                    bool keep_first = first >= 0;
-                    if (first >= 0 && sug >= 0) {
-                        int32_t m1, m2;
-                        int64_t o1, o2, s1, s2;
-                        far(tv2, first, m1, o1, s1);
-                        far(tv, sug, m2, o2, s2);
-                        keep_first = m1 < m2 || (m1 == m2 && (o1 < o2 || (o1 == o2 && s1 <= s2)));
-                    }
+                // the closer of the two tiers' suggestions, by (requirements missed, latency beyond the
+                // bound, accuracy below the bound), the first tier's at a tie; q.closest holds the first tier's
+                if (open && sug >= 0) {
+                    const bool keep_first = side.x >= 0 && closer_or_equal(unpack_side(side), mine);
                     if (!keep_first) q.closest[qi] = sug;
                 }
             } else if (have) {
@@ -1267,10 +1291,8 @@ size_t index_park_bytes(int num_cus)
 }
 
 hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const QueryView &q,
-                               int32_t *park_mem, uint32_t lds_bytes, int num_cus, hipStream_t st, const LaunchEvents *ev,
-                               const TableView *first_tier)
+                               int32_t *park_mem, uint32_t lds_bytes, int num_cus, hipStream_t st, const LaunchEvents *ev)
 {
-    const TableView tv2 = first_tier ? *first_tier : tv;
     const int blocks = index_select_blocks(num_cus);
     if (lds_bytes > 0) {
         const uint32_t fixed = kLdsCtrlBytes + lds_header_bytes(tv.S);
@@ -1289,14 +1311,14 @@ hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const Q
         IndexView ixk = ix;
         if (!hot) ixk.hot_worker = nullptr;
         return launch_kernel(ev, kernel, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), lds_bytes, st, tv, ixk, q,
-                             park_mem, lds_bytes - fixed - hot, tv2);
+                             park_mem, lds_bytes - fixed - hot);
     }
     auto kernel = q.pass == 1 ? k_index_select<false, 1> : q.pass == 2 ? k_index_select<false, 2> :
                   q.pass == 3 ? k_index_select<false, 3> : q.pass == 4 ? k_index_select<false, 4> :
                   q.pass == 5 ? k_index_select<false, 5> : q.pass == 6 ? k_index_select<false, 6> :
                   q.pass == 7 ? k_index_select<false, 7> : k_index_select<false, 0>;
     return launch_kernel(ev, kernel, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), kLdsCtrlBytes, st, tv, ix, q,
-                         park_mem, 0u, tv2);
+                         park_mem, 0u);
 }
 
 }  // namespace infaas

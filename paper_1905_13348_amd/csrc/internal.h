@@ -168,6 +168,10 @@ struct QueryView {
     // the lookup kernel (open_cap records of 16 bytes each), and the number of records in each
     int32_t *open, *open_count;
     int32_t open_cap;
+    // complete Case I: beside every record of those lists, what the first tier suggests for the query and
+    // how far that variant is from the requirements (16 bytes: row or -1, latency beyond the bound, accuracy
+    // below the bound, requirements missed | the 33rd bits), so that the second tier need not look it up
+    int32_t *open_side;
     // worker selection: third result array, and the worker of every caller row for the tier the
     // pass looks at (for answers that do not come from a step of the index)
     int32_t *worker;
@@ -220,10 +224,8 @@ hipError_t launch_index_build(const TableView &tv, const IndexView &ix, hipStrea
 // lds_bytes: dynamic LDS of the lookup kernel when the index is mirrored in LDS, 0 to read it
 // from global memory.  park_mem: index_park_bytes() of device memory (16-byte aligned) for the
 // queues of parked queries; its size does not depend on the number of queries.
-// first_tier: for pass 7 (second tier of the complete Case I), the table of the first tier.
 hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const QueryView &q,
-                               int32_t *park_mem, uint32_t lds_bytes, int num_cus, hipStream_t st, const LaunchEvents *ev = nullptr,
-                               const TableView *first_tier = nullptr);
+                               int32_t *park_mem, uint32_t lds_bytes, int num_cus, hipStream_t st, const LaunchEvents *ev = nullptr);
 int index_select_blocks(int num_cus);
 int32_t index_open_cap(int32_t n, int num_cus);   // records per workgroup of QueryView::open for a pass over n queries
 size_t index_park_bytes(int num_cus);

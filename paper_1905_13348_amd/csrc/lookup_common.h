@@ -87,8 +87,18 @@ __device__ __forceinline__ void search_bodies(const Mem &mem, int nit, const uin
 // the whole slice in rank order: first by (requirements missed, latency beyond `bound`, accuracy
 // below `am`), the earlier rank at a tie.  Entries of a table that serves one state which belong to
 // variants of other states (latency key all ones) are passed over.  Returns the caller's row, the
-// same in every lane, or -1 when the slice has no entry to offer.
-__device__ __forceinline__ int32_t closest_by_scan(const TableView &tv, int32_t t, int32_t b, int64_t am, int64_t bound, int lane)
+// same in every lane, or -1 when the slice has no entry to offer; *how gets its distance.
+struct HowFar {
+    int32_t missed;          // of the two requirements
+    int64_t over, shortf;    // latency beyond the bound, accuracy below the bound (0 when met)
+};
+// (requirements missed, latency beyond the bound, accuracy below the bound): the smaller, the closer
+__device__ __forceinline__ bool closer_or_equal(const HowFar &a, const HowFar &b)
+{
+    return a.missed < b.missed || (a.missed == b.missed && (a.over < b.over || (a.over == b.over && a.shortf <= b.shortf)));
+}
+__device__ __forceinline__ int32_t closest_by_scan(const TableView &tv, int32_t t, int32_t b, int64_t am, int64_t bound, int lane,
+                                                   HowFar *how = nullptr)
 {
     const int32_t seg = tv.seg_off[t], L = tv.seg_len[t];
     const int64_t col = (int64_t)b * tv.Vp + seg;
@@ -111,6 +121,7 @@ __device__ __forceinline__ int32_t closest_by_scan(const TableView &tv, int32_t 
                             (o_over == b_over && (o_short < b_short || (o_short == b_short && o_pos < b_pos)))));
         if (better) { b_missed = o_missed; b_over = o_over; b_short = o_short; b_pos = o_pos; }
     }
+    if (how) { how->missed = b_missed; how->over = b_over; how->shortf = b_short; }
     return b_missed < 3 ? tv.orig_r[col + b_pos] : -1;
 }
 
