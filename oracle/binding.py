@@ -84,6 +84,8 @@ class Oracle:
         lib.oracle_scale.argtypes = ([ctypes.c_int64, ctypes.c_int32] + [_I32P] * 5 + [ctypes.c_int32, ctypes.c_int32]
                                      + [ctypes.c_int64] + [_I32P] * 8)
         lib.oracle_scale.restype = ctypes.c_int
+        lib.oracle_scale_down.argtypes = lib.oracle_scale.argtypes
+        lib.oracle_scale_down.restype = ctypes.c_int
         lib.oracle_update_state.argtypes = [ctypes.c_int64, _I32P, ctypes.c_int64, _I32P, _I32P]
         lib.oracle_update_state.restype = None
         lib.oracle_count_feasible.argtypes = [ctypes.c_int64, ctypes.c_int32, _I32P, _I32P, _I32P,
@@ -284,9 +286,10 @@ class Oracle:
                                                _ptr(inst_idx), _ptr(new_state))
 
     def scale(self, arch_id, sat_qps, hw_cost, load_us, lat_us, lambda_per_s, slack_pct,
-              r_variant, r_instances, r_load_qps, r_slo, r_bidx):
+              r_variant, r_instances, r_load_qps, r_slo, r_bidx, down=False):
         """Scaling decision per request: (action 0 none / 1 replicate / 2 upgrade / 3 impossible,
-        variant to load or -1, instances of it to load)."""
+        variant to load or -1, instances of it to load).  down=True: the scaling-down decision,
+        (action 0 keep / 1 remove / 2 downgrade, variant concerned or -1, instances to unload resp. load)."""
         arch_id, sat_qps, hw_cost, load_us = _i32(arch_id), _i32(sat_qps), _i32(hw_cost), _i32(load_us)
         lat_us = _i32(lat_us)
         V, B = lat_us.shape
@@ -298,13 +301,17 @@ class Oracle:
         for a in (r_instances, r_load_qps, r_slo, r_bidx):
             assert a.shape == (R,)
         action, variant, inst = (np.empty(R, dtype=np.int32) for _ in range(3))
-        rc = self._lib.oracle_scale(V, B, _ptr(arch_id), _ptr(sat_qps), _ptr(hw_cost), _ptr(load_us), _ptr(lat_us),
-                                    int(lambda_per_s), int(slack_pct), R, _ptr(r_variant), _ptr(r_instances),
-                                    _ptr(r_load_qps), _ptr(r_slo), _ptr(r_bidx), _ptr(action), _ptr(variant),
-                                    _ptr(inst))
+        routine = self._lib.oracle_scale_down if down else self._lib.oracle_scale
+        rc = routine(V, B, _ptr(arch_id), _ptr(sat_qps), _ptr(hw_cost), _ptr(load_us), _ptr(lat_us),
+                     int(lambda_per_s), int(slack_pct), R, _ptr(r_variant), _ptr(r_instances),
+                     _ptr(r_load_qps), _ptr(r_slo), _ptr(r_bidx), _ptr(action), _ptr(variant), _ptr(inst))
         if rc != 0:
             raise ValueError("oracle rejected its arguments")
         return action, variant, inst
+
+    def scale_down(self, *args):
+        """Section 4.2.2, scaling down: see scale(..., down=True)."""
+        return self.scale(*args, down=True)
 
     def update_state(self, state: np.ndarray, variant_idx, new_state) -> None:
         """In place: state[variant_idx[i]] = new_state[i], array order."""

@@ -1020,7 +1020,7 @@ void oracle_update_instance_state(int64_t n_inst, int32_t *inst_state, int64_t n
  * count inside 32 bits; likewise lambda <= 1000 per second, slack_pct <= 200 and C <= 2^20);
  * when scaling is needed and neither option is allowed the action code is 3 (the worker has to
  * turn to the controller, step (d) of Section 4.2.2).  Resource limits of the worker
- * (constraint 3) and scaling down are not part of this routine.
+ * (constraint 3) are not part of this routine; scaling down is oracle_scale_down.
  *
  * Outputs per request: action (0 none, 1 replicate, 2 upgrade, 3 needed but impossible), the
  * variant to load (-1 for actions 0 and 3) and the number of its instances to load.
@@ -1093,6 +1093,97 @@ int oracle_scale(int64_t V, int32_t B,
         out_action[r] = best_v == cur ? 1 : 2;
         out_variant[r] = (int32_t)best_v;
         out_instances[r] = (int32_t)best_n;
+    }
+    return 0;
+}
+
+/*
+ * Scaling down (Section 4.2.2, "Scaling down algorithm").
+ *
+ * At regular intervals the selection policy is asked whether the incoming load L of a running
+ * variant cur with n_cur instances can be carried for less: by removing an instance of cur, or by
+ * downgrading to a cheaper variant.  Per request (cur, n_cur, L, S, b):
+ *   remove             unload one instance of cur, allowed when at least one stays and the rest
+ *                      still carries the load with the required headroom,
+ *                      Q[cur] * (n_cur - 1) * 100 >= L * slack_pct  (constraint 1);
+ *   downgrade          switch to a variant u of the same model architecture with a lower hardware
+ *                      cost, C[u] < C[cur], and T_inf[u] <= S (constraint 2 binds every newly loaded
+ *                      instance): load inst(u) = max(1, ceil(L * slack_pct / (100 * Q[u])))
+ *                      instances of u, which carry the load by construction, unload the n_cur of cur;
+ *   keep               otherwise.
+ * The options are compared by the integer program's objective, as in scaling up:
+ *     keep:       0
+ *     remove:     - C[cur]                                       (delta = -1, nothing is loaded)
+ *     downgrade:  C[u] * inst(u) * (1 + lambda * T_load[u])  -  C[cur] * n_cur
+ * and the lowest is taken; only an option that lowers the objective is acted on.
+ *
+ * Readings where the text is silent: one instance is removed per decision; the last instance is
+ * never removed here (unloading a variant altogether is the state machine's business, Section 4);
+ * a downgrade keeps at least one instance serving even when no load arrives; ties go to keeping,
+ * then to removing, then to the lower row among downgrades (no switch without a gain); invalid
+ * requests as in scaling up.  The wait of T_v = T_load[cur] before the action is executed is the
+ * caller's: the decision does not depend on it.
+ *
+ * Outputs per request: action (0 keep, 1 remove, 2 downgrade), the variant concerned (cur for 1,
+ * u for 2, -1 for 0) and the instances of it to unload (1, action 1) or to load (inst(u), action 2).
+ */
+int oracle_scale_down(int64_t V, int32_t B,
+                      const int32_t *arch_id, const int32_t *sat_qps, const int32_t *hw_cost,
+                      const int32_t *load_us, const int32_t *lat_us,
+                      int32_t lambda_per_s, int32_t slack_pct,
+                      int64_t R,
+                      const int32_t *r_variant, const int32_t *r_instances, const int32_t *r_load_qps,
+                      const int32_t *r_slo_us, const int32_t *r_batch_idx,
+                      int32_t *out_action, int32_t *out_variant, int32_t *out_instances)
+{
+    if (V < 0 || B <= 0 || R < 0 || lambda_per_s < 0 || lambda_per_s > 1000 || slack_pct < 0 ||
+        slack_pct > 200)
+        return -1;
+    for (int64_t v = 0; v < V; ++v)
+        if (sat_qps[v] < 1 || hw_cost[v] < 0 || hw_cost[v] > 1048576 || load_us[v] < 0)
+            return -1;
+#pragma omp parallel for schedule(dynamic, 1024)
+    for (int64_t r = 0; r < R; ++r) {
+        int64_t cur = r_variant[r];
+        int32_t b = r_batch_idx[r];
+        out_action[r] = 0;
+        out_variant[r] = -1;
+        out_instances[r] = 0;
+        if (cur < 0 || cur >= V || b < 0 || b >= B || r_instances[r] < 0 || r_load_qps[r] < 0 ||
+            r_instances[r] > 1000000 || r_load_qps[r] > 1000000000)
+            continue;
+        int64_t n_cur = r_instances[r];
+        int64_t need = (int64_t)r_load_qps[r] * (int64_t)slack_pct;        /* hundredths of a query per second */
+        int64_t slo = r_slo_us[r];
+        wide_t lowest = 0;                                                  /* keeping everything */
+        if (n_cur >= 2 && (int64_t)sat_qps[cur] * (n_cur - 1) * 100 >= need) {   /* remove one */
+            wide_t objective = -(wide_t)hw_cost[cur] * 1000000;
+            if (objective < lowest) {
+                lowest = objective;
+                out_action[r] = 1;
+                out_variant[r] = (int32_t)cur;
+                out_instances[r] = 1;
+            }
+        }
+        wide_t unloaded = (wide_t)hw_cost[cur] * n_cur * 1000000;          /* all of cur */
+        for (int64_t u = 0; u < V; ++u) {                                   /* downgrade */
+            if (u == cur || arch_id[u] != arch_id[cur])
+                continue;
+            if ((int64_t)lat_us[u * B + b] > slo || hw_cost[u] >= hw_cost[cur])
+                continue;
+            int64_t per = 100 * (int64_t)sat_qps[u];
+            int64_t inst = (need + per - 1) / per;
+            if (inst < 1)
+                inst = 1;
+            wide_t objective = (wide_t)hw_cost[u] * inst *
+                               ((wide_t)1000000 + (wide_t)lambda_per_s * load_us[u]) - unloaded;
+            if (objective < lowest) {               /* rows ascend: an equal objective keeps the earlier choice */
+                lowest = objective;
+                out_action[r] = 2;
+                out_variant[r] = (int32_t)u;
+                out_instances[r] = (int32_t)inst;
+            }
+        }
     }
     return 0;
 }

@@ -855,7 +855,7 @@ def scale_py(arch_id, sat_qps, hw_cost, load_us, lat_us, lam, slack_pct, r_varia
 
 
 def _scaling_example():
-    names, lat, qps, cost, alone, decide = [], [], [], [], [], []
+    names, lat, qps, cost, alone, decide, down = [], [], [], [], [], [], []
     with open(os.path.join(GOLDEN, "tables_2_3_scaling_example.txt")) as f:
         for line in f:
             p = line.split()
@@ -865,9 +865,11 @@ def _scaling_example():
                 names.append(p[1]); lat.append(int(p[2]) * 1000); qps.append(int(p[3])); cost.append(int(p[4]))
             elif p[0] == "alone":
                 alone.append((int(p[1]), p[2], int(p[3]), int(p[4])))
-            elif p[0] == "decide":
-                decide.append((int(p[1]), int(p[2]) * 1000, p[3], int(p[4]), p[5], p[6], int(p[7])))
-    return names, np.array(lat, np.int32)[:, None], np.array(qps, np.int32), np.array(cost, np.int32), alone, decide
+            elif p[0] in ("decide", "down"):
+                (decide if p[0] == "decide" else down).append(
+                    (int(p[1]), int(p[2]) * 1000, p[3], int(p[4]), p[5], p[6], int(p[7])))
+    return (names, np.array(lat, np.int32)[:, None], np.array(qps, np.int32), np.array(cost, np.int32), alone, decide,
+            down)
 
 
 def pin_scaling_paper_example(o):
@@ -875,7 +877,7 @@ def pin_scaling_paper_example(o):
     registration order of the three variants.  An instance count is read off a replication from
     zero instances; a cost ratio off the decision between two variants."""
     import itertools
-    names, lat, qps, cost, alone, decide = _scaling_example()
+    names, lat, qps, cost, alone, decide, _ = _scaling_example()
     for perm in itertools.permutations(range(3)):
         perm = list(perm)
         row = {names[p]: i for i, p in enumerate(perm)}
@@ -982,8 +984,148 @@ def pin_scaling_closed_forms(o):
     assert one(*tab, 0, 100, [0], [1], [10**9 + 1], [100], [0]) == (0, -1, 0)
 
 
+# ---- scaling down (Section 4.2.2, second algorithm) ---------------------------------------------------
+
+def scale_down_py(arch_id, sat_qps, hw_cost, load_us, lat_us, lam, slack_pct, r_variant, r_instances, r_load,
+                  r_slo, r_bidx):
+    """The scaling-down decision in Python's unbounded integers: every option with its objective
+    (times 1,000,000), the least of them by (objective, keep < remove < downgrade by row)."""
+    V, B = np.asarray(lat_us).shape
+    out = []
+    for cur, n_cur, L, slo, b in zip(*(np.asarray(x).tolist() for x in (r_variant, r_instances, r_load, r_slo, r_bidx))):
+        if not (0 <= cur < V and 0 <= b < B and 0 <= n_cur <= 10**6 and 0 <= L <= 10**9):
+            out.append((0, -1, 0)); continue
+        need = L * slack_pct
+        options = [(0, -2, 0, -1, 0)]   # (objective, order, action, variant, instances)
+        if n_cur - 1 >= 1 and int(sat_qps[cur]) * (n_cur - 1) * 100 >= need:
+            options.append((-int(hw_cost[cur]) * 10**6, -1, 1, cur, 1))
+        for u in range(V):
+            if u == cur or arch_id[u] != arch_id[cur] or int(lat_us[u][b]) > slo or not hw_cost[u] < hw_cost[cur]:
+                continue
+            inst = max(1, -((-need) // (100 * int(sat_qps[u]))))
+            options.append((int(hw_cost[u]) * inst * (10**6 + lam * int(load_us[u])) - int(hw_cost[cur]) * n_cur * 10**6,
+                            u, 2, u, inst))
+        out.append(min(options)[2:])
+    return tuple(np.array(x, dtype=np.int32) for x in zip(*out)) if out else (np.zeros(0, np.int32),) * 3
+
+
+def pin_scale_down_paper_example(o):
+    """The printed example read from the dear side: from one C at 10 QPS the cheapest configurations
+    of Table 3's first two rows (2 x A, resp. 1 x B under 50 ms), in every registration order."""
+    import itertools
+    names, lat, qps, cost, _, _, down = _scaling_example()
+    assert len(down) == 2
+    for perm in itertools.permutations(range(3)):
+        perm = list(perm)
+        row = {names[p]: i for i, p in enumerate(perm)}
+        tab = (np.zeros(3, np.int32), qps[perm], cost[perm], np.zeros(3, np.int32), lat[perm])
+        for load, slo, name, running, action, target, inst in down:
+            a, v, n = o.scale_down(*tab, 0, 100, [row[name]], [running], [load], [slo], [0])
+            assert (a[0], v[0], n[0]) == ({"remove": 1, "downgrade": 2}[action], row[target], inst), (load, slo)
+
+
+def pin_scale_down_python(o):
+    """Random small tables (ties in every field, invalid requests) against the enumerator in Python
+    integers, with several lambdas and headrooms."""
+    rng = np.random.default_rng(23)
+    seen = set()
+    for trial in range(80):
+        V = int(rng.integers(1, 40)); B = int(rng.integers(1, 4))
+        span = int(rng.choice([2, 4, 9, 1000]))
+        arch = rng.integers(0, max(1, V // 6) + 1, V).astype(np.int32)
+        qps = rng.integers(1, span + 1, V).astype(np.int32)
+        cost = rng.integers(0, span + 1, V).astype(np.int32)
+        load = rng.integers(0, 50 * span, V).astype(np.int32)
+        lat = rng.integers(1, span + 1, (V, B)).astype(np.int32)
+        R = 200
+        rv = rng.integers(-1, V + 1, R); rn = rng.integers(-1, 6, R); rl = rng.integers(-1, 6 * span, R)
+        rs = rng.integers(0, span + 2, R); rb = rng.integers(-1, B + 1, R)
+        lam = int(rng.choice([0, 1, 37, 1000])); slack = int(rng.choice([0, 100, 105, 200]))
+        got = o.scale_down(arch, qps, cost, load, lat, lam, slack, rv, rn, rl, rs, rb)
+        want = scale_down_py(arch, qps, cost, load, lat, lam, slack, rv, rn, rl, rs, rb)
+        for g, w in zip(got, want):
+            assert np.array_equal(g, w), f"trial {trial}"
+        seen |= set(want[0].tolist())
+    assert seen == {0, 1, 2}
+
+
+def pin_scale_down_closed_forms(o):
+    """Hand-built cases and limits."""
+    one = lambda *a: tuple(int(x[0]) for x in o.scale_down(*a))
+    arch = np.zeros(3, np.int32); lat = np.array([[10], [10], [10]], np.int32)
+    qps = np.array([40, 10, 10], np.int32); cost = np.array([30, 5, 5], np.int32); load = np.array([0, 0, 0], np.int32)
+    tab = (arch, qps, cost, load, lat)
+    req = lambda n, L, slo=100, cur=0: ([cur], [n], [L], [slo], [0])
+    # 3 x 40 qps at 90 = 3 x 30; 80 qps: two carry it at 100% (remove: -30) but 8 x 5 = 40 - 90 = -50: downgrade, lower row
+    assert one(*tab, 0, 100, *req(3, 80)) == (2, 1, 8)
+    # 120 qps: nothing can go (2 x 40 < 120), 12 x 5 = 60 < 90: downgrade; 121 qps: 13 x 5 = 65
+    assert one(*tab, 0, 100, *req(3, 120)) == (2, 1, 12)
+    assert one(*tab, 0, 100, *req(3, 121)) == (2, 1, 13)
+    # without the cheap rows (other architecture): 80 qps -> remove one; 81 qps -> keep (2 x 40 < 81)
+    solo = (np.array([0, 1, 1], np.int32), qps, cost, load, lat)
+    assert one(*solo, 0, 100, *req(3, 80)) == (1, 0, 1)
+    assert one(*solo, 0, 100, *req(3, 81)) == (0, -1, 0)
+    # headroom: two carry 80 qps at 100% but not at 105%
+    assert one(*solo, 0, 105, *req(3, 80)) == (0, -1, 0)
+    assert one(*solo, 0, 105, *req(3, 76)) == (1, 0, 1)
+    # the last instance stays, also without load; a downgrade keeps one instance serving
+    assert one(*solo, 0, 100, *req(1, 0)) == (0, -1, 0)
+    assert one(*solo, 0, 100, *req(2, 0)) == (1, 0, 1)
+    assert one(*tab, 0, 100, *req(1, 0)) == (2, 1, 1)           # 5 - 30
+    assert one(*tab, 0, 100, *req(0, 0)) == (0, -1, 0)          # nothing runs: nothing to gain
+    # ties: a downgrade that saves exactly what a removal saves loses to it (2 x 30 -> 30 against 6 x 5 = 30)
+    assert one(*tab, 0, 100, *req(2, 40)) == (2, 1, 4)          # 20 - 60 against -30
+    tie = (arch, qps, np.array([30, 10, 10], np.int32), load, lat)
+    assert one(*tie, 0, 100, *req(2, 30)) == (1, 0, 1)          # 3 x 10 - 60 = -30 = -30
+    assert one(*tie, 0, 100, *req(2, 20)) == (2, 1, 2)          # 2 x 10 - 60 = -40
+    # a switch that gains nothing is not made: 6 x 5 = 30 = 1 x 30
+    assert one(*tab, 0, 100, *req(1, 60)) == (0, -1, 0)
+    assert one(*tab, 0, 100, *req(1, 50)) == (2, 1, 5)
+    # cheaper means a lower hardware cost per instance, not a lower total: equal cost is no downgrade
+    same = (arch, np.array([10, 40, 40], np.int32), np.array([30, 30, 29], np.int32), load, lat)
+    assert one(*same, 0, 100, *req(4, 40)) == (2, 2, 1)          # row 1 costs the same per instance: only row 2
+    # lambda: a loading latency of 1 s adds one hardware cost per loaded instance and unit of lambda
+    slow = (arch, qps, cost, np.array([0, 10**6, 3 * 10**6], np.int32), lat)
+    assert one(*slow, 0, 100, *req(3, 120)) == (2, 1, 12)       # 60 - 90
+    assert one(*slow, 1, 100, *req(3, 120)) == (0, -1, 0)       # 120 - 90 > 0 and 240 - 90 > 0
+    assert one(*slow, 1, 100, *req(3, 80)) == (1, 0, 1)         # 80 - 90 = -10 against -30
+    assert one(*slow, 1, 100, *req(3, 40)) == (2, 1, 4)         # 40 - 90 = -50 against -30
+    # the latency objective binds the downgrade's instances, not the ones that stay
+    late = (arch, qps, cost, load, np.array([[300], [200], [10]], np.int32))
+    assert one(*late, 0, 100, *req(3, 80, slo=100)) == (2, 2, 8)
+    assert one(*late, 0, 100, *req(3, 80, slo=5)) == (1, 0, 1)
+    assert one(*late, 0, 100, *req(3, 120, slo=5)) == (0, -1, 0)
+    # the batch-size column of the request
+    two = (arch, qps, cost, load, np.array([[10, 10], [10, 500], [500, 10]], np.int32))
+    assert tuple(int(x[0]) for x in o.scale_down(*two, 0, 100, [0], [3], [120], [100], [1])) == (2, 2, 12)
+    # the largest values do not wrap: 10^9 qps at 200% on a 1 qps variant, lambda 1000, longest loading latency
+    big = (np.zeros(2, np.int32), np.array([2, 1], np.int32), np.array([2**20, 2**20 - 1], np.int32),
+           np.array([I32MAX, I32MAX], np.int32), np.array([[1], [1]], np.int32))
+    assert one(*big, 0, 200, [0], [10**6], [10**9], [1], [0]) == (0, -1, 0)       # 2*10^9 dearer ones against 10^6
+    assert one(*big, 0, 200, [0], [10**6], [10**5], [1], [0]) == (2, 1, 2 * 10**5)
+    assert one(*big, 1000, 200, [0], [10**6], [10**5], [1], [0]) == (1, 0, 1)    # loading makes the switch dearer
+    # an objective of 4.5 * 10^27 whose low 64 bits read as a negative number
+    wrap = (np.zeros(2, np.int32), np.array([2, 1], np.int32), np.array([2**20, 2**20 - 1], np.int32),
+            np.array([0, 2147483641], np.int32), np.array([[1], [1]], np.int32))
+    assert one(*wrap, 1000, 200, [0], [1], [10**9], [1], [0]) == (0, -1, 0)
+    for bad in ((1001, 100), (-1, 100), (0, 201), (0, -1)):
+        try:
+            o.scale_down(*tab, *bad, *req(2, 40))
+        except ValueError:
+            continue
+        raise AssertionError("parameters outside their limits accepted")
+    assert one(*tab, 0, 100, [0], [10**6 + 1], [40], [100], [0]) == (0, -1, 0)
+    assert one(*tab, 0, 100, [0], [3], [10**9 + 1], [100], [0]) == (0, -1, 0)
+
+
 SCALING_PINS = [
     pin_scaling_paper_example,
     pin_scaling_python,
     pin_scaling_closed_forms,
+]
+
+SCALE_DOWN_PINS = [
+    pin_scale_down_paper_example,
+    pin_scale_down_python,
+    pin_scale_down_closed_forms,
 ]

@@ -279,6 +279,51 @@ SCALING_MUTANTS = [
 ]
 
 
+SCALE_DOWN_MUTANTS = [
+    ("down_last_instance_removed", "if (n_cur >= 2 && (int64_t)sat_qps[cur] * (n_cur - 1) * 100 >= need) {", "if (n_cur >= 1 && (int64_t)sat_qps[cur] * (n_cur - 1) * 100 >= need) {"),
+    ("down_capacity_before_removal", "if (n_cur >= 2 && (int64_t)sat_qps[cur] * (n_cur - 1) * 100 >= need) {", "if (n_cur >= 2 && (int64_t)sat_qps[cur] * n_cur * 100 >= need) {"),
+    ("down_strict_capacity_test", "(int64_t)sat_qps[cur] * (n_cur - 1) * 100 >= need) {", "(int64_t)sat_qps[cur] * (n_cur - 1) * 100 > need) {"),
+    ("down_removal_gains_nothing", "wide_t objective = -(wide_t)hw_cost[cur] * 1000000;", "wide_t objective = 0;"),
+    ("down_removal_unscaled", "wide_t objective = -(wide_t)hw_cost[cur] * 1000000;", "wide_t objective = -(wide_t)hw_cost[cur];"),
+    ("down_removal_of_all", "wide_t objective = -(wide_t)hw_cost[cur] * 1000000;", "wide_t objective = -(wide_t)hw_cost[cur] * n_cur * 1000000;"),
+    ("down_headroom_ignored", "int64_t slo = r_slo_us[r];\n        wide_t lowest = 0;", "need = (int64_t)r_load_qps[r] * 100;\n        int64_t slo = r_slo_us[r];\n        wide_t lowest = 0;"),
+    ("down_to_equal_cost", "|| hw_cost[u] >= hw_cost[cur])", "|| hw_cost[u] > hw_cost[cur])"),
+    ("down_to_any_cost", "if ((int64_t)lat_us[u * B + b] > slo || hw_cost[u] >= hw_cost[cur])", "if ((int64_t)lat_us[u * B + b] > slo)"),
+    ("down_ignores_slo", "if ((int64_t)lat_us[u * B + b] > slo || hw_cost[u] >= hw_cost[cur])", "if (hw_cost[u] >= hw_cost[cur])"),
+    ("down_wrong_batch_column", "if ((int64_t)lat_us[u * B + b] > slo || hw_cost[u] >= hw_cost[cur])", "if ((int64_t)lat_us[u * B] > slo || hw_cost[u] >= hw_cost[cur])"),
+    ("down_any_architecture", "if (u == cur || arch_id[u] != arch_id[cur])\n                continue;\n            if ((int64_t)lat_us[u * B + b] > slo || hw_cost[u] >= hw_cost[cur])", "if (u == cur)\n                continue;\n            if ((int64_t)lat_us[u * B + b] > slo || hw_cost[u] >= hw_cost[cur])"),
+    ("down_instances_rounded_down", "int64_t inst = (need + per - 1) / per;\n            if (inst < 1)", "int64_t inst = need / per;\n            if (inst < 1)"),
+    ("down_to_no_instance", "if (inst < 1)\n                inst = 1;", ""),
+    ("down_unloading_not_credited", "((wide_t)1000000 + (wide_t)lambda_per_s * load_us[u]) - unloaded;", "((wide_t)1000000 + (wide_t)lambda_per_s * load_us[u]);"),
+    ("down_unloading_credited_unscaled", "wide_t unloaded = (wide_t)hw_cost[cur] * n_cur * 1000000;", "wide_t unloaded = (wide_t)hw_cost[cur] * n_cur;"),
+    ("down_unloading_one_credited", "wide_t unloaded = (wide_t)hw_cost[cur] * n_cur * 1000000;", "wide_t unloaded = (wide_t)hw_cost[cur] * 1000000;"),
+    ("down_lambda_dropped", "((wide_t)1000000 + (wide_t)lambda_per_s * load_us[u]) - unloaded;", "((wide_t)1000000) - unloaded;"),
+    ("down_objective_in_64_bits", "wide_t objective = (wide_t)hw_cost[u] * inst *\n                               ((wide_t)1000000 + (wide_t)lambda_per_s * load_us[u]) - unloaded;",
+     "wide_t objective = (wide_t)(int64_t)((uint64_t)hw_cost[u] * (uint64_t)inst *\n                               (uint64_t)(1000000 + (int64_t)lambda_per_s * load_us[u])) - unloaded;"),
+    ("down_tie_to_the_switch", "if (objective < lowest) {               /* rows ascend", "if (objective <= lowest) {               /* rows ascend"),
+    ("down_tie_to_removal", "if (objective < lowest) {\n                lowest = objective;\n                out_action[r] = 1;", "if (objective <= lowest) {\n                lowest = objective;\n                out_action[r] = 1;"),
+    ("down_action_codes_swapped", "out_action[r] = 2;\n                out_variant[r] = (int32_t)u;", "out_action[r] = 1;\n                out_variant[r] = (int32_t)u;"),
+    ("down_reports_instances_left", "out_instances[r] = 1;", "out_instances[r] = (int32_t)(n_cur - 1);"),
+    ("down_limits_unchecked", "r_instances[r] > 1000000 || r_load_qps[r] > 1000000000)\n            continue;\n        int64_t n_cur = r_instances[r];\n        int64_t need = (int64_t)r_load_qps[r] * (int64_t)slack_pct;        /* hundredths of a query per second */\n        int64_t slo", "0)\n            continue;\n        int64_t n_cur = r_instances[r];\n        int64_t need = (int64_t)r_load_qps[r] * (int64_t)slack_pct;        /* hundredths of a query per second */\n        int64_t slo"),
+]
+
+
+@pytest.mark.parametrize("name,find,repl", SCALE_DOWN_MUTANTS, ids=[m[0] for m in SCALE_DOWN_MUTANTS])
+def test_scale_down_mutant_is_caught(tmp_path, source_text, name, find, repl):
+    assert source_text.count(find) == 1, f"mutant {name}: pattern not once in the oracle source"
+    src = tmp_path / f"{name}.c"
+    src.write_text(source_text.replace(find, repl))
+    lib = oracle.build_oracle(src=str(src), out=str(tmp_path / f"lib{name}.so"), force=True)
+    mutant = oracle.Oracle(lib)
+    caught = []
+    for pin in pins.SCALE_DOWN_PINS:
+        try:
+            pin(mutant)
+        except (AssertionError, ValueError):
+            caught.append(pin.__name__)
+    assert caught, f"no pin notices the planted mistake '{name}'"
+
+
 @pytest.mark.parametrize("name,find,repl", SCALING_MUTANTS, ids=[m[0] for m in SCALING_MUTANTS])
 def test_scaling_mutant_is_caught(tmp_path, source_text, name, find, repl):
     assert find in source_text, f"mutant {name}: pattern not in the oracle source any more"

@@ -41,6 +41,11 @@ def test_scaling_pin(oracle_lib, pin):
     pin(oracle_lib)
 
 
+@pytest.mark.parametrize("pin", pins.SCALE_DOWN_PINS, ids=lambda f: f.__name__)
+def test_scale_down_pin(oracle_lib, pin):
+    pin(oracle_lib)
+
+
 def test_grouped_equals_literal_on_medium_sample(oracle_lib):
     tb = workloads.make_table(1)
     q = workloads.make_queries(1, n=2000)
