@@ -12,7 +12,8 @@ by loading + inference latency; variant and tier arrays, 24 B per decision); its
 launches are priced together.  With --workers a step is one call of infaas_sel_select_workers
 (the same plus the worker that serves each answer, over a seeded cluster; 28 B per decision).
 With --scale a step is one call of infaas_sel_scale over 4M seeded scaling requests on the table of
-the configuration (replicate or upgrade on a change in load; 32 B per decision).
+the configuration (replicate or upgrade on a change in load; 32 B per decision), with --scale-down
+one call of infaas_sel_scale_down (keep, remove an instance or downgrade).
 
 Prints ONE JSON line: decisions/s, the roofline of the dominant kernel (algorithmic bytes:
 20 B per decision + the variant table once, against 8 TB/s of HBM) timed with HIP events on
@@ -72,8 +73,9 @@ SCALE_LAMBDA, SCALE_SLACK = 50, 105
 SCALE_BYTES_PER_DECISION = 32    # 5 int32 request fields read + 3 int32 results written
 
 
-def bench_scale(args, cfg, spec, tb) -> int:
-    """The scaling-decision call (Section 4.2.2) timed like the selection."""
+def bench_scale(args, cfg, spec, tb, down=False) -> int:
+    """A scaling-decision call (Section 4.2.2: scaling up, or with down=True scaling down) timed like
+    the selection."""
     import numpy as np
     import torch
 
@@ -81,7 +83,7 @@ def bench_scale(args, cfg, spec, tb) -> int:
     import workloads
 
     if args.closest or args.tiered or args.workers or args.engine != "auto":
-        print("bench.py: --scale goes alone", file=sys.stderr)
+        print("bench.py: --scale and --scale-down go alone", file=sys.stderr)
         return 2
     n = min(SCALE_REQUESTS, spec["num_queries"])
     sc = workloads.make_scaling(cfg, tb)
@@ -89,7 +91,8 @@ def bench_scale(args, cfg, spec, tb) -> int:
     sel.load_variants(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us)
     sel.load_scaling(sc.arch_id, sc.sat_qps, sc.hw_cost, sc.load_us, SCALE_LAMBDA, SCALE_SLACK)
     n_sets = int(min(MAX_SETS, max(4, -(-ROTATE_BYTES // (n * SCALE_BYTES_PER_DECISION)))))   # see main()
-    host = [workloads.make_scale_requests(cfg, tb, sc, n, chunk=c) for c in range(n_sets)]
+    make = workloads.make_scale_down_requests if down else workloads.make_scale_requests
+    host = [make(cfg, tb, sc, n, chunk=c) for c in range(n_sets)]
     dev = [[torch.from_numpy(x).cuda() for x in (r.variant, r.instances, r.load_qps, r.slo_us, r.batch_idx)]
            for r in host]
     out_sets = [[torch.empty(n, dtype=torch.int32, device="cuda") for _ in range(3)] for _ in range(n_sets)]
@@ -97,30 +100,31 @@ def bench_scale(args, cfg, spec, tb) -> int:
     t_heat = time.perf_counter()
     while args.preheat_ms > 0 and 1e3 * (time.perf_counter() - t_heat) < args.preheat_ms:
         for _ in range(16):
-            sel.scale(*dev[done % n_sets], *out_sets[done % n_sets])
+            sel.scale(*dev[done % n_sets], *out_sets[done % n_sets], down=down)
             done += 1
         torch.cuda.synchronize()
     for _ in range(args.warmup):
-        sel.scale(*dev[done % n_sets], *out_sets[done % n_sets])
+        sel.scale(*dev[done % n_sets], *out_sets[done % n_sets], down=down)
         done += 1
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):   # the timed region, instrumentation off
-        sel.scale(*dev[done % n_sets], *out_sets[done % n_sets])
+        sel.scale(*dev[done % n_sets], *out_sets[done % n_sets], down=down)
         done += 1
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     sel.set_timing(True)          # the same steps again for the kernel's own duration
     torch.cuda.synchronize()
     for _ in range(args.steps):
-        sel.scale(*dev[done % n_sets], *out_sets[done % n_sets])
+        sel.scale(*dev[done % n_sets], *out_sets[done % n_sets], down=down)
         done += 1
     torch.cuda.synchronize()
     timings = sel.get_timings()
     sel.set_timing(False)
     outs = out_sets[(done - 1) % n_sets]
     ms_per_step = 1e3 * elapsed / args.steps
-    k = timings["scale"]
+    kernel = "scale_down" if down else "scale"
+    k = timings[kernel]
     avg_ms = k["total_ms"] / k["launches"]
     # every request in, every result out, and what the decision reads of the table once: per variant
     # its architecture, throughput, hardware cost, loading latency and the latency at every batch size
@@ -136,11 +140,11 @@ def bench_scale(args, cfg, spec, tb) -> int:
         prof = (sc.arch_id, sc.sat_qps, sc.hw_cost, sc.load_us, tb.lat_us, SCALE_LAMBDA, SCALE_SLACK)
         n0 = min(n, 20_000)
         s0 = time.perf_counter()
-        ref.scale(*prof, *(f[:n0] for f in fields))
+        ref.scale(*prof, *(f[:n0] for f in fields), down=down)
         rate0 = n0 / (time.perf_counter() - s0)
         m = int(min(n, max(n0, rate0 * args.cpu_seconds)))
         s0 = time.perf_counter()
-        want = ref.scale(*prof, *(f[:m] for f in fields))
+        want = ref.scale(*prof, *(f[:m] for f in fields), down=down)
         dt = time.perf_counter() - s0
         mismatches = int(sum((g[:m].cpu().numpy() != w).sum() for g, w in zip(outs, want)))
         cpu = {"value": round(m / dt, 1), "unit": "decisions/s", "cores": ref.num_threads(), "kind": "oracle",
@@ -150,15 +154,15 @@ def bench_scale(args, cfg, spec, tb) -> int:
         "value": round(n * args.steps / elapsed, 1), "unit": "decisions/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
-        "config": {"workload": f"scaling decisions (replicate or upgrade on a change in load): {n} requests per step on "
+        "config": {"workload": f"scaling decisions ({'keep, remove an instance or downgrade at the regular check' if down else 'replicate or upgrade on a change in load'}): {n} requests per step on "
                                f"the table of config {cfg} ({tb.V} variants in {int(np.unique(sc.arch_id).size)} "
                                f"architectures, {tb.B} batch sizes), lambda {SCALE_LAMBDA}/s, headroom {SCALE_SLACK}%",
                    "engine": "auto"},
-        "roofline": {"bound": "hbm", "kernel": "scale", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
-                     "traffic": measured_traffic("scale", cfg, "auto/scale"), "avg_kernel_ms": round(avg_ms, 5),
+                     "traffic": measured_traffic(kernel, cfg, "auto/" + kernel), "avg_kernel_ms": round(avg_ms, 5),
                      "algorithmic_bytes_per_launch": int(algo)},
-        "kernels_ms_per_step": {"scale": round(k["total_ms"] / args.steps, 5)},
+        "kernels_ms_per_step": {kernel: round(k["total_ms"] / args.steps, 5)},
         "cpu_baseline": cpu,
         "parity_sample_mismatches": mismatches,
     }
@@ -201,6 +205,9 @@ def main() -> int:
     ap.add_argument("--scale", action="store_true",
                     help="time infaas_sel_scale (scaling decisions on a change in load: 4M seeded requests, "
                          "lambda 50/s, headroom 105%%; 32 B per decision) instead of the selection")
+    ap.add_argument("--scale-down", action="store_true",
+                    help="time infaas_sel_scale_down (the regular scaling-down check: keep, remove an instance "
+                         "or downgrade; 4M seeded requests, same profile and 32 B per decision)")
     ap.add_argument("--graph", action="store_true",
                     help="after the timed steps (which give the kernel times), capture the steps into HIP graphs "
                          "and time the same number of steps again as graph replays: value and ms_per_step are "
@@ -241,8 +248,11 @@ def main() -> int:
     cfg = args.config
     spec = workloads.config_spec(cfg)
     tb = workloads.make_table(cfg) if args.table == "config" else workloads.make_cliff_table(args.table, cfg)
-    if args.scale:
-        return bench_scale(args, cfg, spec, tb)
+    if args.scale or args.scale_down:
+        if args.scale and args.scale_down:
+            print("bench.py: --scale or --scale-down, not both", file=sys.stderr)
+            return 2
+        return bench_scale(args, cfg, spec, tb, down=args.scale_down)
     chunks = spec["chunks"]
     per_step = spec["num_queries"] // chunks
     engine = {"auto": pkg.ENGINE_AUTO, "scan": pkg.ENGINE_SCAN, "index": pkg.ENGINE_INDEX}[args.engine]

@@ -22,8 +22,8 @@
  * (infaas_sel_select_closest), the state-aware form of the same decision
  * (infaas_sel_load_states / _update_state / _select_tiered), the worker that serves the
  * chosen variant (infaas_sel_load_workers / _update_workers / _select_workers) and the
- * decision on a change in load, Case II of Section 4.2 (infaas_sel_load_scaling /
- * infaas_sel_scale).  They follow the conventions stated here.
+ * decisions on a change in load, Case II of Section 4.2 (infaas_sel_load_scaling /
+ * infaas_sel_scale / infaas_sel_scale_down).  They follow the conventions stated here.
  *
  * Plain C ABI: opaque handle, plain pointers and sizes.  Each pointer below is marked
  * HOST or DEVICE.  Nothing here allocates or frees memory the caller passed in.
@@ -361,8 +361,8 @@ int infaas_sel_select_workers(infaas_sel_t *h, int64_t N,
  *     upgrade:    C[u] * inst(u) * (1 + lambda * T_load[u]) - C[cur] * n_cur
  * in exact integer arithmetic (lambda per second, T_load in microseconds, 128-bit products).
  * Readings where the text is silent: among upgrades of equal cost the lower row; replication
- * wins a tie against the cheapest upgrade; worker resources (constraint 3) and scaling down are
- * not part of the decision.
+ * wins a tie against the cheapest upgrade; worker resources (constraint 3) are not part of the
+ * decision.  Scaling down is infaas_sel_scale_down.
  *
  * Register what the decision reads per variant.  HOST arrays [V], caller row order, copied:
  *   arch_id   model architecture (any int32; compared for equality)
@@ -394,6 +394,39 @@ int infaas_sel_scale(infaas_sel_t *h, int64_t R,
                      const int32_t *d_slo_us, const int32_t *d_batch_idx,
                      int32_t *d_out_action, int32_t *d_out_variant, int32_t *d_out_instances,
                      void *hip_stream);
+
+/*
+ * ---- Scaling down (Section 4.2.2, "Scaling down algorithm") ------------------------------------
+ *
+ * Asked at regular intervals: can the incoming load L of the running variant cur with n_cur
+ * instances be carried for less?  Either REMOVE one instance of cur, allowed when at least one
+ * stays and Q[cur] * (n_cur - 1) carries slack_pct percent of L; or DOWNGRADE to a variant u of the
+ * same model architecture with a lower hardware cost, C[u] < C[cur], and lat_us[u][b] <= slo_us:
+ * load inst(u) = max(1, ceil(L * slack_pct / (100 * Q[u]))) instances of u and unload cur.  By the
+ * objective of the integer program, as in infaas_sel_scale:
+ *     keep:       0
+ *     remove:     - C[cur]
+ *     downgrade:  C[u] * inst(u) * (1 + lambda * T_load[u]) - C[cur] * n_cur
+ * the lowest wins, and only an option that lowers the objective is acted on.  Readings where the
+ * text is silent: one instance per decision, never the last one (unloading a variant altogether
+ * belongs to the state machine of Section 4); ties go to keeping, then to removing, then to the
+ * lower row.  The paper has the autoscaler wait T_v = T_load[cur] before it executes the action;
+ * that wait is the caller's and does not enter the decision.
+ *
+ * Uses what infaas_sel_load_scaling registered.  DEVICE arrays [R], requests as for
+ * infaas_sel_scale (same ranges; a request outside them gets action 0), and
+ *   d_out_action     0 keep, 1 remove, 2 downgrade
+ *   d_out_variant    cur for 1, u for 2, -1 for 0
+ *   d_out_instances  1 instance to unload for 1; inst(u) instances to load for 2 (all n_cur of cur
+ *                    are then unloaded); 0 for 0
+ * Enqueues on hip_stream and returns; allocates nothing.
+ * Errors: INVALID_ARG, NOT_LOADED (no scaling profile loaded), HIP.
+ */
+int infaas_sel_scale_down(infaas_sel_t *h, int64_t R,
+                          const int32_t *d_variant, const int32_t *d_instances, const int32_t *d_load_qps,
+                          const int32_t *d_slo_us, const int32_t *d_batch_idx,
+                          int32_t *d_out_action, int32_t *d_out_variant, int32_t *d_out_instances,
+                          void *hip_stream);
 
 /* Free the handle and everything it owns.  NULL is a no-op. */
 void infaas_sel_destroy(infaas_sel_t *h);
@@ -433,7 +466,8 @@ enum {
     INFAAS_SEL_K_GROUP_FINISH = 16,/* grouped index: answers back into query order */
     INFAAS_SEL_K_INSTANCE_STATES = 17,/* instance state report and the variants' states derived from it */
     INFAAS_SEL_K_CLOSEST_SCAN = 18,/* closest-variant suggestions by exhaustive scan (no index) */
-    INFAAS_SEL_K_COUNT = 19
+    INFAAS_SEL_K_SCALE_DOWN = 19,/* scaling-down decisions */
+    INFAAS_SEL_K_COUNT = 20
 };
 typedef struct {
     int64_t launches[INFAAS_SEL_K_COUNT];

@@ -22,7 +22,7 @@ ENGINE_INDEX = 2
 KERNEL_NAMES = ("update_load", "histogram", "plan", "scatter", "scan_lds", "scan_wide",
                 "finish_wide", "index_build", "index_select", "update_state", "worker_report",
                 "worker_tables", "step_workers", "scale", "group_bin", "group_lookup",
-                "group_finish", "instance_states", "closest_scan")
+                "group_finish", "instance_states", "closest_scan", "scale_down")
 _K_COUNT = len(KERNEL_NAMES)
 
 _I32P = ctypes.POINTER(ctypes.c_int32)
@@ -67,7 +67,7 @@ EXPORTED = ("infaas_sel_create", "infaas_sel_load_variants", "infaas_sel_update_
             "infaas_sel_load_workers",
             "infaas_sel_update_workers", "infaas_sel_load_instance_states", "infaas_sel_update_instance_states",
             "infaas_sel_select_workers", "infaas_sel_load_scaling",
-            "infaas_sel_scale", "infaas_sel_destroy", "infaas_sel_reserve",
+            "infaas_sel_scale", "infaas_sel_scale_down", "infaas_sel_destroy", "infaas_sel_reserve",
             "infaas_sel_read_load", "infaas_sel_set_timing", "infaas_sel_get_timings",
             "infaas_sel_get_info", "infaas_sel_strerror", "infaas_sel_last_error")
 
@@ -110,6 +110,7 @@ def load_library() -> ctypes.CDLL:
     lib.infaas_sel_select_workers.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.infaas_sel_load_scaling.argtypes = [vp, _I32P, _I32P, _I32P, _I32P, ctypes.c_int32, ctypes.c_int32]
     lib.infaas_sel_scale.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.infaas_sel_scale_down.argtypes = lib.infaas_sel_scale.argtypes
     lib.infaas_sel_destroy.argtypes = [vp]
     lib.infaas_sel_destroy.restype = None
     lib.infaas_sel_reserve.argtypes = [vp, ctypes.c_int64]
@@ -302,14 +303,17 @@ class Selector:
                                                  int(lambda_per_s), int(slack_pct)))
 
     def scale(self, d_variant, d_instances, d_load_qps, d_slo_us, d_batch_idx, d_out_action, d_out_variant,
-              d_out_instances, stream=None, n: Optional[int] = None) -> None:
+              d_out_instances, stream=None, n: Optional[int] = None, down: bool = False) -> None:
         n = int(d_variant.numel()) if n is None else int(n)
-        _check(self._lib.infaas_sel_scale(
+        _check((self._lib.infaas_sel_scale_down if down else self._lib.infaas_sel_scale)(
             self._h, n, _dev_ptr(d_variant, n, "d_variant"), _dev_ptr(d_instances, n, "d_instances"),
             _dev_ptr(d_load_qps, n, "d_load_qps"), _dev_ptr(d_slo_us, n, "d_slo_us"),
             _dev_ptr(d_batch_idx, n, "d_batch_idx"), _dev_ptr(d_out_action, n, "d_out_action"),
             _dev_ptr(d_out_variant, n, "d_out_variant"), _dev_ptr(d_out_instances, n, "d_out_instances"),
             _stream_ptr(stream)))
+
+    def scale_down(self, *args, **kw) -> None:
+        self.scale(*args, down=True, **kw)
 
     def destroy(self) -> None:
         if self._h:

@@ -1372,53 +1372,64 @@ int infaas_sel_load_scaling(infaas_sel_t *h, const int32_t *arch_id, const int32
     auto unit_of = [&](int32_t v) {   // cost of one loaded instance, < 2^62
         return (uint64_t)hw_cost[v] * (1000000ull + (uint64_t)lambda_per_s * (uint64_t)load_us[v]);
     };
-    // Candidates of an architecture at a batch size: by descending throughput, and only those that
-    // no other variant beats for every request (at least the throughput, at most the latency, and
-    // a lower cost per instance or the same with a lower row).  Sorted so that whatever beats a
+    // Candidates of an architecture at a batch size, for scaling up: by descending throughput, and only
+    // those that no other variant beats for every request (at least the throughput, at most the latency,
+    // and a lower cost per instance or the same with a lower row).  Sorted so that whatever beats a
     // variant comes before it; being beaten is transitive, so the survivors so far are enough to
     // compare with.  Every row of the architecture then gets its block: its own figures and the
     // first candidates of the prefix of the list whose throughput is above its own.
+    // For scaling down: by ascending hardware cost, "beats" asks for at most the hardware cost besides
+    // (a candidate must be cheaper than the running variant to be one at all), and a row's
+    // candidates are the prefix of the list whose hardware cost is below its own.
     if ((int64_t)B * V * kScaleBlockWords * 4 > ((int64_t)1 << 33)) return INFAAS_SEL_ERR_OOM;   // 8 GB of blocks
-    std::vector<uint32_t> blocks((size_t)std::max<int64_t>((int64_t)B * V, 1) * kScaleBlockWords, 0u);
-    if (V == 0) blocks[0] = 1u;   // the block an invalid request reads: throughput 1, no candidates (it is never used)
-    std::vector<ScaleCand> cand;
-    std::vector<int32_t> order;
-    for (int32_t b = 0; b < B; ++b)
-        for (int32_t a = 0; a < A; ++a) {
-            order.assign(by_arch.begin() + arch_first[(size_t)a], by_arch.begin() + arch_first[(size_t)a + 1]);
-            std::sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
-                if (sat_qps[x] != sat_qps[y]) return sat_qps[x] > sat_qps[y];
-                const uint64_t ux = unit_of(x), uy = unit_of(y);
-                if (ux != uy) return ux < uy;
-                return x < y;
-            });
-            const size_t first = cand.size();
-            for (int32_t v : order) {
-                const ScaleCand r{(uint32_t)sat_qps[v], h->h_lat[(size_t)v * B + b], unit_of(v), v, {0, 0, 0}};
-                bool beaten = false;
-                for (size_t k = first; k < cand.size() && !beaten; ++k)
-                    beaten = cand[k].lat <= r.lat && (cand[k].unit < r.unit || (cand[k].unit == r.unit && cand[k].row < v));
-                if (!beaten) cand.push_back(r);
-            }
-            if (cand.size() > 0x7FFFFFFFull) return INFAAS_SEL_ERR_OUT_OF_RANGE;
-            const size_t n = cand.size() - first;
-            for (int32_t v : order) {
-                uint32_t *w = &blocks[((size_t)b * V + v) * kScaleBlockWords];
-                const uint64_t unit = unit_of(v);
-                size_t m = 0;   // candidates with a higher throughput: a prefix of the list
-                while (m < n && cand[first + m].qps > (uint32_t)sat_qps[v]) ++m;
-                w[0] = (uint32_t)sat_qps[v]; w[1] = (uint32_t)hw_cost[v];
-                w[2] = (uint32_t)unit; w[3] = (uint32_t)(unit >> 32);
-                w[4] = (uint32_t)h->h_lat[(size_t)v * B + b]; w[5] = (uint32_t)m; w[6] = (uint32_t)first;
-                for (size_t j = 0; j < std::min<size_t>(m, kScaleInBlock); ++j) {
-                    const ScaleCand &c = cand[first + j];
-                    uint32_t *sl = w + 8 + 4 * j;
-                    sl[0] = c.qps; sl[1] = (uint32_t)c.lat; sl[2] = (uint32_t)c.unit; sl[3] = (uint32_t)(c.unit >> 32);
-                    w[j < 4 ? 28 + j : 7] = (uint32_t)c.row;
+    std::vector<uint32_t> blocks_of[2];
+    std::vector<ScaleCand> cand_of[2];
+    std::vector<int32_t> order, cand_cost;
+    for (int down = 0; down < 2; ++down) {
+        std::vector<uint32_t> &blocks = blocks_of[down];
+        std::vector<ScaleCand> &cand = cand_of[down];
+        blocks.assign((size_t)std::max<int64_t>((int64_t)B * V, 1) * kScaleBlockWords, 0u);
+        if (V == 0) blocks[0] = 1u;   // the block an invalid request reads: throughput 1, no candidates (it is never used)
+        cand_cost.clear();            // hardware cost of cand[k]
+        for (int32_t b = 0; b < B; ++b)
+            for (int32_t a = 0; a < A; ++a) {
+                order.assign(by_arch.begin() + arch_first[(size_t)a], by_arch.begin() + arch_first[(size_t)a + 1]);
+                std::sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+                    if (!down && sat_qps[x] != sat_qps[y]) return sat_qps[x] > sat_qps[y];
+                    if (down && hw_cost[x] != hw_cost[y]) return hw_cost[x] < hw_cost[y];
+                    const uint64_t ux = unit_of(x), uy = unit_of(y);
+                    if (ux != uy) return ux < uy;
+                    return x < y;
+                });
+                const size_t first = cand.size();
+                for (int32_t v : order) {
+                    const ScaleCand r{(uint32_t)sat_qps[v], h->h_lat[(size_t)v * B + b], unit_of(v), v, {0, 0, 0}};
+                    bool beaten = false;
+                    for (size_t k = first; k < cand.size() && !beaten; ++k)
+                        beaten = cand[k].qps >= r.qps && cand[k].lat <= r.lat &&
+                                 (cand[k].unit < r.unit || (cand[k].unit == r.unit && cand[k].row < v));
+                    if (!beaten) { cand.push_back(r); cand_cost.push_back(hw_cost[v]); }
+                }
+                if (cand.size() > 0x7FFFFFFFull) return INFAAS_SEL_ERR_OUT_OF_RANGE;
+                const size_t n = cand.size() - first;
+                for (int32_t v : order) {
+                    uint32_t *w = &blocks[((size_t)b * V + v) * kScaleBlockWords];
+                    const uint64_t unit = unit_of(v);
+                    size_t m = 0;   // candidates with a higher throughput, resp. a lower hardware cost: a prefix of the list
+                    while (m < n && (down ? cand_cost[first + m] < hw_cost[v] : cand[first + m].qps > (uint32_t)sat_qps[v])) ++m;
+                    w[0] = (uint32_t)sat_qps[v]; w[1] = (uint32_t)hw_cost[v];
+                    w[2] = (uint32_t)unit; w[3] = (uint32_t)(unit >> 32);
+                    w[4] = (uint32_t)h->h_lat[(size_t)v * B + b]; w[5] = (uint32_t)m; w[6] = (uint32_t)first;
+                    for (size_t j = 0; j < std::min<size_t>(m, kScaleInBlock); ++j) {
+                        const ScaleCand &c = cand[first + j];
+                        uint32_t *sl = w + 8 + 4 * j;
+                        sl[0] = c.qps; sl[1] = (uint32_t)c.lat; sl[2] = (uint32_t)c.unit; sl[3] = (uint32_t)(c.unit >> 32);
+                        w[j < 4 ? 28 + j : 7] = (uint32_t)c.row;
+                    }
                 }
             }
-        }
-    if (cand.empty()) cand.push_back(ScaleCand{1u, 0, 0ull, 0, {0, 0, 0}});
+        if (cand.empty()) cand.push_back(ScaleCand{1u, 0, 0ull, 0, {0, 0, 0}});
+    }
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     if (!HIP_OK(hipDeviceSynchronize())) return INFAAS_SEL_ERR_HIP;
@@ -1436,8 +1447,10 @@ int infaas_sel_load_scaling(infaas_sel_t *h, const int32_t *arch_id, const int32
     };
     ScaleView sv{};
     sv.V = V; sv.B = B; sv.slack_pct = slack_pct;
-    sv.blocks = (const uint32_t *)upload(blocks.data(), blocks.size() * 4);
-    sv.cand = (const ScaleCand *)upload(cand.data(), cand.size() * sizeof(ScaleCand));
+    sv.blocks = (const uint32_t *)upload(blocks_of[0].data(), blocks_of[0].size() * 4);
+    sv.cand = (const ScaleCand *)upload(cand_of[0].data(), cand_of[0].size() * sizeof(ScaleCand));
+    sv.blocks_down = (const uint32_t *)upload(blocks_of[1].data(), blocks_of[1].size() * 4);
+    sv.cand_down = (const ScaleCand *)upload(cand_of[1].data(), cand_of[1].size() * sizeof(ScaleCand));
     if (!ok) {
         for (void *p : h->scale_mem) (void)hipFree(p);
         h->scale_mem.clear();
@@ -1448,9 +1461,9 @@ int infaas_sel_load_scaling(infaas_sel_t *h, const int32_t *arch_id, const int32
     return INFAAS_SEL_OK;
 }
 
-int infaas_sel_scale(infaas_sel_t *h, int64_t R, const int32_t *d_variant, const int32_t *d_instances,
-                     const int32_t *d_load_qps, const int32_t *d_slo_us, const int32_t *d_batch_idx,
-                     int32_t *d_out_action, int32_t *d_out_variant, int32_t *d_out_instances, void *hip_stream)
+static int scale_impl(infaas_sel_t *h, bool down, int64_t R, const int32_t *d_variant, const int32_t *d_instances,
+                      const int32_t *d_load_qps, const int32_t *d_slo_us, const int32_t *d_batch_idx,
+                      int32_t *d_out_action, int32_t *d_out_variant, int32_t *d_out_instances, void *hip_stream)
 {
     if (!h || R < 0) return INFAAS_SEL_ERR_INVALID_ARG;
     if (!h->loaded || !h->scaling_loaded) return INFAAS_SEL_ERR_NOT_LOADED;
@@ -1461,11 +1474,27 @@ int infaas_sel_scale(infaas_sel_t *h, int64_t R, const int32_t *d_variant, const
     DeviceGuard g(h->device);
     if (!g.ok) return INFAAS_SEL_ERR_HIP;
     hipStream_t st = (hipStream_t)hip_stream;
-    LaunchTimer t(h, INFAAS_SEL_K_SCALE, st);
-    if (!HIP_OK(launch_scale(h->sv, R, d_variant, d_instances, d_load_qps, d_slo_us, d_batch_idx, d_out_action,
+    LaunchTimer t(h, down ? INFAAS_SEL_K_SCALE_DOWN : INFAAS_SEL_K_SCALE, st);
+    if (!HIP_OK(launch_scale(h->sv, down, R, d_variant, d_instances, d_load_qps, d_slo_us, d_batch_idx, d_out_action,
                              d_out_variant, d_out_instances, h->num_cus, st, t.ev())))
         return INFAAS_SEL_ERR_HIP;
     return INFAAS_SEL_OK;
+}
+
+int infaas_sel_scale(infaas_sel_t *h, int64_t R, const int32_t *d_variant, const int32_t *d_instances,
+                     const int32_t *d_load_qps, const int32_t *d_slo_us, const int32_t *d_batch_idx,
+                     int32_t *d_out_action, int32_t *d_out_variant, int32_t *d_out_instances, void *hip_stream)
+{
+    return scale_impl(h, false, R, d_variant, d_instances, d_load_qps, d_slo_us, d_batch_idx, d_out_action,
+                      d_out_variant, d_out_instances, hip_stream);
+}
+
+int infaas_sel_scale_down(infaas_sel_t *h, int64_t R, const int32_t *d_variant, const int32_t *d_instances,
+                          const int32_t *d_load_qps, const int32_t *d_slo_us, const int32_t *d_batch_idx,
+                          int32_t *d_out_action, int32_t *d_out_variant, int32_t *d_out_instances, void *hip_stream)
+{
+    return scale_impl(h, true, R, d_variant, d_instances, d_load_qps, d_slo_us, d_batch_idx, d_out_action,
+                      d_out_variant, d_out_instances, hip_stream);
 }
 
 void infaas_sel_destroy(infaas_sel_t *h)

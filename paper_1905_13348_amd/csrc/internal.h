@@ -309,8 +309,13 @@ struct ScaleView {
     const uint32_t *blocks;   // [B][V][32]
     const ScaleCand *cand;    // per (batch size, architecture) the variants that can ever win an upgrade, by
                               // descending throughput
+    // The same two for scaling down: the candidates of a row are those for a downgrade (the prefix with a
+    // lower hardware cost of its architecture's list, which is sorted by ascending hardware cost).
+    const uint32_t *blocks_down;
+    const ScaleCand *cand_down;
 };
-hipError_t launch_scale(const ScaleView &sv, int64_t R, const int32_t *r_variant, const int32_t *r_instances,
+// down: the scaling-down decision (keep, remove an instance, downgrade) instead of scaling up
+hipError_t launch_scale(const ScaleView &sv, bool down, int64_t R, const int32_t *r_variant, const int32_t *r_instances,
                         const int32_t *r_load_qps, const int32_t *r_slo_us, const int32_t *r_batch_idx,
                         int32_t *out_action, int32_t *out_variant, int32_t *out_instances, int num_cus,
                         hipStream_t st, const LaunchEvents *ev = nullptr);

@@ -113,3 +113,8 @@ def test_scaling_profiles_and_requests():
     assert 0.75 < need.mean() < 0.95     # most requests need scaling, some do not
     r2 = workloads.make_scale_requests(1, tb, a, 50_000, chunk=1)
     assert not np.array_equal(r.variant, r2.variant)
+    d = workloads.make_scale_down_requests(1, tb, a, 50_000)
+    assert d.R == 50_000 and d.instances.min() >= 1 and d.load_qps.min() >= 0
+    spare = a.sat_qps[d.variant].astype(np.int64) * (d.instances - 1) * 100 >= d.load_qps.astype(np.int64) * 105
+    assert 0.3 < (spare & (d.instances >= 2)).mean() < 0.8     # often an instance can go, often not
+    assert not np.array_equal(d.variant, workloads.make_scale_down_requests(1, tb, a, 50_000, chunk=1).variant)

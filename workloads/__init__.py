@@ -29,5 +29,6 @@ from .configs import (  # noqa: F401
     ScalingProfile,
     ScaleRequests,
     make_scaling,
+    make_scale_down_requests,
     make_scale_requests,
 )

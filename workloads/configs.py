@@ -468,3 +468,22 @@ def make_scale_requests(cfg: int, tb: VariantTable, sc: ScalingProfile, n: int, 
     return ScaleRequests(variant=variant.astype(np.int32), instances=inst.astype(np.int32),
                          load_qps=np.minimum(load, 1_000_000_000).astype(np.int32),
                          slo_us=np.rint(slo).astype(np.int32), batch_idx=bidx.astype(np.int32))
+
+
+def make_scale_down_requests(cfg: int, tb: VariantTable, sc: ScalingProfile, n: int, chunk: int = 0,
+                             seed: Optional[int] = None) -> ScaleRequests:
+    """``n`` scaling-down requests (the regular check of Section 4.2.2): running variant uniform over
+    the table, 1 + Poisson(2) running instances, incoming load = their combined saturation throughput
+    times U(0, 1.2) (mostly below capacity, as when load has fallen; about a sixth above it), latency
+    objective and batch index as in ``make_scale_requests``.  Seed: _SEED0 + cfg + 19000 + chunk."""
+    if seed is None:
+        seed = _SEED0 + cfg + 19000 + chunk
+    rng = np.random.default_rng(np.random.PCG64(seed))
+    variant = rng.integers(0, tb.V, size=n)
+    inst = 1 + rng.poisson(2.0, size=n)
+    load = np.rint(sc.sat_qps[variant].astype(np.float64) * inst * rng.uniform(0.0, 1.2, size=n))
+    slo = np.clip(rng.lognormal(np.log(20000.0), 1.0, size=n), 1000.0, 2_000_000.0)
+    bidx = rng.integers(0, tb.B, size=n)
+    return ScaleRequests(variant=variant.astype(np.int32), instances=inst.astype(np.int32),
+                         load_qps=np.minimum(load, 1_000_000_000).astype(np.int32),
+                         slo_us=np.rint(slo).astype(np.int32), batch_idx=bidx.astype(np.int32))
