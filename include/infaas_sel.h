@@ -431,7 +431,7 @@ int infaas_sel_scale_down(infaas_sel_t *h, int64_t R,
 /* Free the handle and everything it owns.  NULL is a no-op. */
 void infaas_sel_destroy(infaas_sel_t *h);
 
-/* ---- helpers around the five calls above -------------------------------------- */
+/* ---- helpers around the calls above ------------------------------------------- */
 
 /* Pre-grow the scratch memory for calls of up to max_queries queries, so that
  * infaas_sel_select (with states loaded: infaas_sel_select_tiered) does not allocate.
