@@ -392,40 +392,38 @@ __global__ __launch_bounds__(kGrpThreads) void k_group_finish(TableView tv, Inde
     // The barriers order LDS traffic only, so a tile's stores, and the loads of the next tile's answers,
     // stay in flight across them.
     constexpr int kResRounds = kTile / (4 * kGrpThreads);
-    v4i nxt[kResRounds];   // the answers of the tile that comes next, in binned order
-    if ((int32_t)blockIdx.x < ntiles) {
+    v4i nxt[kResRounds];                      // the answers of the tile that comes next, in binned order
+    unsigned long long nxt_pos[kTileRounds];  // and where each of its queries' answers is, four 16-bit positions a word
+    auto request = [&](int32_t tile) {
 #pragma unroll
         for (int r = 0; r < kResRounds; ++r)
-            nxt[r] = __builtin_nontemporal_load((const v4i *)(gs.res + (int64_t)blockIdx.x * kTile + r * 4 * kGrpThreads + tid * 4));
-    }
+            nxt[r] = __builtin_nontemporal_load((const v4i *)(gs.res + (int64_t)tile * kTile + r * 4 * kGrpThreads + tid * 4));
+#pragma unroll
+        for (int r = 0; r < kTileRounds; ++r) {
+            const int64_t i0 = (int64_t)tile * kTile + (int64_t)r * (4 * kGrpThreads) + tid * 4;
+            if (i0 + 4 <= q.n) {
+                nxt_pos[r] = __builtin_nontemporal_load((const unsigned long long *)(gs.perm + i0));
+            } else {
+                nxt_pos[r] = 0ull;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (i0 + e < q.n) nxt_pos[r] |= (unsigned long long)gs.perm[i0 + e] << (16 * e);
+            }
+        }
+    };
+    if ((int32_t)blockIdx.x < ntiles) request((int32_t)blockIdx.x);
     for (int32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const int64_t tile_base = (int64_t)tile * kTile;
         lds_barrier();   // the previous tile's answers have been read
 #pragma unroll
         for (int r = 0; r < kResRounds; ++r) *(v4i *)&l_res[r * 4 * kGrpThreads + tid * 4] = nxt[r];
-        // where each query's answer is (requested before the barrier, used behind it)
         uint32_t pos_all[kTileRounds][4];
 #pragma unroll
-        for (int r = 0; r < kTileRounds; ++r) {
-            const int64_t i0 = tile_base + (int64_t)r * (4 * kGrpThreads) + tid * 4;
-            uint32_t *pos = pos_all[r];
-            pos[0] = pos[1] = pos[2] = pos[3] = 0u;
-            if (i0 + 4 <= q.n) {
-                const unsigned long long pw = __builtin_nontemporal_load((const unsigned long long *)(gs.perm + i0));
-                const uint2 p = make_uint2((uint32_t)pw, (uint32_t)(pw >> 32));
-                pos[0] = p.x & 0xFFFFu; pos[1] = p.x >> 16; pos[2] = p.y & 0xFFFFu; pos[3] = p.y >> 16;
-            } else {
+        for (int r = 0; r < kTileRounds; ++r)
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (i0 + e < q.n) pos[e] = gs.perm[i0 + e];
-            }
-        }
+            for (int e = 0; e < 4; ++e) pos_all[r][e] = (uint32_t)(nxt_pos[r] >> (16 * e)) & 0xFFFFu;
         lds_barrier();
-        if (tile + (int32_t)gridDim.x < ntiles) {
-#pragma unroll
-            for (int r = 0; r < kResRounds; ++r)
-                nxt[r] = __builtin_nontemporal_load((const v4i *)(gs.res + (int64_t)(tile + (int32_t)gridDim.x) * kTile + r * 4 * kGrpThreads + tid * 4));
-        }
+        if (tile + (int32_t)gridDim.x < ntiles) request(tile + (int32_t)gridDim.x);
 #pragma unroll
         for (int r = 0; r < kTileRounds; ++r) {
             const int64_t i0 = tile_base + (int64_t)r * (4 * kGrpThreads) + tid * 4;
@@ -497,8 +495,9 @@ hipError_t launch_group_finish(const TableView &tv, const IndexView &ix, const Q
                                int num_cus, hipStream_t st, const LaunchEvents *ev)
 {
     const int32_t ntiles = (q.n + kTile - 1) / kTile;
-    // two workgroups per compute unit (64 KB of LDS each): one loads a tile's answers while the other writes
-    const int blocks = ntiles < 2 * num_cus ? ntiles : 2 * num_cus;
+    // one workgroup per compute unit (its registers leave no room for a second): the next tile's answers
+    // and positions are requested while the current tile is written
+    const int blocks = ntiles < num_cus ? ntiles : num_cus;
     return launch_kernel(ev, k_group_finish, dim3((unsigned)blocks), dim3(kGrpThreads), 0, st, tv, ix, q, gs, ntiles);
 }
 
