@@ -70,8 +70,8 @@ def test_graph_load_report_and_select(oracle_lib):
 
 
 def test_graph_reports_workers_and_scaling(oracle_lib):
-    """State report, worker report, the selection with workers and a batch of scaling decisions in
-    one graph."""
+    """State report, worker report, the selection with workers and a batch of scaling decisions, up
+    and down, in one graph."""
     import torch
     cfg, n, r = 1, 150_000, 50_000
     tb = workloads.make_table(cfg)
@@ -94,12 +94,14 @@ def test_graph_reports_workers_and_scaling(oracle_lib):
     dr = [torch.empty(r, dtype=torch.int32, device="cuda") for _ in range(5)]
     res = [torch.empty(n, dtype=torch.int32, device="cuda") for _ in range(3)]
     dec = [torch.empty(r, dtype=torch.int32, device="cuda") for _ in range(3)]
+    dec_down = [torch.empty(r, dtype=torch.int32, device="cuda") for _ in range(3)]
 
     def step():
         sel.update_state(*ds)
         sel.update_workers(*dw)
         sel.select_workers(*dq, *res)
         sel.scale(*dr, *dec)
+        sel.scale_down(*dr, *dec_down)
 
     def stage(i):
         q, su, wu, rq = qs[i], sus[i], wus[i], rqs[i]
@@ -121,7 +123,7 @@ def test_graph_reports_workers_and_scaling(oracle_lib):
     for rep in range(5):
         i = rep % 2
         stage(i)
-        for t in res + dec:
+        for t in res + dec + dec_down:
             t.fill_(-9)
         assert int((res[0] + 1).sum().item()) == -8 * n
         graph.replay()
@@ -133,7 +135,9 @@ def test_graph_reports_workers_and_scaling(oracle_lib):
                                          q.batch_idx)
         want_dec = oracle_lib.scale(sc.arch_id, sc.sat_qps, sc.hw_cost, sc.load_us, tb.lat_us, 50, 105, rq.variant,
                                     rq.instances, rq.load_qps, rq.slo_us, rq.batch_idx)
+        want_down = oracle_lib.scale_down(sc.arch_id, sc.sat_qps, sc.hw_cost, sc.load_us, tb.lat_us, 50, 105, rq.variant,
+                                          rq.instances, rq.load_qps, rq.slo_us, rq.batch_idx)
         print(f"graph replay {rep}", flush=True)
-        for g, w in zip(res + dec, want + want_dec):
+        for g, w in zip(res + dec + dec_down, want + want_dec + want_down):
             assert np.array_equal(g.cpu().numpy(), w), f"replay {rep}"
     sel.destroy()
