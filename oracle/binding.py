@@ -278,6 +278,29 @@ class Oracle:
             raise ValueError("oracle rejected its arguments")
         return out, tier, worker
 
+    def get_variant(self, task_id, acc_bp, lat_us, cost, queue_us, state, load_us, variant_hw,
+                    worker_hw, worker_util, inst_variant, inst_worker, inst_load,
+                    q_task, q_slo, q_min_acc, q_bidx, inst_state=None, literal=False):
+        """The whole of Case I (Section 4.1) per query: (variant or -1, tier, worker or -1, variant or
+        suggestion).  Nothing is computed here: variant, tier and worker are those of select_workers
+        (select_instances when the state is kept per instance: `state` is then ignored and the
+        variants' states are the derived ones), the fourth array is that of select_case1 on the
+        same states; both routines make the same state-aware selection, which is checked."""
+        table = (task_id, acc_bp, lat_us, cost, queue_us)
+        cluster = (worker_hw, worker_util, inst_variant, inst_worker, inst_load)
+        queries = (q_task, q_slo, q_min_acc, q_bidx)
+        if inst_state is None:
+            out, tier, worker = self.select_workers(*table, state, load_us, variant_hw, *cluster, *queries,
+                                                    literal=literal)
+        else:
+            out, tier, worker = self.select_instances(*table, load_us, variant_hw, *cluster, inst_state, *queries,
+                                                      literal=literal)
+            state = self.derive_states(_i32(task_id).shape[0], inst_variant, inst_state)
+        out2, tier2, closest = self.select_case1(*table, state, load_us, *queries, literal=literal)
+        if not (np.array_equal(out, out2) and np.array_equal(tier, tier2)):
+            raise AssertionError("the two routines disagree on the state-aware selection")
+        return out, tier, worker, closest
+
     def update_instance_state(self, inst_state: np.ndarray, inst_idx, new_state) -> None:
         """In place: inst_state[inst_idx[i]] = new_state[i], array order, invalid entries skipped."""
         assert inst_state.dtype == np.int32 and inst_state.flags["C_CONTIGUOUS"]
