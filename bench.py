@@ -11,6 +11,8 @@ infaas_sel_select_tiered over seeded variant states (Active variants first, else
 by loading + inference latency; variant and tier arrays, 24 B per decision); its two lookup
 launches are priced together.  With --workers a step is one call of infaas_sel_select_workers
 (the same plus the worker that serves each answer, over a seeded cluster; 28 B per decision).
+With --getvariant a step is one call of infaas_sel_select_workers_closest (that plus the closest
+variant where neither tier answers; 32 B per decision).
 With --scale a step is one call of infaas_sel_scale over 4M seeded scaling requests on the table of
 the configuration (replicate or upgrade on a change in load; 32 B per decision), with --scale-down
 one call of infaas_sel_scale_down (keep, remove an instance or downgrade).
@@ -82,7 +84,7 @@ def bench_scale(args, cfg, spec, tb, down=False) -> int:
     import paper_1905_13348_amd as pkg
     import workloads
 
-    if args.closest or args.tiered or args.workers or args.engine != "auto":
+    if args.closest or args.tiered or args.workers or args.case1 or args.getvariant or args.engine != "auto":
         print("bench.py: --scale and --scale-down go alone", file=sys.stderr)
         return 2
     n = min(SCALE_REQUESTS, spec["num_queries"])
@@ -202,6 +204,9 @@ def main() -> int:
     ap.add_argument("--workers", action="store_true",
                     help="time infaas_sel_select_workers (two-tier selection plus the worker of every answer, "
                          "over a seeded cluster of workers and instances; 28 B per decision)")
+    ap.add_argument("--getvariant", action="store_true",
+                    help="time infaas_sel_select_workers_closest (the whole of Case I: variant, tier, worker and, where "
+                         "neither tier answers, the closest variant; 32 B per decision)")
     ap.add_argument("--scale", action="store_true",
                     help="time infaas_sel_scale (scaling decisions on a change in load: 4M seeded requests, "
                          "lambda 50/s, headroom 105%%; 32 B per decision) instead of the selection")
@@ -256,11 +261,12 @@ def main() -> int:
     chunks = spec["chunks"]
     per_step = spec["num_queries"] // chunks
     engine = {"auto": pkg.ENGINE_AUTO, "scan": pkg.ENGINE_SCAN, "index": pkg.ENGINE_INDEX}[args.engine]
-    if (args.closest or args.tiered or args.workers or args.case1) and \
-            (args.engine != "auto" or args.closest + args.tiered + args.workers + args.case1 > 1):
-        print("bench.py: --closest, --tiered, --case1 and --workers need the index engine (--engine auto), one at a time",
-              file=sys.stderr)
+    if (args.closest or args.tiered or args.workers or args.case1 or args.getvariant) and \
+            (args.engine != "auto" or args.closest + args.tiered + args.workers + args.case1 + args.getvariant > 1):
+        print("bench.py: --closest, --tiered, --case1, --workers and --getvariant need the index engine (--engine auto), "
+              "one at a time", file=sys.stderr)
         return 2
+    with_cluster = args.workers or args.getvariant
 
     sel = pkg.Selector(tb.num_tasks, tb.batch_sizes, device=0, engine=engine)
     sel.load_variants(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us)
@@ -273,10 +279,10 @@ def main() -> int:
         torch.cuda.synchronize()
     states = None
     cluster = None
-    if args.tiered or args.workers or args.case1:
+    if args.tiered or with_cluster or args.case1:
         states = workloads.make_states(cfg, tb.V)
         sel.load_states(states.state, states.load_us)
-    if args.workers:
+    if with_cluster:
         cluster = workloads.make_workers(cfg, states)
         sel.load_workers(cluster.worker_hw, cluster.worker_util, cluster.variant_hw, cluster.inst_variant,
                          cluster.inst_worker, cluster.inst_load)
@@ -286,9 +292,10 @@ def main() -> int:
     # report) and as many result arrays, enough that at least ROTATE_BYTES are touched between two
     # uses of the same buffer: nothing a step reads or writes can still sit in a cache (the part has
     # 256 MB of last-level cache) from the step that used it before.
-    two_results = args.closest or args.tiered or args.workers or args.case1       # suggestion, or tier
-    three_results = args.workers or args.case1                                     # worker, or suggestion beside the tier
-    per_decision = BYTES_PER_DECISION + (4 if two_results else 0) + (4 if three_results else 0)
+    two_results = args.closest or args.tiered or with_cluster or args.case1       # suggestion, or tier
+    three_results = with_cluster or args.case1                                     # worker, or suggestion beside the tier
+    four_results = args.getvariant                                                 # worker and suggestion
+    per_decision = BYTES_PER_DECISION + (4 if two_results else 0) + (4 if three_results else 0) + (4 if four_results else 0)
     set_bytes = per_step * per_decision
     n_sets = int(min(MAX_SETS, max(4, -(-ROTATE_BYTES // set_bytes))))
     if chunks > 1:
@@ -303,9 +310,10 @@ def main() -> int:
     seconds = [torch.empty(per_step, dtype=torch.int32, device="cuda") if two_results else None for _ in range(n_sets)]
     workers_out = [torch.empty(per_step, dtype=torch.int32, device="cuda") if three_results else None
                    for _ in range(n_sets)]
+    fourths = [torch.empty(per_step, dtype=torch.int32, device="cuda") if four_results else None for _ in range(n_sets)]
     updates = []
     worker_updates = []
-    if chunks > 1 and args.workers:   # a report of the cluster before every step as well
+    if chunks > 1 and with_cluster:   # a report of the cluster before every step as well
         for c in range(1, n_sets + 1):
             wu = workloads.make_worker_update(cfg, cluster.W, cluster.I, c)
             worker_updates.append(([torch.from_numpy(x).cuda() for x in
@@ -326,10 +334,13 @@ def main() -> int:
             sel.select_tiered(*dev_q[k], outs[k], seconds[k])
         elif args.case1:
             sel.select_tiered_closest(*dev_q[k], outs[k], seconds[k], workers_out[k])
-        elif args.workers:
+        elif with_cluster:
             if worker_updates:
                 sel.update_workers(*worker_updates[i % len(worker_updates)][0])
-            sel.select_workers(*dev_q[k], outs[k], seconds[k], workers_out[k])
+            if args.getvariant:
+                sel.select_workers_closest(*dev_q[k], outs[k], seconds[k], workers_out[k], fourths[k])
+            else:
+                sel.select_workers(*dev_q[k], outs[k], seconds[k], workers_out[k])
         else:
             sel.select(*dev_q[k], outs[k])
 
@@ -387,9 +398,9 @@ def main() -> int:
     dom_avg_ms = active[dom]["total_ms"] / active[dom]["launches"]
     launches_per_step = active[dom]["launches"] / args.steps
     mode = "/closest" if args.closest else "/tiered" if args.tiered else "/workers" if args.workers else \
-        "/case1" if args.case1 else ""
-    fixed_bytes = table_bytes(tb) + (8 * tb.V if args.tiered or args.workers or args.case1 else 0)   # + state and loading latency
-    if args.workers:   # + hardware of every variant, the workers, the instances
+        "/case1" if args.case1 else "/getvariant" if args.getvariant else ""
+    fixed_bytes = table_bytes(tb) + (8 * tb.V if args.tiered or with_cluster or args.case1 else 0)   # + state and loading latency
+    if with_cluster:   # + hardware of every variant, the workers, the instances
         fixed_bytes += 4 * tb.V + 8 * cluster.W + 12 * cluster.I
     if dom.startswith("group_"):
         # the group-by-group path is three kernels that only together answer a query: they are
@@ -397,7 +408,7 @@ def main() -> int:
         algo_bytes = per_decision * per_step + fixed_bytes
         dom_avg_ms = sum(active[k]["total_ms"] for k in active if k.startswith("group_")) / args.steps
         dom = "group_bin+group_lookup+group_finish"
-    elif (args.tiered or args.workers or args.case1) and dom == "index_select":
+    elif (args.tiered or with_cluster or args.case1) and dom == "index_select":
         # one lookup per tier: the pair is priced as one launch against the bytes of the whole call
         algo_bytes = per_decision * per_step + fixed_bytes
         dom_avg_ms = active[dom]["total_ms"] / args.steps
@@ -425,6 +436,7 @@ def main() -> int:
         ref = oracle.load_oracle()
         q = host_q[(last % n_sets) % n_distinct]
         out, closest, worker = outs[last % n_sets], seconds[last % n_sets], workers_out[last % n_sets]
+        fourth = fourths[last % n_sets]
         queue = base_queue.copy()
         if updates:  # replay the load reports in the order the steps applied them
             for i in range(last + 1):
@@ -433,7 +445,7 @@ def main() -> int:
         fields = (q.task, q.slo_us, q.min_acc_bp, q.batch_idx)
         n0 = min(per_step, 100_000)
         s0 = time.perf_counter()
-        if args.workers:
+        if with_cluster:
             util, iload = cluster.worker_util.copy(), cluster.inst_load.copy()
             if worker_updates:
                 for i in range(last + 1):
@@ -442,8 +454,9 @@ def main() -> int:
                     ref.update_instance_load(iload, wu.inst_idx, wu.inst_load)
 
             def ref_fn(*a):
-                return ref.select_workers(*a[:5], states.state, states.load_us, cluster.variant_hw, cluster.worker_hw,
-                                          util, cluster.inst_variant, cluster.inst_worker, iload, *a[5:])
+                fn = ref.get_variant if args.getvariant else ref.select_workers
+                return fn(*a[:5], states.state, states.load_us, cluster.variant_hw, cluster.worker_hw,
+                          util, cluster.inst_variant, cluster.inst_worker, iload, *a[5:])
         elif args.tiered:
             def ref_fn(*a):
                 return ref.select_tiered(*a[:5], states.state, states.load_us, *a[5:])
@@ -458,7 +471,9 @@ def main() -> int:
         s0 = time.perf_counter()
         want = ref_fn(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, queue, *(f[:n] for f in fields))
         dt = time.perf_counter() - s0
-        if three_results:
+        if four_results:
+            mismatches = int(sum((g[:n].cpu().numpy() != w).sum() for g, w in zip((out, closest, worker, fourth), want)))
+        elif three_results:
             mismatches = int(sum((g[:n].cpu().numpy() != w).sum() for g, w in zip((out, closest, worker), want)))
         elif two_results:
             mismatches = int((out[:n].cpu().numpy() != want[0]).sum() + (closest[:n].cpu().numpy() != want[1]).sum())
@@ -483,7 +498,10 @@ def main() -> int:
                                + (", complete Case I: two tiers, then the closest variant (variant, tier and suggestion arrays)"
                                   if args.case1 else "")
                                + (f", two-tier selection with worker selection over {cluster.W} workers and "
-                                  f"{cluster.I} instances (variant, tier and worker arrays)" if args.workers else ""),
+                                  f"{cluster.I} instances (variant, tier and worker arrays)" if args.workers else "")
+                               + (f", the whole of Case I: two tiers, the worker of every answer over {cluster.W} workers and "
+                                  f"{cluster.I} instances, else the closest variant (variant, tier, worker and suggestion "
+                                  "arrays)" if args.getvariant else ""),
                    "engine": args.engine, "launch": "hip graph replay" if args.graph else "stream",
                    "timed_region": "library instrumentation off; kernel durations from a second pass of the same steps; "
                                    f"{args.preheat_ms:g} ms of the same steps before the warm-up steps"},

@@ -347,6 +347,22 @@ int infaas_sel_select_workers(infaas_sel_t *h, int64_t N,
                               void *hip_stream);
 
 /*
+ * The whole of Case I (Section 4.1) in one call: infaas_sel_select_workers and, for the queries
+ * neither tier answers, the suggestion of infaas_sel_select_tiered_closest.
+ *   d_out_variant, d_out_tier, d_out_worker  [N]  as infaas_sel_select_workers
+ *   d_out_closest                            [N]  as infaas_sel_select_tiered_closest (a suggestion
+ *                                                 is not served: its d_out_worker stays -1)
+ * With instance states loaded the variants' states are the derived ones, as in both calls.
+ * Scratch: 32 bytes per query, as infaas_sel_select_tiered_closest.
+ * Errors: INVALID_ARG, NOT_LOADED (no states or no workers loaded), HIP, OOM.
+ */
+int infaas_sel_select_workers_closest(infaas_sel_t *h, int64_t N,
+                                      const int32_t *d_task, const int32_t *d_slo_us,
+                                      const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
+                                      int32_t *d_out_variant, int32_t *d_out_tier, int32_t *d_out_worker,
+                                      int32_t *d_out_closest, void *hip_stream);
+
+/*
  * ---- Scaling decision on a change in query load: Case II, scaling up (Section 4.2.2) ----------
  *
  * For a running variant cur with n_cur instances and an incoming load of L queries per second:

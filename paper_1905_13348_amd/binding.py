@@ -66,7 +66,7 @@ EXPORTED = ("infaas_sel_create", "infaas_sel_load_variants", "infaas_sel_update_
             "infaas_sel_update_state", "infaas_sel_select_tiered", "infaas_sel_select_tiered_closest",
             "infaas_sel_load_workers",
             "infaas_sel_update_workers", "infaas_sel_load_instance_states", "infaas_sel_update_instance_states",
-            "infaas_sel_select_workers", "infaas_sel_load_scaling",
+            "infaas_sel_select_workers", "infaas_sel_select_workers_closest", "infaas_sel_load_scaling",
             "infaas_sel_scale", "infaas_sel_scale_down", "infaas_sel_destroy", "infaas_sel_reserve",
             "infaas_sel_read_load", "infaas_sel_set_timing", "infaas_sel_get_timings",
             "infaas_sel_get_info", "infaas_sel_strerror", "infaas_sel_last_error")
@@ -108,6 +108,7 @@ def load_library() -> ctypes.CDLL:
     lib.infaas_sel_load_instance_states.argtypes = [vp, _I32P]
     lib.infaas_sel_update_instance_states.argtypes = [vp, ctypes.c_int32, vp, vp, vp]
     lib.infaas_sel_select_workers.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.infaas_sel_select_workers_closest.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.infaas_sel_load_scaling.argtypes = [vp, _I32P, _I32P, _I32P, _I32P, ctypes.c_int32, ctypes.c_int32]
     lib.infaas_sel_scale.argtypes = [vp, ctypes.c_int64, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.infaas_sel_scale_down.argtypes = lib.infaas_sel_scale.argtypes
@@ -294,6 +295,16 @@ class Selector:
             _dev_ptr(d_min_acc_bp, n, "d_min_acc_bp"), _dev_ptr(d_batch_idx, n, "d_batch_idx"),
             _dev_ptr(d_out_variant, n, "d_out_variant"), _dev_ptr(d_out_tier, n, "d_out_tier"),
             _dev_ptr(d_out_worker, n, "d_out_worker"), _stream_ptr(stream)))
+
+    def select_workers_closest(self, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, d_out_tier,
+                               d_out_worker, d_out_closest, stream=None, n: Optional[int] = None) -> None:
+        n = int(d_task.numel()) if n is None else int(n)
+        _check(self._lib.infaas_sel_select_workers_closest(
+            self._h, n, _dev_ptr(d_task, n, "d_task"), _dev_ptr(d_slo_us, n, "d_slo_us"),
+            _dev_ptr(d_min_acc_bp, n, "d_min_acc_bp"), _dev_ptr(d_batch_idx, n, "d_batch_idx"),
+            _dev_ptr(d_out_variant, n, "d_out_variant"), _dev_ptr(d_out_tier, n, "d_out_tier"),
+            _dev_ptr(d_out_worker, n, "d_out_worker"), _dev_ptr(d_out_closest, n, "d_out_closest"),
+            _stream_ptr(stream)))
 
     def load_scaling(self, arch_id, sat_qps, hw_cost, load_us, lambda_per_s: int, slack_pct: int) -> None:
         """Host arrays [V]: model architecture, saturation throughput, hardware cost, loading latency."""

@@ -1018,7 +1018,7 @@ int infaas_sel_select(infaas_sel_t *h, int64_t N, const int32_t *d_task, const i
 
 namespace {
 
-// The state-aware selection, with the worker of every answer when d_out_worker is given, or with
+// The state-aware selection, with the worker of every answer when d_out_worker is given and with
 // the closest variant for the queries neither tier answers when d_out_closest is given.
 int tiered_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,
                 const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
@@ -1071,11 +1071,11 @@ int tiered_impl(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t
         q.open_cap = index_open_cap(q.n, h->num_cus);
         if (workers) { q.worker = d_out_worker + done; q.row_worker = h->wv.row_worker; }
         if (closest) q.closest = d_out_closest + done;
-        q.pass = workers ? 4 : closest ? 6 : 2;
+        q.pass = workers ? (closest ? 8 : 4) : closest ? 6 : 2;
         rc = index_pass(h, q, st);
         if (rc != INFAAS_SEL_OK) return rc;
         if (workers) q.row_worker = h->wv.row_worker + h->V;
-        q.pass = workers ? 5 : closest ? 7 : 3;
+        q.pass = workers ? (closest ? 9 : 5) : closest ? 7 : 3;
         rc = index_pass(h->inactive, q, st);
         if (rc != INFAAS_SEL_OK) return rc;
     }
@@ -1107,6 +1107,15 @@ int infaas_sel_select_workers(infaas_sel_t *h, int64_t N, const int32_t *d_task,
 {
     return tiered_impl(h, N, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, d_out_tier, d_out_worker, true,
                        hip_stream);
+}
+
+int infaas_sel_select_workers_closest(infaas_sel_t *h, int64_t N, const int32_t *d_task, const int32_t *d_slo_us,
+                                      const int32_t *d_min_acc_bp, const int32_t *d_batch_idx,
+                                      int32_t *d_out_variant, int32_t *d_out_tier, int32_t *d_out_worker,
+                                      int32_t *d_out_closest, void *hip_stream)
+{
+    return tiered_impl(h, N, d_task, d_slo_us, d_min_acc_bp, d_batch_idx, d_out_variant, d_out_tier, d_out_worker, true,
+                       hip_stream, d_out_closest, true);
 }
 
 int infaas_sel_load_workers(infaas_sel_t *h, int32_t num_workers, const int32_t *worker_hw, const int32_t *worker_util,

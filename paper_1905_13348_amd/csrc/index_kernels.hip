@@ -724,15 +724,15 @@ __device__ __forceinline__ ClosestStep closest_step(const Mem &mem, int nit, uin
 // 6 and 7: as 2 and 3, and q.closest gets the complete Case I: the selected variant, or for a query
 // that neither tier can answer the closest variant of the two tiers (6 writes the first tier's
 // suggestion, and how far it is from the requirements, beside every record of its lists (q.open_side);
-// 7 compares it with its own).
+// 7 compares it with its own).  8 and 9: 6 and 7 with the workers of 4 and 5.
 template <bool kLds, int kMode>
 __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, IndexView ix, QueryView q,
                                                               int32_t *__restrict__ park_mem, uint32_t lds_cap)
 {
-    constexpr bool kCase1 = kMode == 6 || kMode == 7;
-    constexpr bool kClosest = kMode == 1, kFirst = kMode == 2 || kMode == 4 || kMode == 6;
-    constexpr bool kSecond = kMode == 3 || kMode == 5 || kMode == 7;
-    constexpr bool kWorker = kMode == 4 || kMode == 5;
+    constexpr bool kCase1 = kMode >= 6;
+    constexpr bool kClosest = kMode == 1, kFirst = kMode >= 2 && !(kMode & 1);
+    constexpr bool kSecond = kMode >= 3 && (kMode & 1);
+    constexpr bool kWorker = kMode == 4 || kMode == 5 || kMode == 8 || kMode == 9;
     constexpr bool kSuggest = kClosest || kCase1;   // queries without a feasible variant are parked too, for the suggestion
     extern __shared__ __align__(16) uint32_t lds_w[];  // [16 B control][S + 1 headers][lds_cap bytes of bodies]
     publish_index_stats(tv);
@@ -1031,7 +1031,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
             if (mask) {   // parked queries are always inside the table
                 // (first word: the query; in the last pass of the complete Case I the record's place in the
                 // workgroup's list, where the query and the first tier's suggestion are found)
-                if (df[k]) wq[cnt + lanes_below(mask)] = v4i{kMode == 7 ? cur.unit * kUnit + k * 64 + lane : kSecond ? cur.bi[k] : i0 + qoff(k),
+                if (df[k]) wq[cnt + lanes_below(mask)] = v4i{(kCase1 && kSecond) ? cur.unit * kUnit + k * 64 + lane : kSecond ? cur.bi[k] : i0 + qoff(k),
                                                               cur.sl[k], cur.am[k], (int32_t)sl_of[k]};
                 cnt += (uint32_t)__builtin_popcountll(mask);
                 st_parked += (uint32_t)__builtin_popcountll(mask);
@@ -1067,7 +1067,7 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
         const int32_t *e = (const int32_t *)(wq + first + (have ? lane : 0));
         int32_t qi = __hip_atomic_load(e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         v4i side{-1, 0, 0, 3};   // last pass of the complete Case I: what the first tier suggests, and how far that is
-        if (kMode == 7) {
+        if (kCase1 && kSecond) {
             const int32_t r = have ? qi : 0;
             qi = open_in[r].x;
             side = ((const v4i *)q.open_side + (int64_t)blockIdx.x * q.open_cap)[r];
@@ -1203,9 +1203,9 @@ __global__ __launch_bounds__(kSelThreads) void k_index_select(TableView tv, Inde
                     if (lane == l) { sug = found; mine = how; }
                 }
             }
-            if (kMode == 6 && open)   // for the second tier: this tier's suggestion and how far it is
+            if (kCase1 && kFirst && open)   // for the second tier: this tier's suggestion and how far it is
                 ((v4i *)q.open_side + (int64_t)blockIdx.x * q.open_cap)[open_at] = pack_side(sug, mine);
-            if (kMode == 7) {
+            if (kCase1 && kSecond) {
                 // the closer of the two tiers' suggestions, by (requirements missed, latency beyond the
                 // bound, accuracy below the bound), the first tier's at a tie; q.closest holds the first tier's
                 if (open && sug >= 0) {
@@ -1300,13 +1300,15 @@ hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const Q
         auto kernel = q.pass == 1 ? k_index_select<true, 1> : q.pass == 2 ? k_index_select<true, 2> :
                       q.pass == 3 ? k_index_select<true, 3> : q.pass == 4 ? k_index_select<true, 4> :
                       q.pass == 5 ? k_index_select<true, 5> : q.pass == 6 ? k_index_select<true, 6> :
-                      q.pass == 7 ? k_index_select<true, 7> : k_index_select<true, 0>;
+                      q.pass == 7 ? k_index_select<true, 7> : q.pass == 8 ? k_index_select<true, 8> :
+                      q.pass == 9 ? k_index_select<true, 9> : k_index_select<true, 0>;
         hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds_bytes);
         if (e != hipSuccess) return e;
         // the worker modes keep the 16-bit workers of the hot steps behind the bodies
         uint32_t hot = 0;
-        if (q.pass >= 4 && ix.hot_worker) hot = ((uint32_t)tv.S * ix.hot_rows * 2u + 15u) & ~15u;
+        const bool worker_pass = q.pass == 4 || q.pass == 5 || q.pass == 8 || q.pass == 9;
+        if (worker_pass && ix.hot_worker) hot = ((uint32_t)tv.S * ix.hot_rows * 2u + 15u) & ~15u;
         if (hot + 1024u > lds_bytes - fixed) hot = 0;   // (never with a sensible table; the kernel then must not look for them)
         IndexView ixk = ix;
         if (!hot) ixk.hot_worker = nullptr;
@@ -1316,7 +1318,8 @@ hipError_t launch_index_select(const TableView &tv, const IndexView &ix, const Q
     auto kernel = q.pass == 1 ? k_index_select<false, 1> : q.pass == 2 ? k_index_select<false, 2> :
                   q.pass == 3 ? k_index_select<false, 3> : q.pass == 4 ? k_index_select<false, 4> :
                   q.pass == 5 ? k_index_select<false, 5> : q.pass == 6 ? k_index_select<false, 6> :
-                  q.pass == 7 ? k_index_select<false, 7> : k_index_select<false, 0>;
+                  q.pass == 7 ? k_index_select<false, 7> : q.pass == 8 ? k_index_select<false, 8> :
+                  q.pass == 9 ? k_index_select<false, 9> : k_index_select<false, 0>;
     return launch_kernel(ev, kernel, dim3((unsigned)blocks), dim3((unsigned)kSelThreads), kLdsCtrlBytes, st, tv, ix, q,
                          park_mem, 0u);
 }
