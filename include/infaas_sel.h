@@ -504,7 +504,7 @@ typedef struct {
     int32_t index_truncated;    /* slices whose staircase was cut at its capacity or not stored */
     int32_t index_max_steps;    /* longest staircase of any slice (as stored) */
     int32_t index_hot_rows;     /* steps per slice whose caller row is kept beside the index in LDS */
-    int64_t index_bytes;        /* size of the staircase index */
+    int64_t index_bytes;        /* size of the staircase index (as of the latest build a selection has run behind) */
     int64_t index_steps;        /* steps over all slices */
     int64_t table_bytes;        /* device bytes of the variant store */
     int64_t scratch_bytes;      /* device bytes of scratch currently reserved */

@@ -136,7 +136,7 @@ struct infaas_sel {
     int64_t gs_queries = 0, gs_bytes = 0;    // batch size it is good for; its size
     int32_t *d_park = nullptr;        // queues of parked queries of the lookup kernel (fixed size)
     int64_t park_bytes = 0;
-    uint32_t *host_stats = nullptr;   // pinned, device-visible: four counters of the latest index build (kCtlMaxK0 ..)
+    uint32_t *host_stats = nullptr;   // pinned, device-visible: six counters of the latest index build (kCtlMaxK0 .., pool, steps)
     int32_t *static_park = nullptr;   // the same queues inside the library's static device array (may be null)
     const uint32_t *last_stats = nullptr;   // statistics of the most recent lookup launch (this table's or the Inactive tier's)
 
@@ -330,6 +330,8 @@ int build_index_now(infaas_sel *h)
     if (h->host_stats) {
         void *dev = nullptr;
         for (int i = 0; i < 4; ++i) h->host_stats[i] = h->ix_stats[kCtlMaxK0 + i];
+        h->host_stats[4] = h->ix_stats[kCtlPool];
+        h->host_stats[5] = h->ix_stats[kCtlSteps];
         if (hipHostGetDevicePointer(&dev, h->host_stats, 0) == hipSuccess) {
             h->tv.stat_src = ix.ctrl;
             h->tv.stat_dst = (uint32_t *)dev;
@@ -1613,8 +1615,11 @@ int infaas_sel_get_info(infaas_sel_t *h, infaas_sel_info *out)
                                              : h->ix_stats[kCtlTrunc] + h->ix_stats[kCtlNoBody]);
         out->index_max_steps = (int32_t)(now ? now[kCtlMaxK - kCtlMaxK0] : h->ix_stats[kCtlMaxK]);
         out->index_hot_rows = (int32_t)h->ix.hot_rows;
-        out->index_bytes = h->ix_bytes + (int64_t)h->T * h->B * 16 + (h->ix_steps + 1) * 4;
-        out->index_steps = h->ix_steps;
+        // (with groups the two counters cover only what lies behind the regions: the figures of the load are kept)
+        const bool fresh = now && h->ix.num_groups <= 1;
+        const int64_t pool_now = fresh ? (int64_t)now[4] : h->ix_bytes, steps_now = fresh ? (int64_t)now[5] - 1 : h->ix_steps;
+        out->index_bytes = pool_now + (int64_t)h->T * h->B * 16 + (steps_now + 1) * 4;
+        out->index_steps = steps_now;
         // what the most recent lookup launch did with the queries its first probe could not decide
         std::vector<uint32_t> st((size_t)index_select_blocks(h->num_cus) * kLookupStats, 0u);
         DeviceGuard g(h->device);

@@ -38,8 +38,8 @@ struct TableView {
     // 0xFFFFFFFF): nothing selects them and every entry ranked before them dominates them.
     int32_t *state;             // [Vp] state of each slot, or null when the table is not state-aware
     int32_t want_state;         // the state this table serves
-    // Four counters of the latest build of the table's index (kCtlMaxK0 .. kCtlMaxK) and where the
-    // first kernel of every selection copies them for the host to see (pinned host memory); null: nowhere.
+    // Six counters of the latest build of the table's index (kCtlMaxK0 .. kCtlMaxK, kCtlPool, kCtlSteps) and
+    // where the first kernel of every selection copies them for the host to see (pinned host memory); null: nowhere.
     const uint32_t *stat_src;
     uint32_t *stat_dst;
 };
@@ -140,7 +140,8 @@ constexpr int kCtlWords = 64;
 // Called by every thread of the first kernel of a selection.
 __device__ __forceinline__ void publish_index_stats(const TableView &tv)
 {
-    if (tv.stat_dst && blockIdx.x == 0 && threadIdx.x < 4) tv.stat_dst[threadIdx.x] = tv.stat_src[kCtlMaxK0 + threadIdx.x];
+    if (tv.stat_dst && blockIdx.x == 0 && threadIdx.x < 6)   // words 4, 5: pool bytes and step_row entries handed out
+        tv.stat_dst[threadIdx.x] = tv.stat_src[threadIdx.x < 4 ? kCtlMaxK0 + threadIdx.x : kCtlPool + (threadIdx.x - 4)];
 }
 
 constexpr uint32_t kDummyBodyBytes = 64;     // 4 unused bytes, the empty body (28 bytes), padding
