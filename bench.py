@@ -217,6 +217,11 @@ def main() -> int:
                     help="after the timed steps (which give the kernel times), capture the steps into HIP graphs "
                          "and time the same number of steps again as graph replays: value and ms_per_step are "
                          "then those of the replays")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="after the timed steps (which give the kernel times), time the same number of steps again "
+                         "dealt in turn to this many streams, each with a handle of its own on the same table (handles "
+                         "share nothing, so their calls need no ordering): value and ms_per_step are then those of "
+                         "that loop.  Plain selection on a configuration without load reports only.")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -300,6 +305,12 @@ def main() -> int:
     n_sets = int(min(MAX_SETS, max(4, -(-ROTATE_BYTES // set_bytes))))
     if chunks > 1:
         n_sets = min(n_sets, chunks)
+    if args.streams > 1:
+        if chunks > 1 or two_results or args.graph or args.degrade or not 2 <= args.streams <= 4:
+            print("bench.py: --streams 2..4 goes with the plain selection on a configuration without load reports",
+                  file=sys.stderr)
+            return 2
+        n_sets += (-n_sets) % args.streams     # a set of buffers is always used on the same stream
     n_distinct = min(n_sets, MAX_DISTINCT)
     host_q = [workloads.make_queries(cfg, chunk=c) for c in range(n_distinct)]
     dev_q = []
@@ -388,6 +399,33 @@ def main() -> int:
             done += 1
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
+    if args.streams > 1:
+        sels = [sel]
+        for _ in range(args.streams - 1):
+            other = pkg.Selector(tb.num_tasks, tb.batch_sizes, device=0, engine=engine)
+            other.load_variants(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, tb.queue_us)
+            other.reserve(per_step)
+            sels.append(other)
+        lanes = [torch.cuda.Stream() for _ in sels]
+        done += (-done) % n_sets                # step i: buffers i % n_sets, stream and handle i % streams
+
+        def run(count: int) -> None:
+            nonlocal done
+            for _ in range(count):
+                k, j = done % n_sets, done % len(sels)
+                with torch.cuda.stream(lanes[j]):
+                    sels[j].select(*dev_q[k], outs[k])
+                done += 1
+
+        torch.cuda.synchronize()
+        run(max(args.warmup, 4 * len(sels)))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(args.steps)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        for other in sels[1:]:
+            other.destroy()
     last = done - 1
     ms_per_step = 1e3 * elapsed / args.steps
     value = per_step * args.steps / elapsed
@@ -502,7 +540,8 @@ def main() -> int:
                                + (f", the whole of Case I: two tiers, the worker of every answer over {cluster.W} workers and "
                                   f"{cluster.I} instances, else the closest variant (variant, tier, worker and suggestion "
                                   "arrays)" if args.getvariant else ""),
-                   "engine": args.engine, "launch": "hip graph replay" if args.graph else "stream",
+                   "engine": args.engine, "launch": "hip graph replay" if args.graph else
+                   (f"{args.streams} streams, a handle each" if args.streams > 1 else "stream"),
                    "timed_region": "library instrumentation off; kernel durations from a second pass of the same steps; "
                                    f"{args.preheat_ms:g} ms of the same steps before the warm-up steps"},
         "roofline": roofline,
