@@ -519,6 +519,14 @@ def main() -> int:
             mismatches = int((out[:n].cpu().numpy() != want).sum())
         cpu = {"value": round(n / dt, 1), "unit": "decisions/s", "cores": ref.num_threads(),
                "kind": "oracle", "sample": f"first {n} queries of the last timed batch, {dt:.1f} s"}
+        # and on one host thread, on a sample of about two seconds
+        threads = ref.num_threads()
+        n1 = int(min(n, max(1000, 2.0 * (n / dt) / max(threads, 1))))
+        ref.set_threads(1)
+        s0 = time.perf_counter()
+        ref_fn(tb.task_id, tb.acc_bp, tb.lat_us, tb.cost, queue, *(f[:n1] for f in fields))
+        cpu["one_thread"] = round(n1 / (time.perf_counter() - s0), 1)
+        ref.set_threads(threads)
 
     line = {
         "metric": "variant-selection decisions/sec on 1 MI355X; % of HBM roofline",

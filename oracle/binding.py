@@ -96,10 +96,16 @@ class Oracle:
         lib.oracle_update_load.restype = None
         lib.oracle_num_threads.argtypes = []
         lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_set_threads.argtypes = [ctypes.c_int]
+        lib.oracle_set_threads.restype = ctypes.c_int
         self._lib = lib
 
     def num_threads(self) -> int:
         return int(self._lib.oracle_num_threads())
+
+    def set_threads(self, n: int) -> int:
+        """Host threads for the grouped forms from now on; returns the number in use."""
+        return int(self._lib.oracle_set_threads(int(n)))
 
     def _select(self, fn, task_id, acc_bp, lat_us, cost, queue_us, q_task, q_slo, q_min_acc, q_bidx):
         task_id, acc_bp, queue_us = _i32(task_id), _i32(acc_bp), _i32(queue_us)

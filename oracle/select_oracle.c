@@ -1197,3 +1197,13 @@ int oracle_num_threads(void)
     return 1;
 #endif
 }
+
+/* Host threads the grouped forms are to use from now on (n < 1: leave as is); returns what they use then. */
+int oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1)
+        omp_set_num_threads(n);
+#endif
+    return oracle_num_threads();
+}
